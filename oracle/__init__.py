@@ -1,0 +1,150 @@
+"""CPU oracle for the Atom W4A4 hot path -- TEST INFRASTRUCTURE ONLY.
+
+A plain single-threaded C implementation (``atom_ref.c``) with a numpy/ctypes
+wrapper.  Only the tests, the smoke check and the benchmark's CPU-baseline leg
+may import this package; the product (``paper_2310_19102_amd``) never does, and
+this package never imports the product.
+
+fp16 tensors are numpy ``float16`` arrays; codes are ``uint8`` (two INT4 per
+byte, even column in the low nibble) and ``int8``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "atom_ref.c")
+_LIB = os.path.join(_HERE, "libatom_ref.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile ``atom_ref.c`` with gcc into ``libatom_ref.so`` next to it."""
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+             or os.path.getmtime(_LIB) < os.path.getmtime(os.path.join(_HERE, "atom_ref.h")))
+    if force or stale:
+        cmd = ["gcc", "-O2", "-ftree-vectorize", "-ffp-contract=off", "-fno-fast-math",
+               "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", _SRC, "-o", _LIB, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    L = ctypes.CDLL(_LIB)
+    vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float
+    L.atom_ref_f16_to_f32.restype = f32
+    L.atom_ref_f16_to_f32.argtypes = [ctypes.c_uint16]
+    L.atom_ref_f32_to_f16.restype = ctypes.c_uint16
+    L.atom_ref_f32_to_f16.argtypes = [f32]
+    L.atom_ref_sumsq.restype = f32
+    L.atom_ref_sumsq.argtypes = [vp, i32]
+    L.atom_ref_rmsnorm_row.restype = None
+    L.atom_ref_rmsnorm_row.argtypes = [vp, vp, f32, i32, vp]
+    L.atom_ref_quantize_act.restype = ctypes.c_int
+    L.atom_ref_quantize_act.argtypes = [vp, i64, i64, vp, f32, vp, i32, i32, i32, f32, vp, vp, vp]
+    L.atom_ref_quantize_weight.restype = ctypes.c_int
+    L.atom_ref_quantize_weight.argtypes = [vp, i64, i64, vp, i32, i32, i32, f32, vp, vp, vp]
+    L.atom_ref_w4a4_gemm.restype = ctypes.c_int
+    L.atom_ref_w4a4_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, i32, i32, i32,
+                                     vp, i64, vp, vp]
+    _lib = L
+    return L
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a)
+    if a.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {a.dtype}")
+    return a
+
+
+def f16_to_f32(bits: int) -> float:
+    return float(_load().atom_ref_f16_to_f32(int(bits) & 0xFFFF))
+
+
+def f32_to_f16(value) -> int:
+    return int(_load().atom_ref_f32_to_f16(np.float32(value)))
+
+
+def sumsq(x_row: np.ndarray) -> np.float32:
+    x = _c(x_row, np.float16)
+    return np.float32(_load().atom_ref_sumsq(_p(x), x.shape[0]))
+
+
+def rmsnorm_row(x_row: np.ndarray, gamma, eps: float) -> np.ndarray:
+    x = _c(x_row, np.float16)
+    g = None if gamma is None else _c(gamma, np.float16)
+    y = np.empty(x.shape[0], np.float32)
+    _load().atom_ref_rmsnorm_row(_p(x), _p(g), eps, x.shape[0], _p(y))
+    return y
+
+
+def quantize_act(x, gamma, eps, idx, group_size=128, n_outlier=128, clip=0.9):
+    """Returns (q4 uint8 [M,K4/2], q8 int8 [M,O], scale float16 [M,G])."""
+    x = _c(x, np.float16)
+    M, K = x.shape
+    g = None if gamma is None else _c(gamma, np.float16)
+    idx = _c(idx, np.int32)
+    K4, G = K - n_outlier, K // group_size
+    q4 = np.zeros((M, K4 // 2), np.uint8)
+    q8 = np.zeros((M, n_outlier), np.int8)
+    sc = np.zeros((M, G), np.float16)
+    rc = _load().atom_ref_quantize_act(_p(x), M, K, _p(g), eps, _p(idx), K, group_size,
+                                       n_outlier, clip, _p(q4), _p(q8), _p(sc))
+    if rc != 0:
+        raise ValueError("atom_ref_quantize_act: bad shapes")
+    return q4, q8, sc
+
+
+def quantize_weight(w, idx, group_size=128, n_outlier=128, clip=0.85):
+    """Returns (q4 uint8 [N,K4/2], q8 int8 [N,O], scale float16 [N,G])."""
+    w = _c(w, np.float16)
+    N, K = w.shape
+    idx = _c(idx, np.int32)
+    K4, G = K - n_outlier, K // group_size
+    q4 = np.zeros((N, K4 // 2), np.uint8)
+    q8 = np.zeros((N, n_outlier), np.int8)
+    sc = np.zeros((N, G), np.float16)
+    rc = _load().atom_ref_quantize_weight(_p(w), N, K, _p(idx), K, group_size, n_outlier,
+                                          clip, _p(q4), _p(q8), _p(sc))
+    if rc != 0:
+        raise ValueError("atom_ref_quantize_weight: bad shapes")
+    return q4, q8, sc
+
+
+def w4a4_gemm(a_q4, a_q8, a_scale, w_q4, w_q8, w_scale, group_size=128,
+              want_partials=False, want_acc=False):
+    """Returns dict with 'y' float16 [M,N] and optionally 'partials' int32
+    [M,N,G] and 'acc' float32 [M,N]."""
+    a_q4, w_q4 = _c(a_q4, np.uint8), _c(w_q4, np.uint8)
+    a_q8, w_q8 = _c(a_q8, np.int8), _c(w_q8, np.int8)
+    a_scale, w_scale = _c(a_scale, np.float16), _c(w_scale, np.float16)
+    M, N, O = a_q8.shape[0], w_q8.shape[0], a_q8.shape[1]
+    K = a_q4.shape[1] * 2 + O
+    G = K // group_size
+    y = np.zeros((M, N), np.float16)
+    part = np.zeros((M, N, G), np.int32) if want_partials else None
+    acc = np.zeros((M, N), np.float32) if want_acc else None
+    rc = _load().atom_ref_w4a4_gemm(_p(a_q4), _p(a_q8), _p(a_scale), M, _p(w_q4), _p(w_q8),
+                                    _p(w_scale), N, K, group_size, O, _p(y), N, _p(part), _p(acc))
+    if rc != 0:
+        raise ValueError("atom_ref_w4a4_gemm: bad shapes")
+    out = {"y": y}
+    if want_partials:
+        out["partials"] = part
+    if want_acc:
+        out["acc"] = acc
+    return out

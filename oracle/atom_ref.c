@@ -1,0 +1,248 @@
+/*
+ * atom_ref.c -- CPU oracle for the Atom W4A4 hot path (arxiv 2310.19102).
+ *
+ * TEST INFRASTRUCTURE ONLY: plain single-threaded C, host pointers, no
+ * intrinsics, no blocking, no fusion.  The product never calls this file.
+ * Build with:  gcc -O2 -ffp-contract=off -shared -fPIC atom_ref.c -lm
+ * (-ffp-contract=off keeps every fp32 multiply and add separately rounded;
+ * the only fused multiply-add is the explicit fmaf in the GEMM epilogue).
+ */
+#include "atom_ref.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---------------------------------------------------------------- fp16 -- */
+
+float atom_ref_f16_to_f32(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) << 31;
+    int32_t  e    = (h >> 10) & 0x1f;
+    uint32_t m    = h & 0x3ffu;
+    uint32_t bits;
+    if (e == 0) {
+        if (m == 0) {
+            bits = sign;                          /* signed zero */
+        } else {                                  /* subnormal: m * 2^-24 */
+            int shift = 0;
+            while ((m & 0x400u) == 0) { m <<= 1; ++shift; }
+            m &= 0x3ffu;
+            bits = sign | ((uint32_t)(127 - 15 - shift + 1) << 23) | (m << 13);
+        }
+    } else if (e == 31) {
+        bits = sign | 0x7f800000u | (m << 13);    /* inf / nan */
+    } else {
+        bits = sign | ((uint32_t)(e - 15 + 127) << 23) | (m << 13);
+    }
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return f;
+}
+
+uint16_t atom_ref_f32_to_f16(float f)
+{
+    uint32_t bits;
+    memcpy(&bits, &f, sizeof bits);
+    uint16_t sign = (uint16_t)((bits >> 16) & 0x8000u);
+    uint32_t a = bits & 0x7fffffffu;              /* |f| */
+    if (a >= 0x7f800000u)                         /* inf or nan */
+        return (uint16_t)(sign | 0x7c00u | ((a > 0x7f800000u) ? 0x200u : 0u));
+    if (a >= 0x477ff000u)                         /* >= 65520 rounds to inf */
+        return (uint16_t)(sign | 0x7c00u);
+    if (a < 0x33000000u)                          /* < 2^-25 rounds to zero */
+        return sign;
+    int32_t  e = (int32_t)(a >> 23) - 127;        /* unbiased exponent */
+    uint32_t m = (a & 0x7fffffu) | 0x800000u;     /* 24-bit significand */
+    int drop;                                     /* low bits to discard */
+    uint32_t base;
+    if (e >= -14) { drop = 13;           base = (uint32_t)(e + 15 - 1) << 10; }
+    else          { drop = 13 + (-14 - e); base = 0; }
+    /* keep (24 - drop) bits; for normals the kept leading 1 adds to base */
+    uint32_t kept = m >> drop;
+    uint32_t rem  = m & ((1u << drop) - 1u);
+    uint32_t half = 1u << (drop - 1);
+    if (rem > half || (rem == half && (kept & 1u))) ++kept;
+    return (uint16_t)(sign | (base + kept));      /* carries roll exponents */
+}
+
+/* fp32 -> fp16 for group scales: finite inputs, overflow saturates at the
+ * largest finite fp16 (65504) instead of becoming infinity. */
+static uint16_t scale_to_f16(float s32)
+{
+    uint16_t h = atom_ref_f32_to_f16(s32);
+    if ((h & 0x7fffu) >= 0x7c00u) h = (uint16_t)((h & 0x8000u) | 0x7bffu);
+    return h;
+}
+
+/* ------------------------------------------------------------- RMSNorm -- */
+
+float atom_ref_sumsq(const uint16_t *x, int32_t K)
+{
+    float L[64];
+    for (int l = 0; l < 64; ++l) L[l] = 0.0f;
+    int32_t V = (K + 7) / 8;
+    for (int32_t v = 0; v < V; ++v) {
+        float sq[8];
+        for (int i = 0; i < 8; ++i) {
+            int32_t k = 8 * v + i;
+            float xf = (k < K) ? atom_ref_f16_to_f32(x[k]) : 0.0f;
+            sq[i] = xf * xf;                      /* exact: 11-bit x 11-bit */
+        }
+        float q = ((sq[0] + sq[1]) + (sq[2] + sq[3])) +
+                  ((sq[4] + sq[5]) + (sq[6] + sq[7]));
+        L[v % 64] = L[v % 64] + q;
+    }
+    for (int d = 1; d < 64; d *= 2)
+        for (int l = 0; l + d < 64; l += 2 * d)
+            L[l] = L[l] + L[l + d];
+    return L[0];
+}
+
+void atom_ref_rmsnorm_row(const uint16_t *x, const uint16_t *gamma, float eps,
+                          int32_t K, float *y)
+{
+    if (gamma == NULL) {
+        for (int32_t k = 0; k < K; ++k) y[k] = atom_ref_f16_to_f32(x[k]);
+        return;
+    }
+    float S    = atom_ref_sumsq(x, K);
+    float mean = S / (float)K;
+    float r    = 1.0f / sqrtf(mean + eps);
+    for (int32_t k = 0; k < K; ++k) {
+        float xf = atom_ref_f16_to_f32(x[k]);
+        float t  = xf * r;
+        y[k] = t * atom_ref_f16_to_f32(gamma[k]);
+    }
+}
+
+/* ------------------------------------------------- group quantisation -- */
+
+static int shapes_ok(int32_t K, int32_t Gs, int32_t O)
+{
+    if (K <= 0 || Gs <= 0 || O < 0) return 0;
+    if (Gs % 2) return 0;                         /* two INT4 per byte */
+    if (K % Gs || O % Gs || O >= K) return 0;
+    return 1;
+}
+
+/* Quantise one row whose fp32 values y[] are in ORIGINAL channel order. */
+static void quantize_row(const float *y, const int32_t *idx, int32_t K,
+                         int32_t Gs, int32_t O, float clip, uint8_t *q4,
+                         int8_t *q8, uint16_t *scale)
+{
+    int32_t K4 = K - O, G = K / Gs, G4 = K4 / Gs;
+    for (int32_t g = 0; g < G; ++g) {
+        int   n    = (g < G4) ? 4 : 8;            /* bit-width of the group */
+        int   qmin = -(1 << (n - 1)), qmax = (1 << (n - 1)) - 1;
+        float amax = 0.0f;
+        for (int32_t t = 0; t < Gs; ++t) {
+            float a = fabsf(y[idx[g * Gs + t]]);
+            if (a > amax) amax = a;
+        }
+        float s32 = ((2.0f * amax) * clip) / (float)((1 << n) - 1);
+        uint16_t sh = scale_to_f16(s32);
+        float s = atom_ref_f16_to_f32(sh);
+        scale[g] = sh;
+        for (int32_t t = 0; t < Gs; ++t) {
+            int32_t j = g * Gs + t;
+            int q = 0;
+            if (s != 0.0f) {
+                float v = nearbyintf(y[idx[j]] / s);   /* ties to even */
+                if (v < (float)qmin) v = (float)qmin;
+                if (v > (float)qmax) v = (float)qmax;
+                q = (int)v;
+            }
+            if (n == 4) {
+                uint8_t nib = (uint8_t)(q & 0xf);
+                if (j % 2 == 0) q4[j / 2] = nib;
+                else            q4[j / 2] = (uint8_t)(q4[j / 2] | (nib << 4));
+            } else {
+                q8[j - K4] = (int8_t)q;
+            }
+        }
+    }
+}
+
+int atom_ref_quantize_act(const uint16_t *x, int64_t M, int64_t ldx,
+                          const uint16_t *gamma, float eps, const int32_t *idx,
+                          int32_t K, int32_t Gs, int32_t O, float clip,
+                          uint8_t *q4, int8_t *q8, uint16_t *scale)
+{
+    if (!shapes_ok(K, Gs, O) || ldx < K || M < 0) return -1;
+    int32_t K4 = K - O, G = K / Gs;
+    float *y = (float *)malloc(sizeof(float) * (size_t)K);
+    if (!y) return -1;
+    for (int64_t m = 0; m < M; ++m) {
+        atom_ref_rmsnorm_row(x + m * ldx, gamma, eps, K, y);
+        quantize_row(y, idx, K, Gs, O, clip, q4 + m * (K4 / 2), q8 + m * O,
+                     scale + m * G);
+    }
+    free(y);
+    return 0;
+}
+
+int atom_ref_quantize_weight(const uint16_t *w, int64_t N, int64_t ldw,
+                             const int32_t *idx, int32_t K, int32_t Gs,
+                             int32_t O, float clip, uint8_t *q4, int8_t *q8,
+                             uint16_t *scale)
+{
+    return atom_ref_quantize_act(w, N, ldw, NULL, 0.0f, idx, K, Gs, O, clip,
+                                 q4, q8, scale);
+}
+
+/* ----------------------------------------------------------------- GEMM -- */
+
+/* Codes of one operand as int8 [rows, K]: sign-extended nibbles, then the
+ * INT8 block, i.e. the reordered channel order j = 0..K-1. */
+static int8_t *unpack_codes(const uint8_t *q4, const int8_t *q8, int64_t rows,
+                            int32_t K, int32_t O)
+{
+    int32_t K4 = K - O;
+    int8_t *c = (int8_t *)malloc((size_t)rows * (size_t)K + 1);
+    if (!c) return NULL;
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int32_t j = 0; j < K4; ++j) {
+            uint8_t b   = q4[r * (K4 / 2) + j / 2];
+            int     nib = (j % 2 == 0) ? (b & 0xf) : (b >> 4);
+            c[r * K + j] = (int8_t)((nib >= 8) ? nib - 16 : nib);
+        }
+        for (int32_t j = K4; j < K; ++j) c[r * K + j] = q8[r * O + (j - K4)];
+    }
+    return c;
+}
+
+int atom_ref_w4a4_gemm(const uint8_t *a_q4, const int8_t *a_q8,
+                       const uint16_t *a_scale, int64_t M,
+                       const uint8_t *w_q4, const int8_t *w_q8,
+                       const uint16_t *w_scale, int64_t N, int32_t K,
+                       int32_t Gs, int32_t O, uint16_t *y, int64_t ldy,
+                       int32_t *partials, float *acc_f32)
+{
+    if (!shapes_ok(K, Gs, O) || ldy < N || M < 0 || N < 0) return -1;
+    int32_t G = K / Gs;
+    int8_t *a = unpack_codes(a_q4, a_q8, M, K, O);
+    int8_t *w = unpack_codes(w_q4, w_q8, N, K, O);
+    if (!a || !w) { free(a); free(w); return -1; }
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            float acc = 0.0f;
+            for (int32_t g = 0; g < G; ++g) {
+                const int8_t *ar = a + m * K + g * Gs;
+                const int8_t *wr = w + n * K + g * Gs;
+                int32_t P = 0;                              /* step 1 */
+                for (int32_t t = 0; t < Gs; ++t)
+                    P += (int32_t)ar[t] * (int32_t)wr[t];
+                float ss = atom_ref_f16_to_f32(a_scale[m * G + g]) *
+                           atom_ref_f16_to_f32(w_scale[n * G + g]);
+                acc = fmaf((float)P, ss, acc);              /* steps 2, 3 */
+                if (partials) partials[(m * N + n) * G + g] = P;
+            }
+            if (acc_f32) acc_f32[m * N + n] = acc;
+            y[m * ldy + n] = atom_ref_f32_to_f16(acc);
+        }
+    }
+    free(a);
+    free(w);
+    return 0;
+}

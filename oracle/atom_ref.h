@@ -1,0 +1,92 @@
+/*
+ * atom_ref.h -- CPU oracle for the Atom W4A4 hot path (arxiv 2310.19102).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a plain, slow, single-threaded C
+ * implementation of what the GPU library computes.  It shares no code with
+ * the HIP path and nothing in the product may call it: only the tests, the
+ * smoke check and the benchmark's CPU-baseline leg do.
+ *
+ * Every function takes HOST pointers.  Matrices are row-major.  fp16 values
+ * travel as raw uint16_t bit patterns (IEEE binary16).
+ *
+ * Notation (Section 4.1-4.2 of the paper): K input channels, O outlier
+ * channels kept in INT8 and placed last by the reorder index, K4 = K - O
+ * normal channels in INT4, group size Gs (128 in the paper), G = K / Gs
+ * groups of which the first G4 = K4 / Gs are INT4 and the rest INT8.
+ *
+ * Arithmetic contract (the readings of the paper taken here):
+ *   - symmetric quantisation, Section 2:  s = 2*max|X| / (2^n - 1) * c,
+ *     Xq = clamp(round(X / s), -2^(n-1), 2^(n-1) - 1); evaluated in fp32 as
+ *     ((2*amax)*c)/(2^n-1); "round" is round-half-to-even; the scale is then
+ *     rounded to fp16 (the 16-bit scale per group of the effective-bit
+ *     footnote in Section 4.2, saturated at 65504) and the codes are produced
+ *     by an IEEE fp32 division by that STORED scale.  A zero scale gives zero
+ *     codes.
+ *   - RMSNorm in fp32 (Section 4.5 fuses the layer norm of Llama into the
+ *     quantisation operator); the sum of squares follows one fixed tree
+ *     (see atom_ref_sumsq) so that it has exactly one correct value.
+ *   - GEMM, Section 4.2 steps 1-3: per group an exact int32 partial, then
+ *     acc = fma(float(P), float(sa)*float(sw), acc) over ascending groups in
+ *     fp32, result rounded to fp16.
+ */
+#ifndef ATOM_REF_H
+#define ATOM_REF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* IEEE binary16 <-> binary32, round-half-to-even on narrowing. */
+float    atom_ref_f16_to_f32(uint16_t h);
+uint16_t atom_ref_f32_to_f16(float f);
+
+/* Sum of squares of one row of K fp16 values by the canonical tree:
+ * vectors of 8 consecutive channels are squared and added pairwise
+ * ((0+1)+(2+3))+((4+5)+(6+7)); vector v goes to accumulator v mod 64 in
+ * increasing v; the 64 accumulators are folded with strides 1,2,4,...,32. */
+float atom_ref_sumsq(const uint16_t *x_f16, int32_t K);
+
+/* One row of RMSNorm (Section 4.5): r = 1/sqrt(S/K + eps),
+ * y[k] = (x[k]*r)*gamma[k], all fp32.  gamma == NULL means y = x. */
+void atom_ref_rmsnorm_row(const uint16_t *x_f16, const uint16_t *gamma_f16,
+                          float eps, int32_t K, float *y_out);
+
+/* Fused front end (Sections 4.1-4.3): optional RMSNorm, reorder
+ * yr[j] = y[idx[j]], per-group symmetric quantisation.
+ *   x_f16   [M, ldx]  fp16, K valid columns
+ *   gamma   [K] fp16 in ORIGINAL channel order, or NULL (no norm)
+ *   idx     [K] permutation; the last O entries are the outlier channels
+ *   q4      [M, K4/2] bytes: low nibble = even column, high nibble = odd
+ *   q8      [M, O]    int8
+ *   scale   [M, G]    fp16
+ * Returns 0, or -1 on bad shapes. */
+int atom_ref_quantize_act(const uint16_t *x_f16, int64_t M, int64_t ldx,
+                          const uint16_t *gamma_f16, float eps,
+                          const int32_t *idx, int32_t K, int32_t Gs, int32_t O,
+                          float clip, uint8_t *q4, int8_t *q8, uint16_t *scale);
+
+/* Offline weight path (Section 4.1 reorder, Section 5.1 clip): same as the
+ * front end without the norm; round-to-nearest only (no GPTQ). */
+int atom_ref_quantize_weight(const uint16_t *w_f16, int64_t N, int64_t ldw,
+                             const int32_t *idx, int32_t K, int32_t Gs,
+                             int32_t O, float clip, uint8_t *q4, int8_t *q8,
+                             uint16_t *scale);
+
+/* Mixed-precision group GEMM (Section 4.2, Figure "fused GEMM operator").
+ *   y_f16     [M, ldy] fp16 out
+ *   partials  NULL or [M, N, G] int32 (per-group integer sums)
+ *   acc_f32   NULL or [M, N] fp32 accumulators before the fp16 rounding */
+int atom_ref_w4a4_gemm(const uint8_t *a_q4, const int8_t *a_q8,
+                       const uint16_t *a_scale, int64_t M,
+                       const uint8_t *w_q4, const int8_t *w_q8,
+                       const uint16_t *w_scale, int64_t N,
+                       int32_t K, int32_t Gs, int32_t O,
+                       uint16_t *y_f16, int64_t ldy,
+                       int32_t *partials, float *acc_f32);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
