@@ -1,0 +1,132 @@
+/*
+ * atom.h -- C ABI of the MI355X (gfx950) implementation of the Atom W4A4
+ * hot path (arxiv 2310.19102): fused activation front end, one-time weight
+ * quantisation, and the mixed-precision group-quantised GEMM.
+ *
+ * Conventions common to every entry point
+ *   - Every data pointer is a DEVICE pointer unless it says "host".
+ *   - The caller owns every buffer.  Except where stated the library
+ *     allocates nothing and keeps no state between calls.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream).  Outputs are valid once the stream has
+ *     reached the end of the call.
+ *   - Nothing throws or aborts.  Every failure is a return code decided on the
+ *     host before any kernel is launched (except ATOM_ERR_HIP, which reports
+ *     the launch error).  M == 0 or N == 0 returns ATOM_OK without a launch.
+ *   - Matrices are row-major.  fp16 = IEEE binary16.
+ *   - Contents the host cannot see are not validated: a reorder index that is
+ *     not a permutation of 0..K-1 (checked only `< K` by the kernels, so it
+ *     cannot fault, but the result is meaningless) and non-finite inputs are
+ *     the caller's responsibility.  atom_check_reorder_idx is the host guard.
+ *
+ * Notation (Sections 4.1-4.2): K input channels; the last O = n_outlier
+ * reordered channels are the outliers kept in INT8; K4 = K - O normal channels
+ * in INT4; group size Gs; G = K / Gs groups, the first G4 = K4 / Gs of them
+ * INT4.  Supported: Gs = 128, O a positive multiple of 128 with O < K,
+ * bits 4 / 8, K <= 32768.
+ *
+ * Quantised layouts (what parity is judged on)
+ *   q4    [rows, K4/2] bytes; byte b of a row holds reordered channel 2b in
+ *         its low nibble and 2b+1 in its high nibble, two's complement
+ *   q8    [rows, O]    int8, reordered channels K4 .. K-1
+ *   scale [rows, G]    fp16, group g of the row; the INT8 groups come last
+ */
+#ifndef ATOM_H
+#define ATOM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ATOM_OK              = 0,
+    ATOM_ERR_NULL        = 1,  /* a required pointer is NULL                   */
+    ATOM_ERR_SHAPE       = 2,  /* negative size, ld too small, K % Gs != 0 ... */
+    ATOM_ERR_UNSUPPORTED = 3,  /* Gs != 128, bits != (4, 8), K too large       */
+    ATOM_ERR_ALIGN       = 4,  /* a pointer or leading dimension is misaligned */
+    ATOM_ERR_WORKSPACE   = 5,  /* workspace missing or too small               */
+    ATOM_ERR_HIP         = 6   /* the HIP runtime refused the launch           */
+} atom_status;
+
+/* The quantisation set-up of Section 5.1: { K, 128, 128, 4, 8 }. */
+typedef struct {
+    int32_t K;             /* input channels of the linear layer            */
+    int32_t group_size;    /* Gs, Section 4.2                               */
+    int32_t n_outlier;     /* O, Section 4.1                                */
+    int32_t bits_normal;   /* 4                                             */
+    int32_t bits_outlier;  /* 8                                             */
+} atom_desc;
+
+/*
+ * Fused activation front end (Section 4.3 dynamic quantisation fused into the
+ * preceding operator, Section 4.1 reorder, Section 4.5 workflow):
+ *   y  = gamma ? RMSNorm(x) * gamma : x            (fp32, never stored)
+ *   yr[m, j] = y[m, reorder_idx[j]]
+ *   per group: s = fp16(((2*max|yr|)*clip)/(2^n - 1)),  q = clamp(rne(yr/s))
+ * following the symmetric equations of Section 2.
+ *
+ *   x_f16        [M, ldx] fp16, ldx >= K, 16-byte aligned rows (ldx % 8 == 0)
+ *   gamma_f16    [K] fp16 in ORIGINAL channel order, or NULL for no norm
+ *   eps          RMSNorm epsilon
+ *   reorder_idx  [K] int32: output column j reads input column idx[j]
+ *   clip         clip factor c (0.9 for activations in Section 5.1)
+ *   q4, q8, scale_f16   outputs in the layouts above; q4 and q8 16-byte
+ *                       aligned, scale_f16 2-byte aligned
+ */
+atom_status atom_quantize_act(const void *x_f16, int64_t M, int64_t ldx,
+                              const void *gamma_f16, float eps,
+                              const int32_t *reorder_idx, const atom_desc *d,
+                              float clip, void *q4, void *q8, void *scale_f16,
+                              void *stream);
+
+/*
+ * One-time weight path (Section 4.1: weights are reordered offline with the
+ * activations' index; Section 5.1: clip 0.85): reorder + round-to-nearest
+ * group quantisation of W[N, K] (nn.Linear layout).  No norm, no GPTQ.
+ * Arguments as atom_quantize_act.
+ */
+atom_status atom_quantize_weight(const void *w_f16, int64_t N, int64_t ldw,
+                                 const int32_t *reorder_idx,
+                                 const atom_desc *d, float clip, void *q4,
+                                 void *q8, void *scale_f16, void *stream);
+
+/*
+ * Mixed-precision group GEMM (Section 4.2, fused GEMM operator, steps 1-3):
+ *   P[m, n, g] = sum over the 128 channels of group g of aq * wq   (int32)
+ *   Y[m, n]    = fp16( sum_g float(P[m, n, g]) * a_scale[m, g] * w_scale[n, g] )
+ * accumulated in fp32 over ascending g.
+ *
+ *   a_q4 / a_q8 / a_scale   activation codes and scales for M rows
+ *   w_q4 / w_q8 / w_scale   weight codes and scales for N rows
+ *   y_f16         [M, ldy] fp16 out, ldy >= N
+ *   partials_dbg  NULL, or [M, N, G] int32: every per-group integer sum is
+ *                 also written (a slow path meant for verification)
+ *   workspace     device scratch of at least
+ *                 atom_w4a4_gemm_workspace_bytes(M, N, d) bytes, 256-byte
+ *                 aligned; may be NULL when that size is 0
+ * Code pointers must be 16-byte aligned, scale pointers 2-byte aligned.
+ */
+atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8,
+                           const void *a_scale, int64_t M, const void *w_q4,
+                           const void *w_q8, const void *w_scale, int64_t N,
+                           const atom_desc *d, void *y_f16, int64_t ldy,
+                           int32_t *partials_dbg, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/* Scratch the GEMM needs for these sizes (0 when it needs none). */
+size_t atom_w4a4_gemm_workspace_bytes(int64_t M, int64_t N,
+                                      const atom_desc *d);
+
+/* Host helper: ATOM_OK iff idx_host[0..K) is a permutation of 0..K-1. */
+atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K);
+
+/* Static, NUL-terminated description of a status code. */
+const char *atom_status_string(atom_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

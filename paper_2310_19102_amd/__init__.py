@@ -1,0 +1,19 @@
+"""MI355X-native hot path of Atom's W4A4 quantisation (arxiv 2310.19102).
+
+The product is ``libatom.so`` (hand-written HIP kernels for gfx950 behind the C
+ABI declared in ``include/atom.h``).  This package is a thin binding with the
+same entry-point names: it marshals torch device tensors into plain pointers and
+sizes; every step of the path runs in the library's kernels.  There is no CPU
+or PyTorch fallback: loading fails loudly when the library has not been built.
+"""
+from .binding import (  # noqa: F401
+    AtomError,
+    atom_check_reorder_idx,
+    atom_quantize_act,
+    atom_quantize_weight,
+    atom_status_string,
+    atom_w4a4_gemm,
+    atom_w4a4_gemm_workspace_bytes,
+    library_path,
+    load_library,
+)

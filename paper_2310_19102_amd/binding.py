@@ -1,0 +1,196 @@
+"""ctypes binding of ``libatom.so``: argument marshalling only.
+
+torch is used for device memory and the current HIP stream; no arithmetic of
+the method happens in Python.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libatom.so")
+_lib = None
+
+EXPORTS = (
+    "atom_quantize_act",
+    "atom_quantize_weight",
+    "atom_w4a4_gemm",
+    "atom_w4a4_gemm_workspace_bytes",
+    "atom_check_reorder_idx",
+    "atom_status_string",
+)
+
+
+class AtomError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {atom_status_string(status)} (status {status})")
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("K", ctypes.c_int32), ("group_size", ctypes.c_int32), ("n_outlier", ctypes.c_int32),
+                ("bits_normal", ctypes.c_int32), ("bits_outlier", ctypes.c_int32)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load ``libatom.so`` built in-tree.  Raises if it is missing: there is
+    no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} not found: build it with `python -m paper_2310_19102_amd.build` "
+            "(hipcc, gfx950).  This package has no CPU or PyTorch fallback.")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i64, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    dp = ctypes.POINTER(_Desc)
+    L.atom_quantize_act.restype = ctypes.c_int
+    L.atom_quantize_act.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, vp, vp, vp]
+    L.atom_quantize_weight.restype = ctypes.c_int
+    L.atom_quantize_weight.argtypes = [vp, i64, i64, vp, dp, f32, vp, vp, vp, vp]
+    L.atom_w4a4_gemm.restype = ctypes.c_int
+    L.atom_w4a4_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, dp, vp, i64, vp, vp, sz, vp]
+    L.atom_w4a4_gemm_workspace_bytes.restype = sz
+    L.atom_w4a4_gemm_workspace_bytes.argtypes = [i64, i64, dp]
+    L.atom_check_reorder_idx.restype = ctypes.c_int
+    L.atom_check_reorder_idx.argtypes = [vp, ctypes.c_int32]
+    L.atom_status_string.restype = ctypes.c_char_p
+    L.atom_status_string.argtypes = [ctypes.c_int]
+    _lib = L
+    return L
+
+
+def _desc(K: int, group_size: int, n_outlier: int) -> _Desc:
+    return _Desc(K, group_size, n_outlier, 4, 8)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    return t
+
+
+def atom_status_string(status: int) -> str:
+    return load_library().atom_status_string(int(status)).decode()
+
+
+def atom_check_reorder_idx(idx: torch.Tensor) -> int:
+    """Host check that ``idx`` (CPU int32 tensor) is a permutation. Returns the status."""
+    idx = idx.detach().cpu().contiguous()
+    if idx.dtype != torch.int32:
+        raise TypeError("idx must be int32")
+    return int(load_library().atom_check_reorder_idx(ctypes.c_void_p(idx.data_ptr()), idx.numel()))
+
+
+def _quant_outputs(rows: int, K: int, group_size: int, n_outlier: int, device):
+    q4 = torch.empty((rows, (K - n_outlier) // 2), dtype=torch.uint8, device=device)
+    q8 = torch.empty((rows, n_outlier), dtype=torch.int8, device=device)
+    sc = torch.empty((rows, K // group_size), dtype=torch.float16, device=device)
+    return q4, q8, sc
+
+
+def atom_quantize_act(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float,
+                      reorder_idx: torch.Tensor, group_size: int = 128, n_outlier: int = 128,
+                      clip: float = 0.9, out: Optional[Tuple[torch.Tensor, ...]] = None):
+    """Fused RMSNorm -> reorder -> dynamic group quantisation of ``x`` [M, K]
+    (fp16, last dim contiguous).  Returns ``(q4, q8, scale)`` device tensors."""
+    L = load_library()
+    _dev(x, torch.float16, "x")
+    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if gamma is not None:
+        _dev(gamma, torch.float16, "gamma")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [M, K] with a contiguous last dimension")
+    M, K = x.shape
+    q4, q8, sc = out if out is not None else _quant_outputs(M, K, group_size, n_outlier, x.device)
+    d = _desc(K, group_size, n_outlier)
+    st = L.atom_quantize_act(_ptr(x), M, x.stride(0) if M > 1 else max(K, x.stride(0)), _ptr(gamma),
+                             eps, _ptr(reorder_idx), ctypes.byref(d), clip, _ptr(q4), _ptr(q8),
+                             _ptr(sc), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_quantize_act")
+    return q4, q8, sc
+
+
+def atom_quantize_weight(w: torch.Tensor, reorder_idx: torch.Tensor, group_size: int = 128,
+                         n_outlier: int = 128, clip: float = 0.85,
+                         out: Optional[Tuple[torch.Tensor, ...]] = None):
+    """One-time reorder + group quantisation of ``w`` [N, K] fp16."""
+    L = load_library()
+    _dev(w, torch.float16, "w")
+    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if w.dim() != 2 or w.stride(1) != 1:
+        raise ValueError("w must be [N, K] with a contiguous last dimension")
+    N, K = w.shape
+    q4, q8, sc = out if out is not None else _quant_outputs(N, K, group_size, n_outlier, w.device)
+    d = _desc(K, group_size, n_outlier)
+    st = L.atom_quantize_weight(_ptr(w), N, w.stride(0) if N > 1 else max(K, w.stride(0)),
+                                _ptr(reorder_idx), ctypes.byref(d), clip, _ptr(q4), _ptr(q8),
+                                _ptr(sc), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_quantize_weight")
+    return q4, q8, sc
+
+
+def atom_w4a4_gemm_workspace_bytes(M: int, N: int, K: int, group_size: int = 128,
+                                   n_outlier: int = 128) -> int:
+    d = _desc(K, group_size, n_outlier)
+    return int(load_library().atom_w4a4_gemm_workspace_bytes(M, N, ctypes.byref(d)))
+
+
+def atom_w4a4_gemm(a_q4, a_q8, a_scale, w_q4, w_q8, w_scale, group_size: int = 128,
+                   out: Optional[torch.Tensor] = None, partials: Optional[torch.Tensor] = None,
+                   workspace: Optional[torch.Tensor] = None):
+    """Y[M, N] fp16 = group-dequantised product of quantised activations and
+    weights.  ``partials`` (int32 [M, N, G]) also receives every per-group
+    integer sum."""
+    L = load_library()
+    for t, dt, nm in ((a_q4, torch.uint8, "a_q4"), (a_q8, torch.int8, "a_q8"),
+                      (a_scale, torch.float16, "a_scale"), (w_q4, torch.uint8, "w_q4"),
+                      (w_q8, torch.int8, "w_q8"), (w_scale, torch.float16, "w_scale")):
+        _dev(t, dt, nm)
+        if not t.is_contiguous():
+            raise ValueError(f"{nm} must be contiguous")
+    M, O = a_q8.shape
+    N = w_q8.shape[0]
+    K = a_q4.shape[1] * 2 + O
+    if w_q4.shape[1] != a_q4.shape[1] or w_q8.shape[1] != O:
+        raise ValueError("activation and weight code shapes disagree")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=a_q4.device)
+    _dev(out, torch.float16, "out")
+    if partials is not None:
+        _dev(partials, torch.int32, "partials")
+        if tuple(partials.shape) != (M, N, K // group_size) or not partials.is_contiguous():
+            raise ValueError("partials must be contiguous int32 [M, N, G]")
+    d = _desc(K, group_size, n_outlier=O)
+    need = int(L.atom_w4a4_gemm_workspace_bytes(M, N, ctypes.byref(d)))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=a_q4.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = L.atom_w4a4_gemm(_ptr(a_q4), _ptr(a_q8), _ptr(a_scale), M, _ptr(w_q4), _ptr(w_q8),
+                          _ptr(w_scale), N, ctypes.byref(d), _ptr(out),
+                          out.stride(0) if M > 1 else max(N, out.stride(0)),
+                          _ptr(partials), _ptr(workspace), ws_bytes, _stream())
+    if st != 0:
+        raise AtomError(st, "atom_w4a4_gemm")
+    return out

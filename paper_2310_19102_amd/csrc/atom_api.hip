@@ -1,0 +1,145 @@
+// C-ABI shim: argument validation on the host, then one kernel launch per call.
+// Nothing here allocates, synchronises or keeps state.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <new>
+
+#include "atom.h"
+#include "atom_internal.h"
+
+namespace {
+
+inline bool aligned(const void *p, uintptr_t a)
+{
+    return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;
+}
+
+atom_status check_desc(const atom_desc *d)
+{
+    if (!d) return ATOM_ERR_NULL;
+    if (d->K <= 0 || d->group_size <= 0 || d->n_outlier < 0) return ATOM_ERR_SHAPE;
+    if (d->group_size != atom_internal::kGroup || d->bits_normal != 4 || d->bits_outlier != 8)
+        return ATOM_ERR_UNSUPPORTED;
+    if (d->K % d->group_size || d->n_outlier % d->group_size) return ATOM_ERR_SHAPE;
+    if (d->n_outlier >= d->K) return ATOM_ERR_SHAPE;
+    if (d->n_outlier == 0) return ATOM_ERR_UNSUPPORTED;
+    if (d->K > atom_internal::kMaxK) return ATOM_ERR_UNSUPPORTED;
+    return ATOM_OK;
+}
+
+atom_status quantize_common(const void *x, int64_t rows, int64_t ld, const void *gamma, float eps,
+                            const int32_t *idx, const atom_desc *d, float clip, void *q4,
+                            void *q8, void *scale, void *stream)
+{
+    atom_status st = check_desc(d);
+    if (st != ATOM_OK) return st;
+    if (rows < 0 || ld < d->K) return ATOM_ERR_SHAPE;
+    if (rows == 0) return ATOM_OK;
+    if (!x || !idx || !q4 || !q8 || !scale) return ATOM_ERR_NULL;
+    if (!aligned(x, 16) || (ld % 8) || !aligned(idx, 16) || !aligned(q4, 16) || !aligned(q8, 16) ||
+        !aligned(scale, 2) || (gamma && !aligned(gamma, 16)))
+        return ATOM_ERR_ALIGN;
+    hipError_t err = atom_internal::launch_quantize_rows(x, rows, ld, gamma, eps, idx, d->K,
+                                                         d->n_outlier, clip, q4, q8, scale,
+                                                         static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+atom_status atom_quantize_act(const void *x_f16, int64_t M, int64_t ldx, const void *gamma_f16,
+                              float eps, const int32_t *reorder_idx, const atom_desc *d,
+                              float clip, void *q4, void *q8, void *scale_f16, void *stream)
+{
+    return quantize_common(x_f16, M, ldx, gamma_f16, eps, reorder_idx, d, clip, q4, q8, scale_f16,
+                           stream);
+}
+
+atom_status atom_quantize_weight(const void *w_f16, int64_t N, int64_t ldw,
+                                 const int32_t *reorder_idx, const atom_desc *d, float clip,
+                                 void *q4, void *q8, void *scale_f16, void *stream)
+{
+    return quantize_common(w_f16, N, ldw, nullptr, 0.0f, reorder_idx, d, clip, q4, q8, scale_f16,
+                           stream);
+}
+
+size_t atom_w4a4_gemm_workspace_bytes(int64_t M, int64_t N, const atom_desc *d)
+{
+    if (check_desc(d) != ATOM_OK || M <= 0 || N <= 0) return 0;
+    return atom_internal::gemm_workspace_bytes(M, N, d->K, d->n_outlier);
+}
+
+atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8, const void *a_scale, int64_t M,
+                           const void *w_q4, const void *w_q8, const void *w_scale, int64_t N,
+                           const atom_desc *d, void *y_f16, int64_t ldy, int32_t *partials_dbg,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    atom_status st = check_desc(d);
+    if (st != ATOM_OK) return st;
+    if (M < 0 || N < 0 || ldy < N) return ATOM_ERR_SHAPE;
+    if (M == 0 || N == 0) return ATOM_OK;
+    if (!a_q4 || !a_q8 || !a_scale || !w_q4 || !w_q8 || !w_scale || !y_f16) return ATOM_ERR_NULL;
+    if (!aligned(a_q4, 16) || !aligned(a_q8, 16) || !aligned(a_scale, 2) || !aligned(w_q4, 16) ||
+        !aligned(w_q8, 16) || !aligned(w_scale, 2) || !aligned(y_f16, 2) ||
+        (partials_dbg && !aligned(partials_dbg, 4)))
+        return ATOM_ERR_ALIGN;
+    const size_t need = atom_internal::gemm_workspace_bytes(M, N, d->K, d->n_outlier);
+    if (need) {
+        if (!workspace || workspace_bytes < need) return ATOM_ERR_WORKSPACE;
+        if (!aligned(workspace, 256)) return ATOM_ERR_ALIGN;
+    }
+    atom_internal::GemmArgs g;
+    g.a_q4 = static_cast<const uint8_t *>(a_q4);
+    g.a_q8 = static_cast<const int8_t *>(a_q8);
+    g.a_scale = static_cast<const uint16_t *>(a_scale);
+    g.M = M;
+    g.w_q4 = static_cast<const uint8_t *>(w_q4);
+    g.w_q8 = static_cast<const int8_t *>(w_q8);
+    g.w_scale = static_cast<const uint16_t *>(w_scale);
+    g.N = N;
+    g.K = d->K;
+    g.O = d->n_outlier;
+    g.y = static_cast<uint16_t *>(y_f16);
+    g.ldy = ldy;
+    g.partials = partials_dbg;
+    g.workspace = workspace;
+    g.workspace_bytes = workspace_bytes;
+    hipError_t err = atom_internal::launch_w4a4_gemm(g, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
+atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K)
+{
+    if (!idx_host) return ATOM_ERR_NULL;
+    if (K <= 0) return ATOM_ERR_SHAPE;
+    unsigned char *seen = new (std::nothrow) unsigned char[(size_t)K]();
+    if (!seen) return ATOM_ERR_WORKSPACE;
+    atom_status st = ATOM_OK;
+    for (int32_t j = 0; j < K && st == ATOM_OK; ++j) {
+        const int32_t v = idx_host[j];
+        if (v < 0 || v >= K || seen[(size_t)v]) st = ATOM_ERR_SHAPE;
+        else seen[(size_t)v] = 1;
+    }
+    delete[] seen;
+    return st;
+}
+
+const char *atom_status_string(atom_status s)
+{
+    switch (s) {
+    case ATOM_OK:              return "ok";
+    case ATOM_ERR_NULL:        return "a required pointer is NULL";
+    case ATOM_ERR_SHAPE:       return "invalid shape, leading dimension or reorder index";
+    case ATOM_ERR_UNSUPPORTED: return "unsupported group size, bit-width or K";
+    case ATOM_ERR_ALIGN:       return "misaligned pointer or leading dimension";
+    case ATOM_ERR_WORKSPACE:   return "workspace missing or too small";
+    case ATOM_ERR_HIP:         return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,34 @@
+// Internal launch interface between the C-ABI shim and the kernel files.
+#ifndef ATOM_INTERNAL_H
+#define ATOM_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace atom_internal {
+
+constexpr int kGroup    = 128;     // channels per quantisation group
+constexpr int kMaxK     = 32768;   // a staged fp32 row must fit the 160 KB LDS
+
+size_t quantize_lds_bytes(int K, bool norm);
+
+// One row per workgroup: optional RMSNorm, reorder gather, group quantisation.
+hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, const void *gamma,
+                                float eps, const int32_t *idx, int K, int O, float clip,
+                                void *q4, void *q8, void *scale, hipStream_t stream);
+
+struct GemmArgs {
+    const uint8_t *a_q4; const int8_t *a_q8; const uint16_t *a_scale; int64_t M;
+    const uint8_t *w_q4; const int8_t *w_q8; const uint16_t *w_scale; int64_t N;
+    int K, O;
+    uint16_t *y; int64_t ldy;
+    int32_t *partials;          // NULL or [M, N, G]
+    void *workspace; size_t workspace_bytes;
+};
+
+size_t     gemm_workspace_bytes(int64_t M, int64_t N, int K, int O);
+hipError_t launch_w4a4_gemm(const GemmArgs &a, hipStream_t stream);
+
+}  // namespace atom_internal
+#endif

@@ -1,0 +1,204 @@
+// Fused activation front end and one-time weight quantisation for gfx950.
+//
+// One workgroup (4 wavefronts) per row:
+//   1. the row is read once from HBM with 128-bit loads and staged in LDS as
+//      fp32, in ORIGINAL channel order; with RMSNorm every 8-channel vector also
+//      leaves its sum of squares in LDS;
+//   2. every wavefront folds the vector sums in the fixed order that gives the
+//      sum of squares exactly one correct fp32 value (vector v -> lane v mod 64
+//      in increasing v, then an xor butterfly with strides 1..32), derives
+//      r = 1/sqrt(S/K + eps) and rescales its share of the staged row by
+//      r and gamma;
+//   3. the reorder (Section 4.1 of the paper) is an LDS gather: lane l of a
+//      16-lane row owns 8 consecutive REORDERED channels, so one 16-lane DPP row
+//      holds one group of 128 and the group's amax is a 4-step row reduction;
+//   4. scale (Section 2 symmetric equations, fp32, stored as fp16), IEEE
+//      division by the stored scale, round-half-to-even, clamp, pack: a lane
+//      emits one dword of eight INT4 codes or eight INT8 bytes, coalesced.
+//
+// Compile WITHOUT fast-math: the fp32 division, sqrt and the absence of
+// fused multiply-adds are part of the bit-exact contract with the CPU oracle.
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "atom_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ void halves_to_floats(const uint4 &raw, float *f)
+{
+    const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float2 t = __half22float2(h[i]);
+        f[2 * i]     = t.x;
+        f[2 * i + 1] = t.y;
+    }
+}
+
+// max over the 16 lanes of a DPP row (xor butterfly; max is exact in any order)
+__device__ __forceinline__ float row16_max(float v)
+{
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
+    return v;
+}
+
+template <bool NORM>
+__global__ __launch_bounds__(kThreads)
+void quantize_rows_kernel(const __half *__restrict__ x, int64_t rows, int64_t ld,
+                          const __half *__restrict__ gamma, float eps,
+                          const int32_t *__restrict__ idx, int K, int O, float clip,
+                          uint8_t *__restrict__ q4, int8_t *__restrict__ q8,
+                          __half *__restrict__ scale)
+{
+    extern __shared__ __align__(16) float lds[];
+    float *ybuf = lds;            // [K]   staged row, original channel order
+    float *qbuf = lds + K;        // [K/8] per-vector sums of squares (NORM only)
+
+    const int tid  = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int V    = K >> 3;      // 8-channel vectors per row
+    const int K4   = K - O;
+    const int G    = K >> 7;
+    const int G4   = K4 >> 7;
+
+    for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+        const __half *xr = x + row * ld;
+
+        // ---- 1. stage the row ------------------------------------------------
+        for (int v = tid; v < V; v += kThreads) {
+            uint4 raw = *reinterpret_cast<const uint4 *>(xr + 8 * v);
+            float f[8];
+            halves_to_floats(raw, f);
+            *reinterpret_cast<float4 *>(ybuf + 8 * v)     = make_float4(f[0], f[1], f[2], f[3]);
+            *reinterpret_cast<float4 *>(ybuf + 8 * v + 4) = make_float4(f[4], f[5], f[6], f[7]);
+            if (NORM) {
+                float s0 = f[0] * f[0], s1 = f[1] * f[1], s2 = f[2] * f[2], s3 = f[3] * f[3];
+                float s4 = f[4] * f[4], s5 = f[5] * f[5], s6 = f[6] * f[6], s7 = f[7] * f[7];
+                qbuf[v] = ((s0 + s1) + (s2 + s3)) + ((s4 + s5) + (s6 + s7));
+            }
+        }
+        __syncthreads();
+
+        // ---- 2. RMSNorm ------------------------------------------------------
+        if (NORM) {
+            float L = 0.0f;
+            for (int v = lane; v < V; v += 64) L = L + qbuf[v];
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) L = L + __shfl_xor(L, d, 64);
+            const float mean = L / (float)K;
+            const float r    = 1.0f / sqrtf(mean + eps);
+            // each thread rescales exactly the vectors it staged itself
+            for (int v = tid; v < V; v += kThreads) {
+                uint4 graw = *reinterpret_cast<const uint4 *>(gamma + 8 * v);
+                float g[8];
+                halves_to_floats(graw, g);
+                float4 lo = *reinterpret_cast<float4 *>(ybuf + 8 * v);
+                float4 hi = *reinterpret_cast<float4 *>(ybuf + 8 * v + 4);
+                lo.x = (lo.x * r) * g[0]; lo.y = (lo.y * r) * g[1];
+                lo.z = (lo.z * r) * g[2]; lo.w = (lo.w * r) * g[3];
+                hi.x = (hi.x * r) * g[4]; hi.y = (hi.y * r) * g[5];
+                hi.z = (hi.z * r) * g[6]; hi.w = (hi.w * r) * g[7];
+                *reinterpret_cast<float4 *>(ybuf + 8 * v)     = lo;
+                *reinterpret_cast<float4 *>(ybuf + 8 * v + 4) = hi;
+            }
+            __syncthreads();
+        }
+
+        // ---- 3./4. reorder, group amax, scale, quantise, pack ----------------
+        // A wavefront sweep covers 4 groups: DPP row (lane/16) <-> group.
+        for (int g = 4 * wave + (lane >> 4); g < ((G + 3) & ~3); g += 4 * (kThreads / 64)) {
+            const bool live = g < G;          // ragged last sweep: whole 16-lane rows idle
+            const int  gg   = live ? g : G - 1;
+            const int  j0   = gg * 128 + (lane & 15) * 8;
+            const int4 i0 = *reinterpret_cast<const int4 *>(idx + j0);
+            const int4 i1 = *reinterpret_cast<const int4 *>(idx + j0 + 4);
+            const int  id[8] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
+            float y[8];
+            float amax = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                y[e] = ybuf[min((unsigned)id[e], (unsigned)(K - 1))];
+                amax = fmaxf(amax, fabsf(y[e]));
+            }
+            amax = row16_max(amax);
+
+            const bool  is4   = gg < G4;
+            const float denom = is4 ? 15.0f : 255.0f;
+            const float qmin  = is4 ? -8.0f : -128.0f;
+            const float qmax  = is4 ? 7.0f : 127.0f;
+            const float s32   = ((2.0f * amax) * clip) / denom;
+            const __half sh   = (s32 > 65504.0f) ? __ushort_as_half((unsigned short)0x7bffu)
+                                                 : __float2half_rn(s32);
+            const float s     = __half2float(sh);
+            int q[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float t = rintf(y[e] / s);
+                t = fminf(fmaxf(t, qmin), qmax);
+                q[e] = (s != 0.0f) ? (int)t : 0;
+            }
+            if (live) {
+                if (is4) {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) w |= (uint32_t)(q[e] & 0xF) << (4 * e);
+                    *reinterpret_cast<uint32_t *>(q4 + row * (int64_t)(K4 >> 1) + (j0 >> 1)) = w;
+                } else {
+                    uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        w0 |= (uint32_t)(q[e] & 0xFF) << (8 * e);
+                        w1 |= (uint32_t)(q[e + 4] & 0xFF) << (8 * e);
+                    }
+                    *reinterpret_cast<uint2 *>(q8 + row * (int64_t)O + (j0 - K4)) = make_uint2(w0, w1);
+                }
+                if ((lane & 15) == 0) scale[row * (int64_t)G + gg] = sh;
+            }
+        }
+        __syncthreads();   // ybuf is rewritten by the next row
+    }
+}
+
+}  // namespace
+
+namespace atom_internal {
+
+size_t quantize_lds_bytes(int K, bool norm)
+{
+    return sizeof(float) * (size_t)(K + (norm ? K / 8 : 0));
+}
+
+hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, const void *gamma,
+                                float eps, const int32_t *idx, int K, int O, float clip,
+                                void *q4, void *q8, void *scale, hipStream_t stream)
+{
+    const bool   norm  = gamma != nullptr;
+    const size_t lds   = quantize_lds_bytes(K, norm);
+    const int    grid  = (int)(rows < (int64_t)1 << 20 ? rows : (int64_t)1 << 20);
+    hipError_t   err;
+    if (norm) {
+        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&quantize_rows_kernel<true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return err;
+        hipLaunchKernelGGL(quantize_rows_kernel<true>, dim3(grid), dim3(kThreads), lds, stream,
+                           (const __half *)x, rows, ld, (const __half *)gamma, eps, idx, K, O,
+                           clip, (uint8_t *)q4, (int8_t *)q8, (__half *)scale);
+    } else {
+        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&quantize_rows_kernel<false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return err;
+        hipLaunchKernelGGL(quantize_rows_kernel<false>, dim3(grid), dim3(kThreads), lds, stream,
+                           (const __half *)x, rows, ld, (const __half *)nullptr, eps, idx, K, O,
+                           clip, (uint8_t *)q4, (int8_t *)q8, (__half *)scale);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace atom_internal

@@ -1,0 +1,86 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and its host-only entry points behave."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2310_19102_amd as atom
+from paper_2310_19102_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "atom.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(atom_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = atom.load_library()
+    names = _declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    seen = {atom.atom_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert atom.atom_status_string(99) == "unknown status"
+
+
+def test_check_reorder_idx():
+    assert atom.atom_check_reorder_idx(torch.arange(512, dtype=torch.int32)) == 0
+    bad = torch.arange(512, dtype=torch.int32)
+    bad[7] = 8
+    assert atom.atom_check_reorder_idx(bad) == 2
+    bad[7] = 512
+    assert atom.atom_check_reorder_idx(bad) == 2
+    bad[7] = -1
+    assert atom.atom_check_reorder_idx(bad) == 2
+
+
+def test_host_side_argument_validation_needs_no_gpu():
+    """Failures are decided on the host before any launch, so they can be
+    exercised here with fake (never dereferenced) device pointers."""
+    lib = atom.load_library()
+    D = binding._Desc
+    p = ctypes.c_void_p(0x1000)
+    ok = D(4096, 128, 128, 4, 8)
+    q = lib.atom_quantize_act
+    assert q(None, 4, 4096, None, 0.0, p, ctypes.byref(ok), 0.9, p, p, p, None) == 1
+    assert q(p, 4, 4000, None, 0.0, p, ctypes.byref(ok), 0.9, p, p, p, None) == 2
+    assert q(p, -1, 4096, None, 0.0, p, ctypes.byref(ok), 0.9, p, p, p, None) == 2
+    assert q(p, 0, 4096, None, 0.0, p, ctypes.byref(ok), 0.9, p, p, p, None) == 0
+    assert q(ctypes.c_void_p(0x1002), 4, 4096, None, 0.0, p, ctypes.byref(ok), 0.9, p, p, p, None) == 4
+    assert q(p, 4, 4100, None, 0.0, p, ctypes.byref(ok), 0.9, p, p, p, None) == 4
+    for desc, want in ((D(4096, 64, 128, 4, 8), 3), (D(4096, 128, 128, 3, 8), 3),
+                       (D(4100, 128, 128, 4, 8), 2), (D(4096, 128, 100, 4, 8), 2),
+                       (D(128, 128, 128, 4, 8), 2), (D(65536, 128, 128, 4, 8), 3),
+                       (D(4096, 128, 0, 4, 8), 3)):
+        assert q(p, 4, 65536, None, 0.0, p, ctypes.byref(desc), 0.9, p, p, p, None) == want
+    g = lib.atom_w4a4_gemm
+    assert g(p, p, p, 4, p, p, p, 8, ctypes.byref(ok), p, 4, None, None, 0, None) == 2   # ldy < N
+    assert g(p, p, p, 4, p, None, p, 8, ctypes.byref(ok), p, 8, None, None, 0, None) == 1
+    assert g(p, p, p, 0, p, p, p, 8, ctypes.byref(ok), p, 8, None, None, 0, None) == 0
+    assert g(p, p, p, 4, p, p, p, 8, None, p, 8, None, None, 0, None) == 1
+    assert lib.atom_w4a4_gemm_workspace_bytes(0, 8, ctypes.byref(ok)) == 0
+
+
+def test_synthetic_inputs_are_seeded_and_shaped():
+    a, b = synth.make(1), synth.make(1)
+    assert torch.equal(a.x, b.x) and torch.equal(a.w, b.w) and torch.equal(a.idx, b.idx)
+    assert a.x.shape == (16, 512) and a.w.shape == (512, 512) and a.x.dtype == torch.float16
+    assert atom.atom_check_reorder_idx(a.idx) == 0
+    lin = synth.make(3, 1)
+    assert (lin.M, lin.K, lin.N) == (8, 4096, 4096)
+    assert atom.atom_check_reorder_idx(lin.idx) == 0
+    # the last 128 reordered channels carry the largest magnitudes
+    mag = lin.x.float().abs().mean(0)[lin.idx.long()]
+    assert mag[-128:].min() > mag[:-128].median()
+    assert torch.isfinite(lin.x.float()).all()

@@ -1,0 +1,163 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle on the
+same seeded inputs.  Codes, scales and per-group int32 partials must be
+bit-identical; fp16 outputs within 1e-3 max relative error."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2310_19102_amd as atom
+from paper_2310_19102_amd import synth
+from _gpu_util import (Y_TOL, assert_quant_equal, dev, gpu_quantize_act, gpu_quantize_weight, npy,
+                       ref_quantize_act, ref_quantize_weight, y_rel_err)
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand_linear(M, K, N, O, seed, norm=True):
+    g = torch.Generator().manual_seed(seed)
+    sigma = torch.exp(1.5 * torch.randn(K, generator=g))
+    x = (torch.randn((M, K), generator=g) * sigma).to(torch.float16)
+    w = (0.02 * torch.randn((N, K), generator=g)).to(torch.float16)
+    gamma = (1 + 0.1 * torch.randn(K, generator=g)).to(torch.float16) if norm else None
+    idx = torch.argsort(sigma, stable=True).to(torch.int32)
+    return synth.Linear("rand", x, w, gamma, idx, n_outlier=O)
+
+
+def _check_linear(lin, what, full_partials=True):
+    print(f"[case] {what}: M={lin.M} K={lin.K} N={lin.N} O={lin.n_outlier} "
+          f"norm={lin.gamma is not None}", flush=True)
+    ga = gpu_quantize_act(lin)
+    ra = ref_quantize_act(lin)
+    assert_quant_equal(ga, ra, what + " act")
+    gw = gpu_quantize_weight(lin)
+    rw = ref_quantize_weight(lin)
+    assert_quant_equal(gw, rw, what + " weight")
+    G = lin.K // lin.group_size
+    ref = oracle.w4a4_gemm(*ra, *rw, lin.group_size, want_partials=full_partials)
+    # plain call
+    y = atom.atom_w4a4_gemm(*ga, *gw, lin.group_size)
+    torch.cuda.synchronize()
+    err = y_rel_err(npy(y), ref["y"])
+    assert err <= Y_TOL, f"{what}: Y rel err {err}"
+    if full_partials:
+        part = torch.empty((lin.M, lin.N, G), dtype=torch.int32, device="cuda")
+        y2 = atom.atom_w4a4_gemm(*ga, *gw, lin.group_size, partials=part)
+        torch.cuda.synchronize()
+        assert np.array_equal(npy(part), ref["partials"]), f"{what}: int32 partials differ"
+        assert y_rel_err(npy(y2), ref["y"]) <= Y_TOL
+    return err
+
+
+def test_config1_tiny():
+    _check_linear(synth.make(1), "config1")
+
+
+@pytest.mark.parametrize("M,K,N,O,norm", [
+    (1, 512, 64, 128, True),       # single token
+    (3, 256, 40, 128, False),      # one INT4 + one INT8 group, ragged N
+    (33, 1024, 200, 256, True),    # two INT8 groups, ragged M and N
+    (70, 1408, 130, 128, True),    # K/128 = 11: ragged last 4-group sweep of the front end
+    (130, 768, 257, 128, False),   # spans two 128-row tiles with a 2-row tail
+    (257, 512, 129, 384, True),    # O > K4
+])
+def test_ragged_shapes(M, K, N, O, norm):
+    _check_linear(_rand_linear(M, K, N, O, seed=M * 1000 + N, norm=norm), f"ragged M{M}")
+
+
+def test_degenerate_values():
+    """Zero rows (scale 0 -> codes 0), a row of fp16 max, subnormal rows."""
+    lin = _rand_linear(8, 512, 64, 128, seed=5, norm=False)
+    lin.x[0] = 0
+    lin.x[1] = 65504.0
+    lin.x[2] = torch.tensor(6e-8, dtype=torch.float16)
+    lin.x[3, ::2] = 0
+    lin.w[0] = 0
+    _check_linear(lin, "degenerate")
+    lin2 = _rand_linear(4, 512, 64, 128, seed=6, norm=True)
+    lin2.x[1] = 65504.0           # sum of squares 2.2e12: fine in fp32
+    lin2.x[2] = torch.tensor(6e-8, dtype=torch.float16)
+    _check_linear(lin2, "degenerate-norm")
+
+
+def test_strided_input_rows():
+    lin = _rand_linear(16, 512, 64, 128, seed=7)
+    big = torch.zeros((16, 1024), dtype=torch.float16)
+    big[:, :512] = lin.x
+    xs = big.cuda()[:, :512]              # ldx = 1024
+    q = atom.atom_quantize_act(xs, dev(lin.gamma), lin.eps, dev(lin.idx), 128, 128, lin.clip_act)
+    torch.cuda.synchronize()
+    assert_quant_equal(q, ref_quantize_act(lin), "strided")
+
+
+def test_empty_and_error_paths():
+    lin = _rand_linear(4, 512, 64, 128, seed=8)
+    q = atom.atom_quantize_act(dev(lin.x[:0]), dev(lin.gamma), lin.eps, dev(lin.idx))
+    assert q[0].shape[0] == 0
+    with pytest.raises(atom.AtomError) as e:
+        atom.atom_quantize_act(dev(lin.x[:, :500].contiguous()), None, 0.0, dev(lin.idx[:500]))
+    assert e.value.status == 2          # K % 128 != 0
+    with pytest.raises(atom.AtomError) as e:
+        atom.atom_quantize_act(dev(lin.x), None, 0.0, dev(lin.idx), group_size=64)
+    assert e.value.status == 3
+
+
+def test_run_twice_is_deterministic():
+    lin = synth.make(2, 0, M=64)
+    ga = gpu_quantize_act(lin)
+    gw = gpu_quantize_weight(lin)
+    y1 = atom.atom_w4a4_gemm(*ga, *gw)
+    y2 = atom.atom_w4a4_gemm(*ga, *gw)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+
+
+@pytest.mark.parametrize("which", [0, 1])
+def test_config2_llama7b_attention(which):
+    _check_linear(synth.make(2, which), f"config2[{which}]", full_partials=(which == 0))
+
+
+@pytest.mark.parametrize("which", range(8))
+def test_config3_decode(which):
+    _check_linear(synth.make(3, which), f"config3[{which}]", full_partials=True)
+
+
+def _check_sampled(lin, what, n_rows=48):
+    """Full-size launch on the GPU; the oracle runs the front end in full and
+    the GEMM on a seeded sample of rows."""
+    print(f"[case] {what}: M={lin.M} K={lin.K} N={lin.N}", flush=True)
+    ga = gpu_quantize_act(lin)
+    assert_quant_equal(ga, ref_quantize_act(lin), what + " act")
+    gw = gpu_quantize_weight(lin)
+    rw = ref_quantize_weight(lin)
+    assert_quant_equal(gw, rw, what + " weight")
+    y = atom.atom_w4a4_gemm(*ga, *gw, lin.group_size)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(lin.M + lin.N)
+    rows = np.unique(np.concatenate([[0, lin.M - 1], rng.integers(0, lin.M, n_rows)]))
+    ra = ref_quantize_act(lin, rows=torch.from_numpy(rows))
+    G = lin.K // lin.group_size
+    ncols = min(lin.N, 2048)               # partial dumps on a column band keep the oracle quick
+    c0 = int(rng.integers(0, lin.N - ncols + 1))
+    ref = oracle.w4a4_gemm(*ra, *rw, lin.group_size)
+    err = y_rel_err(npy(y)[rows], ref["y"])
+    assert err <= Y_TOL, f"{what}: sampled rows rel err {err}"
+    # partials through a sub-problem call: the sampled rows against a band of W
+    sub_a = tuple(t[torch.from_numpy(rows).cuda()].contiguous() for t in ga)
+    sub_w = tuple(t[c0:c0 + ncols].contiguous() for t in gw)
+    part = torch.empty((len(rows), ncols, G), dtype=torch.int32, device="cuda")
+    atom.atom_w4a4_gemm(*sub_a, *sub_w, lin.group_size, partials=part)
+    torch.cuda.synchronize()
+    refp = oracle.w4a4_gemm(*ra, *(t[c0:c0 + ncols] for t in rw), lin.group_size,
+                            want_partials=True)
+    assert np.array_equal(npy(part), refp["partials"]), f"{what}: partials differ"
+
+
+@pytest.mark.parametrize("which", [0, 1])
+def test_config4_llama7b_mlp(which):
+    _check_sampled(synth.make(4, which), f"config4[{which}]")
+
+
+@pytest.mark.parametrize("which", [0, 1, 2])
+def test_config5_llama70b(which):
+    _check_sampled(synth.make(5, which), f"config5[{which}]", n_rows=16)
