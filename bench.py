@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the Atom W4A4 hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-extra]
+
+A "step" is one pass of the whole hot path over one batch of seeded synthetic
+input: for every linear of the workload, the fused activation front end
+(RMSNorm where the layer has one, reorder, dynamic group quantisation) followed
+by the mixed-precision group GEMM.  Weights are quantised and packed once,
+outside the timed region, and every input is resident in HBM before timing
+starts.  The default workload is the Llama-7B MLP at M=1024 (gate/up with the
+RMSNorm front end, then down with the norm-less front end).
+
+One JSON line is printed: effective TOPS = sum(2*M*N*K) / time, the roofline
+of the dominant kernel (the group GEMM) from HIP-event timings of its launches
+inside the timed region, and the CPU oracle timed on a bounded row sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import paper_2310_19102_amd as atom          # noqa: E402
+from paper_2310_19102_amd import synth       # noqa: E402
+
+PEAK_INT8_TOPS = 5000.0     # MI355X dense INT8 MFMA, TOP/s
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, GB/s
+
+WORKLOAD_NAMES = {
+    1: "tiny M=16 K=512 N=512",
+    2: "Llama-7B attention projections M=256 K=4096 N=4096 and N=12288",
+    3: "Llama-7B decode sweep M in {1,8,32,64} K=4096 N in {4096,11008}",
+    4: "Llama-7B MLP M=1024: RMSNorm+quant -> gate/up (K=4096,N=22016), quant -> down (K=11008,N=4096)",
+    5: "Llama-70B linears M=4096: QKV (8192x10240), gate/up (8192x57344), down (28672x8192)",
+}
+
+
+class DeviceLinear:
+    """Device-resident operands of one quantised linear layer."""
+
+    def __init__(self, lin, n_weight_copies=1):
+        self.name, self.M, self.K, self.N = lin.name, lin.M, lin.K, lin.N
+        self.G = lin.K // lin.group_size
+        self.lin = lin
+        self.x = lin.x.cuda()
+        self.gamma = None if lin.gamma is None else lin.gamma.cuda()
+        self.idx = lin.idx.cuda()
+        qw = atom.atom_quantize_weight(lin.w.cuda(), self.idx, lin.group_size, lin.n_outlier,
+                                       lin.clip_weight)
+        # a ring of identical packed-weight copies larger than the last-level
+        # cache makes a decode-sized GEMM read its weights from HBM every time
+        self.qw_ring = [qw] + [tuple(t.clone() for t in qw) for _ in range(n_weight_copies - 1)]
+        self.qa = tuple(torch.empty_like(t) for t in atom.atom_quantize_act(
+            self.x, self.gamma, lin.eps, self.idx, lin.group_size, lin.n_outlier, lin.clip_act))
+        self.y = torch.empty((self.M, self.N), dtype=torch.float16, device="cuda")
+        self.ops = 2 * self.M * self.N * self.K
+        row = (self.K - lin.n_outlier) // 2 + lin.n_outlier + 2 * self.G
+        self.gemm_bytes = self.N * row + self.M * row + 2 * self.M * self.N
+        self.turn = 0
+
+    def front_end(self):
+        l = self.lin
+        atom.atom_quantize_act(self.x, self.gamma, l.eps, self.idx, l.group_size, l.n_outlier,
+                               l.clip_act, out=self.qa)
+
+    def gemm(self):
+        qw = self.qw_ring[self.turn % len(self.qw_ring)]
+        self.turn += 1
+        atom.atom_w4a4_gemm(*self.qa, *qw, self.lin.group_size, out=self.y)
+
+
+def run_steps(layers, steps, warmup):
+    """Time `steps` passes; HIP events (on the stream the kernels run on)
+    bracket every GEMM launch and every front-end launch inside the timed
+    region.  Returns (seconds per step, gemm seconds per step, front-end
+    seconds per step, number of GEMM launches per step)."""
+    for _ in range(warmup):
+        for L in layers:
+            L.front_end()
+            L.gemm()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps * len(layers))]
+    t0 = time.perf_counter()
+    i = 0
+    for _ in range(steps):
+        for L in layers:
+            e = ev[i]
+            i += 1
+            e[0].record()
+            L.front_end()
+            e[1].record()
+            L.gemm()
+            e[2].record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    fe = sum(e[0].elapsed_time(e[1]) for e in ev) * 1e-3 / steps
+    ge = sum(e[1].elapsed_time(e[2]) for e in ev) * 1e-3 / steps
+    return dt / steps, ge, fe, len(layers)
+
+
+def cpu_baseline(config, sample_rows):
+    """The CPU oracle, as it stands, on the first `sample_rows` rows of every
+    linear of the workload (single thread; cost is linear in M)."""
+    import oracle
+    ops = 0
+    secs = 0.0
+    for which in range(len(synth.CONFIG_SHAPES[config])):
+        lin = synth.make(config, which)
+        rows = min(sample_rows, lin.M)
+        x = lin.x[:rows].numpy()
+        g = None if lin.gamma is None else lin.gamma.numpy()
+        rw = oracle.quantize_weight(lin.w.numpy(), lin.idx.numpy(), lin.group_size, lin.n_outlier,
+                                    lin.clip_weight)          # untimed, as on the GPU
+        t0 = time.perf_counter()
+        ra = oracle.quantize_act(x, g, lin.eps, lin.idx.numpy(), lin.group_size, lin.n_outlier,
+                                 lin.clip_act)
+        oracle.w4a4_gemm(*ra, *rw, lin.group_size)
+        secs += time.perf_counter() - t0
+        ops += 2 * rows * lin.N * lin.K
+    return {"value": ops / secs / 1e12, "unit": "TOPS", "cores": 1, "kind": "oracle",
+            "sample": f"first {sample_rows} rows of each linear of the workload, all N and K, "
+                      f"front end + GEMM, {secs:.1f} s of single-thread C",
+            "seconds": secs}
+
+
+def extra_measurements():
+    """Context lines beside the headline: the M=256 attention projection and
+    the decode-sized GEMM against the HBM roofline (weights walked through a
+    ring of copies > 1 GB so they are not served from cache)."""
+    out = []
+    lin = synth.make(2, 0)
+    L = DeviceLinear(lin)
+    t, ge, fe, _ = run_steps([L], 200, 20)
+    out.append({"workload": "config2 attn_proj M=256 K=4096 N=4096", "ms_per_step": t * 1e3,
+                "effective_tops": L.ops / t / 1e12, "gemm_us": ge * 1e6, "front_end_us": fe * 1e6,
+                "gemm_mfma_frac": L.ops / ge / 1e12 / PEAK_INT8_TOPS})
+    for which in (1, 5):                       # M=8, N=4096 and N=11008
+        lin = synth.make(3, which)
+        row = (lin.K - lin.n_outlier) // 2 + lin.n_outlier + 2 * (lin.K // lin.group_size)
+        copies = max(2, int(1.2e9 // (lin.N * row)) + 1)
+        L = DeviceLinear(lin, n_weight_copies=copies)
+        for _ in range(20):
+            L.gemm()
+        torch.cuda.synchronize()
+        # one HIP graph of `reps` launches walking the weight ring: the host's
+        # per-call cost (ctypes + Python) is then outside the measurement
+        reps = 4 * copies
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(reps):
+                L.gemm()
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        per = e0.elapsed_time(e1) * 1e-3 / (3 * reps)
+        del graph
+        t, ge, fe, _ = run_steps([L], 200, 20)
+        out.append({"workload": f"config3 decode M={lin.M} K=4096 N={lin.N}, weight ring of {copies}",
+                    "gemm_us_in_graph": per * 1e6, "gemm_bytes": L.gemm_bytes,
+                    "gemm_GBs": L.gemm_bytes / per / 1e9,
+                    "gemm_hbm_frac": L.gemm_bytes / per / 1e9 / PEAK_HBM_GBS,
+                    "step_us_front_end_plus_gemm": t * 1e6,
+                    "effective_tops": L.ops / t / 1e12})
+        del L
+        torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=4, choices=sorted(WORKLOAD_NAMES))
+    ap.add_argument("--no-extra", action="store_true", help="skip the context measurements")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--cpu-rows", type=int, default=256)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding or collectives); use --gpus 1")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    atom.load_library()
+
+    layers = [DeviceLinear(synth.make(args.config, w))
+              for w in range(len(synth.CONFIG_SHAPES[args.config]))]
+    sec, gemm_sec, fe_sec, n_gemm = run_steps(layers, args.steps, args.warmup)
+    ops = sum(L.ops for L in layers)
+    gemm_bytes = sum(L.gemm_bytes for L in layers)
+    achieved = ops / gemm_sec / 1e12
+    hbm_bound = all(L.M <= 64 for L in layers)
+    if hbm_bound:
+        roof = {"bound": "hbm", "achieved": gemm_bytes / gemm_sec / 1e9, "peak": PEAK_HBM_GBS,
+                "unit": "GB/s", "frac": gemm_bytes / gemm_sec / 1e9 / PEAK_HBM_GBS, "traffic": None}
+    else:
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                "frac": achieved / PEAK_INT8_TOPS, "traffic": None}
+    roof.update({"kernel": "w4a4_gemm_kernel", "launches_per_step": n_gemm,
+                 "avg_launch_us": gemm_sec / n_gemm * 1e6,
+                 "front_end_us_per_step": fe_sec * 1e6,
+                 "algorithmic_ops_per_step": ops, "algorithmic_bytes_per_step": gemm_bytes})
+    line = {
+        "metric": "W4A4 group-GEMM effective TOPS (incl. act quant)",
+        "value": ops / sec / 1e12, "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.config], "config_index": args.config,
+                   "linears": [{"name": L.name, "M": L.M, "K": L.K, "N": L.N} for L in layers],
+                   "group_size": 128, "n_outlier": 128, "clip_act": synth.CLIP_ACT,
+                   "clip_weight": synth.CLIP_WEIGHT},
+        "roofline": roof,
+    }
+    del layers
+    torch.cuda.empty_cache()
+    if not args.no_extra:
+        line["extra"] = extra_measurements()
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(args.config, args.cpu_rows)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -258,9 +258,13 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t stream)
     constexpr int LDS = 2 * ((BM + BN) * 128 + (BM + BN) * 4);
     const int64_t MB = (p.M + BM - 1) / BM, NB = (p.N + BN - 1) / BN;
     auto kern = &w4a4_gemm_kernel<BM, BN, WM, WN, DBG>;
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (err != hipSuccess) return err;
+    static bool configured = false;   // one attribute call per kernel variant and process
+    if (!configured) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (err != hipSuccess) return err;
+        configured = true;
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)(MB * NB)), dim3(NT), LDS, stream, p);
     return hipGetLastError();
 }

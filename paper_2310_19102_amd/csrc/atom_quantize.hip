@@ -179,25 +179,27 @@ hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, const v
                                 float eps, const int32_t *idx, int K, int O, float clip,
                                 void *q4, void *q8, void *scale, hipStream_t stream)
 {
-    const bool   norm  = gamma != nullptr;
-    const size_t lds   = quantize_lds_bytes(K, norm);
-    const int    grid  = (int)(rows < (int64_t)1 << 20 ? rows : (int64_t)1 << 20);
-    hipError_t   err;
-    if (norm) {
-        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&quantize_rows_kernel<true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const bool   norm = gamma != nullptr;
+    const size_t lds  = quantize_lds_bytes(K, norm);
+    const int    grid = (int)(rows < (int64_t)1 << 20 ? rows : (int64_t)1 << 20);
+    // the opt-in for more than 64 KB of dynamic LDS is raised only when a call needs more
+    static size_t allowed[2] = {0, 0};
+    const void *fn = norm ? reinterpret_cast<const void *>(&quantize_rows_kernel<true>)
+                          : reinterpret_cast<const void *>(&quantize_rows_kernel<false>);
+    if (lds > allowed[norm]) {
+        hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             (int)lds);
         if (err != hipSuccess) return err;
+        allowed[norm] = lds;
+    }
+    if (norm)
         hipLaunchKernelGGL(quantize_rows_kernel<true>, dim3(grid), dim3(kThreads), lds, stream,
                            (const __half *)x, rows, ld, (const __half *)gamma, eps, idx, K, O,
                            clip, (uint8_t *)q4, (int8_t *)q8, (__half *)scale);
-    } else {
-        err = hipFuncSetAttribute(reinterpret_cast<const void *>(&quantize_rows_kernel<false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (err != hipSuccess) return err;
+    else
         hipLaunchKernelGGL(quantize_rows_kernel<false>, dim3(grid), dim3(kThreads), lds, stream,
                            (const __half *)x, rows, ld, (const __half *)nullptr, eps, idx, K, O,
                            clip, (uint8_t *)q4, (int8_t *)q8, (__half *)scale);
-    }
     return hipGetLastError();
 }
 
