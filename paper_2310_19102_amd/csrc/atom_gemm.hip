@@ -25,30 +25,11 @@
 
 #include "atom_internal.h"
 
+#include "atom_gemm_common.h"
+
 namespace {
 
-typedef int v4i  __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
-struct GemmParams {
-    const uint8_t *a_q4; const int8_t *a_q8; const uint16_t *a_scale;
-    const uint8_t *w_q4; const int8_t *w_q8; const uint16_t *w_scale;
-    uint16_t *y; int32_t *partials;
-    int64_t M, N, ldy;
-    int K, O;
-};
-
-__device__ __forceinline__ float half_bits_to_float(uint16_t h)
-{
-    return __half2float(__ushort_as_half(h));
-}
-
-// Byte offset of 16-byte chunk `chunk` (0..7) of tile row `row`; the xor keeps
-// eight consecutive rows on eight different bank groups.
-__device__ __forceinline__ int lds_off(int row, int chunk)
-{
-    return row * 128 + (((chunk ^ row) & 7) << 4);
-}
+using namespace atom_gemm;
 
 template <int BM, int BN, int WM, int WN, bool DBG>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64)
@@ -274,7 +255,7 @@ hipError_t dispatch(const GemmParams &p, hipStream_t stream)
 {
     if (p.M <= 32) return launch_tile<32, 64, 32, 32, DBG>(p, stream);
     if (p.M <= 64) return launch_tile<64, 64, 32, 32, DBG>(p, stream);
-    return launch_tile<128, 128, 64, 64, DBG>(p, stream);
+    return launch_big(p, stream);
 }
 
 }  // namespace
