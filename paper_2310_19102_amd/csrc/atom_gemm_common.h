@@ -42,7 +42,7 @@ __device__ __forceinline__ int xcd_contiguous_block_id()
     return xcd * per + (xcd < rem ? xcd : rem) + (b >> 3);
 }
 
-// Big-tile software-pipelined kernel for M >= 128 (atom_gemm_big.hip).
+// Big-tile kernel for compute-bound sizes, M > 64 (atom_gemm_big.hip).
 hipError_t launch_big(const GemmParams &p, hipStream_t stream);
 
 }  // namespace atom_gemm
