@@ -177,6 +177,23 @@ def extra_measurements():
     return out
 
 
+def measured_traffic(config):
+    """HBM bytes per GEMM launch from the committed rocprofv3 --pmc summary of this
+    workload (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", f"traffic_config{config}.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    with open(path) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#") and "=" in line:
+                k, v = line.split("=", 1)
+                vals[k.strip()] = float(v.split()[0])
+    if "gemm_fetch_bytes_per_launch" in vals and "gemm_write_bytes_per_launch" in vals:
+        return vals["gemm_fetch_bytes_per_launch"] + vals["gemm_write_bytes_per_launch"]
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -186,12 +203,23 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the context measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--cpu-rows", type=int, default=256)
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding or collectives); use --gpus 1")
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     atom.load_library()
+
+    if args.pmc_calibrate:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)                  # reads 1 GiB, writes 1 GiB per launch
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     layers = [DeviceLinear(synth.make(args.config, w))
               for w in range(len(synth.CONFIG_SHAPES[args.config]))]
@@ -202,11 +230,12 @@ def main():
     hbm_bound = all(L.M <= 64 for L in layers)
     if hbm_bound:
         roof = {"bound": "hbm", "achieved": gemm_bytes / gemm_sec / 1e9, "peak": PEAK_HBM_GBS,
-                "unit": "GB/s", "frac": gemm_bytes / gemm_sec / 1e9 / PEAK_HBM_GBS, "traffic": None}
+                "unit": "GB/s", "frac": gemm_bytes / gemm_sec / 1e9 / PEAK_HBM_GBS,
+                "traffic": measured_traffic(args.config)}
     else:
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-                "frac": achieved / PEAK_INT8_TOPS, "traffic": None}
-    roof.update({"kernel": "w4a4_gemm_kernel", "launches_per_step": n_gemm,
+                "frac": achieved / PEAK_INT8_TOPS, "traffic": measured_traffic(args.config)}
+    roof.update({"kernel": "w4a4_gemm_decode_kernel" if hbm_bound else "w4a4_gemm_big_kernel", "launches_per_step": n_gemm,
                  "avg_launch_us": gemm_sec / n_gemm * 1e6,
                  "front_end_us_per_step": fe_sec * 1e6,
                  "algorithmic_ops_per_step": ops, "algorithmic_bytes_per_step": gemm_bytes})

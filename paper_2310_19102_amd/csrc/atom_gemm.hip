@@ -253,6 +253,7 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t stream)
 template <bool DBG>
 hipError_t dispatch(const GemmParams &p, hipStream_t stream)
 {
+    if (!DBG && p.M <= 64) return launch_decode(p, stream);
     if (p.M <= 32) return launch_tile<32, 64, 32, 32, DBG>(p, stream);
     if (p.M <= 64) return launch_tile<64, 64, 32, 32, DBG>(p, stream);
     return launch_big(p, stream);

@@ -45,5 +45,8 @@ __device__ __forceinline__ int xcd_contiguous_block_id()
 // Big-tile kernel for compute-bound sizes, M > 64 (atom_gemm_big.hip).
 hipError_t launch_big(const GemmParams &p, hipStream_t stream);
 
+// Weight-streaming kernel for decode-sized M <= 64 (atom_gemm_decode.hip).
+hipError_t launch_decode(const GemmParams &p, hipStream_t stream);
+
 }  // namespace atom_gemm
 #endif

@@ -1,0 +1,199 @@
+// Weight-streaming variant of the group GEMM for decode-sized M (M <= 64).
+//
+// Same arithmetic as atom_gemm.hip (Section 4.2 of the paper, steps 1-3), except
+// that the per-group terms of one output are summed in a fixed tree (eight K-slices,
+// each in ascending group order, then slices 0..7) instead of one ascending chain.
+//
+// At these sizes the kernel is bound by reading the packed weights once from HBM
+// (Section 3 of the paper: small-batch dense layers are memory-bound), so the
+// layout of the work follows the weight bytes:
+//   * a workgroup (8 wavefronts) owns 16 output channels = 16 weight rows, all of K;
+//     N/16 workgroups keep every CU busy even at N = 4096;
+//   * wavefront w owns a contiguous run of groups of those rows (split-K inside the
+//     workgroup); it fetches its weight bytes with one 128-bit load per lane and
+//     group (16 rows x 64 bytes per instruction, four groups in flight) and never
+//     shares them, so no LDS staging and no barrier sits on the streaming path;
+//   * the activation codes (M x K/2 bytes, L2-resident) are fetched per wavefront
+//     in the same MFMA register layout; rows >= M are zeros;
+//   * the contraction is the INT8 MFMA 16x16x64: one 128-channel INT4 group is two
+//     MFMAs (even-position and odd-position codes after the nibble widening), an
+//     INT8 group is two MFMAs of 64 channels;
+//   * each wavefront dequantises its own groups into fp32 (convert, scale product,
+//     fused multiply-add), the eight partial tiles meet in LDS once, at the end.
+//
+// MFMA 16x16x64 i8 layout: lane l supplies row (l & 15) of its operand and the
+// 16 bytes of K-chunk (l >> 4); the result has column (l & 15) in lane l and rows
+// 4*(l >> 4) + e in register e = 0..3.  Activations are the row operand.
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "atom_gemm_common.h"
+
+namespace {
+
+using namespace atom_gemm;
+
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+constexpr int NW = 8;                     // wavefronts per workgroup = K-slices
+constexpr int NT = NW * 64;
+constexpr int TN = 16;                    // output channels per workgroup
+
+__device__ __forceinline__ v4i widen_lo(const uint4 &w)
+{
+    v4u t = {(w.x << 4) & 0xF0F0F0F0u, (w.y << 4) & 0xF0F0F0F0u, (w.z << 4) & 0xF0F0F0F0u,
+             (w.w << 4) & 0xF0F0F0F0u};
+    return __builtin_bit_cast(v4i, t);
+}
+__device__ __forceinline__ v4i widen_hi(const uint4 &w)
+{
+    v4u t = {w.x & 0xF0F0F0F0u, w.y & 0xF0F0F0F0u, w.z & 0xF0F0F0F0u, w.w & 0xF0F0F0F0u};
+    return __builtin_bit_cast(v4i, t);
+}
+
+// RB: 16-row blocks of activations (M <= 16 * RB)
+template <int RB>
+__global__ __launch_bounds__(NT)
+void w4a4_gemm_decode_kernel(const GemmParams p)
+{
+    __shared__ float red[NW][RB][4][64];   // [slice][row block][register][lane]
+    // groups whose loads are in flight together per wavefront (register budget)
+    constexpr int DEPTH = RB >= 4 ? 2 : 4;
+
+    const int tid  = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int col = lane & 15, kc = lane >> 4;
+
+    const int K4 = p.K - p.O, G = p.K >> 7, G4 = K4 >> 7;
+    const int64_t n0 = (int64_t)blockIdx.x * TN;
+
+    // this wavefront's run of groups
+    const int g_begin = (int)((int64_t)wave * G / NW);
+    const int g_end   = (int)((int64_t)(wave + 1) * G / NW);
+
+    // weight row of this lane (clamped: rows >= N are computed and never stored)
+    int64_t wr = n0 + col;
+    wr = wr < p.N ? wr : p.N - 1;
+    const uint8_t  *w4 = p.w_q4 + wr * (K4 >> 1) + kc * 16;
+    const int8_t   *w8 = p.w_q8 + wr * p.O + kc * 16;
+    const uint16_t *ws = p.w_scale + wr * G;
+    // activation rows of this lane as the MFMA row operand (row = col index here)
+    const uint8_t *a4[RB];
+    const int8_t  *a8[RB];
+    bool a_ok[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int64_t m = 16 * rb + col;
+        a_ok[rb] = m < p.M;
+        const int64_t mc = a_ok[rb] ? m : 0;
+        a4[rb] = p.a_q4 + mc * (K4 >> 1) + kc * 16;
+        a8[rb] = p.a_q8 + mc * p.O + kc * 16;
+    }
+    // rows of the result held by this lane: 16*rb + 4*kc + e
+    float acc[RB][4];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[rb][e] = 0.0f;
+
+    const v4i zi = {0, 0, 0, 0};
+    const uint4 z4 = make_uint4(0, 0, 0, 0);
+
+    // Groups are processed in batches of DEPTH.  Every load of a batch (weight codes,
+    // weight scales, activation codes, activation scales) is issued before the first is
+    // used, so a wavefront pays the memory latency once per batch, not once per group.
+    for (int gb = g_begin; gb < g_end; gb += DEPTH) {
+        uint4    wq[DEPTH][2];            // [group][half]: an INT4 group uses half 0 only
+        uint4    aq[DEPTH][RB][2];
+        uint16_t wsc[DEPTH];
+        uint16_t asc[DEPTH][RB][4];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const int  g    = gb + d;
+            const bool live = g < g_end;
+            const int  gc   = live ? g : g_end - 1;         // dead slots re-read the last group
+            const bool is4  = gc < G4;
+            if (is4) {
+                wq[d][0] = *reinterpret_cast<const uint4 *>(w4 + (size_t)gc * 64);
+                wq[d][1] = z4;
+            } else {
+                wq[d][0] = *reinterpret_cast<const uint4 *>(w8 + (size_t)(gc - G4) * 128);
+                wq[d][1] = *reinterpret_cast<const uint4 *>(w8 + (size_t)(gc - G4) * 128 + 64);
+            }
+            wsc[d] = ws[gc];
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                aq[d][rb][0] = z4; aq[d][rb][1] = z4;
+                if (a_ok[rb]) {
+                    if (is4) {
+                        aq[d][rb][0] = *reinterpret_cast<const uint4 *>(a4[rb] + (size_t)gc * 64);
+                    } else {
+                        aq[d][rb][0] = *reinterpret_cast<const uint4 *>(a8[rb] + (size_t)(gc - G4) * 128);
+                        aq[d][rb][1] = *reinterpret_cast<const uint4 *>(a8[rb] + (size_t)(gc - G4) * 128 + 64);
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int64_t m = 16 * rb + 4 * kc + e;
+                    asc[d][rb][e] = m < p.M ? p.a_scale[m * G + gc] : (uint16_t)0;
+                }
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            const int g = gb + d;
+            if (g >= g_end) break;
+            const bool is4 = g < G4;
+            v4i b0, b1;
+            if (is4) { b0 = widen_lo(wq[d][0]); b1 = widen_hi(wq[d][0]); }
+            else     { b0 = __builtin_bit_cast(v4i, wq[d][0]); b1 = __builtin_bit_cast(v4i, wq[d][1]); }
+            // 2^-8 of the nibble widening folded into the weight scale (exact)
+            const float wsf = half_bits_to_float(wsc[d]) * (is4 ? (1.0f / 256.0f) : 1.0f);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                v4i x0, x1;
+                if (is4) { x0 = widen_lo(aq[d][rb][0]); x1 = widen_hi(aq[d][rb][0]); }
+                else     { x0 = __builtin_bit_cast(v4i, aq[d][rb][0]); x1 = __builtin_bit_cast(v4i, aq[d][rb][1]); }
+                v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(x0, b0, zi, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_i32_16x16x64_i8(x1, b1, c, 0, 0, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    acc[rb][e] = fmaf((float)c[e], half_bits_to_float(asc[d][rb][e]) * wsf, acc[rb][e]);
+            }
+        }
+    }
+
+    // the eight K-slices meet in LDS and are added in slice order
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) red[wave][rb][e][lane] = acc[rb][e];
+    __syncthreads();
+    for (int idx = tid; idx < RB * 4 * 64; idx += NT) {
+        const int l = idx & 63, e = (idx >> 6) & 3, rb = idx >> 8;
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s += red[w][rb][e][l];
+        const int64_t m = 16 * rb + 4 * (l >> 4) + e;
+        const int64_t n = n0 + (l & 15);
+        if (m < p.M && n < p.N) p.y[m * p.ldy + n] = __half_as_ushort(__float2half_rn(s));
+    }
+}
+
+}  // namespace
+
+namespace atom_gemm {
+
+hipError_t launch_decode(const GemmParams &p, hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)((p.N + TN - 1) / TN);
+    if (p.M <= 16)      hipLaunchKernelGGL(w4a4_gemm_decode_kernel<1>, dim3(blocks), dim3(NT), 0, stream, p);
+    else if (p.M <= 32) hipLaunchKernelGGL(w4a4_gemm_decode_kernel<2>, dim3(blocks), dim3(NT), 0, stream, p);
+    else                hipLaunchKernelGGL(w4a4_gemm_decode_kernel<4>, dim3(blocks), dim3(NT), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace atom_gemm

@@ -60,6 +60,11 @@ def test_config1_tiny():
     (70, 1408, 130, 128, True),    # K/128 = 11: ragged last 4-group sweep of the front end
     (130, 768, 257, 128, False),   # spans two 128-row tiles with a 2-row tail
     (257, 512, 129, 384, True),    # O > K4
+    (8, 1408, 100, 128, True),     # decode kernel: 11 groups over 8 K-slices, ragged N
+    (17, 896, 48, 256, False),     # decode kernel, two row blocks, two INT8 groups
+    (40, 640, 33, 128, True),      # decode kernel, four row blocks; fewer groups than slices
+    (64, 2304, 16, 128, True),     # decode kernel at its largest M, several load batches
+    (65, 384, 72, 128, True),      # smallest M of the big-tile kernel
 ])
 def test_ragged_shapes(M, K, N, O, norm):
     _check_linear(_rand_linear(M, K, N, O, seed=M * 1000 + N, norm=norm), f"ragged M{M}")
