@@ -11,8 +11,8 @@
 //   (3) pulling operand fragments per wavefront straight from L1 saturates the
 //       texture path, so operands are shared through LDS.
 //
-// Workgroup tile 256 x 128, eight wavefronts of 64 x 64 (four 32x32 sub-tiles),
-// two LDS stages, one barrier per K-step.  A K-step moves 64 bytes per operand
+// Workgroup tile 256 x 128 (eight wavefronts) or 128 x 128 (four), wavefront tile
+// 64 x 64 (four 32x32 sub-tiles), two LDS stages, one barrier per K-step.  A K-step moves 64 bytes per operand
 // row HBM -> registers -> LDS (an INT4 group, widened to 128 INT8 bytes on the
 // way; an INT8 group is two half-steps).  Inside a step the hot loop is one
 // branch-free basic block in which the four MFMAs of sub-tile t+1 and the fp16
@@ -42,23 +42,26 @@ typedef float    v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v4h  __attribute__((ext_vector_type(4)));
 typedef unsigned v2u  __attribute__((ext_vector_type(2)));
 
-constexpr int BM = 256, BN = 128;          // workgroup tile
-constexpr int NT = 512;                    // 8 wavefronts: 4 down M x 2 along N
-constexpr int CH = (BM + BN) * 4 / NT;     // 16-byte chunks per thread per K-step (2 act + 1 weight)
-constexpr int STAGE = (BM + BN) * 128 + NT * 4;     // codes + one scale slot per thread
-static_assert(CH == 3 && BM * 4 / NT == 2, "loader layout");
-static_assert(BM + BN <= NT, "one scale per thread");
-
-template <bool DBG>
-__global__ __launch_bounds__(NT)
+// BM x BN: workgroup tile; (BM/64) x (BN/64) wavefronts, at least two per SIMD resident
+template <int BM, int BN, bool DBG>
+__global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, 2)
 void w4a4_gemm_big_kernel(const GemmParams p)
 {
+    constexpr int WM = BM / 64;                         // wavefronts down M
+    constexpr int NT = WM * (BN / 64) * 64;
+    constexpr int RPT = NT / 4;                         // tile rows covered by one loader pass
+    constexpr int CH = (BM + BN) / RPT;                 // 16-byte chunks per thread per K-step
+    constexpr int CHA = BM / RPT;                       // of which activation rows
+    constexpr int STAGE = (BM + BN) * 128 + NT * 4;     // codes + one scale slot per thread
+    static_assert(BM % RPT == 0 && BN % RPT == 0 && RPT % 8 == 0, "loader layout");
+    static_assert(BM + BN <= NT, "one scale per thread");
+
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid  = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wm = wave & 3, wn = wave >> 2;
+    const int wm = wave % WM, wn = wave / WM;
     const int r = lane & 31, h = lane >> 5;
 
     const int K4 = p.K - p.O, G = p.K >> 7, G4 = K4 >> 7, G8 = p.O >> 7;
@@ -69,19 +72,18 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     const int64_t m0  = (int64_t)(logical % MB) * BM;
     const int64_t n0  = (int64_t)(logical / MB) * BN;
 
-    // ---- loader: thread -> (tile row, 16-byte chunk); chunks 0,1 are activation rows
-    // wrow and wrow+128, chunk 2 is weight row wrow.  Rows clamp to the last valid row
-    // (such tile rows are computed and never stored).  32-bit offsets: arrays < 4 GiB.
+    // ---- loader: thread -> (tile row, 16-byte chunk).  Pass i covers rows wrow + i*RPT of
+    // the stacked tile (BM activation rows, then BN weight rows).  Rows clamp to the last
+    // valid row (such tile rows are computed and never stored).  32-bit offsets: arrays
+    // < 4 GiB.
     const int wrow = tid >> 2, wc = tid & 3;
     uint32_t o4[CH];
-    {
-        int64_t ra0 = m0 + wrow, ra1 = m0 + wrow + 128, rb = n0 + wrow;
-        ra0 = ra0 < p.M ? ra0 : p.M - 1;
-        ra1 = ra1 < p.M ? ra1 : p.M - 1;
-        rb  = rb < p.N ? rb : p.N - 1;
-        o4[0] = (uint32_t)(ra0 * (K4 >> 1)) + wc * 16;
-        o4[1] = (uint32_t)(ra1 * (K4 >> 1)) + wc * 16;
-        o4[2] = (uint32_t)(rb * (K4 >> 1)) + wc * 16;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        int64_t row = i < CHA ? m0 + wrow + i * RPT : n0 + wrow + (i - CHA) * RPT;
+        const int64_t last = i < CHA ? p.M - 1 : p.N - 1;
+        row = row < last ? row : last;
+        o4[i] = (uint32_t)(row * (K4 >> 1)) + wc * 16;
     }
     // the one scale this thread stages per group: element offset, or none
     const uint16_t *sbase = tid < BM ? p.a_scale : p.w_scale;
@@ -106,16 +108,18 @@ void w4a4_gemm_big_kernel(const GemmParams p)
             // INT8 steps are few: their row offsets are recomputed instead of kept in VGPRs
             const uint32_t col = (uint32_t)(u - G4) * 64 + wc * 16;   // g8*128 + half*64 + chunk
             const uint32_t h4 = (uint32_t)(K4 >> 1), o = (uint32_t)p.O;
-            const uint32_t r0 = (o4[0] - wc * 16) / h4, r1 = (o4[1] - wc * 16) / h4, r2 = (o4[2] - wc * 16) / h4;
-            pre[0] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(p.a_q8) + (size_t)(r0 * o + col));
-            pre[1] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(p.a_q8) + (size_t)(r1 * o + col));
-            pre[2] = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(p.w_q8) + (size_t)(r2 * o + col));
+#pragma unroll
+            for (int i = 0; i < CH; ++i) {
+                const uint32_t row = (o4[i] - wc * 16) / h4;
+                const uint8_t *src = reinterpret_cast<const uint8_t *>(i < CHA ? p.a_q8 : p.w_q8);
+                pre[i] = *reinterpret_cast<const uint4 *>(src + (size_t)(row * o + col));
+            }
             sc = sbase[(size_t)(soff + (uint32_t)(G4 + ((u - G4) >> 1)))];
         } else {
             const uint32_t col = (uint32_t)u * 64;
-            pre[0] = *reinterpret_cast<const uint4 *>(p.a_q4 + (size_t)(o4[0] + col));
-            pre[1] = *reinterpret_cast<const uint4 *>(p.a_q4 + (size_t)(o4[1] + col));
-            pre[2] = *reinterpret_cast<const uint4 *>(p.w_q4 + (size_t)(o4[2] + col));
+#pragma unroll
+            for (int i = 0; i < CH; ++i)
+                pre[i] = *reinterpret_cast<const uint4 *>((i < CHA ? p.a_q4 : p.w_q4) + (size_t)(o4[i] + col));
             sc = sbase[(size_t)(soff + (uint32_t)u)];
         }
     };
@@ -125,7 +129,7 @@ void w4a4_gemm_big_kernel(const GemmParams p)
         if (decltype(is8)::value) {
 #pragma unroll
             for (int i = 0; i < CH; ++i)
-                *reinterpret_cast<uint4 *>(base + w8 + i * 128 * 128) = pre[i];
+                *reinterpret_cast<uint4 *>(base + w8 + i * RPT * 128) = pre[i];
         } else {
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
@@ -135,8 +139,8 @@ void w4a4_gemm_big_kernel(const GemmParams p)
                 lo.y = (w.y << 4) & 0xF0F0F0F0u; hi.y = w.y & 0xF0F0F0F0u;
                 lo.z = (w.z << 4) & 0xF0F0F0F0u; hi.z = w.z & 0xF0F0F0F0u;
                 lo.w = (w.w << 4) & 0xF0F0F0F0u; hi.w = w.w & 0xF0F0F0F0u;
-                *reinterpret_cast<uint4 *>(base + w4lo + i * 128 * 128) = lo;
-                *reinterpret_cast<uint4 *>(base + w4hi + i * 128 * 128) = hi;
+                *reinterpret_cast<uint4 *>(base + w4lo + i * RPT * 128) = lo;
+                *reinterpret_cast<uint4 *>(base + w4hi + i * RPT * 128) = hi;
             }
         }
         // threads beyond the tile rows write a slot nobody reads: no branch in the hot loop
@@ -325,7 +329,7 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     // layout directly would write 2 bytes per lane).  The last step ended with a barrier,
     // so the stages are free; each wavefront uses a private region, row stride 144 bytes.
     constexpr int OSTRIDE = 144;
-    static_assert(8 * 64 * OSTRIDE <= 2 * STAGE, "output staging fits the operand stages");
+    static_assert((NT / 64) * 64 * OSTRIDE <= 2 * STAGE, "output staging fits the operand stages");
     unsigned char *ot = smem + wave * (64 * OSTRIDE);
 #pragma unroll
     for (int t = 0; t < 4; ++t)
@@ -357,12 +361,13 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     }
 }
 
-template <bool DBG>
+template <int BM, int BN, bool DBG>
 hipError_t launch_cfg(const GemmParams &p, hipStream_t stream)
 {
-    constexpr int LDS = 2 * STAGE;
+    constexpr int NT = (BM / 64) * (BN / 64) * 64;
+    constexpr int LDS = 2 * ((BM + BN) * 128 + NT * 4);
     const int64_t MB = (p.M + BM - 1) / BM, NB = (p.N + BN - 1) / BN;
-    auto kern = &w4a4_gemm_big_kernel<DBG>;
+    auto kern = &w4a4_gemm_big_kernel<BM, BN, DBG>;
     static bool configured = false;   // one attribute call per kernel variant and process
     if (!configured) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -380,7 +385,13 @@ namespace atom_gemm {
 
 hipError_t launch_big(const GemmParams &p, hipStream_t stream)
 {
-    return p.partials ? launch_cfg<true>(p, stream) : launch_cfg<false>(p, stream);
+    if (p.partials) return launch_cfg<128, 128, true>(p, stream);
+    // The 256 x 128 tile does a third less loader work per MFMA; the 128 x 128 tile is
+    // for shapes whose 256 x 128 tiles would leave compute units idle (one 512-thread
+    // workgroup per CU; two of the 256-thread ones).
+    const int64_t big_tiles = ((p.M + 255) / 256) * ((p.N + 127) / 128);
+    if (big_tiles < 512) return launch_cfg<128, 128, false>(p, stream);
+    return launch_cfg<256, 128, false>(p, stream);
 }
 
 }  // namespace atom_gemm
