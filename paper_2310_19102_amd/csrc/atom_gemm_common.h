@@ -24,11 +24,17 @@ __device__ __forceinline__ float half_bits_to_float(uint16_t h)
     return __half2float(__ushort_as_half(h));
 }
 
-// Byte offset of 16-byte chunk `chunk` (0..7) of tile row `row`; the xor keeps
-// eight consecutive rows on eight different bank groups.
+// Byte offset of 16-byte chunk `chunk` (0..7) of tile row `row` (128 bytes per row).
+// Measured on gfx950: a 128-bit LDS read is served 16 lanes per pass out of 64 banks of
+// 4 bytes, so two consecutive rows span the banks once, and a fragment read (16
+// consecutive rows, one chunk index) is conflict-free only if those rows land on 16
+// different 16-byte bank groups.  Xor-ing the chunk with the low three row bits alone
+// repeats after eight rows (2-way conflicts, half the read rate); folding row bit 3 in
+// separates rows r and r+8.  The loader's 128-bit writes (4 rows x 4 chunks per 16
+// lanes) run at their full rate with it as well.  The pattern has period 16 rows.
 __device__ __forceinline__ int lds_off(int row, int chunk)
 {
-    return row * 128 + (((chunk ^ row) & 7) << 4);
+    return row * 128 + (((chunk ^ row ^ ((row >> 3) & 1)) & 7) << 4);
 }
 
 
