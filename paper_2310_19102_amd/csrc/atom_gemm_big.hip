@@ -1,28 +1,27 @@
 // Big-tile variant of the group GEMM for compute-bound sizes (M > 64).
 // Same arithmetic as atom_gemm.hip (Section 4.2 of the paper, steps 1-3); what
-// differs is the schedule, built on three measurements on gfx950:
-//   (1) vector instructions placed between the MFMAs of ONE wavefront are almost
-//       free (the matrix pipe runs 32 cycles per 32x32x32 MFMA), whereas a
-//       wavefront that issues MFMAs back to back starves the other wavefront of
-//       its SIMD of vector issue slots, so overlap has to be built inside each
-//       wavefront's own instruction stream;
-//   (2) the per-group dequantise-accumulate costs about as many vector cycles as
-//       the group's integer MFMAs cost matrix cycles;
+// differs is the schedule, built on measurements on gfx950:
+//   (1) a wavefront keeps issuing vector instructions while its own MFMA runs (32 cycles
+//       per 32x32x32 INT8 MFMA), and with two wavefronts per SIMD a stream of "one MFMA,
+//       eight vector instructions" runs at the vector-ALU rate with the matrix pipe
+//       about 75% busy, provided no slot of that stream waits on memory;
+//   (2) the per-group dequantise-accumulate (one convert and one fused multiply-add per
+//       output element) costs more vector cycles than the group's integer MFMAs cost
+//       matrix cycles, so the vector ALU, not the matrix pipe, bounds this kernel;
 //   (3) pulling operand fragments per wavefront straight from L1 saturates the
 //       texture path, so operands are shared through LDS.
 //
 // Workgroup tile 256 x 128 (eight wavefronts) or 128 x 128 (four), wavefront tile
-// 64 x 64 (four 32x32 sub-tiles), two LDS stages, one barrier per K-step.  A K-step moves 64 bytes per operand
-// row HBM -> registers -> LDS (an INT4 group, widened to 128 INT8 bytes on the
-// way; an INT8 group is two half-steps).  Inside a step the hot loop is one
-// branch-free basic block in which the four MFMAs of sub-tile t+1 and the fp16
-// MFMA that produces the tile of scale products are interleaved with the
-// convert + fused-multiply-add of sub-tile t and with the widening and LDS
-// writes of the NEXT step's operands.
+// 64 x 64 (four 32x32 sub-tiles), two LDS stages, one barrier per K-step.  A K-step is
+// one 128-channel group: 128 bytes per operand row in LDS (an INT4 group travels HBM ->
+// registers -> LDS and is widened to INT8 on the way; an INT8 group is copied).  A step
+// is twenty "slots" of one MFMA each, fenced so that the compiler keeps their order; the
+// vector and memory work of a slot never consumes what the same slot produced (see
+// `step`).
 //
 // The 32x32 tile of scale products a_scale[m,g] * w_scale[n,g] is one fp16 MFMA
 // (rank-1, single non-zero k; the product of two fp16 values is exact in its
-// fp32 accumulator), so the epilogue is one convert and one fused multiply-add
+// fp32 accumulator), so the dequantisation is one convert and one fused multiply-add
 // per element.  INT4 steps carry the 2^8 of the nibble widening in the
 // accumulators; they are rescaled once, before the first INT8 step.
 
@@ -52,6 +51,7 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     constexpr int RPT = NT / 4;                         // tile rows covered by one loader pass
     constexpr int CH = (BM + BN) / RPT;                 // 16-byte chunks per thread per K-step
     constexpr int CHA = BM / RPT;                       // of which activation rows
+    constexpr int CH8 = (BM + BN) * 8 / NT;             // 16-byte chunks per thread of an INT8 group
     constexpr int STAGE = (BM + BN) * 128 + NT * 4;     // codes + one scale slot per thread
     static_assert(BM % RPT == 0 && BN % RPT == 0 && RPT % 8 == 0, "loader layout");
     static_assert(BM + BN <= NT, "one scale per thread");
@@ -64,8 +64,8 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     const int wm = wave % WM, wn = wave / WM;
     const int r = lane & 31, h = lane >> 5;
 
-    const int K4 = p.K - p.O, G = p.K >> 7, G4 = K4 >> 7, G8 = p.O >> 7;
-    const int U  = G4 + 2 * G8;                         // K-steps of 64 bytes per row
+    const int K4 = p.K - p.O, G = p.K >> 7, G4 = K4 >> 7;
+    const int U  = G;                                   // one K-step per group
 
     const int MB      = (int)((p.M + BM - 1) / BM);
     const int logical = xcd_contiguous_block_id();
@@ -98,56 +98,55 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     }
     const int w4lo = lds_off(wrow, wc * 2);             // widened INT4: even-position codes
     const int w4hi = lds_off(wrow, wc * 2 + 1);         //               odd-position codes
-    const int w8   = lds_off(wrow, wc);                 // INT8 half-step: straight copy, chunks 0..3
 
     uint4    pre[CH];
     uint32_t sc = 0;
 
-    auto prefetch = [&](int u, auto is8) {
-        if (decltype(is8)::value) {
-            // INT8 steps are few: their row offsets are recomputed instead of kept in VGPRs
-            const uint32_t col = (uint32_t)(u - G4) * 64 + wc * 16;   // g8*128 + half*64 + chunk
-            const uint32_t h4 = (uint32_t)(K4 >> 1), o = (uint32_t)p.O;
-#pragma unroll
-            for (int i = 0; i < CH; ++i) {
-                const uint32_t row = (o4[i] - wc * 16) / h4;
-                const uint8_t *src = reinterpret_cast<const uint8_t *>(i < CHA ? p.a_q8 : p.w_q8);
-                pre[i] = *reinterpret_cast<const uint4 *>(src + (size_t)(row * o + col));
-            }
-            sc = sbase[(size_t)(soff + (uint32_t)(G4 + ((u - G4) >> 1)))];
-        } else {
-            const uint32_t col = (uint32_t)u * 64;
-#pragma unroll
-            for (int i = 0; i < CH; ++i)
-                pre[i] = *reinterpret_cast<const uint4 *>((i < CHA ? p.a_q4 : p.w_q4) + (size_t)(o4[i] + col));
-            sc = sbase[(size_t)(soff + (uint32_t)u)];
-        }
+    // Loader items.  Chunk i of an INT4 group travels global -> registers (fetch_chunk) a
+    // whole K-step before it travels registers -> LDS (stage_chunk); every group's scale
+    // likewise.
+    auto fetch_chunk = [&](int i, int u) __attribute__((always_inline)) {
+        pre[i] = *reinterpret_cast<const uint4 *>((i < CHA ? p.a_q4 : p.w_q4) + (size_t)(o4[i] + (uint32_t)u * 64));
     };
-    // registers -> LDS stage S; the scale goes in as raw fp16 bits (an MFMA operand)
-    auto stage_to_lds = [&](auto is8, auto stage_c) {
-        unsigned char *base = smem + decltype(stage_c)::value * STAGE;
-        if (decltype(is8)::value) {
-#pragma unroll
-            for (int i = 0; i < CH; ++i)
-                *reinterpret_cast<uint4 *>(base + w8 + i * RPT * 128) = pre[i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < CH; ++i) {
-                const uint4 w = pre[i];
-                uint4 lo, hi;
-                lo.x = (w.x << 4) & 0xF0F0F0F0u; hi.x = w.x & 0xF0F0F0F0u;
-                lo.y = (w.y << 4) & 0xF0F0F0F0u; hi.y = w.y & 0xF0F0F0F0u;
-                lo.z = (w.z << 4) & 0xF0F0F0F0u; hi.z = w.z & 0xF0F0F0F0u;
-                lo.w = (w.w << 4) & 0xF0F0F0F0u; hi.w = w.w & 0xF0F0F0F0u;
-                *reinterpret_cast<uint4 *>(base + w4lo + i * RPT * 128) = lo;
-                *reinterpret_cast<uint4 *>(base + w4hi + i * RPT * 128) = hi;
-            }
-        }
-        // threads beyond the tile rows write a slot nobody reads: no branch in the hot loop
+    auto fetch_scale = [&](int u) __attribute__((always_inline)) {
+        sc = sbase[(size_t)(soff + (uint32_t)u)];
+    };
+    auto stage_chunk = [&](int i, unsigned char *base) __attribute__((always_inline)) {
+        const uint4 w = pre[i];
+        uint4 lo, hi;
+        lo.x = (w.x << 4) & 0xF0F0F0F0u; hi.x = w.x & 0xF0F0F0F0u;
+        lo.y = (w.y << 4) & 0xF0F0F0F0u; hi.y = w.y & 0xF0F0F0F0u;
+        lo.z = (w.z << 4) & 0xF0F0F0F0u; hi.z = w.z & 0xF0F0F0F0u;
+        lo.w = (w.w << 4) & 0xF0F0F0F0u; hi.w = w.w & 0xF0F0F0F0u;
+        *reinterpret_cast<uint4 *>(base + w4lo + i * RPT * 128) = lo;
+        *reinterpret_cast<uint4 *>(base + w4hi + i * RPT * 128) = hi;
+    };
+    // the scale goes in as raw fp16 bits (an MFMA operand); threads beyond the tile rows
+    // write a slot nobody reads: no branch in the hot loop
+    auto stage_scale = [&](unsigned char *base) __attribute__((always_inline)) {
         reinterpret_cast<uint32_t *>(base + (BM + BN) * 128)[tid] = has_scale ? sc : 0u;
     };
+    // An INT8 group (few: one per 128 outlier channels) is copied global -> LDS inside the
+    // step before it, without a step of slack: 128 bytes per tile row, CH8 chunks per thread.
+    auto stage_int8 = [&](int u, unsigned char *base) __attribute__((always_inline)) {
+        uint4 t8[CH8];
+#pragma unroll
+        for (int i = 0; i < CH8; ++i) {
+            const int id = tid + NT * i, row = id >> 3, ch = id & 7;
+            int64_t grow = row < BM ? m0 + row : n0 + (row - BM);
+            const int64_t last = row < BM ? p.M - 1 : p.N - 1;
+            grow = grow < last ? grow : last;
+            const int8_t *src = (row < BM ? p.a_q8 : p.w_q8) + grow * p.O + (size_t)(u - G4) * 128 + ch * 16;
+            t8[i] = *reinterpret_cast<const uint4 *>(src);
+        }
+#pragma unroll
+        for (int i = 0; i < CH8; ++i) {
+            const int id = tid + NT * i;
+            *reinterpret_cast<uint4 *>(base + lds_off(id >> 3, id & 7)) = t8[i];
+        }
+    };
 
-    // ---- fragment addresses: loop invariant; stage and sub-tile offsets are immediates ---
+    // ---- fragment addresses within a stage: loop invariant ------------------------------
     int a_addr[4], b_addr[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
@@ -166,168 +165,202 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     const v16i zi = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     const v16f zf = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
-    auto scale_tile = [&](uint32_t abits, uint32_t bbits) {
+    auto scale_tile = [&](uint32_t abits, uint32_t bbits) __attribute__((always_inline)) {
         const v2u ta = {abits, 0u}, tb = {bbits, 0u};
         return __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_bit_cast(v4h, ta),
                                                     __builtin_bit_cast(v4h, tb), zf, 0, 0, 0);
     };
-    // steps 2 and 3 for one 32x32 sub-tile (i, j) of K-step u
-    auto epilogue = [&](int u, int i, int j, const v16i &c, const v16f &ss) {
+    // steps 2 and 3 for elements e0 .. e0+ne-1 of the 32x32 sub-tile (i, j) of K-step u
+    auto epilogue = [&](int u, int i, int j, const v16i &c, const v16f &ss, int e0, int ne) __attribute__((always_inline)) {
         float *a_ = acc[i * 2 + j];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) a_[e] = fmaf((float)c[e], ss[e], a_[e]);
-        if (DBG) {
-            const int g = u < G4 ? u : G4 + ((u - G4) >> 1);
+        for (int e = e0; e < e0 + ne; ++e) a_[e] = fmaf((float)c[e], ss[e], a_[e]);
+        if (DBG && u >= 0) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
+            for (int e = e0; e < e0 + ne; ++e) {
                 const int64_t m = m0 + wm * 64 + 32 * i + 8 * (e >> 2) + 4 * h + (e & 3);
                 const int64_t n = n0 + wn * 64 + 32 * j + r;
-                if (m < p.M && n < p.N) {
-                    int32_t *dst = p.partials + (m * p.N + n) * G + g;
-                    if (u < G4)                   *dst = c[e] >> 8;
-                    else if (((u - G4) & 1) == 0) *dst = c[e];
-                    else                          *dst += c[e];     // second half of an INT8 group
-                }
+                if (m < p.M && n < p.N) p.partials[(m * p.N + n) * G + u] = u < G4 ? c[e] >> 8 : c[e];
             }
         }
     };
 
-    // One K-step.  NKK: MFMAs per sub-tile (4 for a widened INT4 group, 2 for an INT8
-    // half-step).  NEXT: kind of step u+1, whose operands go registers -> LDS here
-    // (0 = none, 1 = INT4, 2 = INT8).  PF: kind of step u+2, whose global loads are
-    // issued here.  S: LDS stage of this step.  Everything is a compile-time choice so
-    // the step is ONE basic block: branches would let the compiler sink the dequantise
-    // work below them, away from the MFMAs it is meant to overlap with.
-    auto step = [&](int u, auto nkk_c, auto next_c, auto pf_c, auto stage_c) {
-        constexpr int NKK = decltype(nkk_c)::value, NEXT = decltype(next_c)::value;
-        constexpr int PF = decltype(pf_c)::value;
-        constexpr int S = decltype(stage_c)::value;
-        const unsigned char *base = smem + S * STAGE;
-        v4i a[2][NKK], b[2][NKK];
-        auto load_frag = [&](v4i (&f)[NKK], const int (&addr)[4], int blk) {
+    // ---- K-step pipeline -------------------------------------------------------------
+    // Carried from step to step: the first operand fragments and the scale bits of the
+    // coming step (fetched from LDS in the last block of the step before, behind its
+    // barrier, so no LDS latency is exposed at the start of a step), and the integer tile
+    // and scale tile of the last sub-tile of the step before, whose dequantisation
+    // overlaps the first MFMAs of this step.
+    v4i fa0[4], fb0[4];
+    uint32_t sa[2], sb[2];
+    v16i c_pend = zi;
+    v16f s_pend = zf;
+    int  u_pend = -1;                                   // K-step of the pending tile (debug dump)
+
+    auto load_first = [&](const unsigned char *base) __attribute__((always_inline)) {
 #pragma unroll
-            for (int kk = 0; kk < NKK; ++kk)
-                f[kk] = *reinterpret_cast<const v4i *>(base + addr[kk] + blk * 32 * 128);
-        };
-        load_frag(a[0], a_addr, 0);
-        load_frag(b[0], b_addr, 0);
-        uint32_t sa[2], sb[2];
+        for (int kk = 0; kk < 4; ++kk) {
+            fa0[kk] = *reinterpret_cast<const v4i *>(base + a_addr[kk]);
+            fb0[kk] = *reinterpret_cast<const v4i *>(base + b_addr[kk]);
+        }
+    };
+    auto load_scales = [&](const unsigned char *base) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             sa[i] = *reinterpret_cast<const uint32_t *>(base + sa_addr + i * 32 * 4);
             const uint32_t wb = *reinterpret_cast<const uint32_t *>(base + sb_addr + i * 32 * 4);
             sb[i] = h == 0 ? wb : 0u;      // zero on one side keeps k-slots 4..7 empty
         }
-        auto mma = [&](int i, int j) {
+    };
+
+    // One K-step.  NEXT: kind of step u+1 (0 = none, 1 = INT4, 2 = INT8), whose operands go
+    // into the other LDS stage here.  PF: whether step u+2 is an INT4 step, whose global
+    // loads are issued here.  HOT: the steady-state variant (step u+2 exists).
+    //
+    // A step is four blocks, one per 32x32 sub-tile in the order (0,0) (0,1) (1,1) (1,0); a
+    // block is five slots of one MFMA each: the sub-tile's four integer MFMAs, then the
+    // fp16 MFMA of its scale tile.  Beside its MFMA a slot holds
+    //   first slot of blocks 0-2 : loader item (chunk t of step u+1 registers -> LDS, then
+    //                              the global load of chunk t of step u+2 into the same
+    //                              registers: a whole step of slack for HBM latency)
+    //   slots 1-4 of every block : a quarter of the dequantisation of the sub-tile of the
+    //                              block before (of the last sub-tile of the step before,
+    //                              in block 0), whose integer and scale tiles are complete
+    //   blocks 0, 1              : LDS reads of this step's second fragments b1, a1
+    //   block 3                  : LDS reads of the next step's first fragments and scales
+    // LDS hazards, with the single barrier before block 3: step u+1's operands are written
+    // in blocks 0-2 of step u and read after the barrier; the stage they overwrite held
+    // step u-1's, whose last reads (block 1 of step u-1) were complete at that step's
+    // barrier.
+    auto step = [&](int u, auto next_c, auto pf_c, auto hot_c) __attribute__((always_inline)) {
+        constexpr int  NEXT = decltype(next_c)::value;
+        constexpr bool PF = decltype(pf_c)::value, HOT = decltype(hot_c)::value;
+        const unsigned char *base = smem + (u & 1) * STAGE;
+        unsigned char *nbase = smem + ((u + 1) & 1) * STAGE;
+        const bool pf_scale = HOT ? true : u + 2 < U;
+        v4i a1[4], b1[4];
+        uint32_t nsa[2] = {0u, 0u}, nsb[2] = {0u, 0u};  // this step's scale bits stay live to its last slot
+        v16i c_prev = c_pend;
+        v16f s_prev = s_pend;
+        int  u_prev = u_pend;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int ti = t >> 1, tj = (t == 1 || t == 2) ? 1 : 0;       // this block's sub-tile
+            const int pi = ((t + 3) & 3) >> 1, pj = (((t + 3) & 3) == 1 || ((t + 3) & 3) == 2) ? 1 : 0;
+            const v4i *A = ti ? a1 : fa0;
+            const v4i *B = tj ? b1 : fb0;
             v16i c = zi;
+            v16f s = zf;
 #pragma unroll
-            for (int kk = 0; kk < NKK; ++kk)
-                c = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][kk], b[j][kk], c, 0, 0, 0);
-            return c;
-        };
-
-        // block 1: MFMAs of sub-tile (0,0); vector side: the next step's operands go
-        // registers -> LDS.  b[1] is fetched at the end.
-        v16i c00 = mma(0, 0);
-        if (NEXT) {
-            stage_to_lds(std::integral_constant<bool, NEXT == 2>{}, std::integral_constant<int, 1 - S>{});
-        }
-        load_frag(b[1], b_addr, 1);
+            for (int kk = 0; kk < 5; ++kk) {
+                if (kk < 4) c = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kk], B[kk], c, 0, 0, 0);
+                else        s = scale_tile(sa[ti], sb[tj]);
+                // loader items
+                if (NEXT == 1) {
+                    const int item = kk == 0 && t < 3 ? t : (CH == 4 && t == 2 && kk == 2 ? 3 : -1);
+                    if (item >= 0 && item < CH) {
+                        stage_chunk(item, nbase);
+                        if (PF) fetch_chunk(item, u + 2);
+                        if (item == CH - 1) {
+                            stage_scale(nbase);
+                            if (pf_scale) fetch_scale(u + 2);
+                        }
+                    }
+                }
+                if (NEXT == 2 && t == 0 && kk == 0) {
+                    stage_int8(u + 1, nbase);
+                    stage_scale(nbase);
+                    if (pf_scale) fetch_scale(u + 2);
+                }
+                // second fragments of this step
+                if (t == 0 && kk < 4) b1[kk] = *reinterpret_cast<const v4i *>(base + b_addr[kk] + 32 * 128);
+                if (t == 1 && kk < 4) a1[kk] = *reinterpret_cast<const v4i *>(base + a_addr[kk] + 32 * 128);
+                // a quarter of the dequantisation of the block before
+                if (kk >= 1) epilogue(t == 0 ? u_prev : u, pi, pj, c_prev, s_prev, 4 * (kk - 1), 4);
+                // first fragments and scale bits of the next step (behind the barrier)
+                if (NEXT && t == 3 && kk >= 1) {
+                    if (kk <= 2) {
+                        fa0[2 * kk - 2] = *reinterpret_cast<const v4i *>(nbase + a_addr[2 * kk - 2]);
+                        fa0[2 * kk - 1] = *reinterpret_cast<const v4i *>(nbase + a_addr[2 * kk - 1]);
+                        if (kk == 2) {
 #pragma unroll
-        for (int k = 0; k < NKK; ++k) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 10, 0);
-            __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // block 2: scale tile of (0,0) and MFMAs of (0,1); vector side: dequantise (0,0):
-        // the converts come first, so the scale tile is ready when the multiply-adds start.
-        v16f s00 = scale_tile(sa[0], sb[0]);
-        v16i c01 = mma(0, 1);
-        epilogue(u, 0, 0, c00, s00);
-        load_frag(a[1], a_addr, 1);            // a[0] is dead after the MFMAs above
-#pragma unroll
-        for (int k = 0; k < NKK + 1; ++k) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        v16f s01 = scale_tile(sa[0], sb[1]);
-        v16i c11 = mma(1, 1);
-        epilogue(u, 0, 1, c01, s01);
-#pragma unroll
-        for (int k = 0; k < NKK + 1; ++k) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        v16f s11 = scale_tile(sa[1], sb[1]);
-        v16i c10 = mma(1, 0);
-        epilogue(u, 1, 1, c11, s11);
-#pragma unroll
-        for (int k = 0; k < NKK + 1; ++k) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // tail: global loads for step u+2 go out while the last sub-tile is dequantised
-        v16f s10 = scale_tile(sa[1], sb[0]);
-        if (PF == 1) prefetch(u + 2, std::false_type{});
-        if (PF == 2) prefetch(u + 2, std::true_type{});
-        epilogue(u, 1, 0, c10, s10);
-        __syncthreads();
-    };
-
-    // prologue: step 0 into stage 0, step 1 into registers (there is always an INT4
-    // group and an INT8 group: G4 >= 1, G8 >= 1, so U >= 3)
-    prefetch(0, std::false_type{});
-    stage_to_lds(std::false_type{}, std::integral_constant<int, 0>{});
-    if (G4 > 1) prefetch(1, std::false_type{});
-    else        prefetch(1, std::true_type{});
-    __syncthreads();
-
-    using C0 = std::integral_constant<int, 0>;
-    using C1 = std::integral_constant<int, 1>;
-    using C2 = std::integral_constant<int, 2>;
-    using C4 = std::integral_constant<int, 4>;
-
-    // any step, by run-time dispatch to its compile-time variant (used off the hot loop)
-    auto any_step = [&](int u) {
-        const int next = u + 1 >= U ? 0 : (u + 1 < G4 ? 1 : 2);
-        const int pf   = u + 2 >= U ? 0 : (u + 2 < G4 ? 1 : 2);
-        const int s1   = u & 1;
-        if (u < G4) {
-            // next is 1 or 2 and pf is 1 or 2 here (G8 >= 1 gives at least two INT8 half-steps)
-            if (next == 1) {
-                if (pf == 1) { if (s1) step(u, C4{}, C1{}, C1{}, C1{}); else step(u, C4{}, C1{}, C1{}, C0{}); }
-                else         { if (s1) step(u, C4{}, C1{}, C2{}, C1{}); else step(u, C4{}, C1{}, C2{}, C0{}); }
-            } else {
-                if (s1) step(u, C4{}, C2{}, C2{}, C1{}); else step(u, C4{}, C2{}, C2{}, C0{});
+                            for (int i = 0; i < 2; ++i) {
+                                nsa[i] = *reinterpret_cast<const uint32_t *>(nbase + sa_addr + i * 32 * 4);
+                                nsb[i] = *reinterpret_cast<const uint32_t *>(nbase + sb_addr + i * 32 * 4);
+                            }
+                        }
+                    } else {
+                        // fb0 of this step was last used by the MFMA of slot 2 * kk - 5
+                        fb0[2 * kk - 6] = *reinterpret_cast<const v4i *>(nbase + b_addr[2 * kk - 6]);
+                        fb0[2 * kk - 5] = *reinterpret_cast<const v4i *>(nbase + b_addr[2 * kk - 5]);
+                        if (kk == 4) {                  // zero on one side keeps k-slots 4..7 empty
+                            nsb[0] = h == 0 ? nsb[0] : 0u;
+                            nsb[1] = h == 0 ? nsb[1] : 0u;
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-        } else {
-            if (next == 0)    { if (s1) step(u, C2{}, C0{}, C0{}, C1{}); else step(u, C2{}, C0{}, C0{}, C0{}); }
-            else if (pf == 0) { if (s1) step(u, C2{}, C2{}, C0{}, C1{}); else step(u, C2{}, C2{}, C0{}, C0{}); }
-            else              { if (s1) step(u, C2{}, C2{}, C2{}, C1{}); else step(u, C2{}, C2{}, C2{}, C0{}); }
+            if (t == 2) {
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            c_prev = c; s_prev = s; u_prev = u;
         }
+        c_pend = c_prev; s_pend = s_prev; u_pend = u;
+        sa[0] = nsa[0]; sa[1] = nsa[1]; sb[0] = nsb[0]; sb[1] = nsb[1];
     };
+    // dequantise the pending sub-tile now (before the accumulators are rescaled or stored)
+    auto flush_pending = [&]() __attribute__((always_inline)) {
+        epilogue(u_pend, 1, 0, c_pend, s_pend, 0, 16);
+        c_pend = zi; s_pend = zf; u_pend = -1;
+    };
+
+    // prologue: step 0 into stage 0, step 1 into registers if it is an INT4 step (there is
+    // always an INT4 group and an INT8 group: G4 >= 1, G - G4 >= 1)
+#pragma unroll
+    for (int i = 0; i < CH; ++i) fetch_chunk(i, 0);
+    fetch_scale(0);
+#pragma unroll
+    for (int i = 0; i < CH; ++i) stage_chunk(i, smem);
+    stage_scale(smem);
+    if (G4 > 1) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) fetch_chunk(i, 1);
+    }
+    fetch_scale(1);
+    __syncthreads();
+    load_first(smem);
+    load_scales(smem);
+
+    using T = std::true_type;
+    using F = std::false_type;
+    using N0 = std::integral_constant<int, 0>;
+    using N1 = std::integral_constant<int, 1>;
+    using N2 = std::integral_constant<int, 2>;
 
     int u = 0;
-    for (; u + 3 < G4; u += 2) {                        // hot loop: steps u+1, u+2, u+3 are INT4
-        step(u, C4{}, C1{}, C1{}, C0{});
-        step(u + 1, C4{}, C1{}, C1{}, C1{});
+    for (; u + 2 < G4; ++u) step(u, N1{}, T{}, T{});    // hot loop: steps u+1 and u+2 are INT4
+    for (; u < U; ++u) {
+        if (u == G4) {
+            // leave the 2^8 of the nibble widening behind before the first INT8 step
+            flush_pending();
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[t][e] *= (1.0f / 256.0f);
+        }
+        if (u + 1 >= U)      step(u, N0{}, F{}, F{});
+        else if (u + 1 < G4) step(u, N1{}, F{}, F{});   // step u+2 is an INT8 step
+        else                 step(u, N2{}, F{}, F{});
     }
-    for (; u < G4; ++u) any_step(u);                    // the last one to three INT4 steps
-    // leave the 2^8 of the nibble widening behind before the INT8 steps
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[t][e] *= (1.0f / 256.0f);
-    for (; u < U; ++u) any_step(u);
+    flush_pending();
+    __syncthreads();                                    // every fragment read is done: LDS is free
 
     // ---- store: the 64x64 fp16 tile of a wavefront goes through LDS so that global
     // memory sees whole 128-byte rows (a lane holds one column: storing from the MFMA
-    // layout directly would write 2 bytes per lane).  The last step ended with a barrier,
-    // so the stages are free; each wavefront uses a private region, row stride 144 bytes.
+    // layout directly would write 2 bytes per lane).  After the barrier above
+    // the stages are free; each wavefront uses a private region, row stride 144 bytes.
     constexpr int OSTRIDE = 144;
     static_assert((NT / 64) * 64 * OSTRIDE <= 2 * STAGE, "output staging fits the operand stages");
     unsigned char *ot = smem + wave * (64 * OSTRIDE);
