@@ -12,12 +12,14 @@
 //       texture path, so operands are shared through LDS.
 //
 // Workgroup tile 256 x 128 (eight wavefronts) or 128 x 128 (four), wavefront tile
-// 64 x 64 (four 32x32 sub-tiles), two LDS stages, one barrier per K-step.  A K-step is
-// one 128-channel group: 128 bytes per operand row in LDS (an INT4 group travels HBM ->
-// registers -> LDS and is widened to INT8 on the way; an INT8 group is copied).  A step
-// is twenty "slots" of one MFMA each, fenced so that the compiler keeps their order; the
-// vector and memory work of a slot never consumes what the same slot produced (see
-// `step`).
+// 64 x 64 (four 32x32 sub-tiles), two LDS stages, one barrier per K-step.  A K-step
+// moves 64 bytes per operand row HBM -> registers -> LDS, where they take 128 bytes: an
+// INT4 group is widened to INT8 on the way; an INT8 group is two half-steps whose bytes
+// are interleaved with zeros, so that every step has the same shape and ONE branch-free
+// step body serves the whole K loop (a second, slower body for the few odd steps cost
+// a fifth of the run time when it existed).  A step is twenty "slots" of one MFMA each,
+// fenced so that the compiler keeps their order; the vector and memory work of a slot
+// never consumes what the same slot produced (see `step`).
 //
 // The 32x32 tile of scale products a_scale[m,g] * w_scale[n,g] is one fp16 MFMA
 // (rank-1, single non-zero k; the product of two fp16 values is exact in its
@@ -51,7 +53,6 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     constexpr int RPT = NT / 4;                         // tile rows covered by one loader pass
     constexpr int CH = (BM + BN) / RPT;                 // 16-byte chunks per thread per K-step
     constexpr int CHA = BM / RPT;                       // of which activation rows
-    constexpr int CH8 = (BM + BN) * 8 / NT;             // 16-byte chunks per thread of an INT8 group
     constexpr int STAGE = (BM + BN) * 128 + NT * 4;     // codes + one scale slot per thread
     static_assert(BM % RPT == 0 && BN % RPT == 0 && RPT % 8 == 0, "loader layout");
     static_assert(BM + BN <= NT, "one scale per thread");
@@ -65,7 +66,7 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     const int r = lane & 31, h = lane >> 5;
 
     const int K4 = p.K - p.O, G = p.K >> 7, G4 = K4 >> 7;
-    const int U  = G;                                   // one K-step per group
+    const int U  = G4 + 2 * (G - G4);                   // K-steps: one per INT4 group, two per INT8 group
 
     const int MB      = (int)((p.M + BM - 1) / BM);
     const int logical = xcd_contiguous_block_id();
@@ -77,13 +78,14 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     // valid row (such tile rows are computed and never stored).  32-bit offsets: arrays
     // < 4 GiB.
     const int wrow = tid >> 2, wc = tid & 3;
-    uint32_t o4[CH];
+    uint32_t o4[CH], o8[CH];                           // row offsets into the INT4 / INT8 arrays
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
         int64_t row = i < CHA ? m0 + wrow + i * RPT : n0 + wrow + (i - CHA) * RPT;
         const int64_t last = i < CHA ? p.M - 1 : p.N - 1;
         row = row < last ? row : last;
         o4[i] = (uint32_t)(row * (K4 >> 1)) + wc * 16;
+        o8[i] = (uint32_t)(row * p.O) + wc * 16;
     }
     // the one scale this thread stages per group: element offset, or none
     const uint16_t *sbase = tid < BM ? p.a_scale : p.w_scale;
@@ -102,22 +104,33 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     uint4    pre[CH];
     uint32_t sc = 0;
 
-    // Loader items.  Chunk i of an INT4 group travels global -> registers (fetch_chunk) a
-    // whole K-step before it travels registers -> LDS (stage_chunk); every group's scale
-    // likewise.
-    auto fetch_chunk = [&](int i, int u) __attribute__((always_inline)) {
-        pre[i] = *reinterpret_cast<const uint4 *>((i < CHA ? p.a_q4 : p.w_q4) + (size_t)(o4[i] + (uint32_t)u * 64));
+    // Loader items.  Chunk i of step v travels global -> registers (fetch_chunk) a whole
+    // K-step before it travels registers -> LDS (stage_chunk); the step's scale likewise.
+    // The kind of step v (INT4 group, or half of an INT8 group) only changes scalar
+    // operands: base pointer, column, shift and masks.
+    auto group_of = [&](int v) { return v < G4 ? v : G4 + ((v - G4) >> 1); };
+    // `int4_c`: the caller knows at compile time that step v is an INT4 group
+    auto fetch_chunk = [&](int i, int v, auto int4_c) __attribute__((always_inline)) {
+        const bool is8 = decltype(int4_c)::value ? false : v >= G4;
+        const uint8_t *base = i < CHA ? (is8 ? reinterpret_cast<const uint8_t *>(p.a_q8) : p.a_q4)
+                                      : (is8 ? reinterpret_cast<const uint8_t *>(p.w_q8) : p.w_q4);
+        const uint32_t col = (uint32_t)(is8 ? v - G4 : v) * 64;
+        pre[i] = *reinterpret_cast<const uint4 *>(base + (size_t)((is8 ? o8[i] : o4[i]) + col));
     };
-    auto fetch_scale = [&](int u) __attribute__((always_inline)) {
-        sc = sbase[(size_t)(soff + (uint32_t)u)];
+    auto fetch_scale = [&](int v, auto int4_c) __attribute__((always_inline)) {
+        sc = sbase[(size_t)(soff + (uint32_t)(decltype(int4_c)::value ? v : group_of(v)))];
     };
-    auto stage_chunk = [&](int i, unsigned char *base) __attribute__((always_inline)) {
+    // INT4: even-position codes (x16) to chunk 2*wc, odd-position codes (x16) to chunk
+    // 2*wc+1.  INT8 half-step: the 16 codes as they are to chunk 2*wc, zeros to 2*wc+1.
+    auto stage_chunk = [&](int i, int v, unsigned char *base, auto int4_c) __attribute__((always_inline)) {
+        const bool is8 = decltype(int4_c)::value ? false : v >= G4;
+        const uint32_t sh = is8 ? 0u : 4u, mlo = is8 ? 0xFFFFFFFFu : 0xF0F0F0F0u, mhi = is8 ? 0u : 0xF0F0F0F0u;
         const uint4 w = pre[i];
         uint4 lo, hi;
-        lo.x = (w.x << 4) & 0xF0F0F0F0u; hi.x = w.x & 0xF0F0F0F0u;
-        lo.y = (w.y << 4) & 0xF0F0F0F0u; hi.y = w.y & 0xF0F0F0F0u;
-        lo.z = (w.z << 4) & 0xF0F0F0F0u; hi.z = w.z & 0xF0F0F0F0u;
-        lo.w = (w.w << 4) & 0xF0F0F0F0u; hi.w = w.w & 0xF0F0F0F0u;
+        lo.x = (w.x << sh) & mlo; hi.x = w.x & mhi;
+        lo.y = (w.y << sh) & mlo; hi.y = w.y & mhi;
+        lo.z = (w.z << sh) & mlo; hi.z = w.z & mhi;
+        lo.w = (w.w << sh) & mlo; hi.w = w.w & mhi;
         *reinterpret_cast<uint4 *>(base + w4lo + i * RPT * 128) = lo;
         *reinterpret_cast<uint4 *>(base + w4hi + i * RPT * 128) = hi;
     };
@@ -125,25 +138,6 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     // write a slot nobody reads: no branch in the hot loop
     auto stage_scale = [&](unsigned char *base) __attribute__((always_inline)) {
         reinterpret_cast<uint32_t *>(base + (BM + BN) * 128)[tid] = has_scale ? sc : 0u;
-    };
-    // An INT8 group (few: one per 128 outlier channels) is copied global -> LDS inside the
-    // step before it, without a step of slack: 128 bytes per tile row, CH8 chunks per thread.
-    auto stage_int8 = [&](int u, unsigned char *base) __attribute__((always_inline)) {
-        uint4 t8[CH8];
-#pragma unroll
-        for (int i = 0; i < CH8; ++i) {
-            const int id = tid + NT * i, row = id >> 3, ch = id & 7;
-            int64_t grow = row < BM ? m0 + row : n0 + (row - BM);
-            const int64_t last = row < BM ? p.M - 1 : p.N - 1;
-            grow = grow < last ? grow : last;
-            const int8_t *src = (row < BM ? p.a_q8 : p.w_q8) + grow * p.O + (size_t)(u - G4) * 128 + ch * 16;
-            t8[i] = *reinterpret_cast<const uint4 *>(src);
-        }
-#pragma unroll
-        for (int i = 0; i < CH8; ++i) {
-            const int id = tid + NT * i;
-            *reinterpret_cast<uint4 *>(base + lds_off(id >> 3, id & 7)) = t8[i];
-        }
     };
 
     // ---- fragment addresses within a stage: loop invariant ------------------------------
@@ -180,7 +174,12 @@ void w4a4_gemm_big_kernel(const GemmParams p)
             for (int e = e0; e < e0 + ne; ++e) {
                 const int64_t m = m0 + wm * 64 + 32 * i + 8 * (e >> 2) + 4 * h + (e & 3);
                 const int64_t n = n0 + wn * 64 + 32 * j + r;
-                if (m < p.M && n < p.N) p.partials[(m * p.N + n) * G + u] = u < G4 ? c[e] >> 8 : c[e];
+                if (m < p.M && n < p.N) {
+                    int32_t *dst = p.partials + (m * p.N + n) * G + group_of(u);
+                    if (u < G4)                   *dst = c[e] >> 8;
+                    else if (((u - G4) & 1) == 0) *dst = c[e];
+                    else                          *dst += c[e];     // second half of an INT8 group
+                }
             }
         }
     };
@@ -213,9 +212,10 @@ void w4a4_gemm_big_kernel(const GemmParams p)
         }
     };
 
-    // One K-step.  NEXT: kind of step u+1 (0 = none, 1 = INT4, 2 = INT8), whose operands go
-    // into the other LDS stage here.  PF: whether step u+2 is an INT4 step, whose global
-    // loads are issued here.  HOT: the steady-state variant (step u+2 exists).
+    // One K-step; the same code for every step.  The operands of step u+1 go into the
+    // other LDS stage here and the global loads of step u+2 are issued here; past the end
+    // of K the last step's data is fetched and staged again (in bounds, never read).
+    // INT4: steps u+1 and u+2 are known to be INT4 groups (saves the scalar selects).
     //
     // A step is four blocks, one per 32x32 sub-tile in the order (0,0) (0,1) (1,1) (1,0); a
     // block is five slots of one MFMA each: the sub-tile's four integer MFMAs, then the
@@ -232,12 +232,12 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     // in blocks 0-2 of step u and read after the barrier; the stage they overwrite held
     // step u-1's, whose last reads (block 1 of step u-1) were complete at that step's
     // barrier.
-    auto step = [&](int u, auto next_c, auto pf_c, auto hot_c) __attribute__((always_inline)) {
-        constexpr int  NEXT = decltype(next_c)::value;
-        constexpr bool PF = decltype(pf_c)::value, HOT = decltype(hot_c)::value;
+    auto step = [&](int u, auto int4_c) __attribute__((always_inline)) {
+        constexpr bool INT4 = decltype(int4_c)::value;
         const unsigned char *base = smem + (u & 1) * STAGE;
         unsigned char *nbase = smem + ((u + 1) & 1) * STAGE;
-        const bool pf_scale = HOT ? true : u + 2 < U;
+        const int v1 = INT4 || u + 1 < U ? u + 1 : U - 1;
+        const int v2 = INT4 || u + 2 < U ? u + 2 : U - 1;
         v4i a1[4], b1[4];
         uint32_t nsa[2] = {0u, 0u}, nsb[2] = {0u, 0u};  // this step's scale bits stay live to its last slot
         v16i c_prev = c_pend;
@@ -255,22 +255,15 @@ void w4a4_gemm_big_kernel(const GemmParams p)
             for (int kk = 0; kk < 5; ++kk) {
                 if (kk < 4) c = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[kk], B[kk], c, 0, 0, 0);
                 else        s = scale_tile(sa[ti], sb[tj]);
-                // loader items
-                if (NEXT == 1) {
-                    const int item = kk == 0 && t < 3 ? t : (CH == 4 && t == 2 && kk == 2 ? 3 : -1);
-                    if (item >= 0 && item < CH) {
-                        stage_chunk(item, nbase);
-                        if (PF) fetch_chunk(item, u + 2);
-                        if (item == CH - 1) {
-                            stage_scale(nbase);
-                            if (pf_scale) fetch_scale(u + 2);
-                        }
+                // loader item
+                const int item = kk == 0 && t < 3 ? t : (CH == 4 && t == 2 && kk == 2 ? 3 : -1);
+                if (item >= 0 && item < CH) {
+                    stage_chunk(item, v1, nbase, int4_c);
+                    fetch_chunk(item, v2, int4_c);
+                    if (item == CH - 1) {
+                        stage_scale(nbase);
+                        fetch_scale(v2, int4_c);
                     }
-                }
-                if (NEXT == 2 && t == 0 && kk == 0) {
-                    stage_int8(u + 1, nbase);
-                    stage_scale(nbase);
-                    if (pf_scale) fetch_scale(u + 2);
                 }
                 // second fragments of this step
                 if (t == 0 && kk < 4) b1[kk] = *reinterpret_cast<const v4i *>(base + b_addr[kk] + 32 * 128);
@@ -278,7 +271,7 @@ void w4a4_gemm_big_kernel(const GemmParams p)
                 // a quarter of the dequantisation of the block before
                 if (kk >= 1) epilogue(t == 0 ? u_prev : u, pi, pj, c_prev, s_prev, 4 * (kk - 1), 4);
                 // first fragments and scale bits of the next step (behind the barrier)
-                if (NEXT && t == 3 && kk >= 1) {
+                if (t == 3 && kk >= 1) {
                     if (kk <= 2) {
                         fa0[2 * kk - 2] = *reinterpret_cast<const v4i *>(nbase + a_addr[2 * kk - 2]);
                         fa0[2 * kk - 1] = *reinterpret_cast<const v4i *>(nbase + a_addr[2 * kk - 1]);
@@ -316,44 +309,31 @@ void w4a4_gemm_big_kernel(const GemmParams p)
         c_pend = zi; s_pend = zf; u_pend = -1;
     };
 
-    // prologue: step 0 into stage 0, step 1 into registers if it is an INT4 step (there is
-    // always an INT4 group and an INT8 group: G4 >= 1, G - G4 >= 1)
+    // prologue: step 0 into stage 0, step 1 into registers (there is always an INT4 group
+    // and an INT8 group, so U >= 3)
 #pragma unroll
-    for (int i = 0; i < CH; ++i) fetch_chunk(i, 0);
-    fetch_scale(0);
+    for (int i = 0; i < CH; ++i) fetch_chunk(i, 0, std::true_type{});
+    fetch_scale(0, std::true_type{});
 #pragma unroll
-    for (int i = 0; i < CH; ++i) stage_chunk(i, smem);
+    for (int i = 0; i < CH; ++i) stage_chunk(i, 0, smem, std::true_type{});
     stage_scale(smem);
-    if (G4 > 1) {
 #pragma unroll
-        for (int i = 0; i < CH; ++i) fetch_chunk(i, 1);
-    }
-    fetch_scale(1);
+    for (int i = 0; i < CH; ++i) fetch_chunk(i, 1, std::false_type{});
+    fetch_scale(1, std::false_type{});
     __syncthreads();
     load_first(smem);
     load_scales(smem);
 
-    using T = std::true_type;
-    using F = std::false_type;
-    using N0 = std::integral_constant<int, 0>;
-    using N1 = std::integral_constant<int, 1>;
-    using N2 = std::integral_constant<int, 2>;
-
     int u = 0;
-    for (; u + 2 < G4; ++u) step(u, N1{}, T{}, T{});    // hot loop: steps u+1 and u+2 are INT4
-    for (; u < U; ++u) {
-        if (u == G4) {
-            // leave the 2^8 of the nibble widening behind before the first INT8 step
-            flush_pending();
+    for (; u + 2 < G4; ++u) step(u, std::true_type{});  // INT4 groups followed by two more
+    for (; u < G4; ++u) step(u, std::false_type{});     // the last two INT4 groups
+    // leave the 2^8 of the nibble widening behind before the INT8 steps
+    flush_pending();
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[t][e] *= (1.0f / 256.0f);
-        }
-        if (u + 1 >= U)      step(u, N0{}, F{}, F{});
-        else if (u + 1 < G4) step(u, N1{}, F{}, F{});   // step u+2 is an INT8 step
-        else                 step(u, N2{}, F{}, F{});
-    }
+        for (int e = 0; e < 16; ++e) acc[t][e] *= (1.0f / 256.0f);
+    for (; u < U; ++u) step(u, std::false_type{});      // the INT8 groups, two half-steps each
     flush_pending();
     __syncthreads();                                    // every fragment read is done: LDS is free
 
