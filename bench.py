@@ -202,7 +202,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, choices=sorted(WORKLOAD_NAMES))
     ap.add_argument("--no-extra", action="store_true", help="skip the context measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
-    ap.add_argument("--cpu-rows", type=int, default=256)
+    ap.add_argument("--cpu-rows", type=int, default=1024,
+                    help="rows of each linear the CPU oracle is timed on (1024 rows of config 4 take about 12 s)")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
