@@ -166,6 +166,195 @@ void quantize_rows_kernel(const __half *__restrict__ x, int64_t rows, int64_t ld
     }
 }
 
+
+// max over the 16 lanes of a DPP row by rotations (max is exact in any order); one
+// v_max_f32 with a DPP operand per step, no LDS crossbar traffic
+__device__ __forceinline__ float row16_max_dpp(float v)
+{
+#define ATOM_ROW_ROR(n)                                                                          \
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(                          \
+                     0, __builtin_bit_cast(int, v), 0x120 | (n), 0xF, 0xF, false)))
+    ATOM_ROW_ROR(8);
+    ATOM_ROW_ROR(4);
+    ATOM_ROW_ROR(2);
+    ATOM_ROW_ROR(1);
+#undef ATOM_ROW_ROR
+    return v;
+}
+
+// Same result as quantize_rows_kernel, bit for bit, for K <= 2048 * NS and clip >= 2^-20,
+// with the per-element work cut down:
+//   * a workgroup walks several rows; the gather offsets of the reorder (they are the same
+//     for every row) and gamma stay in registers, and the next row's global loads are in
+//     flight while this row is quantised;
+//   * the IEEE division by the group's scale shares the reciprocal refinement across the
+//     group: r = rcp(s), r += r*(1 - s*r), then per element q = y*r and two residual
+//     corrections q += r*(y - s*q).  This is instruction for instruction what the
+//     compiler emits for y / s when v_div_scale does not rescale, which it does not for
+//     the quotients that matter here: s comes from the group's own maximum, so
+//     |y| / s <= (2^n - 1)/(2 clip) * (1 + 2^-11) and s >= 2^-24; quotients below 2^-100
+//     round to code 0 either way.  A zero scale (all-zero group) yields zero codes;
+//   * the group maximum is a DPP rotation reduction.
+template <bool NORM, int NS>
+__global__ __launch_bounds__(kThreads)
+void quantize_rows_fast_kernel(const __half *__restrict__ x, int64_t rows, int64_t ld,
+                               const __half *__restrict__ gamma, float eps,
+                               const int32_t *__restrict__ idx, int K, int O, float clip,
+                               uint8_t *__restrict__ q4, int8_t *__restrict__ q8,
+                               __half *__restrict__ scale)
+{
+    extern __shared__ __align__(16) float lds[];
+    float *ybuf = lds;            // [K]   staged row, original channel order
+    float *qbuf = lds + K;        // [K/8] per-vector sums of squares (NORM only)
+
+    const int tid  = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int V    = K >> 3;
+    const int K4   = K - O;
+    const int G    = K >> 7;
+    const int G4   = K4 >> 7;
+
+    // gather offsets (bytes into ybuf) of this lane's 8 channels in each of its groups
+    uint32_t off[NS][8];
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+        const int g  = 4 * wave + (lane >> 4) + 16 * j;
+        const int gg = g < G ? g : G - 1;
+        const int j0 = gg * 128 + (lane & 15) * 8;
+        const int4 i0 = *reinterpret_cast<const int4 *>(idx + j0);
+        const int4 i1 = *reinterpret_cast<const int4 *>(idx + j0 + 4);
+        const int id[8] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) off[j][e] = 4u * min((unsigned)id[e], (unsigned)(K - 1));
+    }
+    uint4 graw[NORM ? NS : 1];
+    if (NORM) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const int v = tid + kThreads * i;
+            graw[i] = v < V ? *reinterpret_cast<const uint4 *>(gamma + 8 * v) : make_uint4(0, 0, 0, 0);
+        }
+    }
+
+    uint4 raw[NS];
+    auto fetch_row = [&](int64_t row) {
+        const __half *xr = x + row * ld;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const int v = tid + kThreads * i;
+            raw[i] = v < V ? *reinterpret_cast<const uint4 *>(xr + 8 * v) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    int64_t row = blockIdx.x;
+    if (row < rows) fetch_row(row);
+
+    for (; row < rows; row += gridDim.x) {
+        // ---- 1./2. stage the row (after RMSNorm, if any) in LDS, original channel order
+        float r = 1.0f;
+        if (NORM) {
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                const int v = tid + kThreads * i;
+                if (v < V) {
+                    float f[8];
+                    halves_to_floats(raw[i], f);
+                    float s0 = f[0] * f[0], s1 = f[1] * f[1], s2 = f[2] * f[2], s3 = f[3] * f[3];
+                    float s4 = f[4] * f[4], s5 = f[5] * f[5], s6 = f[6] * f[6], s7 = f[7] * f[7];
+                    qbuf[v] = ((s0 + s1) + (s2 + s3)) + ((s4 + s5) + (s6 + s7));
+                }
+            }
+            __syncthreads();
+            float L = 0.0f;
+            for (int v = lane; v < V; v += 64) L = L + qbuf[v];
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) L = L + __shfl_xor(L, d, 64);
+            const float mean = L / (float)K;
+            r = 1.0f / sqrtf(mean + eps);
+        }
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const int v = tid + kThreads * i;
+            if (v < V) {
+                float f[8];
+                halves_to_floats(raw[i], f);
+                if (NORM) {
+                    float g[8];
+                    halves_to_floats(graw[i], g);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) f[e] = (f[e] * r) * g[e];
+                }
+                *reinterpret_cast<float4 *>(ybuf + 8 * v)     = make_float4(f[0], f[1], f[2], f[3]);
+                *reinterpret_cast<float4 *>(ybuf + 8 * v + 4) = make_float4(f[4], f[5], f[6], f[7]);
+            }
+        }
+        // the next row's loads fly while this one is quantised
+        if (row + gridDim.x < rows) fetch_row(row + gridDim.x);
+        __syncthreads();
+
+        // ---- 3./4. reorder, group amax, scale, quantise, pack ----------------
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const int  g    = 4 * wave + (lane >> 4) + 16 * j;
+            const bool live = g < G;          // ragged last sweep: whole 16-lane rows idle
+            const int  gg   = live ? g : G - 1;
+            const int  j0   = gg * 128 + (lane & 15) * 8;
+            float y[8];
+            float amax = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                y[e] = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(ybuf) + off[j][e]);
+                amax = fmaxf(amax, fabsf(y[e]));
+            }
+            amax = row16_max_dpp(amax);
+
+            const bool  is4   = gg < G4;
+            const float denom = is4 ? 15.0f : 255.0f;
+            const float qmin  = is4 ? -8.0f : -128.0f;
+            const float qmax  = is4 ? 7.0f : 127.0f;
+            const float s32   = ((2.0f * amax) * clip) / denom;
+            const __half sh   = (s32 > 65504.0f) ? __ushort_as_half((unsigned short)0x7bffu)
+                                                 : __float2half_rn(s32);
+            const float s     = __half2float(sh);
+            const float r0    = __builtin_amdgcn_rcpf(s);
+            const float e0    = fmaf(-s, r0, 1.0f);
+            const float r1    = fmaf(e0, r0, r0);
+            int q[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float qf = y[e] * r1;
+                float t  = fmaf(-s, qf, y[e]);
+                qf = fmaf(t, r1, qf);
+                t  = fmaf(-s, qf, y[e]);
+                qf = fmaf(t, r1, qf);
+                qf = rintf(qf);
+                qf = fminf(fmaxf(qf, qmin), qmax);
+                q[e] = (int)qf;
+            }
+            const bool nz = s != 0.0f;
+            if (live) {
+                if (is4) {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) w |= (uint32_t)(q[e] & 0xF) << (4 * e);
+                    *reinterpret_cast<uint32_t *>(q4 + row * (int64_t)(K4 >> 1) + (j0 >> 1)) = nz ? w : 0u;
+                } else {
+                    uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        w0 |= (uint32_t)(q[e] & 0xFF) << (8 * e);
+                        w1 |= (uint32_t)(q[e + 4] & 0xFF) << (8 * e);
+                    }
+                    *reinterpret_cast<uint2 *>(q8 + row * (int64_t)O + (j0 - K4)) =
+                        make_uint2(nz ? w0 : 0u, nz ? w1 : 0u);
+                }
+                if ((lane & 15) == 0) scale[row * (int64_t)G + gg] = sh;
+            }
+        }
+        __syncthreads();   // ybuf is rewritten by the next row
+    }
+}
+
 }  // namespace
 
 namespace atom_internal {
@@ -175,12 +364,59 @@ size_t quantize_lds_bytes(int K, bool norm)
     return sizeof(float) * (size_t)(K + (norm ? K / 8 : 0));
 }
 
+template <bool NORM, int NS>
+hipError_t launch_fast(const void *x, int64_t rows, int64_t ld, const void *gamma, float eps,
+                       const int32_t *idx, int K, int O, float clip, void *q4, void *q8,
+                       void *scale, size_t lds, hipStream_t stream)
+{
+    auto kern = &quantize_rows_fast_kernel<NORM, NS>;
+    static size_t allowed = 0;        // the opt-in for more than 64 KB of dynamic LDS
+    if (lds > allowed) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return err;
+        allowed = lds;
+    }
+    // workgroups resident per CU (LDS-limited), then rows dealt evenly over one wave of them
+    int cus = 256;
+    {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+            prop.multiProcessorCount > 0)
+            cus = prop.multiProcessorCount;
+    }
+    int64_t per_cu = (int64_t)(160 * 1024) / (int64_t)(lds > 0 ? lds : 1);
+    per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
+    const int64_t slots = (int64_t)cus * per_cu;
+    const int64_t rows_per_wg = (rows + slots - 1) / slots;
+    const int64_t grid = (rows + rows_per_wg - 1) / rows_per_wg;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, stream, (const __half *)x,
+                       rows, ld, (const __half *)gamma, eps, idx, K, O, clip, (uint8_t *)q4,
+                       (int8_t *)q8, (__half *)scale);
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, const void *gamma,
                                 float eps, const int32_t *idx, int K, int O, float clip,
                                 void *q4, void *q8, void *scale, hipStream_t stream)
 {
     const bool   norm = gamma != nullptr;
     const size_t lds  = quantize_lds_bytes(K, norm);
+    // the fast kernel keeps K/2048 gather-offset sets in registers and relies on a sane clip
+    const int ns = (K + 2047) / 2048;
+    if (ns <= 8 && clip >= 9.5367431640625e-07f && clip <= 1.0f) {
+#define ATOM_FAST(NS_)                                                                              \
+    return norm ? launch_fast<true, NS_>(x, rows, ld, gamma, eps, idx, K, O, clip, q4, q8, scale,  \
+                                         lds, stream)                                              \
+                : launch_fast<false, NS_>(x, rows, ld, gamma, eps, idx, K, O, clip, q4, q8, scale, \
+                                          lds, stream)
+        if (ns <= 2) { ATOM_FAST(2); }
+        if (ns <= 4) { ATOM_FAST(4); }
+        if (ns <= 6) { ATOM_FAST(6); }
+        ATOM_FAST(8);
+#undef ATOM_FAST
+    }
     const int    grid = (int)(rows < (int64_t)1 << 20 ? rows : (int64_t)1 << 20);
     // the opt-in for more than 64 KB of dynamic LDS is raised only when a call needs more
     static size_t allowed[2] = {0, 0};
