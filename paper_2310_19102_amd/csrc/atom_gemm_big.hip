@@ -43,13 +43,18 @@ typedef float    v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v4h  __attribute__((ext_vector_type(4)));
 typedef unsigned v2u  __attribute__((ext_vector_type(2)));
 
-// BM x BN: workgroup tile; (BM/64) x (BN/64) wavefronts, at least two per SIMD resident
-template <int BM, int BN, bool DBG>
-__global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, 2)
+// BM x BN: workgroup tile; KS sets of (BM/64) x (BN/64) wavefronts, at least two
+// wavefronts per SIMD resident.  With KS = 2 the K-steps are split between two wavefront
+// sets that run side by side on their own LDS stages and add their fp32 tiles once at
+// the end (set 0 + set 1, a fixed order): for grids of at most one tile per CU, where a
+// single set would leave every SIMD with one wavefront and nothing to overlap its MFMAs
+// with.
+template <int BM, int BN, int KS, bool DBG>
+__global__ __launch_bounds__((BM / 64) * (BN / 64) * 64 * KS, 2)
 void w4a4_gemm_big_kernel(const GemmParams p)
 {
     constexpr int WM = BM / 64;                         // wavefronts down M
-    constexpr int NT = WM * (BN / 64) * 64;
+    constexpr int NT = WM * (BN / 64) * 64;             // threads of one set
     constexpr int RPT = NT / 4;                         // tile rows covered by one loader pass
     constexpr int CH = (BM + BN) / RPT;                 // 16-byte chunks per thread per K-step
     constexpr int CHA = BM / RPT;                       // of which activation rows
@@ -57,9 +62,13 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     static_assert(BM % RPT == 0 && BN % RPT == 0 && RPT % 8 == 0, "loader layout");
     static_assert(BM + BN <= NT, "one scale per thread");
 
-    extern __shared__ __align__(16) unsigned char smem[];
+    extern __shared__ __align__(16) unsigned char smem_all[];
 
-    const int tid  = threadIdx.x;
+    // K-slice of this set: the same for a whole wavefront, and the compiler is told so
+    const int ks   = KS == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x / NT);
+    const int tid  = KS == 1 ? (int)threadIdx.x : (int)threadIdx.x % NT;   // thread within the set
+    unsigned char *smem = smem_all;                     // the set's offset is folded into the per-thread LDS addresses
+    const int set_off = ks * (2 * STAGE);
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
@@ -67,6 +76,9 @@ void w4a4_gemm_big_kernel(const GemmParams p)
 
     const int K4 = p.K - p.O, G = p.K >> 7, G4 = K4 >> 7;
     const int U  = G4 + 2 * (G - G4);                   // K-steps: one per INT4 group, two per INT8 group
+    // this set's steps [ub, ue); with two sets the first takes the larger half
+    const int ub = ks == 0 ? 0 : (U + 1) / 2;
+    const int ue = KS == 1 ? U : (ks == 0 ? (U + 1) / 2 : U);
 
     const int MB      = (int)((p.M + BM - 1) / BM);
     const int logical = xcd_contiguous_block_id();
@@ -98,8 +110,9 @@ void w4a4_gemm_big_kernel(const GemmParams p)
         has_scale = n0 + (tid - BM) < p.N;
         soff = (uint32_t)((has_scale ? n0 + (tid - BM) : 0) * G);
     }
-    const int w4lo = lds_off(wrow, wc * 2);             // widened INT4: even-position codes
-    const int w4hi = lds_off(wrow, wc * 2 + 1);         //               odd-position codes
+    const int w4lo = set_off + lds_off(wrow, wc * 2);       // widened INT4: even-position codes
+    const int w4hi = set_off + lds_off(wrow, wc * 2 + 1);   //               odd-position codes
+    const int sc_slot = set_off + (BM + BN) * 128 + tid * 4;
 
     uint4    pre[CH];
     uint32_t sc = 0;
@@ -137,18 +150,18 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     // the scale goes in as raw fp16 bits (an MFMA operand); threads beyond the tile rows
     // write a slot nobody reads: no branch in the hot loop
     auto stage_scale = [&](unsigned char *base) __attribute__((always_inline)) {
-        reinterpret_cast<uint32_t *>(base + (BM + BN) * 128)[tid] = has_scale ? sc : 0u;
+        *reinterpret_cast<uint32_t *>(base + sc_slot) = has_scale ? sc : 0u;
     };
 
     // ---- fragment addresses within a stage: loop invariant ------------------------------
     int a_addr[4], b_addr[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-        a_addr[kk] = lds_off(wm * 64 + r, 2 * kk + h);
-        b_addr[kk] = lds_off(BM + wn * 64 + r, 2 * kk + h);
+        a_addr[kk] = set_off + lds_off(wm * 64 + r, 2 * kk + h);
+        b_addr[kk] = set_off + lds_off(BM + wn * 64 + r, 2 * kk + h);
     }
-    const int sa_addr = (BM + BN) * 128 + (wm * 64 + r) * 4;
-    const int sb_addr = (BM + BN) * 128 + (BM + wn * 64 + r) * 4;
+    const int sa_addr = set_off + (BM + BN) * 128 + (wm * 64 + r) * 4;
+    const int sb_addr = set_off + (BM + BN) * 128 + (BM + wn * 64 + r) * 4;
 
     float acc[4][16];
 #pragma unroll
@@ -214,7 +227,8 @@ void w4a4_gemm_big_kernel(const GemmParams p)
 
     // One K-step; the same code for every step.  The operands of step u+1 go into the
     // other LDS stage here and the global loads of step u+2 are issued here; past the end
-    // of K the last step's data is fetched and staged again (in bounds, never read).
+    // of this set's K range the last step's data is fetched and staged again (in bounds,
+    // never read).
     // INT4: steps u+1 and u+2 are known to be INT4 groups (saves the scalar selects).
     //
     // A step is four blocks, one per 32x32 sub-tile in the order (0,0) (0,1) (1,1) (1,0); a
@@ -236,8 +250,8 @@ void w4a4_gemm_big_kernel(const GemmParams p)
         constexpr bool INT4 = decltype(int4_c)::value;
         const unsigned char *base = smem + (u & 1) * STAGE;
         unsigned char *nbase = smem + ((u + 1) & 1) * STAGE;
-        const int v1 = INT4 || u + 1 < U ? u + 1 : U - 1;
-        const int v2 = INT4 || u + 2 < U ? u + 2 : U - 1;
+        const int v1 = INT4 || u + 1 < ue ? u + 1 : ue - 1;
+        const int v2 = INT4 || u + 2 < ue ? u + 2 : ue - 1;
         v4i a1[4], b1[4];
         uint32_t nsa[2] = {0u, 0u}, nsb[2] = {0u, 0u};  // this step's scale bits stay live to its last slot
         v16i c_prev = c_pend;
@@ -309,51 +323,77 @@ void w4a4_gemm_big_kernel(const GemmParams p)
         c_pend = zi; s_pend = zf; u_pend = -1;
     };
 
-    // prologue: step 0 into stage 0, step 1 into registers (there is always an INT4 group
-    // and an INT8 group, so U >= 3)
+    // prologue: the first step into stage 0, the second into registers (a set has at
+    // least two steps: there is always an INT4 group and an INT8 group, so U >= 3)
+    const int ub1 = ub + 1 < ue ? ub + 1 : ue - 1;
 #pragma unroll
-    for (int i = 0; i < CH; ++i) fetch_chunk(i, 0, std::true_type{});
-    fetch_scale(0, std::true_type{});
+    for (int i = 0; i < CH; ++i) fetch_chunk(i, ub, std::false_type{});
+    fetch_scale(ub, std::false_type{});
 #pragma unroll
-    for (int i = 0; i < CH; ++i) stage_chunk(i, 0, smem, std::true_type{});
-    stage_scale(smem);
+    for (int i = 0; i < CH; ++i) stage_chunk(i, ub, smem + (ub & 1) * STAGE, std::false_type{});
+    stage_scale(smem + (ub & 1) * STAGE);
 #pragma unroll
-    for (int i = 0; i < CH; ++i) fetch_chunk(i, 1, std::false_type{});
-    fetch_scale(1, std::false_type{});
+    for (int i = 0; i < CH; ++i) fetch_chunk(i, ub1, std::false_type{});
+    fetch_scale(ub1, std::false_type{});
     __syncthreads();
-    load_first(smem);
-    load_scales(smem);
+    load_first(smem + (ub & 1) * STAGE);
+    load_scales(smem + (ub & 1) * STAGE);
 
-    int u = 0;
-    for (; u + 2 < G4; ++u) step(u, std::true_type{});  // INT4 groups followed by two more
-    for (; u < G4; ++u) step(u, std::false_type{});     // the last two INT4 groups
+    const int e4 = ue < G4 ? ue : G4;                   // end of this set's INT4 steps
+    int u = ub;
+    for (; u + 2 < e4; ++u) step(u, std::true_type{});  // INT4 groups followed by two more
+    for (; u < e4; ++u) step(u, std::false_type{});     // the last two INT4 groups
     // leave the 2^8 of the nibble widening behind before the INT8 steps
     flush_pending();
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[t][e] *= (1.0f / 256.0f);
-    for (; u < U; ++u) step(u, std::false_type{});      // the INT8 groups, two half-steps each
+    for (; u < ue; ++u) step(u, std::false_type{});     // the INT8 groups, two half-steps each
     flush_pending();
+    // every set passes the same number of barriers: the second one may have a step less
+    if (KS == 2 && ks == 1 && (U & 1)) __syncthreads();
     __syncthreads();                                    // every fragment read is done: LDS is free
+
+    // ---- two sets: set 1 hands its fp32 tile over through LDS, set 0 adds it to its own
+    constexpr int XCH = KS == 2 ? (NT / 64) * 64 * 64 * 4 : 0;          // bytes of the exchange area
+    if (KS == 2) {
+        float *xch = reinterpret_cast<float *>(smem_all) + wave * (64 * 64);
+        if (ks == 1) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) xch[(t * 16 + e) * 64 + lane] = acc[t][e];
+        }
+        __syncthreads();
+        if (ks == 0) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[t][e] = acc[t][e] + xch[(t * 16 + e) * 64 + lane];
+        }
+    }
 
     // ---- store: the 64x64 fp16 tile of a wavefront goes through LDS so that global
     // memory sees whole 128-byte rows (a lane holds one column: storing from the MFMA
-    // layout directly would write 2 bytes per lane).  After the barrier above
-    // the stages are free; each wavefront uses a private region, row stride 144 bytes.
+    // layout directly would write 2 bytes per lane).  The stages are free; each wavefront
+    // uses a private region behind the exchange area, row stride 144 bytes.
     constexpr int OSTRIDE = 144;
-    static_assert((NT / 64) * 64 * OSTRIDE <= 2 * STAGE, "output staging fits the operand stages");
-    unsigned char *ot = smem + wave * (64 * OSTRIDE);
+    static_assert(XCH + (NT / 64) * 64 * OSTRIDE <= KS * 2 * STAGE, "output staging fits the operand stages");
+    unsigned char *ot = smem_all + XCH + wave * (64 * OSTRIDE);
+    if (ks == 0) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int row = 32 * (t >> 1) + 8 * (e >> 2) + 4 * h + (e & 3);
-            const int col = 32 * (t & 1) + r;
-            *reinterpret_cast<uint16_t *>(ot + row * OSTRIDE + col * 2) =
-                __half_as_ushort(__float2half_rn(acc[t][e]));
-        }
+            for (int e = 0; e < 16; ++e) {
+                const int row = 32 * (t >> 1) + 8 * (e >> 2) + 4 * h + (e & 3);
+                const int col = 32 * (t & 1) + r;
+                *reinterpret_cast<uint16_t *>(ot + row * OSTRIDE + col * 2) =
+                    __half_as_ushort(__float2half_rn(acc[t][e]));
+            }
+    }
     __syncthreads();
+    if (ks != 0) return;
     const int64_t mw = m0 + wm * 64, nw = n0 + wn * 64;
     const bool vec_ok = ((reinterpret_cast<uintptr_t>(p.y) | (uintptr_t)(p.ldy * 2)) & 15) == 0;
 #pragma unroll
@@ -374,13 +414,13 @@ void w4a4_gemm_big_kernel(const GemmParams p)
     }
 }
 
-template <int BM, int BN, bool DBG>
+template <int BM, int BN, int KS, bool DBG>
 hipError_t launch_cfg(const GemmParams &p, hipStream_t stream)
 {
     constexpr int NT = (BM / 64) * (BN / 64) * 64;
-    constexpr int LDS = 2 * ((BM + BN) * 128 + NT * 4);
+    constexpr int LDS = KS * 2 * ((BM + BN) * 128 + NT * 4);
     const int64_t MB = (p.M + BM - 1) / BM, NB = (p.N + BN - 1) / BN;
-    auto kern = &w4a4_gemm_big_kernel<BM, BN, DBG>;
+    auto kern = &w4a4_gemm_big_kernel<BM, BN, KS, DBG>;
     static bool configured = false;   // one attribute call per kernel variant and process
     if (!configured) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -388,7 +428,7 @@ hipError_t launch_cfg(const GemmParams &p, hipStream_t stream)
         if (err != hipSuccess) return err;
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(MB * NB)), dim3(NT), LDS, stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(MB * NB)), dim3(NT * KS), LDS, stream, p);
     return hipGetLastError();
 }
 
@@ -398,13 +438,16 @@ namespace atom_gemm {
 
 hipError_t launch_big(const GemmParams &p, hipStream_t stream)
 {
-    if (p.partials) return launch_cfg<128, 128, true>(p, stream);
+    if (p.partials) return launch_cfg<128, 128, 1, true>(p, stream);
     // The 256 x 128 tile does a third less loader work per MFMA; the 128 x 128 tile is
     // for shapes whose 256 x 128 tiles would leave compute units idle (one 512-thread
-    // workgroup per CU; two of the 256-thread ones).
+    // workgroup per CU; two of the 256-thread ones); with at most one 128 x 128 tile per
+    // CU (256 CUs) two wavefront sets split K inside the workgroup.
     const int64_t big_tiles = ((p.M + 255) / 256) * ((p.N + 127) / 128);
-    if (big_tiles < 512) return launch_cfg<128, 128, false>(p, stream);
-    return launch_cfg<256, 128, false>(p, stream);
+    const int64_t tiles128  = ((p.M + 127) / 128) * ((p.N + 127) / 128);
+    if (big_tiles >= 512) return launch_cfg<256, 128, 1, false>(p, stream);
+    if (tiles128 <= 256)  return launch_cfg<128, 128, 2, false>(p, stream);
+    return launch_cfg<128, 128, 1, false>(p, stream);
 }
 
 }  // namespace atom_gemm
