@@ -65,6 +65,10 @@ def test_config1_tiny():
     (40, 640, 33, 128, True),      # decode kernel, four row blocks; fewer groups than slices
     (64, 2304, 16, 128, True),     # decode kernel at its largest M, several load batches
     (65, 384, 72, 128, True),      # smallest M of the big-tile kernel
+    (70, 256, 130, 128, False),    # two wavefront sets, three K-steps: one set gets a single step
+    (200, 1152, 300, 256, True),   # two wavefront sets, two INT8 groups, odd/even split of the steps
+    (1200, 256, 3000, 128, False), # 128x128 tiles, one set, minimal K (one INT4 + one INT8 group)
+    (5, 12416, 24, 128, True),     # front end with eight register sets of gather offsets (K > 12288)
 ])
 def test_ragged_shapes(M, K, N, O, norm):
     _check_linear(_rand_linear(M, K, N, O, seed=M * 1000 + N, norm=norm), f"ragged M{M}")
@@ -83,6 +87,22 @@ def test_degenerate_values():
     lin2.x[1] = 65504.0           # sum of squares 2.2e12: fine in fp32
     lin2.x[2] = torch.tensor(6e-8, dtype=torch.float16)
     _check_linear(lin2, "degenerate-norm")
+
+
+def test_front_end_plain_and_fast_kernels_agree():
+    """The front end has a fast kernel (shared reciprocal refinement for the division) and a
+    plain one (compiler-generated IEEE division) that takes over for clip < 2^-20 and for
+    K > 16384; both must give the oracle's codes and scales, whose division is the C
+    compiler's.  Values chosen so that quotients land on and next to rounding ties."""
+    lin = _rand_linear(6, 1024, 32, 128, seed=11, norm=False)
+    # rows of exact multiples of half a quantisation step: every quotient is a tie or an integer
+    step = torch.tensor(0.75, dtype=torch.float16)
+    lin.x[0] = (torch.arange(1024) % 31 - 15).to(torch.float16) * step * 0.5
+    lin.x[1] = lin.x[0] * torch.tensor(1.0009765625, dtype=torch.float16)   # one fp16 ulp off
+    for clip in (0.9, 1.0, 2.0 ** -20, 5e-7, 1e-9):
+        lin.clip_act = clip
+        ga = gpu_quantize_act(lin)
+        assert_quant_equal(ga, ref_quantize_act(lin), f"clip {clip}")
 
 
 def test_strided_input_rows():
