@@ -182,7 +182,8 @@ __device__ __forceinline__ float row16_max_dpp(float v)
     return v;
 }
 
-// Same result as quantize_rows_kernel, bit for bit, for K <= 2048 * NS and clip >= 2^-20,
+// Same result as quantize_rows_kernel, bit for bit, for K <= 8 * NT * NS and clip >= 2^-20
+// (NT threads per row),
 // with the per-element work cut down:
 //   * a workgroup walks several rows; the gather offsets of the reorder (they are the same
 //     for every row) and gamma stay in registers, and the next row's global loads are in
@@ -195,8 +196,8 @@ __device__ __forceinline__ float row16_max_dpp(float v)
 //     |y| / s <= (2^n - 1)/(2 clip) * (1 + 2^-11) and s >= 2^-24; quotients below 2^-100
 //     round to code 0 either way.  A zero scale (all-zero group) yields zero codes;
 //   * the group maximum is a DPP rotation reduction.
-template <bool NORM, int NS>
-__global__ __launch_bounds__(kThreads)
+template <bool NORM, int NS, int NT>
+__global__ __launch_bounds__(NT)
 void quantize_rows_fast_kernel(const __half *__restrict__ x, int64_t rows, int64_t ld,
                                const __half *__restrict__ gamma, float eps,
                                const int32_t *__restrict__ idx, int K, int O, float clip,
@@ -219,7 +220,7 @@ void quantize_rows_fast_kernel(const __half *__restrict__ x, int64_t rows, int64
     uint32_t off[NS][8];
 #pragma unroll
     for (int j = 0; j < NS; ++j) {
-        const int g  = 4 * wave + (lane >> 4) + 16 * j;
+        const int g  = 4 * wave + (lane >> 4) + (NT / 16) * j;
         const int gg = g < G ? g : G - 1;
         const int j0 = gg * 128 + (lane & 15) * 8;
         const int4 i0 = *reinterpret_cast<const int4 *>(idx + j0);
@@ -232,7 +233,7 @@ void quantize_rows_fast_kernel(const __half *__restrict__ x, int64_t rows, int64
     if (NORM) {
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
-            const int v = tid + kThreads * i;
+            const int v = tid + NT * i;
             graw[i] = v < V ? *reinterpret_cast<const uint4 *>(gamma + 8 * v) : make_uint4(0, 0, 0, 0);
         }
     }
@@ -242,7 +243,7 @@ void quantize_rows_fast_kernel(const __half *__restrict__ x, int64_t rows, int64
         const __half *xr = x + row * ld;
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
-            const int v = tid + kThreads * i;
+            const int v = tid + NT * i;
             raw[i] = v < V ? *reinterpret_cast<const uint4 *>(xr + 8 * v) : make_uint4(0, 0, 0, 0);
         }
     };
@@ -255,7 +256,7 @@ void quantize_rows_fast_kernel(const __half *__restrict__ x, int64_t rows, int64
         if (NORM) {
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
-                const int v = tid + kThreads * i;
+                const int v = tid + NT * i;
                 if (v < V) {
                     float f[8];
                     halves_to_floats(raw[i], f);
@@ -274,7 +275,7 @@ void quantize_rows_fast_kernel(const __half *__restrict__ x, int64_t rows, int64
         }
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
-            const int v = tid + kThreads * i;
+            const int v = tid + NT * i;
             if (v < V) {
                 float f[8];
                 halves_to_floats(raw[i], f);
@@ -295,7 +296,7 @@ void quantize_rows_fast_kernel(const __half *__restrict__ x, int64_t rows, int64
         // ---- 3./4. reorder, group amax, scale, quantise, pack ----------------
 #pragma unroll
         for (int j = 0; j < NS; ++j) {
-            const int  g    = 4 * wave + (lane >> 4) + 16 * j;
+            const int  g    = 4 * wave + (lane >> 4) + (NT / 16) * j;
             const bool live = g < G;          // ragged last sweep: whole 16-lane rows idle
             const int  gg   = live ? g : G - 1;
             const int  j0   = gg * 128 + (lane & 15) * 8;
@@ -364,12 +365,12 @@ size_t quantize_lds_bytes(int K, bool norm)
     return sizeof(float) * (size_t)(K + (norm ? K / 8 : 0));
 }
 
-template <bool NORM, int NS>
+template <bool NORM, int NS, int NT>
 hipError_t launch_fast(const void *x, int64_t rows, int64_t ld, const void *gamma, float eps,
                        const int32_t *idx, int K, int O, float clip, void *q4, void *q8,
                        void *scale, size_t lds, hipStream_t stream)
 {
-    auto kern = &quantize_rows_fast_kernel<NORM, NS>;
+    auto kern = &quantize_rows_fast_kernel<NORM, NS, NT>;
     static size_t allowed = 0;        // the opt-in for more than 64 KB of dynamic LDS
     if (lds > allowed) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -377,21 +378,23 @@ hipError_t launch_fast(const void *x, int64_t rows, int64_t ld, const void *gamm
         if (err != hipSuccess) return err;
         allowed = lds;
     }
-    // workgroups resident per CU (LDS-limited), then rows dealt evenly over one wave of them
-    int cus = 256;
-    {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
-            prop.multiProcessorCount > 0)
-            cus = prop.multiProcessorCount;
+    // workgroups resident per CU (LDS- and wave-limited), then rows dealt evenly over one
+    // wave of them
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
     }
     int64_t per_cu = (int64_t)(160 * 1024) / (int64_t)(lds > 0 ? lds : 1);
-    per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
+    const int64_t by_waves = 2048 / NT;                 // 32 wavefronts per CU
+    per_cu = per_cu < 1 ? 1 : (per_cu > by_waves ? by_waves : per_cu);
     const int64_t slots = (int64_t)cus * per_cu;
     const int64_t rows_per_wg = (rows + slots - 1) / slots;
     const int64_t grid = (rows + rows_per_wg - 1) / rows_per_wg;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, stream, (const __half *)x,
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, stream, (const __half *)x,
                        rows, ld, (const __half *)gamma, eps, idx, K, O, clip, (uint8_t *)q4,
                        (int8_t *)q8, (__half *)scale);
     return hipGetLastError();
@@ -403,18 +406,20 @@ hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, const v
 {
     const bool   norm = gamma != nullptr;
     const size_t lds  = quantize_lds_bytes(K, norm);
-    // the fast kernel keeps K/2048 gather-offset sets in registers and relies on a sane clip
-    const int ns = (K + 2047) / 2048;
-    if (ns <= 8 && clip >= 9.5367431640625e-07f && clip <= 1.0f) {
-#define ATOM_FAST(NS_)                                                                              \
-    return norm ? launch_fast<true, NS_>(x, rows, ld, gamma, eps, idx, K, O, clip, q4, q8, scale,  \
-                                         lds, stream)                                              \
-                : launch_fast<false, NS_>(x, rows, ld, gamma, eps, idx, K, O, clip, q4, q8, scale, \
-                                          lds, stream)
-        if (ns <= 2) { ATOM_FAST(2); }
-        if (ns <= 4) { ATOM_FAST(4); }
-        if (ns <= 6) { ATOM_FAST(6); }
-        ATOM_FAST(8);
+    // The fast kernel keeps ceil(K / (8 * threads)) gather-offset sets in registers and
+    // relies on a sane clip; rows of 8192 channels and more are spread over 512 threads.
+    if (K <= 16384 && clip >= 9.5367431640625e-07f && clip <= 1.0f) {
+#define ATOM_FAST(NS_, NT_)                                                                         \
+    return norm ? launch_fast<true, NS_, NT_>(x, rows, ld, gamma, eps, idx, K, O, clip, q4, q8,    \
+                                              scale, lds, stream)                                  \
+                : launch_fast<false, NS_, NT_>(x, rows, ld, gamma, eps, idx, K, O, clip, q4, q8,   \
+                                               scale, lds, stream)
+        if (K <= 2048)  { ATOM_FAST(1, 256); }
+        if (K <= 4096)  { ATOM_FAST(2, 256); }
+        if (K < 8192)   { ATOM_FAST(4, 256); }
+        if (K <= 8192)  { ATOM_FAST(2, 512); }
+        if (K <= 12288) { ATOM_FAST(3, 512); }
+        ATOM_FAST(4, 512);
 #undef ATOM_FAST
     }
     const int    grid = (int)(rows < (int64_t)1 << 20 ? rows : (int64_t)1 << 20);
