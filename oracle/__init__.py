@@ -51,6 +51,9 @@ def _load():
     L.atom_ref_rmsnorm_row.argtypes = [vp, vp, f32, i32, vp]
     L.atom_ref_quantize_act.restype = ctypes.c_int
     L.atom_ref_quantize_act.argtypes = [vp, i64, i64, vp, f32, vp, i32, i32, i32, f32, vp, vp, vp]
+    L.atom_ref_add_quantize_act.restype = ctypes.c_int
+    L.atom_ref_add_quantize_act.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, f32, vp, i32, i32,
+                                            i32, f32, vp, vp, vp]
     L.atom_ref_quantize_weight.restype = ctypes.c_int
     L.atom_ref_quantize_weight.argtypes = [vp, i64, i64, vp, i32, i32, i32, f32, vp, vp, vp]
     L.atom_ref_w4a4_gemm.restype = ctypes.c_int
@@ -107,6 +110,26 @@ def quantize_act(x, gamma, eps, idx, group_size=128, n_outlier=128, clip=0.9):
     if rc != 0:
         raise ValueError("atom_ref_quantize_act: bad shapes")
     return q4, q8, sc
+
+
+def add_quantize_act(x, res, gamma, eps, idx, group_size=128, n_outlier=128, clip=0.9):
+    """Residual add fused in front of the front end.
+    Returns (sum float16 [M,K], q4, q8, scale)."""
+    x, res = _c(x, np.float16), _c(res, np.float16)
+    M, K = x.shape
+    g = None if gamma is None else _c(gamma, np.float16)
+    idx = _c(idx, np.int32)
+    K4, G = K - n_outlier, K // group_size
+    h = np.zeros((M, K), np.float16)
+    q4 = np.zeros((M, K4 // 2), np.uint8)
+    q8 = np.zeros((M, n_outlier), np.int8)
+    sc = np.zeros((M, G), np.float16)
+    rc = _load().atom_ref_add_quantize_act(_p(x), _p(res), M, K, K, _p(h), K, _p(g), eps,
+                                           _p(idx), K, group_size, n_outlier, clip, _p(q4),
+                                           _p(q8), _p(sc))
+    if rc != 0:
+        raise ValueError("atom_ref_add_quantize_act: bad shapes")
+    return h, q4, q8, sc
 
 
 def quantize_weight(w, idx, group_size=128, n_outlier=128, clip=0.85):

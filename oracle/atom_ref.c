@@ -182,6 +182,38 @@ int atom_ref_quantize_act(const uint16_t *x, int64_t M, int64_t ldx,
     return 0;
 }
 
+/* Residual add fused in front of the front end: h = fp16(x + res), the sum of
+ * the two fp16 values formed in fp32 and rounded once to fp16 (when the fp32
+ * sum is inexact the addends are more than 2^13 apart, which is nowhere near
+ * an fp16 rounding tie, so this is the correctly rounded fp16 sum). */
+int atom_ref_add_quantize_act(const uint16_t *x, const uint16_t *res, int64_t M,
+                              int64_t ldx, int64_t ldr, uint16_t *sum_out,
+                              int64_t ldo, const uint16_t *gamma, float eps,
+                              const int32_t *idx, int32_t K, int32_t Gs,
+                              int32_t O, float clip, uint8_t *q4, int8_t *q8,
+                              uint16_t *scale)
+{
+    if (!shapes_ok(K, Gs, O) || ldx < K || ldr < K || ldo < K || M < 0) return -1;
+    int32_t K4 = K - O, G = K / Gs;
+    float    *y = (float *)malloc(sizeof(float) * (size_t)K);
+    uint16_t *h = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)K);
+    if (!y || !h) { free(y); free(h); return -1; }
+    for (int64_t m = 0; m < M; ++m) {
+        for (int32_t k = 0; k < K; ++k) {
+            float a = atom_ref_f16_to_f32(x[m * ldx + k]);
+            float b = atom_ref_f16_to_f32(res[m * ldr + k]);
+            h[k] = atom_ref_f32_to_f16(a + b);
+        }
+        for (int32_t k = 0; k < K; ++k) sum_out[m * ldo + k] = h[k];
+        atom_ref_rmsnorm_row(h, gamma, eps, K, y);
+        quantize_row(y, idx, K, Gs, O, clip, q4 + m * (K4 / 2), q8 + m * O,
+                     scale + m * G);
+    }
+    free(y);
+    free(h);
+    return 0;
+}
+
 int atom_ref_quantize_weight(const uint16_t *w, int64_t N, int64_t ldw,
                              const int32_t *idx, int32_t K, int32_t Gs,
                              int32_t O, float clip, uint8_t *q4, int8_t *q8,

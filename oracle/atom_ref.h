@@ -67,6 +67,20 @@ int atom_ref_quantize_act(const uint16_t *x_f16, int64_t M, int64_t ldx,
                           const int32_t *idx, int32_t K, int32_t Gs, int32_t O,
                           float clip, uint8_t *q4, int8_t *q8, uint16_t *scale);
 
+/* The same front end behind a residual add (Sections 4.1 and 4.3 fuse the
+ * reorder and the dynamic quantisation into the operator before them; in a
+ * Llama block the operator before the norm is the residual add):
+ *   h = fp16(x + res)  (sum formed in fp32, rounded once to fp16),
+ *   sum_out [M, ldo] = h  (the new residual stream; may alias x or res),
+ *   then atom_ref_quantize_act on h. */
+int atom_ref_add_quantize_act(const uint16_t *x_f16, const uint16_t *res_f16,
+                              int64_t M, int64_t ldx, int64_t ldr,
+                              uint16_t *sum_out_f16, int64_t ldo,
+                              const uint16_t *gamma_f16, float eps,
+                              const int32_t *idx, int32_t K, int32_t Gs,
+                              int32_t O, float clip, uint8_t *q4, int8_t *q8,
+                              uint16_t *scale);
+
 /* Offline weight path (Section 4.1 reorder, Section 5.1 clip): same as the
  * front end without the norm; round-to-nearest only (no GPTQ). */
 int atom_ref_quantize_weight(const uint16_t *w_f16, int64_t N, int64_t ldw,

@@ -447,3 +447,59 @@ def test_reorder_leaves_the_product_unchanged_and_outliers_matter():
     bad = run(idx[::-1].copy())           # smallest channels in INT8 instead
     assert good < 0.2
     assert bad > 1.5 * good
+
+
+# ---------------------------------------------------------------- residual add in front
+
+
+def test_add_is_the_correctly_rounded_fp16_sum():
+    """h = fp16(x + res): the oracle forms the sum in fp32 and rounds once; the pin forms it
+    in fp64, where the sum of two fp16 values is always exact, and rounds that once with
+    numpy's double -> half conversion.  Includes pairs more than 2^13 apart (fp32 sum
+    inexact), exact ties, cancellation, subnormals and overflow to infinity."""
+    rng = np.random.default_rng(7)
+    a = rng.standard_normal(4096).astype(np.float16) * np.float16(3.0)
+    b = np.clip(rng.standard_normal(4096) * np.exp(4.0 * rng.standard_normal(4096)), -6e4, 6e4).astype(np.float16)
+    special_a = np.array([2048, 2048, 1, 65504, 65504, -65504, 6e-8, 6e-8, 1024, 0.1, 4096, 4096],
+                         dtype=np.float16)
+    special_b = np.array([1, 3, 2.0 ** -11, 16, 32, 65504, 6e-8, -6e-8, 0.5, -0.1, 2.0 ** -14, 2],
+                         dtype=np.float16)
+    a = np.concatenate([a, special_a, np.zeros(4, np.float16)])[:4096 + 16]
+    b = np.concatenate([b, special_b, np.zeros(4, np.float16)])[:4096 + 16]
+    K = 128 * ((a.size + 127) // 128)                     # whole groups; the rest stays zero
+    x = np.zeros((1, K), np.float16)
+    r = np.zeros((1, K), np.float16)
+    x[0, :a.size], r[0, :b.size] = a, b
+    idx = np.arange(K, dtype=np.int32)
+    with np.errstate(over="ignore"):
+        want = (x.astype(np.float64) + r.astype(np.float64)).astype(np.float16)
+    # keep the quantiser's inputs finite: the sum itself is what is pinned here
+    finite = np.isfinite(want)
+    x[~finite] = 0
+    r[~finite] = 0
+    want[~finite] = 0
+    h, q4, q8, sc = oracle.add_quantize_act(x, r, None, 0.0, idx, 128, 128, 1.0)
+    assert np.array_equal(h.view(np.uint16), want.view(np.uint16))
+    # the one overflowing pair, on its own: 65504 + 32 rounds to infinity in fp16
+    assert oracle.f32_to_f16(np.float32(65504.0) + np.float32(32.0)) == 0x7C00
+
+
+def test_add_quantize_is_quantize_of_the_sum():
+    """The fused entry point equals the plain front end applied to the rounded sum (whose own
+    pins are above), with and without RMSNorm, and the sum is returned."""
+    rng = np.random.default_rng(8)
+    M, K = 5, 512
+    x = (rng.standard_normal((M, K)) * np.exp(rng.standard_normal(K))).astype(np.float16)
+    r = (rng.standard_normal((M, K)) * 0.5).astype(np.float16)
+    gamma = (1 + 0.1 * rng.standard_normal(K)).astype(np.float16)
+    idx = rng.permutation(K).astype(np.int32)
+    hsum = (x.astype(np.float64) + r.astype(np.float64)).astype(np.float16)
+    for g, eps in ((gamma, 1e-6), (None, 0.0)):
+        h, q4, q8, sc = oracle.add_quantize_act(x, r, g, eps, idx, 128, 128, 0.9)
+        w4, w8, wsc = oracle.quantize_act(hsum, g, eps, idx, 128, 128, 0.9)
+        assert np.array_equal(h.view(np.uint16), hsum.view(np.uint16))
+        assert np.array_equal(q4, w4) and np.array_equal(q8, w8)
+        assert np.array_equal(sc.view(np.uint16), wsc.view(np.uint16))
+    # a planted mistake (sum rounded to fp16 only after the norm, i.e. norm on the fp32 sum)
+    # must be visible: x + r has fp16 rounding error in most elements
+    assert np.any(hsum.astype(np.float32) != x.astype(np.float32) + r.astype(np.float32))
