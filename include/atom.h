@@ -83,6 +83,28 @@ atom_status atom_quantize_act(const void *x_f16, int64_t M, int64_t ldx,
                               void *stream);
 
 /*
+ * The same front end behind the residual add of a transformer block (Sections
+ * 4.1 and 4.3: reorder and dynamic quantisation are fused into the operator
+ * before them; Section 4.5 workflow):
+ *   h = fp16(x + residual)          (correctly rounded fp16 sum)
+ *   sum_out_f16 = h                 (the new residual stream)
+ *   then atom_quantize_act on h.
+ *
+ *   residual_f16 [M, ldr] fp16, ldr >= K, ldr % 8 == 0, 16-byte aligned
+ *   sum_out_f16  [M, ldo] fp16, ldo >= K, ldo % 8 == 0, 16-byte aligned; may be
+ *                the same buffer as x_f16 or residual_f16 (same ld), must not
+ *                overlap them otherwise
+ *   other arguments, alignment and errors as atom_quantize_act
+ */
+atom_status atom_add_quantize_act(const void *x_f16, const void *residual_f16,
+                                  int64_t M, int64_t ldx, int64_t ldr,
+                                  void *sum_out_f16, int64_t ldo,
+                                  const void *gamma_f16, float eps,
+                                  const int32_t *reorder_idx,
+                                  const atom_desc *d, float clip, void *q4,
+                                  void *q8, void *scale_f16, void *stream);
+
+/*
  * One-time weight path (Section 4.1: weights are reordered offline with the
  * activations' index; Section 5.1: clip 0.85): reorder + round-to-nearest
  * group quantisation of W[N, K] (nn.Linear layout).  No norm, no GPTQ.

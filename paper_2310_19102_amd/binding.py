@@ -17,6 +17,7 @@ _lib = None
 
 EXPORTS = (
     "atom_quantize_act",
+    "atom_add_quantize_act",
     "atom_quantize_weight",
     "atom_w4a4_gemm",
     "atom_w4a4_gemm_workspace_bytes",
@@ -55,6 +56,8 @@ def load_library():
     dp = ctypes.POINTER(_Desc)
     L.atom_quantize_act.restype = ctypes.c_int
     L.atom_quantize_act.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, vp, vp, vp]
+    L.atom_add_quantize_act.restype = ctypes.c_int
+    L.atom_add_quantize_act.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, f32, vp, dp, f32, vp, vp, vp, vp]
     L.atom_quantize_weight.restype = ctypes.c_int
     L.atom_quantize_weight.argtypes = [vp, i64, i64, vp, dp, f32, vp, vp, vp, vp]
     L.atom_w4a4_gemm.restype = ctypes.c_int
@@ -129,6 +132,39 @@ def atom_quantize_act(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float
     if st != 0:
         raise AtomError(st, "atom_quantize_act")
     return q4, q8, sc
+
+
+def atom_add_quantize_act(x: torch.Tensor, residual: torch.Tensor, gamma: Optional[torch.Tensor],
+                          eps: float, reorder_idx: torch.Tensor, group_size: int = 128,
+                          n_outlier: int = 128, clip: float = 0.9,
+                          sum_out: Optional[torch.Tensor] = None,
+                          out: Optional[Tuple[torch.Tensor, ...]] = None):
+    """``h = fp16(x + residual)`` followed by the front end on ``h``.  ``sum_out`` may be
+    ``x`` or ``residual`` (in place) or a separate [M, K] tensor; a new one by default.
+    Returns ``(h, q4, q8, scale)``."""
+    L = load_library()
+    _dev(x, torch.float16, "x")
+    _dev(residual, torch.float16, "residual")
+    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if gamma is not None:
+        _dev(gamma, torch.float16, "gamma")
+    if x.dim() != 2 or x.stride(1) != 1 or residual.shape != x.shape or residual.stride(1) != 1:
+        raise ValueError("x and residual must be [M, K] with a contiguous last dimension")
+    M, K = x.shape
+    if sum_out is None:
+        sum_out = torch.empty((M, K), dtype=torch.float16, device=x.device)
+    _dev(sum_out, torch.float16, "sum_out")
+    if sum_out.shape != x.shape or sum_out.stride(1) != 1:
+        raise ValueError("sum_out must be [M, K] with a contiguous last dimension")
+    d = _desc(K, group_size, n_outlier)
+    q4, q8, sc = out if out is not None else _quant_outputs(M, K, group_size, n_outlier, x.device)
+    ld = lambda t: t.stride(0) if M > 1 else max(K, t.stride(0))
+    st = L.atom_add_quantize_act(_ptr(x), _ptr(residual), M, ld(x), ld(residual), _ptr(sum_out),
+                                 ld(sum_out), _ptr(gamma), eps, _ptr(reorder_idx), ctypes.byref(d),
+                                 clip, _ptr(q4), _ptr(q8), _ptr(sc), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_add_quantize_act")
+    return sum_out, q4, q8, sc
 
 
 def atom_quantize_weight(w: torch.Tensor, reorder_idx: torch.Tensor, group_size: int = 128,

@@ -40,6 +40,25 @@ __device__ __forceinline__ void halves_to_floats(const uint4 &raw, float *f)
     }
 }
 
+// h = fp16(a + b) per element: the sum of two fp16 values formed in fp32 and rounded once
+// (where the fp32 sum is inexact the addends are more than 2^13 apart, nowhere near an
+// fp16 rounding tie, so this is the correctly rounded fp16 sum)
+__device__ __forceinline__ uint4 add_halves(const uint4 &a, const uint4 &b)
+{
+    float fa[8], fb[8];
+    halves_to_floats(a, fa);
+    halves_to_floats(b, fb);
+    uint4 out;
+    uint32_t *o = reinterpret_cast<uint32_t *>(&out);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t lo = __half_as_ushort(__float2half_rn(fa[2 * i] + fb[2 * i]));
+        const uint32_t hi = __half_as_ushort(__float2half_rn(fa[2 * i + 1] + fb[2 * i + 1]));
+        o[i] = lo | (hi << 16);
+    }
+    return out;
+}
+
 // max over the 16 lanes of a DPP row (xor butterfly; max is exact in any order)
 __device__ __forceinline__ float row16_max(float v)
 {
@@ -48,9 +67,12 @@ __device__ __forceinline__ float row16_max(float v)
     return v;
 }
 
-template <bool NORM>
+// ADD: x is first added to a residual row and the sum (fp16) is written out; x, res and
+// sum_out may alias each other (every element is read and written by the same thread).
+template <bool NORM, bool ADD>
 __global__ __launch_bounds__(kThreads)
-void quantize_rows_kernel(const __half *__restrict__ x, int64_t rows, int64_t ld,
+void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
+                          const __half *res, int64_t ldr, __half *sum_out, int64_t ldo,
                           const __half *__restrict__ gamma, float eps,
                           const int32_t *__restrict__ idx, int K, int O, float clip,
                           uint8_t *__restrict__ q4, int8_t *__restrict__ q8,
@@ -74,6 +96,10 @@ void quantize_rows_kernel(const __half *__restrict__ x, int64_t rows, int64_t ld
         // ---- 1. stage the row ------------------------------------------------
         for (int v = tid; v < V; v += kThreads) {
             uint4 raw = *reinterpret_cast<const uint4 *>(xr + 8 * v);
+            if (ADD) {
+                raw = add_halves(raw, *reinterpret_cast<const uint4 *>(res + row * ldr + 8 * v));
+                *reinterpret_cast<uint4 *>(sum_out + row * ldo + 8 * v) = raw;
+            }
             float f[8];
             halves_to_floats(raw, f);
             *reinterpret_cast<float4 *>(ybuf + 8 * v)     = make_float4(f[0], f[1], f[2], f[3]);
@@ -196,9 +222,10 @@ __device__ __forceinline__ float row16_max_dpp(float v)
 //     |y| / s <= (2^n - 1)/(2 clip) * (1 + 2^-11) and s >= 2^-24; quotients below 2^-100
 //     round to code 0 either way.  A zero scale (all-zero group) yields zero codes;
 //   * the group maximum is a DPP rotation reduction.
-template <bool NORM, int NS, int NT>
+template <bool NORM, int NS, int NT, bool ADD>
 __global__ __launch_bounds__(NT)
-void quantize_rows_fast_kernel(const __half *__restrict__ x, int64_t rows, int64_t ld,
+void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
+                               const __half *res, int64_t ldr, __half *sum_out, int64_t ldo,
                                const __half *__restrict__ gamma, float eps,
                                const int32_t *__restrict__ idx, int K, int O, float clip,
                                uint8_t *__restrict__ q4, int8_t *__restrict__ q8,
@@ -239,18 +266,33 @@ void quantize_rows_fast_kernel(const __half *__restrict__ x, int64_t rows, int64
     }
 
     uint4 raw[NS];
+    uint4 rres[ADD ? NS : 1];
     auto fetch_row = [&](int64_t row) {
         const __half *xr = x + row * ld;
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
             const int v = tid + NT * i;
             raw[i] = v < V ? *reinterpret_cast<const uint4 *>(xr + 8 * v) : make_uint4(0, 0, 0, 0);
+            if (ADD)
+                rres[i] = v < V ? *reinterpret_cast<const uint4 *>(res + row * ldr + 8 * v)
+                                : make_uint4(0, 0, 0, 0);
         }
     };
     int64_t row = blockIdx.x;
     if (row < rows) fetch_row(row);
 
     for (; row < rows; row += gridDim.x) {
+        // ---- 0. residual add; the sum is the new residual stream and the row quantised below
+        if (ADD) {
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                const int v = tid + NT * i;
+                if (v < V) {
+                    raw[i] = add_halves(raw[i], rres[i]);
+                    *reinterpret_cast<uint4 *>(sum_out + row * ldo + 8 * v) = raw[i];
+                }
+            }
+        }
         // ---- 1./2. stage the row (after RMSNorm, if any) in LDS, original channel order
         float r = 1.0f;
         if (NORM) {
@@ -365,12 +407,17 @@ size_t quantize_lds_bytes(int K, bool norm)
     return sizeof(float) * (size_t)(K + (norm ? K / 8 : 0));
 }
 
-template <bool NORM, int NS, int NT>
-hipError_t launch_fast(const void *x, int64_t rows, int64_t ld, const void *gamma, float eps,
-                       const int32_t *idx, int K, int O, float clip, void *q4, void *q8,
-                       void *scale, size_t lds, hipStream_t stream)
+struct QuantArgs {
+    const void *x; int64_t rows, ld;
+    const void *res; int64_t ldr; void *sum_out; int64_t ldo;     // res == nullptr: no residual add
+    const void *gamma; float eps; const int32_t *idx; int K, O; float clip;
+    void *q4, *q8, *scale;
+};
+
+template <bool NORM, int NS, int NT, bool ADD>
+hipError_t launch_fast(const QuantArgs &a, size_t lds, hipStream_t stream)
 {
-    auto kern = &quantize_rows_fast_kernel<NORM, NS, NT>;
+    auto kern = &quantize_rows_fast_kernel<NORM, NS, NT, ADD>;
     static size_t allowed = 0;        // the opt-in for more than 64 KB of dynamic LDS
     if (lds > allowed) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -392,56 +439,61 @@ hipError_t launch_fast(const void *x, int64_t rows, int64_t ld, const void *gamm
     const int64_t by_waves = 2048 / NT;                 // 32 wavefronts per CU
     per_cu = per_cu < 1 ? 1 : (per_cu > by_waves ? by_waves : per_cu);
     const int64_t slots = (int64_t)cus * per_cu;
-    const int64_t rows_per_wg = (rows + slots - 1) / slots;
-    const int64_t grid = (rows + rows_per_wg - 1) / rows_per_wg;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, stream, (const __half *)x,
-                       rows, ld, (const __half *)gamma, eps, idx, K, O, clip, (uint8_t *)q4,
-                       (int8_t *)q8, (__half *)scale);
+    const int64_t rows_per_wg = (a.rows + slots - 1) / slots;
+    const int64_t grid = (a.rows + rows_per_wg - 1) / rows_per_wg;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, stream, (const __half *)a.x,
+                       a.rows, a.ld, (const __half *)a.res, a.ldr, (__half *)a.sum_out, a.ldo,
+                       (const __half *)a.gamma, a.eps, a.idx, a.K, a.O, a.clip, (uint8_t *)a.q4,
+                       (int8_t *)a.q8, (__half *)a.scale);
     return hipGetLastError();
 }
 
-hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, const void *gamma,
+template <bool NORM, bool ADD>
+hipError_t launch_plain(const QuantArgs &a, size_t lds, hipStream_t stream)
+{
+    auto kern = &quantize_rows_kernel<NORM, ADD>;
+    const int grid = (int)(a.rows < (int64_t)1 << 20 ? a.rows : (int64_t)1 << 20);
+    // the opt-in for more than 64 KB of dynamic LDS is raised only when a call needs more
+    static size_t allowed = 0;
+    if (lds > allowed) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return err;
+        allowed = lds;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, (const __half *)a.x, a.rows,
+                       a.ld, (const __half *)a.res, a.ldr, (__half *)a.sum_out, a.ldo,
+                       (const __half *)a.gamma, a.eps, a.idx, a.K, a.O, a.clip, (uint8_t *)a.q4,
+                       (int8_t *)a.q8, (__half *)a.scale);
+    return hipGetLastError();
+}
+
+template <bool NORM, bool ADD>
+hipError_t dispatch_quantize(const QuantArgs &a, hipStream_t stream)
+{
+    const size_t lds = quantize_lds_bytes(a.K, NORM);
+    // The fast kernel keeps ceil(K / (8 * threads)) gather-offset sets in registers and
+    // relies on a sane clip; rows of 8192 channels and more are spread over 512 threads.
+    if (a.K <= 16384 && a.clip >= 9.5367431640625e-07f && a.clip <= 1.0f) {
+        if (a.K <= 2048)  return launch_fast<NORM, 1, 256, ADD>(a, lds, stream);
+        if (a.K <= 4096)  return launch_fast<NORM, 2, 256, ADD>(a, lds, stream);
+        if (a.K < 8192)   return launch_fast<NORM, 4, 256, ADD>(a, lds, stream);
+        if (a.K <= 8192)  return launch_fast<NORM, 2, 512, ADD>(a, lds, stream);
+        if (a.K <= 12288) return launch_fast<NORM, 3, 512, ADD>(a, lds, stream);
+        return launch_fast<NORM, 4, 512, ADD>(a, lds, stream);
+    }
+    return launch_plain<NORM, ADD>(a, lds, stream);
+}
+
+hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, const void *res,
+                                int64_t ldr, void *sum_out, int64_t ldo, const void *gamma,
                                 float eps, const int32_t *idx, int K, int O, float clip,
                                 void *q4, void *q8, void *scale, hipStream_t stream)
 {
-    const bool   norm = gamma != nullptr;
-    const size_t lds  = quantize_lds_bytes(K, norm);
-    // The fast kernel keeps ceil(K / (8 * threads)) gather-offset sets in registers and
-    // relies on a sane clip; rows of 8192 channels and more are spread over 512 threads.
-    if (K <= 16384 && clip >= 9.5367431640625e-07f && clip <= 1.0f) {
-#define ATOM_FAST(NS_, NT_)                                                                         \
-    return norm ? launch_fast<true, NS_, NT_>(x, rows, ld, gamma, eps, idx, K, O, clip, q4, q8,    \
-                                              scale, lds, stream)                                  \
-                : launch_fast<false, NS_, NT_>(x, rows, ld, gamma, eps, idx, K, O, clip, q4, q8,   \
-                                               scale, lds, stream)
-        if (K <= 2048)  { ATOM_FAST(1, 256); }
-        if (K <= 4096)  { ATOM_FAST(2, 256); }
-        if (K < 8192)   { ATOM_FAST(4, 256); }
-        if (K <= 8192)  { ATOM_FAST(2, 512); }
-        if (K <= 12288) { ATOM_FAST(3, 512); }
-        ATOM_FAST(4, 512);
-#undef ATOM_FAST
-    }
-    const int    grid = (int)(rows < (int64_t)1 << 20 ? rows : (int64_t)1 << 20);
-    // the opt-in for more than 64 KB of dynamic LDS is raised only when a call needs more
-    static size_t allowed[2] = {0, 0};
-    const void *fn = norm ? reinterpret_cast<const void *>(&quantize_rows_kernel<true>)
-                          : reinterpret_cast<const void *>(&quantize_rows_kernel<false>);
-    if (lds > allowed[norm]) {
-        hipError_t err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds);
-        if (err != hipSuccess) return err;
-        allowed[norm] = lds;
-    }
-    if (norm)
-        hipLaunchKernelGGL(quantize_rows_kernel<true>, dim3(grid), dim3(kThreads), lds, stream,
-                           (const __half *)x, rows, ld, (const __half *)gamma, eps, idx, K, O,
-                           clip, (uint8_t *)q4, (int8_t *)q8, (__half *)scale);
-    else
-        hipLaunchKernelGGL(quantize_rows_kernel<false>, dim3(grid), dim3(kThreads), lds, stream,
-                           (const __half *)x, rows, ld, (const __half *)nullptr, eps, idx, K, O,
-                           clip, (uint8_t *)q4, (int8_t *)q8, (__half *)scale);
-    return hipGetLastError();
+    const QuantArgs a = {x, rows, ld, res, ldr, sum_out, ldo, gamma, eps, idx, K, O, clip, q4, q8, scale};
+    const bool norm = gamma != nullptr, add = res != nullptr;
+    if (norm) return add ? dispatch_quantize<true, true>(a, stream) : dispatch_quantize<true, false>(a, stream);
+    return add ? dispatch_quantize<false, true>(a, stream) : dispatch_quantize<false, false>(a, stream);
 }
 
 }  // namespace atom_internal

@@ -105,6 +105,71 @@ def test_front_end_plain_and_fast_kernels_agree():
         assert_quant_equal(ga, ref_quantize_act(lin), f"clip {clip}")
 
 
+@pytest.mark.parametrize("M,K,O,norm,clip", [
+    (7, 512, 128, True, 0.9),        # one register set of gather offsets
+    (33, 4096, 128, True, 0.9),      # the Llama-7B hidden size
+    (9, 11008, 128, False, 0.9),     # 512 threads per row
+    (3000, 512, 256, True, 1.0),     # several rows per workgroup: the next row is prefetched
+    (4, 20480, 128, True, 0.9),      # K > 16384: the plain kernel
+    (5, 1024, 128, False, 1e-8),     # clip below 2^-20: the plain kernel
+])
+def test_add_quantize_act(M, K, O, norm, clip):
+    """Residual add fused in front of the front end: the fp16 sum, the codes and the scales
+    are bit-exact against the oracle; in place on either input gives the same."""
+    g = torch.Generator().manual_seed(M * 7 + K)
+    sigma = torch.exp(1.5 * torch.randn(K, generator=g))
+    x = (torch.randn((M, K), generator=g) * sigma).to(torch.float16)
+    res = (torch.randn((M, K), generator=g) * sigma * 0.7).to(torch.float16)
+    res[0, :16] = -x[0, :16]                                  # exact cancellation
+    gamma = (1 + 0.1 * torch.randn(K, generator=g)).to(torch.float16) if norm else None
+    idx = torch.argsort(sigma, stable=True).to(torch.int32)
+    eps = 1e-6 if norm else 0.0
+    print(f"[case] add+quantize M={M} K={K} O={O} norm={norm} clip={clip}", flush=True)
+    want = oracle.add_quantize_act(x.numpy(), res.numpy(), None if gamma is None else gamma.numpy(),
+                                   eps, idx.numpy(), 128, O, clip)
+    xd, rd = dev(x), dev(res)
+    h, q4, q8, sc = atom.atom_add_quantize_act(xd, rd, dev(gamma), eps, dev(idx), 128, O, clip)
+    torch.cuda.synchronize()
+    assert np.array_equal(npy(h).view(np.uint16), want[0].view(np.uint16)), "sum differs"
+    assert_quant_equal((q4, q8, sc), want[1:], "add+quantize")
+    assert np.array_equal(npy(xd).view(np.uint16), x.numpy().view(np.uint16)), "input was modified"
+    # in place on the residual (the usual use), then on x
+    for target in ("residual", "x"):
+        xd, rd = dev(x), dev(res)
+        t = rd if target == "residual" else xd
+        h2, q4, q8, sc = atom.atom_add_quantize_act(xd, rd, dev(gamma), eps, dev(idx), 128, O, clip,
+                                                    sum_out=t)
+        torch.cuda.synchronize()
+        assert h2.data_ptr() == t.data_ptr()
+        assert np.array_equal(npy(t).view(np.uint16), want[0].view(np.uint16)), f"in place on {target}"
+        assert_quant_equal((q4, q8, sc), want[1:], f"in place on {target}")
+
+
+def test_add_quantize_act_strided_and_errors():
+    K = 512
+    g = torch.Generator().manual_seed(3)
+    x = torch.randn((6, K), generator=g).to(torch.float16)
+    res = torch.randn((6, K), generator=g).to(torch.float16)
+    idx = torch.randperm(K, generator=g).to(torch.int32)
+    want = oracle.add_quantize_act(x.numpy(), res.numpy(), None, 0.0, idx.numpy(), 128, 128, 0.9)
+    bx = torch.zeros((6, 2 * K), dtype=torch.float16); bx[:, :K] = x
+    br = torch.zeros((6, 3 * K), dtype=torch.float16); br[:, K:2 * K] = res
+    bo = torch.zeros((6, 2 * K), dtype=torch.float16).cuda()
+    h, q4, q8, sc = atom.atom_add_quantize_act(bx.cuda()[:, :K], br.cuda()[:, K:2 * K], None, 0.0,
+                                               dev(idx), sum_out=bo[:, K:])
+    torch.cuda.synchronize()
+    assert np.array_equal(npy(bo[:, K:]).view(np.uint16), want[0].view(np.uint16))
+    assert not npy(bo[:, :K]).any()                              # nothing written outside
+    assert_quant_equal((q4, q8, sc), want[1:], "strided add")
+    # empty call, and a residual row stride that breaks the 16-byte alignment
+    e = atom.atom_add_quantize_act(dev(x[:0]), dev(res[:0]), None, 0.0, dev(idx))
+    assert e[0].shape[0] == 0 and e[1].shape[0] == 0
+    odd = torch.zeros((6, K + 4), dtype=torch.float16).cuda()[:, :K]
+    with pytest.raises(atom.AtomError) as err:
+        atom.atom_add_quantize_act(dev(x), odd, None, 0.0, dev(idx))
+    assert err.value.status == 4
+
+
 def test_strided_input_rows():
     lin = _rand_linear(16, 512, 64, 128, seed=7)
     big = torch.zeros((16, 1024), dtype=torch.float16)
