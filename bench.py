@@ -174,6 +174,48 @@ def extra_measurements():
                     "effective_tops": L.ops / t / 1e12})
         del L
         torch.cuda.empty_cache()
+    # the front end alone, plain and behind the fused residual add, against the HBM roofline
+    for (cfg, which) in ((4, 0), (5, 0)):
+        lin = synth.make(cfg, which)
+        M, K = lin.M, lin.K
+        x, gamma, idx = lin.x.cuda(), lin.gamma.cuda(), lin.idx.cuda()
+        res = (0.5 * lin.x).cuda()
+        hsum = torch.empty_like(x)
+        qa = atom.atom_quantize_act(x, gamma, lin.eps, idx, lin.group_size, lin.n_outlier, lin.clip_act)
+        codes = (K - lin.n_outlier) // 2 + lin.n_outlier + 2 * (K // lin.group_size)
+        variants = {
+            "front_end": (lambda: atom.atom_quantize_act(x, gamma, lin.eps, idx, lin.group_size,
+                                                         lin.n_outlier, lin.clip_act, out=qa),
+                          M * (2 * K + codes)),
+            "add_front_end": (lambda: atom.atom_add_quantize_act(x, res, gamma, lin.eps, idx,
+                                                                 lin.group_size, lin.n_outlier,
+                                                                 lin.clip_act, sum_out=hsum, out=qa),
+                              M * (3 * 2 * K + codes)),
+        }
+        entry = {"workload": f"front end M={M} K={K} (RMSNorm), in a HIP graph of 50 launches"}
+        for name, (fn, nbytes) in variants.items():
+            fn()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for _ in range(50):
+                    fn()
+            graph.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(4):
+                graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            per = e0.elapsed_time(e1) * 1e-3 / 200
+            del graph
+            entry[name + "_us"] = per * 1e6
+            entry[name + "_bytes"] = nbytes
+            entry[name + "_hbm_frac"] = nbytes / per / 1e9 / PEAK_HBM_GBS
+        out.append(entry)
+        del x, res, hsum, qa
+        torch.cuda.empty_cache()
     return out
 
 
