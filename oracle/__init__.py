@@ -54,6 +54,12 @@ def _load():
     L.atom_ref_add_quantize_act.restype = ctypes.c_int
     L.atom_ref_add_quantize_act.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, f32, vp, i32, i32,
                                             i32, f32, vp, vp, vp]
+    L.atom_ref_expf.restype = f32
+    L.atom_ref_expf.argtypes = [f32]
+    L.atom_ref_silu_mul.restype = f32
+    L.atom_ref_silu_mul.argtypes = [ctypes.c_uint16, ctypes.c_uint16]
+    L.atom_ref_swiglu_quantize_act.restype = ctypes.c_int
+    L.atom_ref_swiglu_quantize_act.argtypes = [vp, vp, i64, i64, i64, vp, i32, i32, i32, f32, vp, vp, vp]
     L.atom_ref_quantize_weight.restype = ctypes.c_int
     L.atom_ref_quantize_weight.argtypes = [vp, i64, i64, vp, i32, i32, i32, f32, vp, vp, vp]
     L.atom_ref_w4a4_gemm.restype = ctypes.c_int
@@ -130,6 +136,39 @@ def add_quantize_act(x, res, gamma, eps, idx, group_size=128, n_outlier=128, cli
     if rc != 0:
         raise ValueError("atom_ref_add_quantize_act: bad shapes")
     return h, q4, q8, sc
+
+
+def expf(x) -> float:
+    return float(_load().atom_ref_expf(float(np.float32(x))))
+
+
+def silu_mul(gate, up):
+    """(g * sigma(g)) * u in fp32 for fp16 arrays of equal shape; float32 array."""
+    g, u = _c(gate, np.float16), _c(up, np.float16)
+    L = _load()
+    out = np.empty(g.shape, np.float32)
+    gb, ub = g.view(np.uint16).ravel(), u.view(np.uint16).ravel()
+    flat = out.ravel()
+    for i in range(gb.size):
+        flat[i] = L.atom_ref_silu_mul(int(gb[i]), int(ub[i]))
+    return out
+
+
+def swiglu_quantize_act(gate, up, idx, group_size=128, n_outlier=128, clip=0.9):
+    """silu(gate)*up fused in front of reorder + group quantisation.
+    Returns (q4, q8, scale)."""
+    g, u = _c(gate, np.float16), _c(up, np.float16)
+    M, K = g.shape
+    idx = _c(idx, np.int32)
+    K4, G = K - n_outlier, K // group_size
+    q4 = np.zeros((M, K4 // 2), np.uint8)
+    q8 = np.zeros((M, n_outlier), np.int8)
+    sc = np.zeros((M, G), np.float16)
+    rc = _load().atom_ref_swiglu_quantize_act(_p(g), _p(u), M, K, K, _p(idx), K, group_size,
+                                              n_outlier, clip, _p(q4), _p(q8), _p(sc))
+    if rc != 0:
+        raise ValueError("atom_ref_swiglu_quantize_act: bad shapes")
+    return q4, q8, sc
 
 
 def quantize_weight(w, idx, group_size=128, n_outlier=128, clip=0.85):

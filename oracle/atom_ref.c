@@ -214,6 +214,64 @@ int atom_ref_add_quantize_act(const uint16_t *x, const uint16_t *res, int64_t M,
     return 0;
 }
 
+/* ------------------------------------------------------- SwiGLU in front -- */
+
+/* exp(x) for x in [-87, 87], from IEEE operations only, so that it has one
+ * value on every machine: n = round(x*log2(e)); r = x - n*ln2 with ln2 split
+ * in two (the first part has 12 trailing zero bits, so n*ln2_hi is exact);
+ * e^r by its Taylor polynomial of degree 7 in Horner form with fused
+ * multiply-adds (|r| <= 0.347: truncation 1.3e-8 relative); the result is
+ * scaled by 2^n through the exponent field (n in [-126, 126]). */
+float atom_ref_expf(float x)
+{
+    if (x < -87.0f) x = -87.0f;
+    if (x > 87.0f) x = 87.0f;
+    float n = nearbyintf(x * 1.44269502162933349609375f);
+    float r = fmaf(n, -0.693145751953125f, x);
+    r = fmaf(n, -1.428606765330187045037746429443359375e-06f, r);
+    float p = 1.0f / 5040.0f;
+    p = fmaf(p, r, 1.0f / 720.0f);
+    p = fmaf(p, r, 1.0f / 120.0f);
+    p = fmaf(p, r, 1.0f / 24.0f);
+    p = fmaf(p, r, 1.0f / 6.0f);
+    p = fmaf(p, r, 0.5f);
+    p = fmaf(p, r, 1.0f);
+    p = fmaf(p, r, 1.0f);
+    union { uint32_t u; float f; } two_n;
+    two_n.u = (uint32_t)((int32_t)n + 127) << 23;
+    return p * two_n.f;
+}
+
+/* silu(g) * u in fp32: sigma = 1 / (1 + exp(-g)) with the exp above and an
+ * IEEE division, then (g * sigma) * u, two fp32 multiplies in this order. */
+float atom_ref_silu_mul(uint16_t gate_f16, uint16_t up_f16)
+{
+    float g = atom_ref_f16_to_f32(gate_f16), u = atom_ref_f16_to_f32(up_f16);
+    float e = atom_ref_expf(-g);
+    float sigma = 1.0f / (1.0f + e);
+    return (g * sigma) * u;
+}
+
+int atom_ref_swiglu_quantize_act(const uint16_t *gate, const uint16_t *up,
+                                 int64_t M, int64_t ldg, int64_t ldu,
+                                 const int32_t *idx, int32_t K, int32_t Gs,
+                                 int32_t O, float clip, uint8_t *q4, int8_t *q8,
+                                 uint16_t *scale)
+{
+    if (!shapes_ok(K, Gs, O) || ldg < K || ldu < K || M < 0) return -1;
+    int32_t K4 = K - O, G = K / Gs;
+    float *y = (float *)malloc(sizeof(float) * (size_t)K);
+    if (!y) return -1;
+    for (int64_t m = 0; m < M; ++m) {
+        for (int32_t k = 0; k < K; ++k)
+            y[k] = atom_ref_silu_mul(gate[m * ldg + k], up[m * ldu + k]);
+        quantize_row(y, idx, K, Gs, O, clip, q4 + m * (K4 / 2), q8 + m * O,
+                     scale + m * G);
+    }
+    free(y);
+    return 0;
+}
+
 int atom_ref_quantize_weight(const uint16_t *w, int64_t N, int64_t ldw,
                              const int32_t *idx, int32_t K, int32_t Gs,
                              int32_t O, float clip, uint8_t *q4, int8_t *q8,

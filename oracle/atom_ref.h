@@ -81,6 +81,21 @@ int atom_ref_add_quantize_act(const uint16_t *x_f16, const uint16_t *res_f16,
                               int32_t O, float clip, uint8_t *q4, int8_t *q8,
                               uint16_t *scale);
 
+/* The front end behind the activation function of the MLP (Sections 4.1, 4.3
+ * and 4.5: the quantisation of the down projection's input is fused into the
+ * operator before it, which in a Llama block is silu(gate) * up):
+ *   y = (g * sigma(g)) * u in fp32, sigma(g) = 1/(1 + exp(-g)), never stored,
+ *   then reorder and group quantisation as in atom_ref_quantize_act (no norm).
+ * exp is the fixed sequence of IEEE operations of atom_ref_expf, so y has one
+ * correct value.  gate [M, ldg], up [M, ldu] fp16. */
+float atom_ref_expf(float x);
+float atom_ref_silu_mul(uint16_t gate_f16, uint16_t up_f16);
+int atom_ref_swiglu_quantize_act(const uint16_t *gate_f16, const uint16_t *up_f16,
+                                 int64_t M, int64_t ldg, int64_t ldu,
+                                 const int32_t *idx, int32_t K, int32_t Gs,
+                                 int32_t O, float clip, uint8_t *q4, int8_t *q8,
+                                 uint16_t *scale);
+
 /* Offline weight path (Section 4.1 reorder, Section 5.1 clip): same as the
  * front end without the norm; round-to-nearest only (no GPTQ). */
 int atom_ref_quantize_weight(const uint16_t *w_f16, int64_t N, int64_t ldw,

@@ -503,3 +503,89 @@ def test_add_quantize_is_quantize_of_the_sum():
     # a planted mistake (sum rounded to fp16 only after the norm, i.e. norm on the fp32 sum)
     # must be visible: x + r has fp16 rounding error in most elements
     assert np.any(hsum.astype(np.float32) != x.astype(np.float32) + r.astype(np.float32))
+
+
+# ---------------------------------------------------------------- SwiGLU in front
+
+
+def test_expf_against_float64():
+    """The oracle's exp is a fixed sequence of IEEE operations; the pin is the libm exp in
+    float64.  A dropped polynomial term (1e-4 and worse), a wrong ln2 split or a wrong sign
+    in the range reduction all exceed the bound by orders of magnitude."""
+    import math
+    xs = np.concatenate([np.linspace(-87, 87, 20001), np.linspace(-0.4, 0.4, 2001),
+                         np.array([0.0, 1.0, -1.0, 0.34657359, -0.34657359, 86.999, -86.999])])
+    worst = 0.0
+    for x in xs.astype(np.float32):
+        got = oracle.expf(x)
+        ref = math.exp(float(x))
+        worst = max(worst, abs(got - ref) / ref)
+    assert worst < 1.0e-7, worst                   # under one fp32 ulp; the degree-7 term alone is 1.2e-7
+    assert oracle.expf(0.0) == 1.0
+    assert oracle.expf(-1000.0) == oracle.expf(-87.0)      # clamped, still a normal number
+    assert oracle.expf(1000.0) == oracle.expf(87.0)
+    assert oracle.expf(-87.0) > 1.1754944e-38
+
+
+def test_silu_mul_against_float64_for_every_fp16_gate():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    g = bits.view(np.float16)
+    g = g[np.isfinite(g)]
+    u = np.full(g.shape, 1.5, np.float16)
+    got = oracle.silu_mul(g, u).astype(np.float64)
+    g64 = g.astype(np.float64)
+    with np.errstate(over="ignore"):
+        ref = g64 / (1.0 + np.exp(-g64)) * 1.5
+    # gates below -87 are clamped in the exp: silu there is below 1e-35 in magnitude either way
+    main = g64 > -87.0
+    err = np.abs(got[main] - ref[main])
+    assert np.all(err <= 6e-7 * np.abs(ref[main]) + 1e-40), (err / (np.abs(ref[main]) + 1e-300)).max()
+    assert np.all(np.abs(got[~main]) < 1e-32)
+    # closed forms: silu(0) = 0; sigma rounds to 1 for large gates, so y = g*u exactly
+    assert oracle.silu_mul(np.array([0.0], np.float16), np.array([3.0], np.float16))[0] == 0.0
+    big = np.array([20.0, 100.0, 1000.0], np.float16)
+    assert np.array_equal(oracle.silu_mul(big, np.array([2.0, 0.5, -4.0], np.float16)),
+                          np.array([40.0, 50.0, -4000.0], np.float32))
+    # the order of the two multiplies is part of the contract: (g*sigma)*u, not g*(sigma*u)
+    gg, uu = np.array([1.2373046875], np.float16), np.array([0.337158203125], np.float16)
+    sig = np.float32(1.0) / (np.float32(1.0) + np.float32(oracle.expf(-np.float32(gg[0]))))
+    assert oracle.silu_mul(gg, uu)[0] == (np.float32(gg[0]) * sig) * np.float32(uu[0])
+
+
+def test_swiglu_quantize_reduces_to_the_plain_front_end():
+    """Where sigma(g) rounds to exactly 1 and g*u is exact in fp16, silu(g)*u is an fp16
+    number and the fused entry point must equal the (pinned) plain front end on it; a
+    second case checks codes and scales on general values by re-deriving them from the
+    fp32 rows with exact rationals."""
+    from fractions import Fraction
+    rng = np.random.default_rng(11)
+    M, K = 4, 256
+    g = rng.integers(20, 60, size=(M, K)).astype(np.float16)            # sigma == 1
+    u = rng.choice(np.array([0.5, 1.0, 2.0, -1.0, -0.25], np.float16), size=(M, K))
+    idx = rng.permutation(K).astype(np.int32)
+    y16 = (g.astype(np.float32) * u.astype(np.float32)).astype(np.float16)
+    assert np.array_equal(y16.astype(np.float32), oracle.silu_mul(g, u))
+    got = oracle.swiglu_quantize_act(g, u, idx, 128, 128, 0.9)
+    want = oracle.quantize_act(y16, None, 0.0, idx, 128, 128, 0.9)
+    for a, b in zip(got, want):
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+    # general values: one row, exact-rational scale and codes from the oracle's own fp32 y
+    g = (rng.standard_normal((1, K)) * 3).astype(np.float16)
+    u = (rng.standard_normal((1, K)) * 2).astype(np.float16)
+    idx = np.arange(K, dtype=np.int32)
+    q4, q8, sc = oracle.swiglu_quantize_act(g, u, idx, 128, 128, 1.0)
+    y = oracle.silu_mul(g, u)[0]
+    amax = max(abs(float(v)) for v in y[:128])
+    s32 = np.float32(np.float32(np.float32(2.0) * np.float32(amax)) * np.float32(1.0)) / np.float32(15.0)
+    assert sc[0, 0] == np.float16(s32)
+    s = Fraction(float(sc[0, 0]))
+    for j in range(0, 128, 7):
+        qf = np.float32(np.float32(y[j]) / np.float32(sc[0, 0]))            # IEEE fp32 division
+        t = Fraction(float(qf))
+        fl = t.numerator // t.denominator
+        frac = t - fl
+        q = fl + (1 if frac > Fraction(1, 2) or (frac == Fraction(1, 2) and fl % 2) else 0)
+        q = max(-8, min(7, q))
+        nib = (int(q4[0, j // 2]) >> (4 * (j % 2))) & 0xF
+        assert (nib - 16 if nib >= 8 else nib) == q, (j, q, nib)
+    assert s > 0
