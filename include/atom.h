@@ -105,6 +105,27 @@ atom_status atom_add_quantize_act(const void *x_f16, const void *residual_f16,
                                   void *q8, void *scale_f16, void *stream);
 
 /*
+ * The front end behind the activation function of the MLP (Sections 4.1, 4.3
+ * and 4.5: the quantisation of the down projection's input is fused into the
+ * operator before it, silu(gate) * up in a Llama block):
+ *   y = (g * sigma(g)) * u in fp32, sigma(g) = 1 / (1 + exp(-g)), never stored,
+ *   then reorder and group quantisation as in atom_quantize_act (no norm).
+ * exp is evaluated by a fixed sequence of IEEE fp32 operations (round x*log2(e),
+ * two-part ln2 reduction, degree-7 Taylor polynomial, exponent-field scaling,
+ * argument clamped to [-87, 87]), so codes and scales have one correct value.
+ *
+ *   gate_f16 [M, ldg], up_f16 [M, ldu] fp16; K = d->K columns each (the
+ *   intermediate size); ldg, ldu >= K and % 8 == 0, rows 16-byte aligned.  The
+ *   two may be the halves of one [M, 2K] matrix (up_f16 = gate_f16 + K).
+ *   other arguments, alignment and errors as atom_quantize_act
+ */
+atom_status atom_swiglu_quantize_act(const void *gate_f16, const void *up_f16,
+                                     int64_t M, int64_t ldg, int64_t ldu,
+                                     const int32_t *reorder_idx,
+                                     const atom_desc *d, float clip, void *q4,
+                                     void *q8, void *scale_f16, void *stream);
+
+/*
  * One-time weight path (Section 4.1: weights are reordered offline with the
  * activations' index; Section 5.1: clip 0.85): reorder + round-to-nearest
  * group quantisation of W[N, K] (nn.Linear layout).  No norm, no GPTQ.

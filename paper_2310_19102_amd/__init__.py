@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     atom_check_reorder_idx,
     atom_quantize_act,
     atom_add_quantize_act,
+    atom_swiglu_quantize_act,
     atom_quantize_weight,
     atom_status_string,
     atom_w4a4_gemm,

@@ -18,6 +18,7 @@ _lib = None
 EXPORTS = (
     "atom_quantize_act",
     "atom_add_quantize_act",
+    "atom_swiglu_quantize_act",
     "atom_quantize_weight",
     "atom_w4a4_gemm",
     "atom_w4a4_gemm_workspace_bytes",
@@ -58,6 +59,8 @@ def load_library():
     L.atom_quantize_act.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, vp, vp, vp]
     L.atom_add_quantize_act.restype = ctypes.c_int
     L.atom_add_quantize_act.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, f32, vp, dp, f32, vp, vp, vp, vp]
+    L.atom_swiglu_quantize_act.restype = ctypes.c_int
+    L.atom_swiglu_quantize_act.argtypes = [vp, vp, i64, i64, i64, vp, dp, f32, vp, vp, vp, vp]
     L.atom_quantize_weight.restype = ctypes.c_int
     L.atom_quantize_weight.argtypes = [vp, i64, i64, vp, dp, f32, vp, vp, vp, vp]
     L.atom_w4a4_gemm.restype = ctypes.c_int
@@ -165,6 +168,29 @@ def atom_add_quantize_act(x: torch.Tensor, residual: torch.Tensor, gamma: Option
     if st != 0:
         raise AtomError(st, "atom_add_quantize_act")
     return sum_out, q4, q8, sc
+
+
+def atom_swiglu_quantize_act(gate: torch.Tensor, up: torch.Tensor, reorder_idx: torch.Tensor,
+                             group_size: int = 128, n_outlier: int = 128, clip: float = 0.9,
+                             out: Optional[Tuple[torch.Tensor, ...]] = None):
+    """``silu(gate) * up`` (fp32, never stored) followed by reorder and group quantisation.
+    ``gate`` and ``up`` are [M, K] fp16 with a contiguous last dimension, e.g. the two halves
+    of the fused gate/up projection's output.  Returns ``(q4, q8, scale)``."""
+    L = load_library()
+    _dev(gate, torch.float16, "gate")
+    _dev(up, torch.float16, "up")
+    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if gate.dim() != 2 or gate.stride(1) != 1 or up.shape != gate.shape or up.stride(1) != 1:
+        raise ValueError("gate and up must be [M, K] with a contiguous last dimension")
+    M, K = gate.shape
+    q4, q8, sc = out if out is not None else _quant_outputs(M, K, group_size, n_outlier, gate.device)
+    d = _desc(K, group_size, n_outlier)
+    ld = lambda t: t.stride(0) if M > 1 else max(K, t.stride(0))
+    st = L.atom_swiglu_quantize_act(_ptr(gate), _ptr(up), M, ld(gate), ld(up), _ptr(reorder_idx),
+                                    ctypes.byref(d), clip, _ptr(q4), _ptr(q8), _ptr(sc), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_swiglu_quantize_act")
+    return q4, q8, sc
 
 
 def atom_quantize_weight(w: torch.Tensor, reorder_idx: torch.Tensor, group_size: int = 128,

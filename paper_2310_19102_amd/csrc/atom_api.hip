@@ -29,25 +29,29 @@ atom_status check_desc(const atom_desc *d)
     return ATOM_OK;
 }
 
-atom_status quantize_common(const void *x, int64_t rows, int64_t ld, const void *res, int64_t ldr,
-                            void *sum_out, int64_t ldo, const void *gamma, float eps,
+atom_status quantize_common(const void *x, int64_t rows, int64_t ld, int pre, const void *res,
+                            int64_t ldr, void *sum_out, int64_t ldo, const void *gamma, float eps,
                             const int32_t *idx, const atom_desc *d, float clip, void *q4,
                             void *q8, void *scale, void *stream)
 {
     atom_status st = check_desc(d);
     if (st != ATOM_OK) return st;
     if (rows < 0 || ld < d->K) return ATOM_ERR_SHAPE;
-    if (res && (ldr < d->K || ldo < d->K)) return ATOM_ERR_SHAPE;
+    if (pre != 0 && ldr < d->K) return ATOM_ERR_SHAPE;
+    if (pre == 1 && ldo < d->K) return ATOM_ERR_SHAPE;
     if (rows == 0) return ATOM_OK;
     if (!x || !idx || !q4 || !q8 || !scale) return ATOM_ERR_NULL;
+    if (pre != 0 && !res) return ATOM_ERR_NULL;
+    if (pre == 1 && !sum_out) return ATOM_ERR_NULL;
     if (!aligned(x, 16) || (ld % 8) || !aligned(idx, 16) || !aligned(q4, 16) || !aligned(q8, 16) ||
         !aligned(scale, 2) || (gamma && !aligned(gamma, 16)))
         return ATOM_ERR_ALIGN;
-    if (res && (!aligned(res, 16) || (ldr % 8) || !aligned(sum_out, 16) || (ldo % 8)))
-        return ATOM_ERR_ALIGN;
-    hipError_t err = atom_internal::launch_quantize_rows(x, rows, ld, res, ldr, sum_out, ldo, gamma,
-                                                         eps, idx, d->K, d->n_outlier, clip, q4, q8,
-                                                         scale, static_cast<hipStream_t>(stream));
+    if (pre != 0 && (!aligned(res, 16) || (ldr % 8))) return ATOM_ERR_ALIGN;
+    if (pre == 1 && (!aligned(sum_out, 16) || (ldo % 8))) return ATOM_ERR_ALIGN;
+    hipError_t err = atom_internal::launch_quantize_rows(x, rows, ld, pre, res, ldr, sum_out, ldo,
+                                                         gamma, eps, idx, d->K, d->n_outlier, clip,
+                                                         q4, q8, scale,
+                                                         static_cast<hipStream_t>(stream));
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
@@ -59,7 +63,7 @@ atom_status atom_quantize_act(const void *x_f16, int64_t M, int64_t ldx, const v
                               float eps, const int32_t *reorder_idx, const atom_desc *d,
                               float clip, void *q4, void *q8, void *scale_f16, void *stream)
 {
-    return quantize_common(x_f16, M, ldx, nullptr, 0, nullptr, 0, gamma_f16, eps, reorder_idx, d, clip, q4, q8, scale_f16,
+    return quantize_common(x_f16, M, ldx, 0, nullptr, 0, nullptr, 0, gamma_f16, eps, reorder_idx, d, clip, q4, q8, scale_f16,
                            stream);
 }
 
@@ -69,11 +73,16 @@ atom_status atom_add_quantize_act(const void *x_f16, const void *residual_f16, i
                                   const atom_desc *d, float clip, void *q4, void *q8,
                                   void *scale_f16, void *stream)
 {
-    if (M > 0 && (!residual_f16 || !sum_out_f16)) return ATOM_ERR_NULL;
-    // a null residual pointer would select the plain front end: keep an empty call valid
-    static const char dummy = 0;
-    const void *res = residual_f16 ? residual_f16 : &dummy;
-    return quantize_common(x_f16, M, ldx, res, ldr, sum_out_f16, ldo, gamma_f16, eps, reorder_idx,
+    return quantize_common(x_f16, M, ldx, 1, residual_f16, ldr, sum_out_f16, ldo, gamma_f16, eps,
+                           reorder_idx, d, clip, q4, q8, scale_f16, stream);
+}
+
+atom_status atom_swiglu_quantize_act(const void *gate_f16, const void *up_f16, int64_t M,
+                                     int64_t ldg, int64_t ldu, const int32_t *reorder_idx,
+                                     const atom_desc *d, float clip, void *q4, void *q8,
+                                     void *scale_f16, void *stream)
+{
+    return quantize_common(gate_f16, M, ldg, 2, up_f16, ldu, nullptr, 0, nullptr, 0.0f, reorder_idx,
                            d, clip, q4, q8, scale_f16, stream);
 }
 
@@ -81,7 +90,7 @@ atom_status atom_quantize_weight(const void *w_f16, int64_t N, int64_t ldw,
                                  const int32_t *reorder_idx, const atom_desc *d, float clip,
                                  void *q4, void *q8, void *scale_f16, void *stream)
 {
-    return quantize_common(w_f16, N, ldw, nullptr, 0, nullptr, 0, nullptr, 0.0f, reorder_idx, d, clip, q4, q8, scale_f16,
+    return quantize_common(w_f16, N, ldw, 0, nullptr, 0, nullptr, 0, nullptr, 0.0f, reorder_idx, d, clip, q4, q8, scale_f16,
                            stream);
 }
 

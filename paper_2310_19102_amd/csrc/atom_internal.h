@@ -14,8 +14,9 @@ constexpr int kMaxK     = 32768;   // a staged fp32 row must fit the 160 KB LDS
 size_t quantize_lds_bytes(int K, bool norm);
 
 // One row per workgroup: optional RMSNorm, reorder gather, group quantisation.
-// res != nullptr: x is first added to the residual rows and the fp16 sum written to sum_out.
-hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, const void *res,
+// pre: 0 = the rows of x as they are; 1 = x + res rounded to fp16, written to sum_out;
+// 2 = silu(x) * res in fp32 (x = gate rows, res = up rows; no norm).
+hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, int pre, const void *res,
                                 int64_t ldr, void *sum_out, int64_t ldo, const void *gamma,
                                 float eps, const int32_t *idx, int K, int O, float clip,
                                 void *q4, void *q8, void *scale, hipStream_t stream);

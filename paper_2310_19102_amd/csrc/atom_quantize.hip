@@ -59,6 +59,40 @@ __device__ __forceinline__ uint4 add_halves(const uint4 &a, const uint4 &b)
     return out;
 }
 
+// exp(x) on [-87, 87] from IEEE operations only (one value on every machine, the CPU
+// oracle's included): n = round(x*log2(e)); r = x - n*ln2 with ln2 split in two, the first
+// part short enough for n*ln2_hi to be exact; e^r by its Taylor polynomial of degree 7 in
+// Horner form; 2^n through the exponent field.
+__device__ __forceinline__ float exp_ieee(float x)
+{
+    x = x < -87.0f ? -87.0f : x;
+    x = x > 87.0f ? 87.0f : x;
+    const float n = rintf(x * 1.44269502162933349609375f);
+    float r = fmaf(n, -0.693145751953125f, x);
+    r = fmaf(n, -1.428606765330187045037746429443359375e-06f, r);
+    float p = 1.0f / 5040.0f;
+    p = fmaf(p, r, 1.0f / 720.0f);
+    p = fmaf(p, r, 1.0f / 120.0f);
+    p = fmaf(p, r, 1.0f / 24.0f);
+    p = fmaf(p, r, 1.0f / 6.0f);
+    p = fmaf(p, r, 0.5f);
+    p = fmaf(p, r, 1.0f);
+    p = fmaf(p, r, 1.0f);
+    return p * __int_as_float(((int)n + 127) << 23);
+}
+
+// silu(g) * u in fp32: sigma = 1/(1 + exp(-g)) with an IEEE division, then (g*sigma)*u
+__device__ __forceinline__ float silu_mul(float g, float u)
+{
+    const float sigma = 1.0f / (1.0f + exp_ieee(-g));
+    return (g * sigma) * u;
+}
+
+// what happens to a row before it is normalised and quantised
+constexpr int kPlain = 0;    // nothing
+constexpr int kAdd = 1;      // x + res, rounded to fp16 and written to sum_out
+constexpr int kSwiglu = 2;   // silu(x) * res in fp32 (x = gate row, res = up row), not stored
+
 // max over the 16 lanes of a DPP row (xor butterfly; max is exact in any order)
 __device__ __forceinline__ float row16_max(float v)
 {
@@ -67,9 +101,10 @@ __device__ __forceinline__ float row16_max(float v)
     return v;
 }
 
-// ADD: x is first added to a residual row and the sum (fp16) is written out; x, res and
-// sum_out may alias each other (every element is read and written by the same thread).
-template <bool NORM, bool ADD>
+// PRE = kAdd: x is first added to a residual row and the sum (fp16) is written out; x, res
+// and sum_out may alias each other (every element is read and written by the same thread).
+// PRE = kSwiglu: the row is silu(x) * res.
+template <bool NORM, int PRE>
 __global__ __launch_bounds__(kThreads)
 void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
                           const __half *res, int64_t ldr, __half *sum_out, int64_t ldo,
@@ -96,12 +131,18 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
         // ---- 1. stage the row ------------------------------------------------
         for (int v = tid; v < V; v += kThreads) {
             uint4 raw = *reinterpret_cast<const uint4 *>(xr + 8 * v);
-            if (ADD) {
+            if (PRE == kAdd) {
                 raw = add_halves(raw, *reinterpret_cast<const uint4 *>(res + row * ldr + 8 * v));
                 *reinterpret_cast<uint4 *>(sum_out + row * ldo + 8 * v) = raw;
             }
             float f[8];
             halves_to_floats(raw, f);
+            if (PRE == kSwiglu) {
+                float u[8];
+                halves_to_floats(*reinterpret_cast<const uint4 *>(res + row * ldr + 8 * v), u);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] = silu_mul(f[e], u[e]);
+            }
             *reinterpret_cast<float4 *>(ybuf + 8 * v)     = make_float4(f[0], f[1], f[2], f[3]);
             *reinterpret_cast<float4 *>(ybuf + 8 * v + 4) = make_float4(f[4], f[5], f[6], f[7]);
             if (NORM) {
@@ -222,7 +263,7 @@ __device__ __forceinline__ float row16_max_dpp(float v)
 //     |y| / s <= (2^n - 1)/(2 clip) * (1 + 2^-11) and s >= 2^-24; quotients below 2^-100
 //     round to code 0 either way.  A zero scale (all-zero group) yields zero codes;
 //   * the group maximum is a DPP rotation reduction.
-template <bool NORM, int NS, int NT, bool ADD>
+template <bool NORM, int NS, int NT, int PRE>
 __global__ __launch_bounds__(NT)
 void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
                                const __half *res, int64_t ldr, __half *sum_out, int64_t ldo,
@@ -266,14 +307,14 @@ void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
     }
 
     uint4 raw[NS];
-    uint4 rres[ADD ? NS : 1];
+    uint4 rres[PRE != kPlain ? NS : 1];
     auto fetch_row = [&](int64_t row) {
         const __half *xr = x + row * ld;
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
             const int v = tid + NT * i;
             raw[i] = v < V ? *reinterpret_cast<const uint4 *>(xr + 8 * v) : make_uint4(0, 0, 0, 0);
-            if (ADD)
+            if (PRE != kPlain)
                 rres[i] = v < V ? *reinterpret_cast<const uint4 *>(res + row * ldr + 8 * v)
                                 : make_uint4(0, 0, 0, 0);
         }
@@ -283,7 +324,7 @@ void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
 
     for (; row < rows; row += gridDim.x) {
         // ---- 0. residual add; the sum is the new residual stream and the row quantised below
-        if (ADD) {
+        if (PRE == kAdd) {
 #pragma unroll
             for (int i = 0; i < NS; ++i) {
                 const int v = tid + NT * i;
@@ -321,6 +362,12 @@ void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
             if (v < V) {
                 float f[8];
                 halves_to_floats(raw[i], f);
+                if (PRE == kSwiglu) {
+                    float u[8];
+                    halves_to_floats(rres[i], u);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) f[e] = silu_mul(f[e], u[e]);
+                }
                 if (NORM) {
                     float g[8];
                     halves_to_floats(graw[i], g);
@@ -409,15 +456,16 @@ size_t quantize_lds_bytes(int K, bool norm)
 
 struct QuantArgs {
     const void *x; int64_t rows, ld;
-    const void *res; int64_t ldr; void *sum_out; int64_t ldo;     // res == nullptr: no residual add
+    int pre;                                                       // kPlain, kAdd or kSwiglu
+    const void *res; int64_t ldr; void *sum_out; int64_t ldo;     // second input row / fp16 sum out
     const void *gamma; float eps; const int32_t *idx; int K, O; float clip;
     void *q4, *q8, *scale;
 };
 
-template <bool NORM, int NS, int NT, bool ADD>
+template <bool NORM, int NS, int NT, int PRE>
 hipError_t launch_fast(const QuantArgs &a, size_t lds, hipStream_t stream)
 {
-    auto kern = &quantize_rows_fast_kernel<NORM, NS, NT, ADD>;
+    auto kern = &quantize_rows_fast_kernel<NORM, NS, NT, PRE>;
     static size_t allowed = 0;        // the opt-in for more than 64 KB of dynamic LDS
     if (lds > allowed) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -448,10 +496,10 @@ hipError_t launch_fast(const QuantArgs &a, size_t lds, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <bool NORM, bool ADD>
+template <bool NORM, int PRE>
 hipError_t launch_plain(const QuantArgs &a, size_t lds, hipStream_t stream)
 {
-    auto kern = &quantize_rows_kernel<NORM, ADD>;
+    auto kern = &quantize_rows_kernel<NORM, PRE>;
     const int grid = (int)(a.rows < (int64_t)1 << 20 ? a.rows : (int64_t)1 << 20);
     // the opt-in for more than 64 KB of dynamic LDS is raised only when a call needs more
     static size_t allowed = 0;
@@ -468,32 +516,34 @@ hipError_t launch_plain(const QuantArgs &a, size_t lds, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <bool NORM, bool ADD>
+template <bool NORM, int PRE>
 hipError_t dispatch_quantize(const QuantArgs &a, hipStream_t stream)
 {
     const size_t lds = quantize_lds_bytes(a.K, NORM);
     // The fast kernel keeps ceil(K / (8 * threads)) gather-offset sets in registers and
     // relies on a sane clip; rows of 8192 channels and more are spread over 512 threads.
     if (a.K <= 16384 && a.clip >= 9.5367431640625e-07f && a.clip <= 1.0f) {
-        if (a.K <= 2048)  return launch_fast<NORM, 1, 256, ADD>(a, lds, stream);
-        if (a.K <= 4096)  return launch_fast<NORM, 2, 256, ADD>(a, lds, stream);
-        if (a.K < 8192)   return launch_fast<NORM, 4, 256, ADD>(a, lds, stream);
-        if (a.K <= 8192)  return launch_fast<NORM, 2, 512, ADD>(a, lds, stream);
-        if (a.K <= 12288) return launch_fast<NORM, 3, 512, ADD>(a, lds, stream);
-        return launch_fast<NORM, 4, 512, ADD>(a, lds, stream);
+        if (a.K <= 2048)  return launch_fast<NORM, 1, 256, PRE>(a, lds, stream);
+        if (a.K <= 4096)  return launch_fast<NORM, 2, 256, PRE>(a, lds, stream);
+        if (a.K < 8192)   return launch_fast<NORM, 4, 256, PRE>(a, lds, stream);
+        if (a.K <= 8192)  return launch_fast<NORM, 2, 512, PRE>(a, lds, stream);
+        if (a.K <= 12288) return launch_fast<NORM, 3, 512, PRE>(a, lds, stream);
+        return launch_fast<NORM, 4, 512, PRE>(a, lds, stream);
     }
-    return launch_plain<NORM, ADD>(a, lds, stream);
+    return launch_plain<NORM, PRE>(a, lds, stream);
 }
 
-hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, const void *res,
+hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, int pre, const void *res,
                                 int64_t ldr, void *sum_out, int64_t ldo, const void *gamma,
                                 float eps, const int32_t *idx, int K, int O, float clip,
                                 void *q4, void *q8, void *scale, hipStream_t stream)
 {
-    const QuantArgs a = {x, rows, ld, res, ldr, sum_out, ldo, gamma, eps, idx, K, O, clip, q4, q8, scale};
-    const bool norm = gamma != nullptr, add = res != nullptr;
-    if (norm) return add ? dispatch_quantize<true, true>(a, stream) : dispatch_quantize<true, false>(a, stream);
-    return add ? dispatch_quantize<false, true>(a, stream) : dispatch_quantize<false, false>(a, stream);
+    const QuantArgs a = {x, rows, ld, pre, res, ldr, sum_out, ldo, gamma, eps, idx, K, O, clip, q4, q8, scale};
+    const bool norm = gamma != nullptr;
+    if (pre == kSwiglu) return dispatch_quantize<false, kSwiglu>(a, stream);   // no norm behind an activation
+    if (pre == kAdd)
+        return norm ? dispatch_quantize<true, kAdd>(a, stream) : dispatch_quantize<false, kAdd>(a, stream);
+    return norm ? dispatch_quantize<true, kPlain>(a, stream) : dispatch_quantize<false, kPlain>(a, stream);
 }
 
 }  // namespace atom_internal

@@ -170,6 +170,49 @@ def test_add_quantize_act_strided_and_errors():
     assert err.value.status == 4
 
 
+@pytest.mark.parametrize("M,K,O,clip", [
+    (7, 512, 128, 0.9),
+    (33, 11008, 128, 0.9),           # the Llama-7B intermediate size, 512 threads per row
+    (3000, 256, 128, 1.0),           # several rows per workgroup
+    (4, 20480, 256, 0.9),            # K > 16384: the plain kernel
+    (5, 1024, 128, 1e-8),            # clip below 2^-20: the plain kernel
+])
+def test_swiglu_quantize_act(M, K, O, clip):
+    """silu(gate)*up fused in front of the front end; gate and up are the two halves of one
+    [M, 2K] matrix, as the fused gate/up projection leaves them.  Codes and scales are
+    bit-exact against the oracle, whose exp is the same fixed sequence of IEEE operations."""
+    g = torch.Generator().manual_seed(M * 13 + K)
+    sigma = torch.exp(1.0 * torch.randn(K, generator=g))
+    gu = torch.empty((M, 2 * K), dtype=torch.float16)
+    gu[:, :K] = (3.0 * torch.randn((M, K), generator=g)).to(torch.float16)
+    gu[:, K:] = (torch.randn((M, K), generator=g) * sigma).to(torch.float16)
+    # gates that exercise the clamp, sigma == 1, zero, and the largest fp16 values
+    gu[0, :8] = torch.tensor([-65504.0, -100.0, -87.5, -20.0, 0.0, 20.0, 100.0, 65504.0]).to(torch.float16)
+    gu[0, K:K + 8] = torch.tensor([1.0, -2.0, 3.0, 0.5, 7.0, 1.0, -0.25, 0.001]).to(torch.float16)
+    idx = torch.argsort(sigma, stable=True).to(torch.int32)
+    print(f"[case] swiglu+quantize M={M} K={K} O={O} clip={clip}", flush=True)
+    want = oracle.swiglu_quantize_act(gu[:, :K].numpy(), gu[:, K:].numpy(), idx.numpy(), 128, O, clip)
+    gud = gu.cuda()
+    got = atom.atom_swiglu_quantize_act(gud[:, :K], gud[:, K:], dev(idx), 128, O, clip)
+    torch.cuda.synchronize()
+    assert_quant_equal(got, want, "swiglu+quantize")
+    assert np.array_equal(npy(gud).view(np.uint16), gu.numpy().view(np.uint16)), "inputs were modified"
+
+
+def test_swiglu_quantize_act_errors():
+    K = 512
+    gate = torch.zeros((4, K), dtype=torch.float16).cuda()
+    idx = torch.arange(K, dtype=torch.int32).cuda()
+    e = atom.atom_swiglu_quantize_act(gate[:0], gate[:0], idx)
+    assert e[0].shape[0] == 0
+    odd = torch.zeros((4, K + 4), dtype=torch.float16).cuda()[:, :K]      # row stride not a multiple of 8
+    with pytest.raises(atom.AtomError) as err:
+        atom.atom_swiglu_quantize_act(gate, odd, idx)
+    assert err.value.status == 4
+    with pytest.raises(ValueError):
+        atom.atom_swiglu_quantize_act(gate, gate[:, :256], idx)
+
+
 def test_strided_input_rows():
     lin = _rand_linear(16, 512, 64, 128, seed=7)
     big = torch.zeros((16, 1024), dtype=torch.float16)
