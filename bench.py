@@ -216,7 +216,64 @@ def extra_measurements():
         out.append(entry)
         del x, res, hsum, qa
         torch.cuda.empty_cache()
+    out.append(mlp_block_chain())
     return out
+
+
+def graph_time(fn, launches=20, replays=5):
+    """Seconds per call of fn() inside a HIP graph of `launches` calls."""
+    fn()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(launches):
+            fn()
+    graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    del graph
+    return e0.elapsed_time(e1) * 1e-3 / (launches * replays)
+
+
+def mlp_block_chain():
+    """The Llama-7B MLP block as one dependent chain on the 4-bit path, every quantisation
+    fused into the operator before it: residual add + RMSNorm + quantise -> gate/up GEMM ->
+    silu(gate)*up + quantise -> down GEMM (M = 1024; shapes of config 4, the down
+    projection fed by the real gate/up output instead of an independent tensor)."""
+    up_lin, down_lin = synth.make(4, 0), synth.make(4, 1)
+    M, K, I = up_lin.M, up_lin.K, down_lin.K
+    x, gamma, idx1 = up_lin.x.cuda(), up_lin.gamma.cuda(), up_lin.idx.cuda()
+    res = (0.5 * up_lin.x).cuda()
+    idx2 = down_lin.idx.cuda()
+    w1 = atom.atom_quantize_weight(up_lin.w.cuda(), idx1, up_lin.group_size, up_lin.n_outlier, up_lin.clip_weight)
+    w2 = atom.atom_quantize_weight(down_lin.w.cuda(), idx2, down_lin.group_size, down_lin.n_outlier,
+                                   down_lin.clip_weight)
+    qa1 = atom.atom_quantize_act(x, gamma, up_lin.eps, idx1)
+    y1 = torch.empty((M, 2 * I), dtype=torch.float16, device="cuda")
+    qa2 = atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], idx2)
+    y2 = torch.empty((M, K), dtype=torch.float16, device="cuda")
+    hsum = torch.empty_like(x)
+
+    def chain():
+        atom.atom_add_quantize_act(x, res, gamma, up_lin.eps, idx1, sum_out=hsum, out=qa1)
+        atom.atom_w4a4_gemm(*qa1, *w1, out=y1)
+        atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], idx2, out=qa2)
+        atom.atom_w4a4_gemm(*qa2, *w2, out=y2)
+
+    t = graph_time(chain)
+    t_swiglu = graph_time(lambda: atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], idx2, out=qa2), 50, 4)
+    ops = 2 * M * (2 * I) * K + 2 * M * K * I
+    codes = (I - down_lin.n_outlier) // 2 + down_lin.n_outlier + 2 * (I // down_lin.group_size)
+    sw_bytes = M * (2 * 2 * I + codes)
+    return {"workload": "Llama-7B MLP block chain M=1024 (add+RMSNorm+quant -> gate/up -> swiglu+quant -> down), HIP graph",
+            "us_per_block": t * 1e6, "effective_tops": ops / t / 1e12,
+            "swiglu_front_end_us": t_swiglu * 1e6, "swiglu_front_end_bytes": sw_bytes,
+            "swiglu_front_end_hbm_frac": sw_bytes / t_swiglu / 1e9 / PEAK_HBM_GBS}
 
 
 def measured_traffic(config):
