@@ -60,6 +60,13 @@ def _load():
     L.atom_ref_silu_mul.argtypes = [ctypes.c_uint16, ctypes.c_uint16]
     L.atom_ref_swiglu_quantize_act.restype = ctypes.c_int
     L.atom_ref_swiglu_quantize_act.argtypes = [vp, vp, i64, i64, i64, vp, i32, i32, i32, f32, vp, vp, vp]
+    L.atom_ref_kv_quantize.restype = ctypes.c_int
+    L.atom_ref_kv_quantize.argtypes = [vp, i64, i64, i32, f32, vp, vp, vp]
+    L.atom_ref_kv_dequant.restype = f32
+    L.atom_ref_kv_dequant.argtypes = [ctypes.c_uint8, ctypes.c_uint16, ctypes.c_int16]
+    L.atom_ref_decode_attention_kv4.restype = ctypes.c_int
+    L.atom_ref_decode_attention_kv4.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
+                                                vp, f32, vp]
     L.atom_ref_quantize_weight.restype = ctypes.c_int
     L.atom_ref_quantize_weight.argtypes = [vp, i64, i64, vp, i32, i32, i32, f32, vp, vp, vp]
     L.atom_ref_w4a4_gemm.restype = ctypes.c_int
@@ -209,4 +216,49 @@ def w4a4_gemm(a_q4, a_q8, a_scale, w_q4, w_q8, w_scale, group_size=128,
         out["partials"] = part
     if want_acc:
         out["acc"] = acc
+    return out
+
+
+def kv_quantize(x, clip=1.0):
+    """Asymmetric INT4 quantisation of rows of head_dim values: x float16 [..., D].
+    Returns (codes uint8 [..., D/2], scale float16 [...], zero int16 [...])."""
+    x = _c(x, np.float16)
+    D = x.shape[-1]
+    lead = x.shape[:-1]
+    x2 = x.reshape(-1, D)
+    R = x2.shape[0]
+    q = np.zeros((R, D // 2), np.uint8)
+    sc = np.zeros(R, np.float16)
+    z = np.zeros(R, np.int16)
+    rc = _load().atom_ref_kv_quantize(_p(x2), R, D, D, clip, _p(q), _p(sc), _p(z))
+    if rc != 0:
+        raise ValueError("atom_ref_kv_quantize: bad shapes")
+    return q.reshape(lead + (D // 2,)), sc.reshape(lead), z.reshape(lead)
+
+
+def kv_dequant(q, scale, zero):
+    """float32 [..., D] from codes [..., D/2], scale [...], zero [...]."""
+    q = _c(q, np.uint8)
+    lo = (q & 0xF).astype(np.int32)
+    hi = (q >> 4).astype(np.int32)
+    codes = np.stack([lo, hi], axis=-1).reshape(q.shape[:-1] + (2 * q.shape[-1],))
+    zz = np.asarray(zero, np.int32)[..., None]
+    return (codes - zz).astype(np.float32) * np.asarray(scale, np.float16).astype(np.float32)[..., None]
+
+
+def decode_attention_kv4(q, kq, ks, kz, vq, vs, vz, seq_len, sm_scale):
+    """q float16 [B,H,D]; caches [B,Hkv,Tmax,...]; seq_len int32 [B].  Returns float16 [B,H,D]."""
+    q = _c(q, np.float16)
+    B, H, D = q.shape
+    kq, vq = _c(kq, np.uint8), _c(vq, np.uint8)
+    ks, vs = _c(ks, np.float16), _c(vs, np.float16)
+    kz, vz = _c(kz, np.int16), _c(vz, np.int16)
+    Hkv, Tmax = kq.shape[1], kq.shape[2]
+    seq_len = _c(seq_len, np.int32)
+    out = np.zeros((B, H, D), np.float16)
+    rc = _load().atom_ref_decode_attention_kv4(_p(q), B, H, Hkv, D, Tmax, _p(seq_len), _p(kq),
+                                               _p(ks), _p(kz), _p(vq), _p(vs), _p(vz), sm_scale,
+                                               _p(out))
+    if rc != 0:
+        raise ValueError("atom_ref_decode_attention_kv4: bad shapes")
     return out

@@ -336,3 +336,108 @@ int atom_ref_w4a4_gemm(const uint8_t *a_q4, const int8_t *a_q8,
     free(w);
     return 0;
 }
+
+/* ------------------------------------------------------------- KV cache -- */
+
+int atom_ref_kv_quantize(const uint16_t *x, int64_t R, int64_t ldx, int32_t D,
+                         float clip, uint8_t *q, uint16_t *scale, int16_t *zero)
+{
+    if (D <= 0 || D % 2 || ldx < D || R < 0) return -1;
+    for (int64_t r = 0; r < R; ++r) {
+        const uint16_t *row = x + r * ldx;
+        float mx = atom_ref_f16_to_f32(row[0]), mn = mx;
+        for (int32_t d = 1; d < D; ++d) {
+            float v = atom_ref_f16_to_f32(row[d]);
+            if (v > mx) mx = v;
+            if (v < mn) mn = v;
+        }
+        float    s32 = ((mx - mn) * clip) / 15.0f;
+        uint16_t sh  = scale_to_f16(s32);
+        float    s   = atom_ref_f16_to_f32(sh);
+        int32_t  z   = 0;
+        if (s != 0.0f) {
+            float zf = nearbyintf(-mn / s);
+            if (zf < -32768.0f) zf = -32768.0f;
+            if (zf > 32767.0f) zf = 32767.0f;
+            z = (int32_t)zf;
+        }
+        scale[r] = sh;
+        zero[r]  = (int16_t)z;
+        for (int32_t d = 0; d < D; d += 2) {
+            int c[2];
+            for (int k = 0; k < 2; ++k) {
+                int code = 0;
+                if (s != 0.0f) {
+                    /* round(x/s) is an integer below 2^24 in magnitude whenever it
+                     * matters; clamp it first so that the integer sum cannot overflow */
+                    float t = nearbyintf(atom_ref_f16_to_f32(row[d + k]) / s);
+                    if (t < -100000.0f) t = -100000.0f;
+                    if (t > 100000.0f) t = 100000.0f;
+                    code = (int)t + z;
+                    if (code < 0) code = 0;
+                    if (code > 15) code = 15;
+                }
+                c[k] = code;
+            }
+            q[r * (D / 2) + d / 2] = (uint8_t)(c[0] | (c[1] << 4));
+        }
+    }
+    return 0;
+}
+
+float atom_ref_kv_dequant(uint8_t code, uint16_t scale_f16, int16_t zero)
+{
+    return (float)((int)code - (int)zero) * atom_ref_f16_to_f32(scale_f16);
+}
+
+int atom_ref_decode_attention_kv4(const uint16_t *q, int32_t B, int32_t H,
+                                  int32_t Hkv, int32_t D, int32_t Tmax,
+                                  const int32_t *seq_len, const uint8_t *kq,
+                                  const uint16_t *ks, const int16_t *kz,
+                                  const uint8_t *vq, const uint16_t *vs,
+                                  const int16_t *vz, float sm_scale,
+                                  uint16_t *out)
+{
+    if (B < 0 || H <= 0 || Hkv <= 0 || H % Hkv || D <= 0 || D % 2 || Tmax < 0) return -1;
+    double *score = (double *)malloc(sizeof(double) * (size_t)(Tmax > 0 ? Tmax : 1));
+    double *acc   = (double *)malloc(sizeof(double) * (size_t)D);
+    if (!score || !acc) { free(score); free(acc); return -1; }
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t T = seq_len[b];
+        if (T < 0 || T > Tmax) { free(score); free(acc); return -1; }
+        for (int32_t h = 0; h < H; ++h) {
+            const int32_t   kvh  = h / (H / Hkv);
+            const int64_t   base = ((int64_t)b * Hkv + kvh) * Tmax;
+            const uint16_t *qv   = q + ((int64_t)b * H + h) * D;
+            uint16_t       *o    = out + ((int64_t)b * H + h) * D;
+            double m = 0.0;
+            for (int32_t t = 0; t < T; ++t) {
+                double dot = 0.0;
+                for (int32_t d = 0; d < D; ++d) {
+                    uint8_t byte = kq[(base + t) * (D / 2) + d / 2];
+                    uint8_t code = (d % 2 == 0) ? (byte & 0xf) : (byte >> 4);
+                    dot += (double)atom_ref_f16_to_f32(qv[d]) *
+                           (double)atom_ref_kv_dequant(code, ks[base + t], kz[base + t]);
+                }
+                score[t] = dot * (double)sm_scale;
+                if (t == 0 || score[t] > m) m = score[t];
+            }
+            double l = 0.0;
+            for (int32_t d = 0; d < D; ++d) acc[d] = 0.0;
+            for (int32_t t = 0; t < T; ++t) {
+                double p = exp(score[t] - m);
+                l += p;
+                for (int32_t d = 0; d < D; ++d) {
+                    uint8_t byte = vq[(base + t) * (D / 2) + d / 2];
+                    uint8_t code = (d % 2 == 0) ? (byte & 0xf) : (byte >> 4);
+                    acc[d] += p * (double)atom_ref_kv_dequant(code, vs[base + t], vz[base + t]);
+                }
+            }
+            for (int32_t d = 0; d < D; ++d)
+                o[d] = atom_ref_f32_to_f16(T > 0 ? (float)(acc[d] / l) : 0.0f);
+        }
+    }
+    free(score);
+    free(acc);
+    return 0;
+}

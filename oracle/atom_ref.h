@@ -115,6 +115,37 @@ int atom_ref_w4a4_gemm(const uint8_t *a_q4, const int8_t *a_q8,
                        uint16_t *y_f16, int64_t ldy,
                        int32_t *partials, float *acc_f32);
 
+/* ---- INT4 KV cache (Section 4.4; asymmetric equations of Section 2) ---------
+ * One row = the D values of one token of one attention head (the paper's
+ * granularity), n = 4 bits:
+ *   s = fp16(((max - min) * clip) / 15)  (stored, saturated at 65504),
+ *   z = clamp(round(-min / s), -32768, 32767)  (stored, int16),
+ *   code = clamp(round(x / s) + z, 0, 15), round = half to even, IEEE fp32
+ *   division by the STORED scale; s == 0 (constant row) gives z = 0, codes 0.
+ * Codes are packed two per byte, even d in the low nibble.
+ * Dequantisation: (code - z) * s in fp32. */
+int atom_ref_kv_quantize(const uint16_t *x_f16, int64_t R, int64_t ldx, int32_t D,
+                         float clip, uint8_t *q /* [R, D/2] */,
+                         uint16_t *scale_f16 /* [R] */, int16_t *zero /* [R] */);
+float atom_ref_kv_dequant(uint8_t code, uint16_t scale_f16, int16_t zero);
+
+/* Decode-stage attention over the INT4 cache (Sections 4.4 and 4.5: the cache is
+ * loaded in low precision and dequantised inside the attention operator).
+ *   q        [B, H, D] fp16, one query token per sequence
+ *   kq, vq   [B, Hkv, Tmax, D/2] codes; ks, vs [B, Hkv, Tmax] fp16 scales;
+ *            kz, vz [B, Hkv, Tmax] int16 zero points; query head h reads
+ *            cache head h / (H / Hkv)
+ *   seq_len  [B] tokens in the cache of each sequence (<= Tmax)
+ *   out[b,h,:] = fp16( sum_t softmax_t(sm_scale * q . k_t) * v_t ), all sums in
+ *   double; an empty cache gives zeros. */
+int atom_ref_decode_attention_kv4(const uint16_t *q_f16, int32_t B, int32_t H,
+                                  int32_t Hkv, int32_t D, int32_t Tmax,
+                                  const int32_t *seq_len, const uint8_t *kq,
+                                  const uint16_t *ks, const int16_t *kz,
+                                  const uint8_t *vq, const uint16_t *vs,
+                                  const int16_t *vz, float sm_scale,
+                                  uint16_t *out_f16);
+
 #ifdef __cplusplus
 }
 #endif
