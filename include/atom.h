@@ -163,6 +163,66 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8,
 size_t atom_w4a4_gemm_workspace_bytes(int64_t M, int64_t N,
                                       const atom_desc *d);
 
+/*
+ * KV-cache quantisation (Section 2, asymmetric uniform quantisation; Section
+ * 4.4: one scale and zero point per attention head, 4 bits; Section 4.5: fused
+ * into the operator that produces K and V, here a kernel of its own that the
+ * producer's epilogue calls on its output rows).  Row r holds the D values of
+ * one head of one token:
+ *   s    = fp16( ((max - min) * clip) / 15 )   IEEE fp32, round to nearest even,
+ *                                              saturated at 65504
+ *   z    = rne(-min / s) clamped to int16       (IEEE fp32 division by the stored s)
+ *   code = clamp(rne(x / s) + z, 0, 15)         dequantised value (code - z) * s
+ * A row with s == 0 (constant row, or a range below fp16's smallest value)
+ * stores codes 0 and z = 0.  Results are bit-exact.
+ *
+ *   x_f16     [R, ldx] fp16, device; ldx >= D, ldx % 8 == 0, 16-byte aligned
+ *   D         64 or 128
+ *   clip      the clipping factor c of Section 4.2 applied to the range (1 = none)
+ *   pos       NULL: row r is written to row r of the outputs (prefill: a whole
+ *             cache at once).  Otherwise device int32 [R / rows_per_seq]: row r
+ *             is written to row r * Tmax + pos[r / rows_per_seq] (decode: the new
+ *             token of every sequence, rows ordered (sequence, head), appended
+ *             in place to a cache laid out [B, Hkv, Tmax]; rows_per_seq = Hkv).
+ *             A position outside [0, Tmax) writes nothing.
+ *   q         [rows, D/2] bytes, two codes per byte, even d in the low nibble;
+ *             4-byte aligned.  scale_f16 [rows] fp16, zero_i16 [rows] int16.
+ * Errors: ATOM_ERR_NULL, ATOM_ERR_SHAPE (R < 0, ldx < D, with pos:
+ * rows_per_seq <= 0, R % rows_per_seq != 0 or Tmax <= 0), ATOM_ERR_UNSUPPORTED
+ * (D), ATOM_ERR_ALIGN.  R == 0 returns ATOM_OK without a launch.
+ */
+atom_status atom_kv_quantize(const void *x_f16, int64_t R, int64_t ldx,
+                             int32_t D, float clip, const int32_t *pos,
+                             int32_t rows_per_seq, int64_t Tmax, void *q,
+                             void *scale_f16, void *zero_i16, void *stream);
+
+/*
+ * Decode-stage self-attention of one new token per sequence over the INT4 KV
+ * cache (Section 4.4: the cache is loaded in 4 bits and dequantised inside the
+ * attention operator, whose arithmetic stays in floating point; Section 4.5):
+ *   K[t, :] = (k_codes[t, :] - k_zero[t]) * k_scale[t], V likewise
+ *   out[b, h, :] = softmax_t( sm_scale * q[b, h, :] . K[b, kv(h), t, :] ) V[b, kv(h)]
+ * over t < seq_len[b]; kv(h) = h / (H / Hkv) (grouped-query attention when
+ * Hkv < H).  fp32 arithmetic, fp16 output; seq_len[b] == 0 gives zeros.
+ *
+ *   q_f16    [B, H, D] fp16, device, 16-byte aligned; D = 128
+ *   seq_len  device int32 [B]; values are clamped to [0, Tmax] by the kernel
+ *   k_codes, v_codes [B, Hkv, Tmax, D/2] bytes (16-byte aligned);
+ *   k_scale, v_scale [B, Hkv, Tmax] fp16; k_zero, v_zero [B, Hkv, Tmax] int16,
+ *   as atom_kv_quantize writes them
+ *   out_f16  [B, H, D] fp16
+ * Errors: ATOM_ERR_NULL, ATOM_ERR_SHAPE (negative sizes, H % Hkv != 0),
+ * ATOM_ERR_UNSUPPORTED (D != 128), ATOM_ERR_ALIGN.  B == 0 returns ATOM_OK.
+ */
+atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H,
+                                      int32_t Hkv, int32_t D, int64_t Tmax,
+                                      const int32_t *seq_len,
+                                      const void *k_codes, const void *k_scale,
+                                      const void *k_zero, const void *v_codes,
+                                      const void *v_scale, const void *v_zero,
+                                      float sm_scale, void *out_f16,
+                                      void *stream);
+
 /* Host helper: ATOM_OK iff idx_host[0..K) is a permutation of 0..K-1. */
 atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K);
 

@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     atom_add_quantize_act,
     atom_swiglu_quantize_act,
     atom_quantize_weight,
+    atom_kv_quantize,
+    atom_decode_attention_kv4,
     atom_status_string,
     atom_w4a4_gemm,
     atom_w4a4_gemm_workspace_bytes,

@@ -22,6 +22,8 @@ EXPORTS = (
     "atom_quantize_weight",
     "atom_w4a4_gemm",
     "atom_w4a4_gemm_workspace_bytes",
+    "atom_kv_quantize",
+    "atom_decode_attention_kv4",
     "atom_check_reorder_idx",
     "atom_status_string",
 )
@@ -67,6 +69,12 @@ def load_library():
     L.atom_w4a4_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, dp, vp, i64, vp, vp, sz, vp]
     L.atom_w4a4_gemm_workspace_bytes.restype = sz
     L.atom_w4a4_gemm_workspace_bytes.argtypes = [i64, i64, dp]
+    i32 = ctypes.c_int32
+    L.atom_kv_quantize.restype = ctypes.c_int
+    L.atom_kv_quantize.argtypes = [vp, i64, i64, i32, f32, vp, i32, i64, vp, vp, vp, vp]
+    L.atom_decode_attention_kv4.restype = ctypes.c_int
+    L.atom_decode_attention_kv4.argtypes = [vp, i32, i32, i32, i32, i64, vp, vp, vp, vp, vp, vp, vp,
+                                            f32, vp, vp]
     L.atom_check_reorder_idx.restype = ctypes.c_int
     L.atom_check_reorder_idx.argtypes = [vp, ctypes.c_int32]
     L.atom_status_string.restype = ctypes.c_char_p
@@ -255,4 +263,92 @@ def atom_w4a4_gemm(a_q4, a_q8, a_scale, w_q4, w_q8, w_scale, group_size: int = 1
                           _ptr(partials), _ptr(workspace), ws_bytes, _stream())
     if st != 0:
         raise AtomError(st, "atom_w4a4_gemm")
+    return out
+
+
+def atom_kv_quantize(x: torch.Tensor, clip: float = 1.0,
+                     cache: Optional[Tuple[torch.Tensor, ...]] = None,
+                     pos: Optional[torch.Tensor] = None):
+    """Asymmetric INT4 quantisation of K or V rows, one scale and zero point per head.
+
+    Without ``cache``: ``x`` is [..., D] fp16 (any leading shape, contiguous); returns
+    new ``(codes [..., D/2] uint8, scale [...] fp16, zero [...] int16)``.
+    With ``cache = (codes [B, Hkv, Tmax, D/2], scale [B, Hkv, Tmax], zero [B, Hkv, Tmax])``
+    and ``pos`` (device int32 [B]): ``x`` is [B, Hkv, D], the new token of every sequence,
+    written in place at position ``pos[b]``; returns ``cache``."""
+    L = load_library()
+    _dev(x, torch.float16, "x")
+    if x.dim() < 1 or not x.is_contiguous():
+        raise ValueError("x must be contiguous [..., D]")
+    D = x.shape[-1]
+    R = x.numel() // D if D else 0
+    if cache is None:
+        if pos is not None:
+            raise ValueError("pos needs a cache to append to")
+        lead = tuple(x.shape[:-1])
+        codes = torch.empty(lead + (D // 2,), dtype=torch.uint8, device=x.device)
+        scale = torch.empty(lead, dtype=torch.float16, device=x.device)
+        zero = torch.empty(lead, dtype=torch.int16, device=x.device)
+        st = L.atom_kv_quantize(_ptr(x), R, D, D, clip, None, 0, 0, _ptr(codes), _ptr(scale),
+                                _ptr(zero), _stream())
+    else:
+        codes, scale, zero = cache
+        _dev(codes, torch.uint8, "cache codes")
+        _dev(scale, torch.float16, "cache scale")
+        _dev(zero, torch.int16, "cache zero")
+        if pos is None:
+            raise ValueError("appending to a cache needs pos")
+        _dev(pos, torch.int32, "pos")
+        if x.dim() != 3 or codes.dim() != 4 or not (codes.is_contiguous() and scale.is_contiguous()
+                                                    and zero.is_contiguous()):
+            raise ValueError("x must be [B, Hkv, D] and the cache contiguous [B, Hkv, Tmax, ...]")
+        B, Hkv, Tmax = codes.shape[:3]
+        if (tuple(x.shape) != (B, Hkv, D) or codes.shape[3] * 2 != D or tuple(scale.shape) != (B, Hkv, Tmax)
+                or tuple(zero.shape) != (B, Hkv, Tmax) or tuple(pos.shape) != (B,)
+                or not pos.is_contiguous()):
+            raise ValueError("cache, x and pos shapes disagree")
+        st = L.atom_kv_quantize(_ptr(x), R, D, D, clip, _ptr(pos), Hkv, Tmax, _ptr(codes),
+                                _ptr(scale), _ptr(zero), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_kv_quantize")
+    return codes, scale, zero
+
+
+def atom_decode_attention_kv4(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...],
+                              v_cache: Tuple[torch.Tensor, ...], seq_len: torch.Tensor,
+                              sm_scale: float, out: Optional[torch.Tensor] = None):
+    """Attention of one query token per sequence over the INT4 cache.  ``q`` [B, H, D] fp16;
+    each cache is ``(codes [B, Hkv, Tmax, D/2] uint8, scale [B, Hkv, Tmax] fp16,
+    zero [B, Hkv, Tmax] int16)``; ``seq_len`` device int32 [B].  Returns [B, H, D] fp16."""
+    L = load_library()
+    _dev(q, torch.float16, "q")
+    _dev(seq_len, torch.int32, "seq_len")
+    if q.dim() != 3 or not q.is_contiguous():
+        raise ValueError("q must be contiguous [B, H, D]")
+    B, H, D = q.shape
+    kq, ks, kz = k_cache
+    vq, vs, vz = v_cache
+    for t, dt, nm in ((kq, torch.uint8, "k codes"), (vq, torch.uint8, "v codes"),
+                      (ks, torch.float16, "k scale"), (vs, torch.float16, "v scale"),
+                      (kz, torch.int16, "k zero"), (vz, torch.int16, "v zero")):
+        _dev(t, dt, nm)
+        if not t.is_contiguous():
+            raise ValueError(f"{nm} must be contiguous")
+    if kq.dim() != 4 or kq.shape[0] != B or kq.shape[3] * 2 != D:
+        raise ValueError("k codes must be [B, Hkv, Tmax, D/2]")
+    Hkv, Tmax = kq.shape[1], kq.shape[2]
+    if (vq.shape != kq.shape or tuple(ks.shape) != (B, Hkv, Tmax) or ks.shape != vs.shape
+            or kz.shape != ks.shape or vz.shape != ks.shape or tuple(seq_len.shape) != (B,)
+            or not seq_len.is_contiguous()):
+        raise ValueError("cache and seq_len shapes disagree")
+    if out is None:
+        out = torch.empty((B, H, D), dtype=torch.float16, device=q.device)
+    _dev(out, torch.float16, "out")
+    if tuple(out.shape) != (B, H, D) or not out.is_contiguous():
+        raise ValueError("out must be contiguous [B, H, D]")
+    st = L.atom_decode_attention_kv4(_ptr(q), B, H, Hkv, D, Tmax, _ptr(seq_len), _ptr(kq), _ptr(ks),
+                                     _ptr(kz), _ptr(vq), _ptr(vs), _ptr(vz), sm_scale, _ptr(out),
+                                     _stream())
+    if st != 0:
+        raise AtomError(st, "atom_decode_attention_kv4")
     return out

@@ -139,6 +139,49 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8, const void *a_sca
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
+atom_status atom_kv_quantize(const void *x_f16, int64_t R, int64_t ldx, int32_t D, float clip,
+                             const int32_t *pos, int32_t rows_per_seq, int64_t Tmax, void *q,
+                             void *scale_f16, void *zero_i16, void *stream)
+{
+    if (D != 64 && D != 128) return D > 0 && D % 2 == 0 ? ATOM_ERR_UNSUPPORTED : ATOM_ERR_SHAPE;
+    if (R < 0 || ldx < D) return ATOM_ERR_SHAPE;
+    if (pos && (rows_per_seq <= 0 || R % rows_per_seq || Tmax <= 0)) return ATOM_ERR_SHAPE;
+    if (R == 0) return ATOM_OK;
+    if (!x_f16 || !q || !scale_f16 || !zero_i16) return ATOM_ERR_NULL;
+    if (!aligned(x_f16, 16) || (ldx % 8) || !aligned(q, 4) || !aligned(scale_f16, 2) ||
+        !aligned(zero_i16, 2) || (pos && !aligned(pos, 4)))
+        return ATOM_ERR_ALIGN;
+    if (R * (D / 8) / 256 + 1 > 0x7fffffffLL) return ATOM_ERR_UNSUPPORTED;
+    hipError_t err = atom_internal::launch_kv_quantize(x_f16, R, ldx, D, clip, pos, rows_per_seq,
+                                                       Tmax, q, scale_f16, zero_i16,
+                                                       static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
+atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H, int32_t Hkv,
+                                      int32_t D, int64_t Tmax, const int32_t *seq_len,
+                                      const void *k_codes, const void *k_scale, const void *k_zero,
+                                      const void *v_codes, const void *v_scale, const void *v_zero,
+                                      float sm_scale, void *out_f16, void *stream)
+{
+    if (B < 0 || H <= 0 || Hkv <= 0 || H % Hkv || D <= 0 || Tmax < 0 || Tmax > 0x7fffffffLL)
+        return ATOM_ERR_SHAPE;
+    if (D != 128) return ATOM_ERR_UNSUPPORTED;
+    if ((int64_t)B * H > 0x7fffffffLL) return ATOM_ERR_UNSUPPORTED;
+    if (B == 0) return ATOM_OK;
+    if (!q_f16 || !seq_len || !out_f16) return ATOM_ERR_NULL;
+    if (Tmax > 0 && (!k_codes || !k_scale || !k_zero || !v_codes || !v_scale || !v_zero))
+        return ATOM_ERR_NULL;
+    if (!aligned(q_f16, 16) || !aligned(seq_len, 4) || !aligned(out_f16, 2) ||
+        !aligned(k_codes, 16) || !aligned(v_codes, 16) || !aligned(k_scale, 2) ||
+        !aligned(v_scale, 2) || !aligned(k_zero, 2) || !aligned(v_zero, 2))
+        return ATOM_ERR_ALIGN;
+    hipError_t err = atom_internal::launch_decode_attention_kv4(
+        q_f16, B, H, Hkv, Tmax, seq_len, k_codes, k_scale, k_zero, v_codes, v_scale, v_zero,
+        sm_scale, out_f16, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
 atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K)
 {
     if (!idx_host) return ATOM_ERR_NULL;

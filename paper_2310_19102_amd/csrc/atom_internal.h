@@ -33,5 +33,15 @@ struct GemmArgs {
 size_t     gemm_workspace_bytes(int64_t M, int64_t N, int K, int O);
 hipError_t launch_w4a4_gemm(const GemmArgs &a, hipStream_t stream);
 
+// KV cache: asymmetric INT4 rows of D = 64 or 128 values; decode attention over the cache.
+hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, float clip,
+                              const int32_t *pos, int32_t rows_per_seq, int64_t Tmax, void *q,
+                              void *scale, void *zero, hipStream_t stream);
+hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int64_t Tmax,
+                                       const int32_t *seq_len, const void *kq, const void *ks,
+                                       const void *kz, const void *vq, const void *vs,
+                                       const void *vz, float sm_scale, void *out,
+                                       hipStream_t stream);
+
 }  // namespace atom_internal
 #endif

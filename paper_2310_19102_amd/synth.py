@@ -138,3 +138,31 @@ def make(config: int, which: int = 0, M: Optional[int] = None) -> Linear:
     if config == 1:
         return tiny_linear(config, m, K, N)
     return llama_linear(name, m, K, N, config, tensor_base=10 * which, norm=norm, w_std=std)
+
+
+@dataclass
+class KVCase:
+    """Inputs of one decode-attention step over a KV cache (all CPU tensors)."""
+    q: torch.Tensor         # [B, H, D] fp16 query of the new token
+    k: torch.Tensor         # [B, Hkv, Tmax, D] fp16 keys
+    v: torch.Tensor         # [B, Hkv, Tmax, D] fp16 values
+    seq_len: torch.Tensor   # [B] int32, tokens in the cache per sequence
+    sm_scale: float
+
+
+def kv_case(B: int, H: int, Hkv: int, D: int, Tmax: int, seq_lens=None, case_id: int = 0) -> KVCase:
+    """Keys with per-channel offsets and magnitudes (a few channels of a head are
+    consistently larger, which is what an asymmetric per-head range has to absorb; Section
+    4.4), values close to Gaussian, a unit-variance query.  ``seq_lens`` defaults to a
+    ragged mix between Tmax/4 and Tmax."""
+    cfg = 900 + case_id
+    mu = torch.randn((1, Hkv, 1, D), generator=_gen(cfg, 0))
+    sigma = torch.exp(0.5 * torch.randn((1, Hkv, 1, D), generator=_gen(cfg, 1)))
+    k = (torch.randn((B, Hkv, Tmax, D), generator=_gen(cfg, 2)) * sigma + mu).to(torch.float16)
+    v = (0.5 * torch.randn((B, Hkv, Tmax, D), generator=_gen(cfg, 3))).to(torch.float16)
+    q = torch.randn((B, H, D), generator=_gen(cfg, 4)).to(torch.float16)
+    if seq_lens is None:
+        lo = max(1, Tmax // 4)
+        seq_lens = torch.randint(lo, Tmax + 1, (B,), generator=_gen(cfg, 5)) if Tmax > 0 else torch.zeros(B)
+    seq_len = torch.as_tensor(seq_lens, dtype=torch.int32)
+    return KVCase(q, k, v, seq_len, 1.0 / float(D) ** 0.5)
