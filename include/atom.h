@@ -211,8 +211,15 @@ atom_status atom_kv_quantize(const void *x_f16, int64_t R, int64_t ldx,
  *   k_scale, v_scale [B, Hkv, Tmax] fp16; k_zero, v_zero [B, Hkv, Tmax] int16,
  *   as atom_kv_quantize writes them
  *   out_f16  [B, H, D] fp16
+ *   workspace  device scratch of at least
+ *            atom_decode_attention_kv4_workspace_bytes(B, H, D, Tmax) bytes, 16-byte
+ *            aligned (may be NULL when that is 0): when B * H alone cannot fill
+ *            the GPU the token range is split over several workgroups whose
+ *            partial (max, sum, accumulator) triples meet in a second kernel.
+ *            Contents need no initialisation and are dead after the call.
  * Errors: ATOM_ERR_NULL, ATOM_ERR_SHAPE (negative sizes, H % Hkv != 0),
- * ATOM_ERR_UNSUPPORTED (D != 128), ATOM_ERR_ALIGN.  B == 0 returns ATOM_OK.
+ * ATOM_ERR_UNSUPPORTED (D != 128), ATOM_ERR_ALIGN, ATOM_ERR_WORKSPACE.
+ * B == 0 returns ATOM_OK.
  */
 atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H,
                                       int32_t Hkv, int32_t D, int64_t Tmax,
@@ -221,7 +228,12 @@ atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H,
                                       const void *k_zero, const void *v_codes,
                                       const void *v_scale, const void *v_zero,
                                       float sm_scale, void *out_f16,
+                                      void *workspace, size_t workspace_bytes,
                                       void *stream);
+
+/* Scratch atom_decode_attention_kv4 needs for these sizes (0 when none). */
+size_t atom_decode_attention_kv4_workspace_bytes(int32_t B, int32_t H,
+                                                 int32_t D, int64_t Tmax);
 
 /* Host helper: ATOM_OK iff idx_host[0..K) is a permutation of 0..K-1. */
 atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K);

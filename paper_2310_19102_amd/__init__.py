@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     atom_quantize_weight,
     atom_kv_quantize,
     atom_decode_attention_kv4,
+    atom_decode_attention_kv4_workspace_bytes,
     atom_status_string,
     atom_w4a4_gemm,
     atom_w4a4_gemm_workspace_bytes,

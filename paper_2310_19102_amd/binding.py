@@ -24,6 +24,7 @@ EXPORTS = (
     "atom_w4a4_gemm_workspace_bytes",
     "atom_kv_quantize",
     "atom_decode_attention_kv4",
+    "atom_decode_attention_kv4_workspace_bytes",
     "atom_check_reorder_idx",
     "atom_status_string",
 )
@@ -74,7 +75,9 @@ def load_library():
     L.atom_kv_quantize.argtypes = [vp, i64, i64, i32, f32, vp, i32, i64, vp, vp, vp, vp]
     L.atom_decode_attention_kv4.restype = ctypes.c_int
     L.atom_decode_attention_kv4.argtypes = [vp, i32, i32, i32, i32, i64, vp, vp, vp, vp, vp, vp, vp,
-                                            f32, vp, vp]
+                                            f32, vp, vp, sz, vp]
+    L.atom_decode_attention_kv4_workspace_bytes.restype = sz
+    L.atom_decode_attention_kv4_workspace_bytes.argtypes = [i32, i32, i32, i64]
     L.atom_check_reorder_idx.restype = ctypes.c_int
     L.atom_check_reorder_idx.argtypes = [vp, ctypes.c_int32]
     L.atom_status_string.restype = ctypes.c_char_p
@@ -266,6 +269,10 @@ def atom_w4a4_gemm(a_q4, a_q8, a_scale, w_q4, w_q8, w_scale, group_size: int = 1
     return out
 
 
+def atom_decode_attention_kv4_workspace_bytes(B: int, H: int, D: int, Tmax: int) -> int:
+    return int(load_library().atom_decode_attention_kv4_workspace_bytes(B, H, D, Tmax))
+
+
 def atom_kv_quantize(x: torch.Tensor, clip: float = 1.0,
                      cache: Optional[Tuple[torch.Tensor, ...]] = None,
                      pos: Optional[torch.Tensor] = None):
@@ -316,7 +323,8 @@ def atom_kv_quantize(x: torch.Tensor, clip: float = 1.0,
 
 def atom_decode_attention_kv4(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...],
                               v_cache: Tuple[torch.Tensor, ...], seq_len: torch.Tensor,
-                              sm_scale: float, out: Optional[torch.Tensor] = None):
+                              sm_scale: float, out: Optional[torch.Tensor] = None,
+                              workspace: Optional[torch.Tensor] = None):
     """Attention of one query token per sequence over the INT4 cache.  ``q`` [B, H, D] fp16;
     each cache is ``(codes [B, Hkv, Tmax, D/2] uint8, scale [B, Hkv, Tmax] fp16,
     zero [B, Hkv, Tmax] int16)``; ``seq_len`` device int32 [B].  Returns [B, H, D] fp16."""
@@ -346,9 +354,13 @@ def atom_decode_attention_kv4(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...]
     _dev(out, torch.float16, "out")
     if tuple(out.shape) != (B, H, D) or not out.is_contiguous():
         raise ValueError("out must be contiguous [B, H, D]")
+    need = int(L.atom_decode_attention_kv4_workspace_bytes(B, H, D, Tmax))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     st = L.atom_decode_attention_kv4(_ptr(q), B, H, Hkv, D, Tmax, _ptr(seq_len), _ptr(kq), _ptr(ks),
                                      _ptr(kz), _ptr(vq), _ptr(vs), _ptr(vz), sm_scale, _ptr(out),
-                                     _stream())
+                                     _ptr(workspace), ws_bytes, _stream())
     if st != 0:
         raise AtomError(st, "atom_decode_attention_kv4")
     return out

@@ -162,7 +162,8 @@ atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H, i
                                       int32_t D, int64_t Tmax, const int32_t *seq_len,
                                       const void *k_codes, const void *k_scale, const void *k_zero,
                                       const void *v_codes, const void *v_scale, const void *v_zero,
-                                      float sm_scale, void *out_f16, void *stream)
+                                      float sm_scale, void *out_f16, void *workspace,
+                                      size_t workspace_bytes, void *stream)
 {
     if (B < 0 || H <= 0 || Hkv <= 0 || H % Hkv || D <= 0 || Tmax < 0 || Tmax > 0x7fffffffLL)
         return ATOM_ERR_SHAPE;
@@ -176,10 +177,21 @@ atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H, i
         !aligned(k_codes, 16) || !aligned(v_codes, 16) || !aligned(k_scale, 2) ||
         !aligned(v_scale, 2) || !aligned(k_zero, 2) || !aligned(v_zero, 2))
         return ATOM_ERR_ALIGN;
+    const size_t need = atom_internal::decode_attention_workspace_bytes(B, H, Tmax);
+    if (need) {
+        if (!workspace || workspace_bytes < need) return ATOM_ERR_WORKSPACE;
+        if (!aligned(workspace, 16)) return ATOM_ERR_ALIGN;
+    }
     hipError_t err = atom_internal::launch_decode_attention_kv4(
         q_f16, B, H, Hkv, Tmax, seq_len, k_codes, k_scale, k_zero, v_codes, v_scale, v_zero,
-        sm_scale, out_f16, static_cast<hipStream_t>(stream));
+        sm_scale, out_f16, workspace, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
+size_t atom_decode_attention_kv4_workspace_bytes(int32_t B, int32_t H, int32_t D, int64_t Tmax)
+{
+    if (B <= 0 || H <= 0 || D != 128 || Tmax <= 0 || Tmax > 0x7fffffffLL) return 0;
+    return atom_internal::decode_attention_workspace_bytes(B, H, Tmax);
 }
 
 atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K)

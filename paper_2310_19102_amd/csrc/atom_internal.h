@@ -40,8 +40,9 @@ hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, floa
 hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int64_t Tmax,
                                        const int32_t *seq_len, const void *kq, const void *ks,
                                        const void *kz, const void *vq, const void *vs,
-                                       const void *vz, float sm_scale, void *out,
+                                       const void *vz, float sm_scale, void *out, void *workspace,
                                        hipStream_t stream);
+size_t     decode_attention_workspace_bytes(int B, int H, int64_t Tmax);
 
 }  // namespace atom_internal
 #endif

@@ -155,7 +155,8 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
                                  const uint8_t *__restrict__ kq, const __half *__restrict__ ks,
                                  const int16_t *__restrict__ kz, const uint8_t *__restrict__ vq,
                                  const __half *__restrict__ vs, const int16_t *__restrict__ vz,
-                                 float sm_scale, __half *__restrict__ out)
+                                 float sm_scale, __half *__restrict__ out, int tiles_per_split,
+                                 float *__restrict__ part)
 {
     constexpr int D = 128;
     __shared__ float s_acc[kWaves][D];
@@ -191,7 +192,9 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
     float zacc = 0.0f;                    // running sum of (p * v_scale) * v_zero
     float m_run = -INFINITY, l_run = 0.0f;
 
-    const int ntiles = (T + kTile - 1) / kTile;
+    // this workgroup's share of the steps (all of them when the grid has one split)
+    const int tile0  = blockIdx.y * tiles_per_split;
+    const int ntiles = min((T + kTile - 1) / kTile, tile0 + tiles_per_split);
     uint4 kraw, vraw;
     uint32_t kmeta, vmeta;                // scale bits | zero << 16
     auto fetch = [&](int tile) {
@@ -203,8 +206,8 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
         kmeta = (uint32_t)__half_as_ushort(ks[row]) | ((uint32_t)(uint16_t)kz[row] << 16);
         vmeta = (uint32_t)__half_as_ushort(vs[row]) | ((uint32_t)(uint16_t)vz[row] << 16);
     };
-    if (wave < ntiles) fetch(wave);
-    for (int tile = wave; tile < ntiles; tile += kWaves) {
+    if (tile0 + wave < ntiles) fetch(tile0 + wave);
+    for (int tile = tile0 + wave; tile < ntiles; tile += kWaves) {
         const uint4 kc = kraw, vc = vraw;
         const uint32_t km = kmeta, vm = vmeta;
         if (tile + kWaves < ntiles) fetch(tile + kWaves);
@@ -231,16 +234,22 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
 
         // ---- online softmax (every lane of the wavefront ends up with the same m and l)
         const float m_new = fmaxf(m_run, row16_max(score));
-        const float alpha = __expf(m_run - m_new);        // 0 on the first step
-        const float p     = __expf(score - m_new);
-        l_run = l_run * alpha + row16_sum(p);
-        m_run = m_new;
+        if (m_new > m_run) {                              // rare after the first few steps
+            const float alpha = __expf(m_run - m_new);    // 0 on the first step
+            l_run *= alpha;
+            zacc *= alpha;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) acc[i] *= alpha;
+            m_run = m_new;
+        }
+        const float p = __expf(score - m_run);
+        l_run += row16_sum(p);
 
         // ---- values
         const float v_s = __half2float(__ushort_as_half((unsigned short)(vm & 0xFFFFu)));
         const float v_z = (float)(int16_t)(vm >> 16);
         const float wgt = p * v_s;
-        zacc = zacc * alpha + wgt * v_z;
+        zacc = fmaf(wgt, v_z, zacc);
         const uint32_t vw[4] = {vc.x, vc.y, vc.z, vc.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -249,8 +258,8 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
             for (int i = 0; i < 4; ++i) {
                 // byte i of lo is code 2i, byte i of hi is code 2i + 1
                 const float c0 = (float)((lo >> (8 * i)) & 0xFFu), c1 = (float)((hi >> (8 * i)) & 0xFFu);
-                acc[8 * j + 2 * i]     = fmaf(wgt, c0, acc[8 * j + 2 * i] * alpha);
-                acc[8 * j + 2 * i + 1] = fmaf(wgt, c1, acc[8 * j + 2 * i + 1] * alpha);
+                acc[8 * j + 2 * i]     = fmaf(wgt, c0, acc[8 * j + 2 * i]);
+                acc[8 * j + 2 * i + 1] = fmaf(wgt, c1, acc[8 * j + 2 * i + 1]);
             }
         }
     }
@@ -281,8 +290,36 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
             num += e * s_acc[w][tid];
             den += e * s_l[w];
         }
-        out[((int64_t)b * H + h) * D + tid] = __float2half_rn(den > 0.0f ? num / den : 0.0f);
+        if (part == nullptr) {
+            out[((int64_t)b * H + h) * D + tid] = __float2half_rn(den > 0.0f ? num / den : 0.0f);
+        } else {                                          // one partial (M, den, num[D]) per split
+            float *dst = part + ((int64_t)blockIdx.x * gridDim.y + blockIdx.y) * (D + 2);
+            dst[2 + tid] = num;
+            if (tid == 0) {
+                dst[0] = M;
+                dst[1] = den;
+            }
+        }
     }
+}
+
+// Second pass of a split launch: the partials of one (sequence, head) merge as the
+// wavefronts did, out = sum_s e^(M_s - M) num_s / sum_s e^(M_s - M) den_s.
+__global__ __launch_bounds__(128)
+void decode_attention_merge_kernel(const float *__restrict__ part, int S, __half *__restrict__ out)
+{
+    constexpr int D = 128;
+    const float *src = part + (int64_t)blockIdx.x * S * (D + 2);
+    float M = -INFINITY;
+    for (int s = 0; s < S; ++s) M = fmaxf(M, src[s * (D + 2)]);
+    float num = 0.0f, den = 0.0f;
+    for (int s = 0; s < S; ++s) {
+        const float ms = src[s * (D + 2)];
+        const float e  = ms == -INFINITY ? 0.0f : __expf(ms - M);
+        num += e * src[s * (D + 2) + 2 + threadIdx.x];
+        den += e * src[s * (D + 2) + 1];
+    }
+    out[(int64_t)blockIdx.x * D + threadIdx.x] = __float2half_rn(den > 0.0f ? num / den : 0.0f);
 }
 
 }  // namespace
@@ -306,16 +343,44 @@ hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, floa
     return hipGetLastError();
 }
 
+// Splits of the token range per (sequence, head): enough workgroups to keep about five per
+// compute unit resident, never less than 16 steps (256 tokens) per split.
+int decode_attention_splits(int B, int H, int64_t Tmax)
+{
+    const int64_t tiles = (Tmax + kTile - 1) / kTile;
+    const int64_t bh    = (int64_t)B * H;
+    int64_t want = (1280 + bh - 1) / bh;
+    int64_t cap  = tiles / 16;
+    if (want > cap) want = cap;
+    if (want > 64) want = 64;
+    return want < 1 ? 1 : (int)want;
+}
+
+size_t decode_attention_workspace_bytes(int B, int H, int64_t Tmax)
+{
+    const int S = decode_attention_splits(B, H, Tmax);
+    return S > 1 ? (size_t)B * H * S * (128 + 2) * sizeof(float) : 0;
+}
+
 hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int64_t Tmax,
                                        const int32_t *seq_len, const void *kq, const void *ks,
                                        const void *kz, const void *vq, const void *vs,
-                                       const void *vz, float sm_scale, void *out,
+                                       const void *vz, float sm_scale, void *out, void *workspace,
                                        hipStream_t stream)
 {
-    hipLaunchKernelGGL(decode_attention_kv4_kernel, dim3((unsigned)(B * H)), dim3(kWaves * 64), 0,
-                       stream, (const __half *)q, H, Hkv, Tmax, seq_len, (const uint8_t *)kq,
-                       (const __half *)ks, (const int16_t *)kz, (const uint8_t *)vq,
-                       (const __half *)vs, (const int16_t *)vz, sm_scale, (__half *)out);
+    const int S     = decode_attention_splits(B, H, Tmax);
+    const int tiles = (int)((Tmax + kTile - 1) / kTile);
+    const int tps   = S > 1 ? (tiles + S - 1) / S : (tiles > 0 ? tiles : 1);
+    float *part = S > 1 ? (float *)workspace : nullptr;
+    hipLaunchKernelGGL(decode_attention_kv4_kernel, dim3((unsigned)(B * H), (unsigned)S),
+                       dim3(kWaves * 64), 0, stream, (const __half *)q, H, Hkv, Tmax, seq_len,
+                       (const uint8_t *)kq, (const __half *)ks, (const int16_t *)kz,
+                       (const uint8_t *)vq, (const __half *)vs, (const int16_t *)vz, sm_scale,
+                       (__half *)out, tps, part);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || S == 1) return err;
+    hipLaunchKernelGGL(decode_attention_merge_kernel, dim3((unsigned)(B * H)), dim3(128), 0, stream,
+                       (const float *)part, S, (__half *)out);
     return hipGetLastError();
 }
 

@@ -126,6 +126,8 @@ def _attention_case(kv, what):
     (2, 8, 2, 257, [257, 129]),          # grouped-query attention: 4 query heads per cache head
     (1, 32, 32, 1000, None),             # Llama-7B heads, a mix of lengths
     (4, 8, 1, 70, [1, 2, 3, 70]),        # multi-query; fewer tokens than wavefronts
+    (2, 2, 2, 2048, [2048, 300]),        # token range split 8 ways; most splits of sequence 1 are empty
+    (1, 4, 2, 1500, [1234]),             # split 5 ways with a ragged last split
 ])
 def test_decode_attention(B, H, Hkv, Tmax, lens):
     kv = synth.kv_case(B, H, Hkv, 128, Tmax, seq_lens=lens, case_id=10 + Tmax)
@@ -187,6 +189,19 @@ def test_decode_attention_errors():
     with pytest.raises(atom.AtomError) as e:                      # H not a multiple of Hkv
         atom.atom_decode_attention_kv4(kv.q.cuda()[:, :3].contiguous(), kc, vc, kv.seq_len.cuda(), 1.0)
     assert e.value.status == 2
+    big = synth.kv_case(1, 2, 2, 128, 600, case_id=8)            # needs a workspace: too small / missing
+    assert atom.atom_decode_attention_kv4_workspace_bytes(1, 2, 128, 600) > 0
+    assert atom.atom_decode_attention_kv4_workspace_bytes(64, 32, 128, 600) == 0
+    L = atom.load_library()
+    import ctypes
+    bk, bv = atom.atom_kv_quantize(big.k.cuda()), atom.atom_kv_quantize(big.v.cuda())
+    o = torch.empty((1, 2, 128), dtype=torch.float16, device="cuda")
+    P = lambda t: ctypes.c_void_p(t.data_ptr())
+    args = [P(big.q.cuda()), 1, 2, 2, 128, 600, P(big.seq_len.cuda()), P(bk[0]), P(bk[1]), P(bk[2]),
+            P(bv[0]), P(bv[1]), P(bv[2]), 1.0, P(o)]
+    assert L.atom_decode_attention_kv4(*args, None, 0, None) == 5
+    small = torch.empty(64, dtype=torch.uint8, device="cuda")
+    assert L.atom_decode_attention_kv4(*args, P(small), 64, None) == 5
     kv64 = synth.kv_case(1, 2, 2, 64, 8, case_id=7)
     with pytest.raises(atom.AtomError) as e:                      # head dimension 64: not built
         atom.atom_decode_attention_kv4(kv64.q.cuda(), atom.atom_kv_quantize(kv64.k.cuda()),
