@@ -131,31 +131,72 @@ __device__ __forceinline__ float row16_max(float v)
     return v;
 }
 
-constexpr int kWaves = 4;                 // wavefronts per workgroup, each walks every 4th tile
-constexpr int kTile  = 16;                // tokens per wavefront step
+// The eight codes of a dword (code n in bits 4n..4n+3) as four fp16 pairs with two shifts:
+// a code placed in mantissa bits 6..9 under the exponent of 16 reads as 16 + c, one placed
+// in bits 2..5 under the exponent of 256 reads as 256 + c, both exactly.
+//   pr[0] = (16 + n1, 16 + n5)   pr[1] = (256 + n0, 256 + n4)      from w << 2
+//   pr[2] = (16 + n3, 16 + n7)   pr[3] = (256 + n2, 256 + n6)      from w >> 6
+// The offsets are subtracted once per sum by the caller.
+constexpr int   kNib[4] = {1, 0, 3, 2};                  // low-half code of pair k
+constexpr float kOff[4] = {16.0f, 256.0f, 16.0f, 256.0f};
 
-// One workgroup per (sequence, query head), head dimension 128.  A wavefront step covers 16
-// tokens: lane l holds token (l & 15) and the 32 head dimensions of chunk (l >> 4), i.e.
-// 16 bytes of that token's K row and 16 bytes of its V row (a wavefront load is 1 KB of
-// contiguous cache).
-//   scores  : the codes become fp16 16 + c, two at a time: a code placed in mantissa bits
-//             6..9 under the exponent of 16 (0x4C00) adds exactly c; they meet the matching
-//             pairs of q in v_dot2_f32_f16 (fp32 accumulate); the 16 and the zero point
-//             leave as (16 + z) * sum(q) per chunk (a small offset keeps the cancellation
-//             in fp32 harmless); the four
-//             chunks of a token are added across lanes; then * scale * sm_scale.
-//   softmax : online, per wavefront (running max m and sum l).
-//   values  : acc[d] += (p * v_scale) * code[d] per lane, the zero points as one running
-//             sum of (p * v_scale) * z; the 16 tokens of the lanes meet once, at the end;
-//             the four wavefronts merge through LDS.
-// The next step's loads are issued before the current one is used.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(magic));
+    return r;
+}
+
+// All eight as 16 + c, pr[k] = (16 + n_k, 16 + n_(k+4)), with four shifts: for sums whose
+// result may be small against the offsets' total (the value side of attention).
+__device__ __forceinline__ void unpack8_16(uint32_t w, uint32_t (&pr)[4])
+{
+    pr[0] = and_or(w << 6, 0x03C003C0u, 0x4C004C00u);
+    pr[1] = and_or(w << 2, 0x03C003C0u, 0x4C004C00u);
+    pr[2] = and_or(w >> 2, 0x03C003C0u, 0x4C004C00u);
+    pr[3] = and_or(w >> 6, 0x03C003C0u, 0x4C004C00u);
+}
+
+__device__ __forceinline__ void unpack8(uint32_t w, uint32_t (&pr)[4])
+{
+    const uint32_t a = w << 2, b = w >> 6;
+    pr[0] = and_or(a, 0x03C003C0u, 0x4C004C00u);
+    pr[1] = and_or(a, 0x003C003Cu, 0x5C005C00u);
+    pr[2] = and_or(b, 0x03C003C0u, 0x4C004C00u);
+    pr[3] = and_or(b, 0x003C003Cu, 0x5C005C00u);
+}
+
+constexpr int kWaves = 4;                 // wavefronts per workgroup
+constexpr int kTile  = 16;                // tokens per wavefront step
+constexpr int kTokens = 64;                // tokens per wavefront group: four steps, one per ring slot
+
+// One workgroup per (sequence, query head) and split of the token range, head dimension 128.
+// A wavefront owns every fourth group of 64 tokens and walks it in four steps of 16 tokens:
+// lane l holds token (l & 15) and the 32 head dimensions of chunk (l >> 4), i.e. 16 bytes of
+// that token's K row and 16 bytes of its V row (a wavefront load is 1 KB of contiguous cache).
+//   scores  : the codes become fp16 offset + c, two at a time (unpack8), and meet the
+//             matching pairs of q in v_dot2_f32_f16 (fp32 accumulate); the offsets and the
+//             zero point leave as sum(offset * q) + z * sum(q) per chunk (offsets of 16 and
+//             256 keep the cancellation in fp32 harmless); the four chunks of a token are
+//             added across lanes; then * scale * sm_scale.
+//   softmax : online, per wavefront (running max m and sum l); the accumulators are rescaled
+//             only when the maximum moves.
+//   values  : acc[d] += w * (16 + code[d]) with w = p * v_scale (unpack8_16), the fp16 codes
+//             read by mixed-precision fmas; the 16 and the zero points leave at the end
+//             through the running sums of w and w * z; the 16 tokens of the lanes meet
+//             once, at the end; the four wavefronts merge through LDS.
+//   loads   : the codes of the next group (four steps ahead) are in flight while a step is
+//             computed.  Scales and zero points are read once per group, lane l taking
+//             token l of the 64, one full cache line per array, and reach the lane that
+//             needs them through ds_bpermute: 2-byte loads per step would have several
+//             wavefronts wait on the same line, which stalls the vector cache.
 __global__ __launch_bounds__(kWaves * 64)
 void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, int64_t Tmax,
                                  const int32_t *__restrict__ seq_len,
                                  const uint8_t *__restrict__ kq, const __half *__restrict__ ks,
                                  const int16_t *__restrict__ kz, const uint8_t *__restrict__ vq,
                                  const __half *__restrict__ vs, const int16_t *__restrict__ vz,
-                                 float sm_scale, __half *__restrict__ out, int tiles_per_split,
+                                 float sm_scale, __half *__restrict__ out, int groups_per_split,
                                  float *__restrict__ part)
 {
     constexpr int D = 128;
@@ -164,79 +205,98 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
 
     const int b = blockIdx.x / H, h = blockIdx.x % H;
     const int kvh = h / (H / Hkv);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tl = lane & 15, c = lane >> 4;
     int T = seq_len[b];
     T = T < 0 ? 0 : (T > Tmax ? (int)Tmax : T);          // never read past the cache
     const int64_t base = ((int64_t)b * Hkv + kvh) * Tmax;
+    const uint8_t *kb = kq + base * (D / 2), *vb = vq + base * (D / 2);
+    const __half  *ksb = ks + base, *vsb = vs + base;
+    const int16_t *kzb = kz + base, *vzb = vz + base;
 
-    // this lane's 32 query values as 16 pairs in the order the codes come out of a dword:
-    // dword j holds d = 32c + 8j + 0..7; one masked shift picks nibbles (i, i + 4)
+    // this workgroup's share of the groups (all of them when the grid has one split)
+    const int g_first = blockIdx.y * groups_per_split;
+    const int g_end   = min((T + kTokens - 1) / kTokens, g_first + groups_per_split);
+    int  G     = g_first + wave;
+    const bool alive = G < g_end;                        // then T >= 1: clamped addresses are valid
+
+    struct Stage { uint4 k, v; };
+    Stage st[4];
+    uint32_t kmeta = 0, vmeta = 0;        // scale bits | zero << 16 of token `lane` of the group
+    auto fetch = [&](Stage &s_, int tile) {
+        int t = tile * kTile + tl;
+        t = t < T ? t : T - 1;            // masked tokens and steps past the end repeat the last token
+        const uint32_t off = (uint32_t)t * (D / 2) + 16u * c;
+        s_.k = *reinterpret_cast<const uint4 *>(kb + off);
+        s_.v = *reinterpret_cast<const uint4 *>(vb + off);
+    };
+    auto fetch_meta = [&](int g, uint32_t &km, uint32_t &vm) {
+        int t = g * kTokens + lane;
+        t = t < T ? t : T - 1;
+        km = (uint32_t)__half_as_ushort(ksb[(uint32_t)t]) | ((uint32_t)(uint16_t)kzb[(uint32_t)t] << 16);
+        vm = (uint32_t)__half_as_ushort(vsb[(uint32_t)t]) | ((uint32_t)(uint16_t)vzb[(uint32_t)t] << 16);
+    };
+    if (alive) {                          // the first loads leave before q is read
+        fetch_meta(G, kmeta, vmeta);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fetch(st[i], 4 * G + i);
+    }
+
+    // this lane's 32 query values as 16 pairs in the order unpack8 delivers the codes of a
+    // dword (dword j holds d = 32c + 8j + 0..7), and the sums that take the offsets back out
     h2 qp[16];
-    float qsum = 0.0f;
+    float qsum = 0.0f, qoff = 0.0f;       // sum(q), sum(offset(d) * q)
     {
         const __half *qv = q + ((int64_t)b * H + h) * D + 32 * c;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const __half a = qv[8 * j + i], bb = qv[8 * j + i + 4];
-                qp[4 * j + i] = h2{(_Float16)__half2float(a), (_Float16)__half2float(bb)};
-                qsum += __half2float(a) + __half2float(bb);
+            for (int k = 0; k < 4; ++k) {
+                const float lo = __half2float(qv[8 * j + kNib[k]]), hi = __half2float(qv[8 * j + kNib[k] + 4]);
+                qp[4 * j + k] = h2{(_Float16)lo, (_Float16)hi};
+                qsum += lo + hi;
+                qoff += kOff[k] * (lo + hi);
             }
     }
 
-    float acc[32];
+    float acc[32];                        // acc[8j + 2k + half] <-> d = 32c + 8j + k + 4 half
 #pragma unroll
     for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
-    float zacc = 0.0f;                    // running sum of (p * v_scale) * v_zero
+    float wsum = 0.0f, zacc = 0.0f;       // running sums of w = p * v_scale and of w * v_zero
     float m_run = -INFINITY, l_run = 0.0f;
 
-    // this workgroup's share of the steps (all of them when the grid has one split)
-    const int tile0  = blockIdx.y * tiles_per_split;
-    const int ntiles = min((T + kTile - 1) / kTile, tile0 + tiles_per_split);
-    uint4 kraw, vraw;
-    uint32_t kmeta, vmeta;                // scale bits | zero << 16
-    auto fetch = [&](int tile) {
-        int t = tile * kTile + tl;
-        t = t < T ? t : T - 1;            // masked tokens repeat the last valid one
-        const int64_t row = base + t;
-        kraw = *reinterpret_cast<const uint4 *>(kq + row * (D / 2) + 16 * c);
-        vraw = *reinterpret_cast<const uint4 *>(vq + row * (D / 2) + 16 * c);
-        kmeta = (uint32_t)__half_as_ushort(ks[row]) | ((uint32_t)(uint16_t)kz[row] << 16);
-        vmeta = (uint32_t)__half_as_ushort(vs[row]) | ((uint32_t)(uint16_t)vz[row] << 16);
-    };
-    if (tile0 + wave < ntiles) fetch(tile0 + wave);
-    for (int tile = tile0 + wave; tile < ntiles; tile += kWaves) {
-        const uint4 kc = kraw, vc = vraw;
-        const uint32_t km = kmeta, vm = vmeta;
-        if (tile + kWaves < ntiles) fetch(tile + kWaves);
+    auto consume = [&](const Stage &s_, int tile, int slot) {
+        // this token's scale and zero point sit in lane 16 * slot + tl
+        const int src = (16 * slot + tl) << 2;
+        const uint32_t km = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)kmeta);
+        const uint32_t vm = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)vmeta);
 
         // ---- scores
-        const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w};
+        const uint32_t kw[4] = {s_.k.x, s_.k.y, s_.k.z, s_.k.w};
         float dot = 0.0f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 4; ++j) {
+            uint32_t pr[4];
+            unpack8(kw[j], pr);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                // nibbles (i, i + 4) moved to mantissa bits 6..9 of the two halves
-                const uint32_t sh   = i < 2 ? kw[j] << (6 - 4 * i) : kw[j] >> (4 * i - 6);
-                const uint32_t pair = (sh & 0x03C003C0u) | 0x4C004C00u;
-                dot = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, pair), qp[4 * j + i], dot, false);
-            }
+            for (int k = 0; k < 4; ++k)
+                dot = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, pr[k]), qp[4 * j + k], dot, false);
+        }
         const float k_s = __half2float(__ushort_as_half((unsigned short)(km & 0xFFFFu)));
         const float k_z = (float)(int16_t)(km >> 16);
-        float part = dot - (16.0f + k_z) * qsum;
-        part += __shfl_xor(part, 16, 64);
-        part += __shfl_xor(part, 32, 64);
+        float part_ = dot - fmaf(k_z, qsum, qoff);
+        part_ += __shfl_xor(part_, 16, 64);
+        part_ += __shfl_xor(part_, 32, 64);
         const bool valid = tile * kTile + tl < T;
-        const float score = valid ? part * (k_s * sm_scale) : -INFINITY;
+        const float score = valid ? part_ * (k_s * sm_scale) : -INFINITY;
 
         // ---- online softmax (every lane of the wavefront ends up with the same m and l)
         const float m_new = fmaxf(m_run, row16_max(score));
         if (m_new > m_run) {                              // rare after the first few steps
             const float alpha = __expf(m_run - m_new);    // 0 on the first step
             l_run *= alpha;
+            wsum *= alpha;
             zacc *= alpha;
 #pragma unroll
             for (int i = 0; i < 32; ++i) acc[i] *= alpha;
@@ -245,32 +305,57 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
         const float p = __expf(score - m_run);
         l_run += row16_sum(p);
 
-        // ---- values
+        // ---- values: the fp16 halves go straight into mixed-precision fmas
         const float v_s = __half2float(__ushort_as_half((unsigned short)(vm & 0xFFFFu)));
         const float v_z = (float)(int16_t)(vm >> 16);
         const float wgt = p * v_s;
+        wsum += wgt;
         zacc = fmaf(wgt, v_z, zacc);
-        const uint32_t vw[4] = {vc.x, vc.y, vc.z, vc.w};
+        const uint32_t vw[4] = {s_.v.x, s_.v.y, s_.v.z, s_.v.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint32_t lo = vw[j] & 0x0F0F0F0Fu, hi = (vw[j] >> 4) & 0x0F0F0F0Fu;
+            uint32_t pr[4];
+            unpack8_16(vw[j], pr);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const h2 cv = __builtin_bit_cast(h2, pr[k]);
+                acc[8 * j + 2 * k]     = fmaf(wgt, (float)cv[0], acc[8 * j + 2 * k]);
+                acc[8 * j + 2 * k + 1] = fmaf(wgt, (float)cv[1], acc[8 * j + 2 * k + 1]);
+            }
+        }
+    };
+
+    if (alive) {
+        while (G < g_end) {
+            const int Gn = G + kWaves;                    // past the end: clamped, unused loads
+            uint32_t nk, nv;
+            fetch_meta(Gn, nk, nv);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                // byte i of lo is code 2i, byte i of hi is code 2i + 1
-                const float c0 = (float)((lo >> (8 * i)) & 0xFFu), c1 = (float)((hi >> (8 * i)) & 0xFFu);
-                acc[8 * j + 2 * i]     = fmaf(wgt, c0, acc[8 * j + 2 * i]);
-                acc[8 * j + 2 * i + 1] = fmaf(wgt, c1, acc[8 * j + 2 * i + 1]);
+                const int tile = 4 * G + i;
+                if (tile * kTile < T) consume(st[i], tile, i);
+                fetch(st[i], 4 * Gn + i);                 // the slot's next use is four steps away
             }
+            kmeta = nk;
+            vmeta = nv;
+            G = Gn;
         }
     }
 
     // ---- the 16 tokens of the lanes meet; lane (0, c) then holds chunk c of this wavefront
     zacc = row16_sum(zacc);
+    wsum = row16_sum(wsum);
 #pragma unroll
-    for (int i = 0; i < 32; ++i) acc[i] = row16_sum(acc[i]) - zacc;
+    for (int i = 0; i < 32; ++i) acc[i] = row16_sum(acc[i]);
     if (tl == 0) {
 #pragma unroll
-        for (int i = 0; i < 32; ++i) s_acc[wave][32 * c + i] = acc[i];
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf)            // the offsets and zero points leave here
+                    s_acc[wave][32 * c + 8 * j + k + 4 * hf] =
+                        acc[8 * j + 2 * k + hf] - fmaf(16.0f, wsum, zacc);
     }
     if (lane == 0) {
         s_m[wave] = m_run;
@@ -344,13 +429,13 @@ hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, floa
 }
 
 // Splits of the token range per (sequence, head): enough workgroups to keep about five per
-// compute unit resident, never less than 16 steps (256 tokens) per split.
+// compute unit resident, never less than one 64-token group per wavefront and split.
 int decode_attention_splits(int B, int H, int64_t Tmax)
 {
-    const int64_t tiles = (Tmax + kTile - 1) / kTile;
-    const int64_t bh    = (int64_t)B * H;
+    const int64_t groups = (Tmax + kTokens - 1) / kTokens;
+    const int64_t bh     = (int64_t)B * H;
     int64_t want = (1280 + bh - 1) / bh;
-    int64_t cap  = tiles / 16;
+    int64_t cap  = groups / kWaves;
     if (want > cap) want = cap;
     if (want > 64) want = 64;
     return want < 1 ? 1 : (int)want;
@@ -368,9 +453,9 @@ hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int
                                        const void *vz, float sm_scale, void *out, void *workspace,
                                        hipStream_t stream)
 {
-    const int S     = decode_attention_splits(B, H, Tmax);
-    const int tiles = (int)((Tmax + kTile - 1) / kTile);
-    const int tps   = S > 1 ? (tiles + S - 1) / S : (tiles > 0 ? tiles : 1);
+    const int S      = decode_attention_splits(B, H, Tmax);
+    const int groups = (int)((Tmax + kTokens - 1) / kTokens);
+    const int tps    = S > 1 ? (groups + S - 1) / S : (groups > 0 ? groups : 1);
     float *part = S > 1 ? (float *)workspace : nullptr;
     hipLaunchKernelGGL(decode_attention_kv4_kernel, dim3((unsigned)(B * H), (unsigned)S),
                        dim3(kWaves * 64), 0, stream, (const __half *)q, H, Hkv, Tmax, seq_len,
