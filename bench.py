@@ -217,6 +217,46 @@ def extra_measurements():
         del x, res, hsum, qa
         torch.cuda.empty_cache()
     out.append(mlp_block_chain())
+    out.extend(kv_cache_measurements())
+    return out
+
+
+def kv_cache_measurements():
+    """INT4 KV cache, Llama-7B heads (32 x 128): decode attention over the quantised cache
+    against the HBM roofline (algorithmic bytes: 2 x (64 B codes + 2 B scale + 2 B zero) per
+    cached token and head), and the quantise-on-append of one new token per sequence."""
+    out = []
+    H, D = 32, 128
+    gen = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED)
+    for (B, T) in ((8, 4096), (64, 1024), (128, 2048)):
+        k = torch.randn((B, H, T, D), generator=gen, device="cuda", dtype=torch.float16)
+        kc = atom.atom_kv_quantize(k)
+        k.normal_(generator=gen)
+        k *= 0.5
+        vc = atom.atom_kv_quantize(k)
+        del k
+        q = torch.randn((B, H, D), generator=gen, device="cuda", dtype=torch.float16)
+        seq_len = torch.full((B,), T, dtype=torch.int32, device="cuda")
+        o = torch.empty_like(q)
+        need = atom.atom_decode_attention_kv4_workspace_bytes(B, H, D, T)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        t = graph_time(lambda: atom.atom_decode_attention_kv4(q, kc, vc, seq_len, D ** -0.5, out=o,
+                                                              workspace=ws), 20, 5)
+        nbytes = B * H * T * 2 * (D // 2 + 4)
+        entry = {"workload": f"decode attention over the INT4 KV cache, B={B} H={H} D={D} T={T}, HIP graph",
+                 "attention_us": t * 1e6, "cache_bytes": nbytes, "GBs": nbytes / t / 1e9,
+                 "hbm_frac": nbytes / t / 1e9 / PEAK_HBM_GBS}
+        # append: the new token's K and V rows of every sequence, quantised in place
+        new = torch.randn((B, H, D), generator=gen, device="cuda", dtype=torch.float16)
+        pos = torch.full((B,), T - 1, dtype=torch.int32, device="cuda")
+
+        def append():
+            atom.atom_kv_quantize(new, cache=kc, pos=pos)
+            atom.atom_kv_quantize(new, cache=vc, pos=pos)
+        entry["append_k_and_v_us"] = graph_time(append, 20, 5) * 1e6
+        out.append(entry)
+        del kc, vc, ws
+        torch.cuda.empty_cache()
     return out
 
 
@@ -303,6 +343,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--cpu-rows", type=int, default=1024,
                     help="rows of each linear the CPU oracle is timed on (1024 rows of config 4 take about 12 s)")
+    ap.add_argument("--kv-only", action="store_true",
+                    help="print only the INT4 KV-cache measurements (a short run to put under rocprofv3)")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -320,6 +362,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.kv_only:
+        print(json.dumps({"kv_cache": kv_cache_measurements()}))
+        return
 
     layers = [DeviceLinear(synth.make(args.config, w))
               for w in range(len(synth.CONFIG_SHAPES[args.config]))]

@@ -220,20 +220,21 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
     const int g_end   = min((T + kTokens - 1) / kTokens, g_first + groups_per_split);
     int  G     = g_first + wave;
     const bool alive = G < g_end;                        // then T >= 1: clamped addresses are valid
+    const int  t_last = min(T, g_end * kTokens) - 1;     // loads never leave this split's tokens
 
     struct Stage { uint4 k, v; };
     Stage st[4];
     uint32_t kmeta = 0, vmeta = 0;        // scale bits | zero << 16 of token `lane` of the group
     auto fetch = [&](Stage &s_, int tile) {
         int t = tile * kTile + tl;
-        t = t < T ? t : T - 1;            // masked tokens and steps past the end repeat the last token
+        t = t <= t_last ? t : t_last;     // masked tokens and steps past the end repeat the last token
         const uint32_t off = (uint32_t)t * (D / 2) + 16u * c;
         s_.k = *reinterpret_cast<const uint4 *>(kb + off);
         s_.v = *reinterpret_cast<const uint4 *>(vb + off);
     };
     auto fetch_meta = [&](int g, uint32_t &km, uint32_t &vm) {
         int t = g * kTokens + lane;
-        t = t < T ? t : T - 1;
+        t = t <= t_last ? t : t_last;
         km = (uint32_t)__half_as_ushort(ksb[(uint32_t)t]) | ((uint32_t)(uint16_t)kzb[(uint32_t)t] << 16);
         vm = (uint32_t)__half_as_ushort(vsb[(uint32_t)t]) | ((uint32_t)(uint16_t)vzb[(uint32_t)t] << 16);
     };
