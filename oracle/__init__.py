@@ -67,6 +67,21 @@ def _load():
     L.atom_ref_decode_attention_kv4.restype = ctypes.c_int
     L.atom_ref_decode_attention_kv4.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp,
                                                 vp, f32, vp]
+    u8 = ctypes.c_uint8
+    L.atom_ref_e2m1_to_f32.restype = f32
+    L.atom_ref_e2m1_to_f32.argtypes = [u8]
+    L.atom_ref_e4m3_to_f32.restype = f32
+    L.atom_ref_e4m3_to_f32.argtypes = [u8]
+    L.atom_ref_f32_to_e2m1.restype = u8
+    L.atom_ref_f32_to_e2m1.argtypes = [f32]
+    L.atom_ref_f32_to_e4m3.restype = u8
+    L.atom_ref_f32_to_e4m3.argtypes = [f32]
+    L.atom_ref_mx_scale_byte.restype = u8
+    L.atom_ref_mx_scale_byte.argtypes = [f32, ctypes.c_int]
+    L.atom_ref_mx_quantize_act.restype = ctypes.c_int
+    L.atom_ref_mx_quantize_act.argtypes = [vp, i64, i64, vp, f32, vp, i32, i32, f32, vp, vp, vp]
+    L.atom_ref_mx_gemm.restype = ctypes.c_int
+    L.atom_ref_mx_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, i32, i32, vp, i64]
     L.atom_ref_quantize_weight.restype = ctypes.c_int
     L.atom_ref_quantize_weight.argtypes = [vp, i64, i64, vp, i32, i32, i32, f32, vp, vp, vp]
     L.atom_ref_w4a4_gemm.restype = ctypes.c_int
@@ -262,3 +277,62 @@ def decode_attention_kv4(q, kq, ks, kz, vq, vs, vz, seq_len, sm_scale):
     if rc != 0:
         raise ValueError("atom_ref_decode_attention_kv4: bad shapes")
     return out
+
+
+# ---- MX (microscaling) variant: FP4 E2M1 normal channels, FP8 E4M3 outliers, E8M0 scale per 32
+
+def e2m1_to_f32(code):
+    return float(_load().atom_ref_e2m1_to_f32(int(code)))
+
+
+def e4m3_to_f32(code):
+    return float(_load().atom_ref_e4m3_to_f32(int(code)))
+
+
+def f32_to_e2m1(v):
+    return int(_load().atom_ref_f32_to_e2m1(float(np.float32(v))))
+
+
+def f32_to_e4m3(v):
+    return int(_load().atom_ref_f32_to_e4m3(float(np.float32(v))))
+
+
+def mx_scale_byte(clipped_amax, emax):
+    return int(_load().atom_ref_mx_scale_byte(float(np.float32(clipped_amax)), int(emax)))
+
+
+def mx_quantize_act(x, gamma, eps, idx, n_outlier=128, clip=1.0):
+    """x float16 [M, K]; gamma float16 [K] or None (no norm).  Returns
+    (q4 uint8 [M, K4/2], q8 uint8 [M, O], e8 uint8 [M, K/32])."""
+    x = _c(x, np.float16)
+    idx = _c(idx, np.int32)
+    M, K = x.shape
+    O = int(n_outlier)
+    q4 = np.zeros((M, (K - O) // 2), np.uint8)
+    q8 = np.zeros((M, O), np.uint8)
+    e8 = np.zeros((M, K // 32), np.uint8)
+    g = None if gamma is None else _c(gamma, np.float16)
+    rc = _load().atom_ref_mx_quantize_act(_p(x), M, K, None if g is None else _p(g), eps, _p(idx), K, O,
+                                          clip, _p(q4), _p(q8), _p(e8))
+    if rc != 0:
+        raise ValueError("atom_ref_mx_quantize_act: bad shapes")
+    return q4, q8, e8
+
+
+def mx_quantize_weight(w, idx, n_outlier=128, clip=1.0):
+    return mx_quantize_act(w, None, 0.0, idx, n_outlier, clip)
+
+
+def mx_gemm(a_q4, a_q8, a_e8, w_q4, w_q8, w_e8):
+    """Y float16 [M, N] from the two MX-quantised operands."""
+    a_q4, a_q8, a_e8 = _c(a_q4, np.uint8), _c(a_q8, np.uint8), _c(a_e8, np.uint8)
+    w_q4, w_q8, w_e8 = _c(w_q4, np.uint8), _c(w_q8, np.uint8), _c(w_e8, np.uint8)
+    M, O = a_q8.shape
+    N = w_q8.shape[0]
+    K = 2 * a_q4.shape[1] + O
+    y = np.zeros((M, N), np.float16)
+    rc = _load().atom_ref_mx_gemm(_p(a_q4), _p(a_q8), _p(a_e8), M, _p(w_q4), _p(w_q8), _p(w_e8), N, K, O,
+                                  _p(y), N)
+    if rc != 0:
+        raise ValueError("atom_ref_mx_gemm: bad shapes")
+    return y

@@ -441,3 +441,158 @@ int atom_ref_decode_attention_kv4(const uint16_t *q, int32_t B, int32_t H,
     free(acc);
     return 0;
 }
+
+/* ------------------------------------------- MX (microscaling) variant -- */
+/* Section 5.2 / 6 of the paper evaluates the same recipe with FP4 codes and
+ * names the MX formats, whose group scaling new hardware applies by itself.
+ * Formats as the MX specification the paper cites defines them: a block of 32
+ * elements shares one E8M0 scale 2^(byte - 127); the elements are FP4 E2M1
+ * (normal channels) or FP8 E4M3 (outlier channels). */
+
+static const float kE2M1[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+
+float atom_ref_e2m1_to_f32(uint8_t code)
+{
+    float v = kE2M1[code & 7];
+    return (code & 8) ? -v : v;
+}
+
+float atom_ref_e4m3_to_f32(uint8_t code)
+{
+    int   s = code >> 7, e = (code >> 3) & 15, m = code & 7;
+    float v;
+    if (e == 15 && m == 7) return NAN;               /* the format has no infinity */
+    if (e == 0) v = ldexpf((float)m, -9);            /* subnormal: m/8 * 2^-6 */
+    else        v = ldexpf(1.0f + (float)m / 8.0f, e - 7);
+    return s ? -v : v;
+}
+
+/* Nearest representable magnitude among codes 0..last, ties to the even code
+ * (= even mantissa), magnitudes beyond the largest one saturate to it. */
+static uint8_t nearest_code(float a, int last, float (*decode)(uint8_t))
+{
+    int best = 0;
+    double bestd = fabs((double)a - (double)decode(0));
+    for (int c = 1; c <= last; ++c) {
+        double d = fabs((double)a - (double)decode((uint8_t)c));
+        if (d < bestd || (d == bestd && (c % 2 == 0))) { best = c; bestd = d; }
+    }
+    return (uint8_t)best;
+}
+
+uint8_t atom_ref_f32_to_e2m1(float v)
+{
+    uint8_t c = nearest_code(fabsf(v), 7, atom_ref_e2m1_to_f32);
+    return (uint8_t)(c | (signbit(v) ? 8 : 0));
+}
+
+uint8_t atom_ref_f32_to_e4m3(float v)
+{
+    uint8_t c = nearest_code(fabsf(v), 0x7e, atom_ref_e4m3_to_f32);
+    return (uint8_t)(c | (signbit(v) ? 0x80 : 0));
+}
+
+/* E8M0 byte of a block whose clipped absolute maximum is a: the exponent of
+ * the largest power of two not above a, minus the element format's largest
+ * exponent emax (2 for E2M1, 8 for E4M3), clamped to [-127, 127]. */
+uint8_t atom_ref_mx_scale_byte(float a, int emax)
+{
+    if (!(a > 0.0f)) return 0;
+    int e;
+    (void)frexpf(a, &e);                             /* a = f * 2^e, f in [0.5, 1) */
+    int E = (e - 1) - emax;
+    if (E < -127) E = -127;
+    if (E > 127) E = 127;
+    return (uint8_t)(E + 127);
+}
+
+/* One row, fp32 values y[] in ORIGINAL channel order. */
+static void mx_quantize_row(const float *y, const int32_t *idx, int32_t K, int32_t O,
+                            float clip, uint8_t *q4, uint8_t *q8, uint8_t *e8)
+{
+    int32_t K4 = K - O;
+    for (int32_t b = 0; b < K / 32; ++b) {
+        int   fp4  = (b * 32 < K4);
+        float amax = 0.0f;
+        for (int32_t t = 0; t < 32; ++t) {
+            float a = fabsf(y[idx[b * 32 + t]]);
+            if (a > amax) amax = a;
+        }
+        uint8_t byte = atom_ref_mx_scale_byte(amax * clip, fp4 ? 2 : 8);
+        e8[b] = byte;
+        for (int32_t t = 0; t < 32; ++t) {
+            int32_t j = b * 32 + t;
+            float   v = ldexpf(y[idx[j]], 127 - (int)byte);   /* y / 2^(byte-127), exact */
+            if (fp4) {
+                uint8_t c = atom_ref_f32_to_e2m1(v);
+                if (j % 2 == 0) q4[j / 2] = c;
+                else            q4[j / 2] = (uint8_t)(q4[j / 2] | (c << 4));
+            } else {
+                q8[j - K4] = atom_ref_f32_to_e4m3(v);
+            }
+        }
+    }
+}
+
+static int mx_shapes_ok(int32_t K, int32_t O)
+{
+    return K > 0 && O >= 0 && O < K && K % 32 == 0 && O % 32 == 0;
+}
+
+int atom_ref_mx_quantize_act(const uint16_t *x, int64_t M, int64_t ldx,
+                             const uint16_t *gamma, float eps, const int32_t *idx,
+                             int32_t K, int32_t O, float clip, uint8_t *q4,
+                             uint8_t *q8, uint8_t *e8)
+{
+    if (!mx_shapes_ok(K, O) || ldx < K || M < 0) return -1;
+    float *y = (float *)malloc(sizeof(float) * (size_t)K);
+    if (!y) return -1;
+    for (int64_t m = 0; m < M; ++m) {
+        atom_ref_rmsnorm_row(x + m * ldx, gamma, eps, K, y);
+        mx_quantize_row(y, idx, K, O, clip, q4 + m * ((K - O) / 2), q8 + m * O,
+                        e8 + m * (K / 32));
+    }
+    free(y);
+    return 0;
+}
+
+int atom_ref_mx_gemm(const uint8_t *a_q4, const uint8_t *a_q8, const uint8_t *a_e8,
+                     int64_t M, const uint8_t *w_q4, const uint8_t *w_q8,
+                     const uint8_t *w_e8, int64_t N, int32_t K, int32_t O,
+                     uint16_t *y, int64_t ldy)
+{
+    if (!mx_shapes_ok(K, O) || M < 0 || N < 0 || ldy < N) return -1;
+    int32_t K4 = K - O, NB = K / 32;
+    /* decode both operands once */
+    float *a = (float *)malloc(sizeof(float) * (size_t)(M > 0 ? M : 1) * (size_t)K);
+    float *w = (float *)malloc(sizeof(float) * (size_t)(N > 0 ? N : 1) * (size_t)K);
+    if (!a || !w) { free(a); free(w); return -1; }
+    for (int pass = 0; pass < 2; ++pass) {
+        int64_t        R  = pass ? N : M;
+        const uint8_t *q4 = pass ? w_q4 : a_q4, *q8 = pass ? w_q8 : a_q8;
+        float         *d  = pass ? w : a;
+        for (int64_t r = 0; r < R; ++r)
+            for (int32_t k = 0; k < K; ++k) {
+                if (k < K4) {
+                    uint8_t byte = q4[r * (K4 / 2) + k / 2];
+                    d[r * K + k] = atom_ref_e2m1_to_f32((k % 2) ? (byte >> 4) : (byte & 0xf));
+                } else {
+                    d[r * K + k] = atom_ref_e4m3_to_f32(q8[r * O + (k - K4)]);
+                }
+            }
+    }
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int32_t b = 0; b < NB; ++b) {
+                double p = 0.0;
+                for (int32_t t = 0; t < 32; ++t)
+                    p += (double)a[m * K + b * 32 + t] * (double)w[n * K + b * 32 + t];
+                acc += ldexp(p, (int)a_e8[m * NB + b] - 127 + (int)w_e8[n * NB + b] - 127);
+            }
+            y[m * ldy + n] = atom_ref_f32_to_f16((float)acc);
+        }
+    free(a);
+    free(w);
+    return 0;
+}

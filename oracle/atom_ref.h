@@ -146,6 +146,37 @@ int atom_ref_decode_attention_kv4(const uint16_t *q_f16, int32_t B, int32_t H,
                                   const int16_t *vz, float sm_scale,
                                   uint16_t *out_f16);
 
+/* ---- MX (microscaling) variant of the path.  The paper evaluates its recipe
+ * with FP4 codes and names the MX formats, whose group scaling is applied by
+ * the hardware (last paragraph of the accuracy evaluation, Section 5.2).  The
+ * reading taken: the reorder and the mixed precision stay; a block of 32
+ * reordered channels shares one power-of-two scale (E8M0 byte, 2^(byte-127));
+ * normal channels are FP4 E2M1 (magnitudes 0 .5 1 1.5 2 3 4 6, sign in bit 3),
+ * the O outlier channels FP8 E4M3 (bias 7, no infinity, largest 448), as the
+ * MX specification the paper cites defines them:
+ *   byte  = clamp(floor(log2(amax * clip)) - emax, -127, 127) + 127,
+ *           emax = 2 (E2M1) or 8 (E4M3); an all-zero block gives byte 0
+ *   code  = nearest representable of y / 2^(byte-127), ties to the even
+ *           mantissa, magnitudes beyond the largest saturate to it
+ * Layout: q4 [rows, K4/2] two codes per byte, even channel in the low nibble;
+ * q8 [rows, O] bytes; e8 [rows, K/32] bytes, FP4 blocks first.
+ * GEMM: Y[m,n] = fp16( sum_b 2^(ea[m,b]+ew[n,b]-254) * sum_{k in b} a*w ), all
+ * sums in double. */
+float   atom_ref_e2m1_to_f32(uint8_t code);
+float   atom_ref_e4m3_to_f32(uint8_t code);
+uint8_t atom_ref_f32_to_e2m1(float v);
+uint8_t atom_ref_f32_to_e4m3(float v);
+uint8_t atom_ref_mx_scale_byte(float clipped_amax, int emax);
+/* gamma == NULL: no norm (weights, or activations behind an activation function) */
+int atom_ref_mx_quantize_act(const uint16_t *x_f16, int64_t M, int64_t ldx,
+                             const uint16_t *gamma_f16, float eps,
+                             const int32_t *idx, int32_t K, int32_t O, float clip,
+                             uint8_t *q4, uint8_t *q8, uint8_t *e8);
+int atom_ref_mx_gemm(const uint8_t *a_q4, const uint8_t *a_q8, const uint8_t *a_e8,
+                     int64_t M, const uint8_t *w_q4, const uint8_t *w_q8,
+                     const uint8_t *w_e8, int64_t N, int32_t K, int32_t O,
+                     uint16_t *y_f16, int64_t ldy);
+
 #ifdef __cplusplus
 }
 #endif
