@@ -235,6 +235,56 @@ atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H,
 size_t atom_decode_attention_kv4_workspace_bytes(int32_t B, int32_t H,
                                                  int32_t D, int64_t Tmax);
 
+/*
+ * MX variant of the path.  The paper also runs its recipe with FP4 codes and
+ * names the MX formats, whose group scaling new hardware applies by itself and
+ * which it expects to remove the group-dequantisation overhead of the fused
+ * GEMM (Section 5.2, FP4 paragraph; overhead: Section 5.4.2).  On gfx950 that
+ * hardware is the scaled FP8/FP6/FP4 MFMA.  Reading taken here: reorder and
+ * mixed precision stay as they are; a block of 32 reordered channels shares one
+ * power-of-two scale (E8M0 byte, 2^(byte - 127)); the K4 = K - O normal
+ * channels are FP4 E2M1 (magnitudes 0 .5 1 1.5 2 3 4 6, sign in bit 3), the O
+ * outlier channels FP8 E4M3 (bias 7, largest 448, no infinity):
+ *   byte = clamp(floor(log2(amax * clip)) - emax, -127, 127) + 127, emax = 2
+ *          (E2M1) or 8 (E4M3); an all-zero block gives byte 0
+ *   code = nearest representable of y / 2^(byte - 127), ties to the even
+ *          mantissa, larger magnitudes saturate
+ * Results are bit-exact.  d->group_size must be 32, bits 4 / 8; K and O
+ * multiples of 128, 0 < O < K, K <= 32768.
+ *
+ *   x_f16, gamma_f16, eps, reorder_idx, clip: as atom_quantize_act
+ *   q4 [M, K4/2] two FP4 codes per byte, even reordered channel in the low
+ *   nibble; q8 [M, O] FP8 codes; e8 [M, K/32] scale bytes, FP4 blocks first
+ *   (q4, q8 16-byte aligned, e8 4-byte aligned)
+ * Errors as atom_quantize_act.
+ */
+atom_status atom_mx_quantize_act(const void *x_f16, int64_t M, int64_t ldx,
+                                 const void *gamma_f16, float eps,
+                                 const int32_t *reorder_idx, const atom_desc *d,
+                                 float clip, void *q4, void *q8, void *e8,
+                                 void *stream);
+
+/* Weights of the MX variant: reorder + quantisation of W[N, K], no norm. */
+atom_status atom_mx_quantize_weight(const void *w_f16, int64_t N, int64_t ldw,
+                                    const int32_t *reorder_idx,
+                                    const atom_desc *d, float clip, void *q4,
+                                    void *q8, void *e8, void *stream);
+
+/*
+ * GEMM of the MX variant:
+ *   Y[m, n] = fp16( sum_b 2^(ea[m,b] + ew[n,b] - 254) * sum_{k in block b} a[m,k] * w[n,k] )
+ * over all K/32 blocks, the block scaling applied by the matrix instruction
+ * itself, fp32 accumulation inside it (the order of its additions is the
+ * hardware's; the result is within the library's 1e-3 tolerance of the exact
+ * sum).  Operands as atom_mx_quantize_act / _weight produce them; Y [M, ldy]
+ * fp16, ldy >= N.  No workspace.
+ * Errors: ATOM_ERR_NULL, ATOM_ERR_SHAPE, ATOM_ERR_UNSUPPORTED, ATOM_ERR_ALIGN.
+ */
+atom_status atom_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8,
+                         int64_t M, const void *w_q4, const void *w_q8,
+                         const void *w_e8, int64_t N, const atom_desc *d,
+                         void *y_f16, int64_t ldy, void *stream);
+
 /* Host helper: ATOM_OK iff idx_host[0..K) is a permutation of 0..K-1. */
 atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K);
 

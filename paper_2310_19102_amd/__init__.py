@@ -13,6 +13,9 @@ from .binding import (  # noqa: F401
     atom_add_quantize_act,
     atom_swiglu_quantize_act,
     atom_quantize_weight,
+    atom_mx_quantize_act,
+    atom_mx_quantize_weight,
+    atom_mx_gemm,
     atom_kv_quantize,
     atom_decode_attention_kv4,
     atom_decode_attention_kv4_workspace_bytes,

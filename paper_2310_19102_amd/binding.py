@@ -22,6 +22,9 @@ EXPORTS = (
     "atom_quantize_weight",
     "atom_w4a4_gemm",
     "atom_w4a4_gemm_workspace_bytes",
+    "atom_mx_quantize_act",
+    "atom_mx_quantize_weight",
+    "atom_mx_gemm",
     "atom_kv_quantize",
     "atom_decode_attention_kv4",
     "atom_decode_attention_kv4_workspace_bytes",
@@ -71,6 +74,12 @@ def load_library():
     L.atom_w4a4_gemm_workspace_bytes.restype = sz
     L.atom_w4a4_gemm_workspace_bytes.argtypes = [i64, i64, dp]
     i32 = ctypes.c_int32
+    L.atom_mx_quantize_act.restype = ctypes.c_int
+    L.atom_mx_quantize_act.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, vp, vp, vp]
+    L.atom_mx_quantize_weight.restype = ctypes.c_int
+    L.atom_mx_quantize_weight.argtypes = [vp, i64, i64, vp, dp, f32, vp, vp, vp, vp]
+    L.atom_mx_gemm.restype = ctypes.c_int
+    L.atom_mx_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, dp, vp, i64, vp]
     L.atom_kv_quantize.restype = ctypes.c_int
     L.atom_kv_quantize.argtypes = [vp, i64, i64, i32, f32, vp, i32, i64, vp, vp, vp, vp]
     L.atom_decode_attention_kv4.restype = ctypes.c_int
@@ -363,4 +372,79 @@ def atom_decode_attention_kv4(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...]
                                      _ptr(workspace), ws_bytes, _stream())
     if st != 0:
         raise AtomError(st, "atom_decode_attention_kv4")
+    return out
+
+
+def _mx_outputs(rows: int, K: int, n_outlier: int, device):
+    q4 = torch.empty((rows, (K - n_outlier) // 2), dtype=torch.uint8, device=device)
+    q8 = torch.empty((rows, n_outlier), dtype=torch.uint8, device=device)
+    e8 = torch.empty((rows, K // 32), dtype=torch.uint8, device=device)
+    return q4, q8, e8
+
+
+def atom_mx_quantize_act(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float,
+                         reorder_idx: torch.Tensor, n_outlier: int = 128, clip: float = 1.0,
+                         out: Optional[Tuple[torch.Tensor, ...]] = None):
+    """MX variant of the front end: RMSNorm -> reorder -> FP4 E2M1 (normal channels) / FP8 E4M3
+    (outliers) with one E8M0 scale byte per 32 channels.  Returns ``(q4, q8, e8)``."""
+    L = load_library()
+    _dev(x, torch.float16, "x")
+    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if gamma is not None:
+        _dev(gamma, torch.float16, "gamma")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [M, K] with a contiguous last dimension")
+    M, K = x.shape
+    q4, q8, e8 = out if out is not None else _mx_outputs(M, K, n_outlier, x.device)
+    d = _Desc(K, 32, n_outlier, 4, 8)
+    st = L.atom_mx_quantize_act(_ptr(x), M, x.stride(0) if M > 1 else max(K, x.stride(0)), _ptr(gamma),
+                                eps, _ptr(reorder_idx), ctypes.byref(d), clip, _ptr(q4), _ptr(q8),
+                                _ptr(e8), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_mx_quantize_act")
+    return q4, q8, e8
+
+
+def atom_mx_quantize_weight(w: torch.Tensor, reorder_idx: torch.Tensor, n_outlier: int = 128,
+                            clip: float = 1.0, out: Optional[Tuple[torch.Tensor, ...]] = None):
+    """One-time reorder + MX quantisation of ``w`` [N, K] fp16."""
+    L = load_library()
+    _dev(w, torch.float16, "w")
+    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if w.dim() != 2 or w.stride(1) != 1:
+        raise ValueError("w must be [N, K] with a contiguous last dimension")
+    N, K = w.shape
+    q4, q8, e8 = out if out is not None else _mx_outputs(N, K, n_outlier, w.device)
+    d = _Desc(K, 32, n_outlier, 4, 8)
+    st = L.atom_mx_quantize_weight(_ptr(w), N, w.stride(0) if N > 1 else max(K, w.stride(0)),
+                                   _ptr(reorder_idx), ctypes.byref(d), clip, _ptr(q4), _ptr(q8),
+                                   _ptr(e8), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_mx_quantize_weight")
+    return q4, q8, e8
+
+
+def atom_mx_gemm(a_q4, a_q8, a_e8, w_q4, w_q8, w_e8, out: Optional[torch.Tensor] = None):
+    """Y[M, N] fp16 from the two MX-quantised operands; the block scales are applied by the
+    scaled MFMA instruction itself."""
+    L = load_library()
+    for t, nm in ((a_q4, "a_q4"), (a_q8, "a_q8"), (a_e8, "a_e8"), (w_q4, "w_q4"), (w_q8, "w_q8"),
+                  (w_e8, "w_e8")):
+        _dev(t, torch.uint8, nm)
+        if not t.is_contiguous():
+            raise ValueError(f"{nm} must be contiguous")
+    M, O = a_q8.shape
+    N = w_q8.shape[0]
+    K = a_q4.shape[1] * 2 + O
+    if w_q4.shape[1] != a_q4.shape[1] or w_q8.shape[1] != O or a_e8.shape[1] != K // 32 or w_e8.shape[1] != K // 32:
+        raise ValueError("activation and weight code shapes disagree")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=a_q4.device)
+    _dev(out, torch.float16, "out")
+    d = _Desc(K, 32, O, 4, 8)
+    st = L.atom_mx_gemm(_ptr(a_q4), _ptr(a_q8), _ptr(a_e8), M, _ptr(w_q4), _ptr(w_q8), _ptr(w_e8), N,
+                        ctypes.byref(d), _ptr(out), out.stride(0) if M > 1 else max(N, out.stride(0)),
+                        _stream())
+    if st != 0:
+        raise AtomError(st, "atom_mx_gemm")
     return out

@@ -194,6 +194,83 @@ size_t atom_decode_attention_kv4_workspace_bytes(int32_t B, int32_t H, int32_t D
     return atom_internal::decode_attention_workspace_bytes(B, H, Tmax);
 }
 
+}  // extern "C"
+
+namespace {
+
+atom_status check_desc_mx(const atom_desc *d)
+{
+    if (!d) return ATOM_ERR_NULL;
+    if (d->K <= 0 || d->group_size <= 0 || d->n_outlier < 0) return ATOM_ERR_SHAPE;
+    if (d->group_size != 32 || d->bits_normal != 4 || d->bits_outlier != 8) return ATOM_ERR_UNSUPPORTED;
+    if (d->K % 128 || d->n_outlier % 128 || d->n_outlier >= d->K) return ATOM_ERR_SHAPE;
+    if (d->n_outlier == 0 || d->K > atom_internal::kMaxK) return ATOM_ERR_UNSUPPORTED;
+    return ATOM_OK;
+}
+
+atom_status mx_quantize_common(const void *x, int64_t rows, int64_t ld, const void *gamma, float eps,
+                               const int32_t *idx, const atom_desc *d, float clip, void *q4, void *q8,
+                               void *e8, void *stream)
+{
+    atom_status st = check_desc_mx(d);
+    if (st != ATOM_OK) return st;
+    if (rows < 0 || ld < d->K) return ATOM_ERR_SHAPE;
+    if (rows == 0) return ATOM_OK;
+    if (!x || !idx || !q4 || !q8 || !e8) return ATOM_ERR_NULL;
+    if (!aligned(x, 16) || (ld % 8) || !aligned(idx, 16) || !aligned(q4, 16) || !aligned(q8, 16) ||
+        !aligned(e8, 4) || (gamma && !aligned(gamma, 16)))
+        return ATOM_ERR_ALIGN;
+    hipError_t err = atom_internal::launch_quantize_rows_mx(x, rows, ld, gamma, eps, idx, d->K,
+                                                            d->n_outlier, clip, q4, q8, e8,
+                                                            static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+atom_status atom_mx_quantize_act(const void *x_f16, int64_t M, int64_t ldx, const void *gamma_f16,
+                                 float eps, const int32_t *reorder_idx, const atom_desc *d, float clip,
+                                 void *q4, void *q8, void *e8, void *stream)
+{
+    return mx_quantize_common(x_f16, M, ldx, gamma_f16, eps, reorder_idx, d, clip, q4, q8, e8, stream);
+}
+
+atom_status atom_mx_quantize_weight(const void *w_f16, int64_t N, int64_t ldw,
+                                    const int32_t *reorder_idx, const atom_desc *d, float clip,
+                                    void *q4, void *q8, void *e8, void *stream)
+{
+    return mx_quantize_common(w_f16, N, ldw, nullptr, 0.0f, reorder_idx, d, clip, q4, q8, e8, stream);
+}
+
+atom_status atom_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8, int64_t M,
+                         const void *w_q4, const void *w_q8, const void *w_e8, int64_t N,
+                         const atom_desc *d, void *y_f16, int64_t ldy, void *stream)
+{
+    atom_status st = check_desc_mx(d);
+    if (st != ATOM_OK) return st;
+    if (M < 0 || N < 0 || ldy < N) return ATOM_ERR_SHAPE;
+    if (M == 0 || N == 0) return ATOM_OK;
+    if (!a_q4 || !a_q8 || !a_e8 || !w_q4 || !w_q8 || !w_e8 || !y_f16) return ATOM_ERR_NULL;
+    if (!aligned(a_q4, 16) || !aligned(a_q8, 16) || !aligned(a_e8, 4) || !aligned(w_q4, 16) ||
+        !aligned(w_q8, 16) || !aligned(w_e8, 4) || !aligned(y_f16, 2))
+        return ATOM_ERR_ALIGN;
+    // row offsets are kept in 32 bits inside the kernel
+    const int64_t pitch = (d->K - d->n_outlier) / 2 > d->n_outlier ? (d->K - d->n_outlier) / 2 : d->n_outlier;
+    if (M * pitch >= (int64_t)1 << 32 || N * pitch >= (int64_t)1 << 32) return ATOM_ERR_UNSUPPORTED;
+    const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    if (tiles > 0x7fffffffLL) return ATOM_ERR_UNSUPPORTED;
+    hipError_t err = atom_internal::launch_mx_gemm(a_q4, a_q8, a_e8, M, w_q4, w_q8, w_e8, N, d->K,
+                                                   d->n_outlier, y_f16, ldy,
+                                                   static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
+}  // extern "C"
+
+extern "C" {
+
 atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K)
 {
     if (!idx_host) return ATOM_ERR_NULL;

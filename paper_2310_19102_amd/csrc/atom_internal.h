@@ -33,6 +33,15 @@ struct GemmArgs {
 size_t     gemm_workspace_bytes(int64_t M, int64_t N, int K, int O);
 hipError_t launch_w4a4_gemm(const GemmArgs &a, hipStream_t stream);
 
+// MX variant: front end (FP4 / FP8 codes, E8M0 scale byte per 32 channels) and GEMM on the
+// scaled FP8/FP6/FP4 MFMA.
+hipError_t launch_quantize_rows_mx(const void *x, int64_t rows, int64_t ld, const void *gamma,
+                                   float eps, const int32_t *idx, int K, int O, float clip, void *q4,
+                                   void *q8, void *e8, hipStream_t stream);
+hipError_t launch_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8, int64_t M,
+                          const void *w_q4, const void *w_q8, const void *w_e8, int64_t N, int K,
+                          int O, void *y, int64_t ldy, hipStream_t stream);
+
 // KV cache: asymmetric INT4 rows of D = 64 or 128 values; decode attention over the cache.
 hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, float clip,
                               const int32_t *pos, int32_t rows_per_seq, int64_t Tmax, void *q,

@@ -104,7 +104,7 @@ __device__ __forceinline__ float row16_max(float v)
 // PRE = kAdd: x is first added to a residual row and the sum (fp16) is written out; x, res
 // and sum_out may alias each other (every element is read and written by the same thread).
 // PRE = kSwiglu: the row is silu(x) * res.
-template <bool NORM, int PRE>
+template <bool NORM, int PRE, bool MX = false>
 __global__ __launch_bounds__(kThreads)
 void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
                           const __half *res, int64_t ldr, __half *sum_out, int64_t ldo,
@@ -194,9 +194,50 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
                 y[e] = ybuf[min((unsigned)id[e], (unsigned)(K - 1))];
                 amax = fmaxf(amax, fabsf(y[e]));
             }
+            const bool  is4   = gg < G4;
+            if constexpr (MX) {
+                // MX variant: the 16 lanes hold four blocks of 32 channels (4 lanes each);
+                // one power-of-two scale per block, FP4 E2M1 or FP8 E4M3 elements
+                amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
+                amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
+                const float a = amax * clip;
+                int byte = 0;
+                if (a > 0.0f) {
+                    int E = (__builtin_amdgcn_frexp_expf(a) - 1) - (is4 ? 2 : 8);   // floor(log2 a) - emax
+                    E = E < -127 ? -127 : (E > 127 ? 127 : E);
+                    byte = E + 127;
+                }
+                uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float    v    = __builtin_amdgcn_ldexpf(y[e], 127 - byte);   // exact
+                    const uint32_t sign = __float_as_uint(v) >> 31;
+                    const float    m    = fabsf(v);
+                    if (is4) {
+                        const uint32_t c = (uint32_t)(m > 0.25f) + (m >= 0.75f) + (m > 1.25f) + (m >= 1.75f) +
+                                           (m > 2.5f) + (m >= 3.5f) + (m > 5.0f);
+                        w0 |= (c | (sign << 3)) << (4 * e);
+                    } else {
+                        const float    t = fminf(m, 448.0f);
+                        const uint32_t u = __float_as_uint(t);
+                        // below 2^-6: multiples of 2^-9; above: round the mantissa to 3 bits, ties to even
+                        const uint32_t c = t < 0.015625f ? (uint32_t)rintf(t * 512.0f)
+                                                         : ((u + 0x7FFFFu + ((u >> 20) & 1u)) >> 20) - 960u;
+                        const uint32_t b = c | (sign << 7);
+                        if (e < 4) w0 |= b << (8 * e);
+                        else       w1 |= b << (8 * (e - 4));
+                    }
+                }
+                if (live) {
+                    if (is4) *reinterpret_cast<uint32_t *>(q4 + row * (int64_t)(K4 >> 1) + (j0 >> 1)) = w0;
+                    else     *reinterpret_cast<uint2 *>(q8 + row * (int64_t)O + (j0 - K4)) = make_uint2(w0, w1);
+                    if ((lane & 3) == 0)
+                        reinterpret_cast<uint8_t *>(scale)[row * (int64_t)(K >> 5) + (j0 >> 5)] = (uint8_t)byte;
+                }
+                continue;
+            }
             amax = row16_max(amax);
 
-            const bool  is4   = gg < G4;
             const float denom = is4 ? 15.0f : 255.0f;
             const float qmin  = is4 ? -8.0f : -128.0f;
             const float qmax  = is4 ? 7.0f : 127.0f;
@@ -531,6 +572,29 @@ hipError_t dispatch_quantize(const QuantArgs &a, hipStream_t stream)
         return launch_fast<NORM, 4, 512, PRE>(a, lds, stream);
     }
     return launch_plain<NORM, PRE>(a, lds, stream);
+}
+
+// MX variant of the front end (FP4 / FP8 elements, one E8M0 scale byte per 32 channels in e8).
+hipError_t launch_quantize_rows_mx(const void *x, int64_t rows, int64_t ld, const void *gamma,
+                                   float eps, const int32_t *idx, int K, int O, float clip, void *q4,
+                                   void *q8, void *e8, hipStream_t stream)
+{
+    const bool   norm = gamma != nullptr;
+    const size_t lds  = quantize_lds_bytes(K, norm);
+    auto kern = norm ? &quantize_rows_kernel<true, kPlain, true> : &quantize_rows_kernel<false, kPlain, true>;
+    static size_t allowed[2] = {0, 0};
+    if (lds > allowed[norm]) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return err;
+        allowed[norm] = lds;
+    }
+    const int grid = (int)(rows < (int64_t)1 << 20 ? rows : (int64_t)1 << 20);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, (const __half *)x, rows, ld,
+                       (const __half *)nullptr, (int64_t)0, (__half *)nullptr, (int64_t)0,
+                       (const __half *)gamma, eps, idx, K, O, clip, (uint8_t *)q4, (int8_t *)q8,
+                       (__half *)e8);
+    return hipGetLastError();
 }
 
 hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, int pre, const void *res,
