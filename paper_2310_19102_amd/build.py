@@ -30,6 +30,11 @@ FLAGS = [
 ]
 
 
+# per-source overrides: the MX GEMM never touches its accumulators with the vector ALU inside the
+# K loop, so its 256 accumulator registers per lane belong in the AccVGPRs
+SOURCE_FLAGS = {"atom_mx.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=0"]}
+
+
 def build(verbose: bool = False, extra_flags=(), lib: str = LIB, tag: str = "") -> str:
     """Compile every kernel file and link ``libatom.so`` next to this module."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -37,7 +42,7 @@ def build(verbose: bool = False, extra_flags=(), lib: str = LIB, tag: str = "") 
     procs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, src.replace(".hip", tag + ".o"))
-        cmd = [hipcc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *SOURCE_FLAGS.get(src, []), *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))

@@ -19,6 +19,8 @@
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "atom_gemm_common.h"
 #include "atom_internal.h"
 
@@ -29,9 +31,10 @@ typedef int   v8i  __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 256, BN = 256;         // workgroup tile
-constexpr int NT = 512;                   // 8 wavefronts: 4 (rows of 64) x 2 (columns of 128)
+constexpr int NT = 256;                   // 4 wavefronts, 2 x 2, each 128 x 128 (4 x 4 MFMA tiles)
 constexpr int ROWB = 64;                  // bytes per tile row and K step: 128 FP4 or 64 FP8 channels
 constexpr int STAGE = (BM + BN) * ROWB;   // 32 KB
+constexpr int NLD = STAGE / 16 / NT;      // 16-byte chunks per thread and step (8)
 
 struct MxParams {
     const uint8_t *a_q4, *a_q8, *a_e8;
@@ -66,10 +69,12 @@ __device__ __forceinline__ v8i join(v4i lo, v4i hi)
 }
 
 // One K step per iteration: 64 bytes of every tile row, i.e. 128 FP4 channels (two MFMA
-// sub-steps) or 64 FP8 channels (one).  Global -> registers -> LDS with two LDS stages:
-// while step u is multiplied, step u+1 sits in the other stage and step u+2 is on its way
-// into registers; one barrier per step.
-__global__ __launch_bounds__(NT)
+// sub-steps) or 64 FP8 channels (one).  One wavefront per SIMD: the 16 accumulator tiles of a
+// wavefront (256 registers) live in the accumulation registers, everything else in the
+// architectural ones.  Global -> registers -> LDS with two LDS stages: while step u is
+// multiplied, step u+1 sits in the other stage and step u+2 is on its way into registers;
+// one barrier per step.
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void mx_gemm_kernel(MxParams p)
 {
     extern __shared__ __align__(16) uint8_t smem[];
@@ -85,154 +90,205 @@ void mx_gemm_kernel(MxParams p)
     const int K4 = p.K - p.O, NB = p.K >> 5;
     const int S4 = K4 >> 7, S8 = p.O >> 6, S = S4 + S8;
 
-    // ---- loader: chunk id = tid + NT * i, row = id / 4 (A rows first), chunk = id % 4 = tid % 4;
-    // 32-bit row numbers and offsets keep the addressing in few registers
+    // ---- loader: chunk id = tid + NT * i, row = id / 4 (A rows first), chunk = tid % 4
     const int ch = tid & 3;
-    uint32_t lrow[4];
-    int dst[4];
+    uint32_t off4[NLD], off8[NLD];                                 // byte offsets of the rows
+    int dst[NLD];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = (tid + NT * i) >> 2;                       // i < 2: A rows, else B rows
-        int64_t r = i < 2 ? m0 + row : n0 + (row - BM);
-        const int64_t last = (i < 2 ? p.M : p.N) - 1;
-        lrow[i] = (uint32_t)(r < last ? r : last);                 // ragged tiles repeat the last row
+    for (int i = 0; i < NLD; ++i) {
+        const int row = (tid + NT * i) >> 2;                       // i < NLD / 2: A rows, else B rows
+        int64_t r = i < NLD / 2 ? m0 + row : n0 + (row - BM);
+        const int64_t last = (i < NLD / 2 ? p.M : p.N) - 1;
+        r = r < last ? r : last;                                   // ragged tiles repeat the last row
+        off4[i] = (uint32_t)r * (uint32_t)(K4 >> 1) + 16u * ch;
+        off8[i] = (uint32_t)r * (uint32_t)p.O + 16u * ch;
         dst[i]  = mx_lds_off(row, ch);
     }
-    auto fetch = [&](int u, uint4 (&v)[4]) {
-        const bool f4 = u < S4;
-        const uint32_t pitch = f4 ? (uint32_t)(K4 >> 1) : (uint32_t)p.O;
-        const uint32_t col   = (uint32_t)(f4 ? u : u - S4) * ROWB + 16u * ch;
+    auto fetch = [&](int u, v4i (&v)[NLD]) __attribute__((always_inline)) {
+        const bool     f4  = u < S4;
+        const uint32_t col = (uint32_t)(f4 ? u : u - S4) * ROWB;
+        const uint8_t *pa = f4 ? p.a_q4 : p.a_q8, *pw = f4 ? p.w_q4 : p.w_q8;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint8_t *base = i < 2 ? (f4 ? p.a_q4 : p.a_q8) : (f4 ? p.w_q4 : p.w_q8);
-            v[i] = *reinterpret_cast<const uint4 *>(base + ((uint64_t)lrow[i] * pitch + col));
-        }
+        for (int i = 0; i < NLD; ++i)
+            v[i] = *reinterpret_cast<const v4i *>((i < NLD / 2 ? pa : pw) + ((f4 ? off4[i] : off8[i]) + col));
     };
-    auto stage = [&](int buf, const uint4 (&v)[4]) {
+    auto stage = [&](int buf, const v4i (&v)[NLD]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(smem + buf * STAGE + dst[i]) = v[i];
+        for (int i = 0; i < NLD; ++i) *reinterpret_cast<v4i *>(smem + buf * STAGE + dst[i]) = v[i];
     };
 
-    // ---- scales: one dword (four blocks) per row and per FP4 step or pair of FP8 steps,
-    // shifted at load time so that the lane's own block of a sub-step sits in byte 0 or 2
-    uint32_t ea[2], eb[4];                                          // byte offsets of the rows' scale lines
+    // ---- scales: one dword (four blocks) per row and per FP4 step or pair of FP8 steps; when
+    // it becomes the current one (a step after its load, so nothing waits on memory) it is
+    // shifted so that the lane's own block of a sub-step sits in byte 0 or 2
+    uint32_t ea[4], eb[4];                                          // byte offsets of the rows' scale lines
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        int64_t r = m0 + 64 * wm + 32 * s + lr;
+    for (int s = 0; s < 4; ++s) {
+        int64_t r = m0 + 128 * wm + 32 * s + lr;
         r = r < p.M - 1 ? r : p.M - 1;
         ea[s] = (uint32_t)r * (uint32_t)NB;
-    }
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        int64_t r = n0 + 128 * wn + 32 * t + lr;
+        r = n0 + 128 * wn + 32 * s + lr;
         r = r < p.N - 1 ? r : p.N - 1;
-        eb[t] = (uint32_t)r * (uint32_t)NB;
+        eb[s] = (uint32_t)r * (uint32_t)NB;
     }
-    auto fetch_scales = [&](int u, int (&sa)[2], int (&sb)[4]) {
+    auto fetch_scales = [&](int u, int (&sa)[4], int (&sb)[4]) __attribute__((always_inline)) {
         // dword index of step u: FP4 step u -> u; FP8 steps 2j, 2j+1 -> S4 + j
         const uint32_t dw = 4u * (uint32_t)(u < S4 ? u : S4 + ((u - S4) >> 1));
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
-            sa[s] = (int)(*reinterpret_cast<const uint32_t *>(p.a_e8 + (ea[s] + dw)) >> (8 * g));
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-            sb[t] = (int)(*reinterpret_cast<const uint32_t *>(p.w_e8 + (eb[t] + dw)) >> (8 * g));
+        for (int s = 0; s < 4; ++s) {
+            sa[s] = (int)*reinterpret_cast<const uint32_t *>(p.a_e8 + (ea[s] + dw));
+            sb[s] = (int)*reinterpret_cast<const uint32_t *>(p.w_e8 + (eb[s] + dw));
+        }
     };
 
-    v16f acc[2][4];
+    v16f acc[4][4];
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+    for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[s][t][v] = 0.0f;
 
-    // fragment addresses: A rows 64 wm + 32 s + lr, B rows BM + 128 wn + 32 t + lr.  Rows 32
+    // fragment addresses: A rows 128 wm + 32 s + lr, B rows BM + 128 wn + 32 t + lr.  Rows 32
     // apart rotate alike, so sub-tiles are a constant 2048 bytes apart; chunk c + 2 is the
     // xor of chunk c's offset with 32.
-    const int a_base = mx_lds_off(64 * wm + lr, g);
+    const int a_base = mx_lds_off(128 * wm + lr, g);
     const int b_base = mx_lds_off(BM + 128 * wn + lr, g);
 
-    uint4 regs[4];
-    int sa[2], sb[4], sa_nxt[2] = {0, 0}, sb_nxt[4] = {0, 0, 0, 0};
+    v4i regs[NLD];
+    // scales: current step (shifted) and next step (raw dwords, loaded a whole step before
+    // they are shifted, straight into the registers the previous set has just left)
+    int sa[4], sb[4], sa_nxt[4] = {0, 0, 0, 0}, sb_nxt[4] = {0, 0, 0, 0};
     fetch(0, regs);
-    fetch_scales(0, sa, sb);
+    fetch_scales(0, sa_nxt, sb_nxt);
     stage(0, regs);
-    if (S > 1) fetch(1, regs);
+    fetch(min(1, S - 1), regs);
     __syncthreads();
 
-    for (int u = 0; u < S; ++u) {
-        const uint8_t *buf = smem + (u & 1) * STAGE;
-        if (u + 1 < S) {
-            stage((u + 1) & 1, regs);                     // that stage was last read in step u-1
-            fetch_scales(u + 1, sa_nxt, sb_nxt);
+    // 16 MFMAs on one set of fragments; format and scale byte are compile-time
+    auto mma16 = [&](auto fmt, auto opsel, const v8i (&af)[4], const v8i (&bf)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                acc[s][t] = mfma_mx<decltype(fmt)::value, decltype(opsel)::value>(af[s], bf[t], acc[s][t],
+                                                                                  sa[s], sb[t]);
+    };
+    // top of step u: step u+1 goes from registers into the other stage (last read in step
+    // u-1, before that step's barrier), step u+2 leaves global memory.  Nothing here is
+    // conditional (the last steps stage and fetch data nobody reads): with one path through the
+    // loop the compiler's wait counts let the loads of a whole step stay in flight.
+    // (a macro rather than a lambda that captures the lambdas above: closures nested that way
+    // keep the register arrays in scratch memory)
+#define ATOM_MX_ADVANCE(u)                                                                       \
+    do {                                                                                         \
+        stage(((u) + 1) & 1, regs);                                                              \
+        fetch(min((u) + 2, S - 1), regs);                                                        \
+    } while (0)
+    // end of step u: the next step's scales become current, the ones of step u+2 are requested
+    auto next_scales = [&](int u) __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);                // keep the use a whole step behind the load
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            sa[s] = (int)((unsigned)sa_nxt[s] >> (8 * g));
+            sb[s] = (int)((unsigned)sb_nxt[s] >> (8 * g));
         }
-        if (u + 2 < S) fetch(u + 2, regs);
+        fetch_scales(min(u + 2, S - 1), sa_nxt, sb_nxt);
+    };
+    next_scales(-1);                      // the scales of step 0 (and the request for step 1)
+    using fp4 = std::integral_constant<int, 4>;
+    using fp8 = std::integral_constant<int, 0>;
+    using b0  = std::integral_constant<int, 0>;
+    using b2  = std::integral_constant<int, 2>;
 
-        if (u < S4) {
-            // two sub-steps of 64 FP4 channels: bytes [0,32) and [32,64) of the row, the lane
-            // takes chunk 2 k + g
+    // ---- FP4 steps: two sub-steps of 64 channels, bytes [0,32) and [32,64) of the row; the
+    // lane takes chunk 2 k + g.  Software pipeline: the second sub-step's fragments are read
+    // under the first sub-step's MFMAs, the next step's first fragments under the second's
+    // (the barrier that publishes the next stage sits between the two).
+    v8i af[4], bf[4];
 #pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                v8i af[2], bf[4];
+    for (int s = 0; s < 4; ++s) {
+        af[s] = widen(*reinterpret_cast<const v4i *>(smem + (a_base + 2048 * s)));
+        bf[s] = widen(*reinterpret_cast<const v4i *>(smem + (b_base + 2048 * s)));
+    }
+    for (int u = 0; u < S4; ++u) {
+        const uint8_t *buf = smem + (u & 1) * STAGE, *nbuf = smem + ((u + 1) & 1) * STAGE;
+        ATOM_MX_ADVANCE(u);
+        v8i ag[4], bg[4];
 #pragma unroll
-                for (int s = 0; s < 2; ++s)
-                    af[s] = widen(*reinterpret_cast<const v4i *>(buf + ((a_base ^ (32 * k)) + 2048 * s)));
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    bf[t] = widen(*reinterpret_cast<const v4i *>(buf + ((b_base ^ (32 * k)) + 2048 * t)));
-#pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int t = 0; t < 4; ++t)
-                        acc[s][t] = k == 0 ? mfma_mx<4, 0>(af[s], bf[t], acc[s][t], sa[s], sb[t])
-                                           : mfma_mx<4, 2>(af[s], bf[t], acc[s][t], sa[s], sb[t]);
-            }
-        } else {
-            // one step of 64 FP8 channels: the lane's low 16 bytes are chunk g (block 0 of the
-            // step), its high 16 bytes chunk 2 + g (block 1); it carries the scale of block g,
-            // byte 2 (u8 & 1) + g of the pair's dword.  Two halves of the columns at a time to
-            // keep the fragments in few registers.
-            const bool odd = (u - S4) & 1;
-            v8i af[2];
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-                af[s] = join(*reinterpret_cast<const v4i *>(buf + (a_base + 2048 * s)),
-                             *reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));
-#pragma unroll
-            for (int th = 0; th < 2; ++th) {
-                v8i bf[2];
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-                    bf[t] = join(*reinterpret_cast<const v4i *>(buf + (b_base + 2048 * (2 * th + t))),
-                                 *reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * (2 * th + t))));
-#pragma unroll
-                for (int s = 0; s < 2; ++s)
-#pragma unroll
-                    for (int t = 0; t < 2; ++t)
-                        acc[s][2 * th + t] =
-                            odd ? mfma_mx<0, 2>(af[s], bf[t], acc[s][2 * th + t], sa[s], sb[2 * th + t])
-                                : mfma_mx<0, 0>(af[s], bf[t], acc[s][2 * th + t], sa[s], sb[2 * th + t]);
-            }
+        for (int s = 0; s < 4; ++s) {
+            ag[s] = widen(*reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));
+            bg[s] = widen(*reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * s)));
         }
+        mma16(fp4{}, b0{}, af, bf);
 #pragma unroll
-        for (int s = 0; s < 2; ++s) sa[s] = sa_nxt[s];
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);    // two MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // one LDS read
+        }
+        __syncthreads();                  // stage u+1 is complete, stage u has been read
+        // (after the last FP4 step these reads fetch FP8 bytes that are not used)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) sb[t] = sb_nxt[t];
+        for (int s = 0; s < 4; ++s) {
+            af[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (a_base + 2048 * s)));
+            bf[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (b_base + 2048 * s)));
+        }
+        mma16(fp4{}, b2{}, ag, bg);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 1);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+        }
+        next_scales(u);
+    }
+    auto finish = [&](int u) __attribute__((always_inline)) {
+        next_scales(u);
         __syncthreads();
+    };
+    // ---- FP8 steps, in pairs (64 channels each): the lane's low 16 bytes are chunk g (block 0
+    // of the step), its high 16 bytes chunk 2 + g (block 1); it carries the scale of block g,
+    // byte 2 (step & 1) + g of the pair's dword
+    auto load8 = [&](const uint8_t *buf, v8i (&af)[4], v8i (&bf)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            af[s] = join(*reinterpret_cast<const v4i *>(buf + (a_base + 2048 * s)),
+                         *reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));
+            bf[s] = join(*reinterpret_cast<const v4i *>(buf + (b_base + 2048 * s)),
+                         *reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * s)));
+        }
+    };
+    for (int u = S4; u < S; u += 2) {
+        {
+            ATOM_MX_ADVANCE(u);
+            v8i af[4], bf[4];
+            load8(smem + (u & 1) * STAGE, af, bf);
+            mma16(fp8{}, b0{}, af, bf);
+            finish(u);
+        }
+        {
+            ATOM_MX_ADVANCE(u + 1);
+            v8i af[4], bf[4];
+            load8(smem + ((u + 1) & 1) * STAGE, af, bf);
+            mma16(fp8{}, b2{}, af, bf);
+            finish(u + 1);
+        }
     }
 
-    // ---- store: lane holds column lr of sub-tile t, rows 8 (v / 4) + 4 g + v % 4 of sub-tile s
+#undef ATOM_MX_ADVANCE
+
+    // ---- store: lane holds column lr of sub-tile t, rows 8 (v / 4) + 4 g + v % 4 of sub-tile s;
+    // one lane-dependent offset, everything else wavefront-uniform
+    const int64_t row0 = m0 + 128 * wm + 4 * g, col0 = n0 + 128 * wn + lr;
+    uint16_t *yp = p.y + row0 * p.ldy + col0;
 #pragma unroll
-    for (int s = 0; s < 2; ++s)
+    for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int64_t col = n0 + 128 * wn + 32 * t + lr;
+        for (int v = 0; v < 16; ++v) {
+            const int dr = 32 * s + 8 * (v >> 2) + (v & 3);
+            if (row0 + dr < p.M) {
+                uint16_t *yr = yp + (int64_t)dr * p.ldy;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t row = m0 + 64 * wm + 32 * s + 8 * (v >> 2) + 4 * g + (v & 3);
-                if (row < p.M && col < p.N)
-                    p.y[row * p.ldy + col] = __half_as_ushort(__float2half_rn(acc[s][t][v]));
+                for (int t = 0; t < 4; ++t)
+                    if (col0 + 32 * t < p.N) yr[32 * t] = __half_as_ushort(__float2half_rn(acc[s][t][v]));
             }
         }
 }
