@@ -253,9 +253,15 @@ size_t atom_decode_attention_kv4_workspace_bytes(int32_t B, int32_t H,
  * multiples of 128, 0 < O < K, K <= 32768.
  *
  *   x_f16, gamma_f16, eps, reorder_idx, clip: as atom_quantize_act
- *   q4 [M, K4/2] two FP4 codes per byte, even reordered channel in the low
- *   nibble; q8 [M, O] FP8 codes; e8 [M, K/32] scale bytes, FP4 blocks first
- *   (q4, q8 16-byte aligned, e8 4-byte aligned)
+ * Layout (step-major, so that the GEMM streams whole cache lines): with M the
+ * number of rows of the call,
+ *   q4 [K4/128, M, 64] bytes: 128 reordered channels of a row per 64 bytes, two
+ *      FP4 codes per byte, even channel in the low nibble
+ *   q8 [O/64, M, 64] bytes: 64 outlier channels of a row, one FP8 code each
+ *   e8 [K/128, M, 4] bytes: the four scale bytes of 128 channels of a row, FP4
+ *      blocks first
+ *   (q4, q8 16-byte aligned, e8 4-byte aligned).  The arrays of one call belong
+ *   to that call's M rows as a whole; a GEMM takes them as produced.
  * Errors as atom_quantize_act.
  */
 atom_status atom_mx_quantize_act(const void *x_f16, int64_t M, int64_t ldx,

@@ -376,9 +376,10 @@ def atom_decode_attention_kv4(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...]
 
 
 def _mx_outputs(rows: int, K: int, n_outlier: int, device):
-    q4 = torch.empty((rows, (K - n_outlier) // 2), dtype=torch.uint8, device=device)
-    q8 = torch.empty((rows, n_outlier), dtype=torch.uint8, device=device)
-    e8 = torch.empty((rows, K // 32), dtype=torch.uint8, device=device)
+    # step-major: [K step][row][64 bytes], scales [128-channel slab][row][4 bytes]
+    q4 = torch.empty(((K - n_outlier) // 128, rows, 64), dtype=torch.uint8, device=device)
+    q8 = torch.empty((n_outlier // 64, rows, 64), dtype=torch.uint8, device=device)
+    e8 = torch.empty((K // 128, rows, 4), dtype=torch.uint8, device=device)
     return q4, q8, e8
 
 
@@ -433,10 +434,13 @@ def atom_mx_gemm(a_q4, a_q8, a_e8, w_q4, w_q8, w_e8, out: Optional[torch.Tensor]
         _dev(t, torch.uint8, nm)
         if not t.is_contiguous():
             raise ValueError(f"{nm} must be contiguous")
-    M, O = a_q8.shape
-    N = w_q8.shape[0]
-    K = a_q4.shape[1] * 2 + O
-    if w_q4.shape[1] != a_q4.shape[1] or w_q8.shape[1] != O or a_e8.shape[1] != K // 32 or w_e8.shape[1] != K // 32:
+    if a_q4.dim() != 3 or a_q8.dim() != 3 or w_q4.dim() != 3 or w_q8.dim() != 3:
+        raise ValueError("operands must be the step-major arrays atom_mx_quantize_* produce")
+    M, N = a_q8.shape[1], w_q8.shape[1]
+    O = a_q8.shape[0] * 64
+    K = a_q4.shape[0] * 128 + O
+    if (w_q4.shape[0] != a_q4.shape[0] or w_q8.shape[0] != a_q8.shape[0] or a_q4.shape[1] != M
+            or w_q4.shape[1] != N or tuple(a_e8.shape) != (K // 128, M, 4) or tuple(w_e8.shape) != (K // 128, N, 4)):
         raise ValueError("activation and weight code shapes disagree")
     if out is None:
         out = torch.empty((M, N), dtype=torch.float16, device=a_q4.device)

@@ -256,9 +256,7 @@ atom_status atom_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8, i
     if (!aligned(a_q4, 16) || !aligned(a_q8, 16) || !aligned(a_e8, 4) || !aligned(w_q4, 16) ||
         !aligned(w_q8, 16) || !aligned(w_e8, 4) || !aligned(y_f16, 2))
         return ATOM_ERR_ALIGN;
-    // row offsets are kept in 32 bits inside the kernel
-    const int64_t pitch = (d->K - d->n_outlier) / 2 > d->n_outlier ? (d->K - d->n_outlier) / 2 : d->n_outlier;
-    if (M * pitch >= (int64_t)1 << 32 || N * pitch >= (int64_t)1 << 32) return ATOM_ERR_UNSUPPORTED;
+    if (M >= (int64_t)1 << 26 || N >= (int64_t)1 << 26) return ATOM_ERR_UNSUPPORTED;   // 32-bit row offsets
     const int64_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
     if (tiles > 0x7fffffffLL) return ATOM_ERR_UNSUPPORTED;
     hipError_t err = atom_internal::launch_mx_gemm(a_q4, a_q8, a_e8, M, w_q4, w_q8, w_e8, N, d->K,

@@ -68,8 +68,8 @@ __device__ __forceinline__ v8i join(v4i lo, v4i hi)
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
-// One K step per iteration: 64 bytes of every tile row, i.e. 128 FP4 channels (two MFMA
-// sub-steps) or 64 FP8 channels (one).  One wavefront per SIMD: the 16 accumulator tiles of a
+// One K step per iteration: 64 bytes of every tile row, i.e. 64 FP8 channels (one MFMA per
+// tile pair; these outlier steps come first) or 128 FP4 channels (two MFMA sub-steps).  One wavefront per SIMD: the 16 accumulator tiles of a
 // wavefront (256 registers) live in the accumulation registers, everything else in the
 // architectural ones.  Global -> registers -> LDS with two LDS stages: while step u is
 // multiplied, step u+1 sits in the other stage and step u+2 is on its way into registers;
@@ -87,12 +87,14 @@ void mx_gemm_kernel(MxParams p)
     const int bid = atom_gemm::xcd_contiguous_block_id();
     const int64_t m0 = (int64_t)(bid % tiles_m) * BM, n0 = (int64_t)(bid / tiles_m) * BN;
 
-    const int K4 = p.K - p.O, NB = p.K >> 5;
+    const int K4 = p.K - p.O;
     const int S4 = K4 >> 7, S8 = p.O >> 6, S = S4 + S8;
 
-    // ---- loader: chunk id = tid + NT * i, row = id / 4 (A rows first), chunk = tid % 4
+    // ---- loader: chunk id = tid + NT * i, row = id / 4 (A rows first), chunk = tid % 4.  The
+    // operands are stored step-major ([step][row][64 bytes]), so a step's 64 bytes of 16
+    // consecutive rows are one contiguous kilobyte and every cache line that is fetched is used.
     const int ch = tid & 3;
-    uint32_t off4[NLD], off8[NLD];                                 // byte offsets of the rows
+    uint32_t off[NLD];                                             // byte offset inside a step's slab
     int dst[NLD];
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
@@ -100,43 +102,47 @@ void mx_gemm_kernel(MxParams p)
         int64_t r = i < NLD / 2 ? m0 + row : n0 + (row - BM);
         const int64_t last = (i < NLD / 2 ? p.M : p.N) - 1;
         r = r < last ? r : last;                                   // ragged tiles repeat the last row
-        off4[i] = (uint32_t)r * (uint32_t)(K4 >> 1) + 16u * ch;
-        off8[i] = (uint32_t)r * (uint32_t)p.O + 16u * ch;
-        dst[i]  = mx_lds_off(row, ch);
+        off[i] = (uint32_t)r * ROWB + 16u * ch;
+        dst[i] = mx_lds_off(row, ch);
     }
+    // steps 0 .. S8-1 are the FP8 (outlier) steps, the FP4 steps follow: S8 is even, so the
+    // parity of a step is known at compile time wherever the two-step unrolling needs it
     auto fetch = [&](int u, v4i (&v)[NLD]) __attribute__((always_inline)) {
-        const bool     f4  = u < S4;
-        const uint32_t col = (uint32_t)(f4 ? u : u - S4) * ROWB;
-        const uint8_t *pa = f4 ? p.a_q4 : p.a_q8, *pw = f4 ? p.w_q4 : p.w_q8;
+        const bool    f8 = u < S8;
+        const int64_t sl = f8 ? u : u - S8;                        // slab index inside q8 or q4
+        const uint8_t *pa = (f8 ? p.a_q8 : p.a_q4) + sl * p.M * ROWB;
+        const uint8_t *pw = (f8 ? p.w_q8 : p.w_q4) + sl * p.N * ROWB;
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
-            v[i] = *reinterpret_cast<const v4i *>((i < NLD / 2 ? pa : pw) + ((f4 ? off4[i] : off8[i]) + col));
+            v[i] = *reinterpret_cast<const v4i *>((i < NLD / 2 ? pa : pw) + off[i]);
     };
     auto stage = [&](int buf, const v4i (&v)[NLD]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NLD; ++i) *reinterpret_cast<v4i *>(smem + buf * STAGE + dst[i]) = v[i];
     };
 
-    // ---- scales: one dword (four blocks) per row and per FP4 step or pair of FP8 steps; when
-    // it becomes the current one (a step after its load, so nothing waits on memory) it is
-    // shifted so that the lane's own block of a sub-step sits in byte 0 or 2
-    uint32_t ea[4], eb[4];                                          // byte offsets of the rows' scale lines
+    // ---- scales: one dword (four blocks) per row and per 128 channels, i.e. per FP4 step or
+    // pair of FP8 steps, stored [K / 128][rows]; when it becomes the current one (a step after
+    // its load, so nothing waits on memory) it is shifted so that the lane's own block of a
+    // sub-step sits in byte 0 or 2
+    uint32_t ea[4], eb[4];                                          // byte offsets of the rows
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         int64_t r = m0 + 128 * wm + 32 * s + lr;
         r = r < p.M - 1 ? r : p.M - 1;
-        ea[s] = (uint32_t)r * (uint32_t)NB;
+        ea[s] = (uint32_t)r * 4u;
         r = n0 + 128 * wn + 32 * s + lr;
         r = r < p.N - 1 ? r : p.N - 1;
-        eb[s] = (uint32_t)r * (uint32_t)NB;
+        eb[s] = (uint32_t)r * 4u;
     }
-    auto fetch_scales = [&](int u, int (&sa)[4], int (&sb)[4]) __attribute__((always_inline)) {
-        // dword index of step u: FP4 step u -> u; FP8 steps 2j, 2j+1 -> S4 + j
-        const uint32_t dw = 4u * (uint32_t)(u < S4 ? u : S4 + ((u - S4) >> 1));
+    auto fetch_scales = [&](int u, int (&sa_)[4], int (&sb_)[4]) __attribute__((always_inline)) {
+        // dword slab of step u: FP8 steps 2j, 2j+1 -> S4 + j; FP4 step u -> u - S8
+        const int64_t  d  = u < S8 ? S4 + (u >> 1) : u - S8;
+        const uint8_t *pa = p.a_e8 + d * p.M * 4, *pw = p.w_e8 + d * p.N * 4;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            sa[s] = (int)*reinterpret_cast<const uint32_t *>(p.a_e8 + (ea[s] + dw));
-            sb[s] = (int)*reinterpret_cast<const uint32_t *>(p.w_e8 + (eb[s] + dw));
+            sa_[s] = (int)*reinterpret_cast<const uint32_t *>(pa + ea[s]);
+            sb_[s] = (int)*reinterpret_cast<const uint32_t *>(pw + eb[s]);
         }
     };
 
@@ -154,14 +160,17 @@ void mx_gemm_kernel(MxParams p)
     const int a_base = mx_lds_off(128 * wm + lr, g);
     const int b_base = mx_lds_off(BM + 128 * wn + lr, g);
 
-    v4i regs[NLD];
+    // two register sets in flight: tile t travels in set t & 1, requested two steps before it is
+    // staged (one step of MFMAs is shorter than a trip to memory under load)
+    v4i regs[2][NLD];
     // scales: current step (shifted) and next step (raw dwords, loaded a whole step before
     // they are shifted, straight into the registers the previous set has just left)
     int sa[4], sb[4], sa_nxt[4] = {0, 0, 0, 0}, sb_nxt[4] = {0, 0, 0, 0};
-    fetch(0, regs);
+    fetch(0, regs[0]);
     fetch_scales(0, sa_nxt, sb_nxt);
-    stage(0, regs);
-    fetch(min(1, S - 1), regs);
+    stage(0, regs[0]);
+    fetch(min(1, S - 1), regs[1]);
+    fetch(min(2, S - 1), regs[0]);
     __syncthreads();
 
     // 16 MFMAs on one set of fragments; format and scale byte are compile-time
@@ -173,16 +182,16 @@ void mx_gemm_kernel(MxParams p)
                 acc[s][t] = mfma_mx<decltype(fmt)::value, decltype(opsel)::value>(af[s], bf[t], acc[s][t],
                                                                                   sa[s], sb[t]);
     };
-    // top of step u: step u+1 goes from registers into the other stage (last read in step
-    // u-1, before that step's barrier), step u+2 leaves global memory.  Nothing here is
-    // conditional (the last steps stage and fetch data nobody reads): with one path through the
-    // loop the compiler's wait counts let the loads of a whole step stay in flight.
-    // (a macro rather than a lambda that captures the lambdas above: closures nested that way
-    // keep the register arrays in scratch memory)
-#define ATOM_MX_ADVANCE(u)                                                                       \
+    // top of step u: tile u+1 goes from its register set into the other stage (last read in
+    // step u-1, before that step's barrier), tile u+3 leaves global memory into the same set.
+    // Nothing here is conditional (the last steps stage and fetch data nobody reads): with one
+    // path through the loop the compiler's wait counts let the loads of two steps stay in
+    // flight.  (A macro rather than a lambda that captures the lambdas above: closures nested
+    // that way keep the register arrays in scratch memory.)
+#define ATOM_MX_ADVANCE(u, SET)                                                                  \
     do {                                                                                         \
-        stage(((u) + 1) & 1, regs);                                                              \
-        fetch(min((u) + 2, S - 1), regs);                                                        \
+        stage(((u) + 1) & 1, regs[SET]);                                                         \
+        fetch(min((u) + 3, S - 1), regs[SET]);                                                   \
     } while (0)
     // end of step u: the next step's scales become current, the ones of step u+2 are requested
     auto next_scales = [&](int u) __attribute__((always_inline)) {
@@ -200,78 +209,77 @@ void mx_gemm_kernel(MxParams p)
     using b0  = std::integral_constant<int, 0>;
     using b2  = std::integral_constant<int, 2>;
 
+    // ---- FP8 steps first, in pairs (64 channels each): the lane's low 16 bytes are chunk g
+    // (block 0 of the step), its high 16 bytes chunk 2 + g (block 1); it carries the scale of
+    // block g, byte 2 (step & 1) + g of the pair's dword
+    auto load8 = [&](const uint8_t *buf, v8i (&af8)[4], v8i (&bf8)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            af8[s] = join(*reinterpret_cast<const v4i *>(buf + (a_base + 2048 * s)),
+                          *reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));
+            bf8[s] = join(*reinterpret_cast<const v4i *>(buf + (b_base + 2048 * s)),
+                          *reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * s)));
+        }
+    };
+#define ATOM_MX_FP8_STEP(u, SET, OPSEL)                                                          \
+    do {                                                                                         \
+        ATOM_MX_ADVANCE(u, SET);                                                                 \
+        v8i af8[4], bf8[4];                                                                      \
+        load8(smem + ((u) & 1) * STAGE, af8, bf8);                                               \
+        mma16(fp8{}, OPSEL{}, af8, bf8);                                                         \
+        next_scales(u);                                                                          \
+        __syncthreads();                                                                         \
+    } while (0)
+    int u = 0;
+    for (; u < S8; u += 2) {              // tile u+1 is odd: set 1; tile u+2 even: set 0
+        ATOM_MX_FP8_STEP(u, 1, b0);
+        ATOM_MX_FP8_STEP(u + 1, 0, b2);
+    }
+#undef ATOM_MX_FP8_STEP
+
     // ---- FP4 steps: two sub-steps of 64 channels, bytes [0,32) and [32,64) of the row; the
     // lane takes chunk 2 k + g.  Software pipeline: the second sub-step's fragments are read
     // under the first sub-step's MFMAs, the next step's first fragments under the second's
     // (the barrier that publishes the next stage sits between the two).
     v8i af[4], bf[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
+    for (int s = 0; s < 4; ++s) {         // u is even here: stage 0
         af[s] = widen(*reinterpret_cast<const v4i *>(smem + (a_base + 2048 * s)));
         bf[s] = widen(*reinterpret_cast<const v4i *>(smem + (b_base + 2048 * s)));
     }
-    for (int u = 0; u < S4; ++u) {
-        const uint8_t *buf = smem + (u & 1) * STAGE, *nbuf = smem + ((u + 1) & 1) * STAGE;
-        ATOM_MX_ADVANCE(u);
-        v8i ag[4], bg[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            ag[s] = widen(*reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));
-            bg[s] = widen(*reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * s)));
-        }
-        mma16(fp4{}, b0{}, af, bf);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);    // two MFMAs
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // one LDS read
-        }
-        __syncthreads();                  // stage u+1 is complete, stage u has been read
-        // (after the last FP4 step these reads fetch FP8 bytes that are not used)
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            af[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (a_base + 2048 * s)));
-            bf[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (b_base + 2048 * s)));
-        }
-        mma16(fp4{}, b2{}, ag, bg);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 1);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
-        }
-        next_scales(u);
+#define ATOM_MX_FP4_STEP(u, SET)                                                                 \
+    do {                                                                                         \
+        const uint8_t *buf = smem + ((u) & 1) * STAGE, *nbuf = smem + (((u) + 1) & 1) * STAGE;   \
+        ATOM_MX_ADVANCE(u, SET);                                                                 \
+        v8i ag[4], bg[4];                                                                        \
+        _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                          \
+            ag[s] = widen(*reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));     \
+            bg[s] = widen(*reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * s)));     \
+        }                                                                                        \
+        mma16(fp4{}, b0{}, af, bf);                                                              \
+        _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                          \
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); /* two MFMAs */                   \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); /* one LDS read */                \
+        }                                                                                        \
+        __syncthreads(); /* stage u+1 is complete, stage u has been read */                      \
+        /* (after the last step these reads fetch bytes that are not used) */                    \
+        _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                          \
+            af[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (a_base + 2048 * s)));           \
+            bf[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (b_base + 2048 * s)));           \
+        }                                                                                        \
+        mma16(fp4{}, b2{}, ag, bg);                                                              \
+        _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                          \
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 1);                                   \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);                                   \
+        }                                                                                        \
+        next_scales(u);                                                                          \
+    } while (0)
+    for (; u + 1 < S; u += 2) {
+        ATOM_MX_FP4_STEP(u, 1);
+        ATOM_MX_FP4_STEP(u + 1, 0);
     }
-    auto finish = [&](int u) __attribute__((always_inline)) {
-        next_scales(u);
-        __syncthreads();
-    };
-    // ---- FP8 steps, in pairs (64 channels each): the lane's low 16 bytes are chunk g (block 0
-    // of the step), its high 16 bytes chunk 2 + g (block 1); it carries the scale of block g,
-    // byte 2 (step & 1) + g of the pair's dword
-    auto load8 = [&](const uint8_t *buf, v8i (&af)[4], v8i (&bf)[4]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            af[s] = join(*reinterpret_cast<const v4i *>(buf + (a_base + 2048 * s)),
-                         *reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));
-            bf[s] = join(*reinterpret_cast<const v4i *>(buf + (b_base + 2048 * s)),
-                         *reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * s)));
-        }
-    };
-    for (int u = S4; u < S; u += 2) {
-        {
-            ATOM_MX_ADVANCE(u);
-            v8i af[4], bf[4];
-            load8(smem + (u & 1) * STAGE, af, bf);
-            mma16(fp8{}, b0{}, af, bf);
-            finish(u);
-        }
-        {
-            ATOM_MX_ADVANCE(u + 1);
-            v8i af[4], bf[4];
-            load8(smem + ((u + 1) & 1) * STAGE, af, bf);
-            mma16(fp8{}, b2{}, af, bf);
-            finish(u + 1);
-        }
-    }
+    if (u < S) ATOM_MX_FP4_STEP(u, 1);
+#undef ATOM_MX_FP4_STEP
 
 #undef ATOM_MX_ADVANCE
 

@@ -229,10 +229,16 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
                     }
                 }
                 if (live) {
-                    if (is4) *reinterpret_cast<uint32_t *>(q4 + row * (int64_t)(K4 >> 1) + (j0 >> 1)) = w0;
-                    else     *reinterpret_cast<uint2 *>(q8 + row * (int64_t)O + (j0 - K4)) = make_uint2(w0, w1);
+                    // step-major layout: 64 bytes (128 FP4 or 64 FP8 channels) of every row
+                    // are contiguous per K step, scales as one dword per row and 128 channels
+                    if (is4)
+                        *reinterpret_cast<uint32_t *>(q4 + ((int64_t)(j0 >> 7) * rows + row) * 64 + ((j0 & 127) >> 1)) = w0;
+                    else
+                        *reinterpret_cast<uint2 *>(q8 + ((int64_t)((j0 - K4) >> 6) * rows + row) * 64 + ((j0 - K4) & 63)) =
+                            make_uint2(w0, w1);
                     if ((lane & 3) == 0)
-                        reinterpret_cast<uint8_t *>(scale)[row * (int64_t)(K >> 5) + (j0 >> 5)] = (uint8_t)byte;
+                        reinterpret_cast<uint8_t *>(scale)[((int64_t)(j0 >> 7) * rows + row) * 4 + ((j0 >> 5) & 3)] =
+                            (uint8_t)byte;
                 }
                 continue;
             }

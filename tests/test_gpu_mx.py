@@ -25,9 +25,18 @@ def _npy(t):
     return t.detach().cpu().numpy()
 
 
+def _row_major(g):
+    """The library's step-major arrays ([step][row][64 bytes], scales [slab][row][4]) as the
+    oracle's row-major ones: a pure permutation of bytes."""
+    q4, q8, e8 = (_npy(t) for t in g)
+    rows = q4.shape[1]
+    return (q4.transpose(1, 0, 2).reshape(rows, -1), q8.transpose(1, 0, 2).reshape(rows, -1),
+            e8.transpose(1, 0, 2).reshape(rows, -1))
+
+
 def _equal(g, r, what):
-    for name, a, b in zip(("q4", "q8", "e8"), g, r):
-        a = _npy(a)
+    for name, a, b in zip(("q4", "q8", "e8"), _row_major(g) if g[0].ndim == 3 else g, r):
+        a = _npy(a) if hasattr(a, "detach") else a
         assert a.shape == b.shape, f"{what}: {name} shape"
         if not np.array_equal(a, b):
             bad = np.argwhere(a != b)
@@ -160,8 +169,8 @@ def test_mx_full_size_sampled():
     cols = np.sort(np.concatenate([rng.choice(lin.N, 120, replace=False), [0, lin.N - 1]]))
     ra = oracle.mx_quantize_act(lin.x.numpy()[rows], lin.gamma.numpy(), lin.eps, lin.idx.numpy(), lin.n_outlier, 0.9)
     rw = oracle.mx_quantize_weight(lin.w.numpy()[cols], lin.idx.numpy(), lin.n_outlier, 0.85)
-    _equal(tuple(t[torch.as_tensor(rows).cuda()] for t in ga), ra, "act rows")
-    _equal(tuple(t[torch.as_tensor(cols).cuda()] for t in gw), rw, "weight rows")
+    _equal(tuple(t[rows] for t in _row_major(ga)), ra, "act rows")
+    _equal(tuple(t[cols] for t in _row_major(gw)), rw, "weight rows")
     ref = oracle.mx_gemm(*ra, *rw)
     err = _rel_err(y[np.ix_(rows, cols)], ref, ra, rw)
     assert err <= 1.0, f"sampled Y error {err} x the allowed"
@@ -182,3 +191,5 @@ def test_mx_errors():
     assert not _npy(y).any()
     empty = atom.atom_mx_quantize_act(x[:0], None, 0.0, idx, 128, 1.0)
     assert atom.atom_mx_gemm(*empty, *q).shape == (0, 4)
+    with pytest.raises(ValueError):                           # row-major arrays are not accepted
+        atom.atom_mx_gemm(q[0].reshape(4, -1), q[1].reshape(4, -1), q[2].reshape(4, -1), *q)
