@@ -33,8 +33,12 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 constexpr int BM = 256, BN = 256;         // workgroup tile
 constexpr int NT = 256;                   // 4 wavefronts, 2 x 2, each 128 x 128 (4 x 4 MFMA tiles)
 constexpr int ROWB = 64;                  // bytes per tile row and K step: 128 FP4 or 64 FP8 channels
-constexpr int STAGE = (BM + BN) * ROWB;   // 32 KB
-constexpr int NLD = STAGE / 16 / NT;      // 16-byte chunks per thread and step (8)
+constexpr int CODES = (BM + BN) * ROWB;   // 32 KB of codes per stage
+constexpr int STAGE = CODES + (BM + BN) * 4;   // + one scale dword per row
+constexpr int NLD = CODES / 16 / NT;      // 16-byte chunks per thread and step (8)
+constexpr int EPI_PITCH = 272;            // bytes per output row of a wavefront's LDS region
+constexpr int EPI_WAVE  = 64 * EPI_PITCH; // 64 rows per pass
+constexpr int LDS_BYTES = 4 * EPI_WAVE > 2 * STAGE ? 4 * EPI_WAVE : 2 * STAGE;
 
 struct MxParams {
     const uint8_t *a_q4, *a_q8, *a_e8;
@@ -93,6 +97,8 @@ void mx_gemm_kernel(MxParams p)
     // ---- loader: chunk id = tid + NT * i, row = id / 4 (A rows first), chunk = tid % 4.  The
     // operands are stored step-major ([step][row][64 bytes]), so a step's 64 bytes of 16
     // consecutive rows are one contiguous kilobyte and every cache line that is fetched is used.
+    // The scale dwords of the step's 512 rows ([K / 128][rows][4 bytes]) travel the same way,
+    // two per thread, into the 2 KB behind the codes of a stage.
     const int ch = tid & 3;
     uint32_t off[NLD];                                             // byte offset inside a step's slab
     int dst[NLD];
@@ -105,45 +111,29 @@ void mx_gemm_kernel(MxParams p)
         off[i] = (uint32_t)r * ROWB + 16u * ch;
         dst[i] = mx_lds_off(row, ch);
     }
+    const uint32_t sca = (uint32_t)(m0 + tid < p.M ? m0 + tid : p.M - 1) * 4u;
+    const uint32_t scb = (uint32_t)(n0 + tid < p.N ? n0 + tid : p.N - 1) * 4u;
+    struct Regs { v4i v[NLD]; uint32_t sa, sb; };
     // steps 0 .. S8-1 are the FP8 (outlier) steps, the FP4 steps follow: S8 is even, so the
     // parity of a step is known at compile time wherever the two-step unrolling needs it
-    auto fetch = [&](int u, v4i (&v)[NLD]) __attribute__((always_inline)) {
+    auto fetch = [&](int u, Regs &r) __attribute__((always_inline)) {
         const bool    f8 = u < S8;
         const int64_t sl = f8 ? u : u - S8;                        // slab index inside q8 or q4
+        const int64_t d  = f8 ? S4 + (u >> 1) : u - S8;            // slab index inside e8
         const uint8_t *pa = (f8 ? p.a_q8 : p.a_q4) + sl * p.M * ROWB;
         const uint8_t *pw = (f8 ? p.w_q8 : p.w_q4) + sl * p.N * ROWB;
 #pragma unroll
         for (int i = 0; i < NLD; ++i)
-            v[i] = *reinterpret_cast<const v4i *>((i < NLD / 2 ? pa : pw) + off[i]);
+            r.v[i] = *reinterpret_cast<const v4i *>((i < NLD / 2 ? pa : pw) + off[i]);
+        r.sa = *reinterpret_cast<const uint32_t *>(p.a_e8 + d * p.M * 4 + sca);
+        r.sb = *reinterpret_cast<const uint32_t *>(p.w_e8 + d * p.N * 4 + scb);
     };
-    auto stage = [&](int buf, const v4i (&v)[NLD]) __attribute__((always_inline)) {
+    auto stage = [&](int buf, const Regs &r) __attribute__((always_inline)) {
+        uint8_t *st = smem + buf * STAGE;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) *reinterpret_cast<v4i *>(smem + buf * STAGE + dst[i]) = v[i];
-    };
-
-    // ---- scales: one dword (four blocks) per row and per 128 channels, i.e. per FP4 step or
-    // pair of FP8 steps, stored [K / 128][rows]; when it becomes the current one (a step after
-    // its load, so nothing waits on memory) it is shifted so that the lane's own block of a
-    // sub-step sits in byte 0 or 2
-    uint32_t ea[4], eb[4];                                          // byte offsets of the rows
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        int64_t r = m0 + 128 * wm + 32 * s + lr;
-        r = r < p.M - 1 ? r : p.M - 1;
-        ea[s] = (uint32_t)r * 4u;
-        r = n0 + 128 * wn + 32 * s + lr;
-        r = r < p.N - 1 ? r : p.N - 1;
-        eb[s] = (uint32_t)r * 4u;
-    }
-    auto fetch_scales = [&](int u, int (&sa_)[4], int (&sb_)[4]) __attribute__((always_inline)) {
-        // dword slab of step u: FP8 steps 2j, 2j+1 -> S4 + j; FP4 step u -> u - S8
-        const int64_t  d  = u < S8 ? S4 + (u >> 1) : u - S8;
-        const uint8_t *pa = p.a_e8 + d * p.M * 4, *pw = p.w_e8 + d * p.N * 4;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            sa_[s] = (int)*reinterpret_cast<const uint32_t *>(pa + ea[s]);
-            sb_[s] = (int)*reinterpret_cast<const uint32_t *>(pw + eb[s]);
-        }
+        for (int i = 0; i < NLD; ++i) *reinterpret_cast<v4i *>(st + dst[i]) = r.v[i];
+        *reinterpret_cast<uint32_t *>(st + CODES + 4 * tid)          = r.sa;
+        *reinterpret_cast<uint32_t *>(st + CODES + 4 * (BM + tid))   = r.sb;
     };
 
     v16f acc[4][4];
@@ -159,51 +149,61 @@ void mx_gemm_kernel(MxParams p)
     // xor of chunk c's offset with 32.
     const int a_base = mx_lds_off(128 * wm + lr, g);
     const int b_base = mx_lds_off(BM + 128 * wn + lr, g);
+    const int sa_off = CODES + 4 * (128 * wm + lr), sb_off = CODES + 4 * (BM + 128 * wn + lr);
+    // the four blocks of a row's 128 channels are the bytes of its scale dword; shifted by
+    // 8 g, the lane's own block of a sub-step sits in byte 0 or 2, which op_sel picks
+    int sa[4], sb[4];
+    auto read_scales = [&](const uint8_t *buf) __attribute__((always_inline)) {
+#if defined(ATOM_MX_ABL_NOSCALE)
+        if (buf != smem) return;
+#endif
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            sa[s] = (int)(*reinterpret_cast<const uint32_t *>(buf + sa_off + 128 * s) >> (8 * g));
+            sb[s] = (int)(*reinterpret_cast<const uint32_t *>(buf + sb_off + 128 * s) >> (8 * g));
+        }
+    };
 
     // two register sets in flight: tile t travels in set t & 1, requested two steps before it is
     // staged (one step of MFMAs is shorter than a trip to memory under load)
-    v4i regs[2][NLD];
-    // scales: current step (shifted) and next step (raw dwords, loaded a whole step before
-    // they are shifted, straight into the registers the previous set has just left)
-    int sa[4], sb[4], sa_nxt[4] = {0, 0, 0, 0}, sb_nxt[4] = {0, 0, 0, 0};
+    Regs regs[2];
     fetch(0, regs[0]);
-    fetch_scales(0, sa_nxt, sb_nxt);
     stage(0, regs[0]);
     fetch(min(1, S - 1), regs[1]);
     fetch(min(2, S - 1), regs[0]);
     __syncthreads();
 
     // 16 MFMAs on one set of fragments; format and scale byte are compile-time
-    auto mma16 = [&](auto fmt, auto opsel, const v8i (&af)[4], const v8i (&bf)[4]) __attribute__((always_inline)) {
+    auto mma16 = [&](auto fmt, auto opsel, const v8i (&af)[4], const v8i (&bf)[4], const int (&sa_)[4],
+                     const int (&sb_)[4]) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
             for (int t = 0; t < 4; ++t)
                 acc[s][t] = mfma_mx<decltype(fmt)::value, decltype(opsel)::value>(af[s], bf[t], acc[s][t],
-                                                                                  sa[s], sb[t]);
+                                                                                  sa_[s], sb_[t]);
     };
     // top of step u: tile u+1 goes from its register set into the other stage (last read in
     // step u-1, before that step's barrier), tile u+3 leaves global memory into the same set.
     // Nothing here is conditional (the last steps stage and fetch data nobody reads): with one
     // path through the loop the compiler's wait counts let the loads of two steps stay in
-    // flight.  (A macro rather than a lambda that captures the lambdas above: closures nested
+    // flight.  (Macros rather than lambdas that capture the lambdas above: closures nested
     // that way keep the register arrays in scratch memory.)
+#if defined(ATOM_MX_ABL_NOSTAGE)
+#define ATOM_MX_STAGE(u, SET)
+#else
+#define ATOM_MX_STAGE(u, SET) stage(((u) + 1) & 1, regs[SET])
+#endif
+#if defined(ATOM_MX_ABL_NOFETCH)
+#define ATOM_MX_FETCH(u, SET)
+#else
+#define ATOM_MX_FETCH(u, SET) fetch(min((u) + 3, S - 1), regs[SET])
+#endif
 #define ATOM_MX_ADVANCE(u, SET)                                                                  \
     do {                                                                                         \
-        stage(((u) + 1) & 1, regs[SET]);                                                         \
-        fetch(min((u) + 3, S - 1), regs[SET]);                                                   \
+        ATOM_MX_STAGE(u, SET);                                                                   \
+        ATOM_MX_FETCH(u, SET);                                                                   \
     } while (0)
-    // end of step u: the next step's scales become current, the ones of step u+2 are requested
-    auto next_scales = [&](int u) __attribute__((always_inline)) {
-        __builtin_amdgcn_sched_barrier(0);                // keep the use a whole step behind the load
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            sa[s] = (int)((unsigned)sa_nxt[s] >> (8 * g));
-            sb[s] = (int)((unsigned)sb_nxt[s] >> (8 * g));
-        }
-        fetch_scales(min(u + 2, S - 1), sa_nxt, sb_nxt);
-    };
-    next_scales(-1);                      // the scales of step 0 (and the request for step 1)
     using fp4 = std::integral_constant<int, 4>;
     using fp8 = std::integral_constant<int, 0>;
     using b0  = std::integral_constant<int, 0>;
@@ -226,8 +226,8 @@ void mx_gemm_kernel(MxParams p)
         ATOM_MX_ADVANCE(u, SET);                                                                 \
         v8i af8[4], bf8[4];                                                                      \
         load8(smem + ((u) & 1) * STAGE, af8, bf8);                                               \
-        mma16(fp8{}, OPSEL{}, af8, bf8);                                                         \
-        next_scales(u);                                                                          \
+        read_scales(smem + ((u) & 1) * STAGE);                                                   \
+        mma16(fp8{}, OPSEL{}, af8, bf8, sa, sb);                                                 \
         __syncthreads();                                                                         \
     } while (0)
     int u = 0;
@@ -239,40 +239,59 @@ void mx_gemm_kernel(MxParams p)
 
     // ---- FP4 steps: two sub-steps of 64 channels, bytes [0,32) and [32,64) of the row; the
     // lane takes chunk 2 k + g.  Software pipeline: the second sub-step's fragments are read
-    // under the first sub-step's MFMAs, the next step's first fragments under the second's
-    // (the barrier that publishes the next stage sits between the two).
+    // under the first sub-step's MFMAs, the next step's first fragments and scales under the
+    // second's (the barrier that publishes the next stage sits between the two).
     v8i af[4], bf[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {         // u is even here: stage 0
         af[s] = widen(*reinterpret_cast<const v4i *>(smem + (a_base + 2048 * s)));
         bf[s] = widen(*reinterpret_cast<const v4i *>(smem + (b_base + 2048 * s)));
     }
+    read_scales(smem);
+#if defined(ATOM_MX_ABL_NOREAD)
+#define ATOM_MX_RD(old, ptr) (old)
+#else
+#define ATOM_MX_RD(old, ptr) widen(*reinterpret_cast<const v4i *>(ptr))
+#endif
+#if defined(ATOM_MX_ABL_NOSYNC)
+#define ATOM_MX_SYNC()
+#else
+#define ATOM_MX_SYNC() __syncthreads()
+#endif
 #define ATOM_MX_FP4_STEP(u, SET)                                                                 \
     do {                                                                                         \
         const uint8_t *buf = smem + ((u) & 1) * STAGE, *nbuf = smem + (((u) + 1) & 1) * STAGE;   \
         ATOM_MX_ADVANCE(u, SET);                                                                 \
         v8i ag[4], bg[4];                                                                        \
         _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                          \
-            ag[s] = widen(*reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));     \
-            bg[s] = widen(*reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * s)));     \
+            ag[s] = ATOM_MX_RD(af[s], buf + ((a_base ^ 32) + 2048 * s));                         \
+            bg[s] = ATOM_MX_RD(bf[s], buf + ((b_base ^ 32) + 2048 * s));                         \
         }                                                                                        \
-        mma16(fp4{}, b0{}, af, bf);                                                              \
+        mma16(fp4{}, b0{}, af, bf, sa, sb);                                                      \
+        /* the eight reads go out under the first eight MFMAs, the other eight cover them */    \
         _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                          \
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0); /* two MFMAs */                   \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); /* one MFMA */                    \
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); /* one LDS read */                \
         }                                                                                        \
-        __syncthreads(); /* stage u+1 is complete, stage u has been read */                      \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                       \
+        ATOM_MX_SYNC(); /* stage u+1 is complete, stage u has been read */                       \
+        __builtin_amdgcn_sched_barrier(0);                                                       \
         /* (after the last step these reads fetch bytes that are not used) */                    \
+        int sc[4], sd[4];                                                                        \
         _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                          \
-            af[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (a_base + 2048 * s)));           \
-            bf[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (b_base + 2048 * s)));           \
+            sc[s] = sa[s];                                                                       \
+            sd[s] = sb[s];                                                                       \
+            af[s] = ATOM_MX_RD(af[s], nbuf + (a_base + 2048 * s));                               \
+            bf[s] = ATOM_MX_RD(bf[s], nbuf + (b_base + 2048 * s));                               \
         }                                                                                        \
-        mma16(fp4{}, b2{}, ag, bg);                                                              \
+        read_scales(nbuf);                                                                       \
+        mma16(fp4{}, b2{}, ag, bg, sc, sd);                                                      \
         _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                          \
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 1);                                   \
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);                                   \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);                                   \
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);                                   \
         }                                                                                        \
-        next_scales(u);                                                                          \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 1);                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                       \
     } while (0)
     for (; u + 1 < S; u += 2) {
         ATOM_MX_FP4_STEP(u, 1);
@@ -280,25 +299,56 @@ void mx_gemm_kernel(MxParams p)
     }
     if (u < S) ATOM_MX_FP4_STEP(u, 1);
 #undef ATOM_MX_FP4_STEP
-
 #undef ATOM_MX_ADVANCE
 
-    // ---- store: lane holds column lr of sub-tile t, rows 8 (v / 4) + 4 g + v % 4 of sub-tile s;
-    // one lane-dependent offset, everything else wavefront-uniform
-    const int64_t row0 = m0 + 128 * wm + 4 * g, col0 = n0 + 128 * wn + lr;
-    uint16_t *yp = p.y + row0 * p.ldy + col0;
+    // ---- store: lane holds column lr of sub-tile t, rows 8 (v / 4) + 4 g + v % 4 of sub-tile s.
+    const int64_t wrow = m0 + 128 * wm, wcol = n0 + 128 * wn;      // this wavefront's 128 x 128 block
+    const bool whole = wrow + 128 <= p.M && wcol + 128 <= p.N && (p.ldy & 7) == 0 &&
+                       (reinterpret_cast<uintptr_t>(p.y) & 15) == 0;
+    __syncthreads();                                               // the stages are dead from here on
+    if (whole) {
+        // Through LDS, so that global memory sees whole 16-byte pieces of rows (2-byte stores
+        // straight from the accumulator layout cost several times the K loop of a tile): two
+        // passes of 64 rows; a wavefront's region is 64 rows x 128 columns of fp16, rows 272
+        // bytes apart (the pad keeps the two row groups of a write on different banks).
+        uint8_t *reg = smem + wave * EPI_WAVE;
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
+        for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int dr = 32 * s + 8 * (v >> 2) + (v & 3);
-            if (row0 + dr < p.M) {
-                uint16_t *yr = yp + (int64_t)dr * p.ldy;
+            for (int sh = 0; sh < 2; ++sh)
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
-                    if (col0 + 32 * t < p.N) yr[32 * t] = __half_as_ushort(__float2half_rn(acc[s][t][v]));
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int r = 32 * sh + 8 * (v >> 2) + 4 * g + (v & 3);
+                        *reinterpret_cast<uint16_t *>(reg + r * EPI_PITCH + 2 * (32 * t + lr)) =
+                            __half_as_ushort(__float2half_rn(acc[2 * pass + sh][t][v]));
+                    }
+            // 16 lanes per row: lane l takes columns 8 (l % 16) .. +7 of rows l / 16 + 4 i
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int r = 4 * i + (lane >> 4);
+                const v4i d = *reinterpret_cast<const v4i *>(reg + r * EPI_PITCH + 16 * (lane & 15));
+                *reinterpret_cast<v4i *>(p.y + (wrow + 64 * pass + r) * p.ldy + wcol + 8 * (lane & 15)) = d;
             }
         }
+    } else {
+        // ragged edge tiles: element by element
+        const int64_t row0 = wrow + 4 * g, col0 = wcol + lr;
+        uint16_t *yp = p.y + row0 * p.ldy + col0;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int dr = 32 * s + 8 * (v >> 2) + (v & 3);
+                if (row0 + dr < p.M) {
+                    uint16_t *yr = yp + (int64_t)dr * p.ldy;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if (col0 + 32 * t < p.N) yr[32 * t] = __half_as_ushort(__float2half_rn(acc[s][t][v]));
+                }
+            }
+    }
 }
 
 }  // namespace
@@ -316,12 +366,12 @@ hipError_t launch_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8, 
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (err != hipSuccess) return err;
         attr_set = true;
     }
     const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-    hipLaunchKernelGGL(mx_gemm_kernel, dim3((unsigned)tiles), dim3(NT), 2 * STAGE, stream, p);
+    hipLaunchKernelGGL(mx_gemm_kernel, dim3((unsigned)tiles), dim3(NT), LDS_BYTES, stream, p);
     return hipGetLastError();
 }
 
