@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include <type_traits>
 
@@ -351,6 +352,250 @@ void mx_gemm_kernel(MxParams p)
     }
 }
 
+// The same GEMM with the operands going from global memory straight into LDS
+// (global_load_lds_dwordx4: lane i's 16 bytes land at the LDS address in M0 plus 16 i), so no
+// wavefront spends issue slots on staging registers and ds_write.  Four stages: while step u
+// is multiplied, tile u+1 has landed or is landing, tile u+2 is on its way and tile u+3 is
+// requested.  A wavefront
+// instruction fills one kilobyte = 16 tile rows; lane l supplies the chunk that the rotated
+// layout wants at its position: row l / 4 of the 16, chunk ((l % 4) - (l / 16)) % 4.
+// The loads are inline assembly, the compiler does not count them: the waits on vmcnt before
+// the barriers below are written by hand (ten loads per wavefront and tile, two tiles may
+// stay in flight).
+constexpr int DMA_STAGES = 4;
+constexpr int DMA_LDS = DMA_STAGES * STAGE > 4 * EPI_WAVE ? DMA_STAGES * STAGE : 4 * EPI_WAVE;
+
+__device__ __forceinline__ void dma16(uint32_t lds, uint32_t voff, const uint8_t *sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+__device__ __forceinline__ void dma4(uint32_t lds, uint32_t voff, const uint8_t *sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :: "s"(lds), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void mx_gemm_dma_kernel(MxParams p)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lr = lane & 31, g = lane >> 5;
+
+    const int tiles_m = (int)((p.M + BM - 1) / BM);
+    const int bid = atom_gemm::xcd_contiguous_block_id();
+    const int64_t m0 = (int64_t)(bid % tiles_m) * BM, n0 = (int64_t)(bid / tiles_m) * BN;
+
+    const int K4 = p.K - p.O;
+    const int S4 = K4 >> 7, S8 = p.O >> 6, S = S4 + S8;
+
+    // ---- loader: wavefront w fills the kilobyte blocks 8 w .. 8 w + 7 of a stage (blocks
+    // 0..15 are the A rows, 16..31 the B rows: wavefronts 0, 1 load A, wavefronts 2, 3 load B)
+    // and 64 of the A and 64 of the B scale dwords
+    const bool loadsA = wave < 2;
+    uint32_t goff[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int trow = 16 * (8 * wave + j) + (lane >> 2);              // row of the 512-row stage
+        int64_t r = loadsA ? m0 + trow : n0 + (trow - BM);
+        const int64_t last = (loadsA ? p.M : p.N) - 1;
+        r = r < last ? r : last;                                         // ragged tiles repeat the last row
+        goff[j] = (uint32_t)r * ROWB + 16u * (((lane & 3) - (lane >> 4)) & 3);
+    }
+    const uint32_t sca = (uint32_t)(m0 + 64 * wave + lane < p.M ? m0 + 64 * wave + lane : p.M - 1) * 4u;
+    const uint32_t scb = (uint32_t)(n0 + 64 * wave + lane < p.N ? n0 + 64 * wave + lane : p.N - 1) * 4u;
+    const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+    // steps 0 .. S8-1 are the FP8 (outlier) steps, the FP4 steps follow
+    auto request = [&](int u, int buf) __attribute__((always_inline)) {
+        const bool    f8 = u < S8;
+        const int64_t sl = f8 ? u : u - S8;                        // slab index inside q8 or q4
+        const int64_t d  = f8 ? S4 + (u >> 1) : u - S8;            // slab index inside e8
+        const uint8_t *src = loadsA ? (f8 ? p.a_q8 : p.a_q4) + sl * p.M * ROWB
+                                    : (f8 ? p.w_q8 : p.w_q4) + sl * p.N * ROWB;
+        const uint32_t st = lds0 + buf * STAGE;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dma16(st + 1024 * (8 * wave + j), goff[j], src);
+        dma4(st + CODES + 256 * wave, sca, p.a_e8 + d * p.M * 4);
+        dma4(st + CODES + 4 * BM + 256 * wave, scb, p.w_e8 + d * p.N * 4);
+    };
+    // all but the two newest tiles' loads of this wavefront have landed, and its own LDS reads are done
+#define ATOM_MX_LANDED() __builtin_amdgcn_s_waitcnt(0x4074) /* vmcnt(20), lgkmcnt(0) */
+
+    v16f acc[4][4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[s][t][v] = 0.0f;
+
+    const int a_base = mx_lds_off(128 * wm + lr, g);
+    const int b_base = mx_lds_off(BM + 128 * wn + lr, g);
+    const int sa_off = CODES + 4 * (128 * wm + lr), sb_off = CODES + 4 * (BM + 128 * wn + lr);
+    int sa[4], sb[4];
+    auto read_scales = [&](const uint8_t *buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            sa[s] = (int)(*reinterpret_cast<const uint32_t *>(buf + sa_off + 128 * s) >> (8 * g));
+            sb[s] = (int)(*reinterpret_cast<const uint32_t *>(buf + sb_off + 128 * s) >> (8 * g));
+        }
+    };
+    auto mma16 = [&](auto fmt, auto opsel, const v8i (&af)[4], const v8i (&bf)[4], const int (&sa_)[4],
+                     const int (&sb_)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                acc[s][t] = mfma_mx<decltype(fmt)::value, decltype(opsel)::value>(af[s], bf[t], acc[s][t],
+                                                                                  sa_[s], sb_[t]);
+    };
+    using fp4 = std::integral_constant<int, 4>;
+    using fp8 = std::integral_constant<int, 0>;
+    using b0  = std::integral_constant<int, 0>;
+    using b2  = std::integral_constant<int, 2>;
+
+    // stage indices of tiles u, u+1, u+2, u+3
+    int cur = 0, nxt = 1, nx2 = 2, nx3 = 3;
+    request(0, 0);
+    request(min(1, S - 1), 1);
+    request(min(2, S - 1), 2);
+    ATOM_MX_LANDED();
+    __syncthreads();
+
+    // ---- FP8 steps first, in pairs
+    auto load8 = [&](const uint8_t *buf, v8i (&af8)[4], v8i (&bf8)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            af8[s] = join(*reinterpret_cast<const v4i *>(buf + (a_base + 2048 * s)),
+                          *reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));
+            bf8[s] = join(*reinterpret_cast<const v4i *>(buf + (b_base + 2048 * s)),
+                          *reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * s)));
+        }
+    };
+#define ATOM_MX_ROTATE()                                                                         \
+    do {                                                                                         \
+        const int t_ = cur;                                                                      \
+        cur = nxt;                                                                               \
+        nxt = nx2;                                                                               \
+        nx2 = nx3;                                                                               \
+        nx3 = t_;                                                                                \
+    } while (0)
+#define ATOM_MX_FP8_STEP(u, OPSEL)                                                               \
+    do {                                                                                         \
+        request(min((u) + 3, S - 1), nx3);                                                       \
+        v8i af8[4], bf8[4];                                                                      \
+        load8(smem + cur * STAGE, af8, bf8);                                                     \
+        read_scales(smem + cur * STAGE);                                                         \
+        mma16(fp8{}, OPSEL{}, af8, bf8, sa, sb);                                                 \
+        ATOM_MX_LANDED();                                                                        \
+        __syncthreads();                                                                         \
+        ATOM_MX_ROTATE();                                                                        \
+    } while (0)
+    int u = 0;
+    for (; u < S8; u += 2) {
+        ATOM_MX_FP8_STEP(u, b0);
+        ATOM_MX_FP8_STEP(u + 1, b2);
+    }
+#undef ATOM_MX_FP8_STEP
+
+    // ---- FP4 steps, software-pipelined as in mx_gemm_kernel
+    v8i af[4], bf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        af[s] = widen(*reinterpret_cast<const v4i *>(smem + cur * STAGE + (a_base + 2048 * s)));
+        bf[s] = widen(*reinterpret_cast<const v4i *>(smem + cur * STAGE + (b_base + 2048 * s)));
+    }
+    read_scales(smem + cur * STAGE);
+    for (; u < S; ++u) {
+        const uint8_t *buf = smem + cur * STAGE, *nbuf = smem + nxt * STAGE;
+        request(min(u + 3, S - 1), nx3);
+        v8i ag[4], bg[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            ag[s] = widen(*reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));
+            bg[s] = widen(*reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * s)));
+        }
+        mma16(fp4{}, b0{}, af, bf, sa, sb);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        ATOM_MX_LANDED();                 // tile u+1 is in its stage ...
+        __syncthreads();                  // ... for every wavefront; stage u has been read
+        __builtin_amdgcn_sched_barrier(0);
+        int sc[4], sd[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            sc[s] = sa[s];
+            sd[s] = sb[s];
+            af[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (a_base + 2048 * s)));
+            bf[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (b_base + 2048 * s)));
+        }
+        read_scales(nbuf);
+        mma16(fp4{}, b2{}, ag, bg, sc, sd);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        ATOM_MX_ROTATE();
+    }
+#undef ATOM_MX_ROTATE
+#undef ATOM_MX_LANDED
+
+    // ---- store, as in mx_gemm_kernel; the last (repeated) requests must have landed before the
+    // stages are reused
+    __builtin_amdgcn_s_waitcnt(0x0F70);                            // vmcnt(0)
+    const int64_t wrow = m0 + 128 * wm, wcol = n0 + 128 * wn;
+    const bool whole = wrow + 128 <= p.M && wcol + 128 <= p.N && (p.ldy & 7) == 0 &&
+                       (reinterpret_cast<uintptr_t>(p.y) & 15) == 0;
+    __syncthreads();
+    if (whole) {
+        uint8_t *reg = smem + wave * EPI_WAVE;
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+            for (int sh = 0; sh < 2; ++sh)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int r = 32 * sh + 8 * (v >> 2) + 4 * g + (v & 3);
+                        *reinterpret_cast<uint16_t *>(reg + r * EPI_PITCH + 2 * (32 * t + lr)) =
+                            __half_as_ushort(__float2half_rn(acc[2 * pass + sh][t][v]));
+                    }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int r = 4 * i + (lane >> 4);
+                const v4i d = *reinterpret_cast<const v4i *>(reg + r * EPI_PITCH + 16 * (lane & 15));
+                *reinterpret_cast<v4i *>(p.y + (wrow + 64 * pass + r) * p.ldy + wcol + 8 * (lane & 15)) = d;
+            }
+        }
+    } else {
+        const int64_t row0 = wrow + 4 * g, col0 = wcol + lr;
+        uint16_t *yp = p.y + row0 * p.ldy + col0;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int dr = 32 * s + 8 * (v >> 2) + (v & 3);
+                if (row0 + dr < p.M) {
+                    uint16_t *yr = yp + (int64_t)dr * p.ldy;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if (col0 + 32 * t < p.N) yr[32 * t] = __half_as_ushort(__float2half_rn(acc[s][t][v]));
+                }
+            }
+    }
+}
+
 }  // namespace
 
 namespace atom_internal {
@@ -363,15 +608,27 @@ hipError_t launch_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8, 
     p.a_q4 = (const uint8_t *)a_q4; p.a_q8 = (const uint8_t *)a_q8; p.a_e8 = (const uint8_t *)a_e8;
     p.w_q4 = (const uint8_t *)w_q4; p.w_q8 = (const uint8_t *)w_q8; p.w_e8 = (const uint8_t *)w_e8;
     p.y = (uint16_t *)y; p.M = M; p.N = N; p.ldy = ldy; p.K = K; p.O = O;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (err != hipSuccess) return err;
-        attr_set = true;
-    }
     const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-    hipLaunchKernelGGL(mx_gemm_kernel, dim3((unsigned)tiles), dim3(NT), LDS_BYTES, stream, p);
+    static const bool use_regs = getenv("ATOM_MX_NO_DMA") != nullptr;   // the register-staged kernel, for comparison
+    if (use_regs) {
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+            if (err != hipSuccess) return err;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(mx_gemm_kernel, dim3((unsigned)tiles), dim3(NT), LDS_BYTES, stream, p);
+    } else {
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_dma_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS);
+            if (err != hipSuccess) return err;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(mx_gemm_dma_kernel, dim3((unsigned)tiles), dim3(NT), DMA_LDS, stream, p);
+    }
     return hipGetLastError();
 }
 
