@@ -31,6 +31,7 @@ from paper_2310_19102_amd import synth       # noqa: E402
 
 PEAK_INT8_TOPS = 5000.0     # MI355X dense INT8 MFMA, TOP/s
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, GB/s
+PEAK_FP4_TFLOPS = 10100.0   # MI355X dense FP4 MFMA, TFLOP/s
 
 WORKLOAD_NAMES = {
     1: "tiny M=16 K=512 N=512",
@@ -218,6 +219,49 @@ def extra_measurements():
         torch.cuda.empty_cache()
     out.append(mlp_block_chain())
     out.extend(kv_cache_measurements())
+    out.extend(mx_measurements())
+    return out
+
+
+def mx_measurements():
+    """MX variant (FP4 E2M1 + FP8 E4M3 outliers, E8M0 scale per 32, block scaling inside the
+    scaled MFMA): the two linears of the default workload, front end + GEMM per linear in one
+    HIP graph, and a large square GEMM; the GEMM against the dense FP4 MFMA peak."""
+    out = []
+    cases = [("config4 " + n, synth.make(4, w)) for w, n in ((0, "mlp_gate_up"), (1, "mlp_down"))]
+    total_ops, total_t = 0, 0.0
+    for name, lin in cases:
+        M, K, N = lin.M, lin.K, lin.N
+        x, idx = lin.x.cuda(), lin.idx.cuda()
+        gamma = None if lin.gamma is None else lin.gamma.cuda()
+        qw = atom.atom_mx_quantize_weight(lin.w.cuda(), idx, lin.n_outlier, lin.clip_weight)
+        qa = atom.atom_mx_quantize_act(x, gamma, lin.eps, idx, lin.n_outlier, lin.clip_act)
+        y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+        t_gemm = graph_time(lambda: atom.atom_mx_gemm(*qa, *qw, out=y), 20, 5)
+        t_fe = graph_time(lambda: atom.atom_mx_quantize_act(x, gamma, lin.eps, idx, lin.n_outlier,
+                                                            lin.clip_act, out=qa), 20, 5)
+        ops = 2 * M * N * K
+        total_ops += ops
+        total_t += t_gemm + t_fe
+        out.append({"workload": f"MX variant, {name} M={M} K={K} N={N}, HIP graph",
+                    "gemm_us": t_gemm * 1e6, "front_end_us": t_fe * 1e6,
+                    "gemm_tflops": ops / t_gemm / 1e12, "gemm_fp4_mfma_frac": ops / t_gemm / 1e12 / PEAK_FP4_TFLOPS})
+        del qw, qa, y, x
+        torch.cuda.empty_cache()
+    out.append({"workload": "MX variant, config4 step (both linears, front end + GEMM)",
+                "us_per_step": total_t * 1e6, "effective_tflops": total_ops / total_t / 1e12})
+    M = K = N = 8192
+    gen = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED + 7)
+    x = torch.randn((M, K), generator=gen, device="cuda", dtype=torch.float16)
+    w = torch.randn((N, K), generator=gen, device="cuda", dtype=torch.float16) * 0.02
+    idx = torch.arange(K, dtype=torch.int32, device="cuda")
+    qa = atom.atom_mx_quantize_act(x, None, 0.0, idx, 128, 0.9)
+    qw = atom.atom_mx_quantize_weight(w, idx, 128, 0.85)
+    y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    t = graph_time(lambda: atom.atom_mx_gemm(*qa, *qw, out=y), 10, 5)
+    out.append({"workload": "MX variant, GEMM M=K=N=8192, HIP graph", "gemm_us": t * 1e6,
+                "gemm_tflops": 2 * M * N * K / t / 1e12,
+                "gemm_fp4_mfma_frac": 2 * M * N * K / t / 1e12 / PEAK_FP4_TFLOPS})
     return out
 
 
@@ -345,6 +389,8 @@ def main():
                     help="rows of each linear the CPU oracle is timed on (1024 rows of config 4 take about 12 s)")
     ap.add_argument("--kv-only", action="store_true",
                     help="print only the INT4 KV-cache measurements (a short run to put under rocprofv3)")
+    ap.add_argument("--mx-only", action="store_true",
+                    help="print only the MX-variant measurements (a short run to put under rocprofv3)")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -365,6 +411,9 @@ def main():
 
     if args.kv_only:
         print(json.dumps({"kv_cache": kv_cache_measurements()}))
+        return
+    if args.mx_only:
+        print(json.dumps({"mx": mx_measurements()}))
         return
 
     layers = [DeviceLinear(synth.make(args.config, w))
