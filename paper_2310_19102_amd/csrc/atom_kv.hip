@@ -166,12 +166,11 @@ __device__ __forceinline__ void unpack8(uint32_t w, uint32_t (&pr)[4])
     pr[3] = and_or(b, 0x003C003Cu, 0x5C005C00u);
 }
 
-constexpr int kWaves = 4;                 // wavefronts per workgroup
 constexpr int kTile  = 16;                // tokens per wavefront step
 constexpr int kTokens = 64;                // tokens per wavefront group: four steps, one per ring slot
 
 // One workgroup per (sequence, query head) and split of the token range, head dimension 128.
-// A wavefront owns every fourth group of 64 tokens and walks it in four steps of 16 tokens:
+// A wavefront owns every kWaves-th group of 64 tokens and walks it in four steps of 16 tokens:
 // lane l holds token (l & 15) and the 32 head dimensions of chunk (l >> 4), i.e. 16 bytes of
 // that token's K row and 16 bytes of its V row (a wavefront load is 1 KB of contiguous cache).
 //   scores  : the codes become fp16 offset + c, two at a time (unpack8), and meet the
@@ -182,14 +181,15 @@ constexpr int kTokens = 64;                // tokens per wavefront group: four s
 //   softmax : online, per wavefront (running max m and sum l); the accumulators are rescaled
 //             only when the maximum moves.
 //   values  : acc[d] += w * (16 + code[d]) with w = p * v_scale (unpack8_16), the fp16 codes
-//             read by mixed-precision fmas; the 16 and the zero points leave at the end
-//             through the running sums of w and w * z; the 16 tokens of the lanes meet
-//             once, at the end; the four wavefronts merge through LDS.
+//             read by mixed-precision fmas; the 16 and the zero points leave once per group
+//             of 64 tokens through the sums of w and w * z; the 16 tokens of the lanes meet
+//             once, at the end; the wavefronts merge through LDS.
 //   loads   : the codes of the next group (four steps ahead) are in flight while a step is
 //             computed.  Scales and zero points are read once per group, lane l taking
 //             token l of the 64, one full cache line per array, and reach the lane that
 //             needs them through ds_bpermute: 2-byte loads per step would have several
 //             wavefronts wait on the same line, which stalls the vector cache.
+template <int kWaves>                     // wavefronts per workgroup: 4, or 16 when B * H alone is a thin grid
 __global__ __launch_bounds__(kWaves * 64)
 void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, int64_t Tmax,
                                  const int32_t *__restrict__ seq_len,
@@ -264,7 +264,7 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
     float acc[32];                        // acc[8j + 2k + half] <-> d = 32c + 8j + k + 4 half
 #pragma unroll
     for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
-    float wsum = 0.0f, zacc = 0.0f;       // running sums of w = p * v_scale and of w * v_zero
+    float wsum = 0.0f, zacc = 0.0f;       // sums of w = p * v_scale and of w * v_zero since the last flush
     float m_run = -INFINITY, l_run = 0.0f;
 
     auto consume = [&](const Stage &s_, int tile, int slot) {
@@ -337,6 +337,14 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
                 if (tile * kTile < T) consume(st[i], tile, i);
                 fetch(st[i], 4 * Gn + i);                 // the slot's next use is four steps away
             }
+            // the offsets of this group's four steps leave the accumulators now, not at the end:
+            // left in, their sum grows with the sequence and its rounding would show in
+            // outputs that are small against it
+            const float off = fmaf(16.0f, wsum, zacc);
+#pragma unroll
+            for (int i = 0; i < 32; ++i) acc[i] -= off;
+            wsum = 0.0f;
+            zacc = 0.0f;
             kmeta = nk;
             vmeta = nv;
             G = Gn;
@@ -344,8 +352,6 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
     }
 
     // ---- the 16 tokens of the lanes meet; lane (0, c) then holds chunk c of this wavefront
-    zacc = row16_sum(zacc);
-    wsum = row16_sum(wsum);
 #pragma unroll
     for (int i = 0; i < 32; ++i) acc[i] = row16_sum(acc[i]);
     if (tl == 0) {
@@ -354,9 +360,8 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
 #pragma unroll
             for (int k = 0; k < 4; ++k)
 #pragma unroll
-                for (int hf = 0; hf < 2; ++hf)            // the offsets and zero points leave here
-                    s_acc[wave][32 * c + 8 * j + k + 4 * hf] =
-                        acc[8 * j + 2 * k + hf] - fmaf(16.0f, wsum, zacc);
+                for (int hf = 0; hf < 2; ++hf)
+                    s_acc[wave][32 * c + 8 * j + k + 4 * hf] = acc[8 * j + 2 * k + hf];
     }
     if (lane == 0) {
         s_m[wave] = m_run;
@@ -429,22 +434,31 @@ hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, floa
     return hipGetLastError();
 }
 
-// Splits of the token range per (sequence, head): enough workgroups to keep about five per
-// compute unit resident, never less than one 64-token group per wavefront and split.
-int decode_attention_splits(int B, int H, int64_t Tmax)
+// Shape of the launch.  B * H workgroups of four wavefronts fill the GPU from about five per
+// compute unit; a grid of at most 384 workgroups first gets 16 wavefronts per workgroup (the token range is
+// shared inside the workgroup, which merges through LDS: no second kernel), and below 256
+// workgroups the token range is also split over several workgroups whose partials meet in
+// decode_attention_merge_kernel.  Never less than one 64-token group per wavefront and split.
+struct AttentionShape { int waves, splits; };
+AttentionShape decode_attention_shape(int B, int H, int64_t Tmax)
 {
     const int64_t groups = (Tmax + kTokens - 1) / kTokens;
     const int64_t bh     = (int64_t)B * H;
-    int64_t want = (1280 + bh - 1) / bh;
-    int64_t cap  = groups / kWaves;
+    if (bh > 384 || groups < 16) {
+        int64_t want = (1280 + bh - 1) / bh, cap = groups / 4;
+        if (want > cap) want = cap;
+        if (want > 64) want = 64;
+        return {4, want < 1 ? 1 : (int)want};
+    }
+    int64_t want = (256 + bh - 1) / bh, cap = groups / 16;     // 256 x 16 wavefronts = four per SIMD
     if (want > cap) want = cap;
     if (want > 64) want = 64;
-    return want < 1 ? 1 : (int)want;
+    return {16, want < 1 ? 1 : (int)want};
 }
 
 size_t decode_attention_workspace_bytes(int B, int H, int64_t Tmax)
 {
-    const int S = decode_attention_splits(B, H, Tmax);
+    const int S = decode_attention_shape(B, H, Tmax).splits;
     return S > 1 ? (size_t)B * H * S * (128 + 2) * sizeof(float) : 0;
 }
 
@@ -454,15 +468,22 @@ hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int
                                        const void *vz, float sm_scale, void *out, void *workspace,
                                        hipStream_t stream)
 {
-    const int S      = decode_attention_splits(B, H, Tmax);
+    const AttentionShape sh = decode_attention_shape(B, H, Tmax);
+    const int S      = sh.splits;
     const int groups = (int)((Tmax + kTokens - 1) / kTokens);
     const int tps    = S > 1 ? (groups + S - 1) / S : (groups > 0 ? groups : 1);
     float *part = S > 1 ? (float *)workspace : nullptr;
-    hipLaunchKernelGGL(decode_attention_kv4_kernel, dim3((unsigned)(B * H), (unsigned)S),
-                       dim3(kWaves * 64), 0, stream, (const __half *)q, H, Hkv, Tmax, seq_len,
-                       (const uint8_t *)kq, (const __half *)ks, (const int16_t *)kz,
-                       (const uint8_t *)vq, (const __half *)vs, (const int16_t *)vz, sm_scale,
-                       (__half *)out, tps, part);
+    if (sh.waves == 4)
+        hipLaunchKernelGGL(decode_attention_kv4_kernel<4>, dim3((unsigned)(B * H), (unsigned)S), dim3(256),
+                           0, stream, (const __half *)q, H, Hkv, Tmax, seq_len, (const uint8_t *)kq,
+                           (const __half *)ks, (const int16_t *)kz, (const uint8_t *)vq,
+                           (const __half *)vs, (const int16_t *)vz, sm_scale, (__half *)out, tps, part);
+    else
+        hipLaunchKernelGGL(decode_attention_kv4_kernel<16>, dim3((unsigned)(B * H), (unsigned)S),
+                           dim3(1024), 0, stream, (const __half *)q, H, Hkv, Tmax, seq_len,
+                           (const uint8_t *)kq, (const __half *)ks, (const int16_t *)kz,
+                           (const uint8_t *)vq, (const __half *)vs, (const int16_t *)vz, sm_scale,
+                           (__half *)out, tps, part);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || S == 1) return err;
     hipLaunchKernelGGL(decode_attention_merge_kernel, dim3((unsigned)(B * H)), dim3(128), 0, stream,

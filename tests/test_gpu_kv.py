@@ -126,8 +126,10 @@ def _attention_case(kv, what):
     (2, 8, 2, 257, [257, 129]),          # grouped-query attention: 4 query heads per cache head
     (1, 32, 32, 1000, None),             # Llama-7B heads, a mix of lengths
     (4, 8, 1, 70, [1, 2, 3, 70]),        # multi-query; fewer tokens than wavefronts
-    (2, 2, 2, 2048, [2048, 300]),        # token range split 8 ways; most splits of sequence 1 are empty
-    (1, 4, 2, 1500, [1234]),             # split 5 ways with a ragged last split
+    (2, 2, 2, 2048, [2048, 300]),        # token range split; most of sequence 1's share is empty
+    (1, 4, 2, 1500, [1234]),             # 16 wavefronts per workgroup, ragged last group
+    (1, 2, 1, 8192, [8000]),             # 16 wavefronts per workgroup and 8 splits
+    (5, 64, 8, 1100, None),              # 320 workgroups of 16 wavefronts, no split; 8 query heads per cache head
 ])
 def test_decode_attention(B, H, Hkv, Tmax, lens):
     kv = synth.kv_case(B, H, Hkv, 128, Tmax, seq_lens=lens, case_id=10 + Tmax)
