@@ -363,7 +363,6 @@ void mx_gemm_kernel(MxParams p)
 // the barriers below are written by hand (ten loads per wavefront and tile, two tiles may
 // stay in flight).
 constexpr int DMA_STAGES = 4;
-constexpr int DMA_LDS = DMA_STAGES * STAGE > 4 * EPI_WAVE ? DMA_STAGES * STAGE : 4 * EPI_WAVE;
 
 __device__ __forceinline__ void dma16(uint32_t lds, uint32_t voff, const uint8_t *sbase)
 {
@@ -376,31 +375,51 @@ __device__ __forceinline__ void dma4(uint32_t lds, uint32_t voff, const uint8_t 
                  :: "s"(lds), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1)))
+// Geometry for WT x WT MFMA tiles per wavefront (2 x 2 wavefronts): WT = 4 is the 256 x 256
+// workgroup tile, WT = 2 a 128 x 128 tile for grids that would leave most of the GPU idle
+// with the large one (its 64 accumulator registers let two workgroups share a CU).
+template <int WT>
+struct DmaGeom {
+    static constexpr int TB     = 64 * WT;                 // tile rows = tile columns
+    static constexpr int CODES  = 2 * TB * ROWB;           // bytes of codes per stage
+    static constexpr int STAGE  = CODES + 2 * 256 * 4;     // + 256 A and 256 B scale dwords (rows past TB unused)
+    static constexpr int NBLK   = 2 * TB / 16 / 4;         // kilobyte blocks per wavefront and stage
+    static constexpr int PITCH  = 64 * WT + 16;            // output row of a wavefront in LDS, bytes
+    static constexpr int EPIW   = 64 * PITCH;              // 64 rows per pass
+    static constexpr int LDS    = DMA_STAGES * STAGE > 4 * EPIW ? DMA_STAGES * STAGE : 4 * EPIW;
+    static constexpr int LOADS  = NBLK + 2;                // DMA instructions per wavefront and tile
+    // s_waitcnt: vmcnt(2 * LOADS) (two tiles may stay in flight), lgkmcnt(0), expcnt untouched
+    static constexpr int LANDED = ((2 * LOADS) & 15) | (7 << 4) | (((2 * LOADS) >> 4) << 14);
+};
+
+template <int WT>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, WT == 4 ? 1 : 2)))
 void mx_gemm_dma_kernel(MxParams p)
 {
+    using Gm = DmaGeom<WT>;
+    constexpr int TB = Gm::TB, CODES_ = Gm::CODES, STAGE_ = Gm::STAGE, NBLK = Gm::NBLK;
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int lr = lane & 31, g = lane >> 5;
 
-    const int tiles_m = (int)((p.M + BM - 1) / BM);
+    const int tiles_m = (int)((p.M + TB - 1) / TB);
     const int bid = atom_gemm::xcd_contiguous_block_id();
-    const int64_t m0 = (int64_t)(bid % tiles_m) * BM, n0 = (int64_t)(bid / tiles_m) * BN;
+    const int64_t m0 = (int64_t)(bid % tiles_m) * TB, n0 = (int64_t)(bid / tiles_m) * TB;
 
     const int K4 = p.K - p.O;
     const int S4 = K4 >> 7, S8 = p.O >> 6, S = S4 + S8;
 
-    // ---- loader: wavefront w fills the kilobyte blocks 8 w .. 8 w + 7 of a stage (blocks
-    // 0..15 are the A rows, 16..31 the B rows: wavefronts 0, 1 load A, wavefronts 2, 3 load B)
-    // and 64 of the A and 64 of the B scale dwords
+    // ---- loader: wavefront w fills the kilobyte blocks NBLK w .. NBLK w + NBLK - 1 of a stage
+    // (the first half of the blocks are the A rows: wavefronts 0, 1 load A, wavefronts 2, 3
+    // load B) and 64 of the A and 64 of the B scale dwords
     const bool loadsA = wave < 2;
-    uint32_t goff[8];
+    uint32_t goff[NBLK];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int trow = 16 * (8 * wave + j) + (lane >> 2);              // row of the 512-row stage
-        int64_t r = loadsA ? m0 + trow : n0 + (trow - BM);
+    for (int j = 0; j < NBLK; ++j) {
+        const int trow = 16 * (NBLK * wave + j) + (lane >> 2);           // row of the 2 TB-row stage
+        int64_t r = loadsA ? m0 + trow : n0 + (trow - TB);
         const int64_t last = (loadsA ? p.M : p.N) - 1;
         r = r < last ? r : last;                                         // ragged tiles repeat the last row
         goff[j] = (uint32_t)r * ROWB + 16u * (((lane & 3) - (lane >> 4)) & 3);
@@ -415,40 +434,40 @@ void mx_gemm_dma_kernel(MxParams p)
         const int64_t d  = f8 ? S4 + (u >> 1) : u - S8;            // slab index inside e8
         const uint8_t *src = loadsA ? (f8 ? p.a_q8 : p.a_q4) + sl * p.M * ROWB
                                     : (f8 ? p.w_q8 : p.w_q4) + sl * p.N * ROWB;
-        const uint32_t st = lds0 + buf * STAGE;
+        const uint32_t st = lds0 + buf * STAGE_;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) dma16(st + 1024 * (8 * wave + j), goff[j], src);
-        dma4(st + CODES + 256 * wave, sca, p.a_e8 + d * p.M * 4);
-        dma4(st + CODES + 4 * BM + 256 * wave, scb, p.w_e8 + d * p.N * 4);
+        for (int j = 0; j < NBLK; ++j) dma16(st + 1024 * (NBLK * wave + j), goff[j], src);
+        dma4(st + CODES_ + 256 * wave, sca, p.a_e8 + d * p.M * 4);
+        dma4(st + CODES_ + 1024 + 256 * wave, scb, p.w_e8 + d * p.N * 4);
     };
     // all but the two newest tiles' loads of this wavefront have landed, and its own LDS reads are done
-#define ATOM_MX_LANDED() __builtin_amdgcn_s_waitcnt(0x4074) /* vmcnt(20), lgkmcnt(0) */
+#define ATOM_MX_LANDED() __builtin_amdgcn_s_waitcnt(Gm::LANDED)
 
-    v16f acc[4][4];
+    v16f acc[WT][WT];
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
+    for (int s = 0; s < WT; ++s)
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < WT; ++t)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[s][t][v] = 0.0f;
 
-    const int a_base = mx_lds_off(128 * wm + lr, g);
-    const int b_base = mx_lds_off(BM + 128 * wn + lr, g);
-    const int sa_off = CODES + 4 * (128 * wm + lr), sb_off = CODES + 4 * (BM + 128 * wn + lr);
-    int sa[4], sb[4];
+    const int a_base = mx_lds_off(32 * WT * wm + lr, g);
+    const int b_base = mx_lds_off(TB + 32 * WT * wn + lr, g);
+    const int sa_off = CODES_ + 4 * (32 * WT * wm + lr), sb_off = CODES_ + 1024 + 4 * (32 * WT * wn + lr);
+    int sa[WT], sb[WT];
     auto read_scales = [&](const uint8_t *buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int s = 0; s < WT; ++s) {
             sa[s] = (int)(*reinterpret_cast<const uint32_t *>(buf + sa_off + 128 * s) >> (8 * g));
             sb[s] = (int)(*reinterpret_cast<const uint32_t *>(buf + sb_off + 128 * s) >> (8 * g));
         }
     };
-    auto mma16 = [&](auto fmt, auto opsel, const v8i (&af)[4], const v8i (&bf)[4], const int (&sa_)[4],
-                     const int (&sb_)[4]) __attribute__((always_inline)) {
+    auto mma = [&](auto fmt, auto opsel, const v8i (&af)[WT], const v8i (&bf)[WT], const int (&sa_)[WT],
+                   const int (&sb_)[WT]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < WT; ++s)
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int t = 0; t < WT; ++t)
                 acc[s][t] = mfma_mx<decltype(fmt)::value, decltype(opsel)::value>(af[s], bf[t], acc[s][t],
                                                                                   sa_[s], sb_[t]);
     };
@@ -466,9 +485,9 @@ void mx_gemm_dma_kernel(MxParams p)
     __syncthreads();
 
     // ---- FP8 steps first, in pairs
-    auto load8 = [&](const uint8_t *buf, v8i (&af8)[4], v8i (&bf8)[4]) __attribute__((always_inline)) {
+    auto load8 = [&](const uint8_t *buf, v8i (&af8)[WT], v8i (&bf8)[WT]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int s = 0; s < WT; ++s) {
             af8[s] = join(*reinterpret_cast<const v4i *>(buf + (a_base + 2048 * s)),
                           *reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));
             bf8[s] = join(*reinterpret_cast<const v4i *>(buf + (b_base + 2048 * s)),
@@ -486,10 +505,10 @@ void mx_gemm_dma_kernel(MxParams p)
 #define ATOM_MX_FP8_STEP(u, OPSEL)                                                               \
     do {                                                                                         \
         request(min((u) + 3, S - 1), nx3);                                                       \
-        v8i af8[4], bf8[4];                                                                      \
-        load8(smem + cur * STAGE, af8, bf8);                                                     \
-        read_scales(smem + cur * STAGE);                                                         \
-        mma16(fp8{}, OPSEL{}, af8, bf8, sa, sb);                                                 \
+        v8i af8[WT], bf8[WT];                                                                    \
+        load8(smem + cur * STAGE_, af8, bf8);                                                    \
+        read_scales(smem + cur * STAGE_);                                                        \
+        mma(fp8{}, OPSEL{}, af8, bf8, sa, sb);                                                   \
         ATOM_MX_LANDED();                                                                        \
         __syncthreads();                                                                         \
         ATOM_MX_ROTATE();                                                                        \
@@ -502,48 +521,49 @@ void mx_gemm_dma_kernel(MxParams p)
 #undef ATOM_MX_FP8_STEP
 
     // ---- FP4 steps, software-pipelined as in mx_gemm_kernel
-    v8i af[4], bf[4];
+    v8i af[WT], bf[WT];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        af[s] = widen(*reinterpret_cast<const v4i *>(smem + cur * STAGE + (a_base + 2048 * s)));
-        bf[s] = widen(*reinterpret_cast<const v4i *>(smem + cur * STAGE + (b_base + 2048 * s)));
+    for (int s = 0; s < WT; ++s) {
+        af[s] = widen(*reinterpret_cast<const v4i *>(smem + cur * STAGE_ + (a_base + 2048 * s)));
+        bf[s] = widen(*reinterpret_cast<const v4i *>(smem + cur * STAGE_ + (b_base + 2048 * s)));
     }
-    read_scales(smem + cur * STAGE);
+    read_scales(smem + cur * STAGE_);
     for (; u < S; ++u) {
-        const uint8_t *buf = smem + cur * STAGE, *nbuf = smem + nxt * STAGE;
+        const uint8_t *buf = smem + cur * STAGE_, *nbuf = smem + nxt * STAGE_;
         request(min(u + 3, S - 1), nx3);
-        v8i ag[4], bg[4];
+        v8i ag[WT], bg[WT];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int s = 0; s < WT; ++s) {
             ag[s] = widen(*reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));
             bg[s] = widen(*reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * s)));
         }
-        mma16(fp4{}, b0{}, af, bf, sa, sb);
+        mma(fp4{}, b0{}, af, bf, sa, sb);
+        // the reads go out under the first MFMAs, the remaining MFMAs cover them
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < 2 * WT; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        if (WT * WT > 2 * WT) __builtin_amdgcn_sched_group_barrier(0x008, WT * WT - 2 * WT, 0);
         ATOM_MX_LANDED();                 // tile u+1 is in its stage ...
         __syncthreads();                  // ... for every wavefront; stage u has been read
         __builtin_amdgcn_sched_barrier(0);
-        int sc[4], sd[4];
+        int sc[WT], sd[WT];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int s = 0; s < WT; ++s) {
             sc[s] = sa[s];
             sd[s] = sb[s];
             af[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (a_base + 2048 * s)));
             bf[s] = widen(*reinterpret_cast<const v4i *>(nbuf + (b_base + 2048 * s)));
         }
         read_scales(nbuf);
-        mma16(fp4{}, b2{}, ag, bg, sc, sd);
+        mma(fp4{}, b2{}, ag, bg, sc, sd);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < 2 * WT; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 1);
+        if (WT * WT > 2 * WT) __builtin_amdgcn_sched_group_barrier(0x008, WT * WT - 2 * WT, 1);
         __builtin_amdgcn_sched_barrier(0);
         ATOM_MX_ROTATE();
     }
@@ -553,43 +573,45 @@ void mx_gemm_dma_kernel(MxParams p)
     // ---- store, as in mx_gemm_kernel; the last (repeated) requests must have landed before the
     // stages are reused
     __builtin_amdgcn_s_waitcnt(0x0F70);                            // vmcnt(0)
-    const int64_t wrow = m0 + 128 * wm, wcol = n0 + 128 * wn;
-    const bool whole = wrow + 128 <= p.M && wcol + 128 <= p.N && (p.ldy & 7) == 0 &&
+    const int64_t wrow = m0 + 32 * WT * wm, wcol = n0 + 32 * WT * wn;
+    const bool whole = wrow + 32 * WT <= p.M && wcol + 32 * WT <= p.N && (p.ldy & 7) == 0 &&
                        (reinterpret_cast<uintptr_t>(p.y) & 15) == 0;
     __syncthreads();
     if (whole) {
-        uint8_t *reg = smem + wave * EPI_WAVE;
+        // passes of 64 rows; a row of the wavefront's block is 64 WT bytes = 4 WT lanes of 16 bytes
+        uint8_t *reg = smem + wave * Gm::EPIW;
+        constexpr int LPR = 4 * WT;                                // lanes per output row
 #pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
+        for (int pass = 0; pass < WT / 2; ++pass) {
 #pragma unroll
             for (int sh = 0; sh < 2; ++sh)
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
+                for (int t = 0; t < WT; ++t)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int r = 32 * sh + 8 * (v >> 2) + 4 * g + (v & 3);
-                        *reinterpret_cast<uint16_t *>(reg + r * EPI_PITCH + 2 * (32 * t + lr)) =
+                        *reinterpret_cast<uint16_t *>(reg + r * Gm::PITCH + 2 * (32 * t + lr)) =
                             __half_as_ushort(__float2half_rn(acc[2 * pass + sh][t][v]));
                     }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int r = 4 * i + (lane >> 4);
-                const v4i d = *reinterpret_cast<const v4i *>(reg + r * EPI_PITCH + 16 * (lane & 15));
-                *reinterpret_cast<v4i *>(p.y + (wrow + 64 * pass + r) * p.ldy + wcol + 8 * (lane & 15)) = d;
+            for (int i = 0; i < 64 * LPR / 64; ++i) {
+                const int r = (64 / LPR) * i + lane / LPR;
+                const v4i d = *reinterpret_cast<const v4i *>(reg + r * Gm::PITCH + 16 * (lane % LPR));
+                *reinterpret_cast<v4i *>(p.y + (wrow + 64 * pass + r) * p.ldy + wcol + 8 * (lane % LPR)) = d;
             }
         }
     } else {
         const int64_t row0 = wrow + 4 * g, col0 = wcol + lr;
         uint16_t *yp = p.y + row0 * p.ldy + col0;
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < WT; ++s)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int dr = 32 * s + 8 * (v >> 2) + (v & 3);
                 if (row0 + dr < p.M) {
                     uint16_t *yr = yp + (int64_t)dr * p.ldy;
 #pragma unroll
-                    for (int t = 0; t < 4; ++t)
+                    for (int t = 0; t < WT; ++t)
                         if (col0 + 32 * t < p.N) yr[32 * t] = __half_as_ushort(__float2half_rn(acc[s][t][v]));
                 }
             }
@@ -619,15 +641,27 @@ hipError_t launch_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8, 
             attr_set = true;
         }
         hipLaunchKernelGGL(mx_gemm_kernel, dim3((unsigned)tiles), dim3(NT), LDS_BYTES, stream, p);
-    } else {
+    } else if (tiles >= 192) {
         static bool attr_set = false;
         if (!attr_set) {
-            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_dma_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS);
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_dma_kernel<4>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, DmaGeom<4>::LDS);
             if (err != hipSuccess) return err;
             attr_set = true;
         }
-        hipLaunchKernelGGL(mx_gemm_dma_kernel, dim3((unsigned)tiles), dim3(NT), DMA_LDS, stream, p);
+        hipLaunchKernelGGL(mx_gemm_dma_kernel<4>, dim3((unsigned)tiles), dim3(NT), DmaGeom<4>::LDS, stream, p);
+    } else {
+        // fewer 256 x 256 tiles than would occupy three quarters of the CUs: 128 x 128 tiles, two
+        // workgroups per CU (measured on M = 1024, K = 11008, N = 4096: 82 -> 40 us)
+        const int64_t small = ((M + 127) / 128) * ((N + 127) / 128);
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_dma_kernel<2>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, DmaGeom<2>::LDS);
+            if (err != hipSuccess) return err;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(mx_gemm_dma_kernel<2>, dim3((unsigned)small), dim3(NT), DmaGeom<2>::LDS, stream, p);
     }
     return hipGetLastError();
 }
