@@ -84,3 +84,57 @@ def test_synthetic_inputs_are_seeded_and_shaped():
     mag = lin.x.float().abs().mean(0)[lin.idx.long()]
     assert mag[-128:].min() > mag[:-128].median()
     assert torch.isfinite(lin.x.float()).all()
+
+
+def test_host_side_validation_of_the_kv_cache_and_mx_entry_points():
+    """Same contract for the entry points of the INT4 KV cache and of the MX variant."""
+    lib = atom.load_library()
+    D = binding._Desc
+    p = ctypes.c_void_p(0x1000)
+    kvq = lib.atom_kv_quantize
+    assert kvq(None, 4, 128, 128, 1.0, None, 0, 0, p, p, p, None) == 1
+    assert kvq(p, 4, 128, 96, 1.0, None, 0, 0, p, p, p, None) == 3              # head dimension not built
+    assert kvq(p, 4, 128, 7, 1.0, None, 0, 0, p, p, p, None) == 2
+    assert kvq(p, 4, 64, 128, 1.0, None, 0, 0, p, p, p, None) == 2              # ldx < D
+    assert kvq(p, 5, 128, 128, 1.0, p, 4, 16, p, p, p, None) == 2               # rows not a multiple of rows_per_seq
+    assert kvq(p, 4, 128, 128, 1.0, p, 4, 0, p, p, p, None) == 2                # Tmax
+    assert kvq(p, 0, 128, 128, 1.0, None, 0, 0, p, p, p, None) == 0
+    assert kvq(ctypes.c_void_p(0x1002), 4, 128, 128, 1.0, None, 0, 0, p, p, p, None) == 4
+    att = lib.atom_decode_attention_kv4
+    base = [p, 2, 8, 4, 128, 64, p, p, p, p, p, p, p, 1.0, p]
+    assert att(*base[:2], 6, *base[3:], None, 0, None) == 2                     # H % Hkv
+    assert att(*base[:4], 64, *base[5:], None, 0, None) == 3                    # head dimension
+    assert att(*base[:6], None, *base[7:], None, 0, None) == 1                  # seq_len
+    assert att(p, 0, *base[2:], None, 0, None) == 0
+    assert lib.atom_decode_attention_kv4_workspace_bytes(64, 32, 128, 1024) == 0
+    need = lib.atom_decode_attention_kv4_workspace_bytes(1, 2, 128, 8192)
+    assert need > 0 and need % (130 * 4) == 0
+    assert att(p, 1, 2, 2, 128, 8192, p, p, p, p, p, p, p, 1.0, p, None, 0, None) == 5   # workspace missing
+    assert lib.atom_decode_attention_kv4_workspace_bytes(1, 2, 64, 8192) == 0
+
+    mq = lib.atom_mx_quantize_act
+    ok = D(4096, 32, 128, 4, 8)
+    assert mq(None, 4, 4096, None, 0.0, p, ctypes.byref(ok), 1.0, p, p, p, None) == 1
+    assert mq(p, 0, 4096, None, 0.0, p, ctypes.byref(ok), 1.0, p, p, p, None) == 0
+    for desc, want in ((D(4096, 128, 128, 4, 8), 3), (D(4096, 32, 64, 4, 8), 2), (D(4096, 32, 0, 4, 8), 3),
+                       (D(4000, 32, 128, 4, 8), 2), (D(4096, 32, 128, 4, 4), 3)):
+        assert mq(p, 4, 65536, None, 0.0, p, ctypes.byref(desc), 1.0, p, p, p, None) == want
+    mg = lib.atom_mx_gemm
+    assert mg(p, p, p, 4, p, p, p, 8, ctypes.byref(ok), p, 4, None) == 2         # ldy < N
+    assert mg(p, p, None, 4, p, p, p, 8, ctypes.byref(ok), p, 8, None) == 1
+    assert mg(p, p, p, 0, p, p, p, 8, ctypes.byref(ok), p, 8, None) == 0
+    assert mg(p, p, ctypes.c_void_p(0x1002), 4, p, p, p, 8, ctypes.byref(ok), p, 8, None) == 4
+
+
+def test_kv_inputs_are_seeded():
+    a, b = synth.kv_case(2, 4, 2, 128, 33, case_id=1), synth.kv_case(2, 4, 2, 128, 33, case_id=1)
+    assert torch.equal(a.k, b.k) and torch.equal(a.v, b.v) and torch.equal(a.q, b.q)
+    assert torch.equal(a.seq_len, b.seq_len) and int(a.seq_len.max()) <= 33 and int(a.seq_len.min()) >= 1
+    assert a.k.shape == (2, 2, 33, 128) and a.q.shape == (2, 4, 128) and a.k.dtype == torch.float16
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
