@@ -54,7 +54,10 @@ __device__ __forceinline__ v4i widen_hi(const uint4 &w)
 }
 
 // RB: 16-row blocks of activations (M <= 16 * RB)
-template <int RB>
+// VS: every wavefront's run of groups is a whole number of batches that start on a multiple
+//     of four groups, so the four scales of a batch are one aligned 8-byte load per row
+//     (instead of four 2-byte loads that several wavefronts request from the same lines)
+template <int RB, bool VS>
 __global__ __launch_bounds__(NT)
 void w4a4_gemm_decode_kernel(const GemmParams p)
 {
@@ -123,7 +126,7 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
                 wq[d][0] = *reinterpret_cast<const uint4 *>(w8 + (size_t)(gc - G4) * 128);
                 wq[d][1] = *reinterpret_cast<const uint4 *>(w8 + (size_t)(gc - G4) * 128 + 64);
             }
-            wsc[d] = ws[gc];
+            if constexpr (!VS) wsc[d] = ws[gc];
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
                 aq[d][rb][0] = z4; aq[d][rb][1] = z4;
@@ -135,12 +138,30 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
                         aq[d][rb][1] = *reinterpret_cast<const uint4 *>(a8[rb] + (size_t)(gc - G4) * 128 + 64);
                     }
                 }
+                if constexpr (!VS) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int64_t m = 16 * rb + 4 * kc + e;
+                        asc[d][rb][e] = m < p.M ? p.a_scale[m * G + gc] : (uint16_t)0;
+                    }
+                }
+            }
+        }
+        if constexpr (VS) {
+            static_assert(!VS || DEPTH == 4, "a batch is four groups");
+            const uint2 wv = *reinterpret_cast<const uint2 *>(ws + gb);
+            wsc[0] = (uint16_t)wv.x; wsc[1] = (uint16_t)(wv.x >> 16);
+            wsc[2] = (uint16_t)wv.y; wsc[3] = (uint16_t)(wv.y >> 16);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int64_t m = 16 * rb + 4 * kc + e;
-                    asc[d][rb][e] = m < p.M ? p.a_scale[m * G + gc] : (uint16_t)0;
+                    uint2 av = make_uint2(0, 0);
+                    if (m < p.M) av = *reinterpret_cast<const uint2 *>(p.a_scale + m * G + gb);
+                    asc[0][rb][e] = (uint16_t)av.x; asc[1][rb][e] = (uint16_t)(av.x >> 16);
+                    asc[2][rb][e] = (uint16_t)av.y; asc[3][rb][e] = (uint16_t)(av.y >> 16);
                 }
-            }
         }
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
@@ -190,9 +211,19 @@ namespace atom_gemm {
 hipError_t launch_decode(const GemmParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)((p.N + TN - 1) / TN);
-    if (p.M <= 16)      hipLaunchKernelGGL(w4a4_gemm_decode_kernel<1>, dim3(blocks), dim3(NT), 0, stream, p);
-    else if (p.M <= 32) hipLaunchKernelGGL(w4a4_gemm_decode_kernel<2>, dim3(blocks), dim3(NT), 0, stream, p);
-    else                hipLaunchKernelGGL(w4a4_gemm_decode_kernel<4>, dim3(blocks), dim3(NT), 0, stream, p);
+    // vector scale loads: every wavefront's run of G / NW groups starts on a multiple of four
+    // and is a whole number of four-group batches; both scale arrays 8-byte aligned
+    const int  G  = p.K >> 7;
+    const bool vs = G % (4 * NW) == 0 && ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 7) == 0;
+    if (p.M <= 16) {
+        if (vs) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, false>), dim3(blocks), dim3(NT), 0, stream, p);
+    } else if (p.M <= 32) {
+        if (vs) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, false>), dim3(blocks), dim3(NT), 0, stream, p);
+    } else {
+        hipLaunchKernelGGL((w4a4_gemm_decode_kernel<4, false>), dim3(blocks), dim3(NT), 0, stream, p);
+    }
     return hipGetLastError();
 }
 
