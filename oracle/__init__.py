@@ -82,6 +82,8 @@ def _load():
     L.atom_ref_mx_quantize_act.argtypes = [vp, i64, i64, vp, f32, vp, i32, i32, f32, vp, vp, vp]
     L.atom_ref_mx_gemm.restype = ctypes.c_int
     L.atom_ref_mx_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, i32, i32, vp, i64]
+    L.atom_ref_calibrate_reorder.restype = ctypes.c_int
+    L.atom_ref_calibrate_reorder.argtypes = [vp, i64, i64, i32, vp, vp]
     L.atom_ref_quantize_weight.restype = ctypes.c_int
     L.atom_ref_quantize_weight.argtypes = [vp, i64, i64, vp, i32, i32, i32, f32, vp, vp, vp]
     L.atom_ref_w4a4_gemm.restype = ctypes.c_int
@@ -336,3 +338,16 @@ def mx_gemm(a_q4, a_q8, a_e8, w_q4, w_q8, w_e8):
     if rc != 0:
         raise ValueError("atom_ref_mx_gemm: bad shapes")
     return y
+
+
+def calibrate_reorder(x):
+    """Per-channel square sums (float64 [K]) of calibration activations x float16 [T, K] and the
+    reorder index (int32 [K], ascending by (square sum, channel), outliers last)."""
+    x = _c(x, np.float16)
+    T, K = x.shape
+    stat = np.zeros(K, np.float64)
+    idx = np.zeros(K, np.int32)
+    rc = _load().atom_ref_calibrate_reorder(_p(x), T, K, K, _p(stat), _p(idx))
+    if rc != 0:
+        raise ValueError("atom_ref_calibrate_reorder: bad shapes")
+    return stat, idx

@@ -596,3 +596,37 @@ int atom_ref_mx_gemm(const uint8_t *a_q4, const uint8_t *a_q8, const uint8_t *a_
     free(w);
     return 0;
 }
+
+/* ------------------------------------------------ offline calibration -- */
+/* Section 5.1: the outlier channels are the ones with the highest square sum
+ * over the calibration activations; activations and weights are reordered by
+ * their indices.  Statistic of channel k: sum_t x[t,k]^2 in double, the rows
+ * of a chunk of 256 added in ascending order and the chunk sums added in
+ * ascending order (one fixed tree, so the value is unique).  Index: channels in
+ * ascending order of (statistic, channel number): the O largest come last for
+ * every O, and equal channels keep their order. */
+int atom_ref_calibrate_reorder(const uint16_t *x, int64_t T, int64_t ldx, int32_t K,
+                               double *stat, int32_t *idx)
+{
+    if (T < 0 || K <= 0 || ldx < K) return -1;
+    for (int32_t k = 0; k < K; ++k) {
+        double s = 0.0;
+        for (int64_t c = 0; c < T; c += 256) {
+            double part = 0.0;
+            int64_t end = c + 256 < T ? c + 256 : T;
+            for (int64_t t = c; t < end; ++t) {
+                double v = (double)atom_ref_f16_to_f32(x[t * ldx + k]);
+                part += v * v;
+            }
+            s += part;
+        }
+        stat[k] = s;
+    }
+    for (int32_t i = 0; i < K; ++i) {
+        int32_t rank = 0;
+        for (int32_t j = 0; j < K; ++j)
+            if (stat[j] < stat[i] || (stat[j] == stat[i] && j < i)) ++rank;
+        idx[rank] = i;
+    }
+    return 0;
+}

@@ -177,6 +177,14 @@ int atom_ref_mx_gemm(const uint8_t *a_q4, const uint8_t *a_q8, const uint8_t *a_
                      const uint8_t *w_e8, int64_t N, int32_t K, int32_t O,
                      uint16_t *y_f16, int64_t ldy);
 
+/* ---- Offline calibration (Section 5.1): per-channel square sum of the
+ * calibration activations x [T, ldx] fp16 in double (rows of a 256-row chunk in
+ * ascending order, then the chunks in ascending order), and the reorder index:
+ * channels in ascending order of (square sum, channel number), so that the O
+ * channels with the highest square sums come last. */
+int atom_ref_calibrate_reorder(const uint16_t *x_f16, int64_t T, int64_t ldx, int32_t K,
+                               double *stat /* [K] */, int32_t *idx /* [K] */);
+
 #ifdef __cplusplus
 }
 #endif
