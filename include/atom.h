@@ -291,6 +291,32 @@ atom_status atom_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8,
                          const void *w_e8, int64_t N, const atom_desc *d,
                          void *y_f16, int64_t ldy, void *stream);
 
+/*
+ * Offline calibration (Section 5.1: the channels with the highest square sums
+ * over the calibration activations are the outliers; activations and weights
+ * are reordered by their indices).  From calibration activations X [T, ldx]
+ * fp16 (device; T rows of K channels, e.g. the inputs a layer saw on the
+ * calibration sentences):
+ *   stat[k] = sum_t X[t, k]^2 in double, the rows of a chunk of 256 added in
+ *             ascending order, then the chunk sums in ascending order
+ *   idx     = the channels in ascending order of (stat, channel number): a
+ *             permutation whose last O entries are the O channels with the
+ *             highest square sums, for every O; equal channels keep their order
+ * idx is what atom_quantize_act / atom_quantize_weight (and the MX variants)
+ * take as reorder_idx.  Results are bit-exact.  T == 0 gives the identity.
+ *
+ *   workspace  device scratch of atom_calibrate_reorder_workspace_bytes(T, K)
+ *              bytes, 8-byte aligned; its last K doubles hold stat afterwards
+ *   idx_out    device int32 [K]
+ * Errors: ATOM_ERR_NULL, ATOM_ERR_SHAPE (T < 0, K <= 0, ldx < K),
+ * ATOM_ERR_UNSUPPORTED (K > 32768), ATOM_ERR_ALIGN, ATOM_ERR_WORKSPACE.
+ */
+atom_status atom_calibrate_reorder(const void *x_f16, int64_t T, int64_t ldx,
+                                   int32_t K, void *workspace,
+                                   size_t workspace_bytes, int32_t *idx_out,
+                                   void *stream);
+size_t atom_calibrate_reorder_workspace_bytes(int64_t T, int32_t K);
+
 /* Host helper: ATOM_OK iff idx_host[0..K) is a permutation of 0..K-1. */
 atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K);
 

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     atom_mx_quantize_act,
     atom_mx_quantize_weight,
     atom_mx_gemm,
+    atom_calibrate_reorder,
     atom_kv_quantize,
     atom_decode_attention_kv4,
     atom_decode_attention_kv4_workspace_bytes,

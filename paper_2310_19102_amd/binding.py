@@ -25,6 +25,8 @@ EXPORTS = (
     "atom_mx_quantize_act",
     "atom_mx_quantize_weight",
     "atom_mx_gemm",
+    "atom_calibrate_reorder",
+    "atom_calibrate_reorder_workspace_bytes",
     "atom_kv_quantize",
     "atom_decode_attention_kv4",
     "atom_decode_attention_kv4_workspace_bytes",
@@ -80,6 +82,10 @@ def load_library():
     L.atom_mx_quantize_weight.argtypes = [vp, i64, i64, vp, dp, f32, vp, vp, vp, vp]
     L.atom_mx_gemm.restype = ctypes.c_int
     L.atom_mx_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, dp, vp, i64, vp]
+    L.atom_calibrate_reorder.restype = ctypes.c_int
+    L.atom_calibrate_reorder.argtypes = [vp, i64, i64, i32, vp, sz, vp, vp]
+    L.atom_calibrate_reorder_workspace_bytes.restype = sz
+    L.atom_calibrate_reorder_workspace_bytes.argtypes = [i64, i32]
     L.atom_kv_quantize.restype = ctypes.c_int
     L.atom_kv_quantize.argtypes = [vp, i64, i64, i32, f32, vp, i32, i64, vp, vp, vp, vp]
     L.atom_decode_attention_kv4.restype = ctypes.c_int
@@ -452,3 +458,22 @@ def atom_mx_gemm(a_q4, a_q8, a_e8, w_q4, w_q8, w_e8, out: Optional[torch.Tensor]
     if st != 0:
         raise AtomError(st, "atom_mx_gemm")
     return out
+
+
+def atom_calibrate_reorder(x: torch.Tensor):
+    """Reorder index from calibration activations ``x`` [T, K] fp16: the channels in ascending
+    order of their square sums (double), the outliers last.  Returns ``(idx int32 [K],
+    stat float64 [K])`` device tensors."""
+    L = load_library()
+    _dev(x, torch.float16, "x")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [T, K] with a contiguous last dimension")
+    T, K = x.shape
+    need = int(L.atom_calibrate_reorder_workspace_bytes(T, K))
+    ws = torch.empty(max(need, 8) // 8, dtype=torch.float64, device=x.device)
+    idx = torch.empty(K, dtype=torch.int32, device=x.device)
+    st = L.atom_calibrate_reorder(_ptr(x), T, x.stride(0) if T > 1 else max(K, x.stride(0)), K, _ptr(ws),
+                                  ws.numel() * 8, _ptr(idx), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_calibrate_reorder")
+    return idx, ws[-K:]

@@ -269,6 +269,30 @@ atom_status atom_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8, i
 
 extern "C" {
 
+size_t atom_calibrate_reorder_workspace_bytes(int64_t T, int32_t K)
+{
+    if (T < 0 || K <= 0 || K > atom_internal::kMaxK) return 0;
+    return atom_internal::calibrate_workspace_bytes(T, K);
+}
+
+atom_status atom_calibrate_reorder(const void *x_f16, int64_t T, int64_t ldx, int32_t K,
+                                   void *workspace, size_t workspace_bytes, int32_t *idx_out,
+                                   void *stream)
+{
+    if (T < 0 || K <= 0 || ldx < K) return ATOM_ERR_SHAPE;
+    if (K > atom_internal::kMaxK || (T + 255) / 256 > 65535) return ATOM_ERR_UNSUPPORTED;
+    if (!idx_out || !workspace || (T > 0 && !x_f16)) return ATOM_ERR_NULL;
+    if (!aligned(x_f16, 2) || !aligned(workspace, 8) || !aligned(idx_out, 4)) return ATOM_ERR_ALIGN;
+    if (workspace_bytes < atom_internal::calibrate_workspace_bytes(T, K)) return ATOM_ERR_WORKSPACE;
+    hipError_t err = atom_internal::launch_calibrate_reorder(x_f16, T, ldx, K, workspace, idx_out,
+                                                             static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
+}  // extern "C"
+
+extern "C" {
+
 atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K)
 {
     if (!idx_host) return ATOM_ERR_NULL;

@@ -42,6 +42,11 @@ hipError_t launch_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8, 
                           const void *w_q4, const void *w_q8, const void *w_e8, int64_t N, int K,
                           int O, void *y, int64_t ldy, hipStream_t stream);
 
+// Offline calibration: per-channel square sums and the reorder index.
+size_t     calibrate_workspace_bytes(int64_t T, int K);
+hipError_t launch_calibrate_reorder(const void *x, int64_t T, int64_t ldx, int K, void *workspace,
+                                    int32_t *idx, hipStream_t stream);
+
 // KV cache: asymmetric INT4 rows of D = 64 or 128 values; decode attention over the cache.
 hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, float clip,
                               const int32_t *pos, int32_t rows_per_seq, int64_t Tmax, void *q,
