@@ -282,7 +282,7 @@ def kv_cache_measurements():
         q = torch.randn((B, H, D), generator=gen, device="cuda", dtype=torch.float16)
         seq_len = torch.full((B,), T, dtype=torch.int32, device="cuda")
         o = torch.empty_like(q)
-        need = atom.atom_decode_attention_kv4_workspace_bytes(B, H, D, T)
+        need = atom.atom_decode_attention_kv4_workspace_bytes(B, H, H, D, T)
         ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
         t = graph_time(lambda: atom.atom_decode_attention_kv4(q, kc, vc, seq_len, D ** -0.5, out=o,
                                                               workspace=ws), 20, 5)

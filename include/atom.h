@@ -212,7 +212,7 @@ atom_status atom_kv_quantize(const void *x_f16, int64_t R, int64_t ldx,
  *   as atom_kv_quantize writes them
  *   out_f16  [B, H, D] fp16
  *   workspace  device scratch of at least
- *            atom_decode_attention_kv4_workspace_bytes(B, H, D, Tmax) bytes, 16-byte
+ *            atom_decode_attention_kv4_workspace_bytes(B, H, Hkv, D, Tmax) bytes, 16-byte
  *            aligned (may be NULL when that is 0): when B * H alone cannot fill
  *            the GPU the token range is split over several workgroups whose
  *            partial (max, sum, accumulator) triples meet in a second kernel.
@@ -233,7 +233,8 @@ atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H,
 
 /* Scratch atom_decode_attention_kv4 needs for these sizes (0 when none). */
 size_t atom_decode_attention_kv4_workspace_bytes(int32_t B, int32_t H,
-                                                 int32_t D, int64_t Tmax);
+                                                 int32_t Hkv, int32_t D,
+                                                 int64_t Tmax);
 
 /*
  * MX variant of the path.  The paper also runs its recipe with FP4 codes and

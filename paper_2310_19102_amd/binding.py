@@ -92,7 +92,7 @@ def load_library():
     L.atom_decode_attention_kv4.argtypes = [vp, i32, i32, i32, i32, i64, vp, vp, vp, vp, vp, vp, vp,
                                             f32, vp, vp, sz, vp]
     L.atom_decode_attention_kv4_workspace_bytes.restype = sz
-    L.atom_decode_attention_kv4_workspace_bytes.argtypes = [i32, i32, i32, i64]
+    L.atom_decode_attention_kv4_workspace_bytes.argtypes = [i32, i32, i32, i32, i64]
     L.atom_check_reorder_idx.restype = ctypes.c_int
     L.atom_check_reorder_idx.argtypes = [vp, ctypes.c_int32]
     L.atom_status_string.restype = ctypes.c_char_p
@@ -284,8 +284,8 @@ def atom_w4a4_gemm(a_q4, a_q8, a_scale, w_q4, w_q8, w_scale, group_size: int = 1
     return out
 
 
-def atom_decode_attention_kv4_workspace_bytes(B: int, H: int, D: int, Tmax: int) -> int:
-    return int(load_library().atom_decode_attention_kv4_workspace_bytes(B, H, D, Tmax))
+def atom_decode_attention_kv4_workspace_bytes(B: int, H: int, Hkv: int, D: int, Tmax: int) -> int:
+    return int(load_library().atom_decode_attention_kv4_workspace_bytes(B, H, Hkv, D, Tmax))
 
 
 def atom_kv_quantize(x: torch.Tensor, clip: float = 1.0,
@@ -369,7 +369,7 @@ def atom_decode_attention_kv4(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...]
     _dev(out, torch.float16, "out")
     if tuple(out.shape) != (B, H, D) or not out.is_contiguous():
         raise ValueError("out must be contiguous [B, H, D]")
-    need = int(L.atom_decode_attention_kv4_workspace_bytes(B, H, D, Tmax))
+    need = int(L.atom_decode_attention_kv4_workspace_bytes(B, H, Hkv, D, Tmax))
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()

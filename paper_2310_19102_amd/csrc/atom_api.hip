@@ -177,7 +177,7 @@ atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H, i
         !aligned(k_codes, 16) || !aligned(v_codes, 16) || !aligned(k_scale, 2) ||
         !aligned(v_scale, 2) || !aligned(k_zero, 2) || !aligned(v_zero, 2))
         return ATOM_ERR_ALIGN;
-    const size_t need = atom_internal::decode_attention_workspace_bytes(B, H, Tmax);
+    const size_t need = atom_internal::decode_attention_workspace_bytes(B, H, Hkv, Tmax);
     if (need) {
         if (!workspace || workspace_bytes < need) return ATOM_ERR_WORKSPACE;
         if (!aligned(workspace, 16)) return ATOM_ERR_ALIGN;
@@ -188,10 +188,12 @@ atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H, i
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
-size_t atom_decode_attention_kv4_workspace_bytes(int32_t B, int32_t H, int32_t D, int64_t Tmax)
+size_t atom_decode_attention_kv4_workspace_bytes(int32_t B, int32_t H, int32_t Hkv, int32_t D,
+                                                 int64_t Tmax)
 {
-    if (B <= 0 || H <= 0 || D != 128 || Tmax <= 0 || Tmax > 0x7fffffffLL) return 0;
-    return atom_internal::decode_attention_workspace_bytes(B, H, Tmax);
+    if (B <= 0 || H <= 0 || Hkv <= 0 || H % Hkv || D != 128 || Tmax <= 0 || Tmax > 0x7fffffffLL)
+        return 0;
+    return atom_internal::decode_attention_workspace_bytes(B, H, Hkv, Tmax);
 }
 
 }  // extern "C"

@@ -56,7 +56,7 @@ hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int
                                        const void *kz, const void *vq, const void *vs,
                                        const void *vz, float sm_scale, void *out, void *workspace,
                                        hipStream_t stream);
-size_t     decode_attention_workspace_bytes(int B, int H, int64_t Tmax);
+size_t     decode_attention_workspace_bytes(int B, int H, int Hkv, int64_t Tmax);
 
 }  // namespace atom_internal
 #endif

@@ -394,6 +394,327 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
     }
 }
 
+// ---------------------------------------------------------------- grouped-query variant
+
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef float    v4f __attribute__((ext_vector_type(4)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ v8h quad_operand(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    const v4u t = {a, b, c, d};
+    return __builtin_bit_cast(v8h, t);
+}
+
+// unpack8_16 in plain C: these values feed MFMAs, and the wait states an MFMA needs after the
+// instruction that wrote its operand are only inserted for instructions the compiler can see
+// (mask and magic arrive in registers whose contents the compiler cannot see: with literal
+// constants it emits an and and an or, with register operands the fused v_and_or_b32)
+__device__ __forceinline__ void unpack8_16_mfma(uint32_t w, uint32_t mask, uint32_t magic, uint32_t (&pr)[4])
+{
+    pr[0] = ((w << 6) & mask) | magic;
+    pr[1] = ((w << 2) & mask) | magic;
+    pr[2] = ((w >> 2) & mask) | magic;
+    pr[3] = ((w >> 6) & mask) | magic;
+}
+
+constexpr int kGqaWaves    = 4;
+constexpr int kGqaMaxHeads = 16;          // query heads per cache head served by one MFMA column block
+constexpr int kGqaHeadPitch = 4 * 33 + 1; // floats per head in the merge area (32 + 1 per chunk, + 1)
+
+// One workgroup per (sequence, CACHE head) and split of the token range: the Gq = H / Hkv
+// query heads that share a cache head (2 <= Gq <= 16) share every load and every unpacked
+// code, and both contractions run on the fp16 MFMA 16x16x32 (lane l supplies row or column
+// l & 15 and the eight k of chunk l >> 4; the result has column l & 15 in lane l and rows
+// 4 (l >> 4) + e in register e).  A wavefront owns every fourth group of 64 tokens and walks
+// it in four steps of 16 tokens, as in the per-head kernel.
+//   scores  : S[t, h] = sum_d (16 + code[t, d]) q[h, d]: the row operand is the K codes as
+//             fp16 16 + c (lane = token l & 15, 32 head dimensions of chunk l >> 4, four
+//             MFMAs), the column operand q in the same order of d (registers, loaded once);
+//             the result leaves head h = l & 15 and tokens 4 (l >> 4) + e in lane l, and
+//             score = k_scale sm_scale (S - (16 + k_zero) sum_d q).
+//   softmax : online per head; the four lanes of a head agree on the maximum, each keeps
+//             the partial sums of its own tokens; accumulators are rescaled when the
+//             maximum moves.
+//   values  : out^T[d, h] = sum_t (16 + code[t, d]) w[t, h]: the weights are already laid
+//             out as the column operand (tokens 4 (l >> 4) + i of head l & 15); the row
+//             operand wants four TOKENS of one d per lane, so the V codes are loaded four
+//             bytes per lane and token (lane = d group l & 15 of 8 head dimensions, tokens
+//             4 (l >> 4) + i), transposed as bytes in registers and unpacked two tokens at a
+//             time; tile j of the eight result tiles holds d = 8 (row) + j, so lane l ends
+//             with d = 32 (l >> 4) + 8 e + j of head l & 15.
+//             The weights must fit fp16 whatever the scales are: within a group of 64 tokens
+//             w = p * v_scale * 2^15 / (largest v_scale of the group), at most 2^15 and a
+//             normal fp16 number down to p = 2^-29 of it; the group has accumulators of its
+//             own, which join the running ones, times that factor's inverse, at the end of
+//             the group.  One fp16 number per weight is not enough (its rounding alone shows
+//             as 1e-2 of the small outputs of a head): w travels as fp16 hi + fp16 lo, the
+//             16 tokens of a step filling the 32 k of the MFMA as (hi of the four tokens, lo
+//             of the four tokens) against the value codes repeated.
+//             The 16 and the zero point leave BEFORE the contraction: (16 + code) - (16 + zero)
+//             is exact in fp16 (one packed subtraction per pair of codes), so the sums carry
+//             no offset that a long context would have to cancel.  Zero points beyond +-1000
+//             (rows whose values all sit far on one side of zero) are taken out up to that
+//             bound, the rest leaves through sum_t w * rest as in the per-head kernel.
+//   scales  : lane l reads the scale and zero point of token l of the group (one cache line
+//             per array), turns them into four floats and parks them in LDS, where the step
+//             reads the four tokens it needs as broadcast 16-byte reads.
+__global__ __launch_bounds__(kGqaWaves * 64)
+void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hkv, int64_t Tmax,
+                                     const int32_t *__restrict__ seq_len,
+                                     const uint8_t *__restrict__ kq, const __half *__restrict__ ks,
+                                     const int16_t *__restrict__ kz, const uint8_t *__restrict__ vq,
+                                     const __half *__restrict__ vs, const int16_t *__restrict__ vz,
+                                     float sm_scale, __half *__restrict__ out, int groups_per_split,
+                                     float *__restrict__ part)
+{
+    constexpr int D = 128;
+    constexpr int kWaves = kGqaWaves;
+    __shared__ float4 s_meta[kWaves][kTokens];
+    __shared__ float  s_rest[kWaves][kTokens];
+    __shared__ float  s_m[kWaves][kGqaMaxHeads], s_l[kWaves][kGqaMaxHeads];
+    extern __shared__ __align__(16) float s_acc[];        // [kWaves][Gq][kGqaHeadPitch]
+
+    const int Gq = H / Hkv;
+    const int b = blockIdx.x / Hkv, kvh = blockIdx.x % Hkv;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int x = lane & 15, c = lane >> 4;
+    int T = seq_len[b];
+    T = T < 0 ? 0 : (T > Tmax ? (int)Tmax : T);
+    const int64_t base = ((int64_t)b * Hkv + kvh) * Tmax;
+    const uint8_t *kb = kq + base * (D / 2), *vb = vq + base * (D / 2);
+    const __half  *ksb = ks + base, *vsb = vs + base;
+    const int16_t *kzb = kz + base, *vzb = vz + base;
+
+    const int g_first = blockIdx.y * groups_per_split;
+    const int g_end   = min((T + kTokens - 1) / kTokens, g_first + groups_per_split);
+    int  G     = g_first + wave;
+    const bool alive = G < g_end;                        // then T >= 1: clamped addresses are valid
+    const int  t_last = min(T, g_end * kTokens) - 1;     // loads never leave this split's tokens
+
+    struct Stage { uint4 k; uint32_t v0, v1, v2, v3; };
+    Stage st[4];
+    const float k_mul = sm_scale * 1.44269504088896340736f;   // scores in units of log2: exp2 below
+    auto fetch = [&](Stage &s_, int tile) {
+        int t = tile * kTile + x;
+        t = t <= t_last ? t : t_last;     // masked tokens and steps past the end repeat the last token
+        s_.k = *reinterpret_cast<const uint4 *>(kb + (uint32_t)t * (D / 2) + 16u * c);
+        const int t0 = tile * kTile + 4 * c;
+        const int u0 = t0 <= t_last ? t0 : t_last, u1 = t0 + 1 <= t_last ? t0 + 1 : t_last;
+        const int u2 = t0 + 2 <= t_last ? t0 + 2 : t_last, u3 = t0 + 3 <= t_last ? t0 + 3 : t_last;
+        s_.v0 = *reinterpret_cast<const uint32_t *>(vb + (uint32_t)u0 * (D / 2) + 4u * x);
+        s_.v1 = *reinterpret_cast<const uint32_t *>(vb + (uint32_t)u1 * (D / 2) + 4u * x);
+        s_.v2 = *reinterpret_cast<const uint32_t *>(vb + (uint32_t)u2 * (D / 2) + 4u * x);
+        s_.v3 = *reinterpret_cast<const uint32_t *>(vb + (uint32_t)u3 * (D / 2) + 4u * x);
+    };
+    // scales and zero points of token `lane` of group g, raw
+    struct Meta { __half ks, vs; int16_t kz, vz; };
+    auto fetch_meta = [&](int g) {
+        int t = g * kTokens + lane;
+        t = t <= t_last ? t : t_last;
+        return Meta{ksb[(uint32_t)t], vsb[(uint32_t)t], kzb[(uint32_t)t], vzb[(uint32_t)t]};
+    };
+    // ... as (k_scale sm_scale log2 e, 16 + k_zero, v_scale * 2^15 / group max, 16 + v_zero clamped
+    // to +-1000) into LDS, what the clamp cut off beside it; returns the factor that takes the
+    // group's value sums back (0 for an all-zero group)
+    bool  has_rest = false;               // some zero point of the current group was clamped
+    auto install_meta = [&](const Meta &mt) {
+        const float v_s = __half2float(mt.vs);
+        float gm = row16_max(v_s);
+        gm = fmaxf(gm, __shfl_xor(gm, 16, 64));
+        gm = fmaxf(gm, __shfl_xor(gm, 32, 64));
+        const float rinv = gm > 0.0f ? 32768.0f / gm : 0.0f;
+        const float v_off = 16.0f + (float)mt.vz;
+        const float v_cut = fminf(fmaxf(v_off, -1000.0f), 1000.0f);
+        s_meta[wave][lane] = make_float4(__half2float(mt.ks) * k_mul, 16.0f + (float)mt.kz, v_s * rinv, v_cut);
+        s_rest[wave][lane] = v_off - v_cut;
+        has_rest = __ballot(v_off != v_cut) != 0;
+        return gm * (1.0f / 32768.0f);
+    };
+    float f_group = 0.0f;
+    if (alive) {                          // the first loads leave before q is read
+        f_group = install_meta(fetch_meta(G));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fetch(st[i], 4 * G + i);
+    }
+
+    // q of head x as the column operand: MFMA j of a step contracts, for chunk c, the head
+    // dimensions 32c + 8j + {0, 4, 1, 5, 2, 6, 3, 7} (the order unpack8_16 delivers)
+    v8h qb[4];
+    float qsum = 0.0f;
+    {
+        const bool live = x < Gq;
+        const __half *qv = q + ((int64_t)b * H + (int64_t)kvh * Gq + (live ? x : 0)) * D + 32 * c;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float e[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) e[i] = live ? __half2float(qv[8 * j + (i >> 1) + 4 * (i & 1)]) : 0.0f;
+            qb[j] = v8h{(_Float16)e[0], (_Float16)e[1], (_Float16)e[2], (_Float16)e[3],
+                        (_Float16)e[4], (_Float16)e[5], (_Float16)e[6], (_Float16)e[7]};
+            qsum += ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+        }
+        qsum += __shfl_xor(qsum, 16, 64);
+        qsum += __shfl_xor(qsum, 32, 64);
+    }
+
+    v4f acc[8];                           // acc[j][e] <-> out[head x][d = 32c + 8e + j]
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+    uint32_t c_mask = 0x03C003C0u, c_magic = 0x4C004C00u;
+    asm volatile("" : "+s"(c_mask));
+    asm volatile("" : "+v"(c_magic));
+    v4f gacc[8];                          // the same for the current group of 64 tokens, in its own scale
+#pragma unroll
+    for (int j = 0; j < 8; ++j) gacc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+    float m_run = -INFINITY, l_run = 0.0f, off_run = 0.0f;    // l and off: this lane's tokens only
+
+    auto consume = [&](const Stage &s_, int tile, int slot) {
+        // ---- scores
+        const uint32_t kw[4] = {s_.k.x, s_.k.y, s_.k.z, s_.k.w};
+        v4f sa = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t pr[4];
+            unpack8_16_mfma(kw[j], c_mask, c_magic, pr);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_f16(quad_operand(pr[0], pr[1], pr[2], pr[3]), qb[j], sa, 0, 0, 0);
+        }
+        float4 mt[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mt[e] = s_meta[wave][16 * slot + 4 * c + e];
+        float sc[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool valid = tile * kTile + 4 * c + e < T;
+            sc[e] = valid ? mt[e].x * fmaf(-mt[e].y, qsum, sa[e]) : -INFINITY;
+        }
+        // ---- online softmax per head: the four lanes of a head take the same decisions
+        float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        if (m_new > m_run) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first step
+            l_run *= alpha;
+            off_run *= alpha;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                acc[j] *= alpha;
+                gacc[j] *= alpha;
+            }
+            m_run = m_new;
+        }
+        _Float16 whi[4], wlo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float p = __builtin_amdgcn_exp2f(sc[e] - m_run);
+            l_run += p;
+            const float w = p * mt[e].z;
+            whi[e] = (_Float16)w;
+            wlo[e] = (_Float16)(w - (float)whi[e]);
+        }
+        if (has_rest) {                   // rare: the part of a zero point the operands cannot carry
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                off_run = fmaf((float)whi[e] + (float)wlo[e], s_rest[wave][16 * slot + 4 * c + e], off_run);
+        }
+        const v8h pb = {whi[0], whi[1], whi[2], whi[3], wlo[0], wlo[1], wlo[2], wlo[3]};
+        // (16 + zero) of tokens (0, 1) and (2, 3) of this lane as fp16 pairs
+        const h2 z01 = {(_Float16)mt[0].w, (_Float16)mt[1].w}, z23 = {(_Float16)mt[2].w, (_Float16)mt[3].w};
+
+        // ---- values: byte transpose (token i of this lane = dword v_i), then two tokens per unpack
+        const uint32_t w0 = s_.v0, w1 = s_.v1, w2 = s_.v2, w3 = s_.v3;
+        // L01 = [t0.b0 t1.b0 t0.b1 t1.b1], H01 = [t0.b2 t1.b2 t0.b3 t1.b3] (byte 0 first)
+        const uint32_t L01 = (w0 & 0xFFu) | ((w1 & 0xFFu) << 8) | ((w0 & 0xFF00u) << 8) | ((w1 & 0xFF00u) << 16);
+        const uint32_t H01 = ((w0 >> 16) & 0xFFu) | ((w1 >> 8) & 0xFF00u) | ((w0 >> 8) & 0xFF0000u) | (w1 & 0xFF000000u);
+        const uint32_t L23 = (w2 & 0xFFu) | ((w3 & 0xFFu) << 8) | ((w2 & 0xFF00u) << 8) | ((w3 & 0xFF00u) << 16);
+        const uint32_t H23 = ((w2 >> 16) & 0xFFu) | ((w3 >> 8) & 0xFF00u) | ((w2 >> 8) & 0xFF0000u) | (w3 & 0xFF000000u);
+        // Y_b = [t0.b t2.b t1.b t3.b]: the codes of tokens 0 and 1 sit 16 bits apart, as do 2 and 3
+        uint32_t Y[4];
+        Y[0] = (L01 & 0xFFu) | ((L23 & 0xFFu) << 8) | ((L01 & 0xFF00u) << 8) | ((L23 & 0xFF00u) << 16);
+        Y[1] = ((L01 >> 16) & 0xFFu) | ((L23 >> 8) & 0xFF00u) | ((L01 >> 8) & 0xFF0000u) | (L23 & 0xFF000000u);
+        Y[2] = (H01 & 0xFFu) | ((H23 & 0xFFu) << 8) | ((H01 & 0xFF00u) << 8) | ((H23 & 0xFF00u) << 16);
+        Y[3] = ((H01 >> 16) & 0xFFu) | ((H23 >> 8) & 0xFF00u) | ((H01 >> 8) & 0xFF0000u) | (H23 & 0xFF000000u);
+#pragma unroll
+        for (int bt = 0; bt < 4; ++bt) {
+            uint32_t pr[4];               // (t0,t1).lo  (t0,t1).hi  (t2,t3).lo  (t2,t3).hi of byte bt
+            unpack8_16_mfma(Y[bt], c_mask, c_magic, pr);
+            const uint32_t lo01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[0]) - z01);
+            const uint32_t hi01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[1]) - z01);
+            const uint32_t lo23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[2]) - z23);
+            const uint32_t hi23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[3]) - z23);
+            gacc[2 * bt]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(quad_operand(lo01, lo23, lo01, lo23), pb, gacc[2 * bt], 0, 0, 0);
+            gacc[2 * bt + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(quad_operand(hi01, hi23, hi01, hi23), pb, gacc[2 * bt + 1], 0, 0, 0);
+        }
+    };
+
+    if (alive) {
+        while (G < g_end) {
+            const int Gn = G + kWaves;                    // past the end: clamped, unused loads
+            const Meta meta_next = fetch_meta(Gn);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int tile = 4 * G + i;
+                if (tile * kTile < T) consume(st[i], tile, i);
+                fetch(st[i], 4 * Gn + i);                 // the slot's next use is four steps away
+            }
+            // the group's sums, less their offsets, join the running ones in units of v_scale
+            float off = off_run;
+            off += __shfl_xor(off, 16, 64);
+            off += __shfl_xor(off, 32, 64);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                acc[j] += f_group * (gacc[j] - off);
+                gacc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+            off_run = 0.0f;
+            f_group = install_meta(meta_next);            // every read of this group's entries is done
+            G = Gn;
+        }
+    }
+
+    // ---- the wavefronts merge through LDS: out = sum_w e^(m_w - M) acc_w / sum_w e^(m_w - M) l_w
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+    if (x < Gq) {
+        float *dst = s_acc + ((size_t)wave * Gq + x) * kGqaHeadPitch + 33 * c;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[8 * e + j] = acc[j][e];
+        if (c == 0) {
+            s_m[wave][x] = m_run;
+            s_l[wave][x] = l_run;
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < Gq * D; idx += kWaves * 64) {
+        const int hh = idx >> 7, d = idx & (D - 1);
+        float M = s_m[0][hh];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w][hh]);
+        float num = 0.0f, den = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float e = s_m[w][hh] == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(s_m[w][hh] - M);
+            num += e * s_acc[((size_t)w * Gq + hh) * kGqaHeadPitch + 33 * (d >> 5) + (d & 31)];
+            den += e * s_l[w][hh];
+        }
+        const int64_t head = (int64_t)b * H + (int64_t)kvh * Gq + hh;
+        if (part == nullptr) {
+            out[head * D + d] = __float2half_rn(den > 0.0f ? num / den : 0.0f);
+        } else {                          // partials in natural-log units, as the merge kernel reads them
+            float *dst = part + (head * gridDim.y + blockIdx.y) * (D + 2);
+            dst[2 + d] = num;
+            if (d == 0) {
+                dst[0] = M * 0.69314718055994530942f;
+                dst[1] = den;
+            }
+        }
+    }
+}
+
 // Second pass of a split launch: the partials of one (sequence, head) merge as the
 // wavefronts did, out = sum_s e^(M_s - M) num_s / sum_s e^(M_s - M) den_s.
 __global__ __launch_bounds__(128)
@@ -439,26 +760,38 @@ hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, floa
 // shared inside the workgroup, which merges through LDS: no second kernel), and below 256
 // workgroups the token range is also split over several workgroups whose partials meet in
 // decode_attention_merge_kernel.  Never less than one 64-token group per wavefront and split.
-struct AttentionShape { int waves, splits; };
-AttentionShape decode_attention_shape(int B, int H, int64_t Tmax)
+//
+// With 2 to 16 query heads per cache head the grouped-query kernel runs instead: one workgroup of
+// four wavefronts per (sequence, cache head), the token range split until about 1280 workgroups
+// exist.
+struct AttentionShape { int waves, splits; bool gqa; };
+AttentionShape decode_attention_shape(int B, int H, int Hkv, int64_t Tmax)
 {
     const int64_t groups = (Tmax + kTokens - 1) / kTokens;
+    const int     Gq     = H / Hkv;
+    if (Gq >= 2 && Gq <= kGqaMaxHeads) {
+        const int64_t bk = (int64_t)B * Hkv;
+        int64_t want = (1280 + bk - 1) / bk, cap = groups / kGqaWaves;
+        if (want > cap) want = cap;
+        if (want > 64) want = 64;
+        return {kGqaWaves, want < 1 ? 1 : (int)want, true};
+    }
     const int64_t bh     = (int64_t)B * H;
     if (bh > 384 || groups < 16) {
         int64_t want = (1280 + bh - 1) / bh, cap = groups / 4;
         if (want > cap) want = cap;
         if (want > 64) want = 64;
-        return {4, want < 1 ? 1 : (int)want};
+        return {4, want < 1 ? 1 : (int)want, false};
     }
     int64_t want = (256 + bh - 1) / bh, cap = groups / 16;     // 256 x 16 wavefronts = four per SIMD
     if (want > cap) want = cap;
     if (want > 64) want = 64;
-    return {16, want < 1 ? 1 : (int)want};
+    return {16, want < 1 ? 1 : (int)want, false};
 }
 
-size_t decode_attention_workspace_bytes(int B, int H, int64_t Tmax)
+size_t decode_attention_workspace_bytes(int B, int H, int Hkv, int64_t Tmax)
 {
-    const int S = decode_attention_shape(B, H, Tmax).splits;
+    const int S = decode_attention_shape(B, H, Hkv, Tmax).splits;
     return S > 1 ? (size_t)B * H * S * (128 + 2) * sizeof(float) : 0;
 }
 
@@ -468,12 +801,18 @@ hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int
                                        const void *vz, float sm_scale, void *out, void *workspace,
                                        hipStream_t stream)
 {
-    const AttentionShape sh = decode_attention_shape(B, H, Tmax);
+    const AttentionShape sh = decode_attention_shape(B, H, Hkv, Tmax);
     const int S      = sh.splits;
     const int groups = (int)((Tmax + kTokens - 1) / kTokens);
     const int tps    = S > 1 ? (groups + S - 1) / S : (groups > 0 ? groups : 1);
     float *part = S > 1 ? (float *)workspace : nullptr;
-    if (sh.waves == 4)
+    if (sh.gqa) {
+        const size_t lds = (size_t)kGqaWaves * (H / Hkv) * kGqaHeadPitch * sizeof(float);   // <= 34 KB
+        hipLaunchKernelGGL(decode_attention_kv4_gqa_kernel, dim3((unsigned)(B * Hkv), (unsigned)S),
+                           dim3(kGqaWaves * 64), lds, stream, (const __half *)q, H, Hkv, Tmax, seq_len,
+                           (const uint8_t *)kq, (const __half *)ks, (const int16_t *)kz, (const uint8_t *)vq,
+                           (const __half *)vs, (const int16_t *)vz, sm_scale, (__half *)out, tps, part);
+    } else if (sh.waves == 4)
         hipLaunchKernelGGL(decode_attention_kv4_kernel<4>, dim3((unsigned)(B * H), (unsigned)S), dim3(256),
                            0, stream, (const __half *)q, H, Hkv, Tmax, seq_len, (const uint8_t *)kq,
                            (const __half *)ks, (const int16_t *)kz, (const uint8_t *)vq,

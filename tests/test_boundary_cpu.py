@@ -106,11 +106,15 @@ def test_host_side_validation_of_the_kv_cache_and_mx_entry_points():
     assert att(*base[:4], 64, *base[5:], None, 0, None) == 3                    # head dimension
     assert att(*base[:6], None, *base[7:], None, 0, None) == 1                  # seq_len
     assert att(p, 0, *base[2:], None, 0, None) == 0
-    assert lib.atom_decode_attention_kv4_workspace_bytes(64, 32, 128, 1024) == 0
-    need = lib.atom_decode_attention_kv4_workspace_bytes(1, 2, 128, 8192)
+    assert lib.atom_decode_attention_kv4_workspace_bytes(64, 32, 32, 128, 1024) == 0
+    need = lib.atom_decode_attention_kv4_workspace_bytes(1, 2, 2, 128, 8192)
     assert need > 0 and need % (130 * 4) == 0
     assert att(p, 1, 2, 2, 128, 8192, p, p, p, p, p, p, p, 1.0, p, None, 0, None) == 5   # workspace missing
-    assert lib.atom_decode_attention_kv4_workspace_bytes(1, 2, 64, 8192) == 0
+    assert lib.atom_decode_attention_kv4_workspace_bytes(1, 2, 2, 64, 8192) == 0
+    assert lib.atom_decode_attention_kv4_workspace_bytes(1, 6, 4, 128, 8192) == 0            # H % Hkv
+    # grouped-query launches are sized by B * Hkv workgroups: more splits than the per-head shape
+    gq = lib.atom_decode_attention_kv4_workspace_bytes(16, 64, 8, 128, 4096)
+    assert gq > 0 and gq % (16 * 64 * 130 * 4) == 0
 
     mq = lib.atom_mx_quantize_act
     ok = D(4096, 32, 128, 4, 8)

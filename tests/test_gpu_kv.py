@@ -129,7 +129,11 @@ def _attention_case(kv, what):
     (2, 2, 2, 2048, [2048, 300]),        # token range split; most of sequence 1's share is empty
     (1, 4, 2, 1500, [1234]),             # 16 wavefronts per workgroup, ragged last group
     (1, 2, 1, 8192, [8000]),             # 16 wavefronts per workgroup and 8 splits
-    (5, 64, 8, 1100, None),              # 320 workgroups of 16 wavefronts, no split; 8 query heads per cache head
+    (5, 64, 8, 1100, None),              # 8 query heads per cache head (Llama-70B), split token range
+    (2, 6, 2, 130, [130, 64]),           # 3 query heads per cache head: padded MFMA columns
+    (1, 16, 1, 300, [299]),              # 16 query heads on one cache head: every MFMA column live
+    (1, 34, 1, 200, [200]),              # 34 query heads per cache head: per-head kernel
+    (3, 16, 4, 4096, [4096, 0, 77]),     # grouped-query, splits, an empty sequence and a short one
 ])
 def test_decode_attention(B, H, Hkv, Tmax, lens):
     kv = synth.kv_case(B, H, Hkv, 128, Tmax, seq_lens=lens, case_id=10 + Tmax)
@@ -156,6 +160,58 @@ def test_decode_attention_peaked_softmax():
     kv.k[0, :, 150] = (8.0 * kv.q[0]).to(torch.float16)
     kv.k[0, :, 3] = (4.0 * kv.q[0]).to(torch.float16)
     _attention_case(kv, "peaked")
+
+
+@pytest.mark.parametrize("Hkv", [2, 1])
+def test_decode_attention_value_scales_far_apart(Hkv):
+    """Tokens whose value rows differ by many powers of two (scales from 2^-20 to 2^9 of the
+    typical one), the large ones both attended and ignored: no weight may leave the fp16 range
+    of a matrix operand, whichever way the scale is folded."""
+    kv = synth.kv_case(1, 2, Hkv, 128, 300, seq_lens=[300], case_id=12)
+    v = kv.v.float()
+    v[:, :, 5] *= 2.0 ** 9
+    v[:, :, 70] *= 2.0 ** 9
+    v[:, :, 71:100] *= 2.0 ** -12
+    v[:, :, 130:200] *= 2.0 ** -20
+    v[:, :, 250] *= 2.0 ** 6
+    kv.v.copy_(v.to(torch.float16))
+    kv.k[0, :, 70] = (3.0 * kv.q[0, :Hkv]).to(torch.float16)       # token 70 attended, token 5 not
+    _attention_case(kv, f"value scales Hkv={Hkv}")
+
+
+@pytest.mark.parametrize("Hkv", [2, 1])
+def test_decode_attention_values_far_from_zero(Hkv):
+    """Value rows that sit far on one side of zero (a narrow range around +50 or -20): their
+    zero points are in the thousands, beyond what an fp16 operand can carry exactly."""
+    kv = synth.kv_case(1, 2, Hkv, 128, 200, seq_lens=[190], case_id=14)
+    v = kv.v.float()
+    v[:, :, 10:40] = 50.0 + 0.25 * v[:, :, 10:40]
+    v[:, :, 100] = -20.0 + 0.125 * v[:, :, 100]
+    kv.v.copy_(v.to(torch.float16))
+    kc = atom.atom_kv_quantize(kv.v.cuda(), 1.0)
+    assert int(kc[2].abs().max()) > 1500                           # the case is what it claims to be
+    _attention_case(kv, f"values far from zero Hkv={Hkv}")
+
+
+def test_decode_attention_grouped_query_long_context_sampled():
+    """Llama-70B-like decode (64 query heads on 8 cache heads) at batch 4 and 4096 cached tokens:
+    the oracle checks a sample of (sequence, head) pairs."""
+    B, H, Hkv, T = 4, 64, 8, 4096
+    kv = synth.kv_case(B, H, Hkv, 128, T, seq_lens=[T, T - 17, 2049, 700], case_id=13)
+    kc = atom.atom_kv_quantize(kv.k.cuda(), 1.0)
+    vc = atom.atom_kv_quantize(kv.v.cuda(), 1.0)
+    print(f"[case] decode_attention_kv4 grouped-query sampled: B={B} H={H} Hkv={Hkv} T={T}", flush=True)
+    out = _npy(atom.atom_decode_attention_kv4(kv.q.cuda(), kc, vc, kv.seq_len.cuda(), kv.sm_scale))
+    kc, vc = [tuple(_npy(t) for t in c) for c in (kc, vc)]
+    rng = np.random.default_rng(1)
+    pairs = [(0, 0), (3, 63), (1, 8)] + [(int(rng.integers(B)), int(rng.integers(H))) for _ in range(9)]
+    for b, h in pairs:
+        g = h // (H // Hkv)
+        sl = lambda t: np.ascontiguousarray(t[b:b + 1, g:g + 1])
+        ref = oracle.decode_attention_kv4(kv.q.numpy()[b:b + 1, h:h + 1], *(sl(t) for t in kc),
+                                          *(sl(t) for t in vc), kv.seq_len.numpy()[b:b + 1], kv.sm_scale)
+        err = _rel_err(out[b:b + 1, h:h + 1], ref)
+        assert err <= O_TOL, f"(b={b}, h={h}): rel err {err}"
 
 
 def test_decode_attention_long_context_sampled():
@@ -192,8 +248,8 @@ def test_decode_attention_errors():
         atom.atom_decode_attention_kv4(kv.q.cuda()[:, :3].contiguous(), kc, vc, kv.seq_len.cuda(), 1.0)
     assert e.value.status == 2
     big = synth.kv_case(1, 2, 2, 128, 600, case_id=8)            # needs a workspace: too small / missing
-    assert atom.atom_decode_attention_kv4_workspace_bytes(1, 2, 128, 600) > 0
-    assert atom.atom_decode_attention_kv4_workspace_bytes(64, 32, 128, 600) == 0
+    assert atom.atom_decode_attention_kv4_workspace_bytes(1, 2, 2, 128, 600) > 0
+    assert atom.atom_decode_attention_kv4_workspace_bytes(64, 32, 32, 128, 600) == 0
     L = atom.load_library()
     import ctypes
     bk, bv = atom.atom_kv_quantize(big.k.cuda()), atom.atom_kv_quantize(big.v.cuda())
