@@ -31,8 +31,11 @@ FLAGS = [
 
 
 # per-source overrides: the MX GEMM never touches its accumulators with the vector ALU inside the
-# K loop, so its 256 accumulator registers per lane belong in the AccVGPRs
-SOURCE_FLAGS = {"atom_mx.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=0"]}
+# K loop, so its 256 accumulator registers per lane belong in the AccVGPRs; the grouped-query
+# attention kernel rescales its accumulators with the vector ALU (online softmax), and with them
+# in AccVGPRs every step copied all 32 of them out for a rescaling that rarely runs
+SOURCE_FLAGS = {"atom_mx.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=0"],
+                "atom_kv.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def build(verbose: bool = False, extra_flags=(), lib: str = LIB, tag: str = "") -> str:

@@ -418,6 +418,28 @@ __device__ __forceinline__ void unpack8_16_mfma(uint32_t w, uint32_t mask, uint3
     pr[3] = ((w >> 6) & mask) | magic;
 }
 
+// max over the lanes l, l ^ 16, l ^ 32, l ^ 48 with the lane-half swaps of gfx950 (vector ALU
+// speed; a ds_bpermute pair per exchange would sit on the critical path of every step).  A swap
+// exchanges the upper half (32) or the odd rows (16) of its first register with the lower half
+// or the even rows of its second; fed two copies of v, the two results hold, lane by lane, v of
+// the lane itself and of its partner.  This compiler folds max(first result, second result)
+// into the first result, so the second one passes through an empty asm statement (no
+// instruction; it only hides where the value came from), and `zero`, a 0 the compiler cannot
+// see, keeps the two inputs distinct values.
+__device__ __forceinline__ float max_across_chunks(float v, unsigned zero)
+{
+    typedef unsigned v2ui __attribute__((ext_vector_type(2)));
+    unsigned u = __builtin_bit_cast(unsigned, v);
+    v2ui r = __builtin_amdgcn_permlane32_swap(u, u | zero, false, false);
+    unsigned other = r[1];
+    asm volatile("" : "+v"(other));
+    u = __builtin_bit_cast(unsigned, fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, other)));
+    r = __builtin_amdgcn_permlane16_swap(u, u | zero, false, false);
+    other = r[1];
+    asm volatile("" : "+v"(other));
+    return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, other));
+}
+
 constexpr int kGqaWaves    = 4;
 constexpr int kGqaMaxHeads = 16;          // query heads per cache head served by one MFMA column block
 constexpr int kGqaHeadPitch = 4 * 33 + 1; // floats per head in the merge area (32 + 1 per chunk, + 1)
@@ -443,11 +465,11 @@ constexpr int kGqaHeadPitch = 4 * 33 + 1; // floats per head in the merge area (
 //             4 (l >> 4) + i), transposed as bytes in registers and unpacked two tokens at a
 //             time; tile j of the eight result tiles holds d = 8 (row) + j, so lane l ends
 //             with d = 32 (l >> 4) + 8 e + j of head l & 15.
-//             The weights must fit fp16 whatever the scales are: within a group of 64 tokens
-//             w = p * v_scale * 2^15 / (largest v_scale of the group), at most 2^15 and a
-//             normal fp16 number down to p = 2^-29 of it; the group has accumulators of its
-//             own, which join the running ones, times that factor's inverse, at the end of
-//             the group.  One fp16 number per weight is not enough (its rounding alone shows
+//             The weights must fit fp16 whatever the scales are:
+//             w = p * v_scale * 2^15 / R, R the largest v_scale this wavefront has met so far
+//             (fixed per group of 64 tokens; when a new group raises it, the accumulators are
+//             rescaled, as for the running maximum of the scores): at most 2^15, and a normal
+//             fp16 number down to 2^-29 of that.  One fp16 number per weight is not enough (its rounding alone shows
 //             as 1e-2 of the small outputs of a head): w travels as fp16 hi + fp16 lo, the
 //             16 tokens of a step filling the 32 k of the MFMA as (hi of the four tokens, lo
 //             of the four tokens) against the value codes repeated.
@@ -515,26 +537,35 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
         t = t <= t_last ? t : t_last;
         return Meta{ksb[(uint32_t)t], vsb[(uint32_t)t], kzb[(uint32_t)t], vzb[(uint32_t)t]};
     };
-    // ... as (k_scale sm_scale log2 e, 16 + k_zero, v_scale * 2^15 / group max, 16 + v_zero clamped
-    // to +-1000) into LDS, what the clamp cut off beside it; returns the factor that takes the
-    // group's value sums back (0 for an all-zero group)
+    v4f acc[8];                           // acc[j][e] <-> out[head x][d = 32c + 8e + j], in units of R / 2^15
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+    float m_run = -INFINITY, l_run = 0.0f, off_run = 0.0f;    // l and off: this lane's tokens only
+    float R = 0.0f;                       // largest v_scale met so far (the same in every lane)
+    unsigned c_zero = 0u;
+    asm volatile("" : "+s"(c_zero));
     bool  has_rest = false;               // some zero point of the current group was clamped
+    // ... as (k_scale sm_scale log2 e, 16 + k_zero, v_scale * 2^15 / R, 16 + v_zero clamped to
+    // +-1000) into LDS, what the clamp cut off beside it
     auto install_meta = [&](const Meta &mt) {
         const float v_s = __half2float(mt.vs);
-        float gm = row16_max(v_s);
-        gm = fmaxf(gm, __shfl_xor(gm, 16, 64));
-        gm = fmaxf(gm, __shfl_xor(gm, 32, 64));
-        const float rinv = gm > 0.0f ? 32768.0f / gm : 0.0f;
+        const float Rn  = fmaxf(R, max_across_chunks(row16_max(v_s), c_zero));
+        if (Rn > R) {                     // the same decision in every lane; rare after the first groups
+            const float down = R / Rn;    // 0 the first time
+            off_run *= down;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] *= down;
+            R = Rn;
+        }
+        const float rinv  = R > 0.0f ? 32768.0f / R : 0.0f;
         const float v_off = 16.0f + (float)mt.vz;
         const float v_cut = fminf(fmaxf(v_off, -1000.0f), 1000.0f);
         s_meta[wave][lane] = make_float4(__half2float(mt.ks) * k_mul, 16.0f + (float)mt.kz, v_s * rinv, v_cut);
         s_rest[wave][lane] = v_off - v_cut;
         has_rest = __ballot(v_off != v_cut) != 0;
-        return gm * (1.0f / 32768.0f);
     };
-    float f_group = 0.0f;
     if (alive) {                          // the first loads leave before q is read
-        f_group = install_meta(fetch_meta(G));
+        install_meta(fetch_meta(G));
 #pragma unroll
         for (int i = 0; i < 4; ++i) fetch(st[i], 4 * G + i);
     }
@@ -559,16 +590,9 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
         qsum += __shfl_xor(qsum, 32, 64);
     }
 
-    v4f acc[8];                           // acc[j][e] <-> out[head x][d = 32c + 8e + j]
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
     uint32_t c_mask = 0x03C003C0u, c_magic = 0x4C004C00u;
     asm volatile("" : "+s"(c_mask));
     asm volatile("" : "+v"(c_magic));
-    v4f gacc[8];                          // the same for the current group of 64 tokens, in its own scale
-#pragma unroll
-    for (int j = 0; j < 8; ++j) gacc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
-    float m_run = -INFINITY, l_run = 0.0f, off_run = 0.0f;    // l and off: this lane's tokens only
 
     auto consume = [&](const Stage &s_, int tile, int slot) {
         // ---- scores
@@ -591,18 +615,13 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
         }
         // ---- online softmax per head: the four lanes of a head take the same decisions
         float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
+        const float m_new = fmaxf(m_run, max_across_chunks(mx, c_zero));
         if (m_new > m_run) {
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first step
             l_run *= alpha;
             off_run *= alpha;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                acc[j] *= alpha;
-                gacc[j] *= alpha;
-            }
+            for (int j = 0; j < 8; ++j) acc[j] *= alpha;
             m_run = m_new;
         }
         _Float16 whi[4], wlo[4];
@@ -644,8 +663,8 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
             const uint32_t hi01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[1]) - z01);
             const uint32_t lo23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[2]) - z23);
             const uint32_t hi23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[3]) - z23);
-            gacc[2 * bt]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(quad_operand(lo01, lo23, lo01, lo23), pb, gacc[2 * bt], 0, 0, 0);
-            gacc[2 * bt + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(quad_operand(hi01, hi23, hi01, hi23), pb, gacc[2 * bt + 1], 0, 0, 0);
+            acc[2 * bt]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(quad_operand(lo01, lo23, lo01, lo23), pb, acc[2 * bt], 0, 0, 0);
+            acc[2 * bt + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(quad_operand(hi01, hi23, hi01, hi23), pb, acc[2 * bt + 1], 0, 0, 0);
         }
     };
 
@@ -659,17 +678,15 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
                 if (tile * kTile < T) consume(st[i], tile, i);
                 fetch(st[i], 4 * Gn + i);                 // the slot's next use is four steps away
             }
-            // the group's sums, less their offsets, join the running ones in units of v_scale
-            float off = off_run;
-            off += __shfl_xor(off, 16, 64);
-            off += __shfl_xor(off, 32, 64);
+            if (has_rest) {                               // what the operands could not carry of the zero points
+                float off = off_run;
+                off += __shfl_xor(off, 16, 64);
+                off += __shfl_xor(off, 32, 64);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                acc[j] += f_group * (gacc[j] - off);
-                gacc[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+                for (int j = 0; j < 8; ++j) acc[j] -= off;
+                off_run = 0.0f;
             }
-            off_run = 0.0f;
-            f_group = install_meta(meta_next);            // every read of this group's entries is done
+            install_meta(meta_next);                      // every read of this group's entries is done
             G = Gn;
         }
     }
@@ -682,7 +699,7 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
 #pragma unroll
         for (int j = 0; j < 8; ++j)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) dst[8 * e + j] = acc[j][e];
+            for (int e = 0; e < 4; ++e) dst[8 * e + j] = acc[j][e] * (R * (1.0f / 32768.0f));
         if (c == 0) {
             s_m[wave][x] = m_run;
             s_l[wave][x] = l_run;
