@@ -218,7 +218,7 @@ atom_status atom_kv_quantize(const void *x_f16, int64_t R, int64_t ldx,
  *            partial (max, sum, accumulator) triples meet in a second kernel.
  *            Contents need no initialisation and are dead after the call.
  * Errors: ATOM_ERR_NULL, ATOM_ERR_SHAPE (negative sizes, H % Hkv != 0),
- * ATOM_ERR_UNSUPPORTED (D != 128), ATOM_ERR_ALIGN, ATOM_ERR_WORKSPACE.
+ * ATOM_ERR_UNSUPPORTED (D != 128, Tmax > 2^25), ATOM_ERR_ALIGN, ATOM_ERR_WORKSPACE.
  * B == 0 returns ATOM_OK.
  */
 atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H,

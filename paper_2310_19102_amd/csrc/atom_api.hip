@@ -169,6 +169,7 @@ atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H, i
         return ATOM_ERR_SHAPE;
     if (D != 128) return ATOM_ERR_UNSUPPORTED;
     if ((int64_t)B * H > 0x7fffffffLL) return ATOM_ERR_UNSUPPORTED;
+    if (Tmax > (1LL << 25)) return ATOM_ERR_UNSUPPORTED;      // 32-bit byte offsets inside a cache head
     if (B == 0) return ATOM_OK;
     if (!q_f16 || !seq_len || !out_f16) return ATOM_ERR_NULL;
     if (Tmax > 0 && (!k_codes || !k_scale || !k_zero || !v_codes || !v_scale || !v_zero))

@@ -9,6 +9,7 @@
 // i.e. 64 + 4 bytes per token and head at D = 128: 4.25 bits per element.
 
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
@@ -397,8 +398,16 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
 // ---------------------------------------------------------------- grouped-query variant
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 typedef float    v4f __attribute__((ext_vector_type(4)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ v4h pair_operand(uint32_t lo, uint32_t hi)
+{
+    const v2u t = {lo, hi};
+    return __builtin_bit_cast(v4h, t);
+}
 
 __device__ __forceinline__ v8h quad_operand(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
 {
@@ -470,9 +479,8 @@ constexpr int kGqaHeadPitch = 4 * 33 + 1; // floats per head in the merge area (
 //             (fixed per group of 64 tokens; when a new group raises it, the accumulators are
 //             rescaled, as for the running maximum of the scores): at most 2^15, and a normal
 //             fp16 number down to 2^-29 of that.  One fp16 number per weight is not enough (its rounding alone shows
-//             as 1e-2 of the small outputs of a head): w travels as fp16 hi + fp16 lo, the
-//             16 tokens of a step filling the 32 k of the MFMA as (hi of the four tokens, lo
-//             of the four tokens) against the value codes repeated.
+//             as 1e-2 of the small outputs of a head): w travels as fp16 hi + fp16 lo, one
+//             16x16x16 MFMA for each against the same value operand.
 //             The 16 and the zero point leave BEFORE the contraction: (16 + code) - (16 + zero)
 //             is exact in fp16 (one packed subtraction per pair of codes), so the sums carry
 //             no offset that a long context would have to cancel.  Zero points beyond +-1000
@@ -481,7 +489,7 @@ constexpr int kGqaHeadPitch = 4 * 33 + 1; // floats per head in the merge area (
 //   scales  : lane l reads the scale and zero point of token l of the group (one cache line
 //             per array), turns them into four floats and parks them in LDS, where the step
 //             reads the four tokens it needs as broadcast 16-byte reads.
-__global__ __launch_bounds__(kGqaWaves * 64)
+__global__ __launch_bounds__(kGqaWaves * 64)               // (capped at 168 registers it spills and runs slower)
 void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hkv, int64_t Tmax,
                                      const int32_t *__restrict__ seq_len,
                                      const uint8_t *__restrict__ kq, const __half *__restrict__ ks,
@@ -518,17 +526,17 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
     struct Stage { uint4 k; uint32_t v0, v1, v2, v3; };
     Stage st[4];
     const float k_mul = sm_scale * 1.44269504088896340736f;   // scores in units of log2: exp2 below
+    // byte offsets inside this cache head: a tile is 16 rows of 64 bytes; rows past t_last
+    // (masked tokens, steps past the end) read row t_last instead
+    const uint32_t k_lane = 64u * x + 16u * c, k_last = 64u * (uint32_t)max(t_last, 0) + 16u * c;
+    const uint32_t v_lane = 64u * (4u * c) + 4u * x, v_last = 64u * (uint32_t)max(t_last, 0) + 4u * x;
     auto fetch = [&](Stage &s_, int tile) {
-        int t = tile * kTile + x;
-        t = t <= t_last ? t : t_last;     // masked tokens and steps past the end repeat the last token
-        s_.k = *reinterpret_cast<const uint4 *>(kb + (uint32_t)t * (D / 2) + 16u * c);
-        const int t0 = tile * kTile + 4 * c;
-        const int u0 = t0 <= t_last ? t0 : t_last, u1 = t0 + 1 <= t_last ? t0 + 1 : t_last;
-        const int u2 = t0 + 2 <= t_last ? t0 + 2 : t_last, u3 = t0 + 3 <= t_last ? t0 + 3 : t_last;
-        s_.v0 = *reinterpret_cast<const uint32_t *>(vb + (uint32_t)u0 * (D / 2) + 4u * x);
-        s_.v1 = *reinterpret_cast<const uint32_t *>(vb + (uint32_t)u1 * (D / 2) + 4u * x);
-        s_.v2 = *reinterpret_cast<const uint32_t *>(vb + (uint32_t)u2 * (D / 2) + 4u * x);
-        s_.v3 = *reinterpret_cast<const uint32_t *>(vb + (uint32_t)u3 * (D / 2) + 4u * x);
+        const uint32_t t0 = (uint32_t)tile * (kTile * 64u);
+        s_.k  = *reinterpret_cast<const uint4 *>(kb + min(t0 + k_lane, k_last));
+        s_.v0 = *reinterpret_cast<const uint32_t *>(vb + min(t0 + v_lane, v_last));
+        s_.v1 = *reinterpret_cast<const uint32_t *>(vb + min(t0 + v_lane + 64u, v_last));
+        s_.v2 = *reinterpret_cast<const uint32_t *>(vb + min(t0 + v_lane + 128u, v_last));
+        s_.v3 = *reinterpret_cast<const uint32_t *>(vb + min(t0 + v_lane + 192u, v_last));
     };
     // scales and zero points of token `lane` of group g, raw
     struct Meta { __half ks, vs; int16_t kz, vz; };
@@ -594,7 +602,8 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
     asm volatile("" : "+s"(c_mask));
     asm volatile("" : "+v"(c_magic));
 
-    auto consume = [&](const Stage &s_, int tile, int slot) {
+    // `masked_c`: the group holds the end of the sequence, some tokens of the step may lie beyond it
+    auto consume = [&](const Stage &s_, int tile, int slot, auto masked_c) __attribute__((always_inline)) {
         // ---- scores
         const uint32_t kw[4] = {s_.k.x, s_.k.y, s_.k.z, s_.k.w};
         v4f sa = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -609,9 +618,11 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
         for (int e = 0; e < 4; ++e) mt[e] = s_meta[wave][16 * slot + 4 * c + e];
         float sc[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const bool valid = tile * kTile + 4 * c + e < T;
-            sc[e] = valid ? mt[e].x * fmaf(-mt[e].y, qsum, sa[e]) : -INFINITY;
+        for (int e = 0; e < 4; ++e) sc[e] = mt[e].x * fmaf(-mt[e].y, qsum, sa[e]);
+        if constexpr (decltype(masked_c)::value) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (tile * kTile + 4 * c + e >= T) sc[e] = -INFINITY;
         }
         // ---- online softmax per head: the four lanes of a head take the same decisions
         float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
@@ -624,47 +635,55 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
             for (int j = 0; j < 8; ++j) acc[j] *= alpha;
             m_run = m_new;
         }
-        _Float16 whi[4], wlo[4];
+        // w = hi + lo: hi by the packed conversion (which truncates: any rounding will do, lo
+        // takes what hi leaves), two tokens per instruction
+        float w[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const float p = __builtin_amdgcn_exp2f(sc[e] - m_run);
             l_run += p;
-            const float w = p * mt[e].z;
-            whi[e] = (_Float16)w;
-            wlo[e] = (_Float16)(w - (float)whi[e]);
+            w[e] = p * mt[e].z;
         }
+        const h2 hi01 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(w[0], w[1]));
+        const h2 hi23 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(w[2], w[3]));
+        const h2 lo01 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(w[0] - (float)hi01[0], w[1] - (float)hi01[1]));
+        const h2 lo23 = __builtin_bit_cast(h2, __builtin_amdgcn_cvt_pkrtz(w[2] - (float)hi23[0], w[3] - (float)hi23[1]));
         if (has_rest) {                   // rare: the part of a zero point the operands cannot carry
+            const float *rs = &s_rest[wave][16 * slot + 4 * c];   // (hi + lo is w to 2^-22)
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                off_run = fmaf((float)whi[e] + (float)wlo[e], s_rest[wave][16 * slot + 4 * c + e], off_run);
+            for (int e = 0; e < 4; ++e) off_run = fmaf(w[e], rs[e], off_run);
         }
-        const v8h pb = {whi[0], whi[1], whi[2], whi[3], wlo[0], wlo[1], wlo[2], wlo[3]};
+        const v4h pb_hi = {hi01[0], hi01[1], hi23[0], hi23[1]}, pb_lo = {lo01[0], lo01[1], lo23[0], lo23[1]};
         // (16 + zero) of tokens (0, 1) and (2, 3) of this lane as fp16 pairs
         const h2 z01 = {(_Float16)mt[0].w, (_Float16)mt[1].w}, z23 = {(_Float16)mt[2].w, (_Float16)mt[3].w};
 
         // ---- values: byte transpose (token i of this lane = dword v_i), then two tokens per unpack
         const uint32_t w0 = s_.v0, w1 = s_.v1, w2 = s_.v2, w3 = s_.v3;
+        // v_perm_b32 picks each result byte out of eight: 0-3 the second operand's, 4-7 the first's
+        constexpr uint32_t kZipLo = 0x05010400u;          // [b.0 a.0 b.1 a.1] of perm(a, b)
+        constexpr uint32_t kZipHi = 0x07030602u;          // [b.2 a.2 b.3 a.3]
         // L01 = [t0.b0 t1.b0 t0.b1 t1.b1], H01 = [t0.b2 t1.b2 t0.b3 t1.b3] (byte 0 first)
-        const uint32_t L01 = (w0 & 0xFFu) | ((w1 & 0xFFu) << 8) | ((w0 & 0xFF00u) << 8) | ((w1 & 0xFF00u) << 16);
-        const uint32_t H01 = ((w0 >> 16) & 0xFFu) | ((w1 >> 8) & 0xFF00u) | ((w0 >> 8) & 0xFF0000u) | (w1 & 0xFF000000u);
-        const uint32_t L23 = (w2 & 0xFFu) | ((w3 & 0xFFu) << 8) | ((w2 & 0xFF00u) << 8) | ((w3 & 0xFF00u) << 16);
-        const uint32_t H23 = ((w2 >> 16) & 0xFFu) | ((w3 >> 8) & 0xFF00u) | ((w2 >> 8) & 0xFF0000u) | (w3 & 0xFF000000u);
+        const uint32_t L01 = __builtin_amdgcn_perm(w1, w0, kZipLo), H01 = __builtin_amdgcn_perm(w1, w0, kZipHi);
+        const uint32_t L23 = __builtin_amdgcn_perm(w3, w2, kZipLo), H23 = __builtin_amdgcn_perm(w3, w2, kZipHi);
         // Y_b = [t0.b t2.b t1.b t3.b]: the codes of tokens 0 and 1 sit 16 bits apart, as do 2 and 3
         uint32_t Y[4];
-        Y[0] = (L01 & 0xFFu) | ((L23 & 0xFFu) << 8) | ((L01 & 0xFF00u) << 8) | ((L23 & 0xFF00u) << 16);
-        Y[1] = ((L01 >> 16) & 0xFFu) | ((L23 >> 8) & 0xFF00u) | ((L01 >> 8) & 0xFF0000u) | (L23 & 0xFF000000u);
-        Y[2] = (H01 & 0xFFu) | ((H23 & 0xFFu) << 8) | ((H01 & 0xFF00u) << 8) | ((H23 & 0xFF00u) << 16);
-        Y[3] = ((H01 >> 16) & 0xFFu) | ((H23 >> 8) & 0xFF00u) | ((H01 >> 8) & 0xFF0000u) | (H23 & 0xFF000000u);
+        Y[0] = __builtin_amdgcn_perm(L23, L01, kZipLo);
+        Y[1] = __builtin_amdgcn_perm(L23, L01, kZipHi);
+        Y[2] = __builtin_amdgcn_perm(H23, H01, kZipLo);
+        Y[3] = __builtin_amdgcn_perm(H23, H01, kZipHi);
 #pragma unroll
         for (int bt = 0; bt < 4; ++bt) {
             uint32_t pr[4];               // (t0,t1).lo  (t0,t1).hi  (t2,t3).lo  (t2,t3).hi of byte bt
             unpack8_16_mfma(Y[bt], c_mask, c_magic, pr);
-            const uint32_t lo01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[0]) - z01);
-            const uint32_t hi01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[1]) - z01);
-            const uint32_t lo23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[2]) - z23);
-            const uint32_t hi23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[3]) - z23);
-            acc[2 * bt]     = __builtin_amdgcn_mfma_f32_16x16x32_f16(quad_operand(lo01, lo23, lo01, lo23), pb, acc[2 * bt], 0, 0, 0);
-            acc[2 * bt + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(quad_operand(hi01, hi23, hi01, hi23), pb, acc[2 * bt + 1], 0, 0, 0);
+            const uint32_t e01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[0]) - z01);
+            const uint32_t o01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[1]) - z01);
+            const uint32_t e23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[2]) - z23);
+            const uint32_t o23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, pr[3]) - z23);
+            const v4h ve = pair_operand(e01, e23), vo = pair_operand(o01, o23);     // even / odd d of byte bt
+            acc[2 * bt]     = __builtin_amdgcn_mfma_f32_16x16x16f16(ve, pb_hi, acc[2 * bt], 0, 0, 0);
+            acc[2 * bt]     = __builtin_amdgcn_mfma_f32_16x16x16f16(ve, pb_lo, acc[2 * bt], 0, 0, 0);
+            acc[2 * bt + 1] = __builtin_amdgcn_mfma_f32_16x16x16f16(vo, pb_hi, acc[2 * bt + 1], 0, 0, 0);
+            acc[2 * bt + 1] = __builtin_amdgcn_mfma_f32_16x16x16f16(vo, pb_lo, acc[2 * bt + 1], 0, 0, 0);
         }
     };
 
@@ -672,11 +691,19 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
         while (G < g_end) {
             const int Gn = G + kWaves;                    // past the end: clamped, unused loads
             const Meta meta_next = fetch_meta(Gn);
+            if ((G + 1) * kTokens <= T) {                 // every token of the group is inside the sequence
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int tile = 4 * G + i;
-                if (tile * kTile < T) consume(st[i], tile, i);
-                fetch(st[i], 4 * Gn + i);                 // the slot's next use is four steps away
+                for (int i = 0; i < 4; ++i) {
+                    consume(st[i], 4 * G + i, i, std::false_type{});
+                    fetch(st[i], 4 * Gn + i);             // the slot's next use is four steps away
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int tile = 4 * G + i;
+                    if (tile * kTile < T) consume(st[i], tile, i, std::true_type{});
+                    fetch(st[i], 4 * Gn + i);
+                }
             }
             if (has_rest) {                               // what the operands could not carry of the zero points
                 float off = off_run;
@@ -733,22 +760,38 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
 }
 
 // Second pass of a split launch: the partials of one (sequence, head) merge as the
-// wavefronts did, out = sum_s e^(M_s - M) num_s / sum_s e^(M_s - M) den_s.
+// wavefronts did, out = sum_s e^(M_s - M) num_s / sum_s e^(M_s - M) den_s.  At most 64 splits:
+// lane s of the first wavefront takes split s, so the maxima are one load per lane and the
+// weights e^(M_s - M) are computed once; then thread d sums its column over the splits with
+// independent loads (a loop that waits for each split's maximum in turn costs the memory
+// latency 2 S times).
 __global__ __launch_bounds__(128)
 void decode_attention_merge_kernel(const float *__restrict__ part, int S, __half *__restrict__ out)
 {
     constexpr int D = 128;
+    __shared__ float s_e[64];
+    __shared__ float s_den;
     const float *src = part + (int64_t)blockIdx.x * S * (D + 2);
-    float M = -INFINITY;
-    for (int s = 0; s < S; ++s) M = fmaxf(M, src[s * (D + 2)]);
-    float num = 0.0f, den = 0.0f;
-    for (int s = 0; s < S; ++s) {
-        const float ms = src[s * (D + 2)];
-        const float e  = ms == -INFINITY ? 0.0f : __expf(ms - M);
-        num += e * src[s * (D + 2) + 2 + threadIdx.x];
-        den += e * src[s * (D + 2) + 1];
+    const int tid = threadIdx.x;
+    if (tid < 64) {
+        const float ms = tid < S ? src[tid * (D + 2)] : -INFINITY;
+        const float dn = tid < S ? src[tid * (D + 2) + 1] : 0.0f;
+        float M = row16_max(ms);
+        M = fmaxf(M, __shfl_xor(M, 16, 64));
+        M = fmaxf(M, __shfl_xor(M, 32, 64));
+        const float e = ms == -INFINITY ? 0.0f : __expf(ms - M);
+        float den = row16_sum(e * dn);
+        den += __shfl_xor(den, 16, 64);
+        den += __shfl_xor(den, 32, 64);
+        s_e[tid] = e;
+        if (tid == 0) s_den = den;
     }
-    out[(int64_t)blockIdx.x * D + threadIdx.x] = __float2half_rn(den > 0.0f ? num / den : 0.0f);
+    __syncthreads();
+    float num = 0.0f;
+#pragma unroll 8
+    for (int s = 0; s < S; ++s) num = fmaf(s_e[s], src[s * (D + 2) + 2 + tid], num);
+    const float den = s_den;
+    out[(int64_t)blockIdx.x * D + tid] = __float2half_rn(den > 0.0f ? num / den : 0.0f);
 }
 
 }  // namespace
@@ -788,10 +831,13 @@ AttentionShape decode_attention_shape(int B, int H, int Hkv, int64_t Tmax)
     const int     Gq     = H / Hkv;
     if (Gq >= 2 && Gq <= kGqaMaxHeads) {
         const int64_t bk = (int64_t)B * Hkv;
-        int64_t want = (1280 + bk - 1) / bk, cap = groups / kGqaWaves;
+        int64_t want = 1280 / bk, cap = groups / kGqaWaves;   // no split from 641 workgroups on
         if (want > cap) want = cap;
         if (want > 64) want = 64;
-        return {kGqaWaves, want < 1 ? 1 : (int)want, true};
+        if (want < 1) want = 1;
+        // every split a whole number of rounds of the four wavefronts
+        const int64_t per = ((groups + want - 1) / want + kGqaWaves - 1) / kGqaWaves * kGqaWaves;
+        return {kGqaWaves, (int)((groups + per - 1) / per), true};
     }
     const int64_t bh     = (int64_t)B * H;
     if (bh > 384 || groups < 16) {
@@ -821,7 +867,8 @@ hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int
     const AttentionShape sh = decode_attention_shape(B, H, Hkv, Tmax);
     const int S      = sh.splits;
     const int groups = (int)((Tmax + kTokens - 1) / kTokens);
-    const int tps    = S > 1 ? (groups + S - 1) / S : (groups > 0 ? groups : 1);
+    int tps = S > 1 ? (groups + S - 1) / S : (groups > 0 ? groups : 1);
+    if (sh.gqa) tps = (tps + kGqaWaves - 1) / kGqaWaves * kGqaWaves;   // whole rounds of the wavefronts
     float *part = S > 1 ? (float *)workspace : nullptr;
     if (sh.gqa) {
         const size_t lds = (size_t)kGqaWaves * (H / Hkv) * kGqaHeadPitch * sizeof(float);   // <= 34 KB
