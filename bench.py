@@ -266,28 +266,30 @@ def mx_measurements():
 
 
 def kv_cache_measurements():
-    """INT4 KV cache, Llama-7B heads (32 x 128): decode attention over the quantised cache
-    against the HBM roofline (algorithmic bytes: 2 x (64 B codes + 2 B scale + 2 B zero) per
-    cached token and head), and the quantise-on-append of one new token per sequence."""
+    """INT4 KV cache, Llama-7B heads (32 x 128) and Llama-70B heads (64 query heads on 8 cache
+    heads): decode attention over the quantised cache against the HBM roofline (algorithmic
+    bytes: 2 x (64 B codes + 2 B scale + 2 B zero) per cached token and CACHE head), and the
+    quantise-on-append of one new token per sequence."""
     out = []
-    H, D = 32, 128
+    D = 128
     gen = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED)
-    for (B, T) in ((8, 4096), (64, 1024), (128, 2048)):
+    for (B, Hq, H, T) in ((8, 32, 32, 4096), (64, 32, 32, 1024), (128, 32, 32, 2048),
+                          (16, 64, 8, 4096), (128, 64, 8, 2048)):
         k = torch.randn((B, H, T, D), generator=gen, device="cuda", dtype=torch.float16)
         kc = atom.atom_kv_quantize(k)
         k.normal_(generator=gen)
         k *= 0.5
         vc = atom.atom_kv_quantize(k)
         del k
-        q = torch.randn((B, H, D), generator=gen, device="cuda", dtype=torch.float16)
+        q = torch.randn((B, Hq, D), generator=gen, device="cuda", dtype=torch.float16)
         seq_len = torch.full((B,), T, dtype=torch.int32, device="cuda")
         o = torch.empty_like(q)
-        need = atom.atom_decode_attention_kv4_workspace_bytes(B, H, H, D, T)
+        need = atom.atom_decode_attention_kv4_workspace_bytes(B, Hq, H, D, T)
         ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
         t = graph_time(lambda: atom.atom_decode_attention_kv4(q, kc, vc, seq_len, D ** -0.5, out=o,
                                                               workspace=ws), 20, 5)
         nbytes = B * H * T * 2 * (D // 2 + 4)
-        entry = {"workload": f"decode attention over the INT4 KV cache, B={B} H={H} D={D} T={T}, HIP graph",
+        entry = {"workload": f"decode attention over the INT4 KV cache, B={B} H={Hq} Hkv={H} D={D} T={T}, HIP graph",
                  "attention_us": t * 1e6, "cache_bytes": nbytes, "GBs": nbytes / t / 1e9,
                  "hbm_frac": nbytes / t / 1e9 / PEAK_HBM_GBS}
         # append: the new token's K and V rows of every sequence, quantised in place
