@@ -86,6 +86,13 @@ def _load():
     L.atom_ref_calibrate_reorder.argtypes = [vp, i64, i64, i32, vp, vp]
     L.atom_ref_quantize_weight.restype = ctypes.c_int
     L.atom_ref_quantize_weight.argtypes = [vp, i64, i64, vp, i32, i32, i32, f32, vp, vp, vp]
+    L.atom_ref_quantize_act_n.restype = ctypes.c_int
+    L.atom_ref_quantize_act_n.argtypes = [vp, i64, i64, vp, f32, vp, i32, i32, i32, i32, f32, vp, vp, vp]
+    L.atom_ref_add_quantize_act_n.restype = ctypes.c_int
+    L.atom_ref_add_quantize_act_n.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, f32, vp, i32, i32,
+                                              i32, i32, f32, vp, vp, vp]
+    L.atom_ref_swiglu_quantize_act_n.restype = ctypes.c_int
+    L.atom_ref_swiglu_quantize_act_n.argtypes = [vp, vp, i64, i64, i64, vp, i32, i32, i32, i32, f32, vp, vp, vp]
     L.atom_ref_w4a4_gemm.restype = ctypes.c_int
     L.atom_ref_w4a4_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, i32, i32, i32,
                                      vp, i64, vp, vp]
@@ -125,8 +132,9 @@ def rmsnorm_row(x_row: np.ndarray, gamma, eps: float) -> np.ndarray:
     return y
 
 
-def quantize_act(x, gamma, eps, idx, group_size=128, n_outlier=128, clip=0.9):
-    """Returns (q4 uint8 [M,K4/2], q8 int8 [M,O], scale float16 [M,G])."""
+def quantize_act(x, gamma, eps, idx, group_size=128, n_outlier=128, clip=0.9, bits=4):
+    """Returns (q4 uint8 [M,K4/2], q8 int8 [M,O], scale float16 [M,G]).  ``bits``: width of
+    the normal channels, 4 or 3 (codes of either width sit sign-extended in nibbles)."""
     x = _c(x, np.float16)
     M, K = x.shape
     g = None if gamma is None else _c(gamma, np.float16)
@@ -135,14 +143,14 @@ def quantize_act(x, gamma, eps, idx, group_size=128, n_outlier=128, clip=0.9):
     q4 = np.zeros((M, K4 // 2), np.uint8)
     q8 = np.zeros((M, n_outlier), np.int8)
     sc = np.zeros((M, G), np.float16)
-    rc = _load().atom_ref_quantize_act(_p(x), M, K, _p(g), eps, _p(idx), K, group_size,
-                                       n_outlier, clip, _p(q4), _p(q8), _p(sc))
+    rc = _load().atom_ref_quantize_act_n(_p(x), M, K, _p(g), eps, _p(idx), K, group_size,
+                                         n_outlier, bits, clip, _p(q4), _p(q8), _p(sc))
     if rc != 0:
         raise ValueError("atom_ref_quantize_act: bad shapes")
     return q4, q8, sc
 
 
-def add_quantize_act(x, res, gamma, eps, idx, group_size=128, n_outlier=128, clip=0.9):
+def add_quantize_act(x, res, gamma, eps, idx, group_size=128, n_outlier=128, clip=0.9, bits=4):
     """Residual add fused in front of the front end.
     Returns (sum float16 [M,K], q4, q8, scale)."""
     x, res = _c(x, np.float16), _c(res, np.float16)
@@ -154,9 +162,9 @@ def add_quantize_act(x, res, gamma, eps, idx, group_size=128, n_outlier=128, cli
     q4 = np.zeros((M, K4 // 2), np.uint8)
     q8 = np.zeros((M, n_outlier), np.int8)
     sc = np.zeros((M, G), np.float16)
-    rc = _load().atom_ref_add_quantize_act(_p(x), _p(res), M, K, K, _p(h), K, _p(g), eps,
-                                           _p(idx), K, group_size, n_outlier, clip, _p(q4),
-                                           _p(q8), _p(sc))
+    rc = _load().atom_ref_add_quantize_act_n(_p(x), _p(res), M, K, K, _p(h), K, _p(g), eps,
+                                             _p(idx), K, group_size, n_outlier, bits, clip, _p(q4),
+                                             _p(q8), _p(sc))
     if rc != 0:
         raise ValueError("atom_ref_add_quantize_act: bad shapes")
     return h, q4, q8, sc
@@ -178,7 +186,7 @@ def silu_mul(gate, up):
     return out
 
 
-def swiglu_quantize_act(gate, up, idx, group_size=128, n_outlier=128, clip=0.9):
+def swiglu_quantize_act(gate, up, idx, group_size=128, n_outlier=128, clip=0.9, bits=4):
     """silu(gate)*up fused in front of reorder + group quantisation.
     Returns (q4, q8, scale)."""
     g, u = _c(gate, np.float16), _c(up, np.float16)
@@ -188,15 +196,17 @@ def swiglu_quantize_act(gate, up, idx, group_size=128, n_outlier=128, clip=0.9):
     q4 = np.zeros((M, K4 // 2), np.uint8)
     q8 = np.zeros((M, n_outlier), np.int8)
     sc = np.zeros((M, G), np.float16)
-    rc = _load().atom_ref_swiglu_quantize_act(_p(g), _p(u), M, K, K, _p(idx), K, group_size,
-                                              n_outlier, clip, _p(q4), _p(q8), _p(sc))
+    rc = _load().atom_ref_swiglu_quantize_act_n(_p(g), _p(u), M, K, K, _p(idx), K, group_size,
+                                                n_outlier, bits, clip, _p(q4), _p(q8), _p(sc))
     if rc != 0:
         raise ValueError("atom_ref_swiglu_quantize_act: bad shapes")
     return q4, q8, sc
 
 
-def quantize_weight(w, idx, group_size=128, n_outlier=128, clip=0.85):
+def quantize_weight(w, idx, group_size=128, n_outlier=128, clip=0.85, bits=4):
     """Returns (q4 uint8 [N,K4/2], q8 int8 [N,O], scale float16 [N,G])."""
+    if bits != 4:
+        return quantize_act(w, None, 0.0, idx, group_size, n_outlier, clip, bits)
     w = _c(w, np.float16)
     N, K = w.shape
     idx = _c(idx, np.int32)

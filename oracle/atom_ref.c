@@ -126,14 +126,17 @@ static int shapes_ok(int32_t K, int32_t Gs, int32_t O)
     return 1;
 }
 
-/* Quantise one row whose fp32 values y[] are in ORIGINAL channel order. */
+/* Quantise one row whose fp32 values y[] are in ORIGINAL channel order.
+ * `bits` is the width n of the normal channels (4, or 3 for the W3A3 runs of
+ * the accuracy evaluation, Section 5.2); the codes of either width travel in
+ * 4-bit containers, sign-extended.  The outlier channels stay at 8 bits. */
 static void quantize_row(const float *y, const int32_t *idx, int32_t K,
-                         int32_t Gs, int32_t O, float clip, uint8_t *q4,
+                         int32_t Gs, int32_t O, int32_t bits, float clip, uint8_t *q4,
                          int8_t *q8, uint16_t *scale)
 {
     int32_t K4 = K - O, G = K / Gs, G4 = K4 / Gs;
     for (int32_t g = 0; g < G; ++g) {
-        int   n    = (g < G4) ? 4 : 8;            /* bit-width of the group */
+        int   n    = (g < G4) ? bits : 8;         /* bit-width of the group */
         int   qmin = -(1 << (n - 1)), qmax = (1 << (n - 1)) - 1;
         float amax = 0.0f;
         for (int32_t t = 0; t < Gs; ++t) {
@@ -153,7 +156,7 @@ static void quantize_row(const float *y, const int32_t *idx, int32_t K,
                 if (v > (float)qmax) v = (float)qmax;
                 q = (int)v;
             }
-            if (n == 4) {
+            if (g < G4) {
                 uint8_t nib = (uint8_t)(q & 0xf);
                 if (j % 2 == 0) q4[j / 2] = nib;
                 else            q4[j / 2] = (uint8_t)(q4[j / 2] | (nib << 4));
@@ -169,13 +172,21 @@ int atom_ref_quantize_act(const uint16_t *x, int64_t M, int64_t ldx,
                           int32_t K, int32_t Gs, int32_t O, float clip,
                           uint8_t *q4, int8_t *q8, uint16_t *scale)
 {
-    if (!shapes_ok(K, Gs, O) || ldx < K || M < 0) return -1;
+    return atom_ref_quantize_act_n(x, M, ldx, gamma, eps, idx, K, Gs, O, 4, clip, q4, q8, scale);
+}
+
+int atom_ref_quantize_act_n(const uint16_t *x, int64_t M, int64_t ldx,
+                            const uint16_t *gamma, float eps, const int32_t *idx,
+                            int32_t K, int32_t Gs, int32_t O, int32_t bits, float clip,
+                            uint8_t *q4, int8_t *q8, uint16_t *scale)
+{
+    if (!shapes_ok(K, Gs, O) || ldx < K || M < 0 || (bits != 3 && bits != 4)) return -1;
     int32_t K4 = K - O, G = K / Gs;
     float *y = (float *)malloc(sizeof(float) * (size_t)K);
     if (!y) return -1;
     for (int64_t m = 0; m < M; ++m) {
         atom_ref_rmsnorm_row(x + m * ldx, gamma, eps, K, y);
-        quantize_row(y, idx, K, Gs, O, clip, q4 + m * (K4 / 2), q8 + m * O,
+        quantize_row(y, idx, K, Gs, O, bits, clip, q4 + m * (K4 / 2), q8 + m * O,
                      scale + m * G);
     }
     free(y);
@@ -193,7 +204,18 @@ int atom_ref_add_quantize_act(const uint16_t *x, const uint16_t *res, int64_t M,
                               int32_t O, float clip, uint8_t *q4, int8_t *q8,
                               uint16_t *scale)
 {
-    if (!shapes_ok(K, Gs, O) || ldx < K || ldr < K || ldo < K || M < 0) return -1;
+    return atom_ref_add_quantize_act_n(x, res, M, ldx, ldr, sum_out, ldo, gamma, eps, idx, K, Gs, O,
+                                       4, clip, q4, q8, scale);
+}
+
+int atom_ref_add_quantize_act_n(const uint16_t *x, const uint16_t *res, int64_t M,
+                                int64_t ldx, int64_t ldr, uint16_t *sum_out,
+                                int64_t ldo, const uint16_t *gamma, float eps,
+                                const int32_t *idx, int32_t K, int32_t Gs,
+                                int32_t O, int32_t bits, float clip, uint8_t *q4, int8_t *q8,
+                                uint16_t *scale)
+{
+    if (!shapes_ok(K, Gs, O) || ldx < K || ldr < K || ldo < K || M < 0 || (bits != 3 && bits != 4)) return -1;
     int32_t K4 = K - O, G = K / Gs;
     float    *y = (float *)malloc(sizeof(float) * (size_t)K);
     uint16_t *h = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)K);
@@ -206,7 +228,7 @@ int atom_ref_add_quantize_act(const uint16_t *x, const uint16_t *res, int64_t M,
         }
         for (int32_t k = 0; k < K; ++k) sum_out[m * ldo + k] = h[k];
         atom_ref_rmsnorm_row(h, gamma, eps, K, y);
-        quantize_row(y, idx, K, Gs, O, clip, q4 + m * (K4 / 2), q8 + m * O,
+        quantize_row(y, idx, K, Gs, O, bits, clip, q4 + m * (K4 / 2), q8 + m * O,
                      scale + m * G);
     }
     free(y);
@@ -258,14 +280,23 @@ int atom_ref_swiglu_quantize_act(const uint16_t *gate, const uint16_t *up,
                                  int32_t O, float clip, uint8_t *q4, int8_t *q8,
                                  uint16_t *scale)
 {
-    if (!shapes_ok(K, Gs, O) || ldg < K || ldu < K || M < 0) return -1;
+    return atom_ref_swiglu_quantize_act_n(gate, up, M, ldg, ldu, idx, K, Gs, O, 4, clip, q4, q8, scale);
+}
+
+int atom_ref_swiglu_quantize_act_n(const uint16_t *gate, const uint16_t *up,
+                                   int64_t M, int64_t ldg, int64_t ldu,
+                                   const int32_t *idx, int32_t K, int32_t Gs,
+                                   int32_t O, int32_t bits, float clip, uint8_t *q4, int8_t *q8,
+                                   uint16_t *scale)
+{
+    if (!shapes_ok(K, Gs, O) || ldg < K || ldu < K || M < 0 || (bits != 3 && bits != 4)) return -1;
     int32_t K4 = K - O, G = K / Gs;
     float *y = (float *)malloc(sizeof(float) * (size_t)K);
     if (!y) return -1;
     for (int64_t m = 0; m < M; ++m) {
         for (int32_t k = 0; k < K; ++k)
             y[k] = atom_ref_silu_mul(gate[m * ldg + k], up[m * ldu + k]);
-        quantize_row(y, idx, K, Gs, O, clip, q4 + m * (K4 / 2), q8 + m * O,
+        quantize_row(y, idx, K, Gs, O, bits, clip, q4 + m * (K4 / 2), q8 + m * O,
                      scale + m * G);
     }
     free(y);

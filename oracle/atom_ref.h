@@ -115,6 +115,29 @@ int atom_ref_w4a4_gemm(const uint8_t *a_q4, const int8_t *a_q8,
                        uint16_t *y_f16, int64_t ldy,
                        int32_t *partials, float *acc_f32);
 
+/* The same four with the width n of the normal channels as a parameter: 4, or 3
+ * for the W3A3 configuration of the accuracy evaluation (Section 5.2).  Section
+ * 2's equations with n = 3: s = 2*amax*c / 7, codes clamped to [-4, 3]; the
+ * codes still travel sign-extended in 4-bit containers (same q4 layout), the
+ * outlier channels stay at 8 bits, and the GEMM is unchanged. */
+int atom_ref_quantize_act_n(const uint16_t *x_f16, int64_t M, int64_t ldx,
+                            const uint16_t *gamma_f16, float eps,
+                            const int32_t *idx, int32_t K, int32_t Gs, int32_t O,
+                            int32_t bits, float clip, uint8_t *q4, int8_t *q8,
+                            uint16_t *scale);
+int atom_ref_add_quantize_act_n(const uint16_t *x_f16, const uint16_t *res_f16,
+                                int64_t M, int64_t ldx, int64_t ldr,
+                                uint16_t *sum_out_f16, int64_t ldo,
+                                const uint16_t *gamma_f16, float eps,
+                                const int32_t *idx, int32_t K, int32_t Gs,
+                                int32_t O, int32_t bits, float clip, uint8_t *q4,
+                                int8_t *q8, uint16_t *scale);
+int atom_ref_swiglu_quantize_act_n(const uint16_t *gate_f16, const uint16_t *up_f16,
+                                   int64_t M, int64_t ldg, int64_t ldu,
+                                   const int32_t *idx, int32_t K, int32_t Gs,
+                                   int32_t O, int32_t bits, float clip, uint8_t *q4,
+                                   int8_t *q8, uint16_t *scale);
+
 /* ---- INT4 KV cache (Section 4.4; asymmetric equations of Section 2) ---------
  * One row = the D values of one token of one attention head (the paper's
  * granularity), n = 4 bits:

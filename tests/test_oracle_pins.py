@@ -91,10 +91,10 @@ def quant_one_group(y_fp16, bits, clip):
     Gs = n + (n % 2)
     ypad = np.zeros(Gs, np.float16)
     ypad[:n] = y
-    if bits == 4:
+    if bits in (3, 4):
         x = ypad[None, :]
         idx = np.arange(Gs, dtype=np.int32)
-        q4, q8, sc = oracle.quantize_act(x, None, 0.0, idx, group_size=Gs, n_outlier=0, clip=clip)
+        q4, q8, sc = oracle.quantize_act(x, None, 0.0, idx, group_size=Gs, n_outlier=0, clip=clip, bits=bits)
         codes = np_unpack(q4, q8)[0, :n]
     else:
         x = np.concatenate([np.zeros(Gs, np.float16), ypad])[None, :]
@@ -257,7 +257,8 @@ def test_rmsnorm_scale_invariance_eps0():
 
 # ------------------------------------------- exact-rational brute force ----
 
-@pytest.mark.parametrize("bits,clip", [(4, 1.0), (4, 0.9), (4, 0.85), (8, 1.0), (8, 0.9), (8, 0.85)])
+@pytest.mark.parametrize("bits,clip", [(4, 1.0), (4, 0.9), (4, 0.85), (8, 1.0), (8, 0.9), (8, 0.85),
+                                       (3, 1.0), (3, 0.9), (3, 0.85)])
 def test_group_quant_matches_exact_rationals(bits, clip):
     rng = np.random.default_rng(10 * bits + int(clip * 100))
     for trial in range(40):
@@ -589,3 +590,50 @@ def test_swiglu_quantize_reduces_to_the_plain_front_end():
         nib = (int(q4[0, j // 2]) >> (4 * (j % 2))) & 0xF
         assert (nib - 16 if nib >= 8 else nib) == q, (j, q, nib)
     assert s > 0
+
+
+# ------------------------------------------------------------ W3A3 -------
+
+def test_three_bit_codes_ranges_fused_variants_and_gemm():
+    """The W3A3 configuration (Section 5.2): normal channels at n = 3.  Codes stay in [-4, 3]
+    and reach both ends; the outlier block is untouched by the width; the fused front ends
+    and the weight path take the width the same way; and the unchanged GEMM on 3-bit codes
+    equals the float64 product of the dequantised operands."""
+    rng = np.random.default_rng(33)
+    M, N, K, Gs, O = 5, 6, 64, 16, 16
+    x = (rng.standard_normal((M, K)) * np.exp(rng.uniform(-1, 1, (1, K)))).astype(np.float16)
+    w = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
+    idx = rng.permutation(K).astype(np.int32)
+    a3 = oracle.quantize_act(x, None, 0.0, idx, Gs, O, 1.0, bits=3)
+    a4 = oracle.quantize_act(x, None, 0.0, idx, Gs, O, 1.0, bits=4)
+    c3 = np_unpack(a3[0], a3[1])
+    assert c3[:, :K - O].min() == -4 and c3[:, :K - O].max() == 3
+    assert np.array_equal(a3[1], a4[1])                                  # INT8 block: same codes
+    assert np.array_equal(a3[2][:, (K - O) // Gs:], a4[2][:, (K - O) // Gs:])    # and same scales
+    # scale ratio of a normal group: (2 amax c / 7) / (2 amax c / 15) = 15 / 7 up to fp16 rounding
+    r = a3[2][:, :(K - O) // Gs].astype(np.float64) / a4[2][:, :(K - O) // Gs].astype(np.float64)
+    assert np.all(np.abs(r - 15.0 / 7.0) < 15.0 / 7.0 * 2.0 ** -9)
+    # weight path and fused variants
+    w3 = oracle.quantize_weight(w, idx, Gs, O, 0.85, bits=3)
+    w3b = oracle.quantize_act(w, None, 0.0, idx, Gs, O, 0.85, bits=3)
+    assert all(np.array_equal(u, v) for u, v in zip(w3, w3b))
+    res = (rng.standard_normal((M, K)) * 0.5).astype(np.float16)
+    gamma = (1.0 + 0.1 * rng.standard_normal(K)).astype(np.float16)
+    h, *q = oracle.add_quantize_act(x, res, gamma, 1e-5, idx, Gs, O, 0.9, bits=3)
+    q_ref = oracle.quantize_act(h, gamma, 1e-5, idx, Gs, O, 0.9, bits=3)
+    assert all(np.array_equal(u, v) for u, v in zip(q, q_ref))
+    # silu(32) = 32 to fp32 rounding and 32 x is an fp16 number: SwiGLU in front reduces to the
+    # plain front end on 32 x
+    big = np.full((M, K), 32.0, np.float16)
+    assert np.array_equal(oracle.silu_mul(big, x), np.float32(32.0) * x.astype(np.float32))
+    sg = oracle.swiglu_quantize_act(big, x, idx, Gs, O, 0.9, bits=3)
+    sref = oracle.quantize_act((np.float32(32.0) * x.astype(np.float32)).astype(np.float16), None, 0.0, idx,
+                               Gs, O, 0.9, bits=3)
+    assert all(np.array_equal(u, v) for u, v in zip(sg, sref))
+    # GEMM on 3-bit operands against float64
+    y16 = oracle.w4a4_gemm(*a3, *w3, group_size=Gs)["y"]
+    ca, cw = np_unpack(a3[0], a3[1]).astype(np.float64), np_unpack(w3[0], w3[1]).astype(np.float64)
+    sa = np.repeat(a3[2].astype(np.float64), Gs, axis=1)
+    sw = np.repeat(w3[2].astype(np.float64), Gs, axis=1)
+    ref = (ca * sa) @ (cw * sw).T
+    assert np.allclose(y16.astype(np.float64), ref, rtol=2e-3, atol=1e-6)
