@@ -23,7 +23,11 @@
  * reordered channels are the outliers kept in INT8; K4 = K - O normal channels
  * in INT4; group size Gs; G = K / Gs groups, the first G4 = K4 / Gs of them
  * INT4.  Supported: Gs = 128, O a positive multiple of 128 with O < K,
- * bits 4 / 8, K <= 32768.
+ * bits 4 / 8, K <= 32768; and bits 3 / 8, the W3A3 configuration of the
+ * accuracy evaluation (Section 5.2): the normal channels are quantised with
+ * n = 3 in the equations of Section 2 (s = 2 amax c / 7, codes in [-4, 3]) and
+ * still travel one code per nibble, sign-extended, so the layouts below and
+ * the GEMM are the same for both widths.
  *
  * Quantised layouts (what parity is judged on)
  *   q4    [rows, K4/2] bytes; byte b of a row holds reordered channel 2b in
@@ -45,7 +49,7 @@ typedef enum {
     ATOM_OK              = 0,
     ATOM_ERR_NULL        = 1,  /* a required pointer is NULL                   */
     ATOM_ERR_SHAPE       = 2,  /* negative size, ld too small, K % Gs != 0 ... */
-    ATOM_ERR_UNSUPPORTED = 3,  /* Gs != 128, bits != (4, 8), K too large       */
+    ATOM_ERR_UNSUPPORTED = 3,  /* Gs != 128, bits not (4, 8) or (3, 8), K too large */
     ATOM_ERR_ALIGN       = 4,  /* a pointer or leading dimension is misaligned */
     ATOM_ERR_WORKSPACE   = 5,  /* workspace missing or too small               */
     ATOM_ERR_HIP         = 6   /* the HIP runtime refused the launch           */
@@ -56,7 +60,7 @@ typedef struct {
     int32_t K;             /* input channels of the linear layer            */
     int32_t group_size;    /* Gs, Section 4.2                               */
     int32_t n_outlier;     /* O, Section 4.1                                */
-    int32_t bits_normal;   /* 4                                             */
+    int32_t bits_normal;   /* 4, or 3 (W3A3, Section 5.2)                   */
     int32_t bits_outlier;  /* 8                                             */
 } atom_desc;
 

@@ -101,8 +101,8 @@ def load_library():
     return L
 
 
-def _desc(K: int, group_size: int, n_outlier: int) -> _Desc:
-    return _Desc(K, group_size, n_outlier, 4, 8)
+def _desc(K: int, group_size: int, n_outlier: int, bits: int = 4) -> _Desc:
+    return _Desc(K, group_size, n_outlier, bits, 8)
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -142,9 +142,10 @@ def _quant_outputs(rows: int, K: int, group_size: int, n_outlier: int, device):
 
 def atom_quantize_act(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float,
                       reorder_idx: torch.Tensor, group_size: int = 128, n_outlier: int = 128,
-                      clip: float = 0.9, out: Optional[Tuple[torch.Tensor, ...]] = None):
+                      clip: float = 0.9, out: Optional[Tuple[torch.Tensor, ...]] = None, bits: int = 4):
     """Fused RMSNorm -> reorder -> dynamic group quantisation of ``x`` [M, K]
-    (fp16, last dim contiguous).  Returns ``(q4, q8, scale)`` device tensors."""
+    (fp16, last dim contiguous).  Returns ``(q4, q8, scale)`` device tensors.  ``bits``: width
+    of the normal channels, 4 or 3 (same layouts: one code per nibble)."""
     L = load_library()
     _dev(x, torch.float16, "x")
     _dev(reorder_idx, torch.int32, "reorder_idx")
@@ -154,7 +155,7 @@ def atom_quantize_act(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float
         raise ValueError("x must be [M, K] with a contiguous last dimension")
     M, K = x.shape
     q4, q8, sc = out if out is not None else _quant_outputs(M, K, group_size, n_outlier, x.device)
-    d = _desc(K, group_size, n_outlier)
+    d = _desc(K, group_size, n_outlier, bits)
     st = L.atom_quantize_act(_ptr(x), M, x.stride(0) if M > 1 else max(K, x.stride(0)), _ptr(gamma),
                              eps, _ptr(reorder_idx), ctypes.byref(d), clip, _ptr(q4), _ptr(q8),
                              _ptr(sc), _stream())
@@ -167,7 +168,7 @@ def atom_add_quantize_act(x: torch.Tensor, residual: torch.Tensor, gamma: Option
                           eps: float, reorder_idx: torch.Tensor, group_size: int = 128,
                           n_outlier: int = 128, clip: float = 0.9,
                           sum_out: Optional[torch.Tensor] = None,
-                          out: Optional[Tuple[torch.Tensor, ...]] = None):
+                          out: Optional[Tuple[torch.Tensor, ...]] = None, bits: int = 4):
     """``h = fp16(x + residual)`` followed by the front end on ``h``.  ``sum_out`` may be
     ``x`` or ``residual`` (in place) or a separate [M, K] tensor; a new one by default.
     Returns ``(h, q4, q8, scale)``."""
@@ -185,7 +186,7 @@ def atom_add_quantize_act(x: torch.Tensor, residual: torch.Tensor, gamma: Option
     _dev(sum_out, torch.float16, "sum_out")
     if sum_out.shape != x.shape or sum_out.stride(1) != 1:
         raise ValueError("sum_out must be [M, K] with a contiguous last dimension")
-    d = _desc(K, group_size, n_outlier)
+    d = _desc(K, group_size, n_outlier, bits)
     q4, q8, sc = out if out is not None else _quant_outputs(M, K, group_size, n_outlier, x.device)
     ld = lambda t: t.stride(0) if M > 1 else max(K, t.stride(0))
     st = L.atom_add_quantize_act(_ptr(x), _ptr(residual), M, ld(x), ld(residual), _ptr(sum_out),
@@ -198,7 +199,7 @@ def atom_add_quantize_act(x: torch.Tensor, residual: torch.Tensor, gamma: Option
 
 def atom_swiglu_quantize_act(gate: torch.Tensor, up: torch.Tensor, reorder_idx: torch.Tensor,
                              group_size: int = 128, n_outlier: int = 128, clip: float = 0.9,
-                             out: Optional[Tuple[torch.Tensor, ...]] = None):
+                             out: Optional[Tuple[torch.Tensor, ...]] = None, bits: int = 4):
     """``silu(gate) * up`` (fp32, never stored) followed by reorder and group quantisation.
     ``gate`` and ``up`` are [M, K] fp16 with a contiguous last dimension, e.g. the two halves
     of the fused gate/up projection's output.  Returns ``(q4, q8, scale)``."""
@@ -210,7 +211,7 @@ def atom_swiglu_quantize_act(gate: torch.Tensor, up: torch.Tensor, reorder_idx: 
         raise ValueError("gate and up must be [M, K] with a contiguous last dimension")
     M, K = gate.shape
     q4, q8, sc = out if out is not None else _quant_outputs(M, K, group_size, n_outlier, gate.device)
-    d = _desc(K, group_size, n_outlier)
+    d = _desc(K, group_size, n_outlier, bits)
     ld = lambda t: t.stride(0) if M > 1 else max(K, t.stride(0))
     st = L.atom_swiglu_quantize_act(_ptr(gate), _ptr(up), M, ld(gate), ld(up), _ptr(reorder_idx),
                                     ctypes.byref(d), clip, _ptr(q4), _ptr(q8), _ptr(sc), _stream())
@@ -221,7 +222,7 @@ def atom_swiglu_quantize_act(gate: torch.Tensor, up: torch.Tensor, reorder_idx: 
 
 def atom_quantize_weight(w: torch.Tensor, reorder_idx: torch.Tensor, group_size: int = 128,
                          n_outlier: int = 128, clip: float = 0.85,
-                         out: Optional[Tuple[torch.Tensor, ...]] = None):
+                         out: Optional[Tuple[torch.Tensor, ...]] = None, bits: int = 4):
     """One-time reorder + group quantisation of ``w`` [N, K] fp16."""
     L = load_library()
     _dev(w, torch.float16, "w")
@@ -230,7 +231,7 @@ def atom_quantize_weight(w: torch.Tensor, reorder_idx: torch.Tensor, group_size:
         raise ValueError("w must be [N, K] with a contiguous last dimension")
     N, K = w.shape
     q4, q8, sc = out if out is not None else _quant_outputs(N, K, group_size, n_outlier, w.device)
-    d = _desc(K, group_size, n_outlier)
+    d = _desc(K, group_size, n_outlier, bits)
     st = L.atom_quantize_weight(_ptr(w), N, w.stride(0) if N > 1 else max(K, w.stride(0)),
                                 _ptr(reorder_idx), ctypes.byref(d), clip, _ptr(q4), _ptr(q8),
                                 _ptr(sc), _stream())

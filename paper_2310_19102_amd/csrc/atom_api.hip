@@ -20,7 +20,8 @@ atom_status check_desc(const atom_desc *d)
 {
     if (!d) return ATOM_ERR_NULL;
     if (d->K <= 0 || d->group_size <= 0 || d->n_outlier < 0) return ATOM_ERR_SHAPE;
-    if (d->group_size != atom_internal::kGroup || d->bits_normal != 4 || d->bits_outlier != 8)
+    if (d->group_size != atom_internal::kGroup || (d->bits_normal != 4 && d->bits_normal != 3) ||
+        d->bits_outlier != 8)
         return ATOM_ERR_UNSUPPORTED;
     if (d->K % d->group_size || d->n_outlier % d->group_size) return ATOM_ERR_SHAPE;
     if (d->n_outlier >= d->K) return ATOM_ERR_SHAPE;
@@ -49,7 +50,8 @@ atom_status quantize_common(const void *x, int64_t rows, int64_t ld, int pre, co
     if (pre != 0 && (!aligned(res, 16) || (ldr % 8))) return ATOM_ERR_ALIGN;
     if (pre == 1 && (!aligned(sum_out, 16) || (ldo % 8))) return ATOM_ERR_ALIGN;
     hipError_t err = atom_internal::launch_quantize_rows(x, rows, ld, pre, res, ldr, sum_out, ldo,
-                                                         gamma, eps, idx, d->K, d->n_outlier, clip,
+                                                         gamma, eps, idx, d->K, d->n_outlier,
+                                                         d->bits_normal, clip,
                                                          q4, q8, scale,
                                                          static_cast<hipStream_t>(stream));
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;

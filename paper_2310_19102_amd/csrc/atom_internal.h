@@ -16,9 +16,10 @@ size_t quantize_lds_bytes(int K, bool norm);
 // One row per workgroup: optional RMSNorm, reorder gather, group quantisation.
 // pre: 0 = the rows of x as they are; 1 = x + res rounded to fp16, written to sum_out;
 // 2 = silu(x) * res in fp32 (x = gate rows, res = up rows; no norm).
+// nbits: width of the normal channels, 4 or 3 (either way one code per nibble).
 hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, int pre, const void *res,
                                 int64_t ldr, void *sum_out, int64_t ldo, const void *gamma,
-                                float eps, const int32_t *idx, int K, int O, float clip,
+                                float eps, const int32_t *idx, int K, int O, int nbits, float clip,
                                 void *q4, void *q8, void *scale, hipStream_t stream);
 
 struct GemmArgs {

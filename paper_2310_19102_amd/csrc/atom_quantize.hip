@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kThreads)
 void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
                           const __half *res, int64_t ldr, __half *sum_out, int64_t ldo,
                           const __half *__restrict__ gamma, float eps,
-                          const int32_t *__restrict__ idx, int K, int O, float clip,
+                          const int32_t *__restrict__ idx, int K, int O, int nbits, float clip,
                           uint8_t *__restrict__ q4, int8_t *__restrict__ q8,
                           __half *__restrict__ scale)
 {
@@ -244,9 +244,10 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
             }
             amax = row16_max(amax);
 
-            const float denom = is4 ? 15.0f : 255.0f;
-            const float qmin  = is4 ? -8.0f : -128.0f;
-            const float qmax  = is4 ? 7.0f : 127.0f;
+            // normal channels: n = nbits (4, or 3 with the codes still in nibbles), outliers n = 8
+            const float denom = is4 ? (nbits == 3 ? 7.0f : 15.0f) : 255.0f;
+            const float qmin  = is4 ? (nbits == 3 ? -4.0f : -8.0f) : -128.0f;
+            const float qmax  = is4 ? (nbits == 3 ? 3.0f : 7.0f) : 127.0f;
             const float s32   = ((2.0f * amax) * clip) / denom;
             const __half sh   = (s32 > 65504.0f) ? __ushort_as_half((unsigned short)0x7bffu)
                                                  : __float2half_rn(s32);
@@ -315,7 +316,7 @@ __global__ __launch_bounds__(NT)
 void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
                                const __half *res, int64_t ldr, __half *sum_out, int64_t ldo,
                                const __half *__restrict__ gamma, float eps,
-                               const int32_t *__restrict__ idx, int K, int O, float clip,
+                               const int32_t *__restrict__ idx, int K, int O, int nbits, float clip,
                                uint8_t *__restrict__ q4, int8_t *__restrict__ q8,
                                __half *__restrict__ scale)
 {
@@ -446,9 +447,10 @@ void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
             amax = row16_max_dpp(amax);
 
             const bool  is4   = gg < G4;
-            const float denom = is4 ? 15.0f : 255.0f;
-            const float qmin  = is4 ? -8.0f : -128.0f;
-            const float qmax  = is4 ? 7.0f : 127.0f;
+            // normal channels: n = nbits (4, or 3 with the codes still in nibbles), outliers n = 8
+            const float denom = is4 ? (nbits == 3 ? 7.0f : 15.0f) : 255.0f;
+            const float qmin  = is4 ? (nbits == 3 ? -4.0f : -8.0f) : -128.0f;
+            const float qmax  = is4 ? (nbits == 3 ? 3.0f : 7.0f) : 127.0f;
             const float s32   = ((2.0f * amax) * clip) / denom;
             const __half sh   = (s32 > 65504.0f) ? __ushort_as_half((unsigned short)0x7bffu)
                                                  : __float2half_rn(s32);
@@ -505,7 +507,7 @@ struct QuantArgs {
     const void *x; int64_t rows, ld;
     int pre;                                                       // kPlain, kAdd or kSwiglu
     const void *res; int64_t ldr; void *sum_out; int64_t ldo;     // second input row / fp16 sum out
-    const void *gamma; float eps; const int32_t *idx; int K, O; float clip;
+    const void *gamma; float eps; const int32_t *idx; int K, O, nbits; float clip;
     void *q4, *q8, *scale;
 };
 
@@ -538,7 +540,7 @@ hipError_t launch_fast(const QuantArgs &a, size_t lds, hipStream_t stream)
     const int64_t grid = (a.rows + rows_per_wg - 1) / rows_per_wg;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NT), lds, stream, (const __half *)a.x,
                        a.rows, a.ld, (const __half *)a.res, a.ldr, (__half *)a.sum_out, a.ldo,
-                       (const __half *)a.gamma, a.eps, a.idx, a.K, a.O, a.clip, (uint8_t *)a.q4,
+                       (const __half *)a.gamma, a.eps, a.idx, a.K, a.O, a.nbits, a.clip, (uint8_t *)a.q4,
                        (int8_t *)a.q8, (__half *)a.scale);
     return hipGetLastError();
 }
@@ -558,7 +560,7 @@ hipError_t launch_plain(const QuantArgs &a, size_t lds, hipStream_t stream)
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, (const __half *)a.x, a.rows,
                        a.ld, (const __half *)a.res, a.ldr, (__half *)a.sum_out, a.ldo,
-                       (const __half *)a.gamma, a.eps, a.idx, a.K, a.O, a.clip, (uint8_t *)a.q4,
+                       (const __half *)a.gamma, a.eps, a.idx, a.K, a.O, a.nbits, a.clip, (uint8_t *)a.q4,
                        (int8_t *)a.q8, (__half *)a.scale);
     return hipGetLastError();
 }
@@ -598,17 +600,17 @@ hipError_t launch_quantize_rows_mx(const void *x, int64_t rows, int64_t ld, cons
     const int grid = (int)(rows < (int64_t)1 << 20 ? rows : (int64_t)1 << 20);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, (const __half *)x, rows, ld,
                        (const __half *)nullptr, (int64_t)0, (__half *)nullptr, (int64_t)0,
-                       (const __half *)gamma, eps, idx, K, O, clip, (uint8_t *)q4, (int8_t *)q8,
+                       (const __half *)gamma, eps, idx, K, O, 4, clip, (uint8_t *)q4, (int8_t *)q8,
                        (__half *)e8);
     return hipGetLastError();
 }
 
 hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, int pre, const void *res,
                                 int64_t ldr, void *sum_out, int64_t ldo, const void *gamma,
-                                float eps, const int32_t *idx, int K, int O, float clip,
+                                float eps, const int32_t *idx, int K, int O, int nbits, float clip,
                                 void *q4, void *q8, void *scale, hipStream_t stream)
 {
-    const QuantArgs a = {x, rows, ld, pre, res, ldr, sum_out, ldo, gamma, eps, idx, K, O, clip, q4, q8, scale};
+    const QuantArgs a = {x, rows, ld, pre, res, ldr, sum_out, ldo, gamma, eps, idx, K, O, nbits, clip, q4, q8, scale};
     const bool norm = gamma != nullptr;
     if (pre == kSwiglu) return dispatch_quantize<false, kSwiglu>(a, stream);   // no norm behind an activation
     if (pre == kAdd)
