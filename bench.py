@@ -286,10 +286,21 @@ def kv_cache_measurements():
         o = torch.empty_like(q)
         need = atom.atom_decode_attention_kv4_workspace_bytes(B, Hq, H, D, T)
         ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
-        t = graph_time(lambda: atom.atom_decode_attention_kv4(q, kc, vc, seq_len, D ** -0.5, out=o,
-                                                              workspace=ws), 20, 5)
         nbytes = B * H * T * 2 * (D // 2 + 4)
-        entry = {"workload": f"decode attention over the INT4 KV cache, B={B} H={Hq} Hkv={H} D={D} T={T}, HIP graph",
+        # a ring of identical caches larger than the last-level cache (256 MB), walked by the
+        # launches of the graph: a cache of 70-290 MB read again and again would come from there
+        copies = max(1, -(-1_200_000_000 // nbytes)) if nbytes < 1_000_000_000 else 1
+        ring = [(kc, vc)] + [(tuple(t.clone() for t in kc), tuple(t.clone() for t in vc)) for _ in range(copies - 1)]
+        turn = [0]
+
+        def attend():
+            k_, v_ = ring[turn[0] % copies]
+            turn[0] += 1
+            atom.atom_decode_attention_kv4(q, k_, v_, seq_len, D ** -0.5, out=o, workspace=ws)
+        t = graph_time(attend, max(20, 2 * copies), 5)
+        del ring
+        entry = {"workload": f"decode attention over the INT4 KV cache, B={B} H={Hq} Hkv={H} D={D} T={T}, "
+                             f"HIP graph over a ring of {copies} caches",
                  "attention_us": t * 1e6, "cache_bytes": nbytes, "GBs": nbytes / t / 1e9,
                  "hbm_frac": nbytes / t / 1e9 / PEAK_HBM_GBS}
         # append: the new token's K and V rows of every sequence, quantised in place
