@@ -106,6 +106,7 @@ def test_host_side_validation_of_the_kv_cache_and_mx_entry_points():
     assert att(*base[:4], 64, *base[5:], None, 0, None) == 3                    # head dimension
     assert att(*base[:6], None, *base[7:], None, 0, None) == 1                  # seq_len
     assert att(p, 0, *base[2:], None, 0, None) == 0
+    assert att(*base[:5], (1 << 25) + 1, *base[6:], None, 0, None) == 3         # 32-bit byte offsets inside a cache head
     assert lib.atom_decode_attention_kv4_workspace_bytes(64, 32, 32, 128, 1024) == 0
     need = lib.atom_decode_attention_kv4_workspace_bytes(1, 2, 2, 128, 8192)
     assert need > 0 and need % (130 * 4) == 0
