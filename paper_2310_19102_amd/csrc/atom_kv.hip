@@ -27,16 +27,29 @@ typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 template <int LPR>
 __device__ __forceinline__ void row_minmax(float &mx, float &mn)
 {
+    if constexpr (LPR == 16) {            // DPP rotations of the 16-lane row: vector-ALU speed, no LDS crossbar
+#define ATOM_ROW_ROR(n)                                                                              \
+        mx = fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(                        \
+                           0, __builtin_bit_cast(int, mx), 0x120 | (n), 0xF, 0xF, false)));          \
+        mn = fminf(mn, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(                        \
+                           0, __builtin_bit_cast(int, mn), 0x120 | (n), 0xF, 0xF, false)))
+        ATOM_ROW_ROR(8);
+        ATOM_ROW_ROR(4);
+        ATOM_ROW_ROR(2);
+        ATOM_ROW_ROR(1);
+#undef ATOM_ROW_ROR
+    } else {
 #pragma unroll
-    for (int d = 1; d < LPR; d <<= 1) {
-        mx = fmaxf(mx, __shfl_xor(mx, d, 64));
-        mn = fminf(mn, __shfl_xor(mn, d, 64));
+        for (int d = 1; d < LPR; d <<= 1) {
+            mx = fmaxf(mx, __shfl_xor(mx, d, 64));
+            mn = fminf(mn, __shfl_xor(mn, d, 64));
+        }
     }
 }
 
 // One row of D = 8 * LPR values per LPR lanes, 64 / LPR rows per wavefront.
 //   s = fp16(((max - min) * clip) / 15), z = clamp(rne(-min / s)), code = clamp(rne(x/s) + z, 0, 15)
-// with IEEE fp32 divisions by the stored scale; a zero scale gives zero codes and z = 0.
+// with correctly rounded fp32 quotients by the stored scale; a zero scale gives zero codes and z = 0.
 // Output row index: r (pos == nullptr), or r * Tmax + pos[r / rows_per_seq] (append one
 // token per sequence: row r = (sequence, head)); rows whose position is outside
 // [0, Tmax) write nothing.
@@ -48,11 +61,22 @@ void kv_quantize_kernel(const __half *__restrict__ x, int64_t R, int64_t ldx, fl
                         int16_t *__restrict__ zero)
 {
     constexpr int D = 8 * LPR;
-    const int64_t r = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
+    constexpr int kRows = 4;              // rows per lane group and workgroup: four loads in flight per lane
+    const int64_t r0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
+    const int64_t stride = (int64_t)gridDim.x * (256 / LPR);
     const int     j = threadIdx.x % LPR;
+    uint4 raws[kRows];
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+        const int64_t ru = r0 + u * stride;
+        const int64_t rr = ru < R ? ru : R - 1;          // idle lanes repeat the last row
+        raws[u] = *reinterpret_cast<const uint4 *>(x + rr * ldx + 8 * j);
+    }
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+    const int64_t r = r0 + u * stride;
     const bool live = r < R;
-    const int64_t rr = live ? r : R - 1;                 // idle lanes repeat the last row
-    const uint4 raw = *reinterpret_cast<const uint4 *>(x + rr * ldx + 8 * j);
+    const uint4 raw = raws[u];
     const __half2 *hp = reinterpret_cast<const __half2 *>(&raw);
     float f[8];
 #pragma unroll
@@ -74,12 +98,25 @@ void kv_quantize_kernel(const __half *__restrict__ x, int64_t R, int64_t ldx, fl
     int z = 0;
     uint32_t w = 0;
     if (s != 0.0f) {
-        float zf = rintf(-mn / s);
+        // Nine quotients by the same divisor: one refined reciprocal, then two residual
+        // corrections per quotient (q += (y - s q) / s, the residual exact in an fma) give the
+        // correctly rounded y / s that the IEEE division sequence gives, at a third of its
+        // instructions.  y and s are fp16 numbers (s >= 2^-24, |y| <= 65504): no quotient,
+        // reciprocal or residual leaves the fp32 range.
+        const float r0 = __builtin_amdgcn_rcpf(s);
+        const float r1 = fmaf(fmaf(-s, r0, 1.0f), r0, r0);
+        auto div_s = [&](float y) {
+            float qf = y * r1;
+            qf = fmaf(fmaf(-s, qf, y), r1, qf);
+            qf = fmaf(fmaf(-s, qf, y), r1, qf);
+            return qf;
+        };
+        float zf = rintf(div_s(-mn));
         zf = fminf(fmaxf(zf, -32768.0f), 32767.0f);
         z = (int)zf;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            float t = rintf(f[i] / s);
+            float t = rintf(div_s(f[i]));
             t = fminf(fmaxf(t, -100000.0f), 100000.0f);
             int c = (int)t + z;
             c = c < 0 ? 0 : (c > 15 ? 15 : c);
@@ -102,6 +139,7 @@ void kv_quantize_kernel(const __half *__restrict__ x, int64_t R, int64_t ldx, fl
             }
         }
     }
+    }   // rows of this lane group
 }
 
 // ---------------------------------------------------------------- decode attention
@@ -803,7 +841,8 @@ hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, floa
                               void *scale, void *zero, hipStream_t stream)
 {
     const int     lpr  = D / 8;
-    const int64_t grid = (R * lpr + 255) / 256;
+    const int64_t per  = 4 * (256 / lpr);               // rows per workgroup: four per lane group
+    const int64_t grid = (R + per - 1) / per;
     if (D == 128)
         hipLaunchKernelGGL(kv_quantize_kernel<16>, dim3((unsigned)grid), dim3(256), 0, stream,
                            (const __half *)x, R, ldx, clip, pos, rows_per_seq, Tmax, (uint8_t *)q,

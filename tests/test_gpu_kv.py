@@ -61,6 +61,28 @@ def test_kv_quantize_special_rows():
     assert float(ref[1][0]) == 0.0 and int(ref[2][0]) == 0       # the pins of these live on the CPU side
 
 
+def test_kv_quantize_quotients_many_rows():
+    """The kernel divides by the stored scale with a refined reciprocal instead of the IEEE
+    division sequence; both are correctly rounded, so codes and zero points must not differ in
+    a single element over many rows of very different ranges, offsets and tie patterns."""
+    R, D = 60000, 128
+    g = torch.Generator().manual_seed(4242)
+    spread = torch.exp(3.0 * torch.randn((R, 1), generator=g))
+    x = torch.randn((R, D), generator=g) * spread + 5.0 * spread * torch.randn((R, 1), generator=g)
+    # a third of the rows on a half-step grid of a power-of-two scale: every quotient an integer or a tie
+    e = torch.randint(-12, 6, (R // 3, 1), generator=g).float()
+    k = torch.randint(0, 31, (R // 3, D), generator=g).float()
+    k[:, 0] = 0
+    k[:, 1] = 30
+    x[: R // 3] = (k * 0.5 + torch.randint(-40, 40, (R // 3, 1), generator=g).float()) * torch.exp2(e)
+    x = x.clamp(-65000, 65000).to(torch.float16)
+    for clip in (1.0, 0.9):
+        print(f"[case] kv_quantize quotients R={R} clip={clip}", flush=True)
+        out = atom.atom_kv_quantize(x.cuda(), clip)
+        torch.cuda.synchronize()
+        _quant_equal(out, oracle.kv_quantize(x.numpy(), clip), f"quotients clip {clip}")
+
+
 def test_kv_quantize_leading_shape():
     kv = synth.kv_case(2, 8, 4, 128, 37, case_id=1)
     out = atom.atom_kv_quantize(kv.k.cuda(), 1.0)
