@@ -57,7 +57,11 @@ __device__ __forceinline__ v4i widen_hi(const uint4 &w)
 // VS: every wavefront's run of groups is a whole number of batches that start on a multiple
 //     of four groups, so the four scales of a batch are one aligned 8-byte load per row
 //     (instead of four 2-byte loads that several wavefronts request from the same lines)
-template <int RB, bool VS>
+// ONE8: there is exactly one INT8 group (O = 128, the set-up of the paper), the last group of the
+//     last wavefront's run.  The second 64 bytes of its rows then have registers of their own, and
+//     the slots hold one 16-byte piece each: 24 registers less per row block, which is what lets two
+//     workgroups share a CU once every load of a batch is in flight at the same time.
+template <int RB, bool VS, bool ONE8 = false>
 __global__ __launch_bounds__(NT)
 void w4a4_gemm_decode_kernel(const GemmParams p)
 {
@@ -67,7 +71,11 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
 
     const int tid  = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    // (told to be the same in every lane: the INT4 / INT8 decisions below then are scalar branches;
+    // as lane-dependent ones they became exec-masked regions, and the compiler waited for the loads
+    // of a slot at the end of its region before it issued the next slot's: four memory round trips
+    // per wavefront instead of one)
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 15, kc = lane >> 4;
 
     const int K4 = p.K - p.O, G = p.K >> 7, G4 = K4 >> 7;
@@ -109,8 +117,10 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
     // weight scales, activation codes, activation scales) is issued before the first is
     // used, so a wavefront pays the memory latency once per batch, not once per group.
     for (int gb = g_begin; gb < g_end; gb += DEPTH) {
-        uint4    wq[DEPTH][2];            // [group][half]: an INT4 group uses half 0 only
-        uint4    aq[DEPTH][RB][2];
+        constexpr int HALVES = ONE8 ? 1 : 2;
+        uint4    wq[DEPTH][HALVES];       // [group][half]: an INT4 group uses half 0 only
+        uint4    aq[DEPTH][RB][HALVES];
+        uint4    wx, ax[RB];              // ONE8: the second half of the INT8 group (untouched elsewhere)
         uint16_t wsc[DEPTH];
         uint16_t asc[DEPTH][RB][4];
 #pragma unroll
@@ -119,9 +129,13 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
             const bool live = g < g_end;
             const int  gc   = live ? g : g_end - 1;         // dead slots re-read the last group
             const bool is4  = gc < G4;
-            if (is4) {
+            // (an INT4 slot leaves its second half alone: writing zeros there made the compiler wait
+            // for every load in flight, since one of an earlier batch might still target the register)
+            if constexpr (ONE8) {         // one load per slot: array and offset are scalar selects
+                const uint8_t *src = is4 ? w4 + (size_t)gc * 64 : reinterpret_cast<const uint8_t *>(w8);
+                wq[d][0] = *reinterpret_cast<const uint4 *>(src);
+            } else if (is4) {
                 wq[d][0] = *reinterpret_cast<const uint4 *>(w4 + (size_t)gc * 64);
-                wq[d][1] = z4;
             } else {
                 wq[d][0] = *reinterpret_cast<const uint4 *>(w8 + (size_t)(gc - G4) * 128);
                 wq[d][1] = *reinterpret_cast<const uint4 *>(w8 + (size_t)(gc - G4) * 128 + 64);
@@ -129,14 +143,15 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
             if constexpr (!VS) wsc[d] = ws[gc];
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                aq[d][rb][0] = z4; aq[d][rb][1] = z4;
-                if (a_ok[rb]) {
-                    if (is4) {
-                        aq[d][rb][0] = *reinterpret_cast<const uint4 *>(a4[rb] + (size_t)gc * 64);
-                    } else {
-                        aq[d][rb][0] = *reinterpret_cast<const uint4 *>(a8[rb] + (size_t)(gc - G4) * 128);
-                        aq[d][rb][1] = *reinterpret_cast<const uint4 *>(a8[rb] + (size_t)(gc - G4) * 128 + 64);
-                    }
+                // rows >= M load row 0 (no lane-dependent branch around a load) and are zeroed below
+                if constexpr (ONE8) {
+                    const uint8_t *src = is4 ? a4[rb] + (size_t)gc * 64 : reinterpret_cast<const uint8_t *>(a8[rb]);
+                    aq[d][rb][0] = *reinterpret_cast<const uint4 *>(src);
+                } else if (is4) {
+                    aq[d][rb][0] = *reinterpret_cast<const uint4 *>(a4[rb] + (size_t)gc * 64);
+                } else {
+                    aq[d][rb][0] = *reinterpret_cast<const uint4 *>(a8[rb] + (size_t)(gc - G4) * 128);
+                    aq[d][rb][1] = *reinterpret_cast<const uint4 *>(a8[rb] + (size_t)(gc - G4) * 128 + 64);
                 }
                 if constexpr (!VS) {
 #pragma unroll
@@ -146,6 +161,17 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
                     }
                 }
             }
+        }
+        if constexpr (ONE8) {
+            // Unconditional (a branch around these loads made the compiler wait for them inside it):
+            // a batch without the INT8 group reads the first piece of its first group once more.
+            const bool has8 = g_end > G4 && gb + DEPTH >= g_end;
+            const int  g0   = gb < G4 ? gb : G4 - 1;
+            wx = *reinterpret_cast<const uint4 *>(has8 ? reinterpret_cast<const uint8_t *>(w8) + 64 : w4 + (size_t)g0 * 64);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                ax[rb] = *reinterpret_cast<const uint4 *>(has8 ? reinterpret_cast<const uint8_t *>(a8[rb]) + 64
+                                                               : a4[rb] + (size_t)g0 * 64);
         }
         if constexpr (VS) {
             static_assert(!VS || DEPTH == 4, "a batch is four groups");
@@ -157,8 +183,9 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int64_t m = 16 * rb + 4 * kc + e;
-                    uint2 av = make_uint2(0, 0);
-                    if (m < p.M) av = *reinterpret_cast<const uint2 *>(p.a_scale + m * G + gb);
+                    // rows >= M: row 0 is read (no lane-dependent branch around a load), zeros are used
+                    uint2 av = *reinterpret_cast<const uint2 *>(p.a_scale + (m < p.M ? m : 0) * G + gb);
+                    if (m >= p.M) av = make_uint2(0, 0);
                     asc[0][rb][e] = (uint16_t)av.x; asc[1][rb][e] = (uint16_t)(av.x >> 16);
                     asc[2][rb][e] = (uint16_t)av.y; asc[3][rb][e] = (uint16_t)(av.y >> 16);
                 }
@@ -170,14 +197,15 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
             const bool is4 = g < G4;
             v4i b0, b1;
             if (is4) { b0 = widen_lo(wq[d][0]); b1 = widen_hi(wq[d][0]); }
-            else     { b0 = __builtin_bit_cast(v4i, wq[d][0]); b1 = __builtin_bit_cast(v4i, wq[d][1]); }
+            else     { b0 = __builtin_bit_cast(v4i, wq[d][0]); b1 = __builtin_bit_cast(v4i, ONE8 ? wx : wq[d][HALVES - 1]); }
             // 2^-8 of the nibble widening folded into the weight scale (exact)
             const float wsf = half_bits_to_float(wsc[d]) * (is4 ? (1.0f / 256.0f) : 1.0f);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
                 v4i x0, x1;
                 if (is4) { x0 = widen_lo(aq[d][rb][0]); x1 = widen_hi(aq[d][rb][0]); }
-                else     { x0 = __builtin_bit_cast(v4i, aq[d][rb][0]); x1 = __builtin_bit_cast(v4i, aq[d][rb][1]); }
+                else     { x0 = __builtin_bit_cast(v4i, aq[d][rb][0]); x1 = __builtin_bit_cast(v4i, ONE8 ? ax[rb] : aq[d][rb][HALVES - 1]); }
+                if (!a_ok[rb]) { x0 = zi; x1 = zi; }
                 v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(x0, b0, zi, 0, 0, 0);
                 c = __builtin_amdgcn_mfma_i32_16x16x64_i8(x1, b1, c, 0, 0, 0);
 #pragma unroll
@@ -215,7 +243,13 @@ hipError_t launch_decode(const GemmParams &p, hipStream_t stream)
     // and is a whole number of four-group batches; both scale arrays 8-byte aligned
     const int  G  = p.K >> 7;
     const bool vs = G % (4 * NW) == 0 && ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 7) == 0;
-    if (p.M <= 16) {
+    // exactly one INT8 group, and it is the last group of the last wavefront's run (G >= 8)
+    const bool one8 = p.O == 128 && G >= NW;
+    if (p.M <= 16 && vs && one8) {
+        hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+    } else if (p.M <= 32 && vs && one8) {
+        hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+    } else if (p.M <= 16) {
         if (vs) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true>), dim3(blocks), dim3(NT), 0, stream, p);
         else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, false>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (p.M <= 32) {
