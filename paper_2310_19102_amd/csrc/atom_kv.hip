@@ -53,7 +53,9 @@ __device__ __forceinline__ void row_minmax(float &mx, float &mn)
 // Output row index: r (pos == nullptr), or r * Tmax + pos[r / rows_per_seq] (append one
 // token per sequence: row r = (sequence, head)); rows whose position is outside
 // [0, Tmax) write nothing.
-template <int LPR>
+// kRows: rows per lane group, i.e. loads in flight per lane: 4 for bulk quantisation, 1 for the
+// append of a few hundred rows (there four rows per lane group only quarter the grid)
+template <int LPR, int kRows>
 __global__ __launch_bounds__(256)
 void kv_quantize_kernel(const __half *__restrict__ x, int64_t R, int64_t ldx, float clip,
                         const int32_t *__restrict__ pos, int32_t rows_per_seq, int64_t Tmax,
@@ -61,7 +63,6 @@ void kv_quantize_kernel(const __half *__restrict__ x, int64_t R, int64_t ldx, fl
                         int16_t *__restrict__ zero)
 {
     constexpr int D = 8 * LPR;
-    constexpr int kRows = 4;              // rows per lane group and workgroup: four loads in flight per lane
     const int64_t r0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
     const int64_t stride = (int64_t)gridDim.x * (256 / LPR);
     const int     j = threadIdx.x % LPR;
@@ -841,16 +842,16 @@ hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, floa
                               void *scale, void *zero, hipStream_t stream)
 {
     const int     lpr  = D / 8;
-    const int64_t per  = 4 * (256 / lpr);               // rows per workgroup: four per lane group
+    const bool    bulk = R >= 65536;                    // four rows per lane group
+    const int64_t per  = (bulk ? 4 : 1) * (256 / lpr);  // rows per workgroup
     const int64_t grid = (R + per - 1) / per;
-    if (D == 128)
-        hipLaunchKernelGGL(kv_quantize_kernel<16>, dim3((unsigned)grid), dim3(256), 0, stream,
-                           (const __half *)x, R, ldx, clip, pos, rows_per_seq, Tmax, (uint8_t *)q,
-                           (__half *)scale, (int16_t *)zero);
-    else
-        hipLaunchKernelGGL(kv_quantize_kernel<8>, dim3((unsigned)grid), dim3(256), 0, stream,
-                           (const __half *)x, R, ldx, clip, pos, rows_per_seq, Tmax, (uint8_t *)q,
-                           (__half *)scale, (int16_t *)zero);
+#define ATOM_KVQ_LAUNCH(LPR, ROWS)                                                                    \
+    hipLaunchKernelGGL((kv_quantize_kernel<LPR, ROWS>), dim3((unsigned)grid), dim3(256), 0, stream,   \
+                       (const __half *)x, R, ldx, clip, pos, rows_per_seq, Tmax, (uint8_t *)q,        \
+                       (__half *)scale, (int16_t *)zero)
+    if (D == 128) { if (bulk) ATOM_KVQ_LAUNCH(16, 4); else ATOM_KVQ_LAUNCH(16, 1); }
+    else          { if (bulk) ATOM_KVQ_LAUNCH(8, 4);  else ATOM_KVQ_LAUNCH(8, 1); }
+#undef ATOM_KVQ_LAUNCH
     return hipGetLastError();
 }
 
