@@ -119,7 +119,7 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
 
     const int tid  = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: group decisions become scalar
     const int V    = K >> 3;      // 8-channel vectors per row
     const int K4   = K - O;
     const int G    = K >> 7;
@@ -326,7 +326,7 @@ void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
 
     const int tid  = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: group decisions become scalar
     const int V    = K >> 3;
     const int K4   = K - O;
     const int G    = K >> 7;
