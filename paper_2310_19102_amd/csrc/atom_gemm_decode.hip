@@ -62,7 +62,7 @@ __device__ __forceinline__ v4i widen_hi(const uint4 &w)
 //     the slots hold one 16-byte piece each: 24 registers less per row block, which is what lets two
 //     workgroups share a CU once every load of a batch is in flight at the same time.
 template <int RB, bool VS, bool ONE8 = false>
-__global__ __launch_bounds__(NT)
+__global__ __launch_bounds__(NT, (ONE8 && RB == 1) ? 6 : 1)    // six wavefronts per SIMD = three workgroups per CU: 80 registers
 void w4a4_gemm_decode_kernel(const GemmParams p)
 {
     __shared__ float red[NW][RB][4][64];   // [slice][row block][register][lane]
@@ -103,6 +103,17 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
         a4[rb] = p.a_q4 + mc * (K4 >> 1) + kc * 16;
         a8[rb] = p.a_q8 + mc * p.O + kc * 16;
     }
+    // ONE8 addresses every load as scalar base + 32-bit byte offset (arrays below 4 GiB: host),
+    // one register per stream instead of a 64-bit pointer per load
+    const uint32_t w4o = (uint32_t)(wr * (K4 >> 1)) + kc * 16, w8o = (uint32_t)(wr * p.O) + kc * 16;
+    uint32_t a4o[RB], a8o[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int64_t mc = a_ok[rb] ? 16 * rb + col : 0;
+        a4o[rb] = (uint32_t)(mc * (K4 >> 1)) + kc * 16;
+        a8o[rb] = (uint32_t)(mc * p.O) + kc * 16;
+    }
+    const uint8_t *w8b = reinterpret_cast<const uint8_t *>(p.w_q8), *a8b = reinterpret_cast<const uint8_t *>(p.a_q8);
     // rows of the result held by this lane: 16*rb + 4*kc + e
     float acc[RB][4];
 #pragma unroll
@@ -123,6 +134,7 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
         uint4    wx, ax[RB];              // ONE8: the second half of the INT8 group (untouched elsewhere)
         uint16_t wsc[DEPTH];
         uint16_t asc[DEPTH][RB][4];
+        uint2    wvs, avs[RB][4];         // VS: the four scales of the batch stay packed until they are used
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
             const int  g    = gb + d;
@@ -132,8 +144,7 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
             // (an INT4 slot leaves its second half alone: writing zeros there made the compiler wait
             // for every load in flight, since one of an earlier batch might still target the register)
             if constexpr (ONE8) {         // one load per slot: array and offset are scalar selects
-                const uint8_t *src = is4 ? w4 + (size_t)gc * 64 : reinterpret_cast<const uint8_t *>(w8);
-                wq[d][0] = *reinterpret_cast<const uint4 *>(src);
+                wq[d][0] = *reinterpret_cast<const uint4 *>((is4 ? p.w_q4 : w8b) + (is4 ? w4o + (uint32_t)gc * 64u : w8o));
             } else if (is4) {
                 wq[d][0] = *reinterpret_cast<const uint4 *>(w4 + (size_t)gc * 64);
             } else {
@@ -145,8 +156,7 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
             for (int rb = 0; rb < RB; ++rb) {
                 // rows >= M load row 0 (no lane-dependent branch around a load) and are zeroed below
                 if constexpr (ONE8) {
-                    const uint8_t *src = is4 ? a4[rb] + (size_t)gc * 64 : reinterpret_cast<const uint8_t *>(a8[rb]);
-                    aq[d][rb][0] = *reinterpret_cast<const uint4 *>(src);
+                    aq[d][rb][0] = *reinterpret_cast<const uint4 *>((is4 ? p.a_q4 : a8b) + (is4 ? a4o[rb] + (uint32_t)gc * 64u : a8o[rb]));
                 } else if (is4) {
                     aq[d][rb][0] = *reinterpret_cast<const uint4 *>(a4[rb] + (size_t)gc * 64);
                 } else {
@@ -167,27 +177,25 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
             // a batch without the INT8 group reads the first piece of its first group once more.
             const bool has8 = g_end > G4 && gb + DEPTH >= g_end;
             const int  g0   = gb < G4 ? gb : G4 - 1;
-            wx = *reinterpret_cast<const uint4 *>(has8 ? reinterpret_cast<const uint8_t *>(w8) + 64 : w4 + (size_t)g0 * 64);
+            wx = *reinterpret_cast<const uint4 *>((has8 ? w8b : p.w_q4) + (has8 ? w8o + 64u : w4o + (uint32_t)g0 * 64u));
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
-                ax[rb] = *reinterpret_cast<const uint4 *>(has8 ? reinterpret_cast<const uint8_t *>(a8[rb]) + 64
-                                                               : a4[rb] + (size_t)g0 * 64);
+                ax[rb] = *reinterpret_cast<const uint4 *>((has8 ? a8b : p.a_q4) + (has8 ? a8o[rb] + 64u : a4o[rb] + (uint32_t)g0 * 64u));
         }
         if constexpr (VS) {
             static_assert(!VS || DEPTH == 4, "a batch is four groups");
-            const uint2 wv = *reinterpret_cast<const uint2 *>(ws + gb);
-            wsc[0] = (uint16_t)wv.x; wsc[1] = (uint16_t)(wv.x >> 16);
-            wsc[2] = (uint16_t)wv.y; wsc[3] = (uint16_t)(wv.y >> 16);
+            // (32-bit element offsets on the scalar bases: M * G and N * G are far below 2^31)
+            const uint2 wv = *reinterpret_cast<const uint2 *>(p.w_scale + ((uint32_t)wr * (uint32_t)G + (uint32_t)gb));
+            wvs = wv;
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int64_t m = 16 * rb + 4 * kc + e;
                     // rows >= M: row 0 is read (no lane-dependent branch around a load), zeros are used
-                    uint2 av = *reinterpret_cast<const uint2 *>(p.a_scale + (m < p.M ? m : 0) * G + gb);
+                    uint2 av = *reinterpret_cast<const uint2 *>(p.a_scale + ((uint32_t)(m < p.M ? m : 0) * (uint32_t)G + (uint32_t)gb));
                     if (m >= p.M) av = make_uint2(0, 0);
-                    asc[0][rb][e] = (uint16_t)av.x; asc[1][rb][e] = (uint16_t)(av.x >> 16);
-                    asc[2][rb][e] = (uint16_t)av.y; asc[3][rb][e] = (uint16_t)(av.y >> 16);
+                    avs[rb][e] = av;
                 }
         }
 #pragma unroll
@@ -199,7 +207,9 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
             if (is4) { b0 = widen_lo(wq[d][0]); b1 = widen_hi(wq[d][0]); }
             else     { b0 = __builtin_bit_cast(v4i, wq[d][0]); b1 = __builtin_bit_cast(v4i, ONE8 ? wx : wq[d][HALVES - 1]); }
             // 2^-8 of the nibble widening folded into the weight scale (exact)
-            const float wsf = half_bits_to_float(wsc[d]) * (is4 ? (1.0f / 256.0f) : 1.0f);
+            // scale number d of a packed four
+            auto unpack = [&](const uint2 &v) { return (uint16_t)((d < 2 ? v.x : v.y) >> (16 * (d & 1))); };
+            const float wsf = half_bits_to_float(VS ? unpack(wvs) : wsc[d]) * (is4 ? (1.0f / 256.0f) : 1.0f);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
                 v4i x0, x1;
@@ -210,7 +220,7 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
                 c = __builtin_amdgcn_mfma_i32_16x16x64_i8(x1, b1, c, 0, 0, 0);
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    acc[rb][e] = fmaf((float)c[e], half_bits_to_float(asc[d][rb][e]) * wsf, acc[rb][e]);
+                    acc[rb][e] = fmaf((float)c[e], half_bits_to_float(VS ? unpack(avs[rb][e]) : asc[d][rb][e]) * wsf, acc[rb][e]);
             }
         }
     }
@@ -242,9 +252,10 @@ hipError_t launch_decode(const GemmParams &p, hipStream_t stream)
     // vector scale loads: every wavefront's run of G / NW groups starts on a multiple of four
     // and is a whole number of four-group batches; both scale arrays 8-byte aligned
     const int  G  = p.K >> 7;
-    const bool vs = G % (4 * NW) == 0 && ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 7) == 0;
+    const bool vs = G % (4 * NW) == 0 && ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 7) == 0 &&
+                    (uint64_t)p.N * (uint64_t)G < (1ull << 31);          // 32-bit scale offsets
     // exactly one INT8 group, and it is the last group of the last wavefront's run (G >= 8)
-    const bool one8 = p.O == 128 && G >= NW;
+    const bool one8 = p.O == 128 && G >= NW && (uint64_t)p.N * (uint64_t)(p.K >> 1) < (1ull << 32);   // 32-bit byte offsets
     if (p.M <= 16 && vs && one8) {
         hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (p.M <= 32 && vs && one8) {
