@@ -206,6 +206,44 @@ __device__ __forceinline__ void unpack8(uint32_t w, uint32_t (&pr)[4])
     pr[3] = and_or(b, 0x003C003Cu, 0x5C005C00u);
 }
 
+// max over the lanes l, l ^ 16, l ^ 32, l ^ 48 with the lane-half swaps of gfx950 (vector ALU
+// speed; a ds_bpermute pair per exchange would sit on the critical path of every step).  A swap
+// exchanges the upper half (32) or the odd rows (16) of its first register with the lower half
+// or the even rows of its second; fed two copies of v, the two results hold, lane by lane, v of
+// the lane itself and of its partner.  This compiler folds max(first result, second result)
+// into the first result, so the second one passes through an empty asm statement (no
+// instruction; it only hides where the value came from), and `zero`, a 0 the compiler cannot
+// see, keeps the two inputs distinct values.
+__device__ __forceinline__ float max_across_chunks(float v, unsigned zero)
+{
+    typedef unsigned v2ui __attribute__((ext_vector_type(2)));
+    unsigned u = __builtin_bit_cast(unsigned, v);
+    v2ui r = __builtin_amdgcn_permlane32_swap(u, u | zero, false, false);
+    unsigned other = r[1];
+    asm volatile("" : "+v"(other));
+    u = __builtin_bit_cast(unsigned, fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, other)));
+    r = __builtin_amdgcn_permlane16_swap(u, u | zero, false, false);
+    other = r[1];
+    asm volatile("" : "+v"(other));
+    return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, other));
+}
+
+// the same exchange for a sum: v(l) + v(l ^ 16), then that + its l ^ 32 partner (the order of
+// the two ds_bpermute exchanges it replaces: float addition commutes, the result is bit-identical)
+__device__ __forceinline__ float sum_across_chunks(float v, unsigned zero)
+{
+    typedef unsigned v2ui __attribute__((ext_vector_type(2)));
+    unsigned u = __builtin_bit_cast(unsigned, v);
+    v2ui r = __builtin_amdgcn_permlane16_swap(u, u | zero, false, false);
+    unsigned other = r[1];
+    asm volatile("" : "+v"(other));
+    u = __builtin_bit_cast(unsigned, __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, other));
+    r = __builtin_amdgcn_permlane32_swap(u, u | zero, false, false);
+    other = r[1];
+    asm volatile("" : "+v"(other));
+    return __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, other);
+}
+
 constexpr int kTile  = 16;                // tokens per wavefront step
 constexpr int kTokens = 64;                // tokens per wavefront group: four steps, one per ring slot
 
@@ -301,6 +339,8 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
             }
     }
 
+    unsigned c_zero = 0u;                 // a zero the compiler cannot see (sum_across_chunks)
+    asm volatile("" : "+s"(c_zero));
     float acc[32];                        // acc[8j + 2k + half] <-> d = 32c + 8j + k + 4 half
 #pragma unroll
     for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
@@ -326,9 +366,7 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
         }
         const float k_s = __half2float(__ushort_as_half((unsigned short)(km & 0xFFFFu)));
         const float k_z = (float)(int16_t)(km >> 16);
-        float part_ = dot - fmaf(k_z, qsum, qoff);
-        part_ += __shfl_xor(part_, 16, 64);
-        part_ += __shfl_xor(part_, 32, 64);
+        const float part_ = sum_across_chunks(dot - fmaf(k_z, qsum, qoff), c_zero);
         const bool valid = tile * kTile + tl < T;
         const float score = valid ? part_ * (k_s * sm_scale) : -INFINITY;
 
@@ -464,28 +502,6 @@ __device__ __forceinline__ void unpack8_16_mfma(uint32_t w, uint32_t mask, uint3
     pr[1] = ((w << 2) & mask) | magic;
     pr[2] = ((w >> 2) & mask) | magic;
     pr[3] = ((w >> 6) & mask) | magic;
-}
-
-// max over the lanes l, l ^ 16, l ^ 32, l ^ 48 with the lane-half swaps of gfx950 (vector ALU
-// speed; a ds_bpermute pair per exchange would sit on the critical path of every step).  A swap
-// exchanges the upper half (32) or the odd rows (16) of its first register with the lower half
-// or the even rows of its second; fed two copies of v, the two results hold, lane by lane, v of
-// the lane itself and of its partner.  This compiler folds max(first result, second result)
-// into the first result, so the second one passes through an empty asm statement (no
-// instruction; it only hides where the value came from), and `zero`, a 0 the compiler cannot
-// see, keeps the two inputs distinct values.
-__device__ __forceinline__ float max_across_chunks(float v, unsigned zero)
-{
-    typedef unsigned v2ui __attribute__((ext_vector_type(2)));
-    unsigned u = __builtin_bit_cast(unsigned, v);
-    v2ui r = __builtin_amdgcn_permlane32_swap(u, u | zero, false, false);
-    unsigned other = r[1];
-    asm volatile("" : "+v"(other));
-    u = __builtin_bit_cast(unsigned, fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, other)));
-    r = __builtin_amdgcn_permlane16_swap(u, u | zero, false, false);
-    other = r[1];
-    asm volatile("" : "+v"(other));
-    return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, other));
 }
 
 constexpr int kGqaWaves    = 4;
