@@ -244,6 +244,14 @@ __device__ __forceinline__ float sum_across_chunks(float v, unsigned zero)
     return __builtin_bit_cast(float, r[0]) + __builtin_bit_cast(float, other);
 }
 
+// value i (0..31) of the 32 fp16 numbers held by four 16-byte registers (i known at compile time)
+__device__ __forceinline__ float half_of(const uint4 (&raw)[4], int i)
+{
+    const uint4 &v = raw[i >> 3];
+    const uint32_t w = ((i >> 1) & 3) == 0 ? v.x : ((i >> 1) & 3) == 1 ? v.y : ((i >> 1) & 3) == 2 ? v.z : v.w;
+    return __half2float(__ushort_as_half((unsigned short)((i & 1) ? w >> 16 : w & 0xFFFFu)));
+}
+
 constexpr int kTile  = 16;                // tokens per wavefront step
 constexpr int kTokens = 64;                // tokens per wavefront group: four steps, one per ring slot
 
@@ -328,11 +336,14 @@ void decode_attention_kv4_kernel(const __half *__restrict__ q, int H, int Hkv, i
     float qsum = 0.0f, qoff = 0.0f;       // sum(q), sum(offset(d) * q)
     {
         const __half *qv = q + ((int64_t)b * H + h) * D + 32 * c;
+        uint4 qraw[4];                    // 64 bytes as four loads (32 two-byte loads cost a microsecond of prologue)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) qraw[j] = *reinterpret_cast<const uint4 *>(qv + 8 * j);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const float lo = __half2float(qv[8 * j + kNib[k]]), hi = __half2float(qv[8 * j + kNib[k] + 4]);
+                const float lo = half_of(qraw, 8 * j + kNib[k]), hi = half_of(qraw, 8 * j + kNib[k] + 4);
                 qp[4 * j + k] = h2{(_Float16)lo, (_Float16)hi};
                 qsum += lo + hi;
                 qoff += kOff[k] * (lo + hi);
@@ -640,11 +651,14 @@ void decode_attention_kv4_gqa_kernel(const __half *__restrict__ q, int H, int Hk
     {
         const bool live = x < Gq;
         const __half *qv = q + ((int64_t)b * H + (int64_t)kvh * Gq + (live ? x : 0)) * D + 32 * c;
+        uint4 qraw[4];                    // 64 bytes as four loads
+#pragma unroll
+        for (int j = 0; j < 4; ++j) qraw[j] = *reinterpret_cast<const uint4 *>(qv + 8 * j);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float e[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) e[i] = live ? __half2float(qv[8 * j + (i >> 1) + 4 * (i & 1)]) : 0.0f;
+            for (int i = 0; i < 8; ++i) e[i] = live ? half_of(qraw, 8 * j + (i >> 1) + 4 * (i & 1)) : 0.0f;
             qb[j] = v8h{(_Float16)e[0], (_Float16)e[1], (_Float16)e[2], (_Float16)e[3],
                         (_Float16)e[4], (_Float16)e[5], (_Float16)e[6], (_Float16)e[7]};
             qsum += ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
