@@ -892,7 +892,7 @@ hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, floa
 // decode_attention_merge_kernel.  Never less than one 64-token group per wavefront and split.
 //
 // With 2 to 16 query heads per cache head the grouped-query kernel runs instead: one workgroup of
-// four wavefronts per (sequence, cache head), the token range split until about 1280 workgroups
+// four wavefronts per (sequence, cache head), the token range split until about 512 workgroups
 // exist.
 struct AttentionShape { int waves, splits; bool gqa; };
 AttentionShape decode_attention_shape(int B, int H, int Hkv, int64_t Tmax)
@@ -901,7 +901,9 @@ AttentionShape decode_attention_shape(int B, int H, int Hkv, int64_t Tmax)
     const int     Gq     = H / Hkv;
     if (Gq >= 2 && Gq <= kGqaMaxHeads) {
         const int64_t bk = (int64_t)B * Hkv;
-        int64_t want = 1280 / bk, cap = groups / kGqaWaves;   // no split from 641 workgroups on
+        // about 512 workgroups (two per CU, one round); measured against 768 to 4096: more splits only add
+        // prologues, epilogues and merge work
+        int64_t want = 512 / bk, cap = groups / kGqaWaves;    // no split from 257 workgroups on
         if (want > cap) want = cap;
         if (want > 64) want = 64;
         if (want < 1) want = 1;
