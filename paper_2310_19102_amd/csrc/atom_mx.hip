@@ -155,9 +155,6 @@ void mx_gemm_kernel(MxParams p)
     // 8 g, the lane's own block of a sub-step sits in byte 0 or 2, which op_sel picks
     int sa[4], sb[4];
     auto read_scales = [&](const uint8_t *buf) __attribute__((always_inline)) {
-#if defined(ATOM_MX_ABL_NOSCALE)
-        if (buf != smem) return;
-#endif
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             sa[s] = (int)(*reinterpret_cast<const uint32_t *>(buf + sa_off + 128 * s) >> (8 * g));
@@ -190,16 +187,8 @@ void mx_gemm_kernel(MxParams p)
     // path through the loop the compiler's wait counts let the loads of two steps stay in
     // flight.  (Macros rather than lambdas that capture the lambdas above: closures nested
     // that way keep the register arrays in scratch memory.)
-#if defined(ATOM_MX_ABL_NOSTAGE)
-#define ATOM_MX_STAGE(u, SET)
-#else
 #define ATOM_MX_STAGE(u, SET) stage(((u) + 1) & 1, regs[SET])
-#endif
-#if defined(ATOM_MX_ABL_NOFETCH)
-#define ATOM_MX_FETCH(u, SET)
-#else
 #define ATOM_MX_FETCH(u, SET) fetch(min((u) + 3, S - 1), regs[SET])
-#endif
 #define ATOM_MX_ADVANCE(u, SET)                                                                  \
     do {                                                                                         \
         ATOM_MX_STAGE(u, SET);                                                                   \
@@ -249,16 +238,8 @@ void mx_gemm_kernel(MxParams p)
         bf[s] = widen(*reinterpret_cast<const v4i *>(smem + (b_base + 2048 * s)));
     }
     read_scales(smem);
-#if defined(ATOM_MX_ABL_NOREAD)
-#define ATOM_MX_RD(old, ptr) (old)
-#else
 #define ATOM_MX_RD(old, ptr) widen(*reinterpret_cast<const v4i *>(ptr))
-#endif
-#if defined(ATOM_MX_ABL_NOSYNC)
-#define ATOM_MX_SYNC()
-#else
 #define ATOM_MX_SYNC() __syncthreads()
-#endif
 #define ATOM_MX_FP4_STEP(u, SET)                                                                 \
     do {                                                                                         \
         const uint8_t *buf = smem + ((u) & 1) * STAGE, *nbuf = smem + (((u) + 1) & 1) * STAGE;   \
