@@ -70,6 +70,8 @@ def test_config1_tiny():
     (1200, 256, 3000, 128, False), # 128x128 tiles, one set, minimal K (one INT4 + one INT8 group)
     (5, 12416, 24, 128, True),     # front end with eight register sets of gather offsets (K > 12288)
     (48, 384, 8200, 128, False),   # 33..64 rows and many output channels: the big-tile kernel on one partial row tile
+    (200, 4096, 300, 128, True),   # six tiles of the big-tile kernel at the Llama-7B K (33 K-steps, two wavefront sets)
+    (300, 2048, 1000, 256, False), # 24 tiles, 18 K-steps, two INT8 groups, ragged edges
 ])
 def test_ragged_shapes(M, K, N, O, norm):
     _check_linear(_rand_linear(M, K, N, O, seed=M * 1000 + N, norm=norm), f"ragged M{M}")
