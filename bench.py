@@ -219,6 +219,7 @@ def extra_measurements():
         torch.cuda.empty_cache()
     out.append(mlp_block_chain())
     out.extend(kv_cache_measurements())
+    out.extend(decode_layer_measurements())
     out.extend(mx_measurements())
     return out
 
@@ -262,6 +263,83 @@ def mx_measurements():
     out.append({"workload": "MX variant, GEMM M=K=N=8192, HIP graph", "gemm_us": t * 1e6,
                 "gemm_tflops": 2 * M * N * K / t / 1e12,
                 "gemm_fp4_mfma_frac": 2 * M * N * K / t / 1e12 / PEAK_FP4_TFLOPS})
+    return out
+
+
+def decode_layer_measurements():
+    """One Llama-7B decoder layer at decode time as a chain of this library's calls only (the
+    workflow of the paper's Figure of the Atom transformer block, Sections 4.1-4.5): residual add +
+    RMSNorm + quantise -> Q, K, V projections -> INT4 quantise-on-append of the new K and V rows
+    -> attention over the INT4 cache -> quantise -> output projection -> residual add + RMSNorm
+    + quantise -> fused gate/up projection -> silu * up + quantise -> down projection.  (Rotary
+    embedding, which the method does not touch, is left out.)  A ring of layers with their own
+    weights (107 MB each) and caches, larger than the last-level cache, runs as one HIP graph; the
+    figure is microseconds per layer and the tokens/s a 32-layer stack of such layers would reach."""
+    out = []
+    Hd, H, D, F = 4096, 32, 128, 11008
+    gen = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED + 7)
+
+    def rnd(*shape, scale=1.0):
+        return (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * scale).to(torch.float16)
+    idx_h = torch.randperm(Hd, generator=gen, device="cuda").to(torch.int32)
+    idx_f = torch.randperm(F, generator=gen, device="cuda").to(torch.int32)
+    gamma = (1.0 + 0.1 * torch.randn(Hd, generator=gen, device="cuda")).to(torch.float16)
+    for (B, T) in ((8, 1024), (64, 1024)):
+        n_layers = 12                       # 12 x (107 MB weights + caches): well beyond 256 MB
+        layers = []
+        for _ in range(n_layers):
+            lw = {name: atom.atom_quantize_weight(rnd(n, k, scale=0.02), idx_h if k == Hd else idx_f)
+                  for name, n, k in (("q", Hd, Hd), ("k", Hd, Hd), ("v", Hd, Hd), ("o", Hd, Hd),
+                                     ("gu", 2 * F, Hd), ("down", Hd, F))}
+            lw["kc"] = atom.atom_kv_quantize(rnd(B, H, T, D))
+            lw["vc"] = atom.atom_kv_quantize(rnd(B, H, T, D, scale=0.5))
+            layers.append(lw)
+        x, res = rnd(B, Hd), rnd(B, Hd)
+        pos = torch.full((B,), T - 1, dtype=torch.int32, device="cuda")
+        seq_len = torch.full((B,), T, dtype=torch.int32, device="cuda")
+        need = atom.atom_decode_attention_kv4_workspace_bytes(B, H, H, D, T)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        bufs = {"q": torch.empty((B, Hd), dtype=torch.float16, device="cuda"),
+                "k": torch.empty((B, Hd), dtype=torch.float16, device="cuda"),
+                "v": torch.empty((B, Hd), dtype=torch.float16, device="cuda"),
+                "att": torch.empty((B, H, D), dtype=torch.float16, device="cuda"),
+                "o": torch.empty((B, Hd), dtype=torch.float16, device="cuda"),
+                "gu": torch.empty((B, 2 * F), dtype=torch.float16, device="cuda"),
+                "y": torch.empty((B, Hd), dtype=torch.float16, device="cuda"),
+                "h": torch.empty((B, Hd), dtype=torch.float16, device="cuda"),
+                "h2": torch.empty((B, Hd), dtype=torch.float16, device="cuda")}
+
+        def layer(lw, x_in, res_in):
+            _, *qa = atom.atom_add_quantize_act(x_in, res_in, gamma, 1e-5, idx_h, sum_out=bufs["h"])
+            for name in ("q", "k", "v"):
+                atom.atom_w4a4_gemm(*qa, *lw[name], out=bufs[name])
+            atom.atom_kv_quantize(bufs["k"].view(B, H, D), cache=lw["kc"], pos=pos)
+            atom.atom_kv_quantize(bufs["v"].view(B, H, D), cache=lw["vc"], pos=pos)
+            atom.atom_decode_attention_kv4(bufs["q"].view(B, H, D), lw["kc"], lw["vc"], seq_len, D ** -0.5,
+                                           out=bufs["att"], workspace=ws)
+            qo = atom.atom_quantize_act(bufs["att"].view(B, Hd), None, 0.0, idx_h)
+            atom.atom_w4a4_gemm(*qo, *lw["o"], out=bufs["o"])
+            _, *qa2 = atom.atom_add_quantize_act(bufs["o"], bufs["h"], gamma, 1e-5, idx_h, sum_out=bufs["h2"])
+            atom.atom_w4a4_gemm(*qa2, *lw["gu"], out=bufs["gu"])
+            qd = atom.atom_swiglu_quantize_act(bufs["gu"][:, :F], bufs["gu"][:, F:], idx_f)
+            atom.atom_w4a4_gemm(*qd, *lw["down"], out=bufs["y"])
+            return bufs["y"], bufs["h2"]
+
+        def stack():
+            xi, ri = x, res
+            for lw in layers:
+                xi, ri = layer(lw, xi, ri)
+        t = graph_time(stack, 1, 5) / n_layers
+        wbytes = sum(sum(t_.numel() * t_.element_size() for t_ in lw[name])
+                     for lw in layers[:1] for name in ("q", "k", "v", "o", "gu", "down"))
+        cbytes = 2 * B * H * T * (D // 2 + 4)
+        out.append({"workload": f"Llama-7B decoder layer at decode time, B={B}, {T} cached tokens, 13 launches per "
+                                f"layer, HIP graph over {n_layers} layers with their own weights and caches",
+                    "us_per_layer": t * 1e6, "weight_bytes_per_layer": wbytes, "cache_bytes_per_layer": cbytes,
+                    "GBs": (wbytes + cbytes) / t / 1e9, "hbm_frac": (wbytes + cbytes) / t / 1e9 / PEAK_HBM_GBS,
+                    "tokens_per_s_32_layers": B / (32 * t)})
+        del layers, bufs, ws
+        torch.cuda.empty_cache()
     return out
 
 
@@ -402,6 +480,8 @@ def main():
                     help="rows of each linear the CPU oracle is timed on (1024 rows of config 4 take about 12 s)")
     ap.add_argument("--kv-only", action="store_true",
                     help="print only the INT4 KV-cache measurements (a short run to put under rocprofv3)")
+    ap.add_argument("--layer-only", action="store_true",
+                    help="print only the decoder-layer chain (decode time)")
     ap.add_argument("--mx-only", action="store_true",
                     help="print only the MX-variant measurements (a short run to put under rocprofv3)")
     ap.add_argument("--pmc-calibrate", action="store_true",
@@ -427,6 +507,9 @@ def main():
         return
     if args.mx_only:
         print(json.dumps({"mx": mx_measurements()}))
+        return
+    if args.layer_only:
+        print(json.dumps({"decode_layer": decode_layer_measurements()}))
         return
 
     layers = [DeviceLinear(synth.make(args.config, w))
