@@ -67,7 +67,7 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
 {
     __shared__ float red[NW][RB][4][64];   // [slice][row block][register][lane]
     // groups whose loads are in flight together per wavefront (register budget)
-    constexpr int DEPTH = RB >= 4 ? 2 : 4;
+    constexpr int DEPTH = (RB >= 4 && !ONE8) ? 2 : 4;
 
     const int tid  = threadIdx.x;
     const int lane = tid & 63;
@@ -260,6 +260,8 @@ hipError_t launch_decode(const GemmParams &p, hipStream_t stream)
         hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (p.M <= 32 && vs && one8) {
         hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+    } else if (vs && one8) {
+        hipLaunchKernelGGL((w4a4_gemm_decode_kernel<4, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (p.M <= 16) {
         if (vs) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true>), dim3(blocks), dim3(NT), 0, stream, p);
         else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, false>), dim3(blocks), dim3(NT), 0, stream, p);
