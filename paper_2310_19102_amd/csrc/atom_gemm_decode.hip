@@ -54,9 +54,9 @@ __device__ __forceinline__ v4i widen_hi(const uint4 &w)
 }
 
 // RB: 16-row blocks of activations (M <= 16 * RB)
-// VS: every wavefront's run of groups is a whole number of batches that start on a multiple
-//     of four groups, so the four scales of a batch are one aligned 8-byte load per row
-//     (instead of four 2-byte loads that several wavefronts request from the same lines)
+// VS: the wavefronts' runs are whole blocks of four groups (G even), so the four scales of a
+//     batch are one 8-byte load per row (instead of four 2-byte loads that several wavefronts
+//     request from the same lines); needs 4-byte aligned scale arrays
 // ONE8: there is exactly one INT8 group (O = 128, the set-up of the paper), the last group of the
 //     last wavefront's run.  The second 64 bytes of its rows then have registers of their own, and
 //     the slots hold one 16-byte piece each: 24 registers less per row block, which is what lets two
@@ -82,8 +82,11 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
     const int64_t n0 = (int64_t)blockIdx.x * TN;
 
     // this wavefront's run of groups
-    const int g_begin = (int)((int64_t)wave * G / NW);
-    const int g_end   = (int)((int64_t)(wave + 1) * G / NW);
+    // (VS: in whole blocks of four groups, so that a batch's four scales are one 8-byte piece of
+    // a scale row that starts on a multiple of four; the last block of K may be a partial one)
+    const int nblk    = VS ? (G + 3) >> 2 : G;
+    const int g_begin = (VS ? 4 : 1) * (int)((int64_t)wave * nblk / NW);
+    const int g_end   = min(G, (VS ? 4 : 1) * (int)((int64_t)(wave + 1) * nblk / NW));
 
     // weight row of this lane (clamped: rows >= N are computed and never stored)
     int64_t wr = n0 + col;
@@ -185,7 +188,12 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
         if constexpr (VS) {
             static_assert(!VS || DEPTH == 4, "a batch is four groups");
             // (32-bit element offsets on the scalar bases: M * G and N * G are far below 2^31)
-            const uint2 wv = *reinterpret_cast<const uint2 *>(p.w_scale + ((uint32_t)wr * (uint32_t)G + (uint32_t)gb));
+            // a row of scales starts on an even element (G even), its four-blocks on 4-byte
+            // boundaries at least: an 8-byte load that the hardware takes at dword alignment.  The
+            // last block of K reads the last four scales of the row instead (never past the row).
+            typedef uint2 __attribute__((aligned(4))) uint2_a4;
+            const int gbs = gb <= G - 4 ? gb : G - 4;
+            const uint2 wv = *reinterpret_cast<const uint2_a4 *>(p.w_scale + ((uint32_t)wr * (uint32_t)G + (uint32_t)gbs));
             wvs = wv;
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
@@ -193,7 +201,7 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
                 for (int e = 0; e < 4; ++e) {
                     const int64_t m = 16 * rb + 4 * kc + e;
                     // rows >= M: row 0 is read (no lane-dependent branch around a load), zeros are used
-                    uint2 av = *reinterpret_cast<const uint2 *>(p.a_scale + ((uint32_t)(m < p.M ? m : 0) * (uint32_t)G + (uint32_t)gb));
+                    uint2 av = *reinterpret_cast<const uint2_a4 *>(p.a_scale + ((uint32_t)(m < p.M ? m : 0) * (uint32_t)G + (uint32_t)gbs));
                     if (m >= p.M) av = make_uint2(0, 0);
                     avs[rb][e] = av;
                 }
@@ -208,7 +216,8 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
             else     { b0 = __builtin_bit_cast(v4i, wq[d][0]); b1 = __builtin_bit_cast(v4i, ONE8 ? wx : wq[d][HALVES - 1]); }
             // 2^-8 of the nibble widening folded into the weight scale (exact)
             // scale number d of a packed four
-            auto unpack = [&](const uint2 &v) { return (uint16_t)((d < 2 ? v.x : v.y) >> (16 * (d & 1))); };
+            const int sidx = VS ? d + (gb - (gb <= G - 4 ? gb : G - 4)) : d;    // <= 3 for every live slot
+            auto unpack = [&](const uint2 &v) { return (uint16_t)((sidx < 2 ? v.x : v.y) >> (16 * (sidx & 1))); };
             const float wsf = half_bits_to_float(VS ? unpack(wvs) : wsc[d]) * (is4 ? (1.0f / 256.0f) : 1.0f);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
@@ -252,7 +261,7 @@ hipError_t launch_decode(const GemmParams &p, hipStream_t stream)
     // vector scale loads: every wavefront's run of G / NW groups starts on a multiple of four
     // and is a whole number of four-group batches; both scale arrays 8-byte aligned
     const int  G  = p.K >> 7;
-    const bool vs = G % (4 * NW) == 0 && ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 7) == 0 &&
+    const bool vs = G % 2 == 0 && G >= 4 && ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 3) == 0 &&
                     (uint64_t)p.N * (uint64_t)G < (1ull << 31);          // 32-bit scale offsets
     // exactly one INT8 group, and it is the last group of the last wavefront's run (G >= 8)
     const bool one8 = p.O == 128 && G >= NW && (uint64_t)p.N * (uint64_t)(p.K >> 1) < (1ull << 32);   // 32-bit byte offsets

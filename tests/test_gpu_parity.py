@@ -69,6 +69,10 @@ def test_config1_tiny():
     (200, 1152, 300, 256, True),   # two wavefront sets, two INT8 groups, odd/even split of the steps
     (1200, 256, 3000, 128, False), # 128x128 tiles, one set, minimal K (one INT4 + one INT8 group)
     (5, 12416, 24, 128, True),     # front end with eight register sets of gather offsets (K > 12288)
+    (8, 11008, 40, 128, False),    # decode kernel at the Llama-7B down projection: 86 groups = 21.5 blocks of four
+    (16, 5120, 48, 128, True),     # 40 groups (Llama-13B): five blocks over eight wavefronts, three of them idle
+    (40, 2560, 32, 128, True),     # four row blocks, 20 groups
+    (24, 768, 20, 256, True),      # two INT8 groups: the general slots with the blocked runs (6 groups, 2 blocks)
     (48, 384, 8200, 128, False),   # 33..64 rows and many output channels: the big-tile kernel on one partial row tile
     (200, 4096, 300, 128, True),   # six tiles of the big-tile kernel at the Llama-7B K (33 K-steps, two wavefront sets)
     (300, 2048, 1000, 256, False), # 24 tiles, 18 K-steps, two INT8 groups, ragged edges
