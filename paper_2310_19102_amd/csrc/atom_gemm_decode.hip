@@ -57,12 +57,14 @@ __device__ __forceinline__ v4i widen_hi(const uint4 &w)
 // VS: the wavefronts' runs are whole blocks of four groups (G even), so the four scales of a
 //     batch are one 8-byte load per row (instead of four 2-byte loads that several wavefronts
 //     request from the same lines); needs 4-byte aligned scale arrays
+// Q4: with VS, G is a multiple of four and the scale arrays are 8-byte aligned: every block is a
+//     whole one, its scales an aligned piece, and scale number d of the piece belongs to slot d
 // ONE8: there is exactly one INT8 group (O = 128, the set-up of the paper), the last group of the
 //     last wavefront's run.  The second 64 bytes of its rows then have registers of their own, and
 //     the slots hold one 16-byte piece each: 24 registers less per row block, which is what lets two
 //     workgroups share a CU once every load of a batch is in flight at the same time.
-template <int RB, bool VS, bool ONE8 = false>
-__global__ __launch_bounds__(NT, (ONE8 && RB == 1) ? 6 : 1)    // six wavefronts per SIMD = three workgroups per CU: 80 registers
+template <int RB, bool VS, bool ONE8 = false, bool Q4 = false>
+__global__ __launch_bounds__(NT, (ONE8 && RB == 1 && Q4) ? 6 : 1)    // six wavefronts per SIMD = three workgroups per CU: 80 registers
 void w4a4_gemm_decode_kernel(const GemmParams p)
 {
     __shared__ float red[NW][RB][4][64];   // [slice][row block][register][lane]
@@ -188,20 +190,26 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
         if constexpr (VS) {
             static_assert(!VS || DEPTH == 4, "a batch is four groups");
             // (32-bit element offsets on the scalar bases: M * G and N * G are far below 2^31)
-            // a row of scales starts on an even element (G even), its four-blocks on 4-byte
-            // boundaries at least: an 8-byte load that the hardware takes at dword alignment.  The
-            // last block of K reads the last four scales of the row instead (never past the row).
-            typedef uint2 __attribute__((aligned(4))) uint2_a4;
-            const int gbs = gb <= G - 4 ? gb : G - 4;
-            const uint2 wv = *reinterpret_cast<const uint2_a4 *>(p.w_scale + ((uint32_t)wr * (uint32_t)G + (uint32_t)gbs));
-            wvs = wv;
+            // Q4: one aligned 8-byte piece.  Otherwise a row of scales starts on an even element
+            // (G even) and its four-blocks on 4-byte boundaries: two 4-byte loads, the second one
+            // held inside the row where the last block of K has two groups only (its slots are dead).
+            const int g2 = gb + 2 <= G - 2 ? gb + 2 : G - 2;
+            // (scalar base + 32-bit byte offset per lane, like the codes)
+            auto load4 = [&](const uint16_t *base, uint32_t row) {
+                const uint8_t *sb  = reinterpret_cast<const uint8_t *>(base);
+                const uint32_t off = row * (uint32_t)(2 * G);
+                if constexpr (Q4) return *reinterpret_cast<const uint2 *>(base + (row * (uint32_t)G + (uint32_t)gb));
+                else return make_uint2(*reinterpret_cast<const uint32_t *>(sb + 2 * gb + off),
+                                       *reinterpret_cast<const uint32_t *>(sb + 2 * g2 + off));
+            };
+            wvs = load4(p.w_scale, (uint32_t)wr);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int64_t m = 16 * rb + 4 * kc + e;
                     // rows >= M: row 0 is read (no lane-dependent branch around a load), zeros are used
-                    uint2 av = *reinterpret_cast<const uint2_a4 *>(p.a_scale + ((uint32_t)(m < p.M ? m : 0) * (uint32_t)G + (uint32_t)gbs));
+                    uint2 av = load4(p.a_scale, (uint32_t)(m < p.M ? m : 0));
                     if (m >= p.M) av = make_uint2(0, 0);
                     avs[rb][e] = av;
                 }
@@ -216,7 +224,7 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
             else     { b0 = __builtin_bit_cast(v4i, wq[d][0]); b1 = __builtin_bit_cast(v4i, ONE8 ? wx : wq[d][HALVES - 1]); }
             // 2^-8 of the nibble widening folded into the weight scale (exact)
             // scale number d of a packed four
-            const int sidx = VS ? d + (gb - (gb <= G - 4 ? gb : G - 4)) : d;    // <= 3 for every live slot
+            const int sidx = d;
             auto unpack = [&](const uint2 &v) { return (uint16_t)((sidx < 2 ? v.x : v.y) >> (16 * (sidx & 1))); };
             const float wsf = half_bits_to_float(VS ? unpack(wvs) : wsc[d]) * (is4 ? (1.0f / 256.0f) : 1.0f);
 #pragma unroll
@@ -258,19 +266,23 @@ namespace atom_gemm {
 hipError_t launch_decode(const GemmParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)((p.N + TN - 1) / TN);
-    // vector scale loads: every wavefront's run of G / NW groups starts on a multiple of four
-    // and is a whole number of four-group batches; both scale arrays 8-byte aligned
+    // vector scale loads: G even (a scale row then starts on a 4-byte boundary), both scale arrays
+    // 4-byte aligned
     const int  G  = p.K >> 7;
     const bool vs = G % 2 == 0 && G >= 4 && ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 3) == 0 &&
                     (uint64_t)p.N * (uint64_t)G < (1ull << 31);          // 32-bit scale offsets
     // exactly one INT8 group, and it is the last group of the last wavefront's run (G >= 8)
     const bool one8 = p.O == 128 && G >= NW && (uint64_t)p.N * (uint64_t)(p.K >> 1) < (1ull << 32);   // 32-bit byte offsets
+    const bool q4 = G % 4 == 0 && ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 7) == 0;
     if (p.M <= 16 && vs && one8) {
-        hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        if (q4) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (p.M <= 32 && vs && one8) {
-        hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        if (q4) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (vs && one8) {
-        hipLaunchKernelGGL((w4a4_gemm_decode_kernel<4, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        if (q4) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<4, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<4, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (p.M <= 16) {
         if (vs) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true>), dim3(blocks), dim3(NT), 0, stream, p);
         else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, false>), dim3(blocks), dim3(NT), 0, stream, p);
