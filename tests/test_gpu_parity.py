@@ -252,6 +252,31 @@ def test_run_twice_is_deterministic():
     assert torch.equal(y1, y2)
 
 
+@pytest.mark.parametrize("K", [1024, 768, 1280])        # 8 groups (whole blocks of four), 6 and 10 (a half block last)
+@pytest.mark.parametrize("shift", [1, 2, 4])            # scale arrays 2, 4 and 8 bytes off a 16-byte boundary
+def test_decode_gemm_scale_alignment(K, shift):
+    """The decode kernel picks its scale loads (8-byte, 4-byte, 2-byte) by the alignment of the
+    scale arrays and by the group count: every choice gives the same result."""
+    lin = _rand_linear(24, K, 72, 128, seed=60 + K + shift)
+    print(f"[case] scale alignment: K={K} shift={shift}", flush=True)
+    ga = gpu_quantize_act(lin)
+    gw = gpu_quantize_weight(lin)
+    y0 = atom.atom_w4a4_gemm(*ga, *gw)
+
+    def moved(sc):
+        buf = torch.zeros(sc.numel() + 8, dtype=sc.dtype, device=sc.device)
+        off = (-(buf.data_ptr() // 2) % 8 + shift) % 8  # elements to the wanted misalignment
+        v = buf[off:off + sc.numel()].view(sc.shape)
+        v.copy_(sc)
+        assert v.data_ptr() % 16 == 2 * shift
+        return v
+    y1 = atom.atom_w4a4_gemm(ga[0], ga[1], moved(ga[2]), gw[0], gw[1], moved(gw[2]))
+    torch.cuda.synchronize()
+    ref = oracle.w4a4_gemm(*ref_quantize_act(lin), *ref_quantize_weight(lin), lin.group_size, want_partials=False)
+    assert y_rel_err(npy(y0), ref["y"]) <= Y_TOL
+    assert y_rel_err(npy(y1), ref["y"]) <= Y_TOL
+
+
 @pytest.mark.parametrize("which", [0, 1])
 def test_config2_llama7b_attention(which):
     _check_linear(synth.make(2, which), f"config2[{which}]", full_partials=(which == 0))
