@@ -76,32 +76,46 @@ class DeviceLinear:
         atom.atom_w4a4_gemm(*self.qa, *qw, self.lin.group_size, out=self.y)
 
 
-def run_steps(layers, steps, warmup):
+def run_steps(layers, steps, warmup, clock_warmup_s=0.0):
     """Time `steps` passes; HIP events (on the stream the kernels run on)
     bracket every GEMM launch and every front-end launch inside the timed
     region.  Returns (seconds per step, gemm seconds per step, front-end
-    seconds per step, number of GEMM launches per step)."""
+    seconds per step, number of GEMM launches per step).
+
+    clock_warmup_s: the same steps are first run untimed for that long.  An idle
+    GPU needs about 100 steps (30 ms) of this workload to reach its steady clocks:
+    the first 25 steps after start-up or after two idle seconds take 280-310 us
+    each, the next 25 about 254, from step 125 on 228-229."""
+    t_end = time.perf_counter() + clock_warmup_s
+    while time.perf_counter() < t_end:
+        for _ in range(20):
+            for L in layers:
+                L.front_end()
+                L.gemm()
+        torch.cuda.synchronize()
     for _ in range(warmup):
         for L in layers:
             L.front_end()
             L.gemm()
     torch.cuda.synchronize()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps * len(layers))]
+    # one event between any two launches: event 2i sits before front end i, event 2i+1
+    # between it and its GEMM, event 2i+2 after the GEMM (and before the next front end)
+    n = steps * len(layers)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * n + 1)]
     t0 = time.perf_counter()
     i = 0
+    ev[0].record()
     for _ in range(steps):
         for L in layers:
-            e = ev[i]
-            i += 1
-            e[0].record()
             L.front_end()
-            e[1].record()
+            ev[2 * i + 1].record()
             L.gemm()
-            e[2].record()
+            ev[2 * i + 2].record()
+            i += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    fe = sum(e[0].elapsed_time(e[1]) for e in ev) * 1e-3 / steps
-    ge = sum(e[1].elapsed_time(e[2]) for e in ev) * 1e-3 / steps
+    fe = sum(ev[2 * j].elapsed_time(ev[2 * j + 1]) for j in range(n)) * 1e-3 / steps
+    ge = sum(ev[2 * j + 1].elapsed_time(ev[2 * j + 2]) for j in range(n)) * 1e-3 / steps
     return dt / steps, ge, fe, len(layers)
 
 
@@ -137,7 +151,7 @@ def extra_measurements():
     out = []
     lin = synth.make(2, 0)
     L = DeviceLinear(lin)
-    t, ge, fe, _ = run_steps([L], 200, 20)
+    t, ge, fe, _ = run_steps([L], 200, 20, 0.05)
     out.append({"workload": "config2 attn_proj M=256 K=4096 N=4096", "ms_per_step": t * 1e3,
                 "effective_tops": L.ops / t / 1e12, "gemm_us": ge * 1e6, "front_end_us": fe * 1e6,
                 "gemm_mfma_frac": L.ops / ge / 1e12 / PEAK_INT8_TOPS})
@@ -156,8 +170,7 @@ def extra_measurements():
         with torch.cuda.graph(graph):
             for _ in range(reps):
                 L.gemm()
-        graph.replay()
-        torch.cuda.synchronize()
+        warm_replays(graph)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(3):
@@ -166,7 +179,7 @@ def extra_measurements():
         torch.cuda.synchronize()
         per = e0.elapsed_time(e1) * 1e-3 / (3 * reps)
         del graph
-        t, ge, fe, _ = run_steps([L], 200, 20)
+        t, ge, fe, _ = run_steps([L], 200, 20, 0.05)
         out.append({"workload": f"config3 decode M={lin.M} K=4096 N={lin.N}, weight ring of {copies}",
                     "gemm_us_in_graph": per * 1e6, "gemm_bytes": L.gemm_bytes,
                     "gemm_GBs": L.gemm_bytes / per / 1e9,
@@ -201,8 +214,7 @@ def extra_measurements():
             with torch.cuda.graph(graph):
                 for _ in range(50):
                     fn()
-            graph.replay()
-            torch.cuda.synchronize()
+            warm_replays(graph)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(4):
@@ -403,8 +415,7 @@ def graph_time(fn, launches=20, replays=5):
     with torch.cuda.graph(graph):
         for _ in range(launches):
             fn()
-    graph.replay()
-    torch.cuda.synchronize()
+    warm_replays(graph)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(replays):
@@ -413,6 +424,17 @@ def graph_time(fn, launches=20, replays=5):
     torch.cuda.synchronize()
     del graph
     return e0.elapsed_time(e1) * 1e-3 / (launches * replays)
+
+
+def warm_replays(graph, seconds=0.05):
+    """Untimed replays for `seconds` (at least one): capture leaves the GPU idle
+    for some milliseconds and its clocks take about 30 ms of work to come back."""
+    t_end = time.perf_counter() + seconds
+    while True:
+        graph.replay()
+        torch.cuda.synchronize()
+        if time.perf_counter() >= t_end:
+            return
 
 
 def mlp_block_chain():
@@ -471,8 +493,10 @@ def measured_traffic(config):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--clock-warmup", type=float, default=0.25,
+                    help="seconds of untimed steps before the warm-up steps, to bring an idle GPU to its steady clocks")
     ap.add_argument("--config", type=int, default=4, choices=sorted(WORKLOAD_NAMES))
     ap.add_argument("--no-extra", action="store_true", help="skip the context measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
@@ -514,7 +538,7 @@ def main():
 
     layers = [DeviceLinear(synth.make(args.config, w))
               for w in range(len(synth.CONFIG_SHAPES[args.config]))]
-    sec, gemm_sec, fe_sec, n_gemm = run_steps(layers, args.steps, args.warmup)
+    sec, gemm_sec, fe_sec, n_gemm = run_steps(layers, args.steps, args.warmup, args.clock_warmup)
     ops = sum(L.ops for L in layers)
     gemm_bytes = sum(L.gemm_bytes for L in layers)
     achieved = ops / gemm_sec / 1e12
@@ -533,7 +557,7 @@ def main():
     line = {
         "metric": "W4A4 group-GEMM effective TOPS (incl. act quant)",
         "value": ops / sec / 1e12, "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
+        "warmup": args.warmup, "clock_warmup_s": args.clock_warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[args.config], "config_index": args.config,
                    "linears": [{"name": L.name, "M": L.M, "K": L.K, "N": L.N} for L in layers],
