@@ -1,6 +1,7 @@
 // Mixed-precision group-quantised GEMM (Section 4.2 of the paper, steps 1-3)
 // for gfx950: nibble-packed INT4 codes stream from HBM with 128-bit loads, are
-// widened to INT8 on their way into LDS, are contracted on the INT8 MFMA with
+// widened to INT8 (this file: after the LDS fragment read; the big-tile kernel: on
+// their way into LDS), are contracted on the INT8 MFMA with
 // int32 accumulation one 128-channel group at a time, and every group's
 // integer tile is rescaled by a_scale[m,g] * w_scale[n,g] into fp32 VGPR
 // accumulators (ascending g, fused multiply-add), stored as fp16.
@@ -31,12 +32,22 @@ namespace {
 
 using namespace atom_gemm;
 
-template <int BM, int BN, int WM, int WN, bool DBG>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64)
+// KS wavefront sets per workgroup: set s runs the whole pipeline on its own pair of LDS stages
+// over its own contiguous share of the groups; the sets' fp32 tiles meet in LDS at the end and
+// set 0 adds them in set order (a fixed tree).  For launches of few tiles, where the time is the
+// latency of one set's chain of K-steps and most of the chip would otherwise idle.
+// 16 packed bytes -> 16 int8 values 16 * code: the low nibbles, the high nibbles
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ v4i nibbles_lo(v4u w) { return __builtin_bit_cast(v4i, (w << 4) & 0xF0F0F0F0u); }
+__device__ __forceinline__ v4i nibbles_hi(v4u w) { return __builtin_bit_cast(v4i, w & 0xF0F0F0F0u); }
+
+template <int BM, int BN, int WM, int WN, bool DBG, int KS = 1>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64 * KS)
 void w4a4_gemm_kernel(const GemmParams p)
 {
     constexpr int NW = (BM / WM) * (BN / WN);
-    constexpr int NT = NW * 64;
+    constexpr int NT = NW * 64;                          // threads of one set
+    static_assert(!DBG || KS == 1, "the partial-sum dump runs one set");
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int A4 = BM * 4 / NT, B4 = BN * 4 / NT;   // 16-byte chunks per thread, INT4 group
     constexpr int A8 = BM * 8 / NT, B8 = BN * 8 / NT;   // same, INT8 group
@@ -45,11 +56,13 @@ void w4a4_gemm_kernel(const GemmParams p)
     static_assert(BM * 4 % NT == 0 && BN * 4 % NT == 0, "tile/threads mismatch");
     static_assert(A4 >= 1 && B4 >= 1, "tile too small for the thread count");
 
-    extern __shared__ __align__(16) unsigned char smem[];
+    extern __shared__ __align__(16) unsigned char smem_all[];
 
-    const int tid  = threadIdx.x;
+    const int set  = KS == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x / NT);
+    const int tid  = KS == 1 ? (int)threadIdx.x : (int)threadIdx.x - set * NT;
     const int lane = tid & 63;
     const int wave = tid >> 6;
+    unsigned char *smem = smem_all + set * (2 * STAGE);
     const int wm   = wave / (BN / WN);
     const int wn   = wave % (BN / WN);
 
@@ -69,80 +82,89 @@ void w4a4_gemm_kernel(const GemmParams p)
     const int64_t m0 = (int64_t)(logical % MB) * BM;
     const int64_t n0 = (int64_t)(logical / MB) * BN;
 
-    uint4    pre[A8 + B8];
-    uint16_t sc[SC];
+    // the operands of one group on their way from global memory to LDS
+    // (first-class vector values: nothing here may end up in scratch)
+    struct Pre { v4u a[A8], b[B8]; uint16_t sc[SC]; };
 
-    auto prefetch = [&](int g) {
+    // Row pointers of the INT4 loads and of the scale loads, computed once: left inside the
+    // loop, their 64-bit multiplies were most of a trip's vector instructions.  (The INT8
+    // groups are the last trip or two of the last set: their addresses are made on the spot.)
+    const uint8_t *a4p[A4], *w4p[B4];
+#pragma unroll
+    for (int i = 0; i < A4; ++i) {
+        int64_t r = m0 + (tid >> 2) + i * (NT / 4);
+        r = r < p.M ? r : p.M - 1;
+        a4p[i] = p.a_q4 + r * a4s + (tid & 3) * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < B4; ++i) {
+        int64_t r = n0 + (tid >> 2) + i * (NT / 4);
+        r = r < p.N ? r : p.N - 1;
+        w4p[i] = p.w_q4 + r * a4s + (tid & 3) * 16;
+    }
+    // thread t < BM stages the scale of activation row t, thread BM + t that of weight row t;
+    // rows past the end read the last row (their results are never stored), other threads
+    // read a value nobody uses: no load sits behind a lane-dependent branch
+    const uint16_t *scp[SC];
+#pragma unroll
+    for (int i = 0; i < SC; ++i) {
+        const int t = tid + i * NT;
+        int64_t ra = m0 + (t < BM ? t : 0), rw = n0 + (t >= BM && t < BM + BN ? t - BM : 0);
+        ra = ra < p.M ? ra : p.M - 1;
+        rw = rw < p.N ? rw : p.N - 1;
+        scp[i] = t >= BM && t < BM + BN ? p.w_scale + rw * G : p.a_scale + ra * G;
+    }
+
+    auto prefetch = [&](int g, Pre &pre) {
+        v4u (&preA)[A8] = pre.a; v4u (&preB)[B8] = pre.b; uint16_t (&sc)[SC] = pre.sc;
         if (g < G4) {
 #pragma unroll
-            for (int i = 0; i < A4; ++i) {
-                int64_t r = m0 + (tid >> 2) + i * (NT / 4);
-                r = r < p.M ? r : p.M - 1;
-                pre[i] = *reinterpret_cast<const uint4 *>(p.a_q4 + r * a4s + g * 64 + (tid & 3) * 16);
-            }
+            for (int i = 0; i < A4; ++i) preA[i] = *reinterpret_cast<const v4u *>(a4p[i] + g * 64);
 #pragma unroll
-            for (int i = 0; i < B4; ++i) {
-                int64_t r = n0 + (tid >> 2) + i * (NT / 4);
-                r = r < p.N ? r : p.N - 1;
-                pre[A8 + i] = *reinterpret_cast<const uint4 *>(p.w_q4 + r * a4s + g * 64 + (tid & 3) * 16);
-            }
+            for (int i = 0; i < B4; ++i) preB[i] = *reinterpret_cast<const v4u *>(w4p[i] + g * 64);
         } else {
             const int g8 = g - G4;
 #pragma unroll
             for (int i = 0; i < A8; ++i) {
                 int64_t r = m0 + (tid >> 3) + i * (NT / 8);
                 r = r < p.M ? r : p.M - 1;
-                pre[i] = *reinterpret_cast<const uint4 *>(p.a_q8 + r * o8s + g8 * 128 + (tid & 7) * 16);
+                preA[i] = *reinterpret_cast<const v4u *>(p.a_q8 + r * o8s + g8 * 128 + (tid & 7) * 16);
             }
 #pragma unroll
             for (int i = 0; i < B8; ++i) {
                 int64_t r = n0 + (tid >> 3) + i * (NT / 8);
                 r = r < p.N ? r : p.N - 1;
-                pre[A8 + i] = *reinterpret_cast<const uint4 *>(p.w_q8 + r * o8s + g8 * 128 + (tid & 7) * 16);
+                preB[i] = *reinterpret_cast<const v4u *>(p.w_q8 + r * o8s + g8 * 128 + (tid & 7) * 16);
             }
         }
 #pragma unroll
-        for (int i = 0; i < SC; ++i) {
-            const int t = tid + i * NT;
-            uint16_t v = 0;
-            if (t < BM) {
-                if (m0 + t < p.M) v = p.a_scale[(m0 + t) * G + g];
-            } else if (t < BM + BN) {
-                if (n0 + (t - BM) < p.N) v = p.w_scale[(n0 + (t - BM)) * G + g];
-            }
-            sc[i] = v;
-        }
+        for (int i = 0; i < SC; ++i) sc[i] = scp[i][g];
     };
 
-    auto stage_to_lds = [&](int g, int stage) {
+    auto stage_to_lds = [&](int g, int stage, const Pre &pre) {
+        const v4u (&preA)[A8] = pre.a; const v4u (&preB)[B8] = pre.b; const uint16_t (&sc)[SC] = pre.sc;
         unsigned char *sA = smem + stage * STAGE;
         unsigned char *sB = sA + BM * 128;
         float *sS = reinterpret_cast<float *>(sB + BN * 128);
         if (g < G4) {
-            const int c2 = (tid & 3) * 2;
-            auto widen = [&](const uint4 &w, unsigned char *base, int row) {
-                uint4 lo, hi;
-                lo.x = (w.x << 4) & 0xF0F0F0F0u; hi.x = w.x & 0xF0F0F0F0u;
-                lo.y = (w.y << 4) & 0xF0F0F0F0u; hi.y = w.y & 0xF0F0F0F0u;
-                lo.z = (w.z << 4) & 0xF0F0F0F0u; hi.z = w.z & 0xF0F0F0F0u;
-                lo.w = (w.w << 4) & 0xF0F0F0F0u; hi.w = w.w & 0xF0F0F0F0u;
-                *reinterpret_cast<uint4 *>(base + lds_off(row, c2))     = lo;
-                *reinterpret_cast<uint4 *>(base + lds_off(row, c2 + 1)) = hi;
-            };
+            // an INT4 group stays packed in LDS (pieces 0..3 of the row's slot; LDS writes run
+            // at a third of the read rate): the nibbles are widened after the fragment read
 #pragma unroll
-            for (int i = 0; i < A4; ++i) widen(pre[i], sA, (tid >> 2) + i * (NT / 4));
+            for (int i = 0; i < A4; ++i)
+                *reinterpret_cast<v4u *>(sA + lds_off((tid >> 2) + i * (NT / 4), tid & 3)) = preA[i];
 #pragma unroll
-            for (int i = 0; i < B4; ++i) widen(pre[A8 + i], sB, (tid >> 2) + i * (NT / 4));
+            for (int i = 0; i < B4; ++i)
+                *reinterpret_cast<v4u *>(sB + lds_off((tid >> 2) + i * (NT / 4), tid & 3)) = preB[i];
         } else {
 #pragma unroll
             for (int i = 0; i < A8; ++i) {
                 const int row = (tid >> 3) + i * (NT / 8);
-                *reinterpret_cast<uint4 *>(sA + lds_off(row, tid & 7)) = pre[i];
+                *reinterpret_cast<v4u *>(sA + lds_off(row, tid & 7)) = preA[i];
             }
 #pragma unroll
             for (int i = 0; i < B8; ++i) {
                 const int row = (tid >> 3) + i * (NT / 8);
-                *reinterpret_cast<uint4 *>(sB + lds_off(row, tid & 7)) = pre[A8 + i];
+                *reinterpret_cast<v4u *>(sB + lds_off(row, tid & 7)) = preB[i];
             }
         }
 #pragma unroll
@@ -160,12 +182,23 @@ void w4a4_gemm_kernel(const GemmParams p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    prefetch(0);
-    for (int g = 0; g < G; ++g) {
-        const int stage = g & 1;
-        stage_to_lds(g, stage);
+    // this set's groups; every set makes the same number of trips (and barriers), a set whose
+    // share is one group shorter idles through the last one
+    const int g_begin = (int)((int64_t)set * G / KS), g_end = (int)((int64_t)(set + 1) * G / KS);
+    const int trips   = (G + KS - 1) / KS;
+    // Two groups are in flight in registers: the loads issued in trip `it` are consumed at the
+    // start of trip it + 2 (with one group of slack a trip lasted as long as a memory round trip).
+    Pre pre0, pre1;
+    if (g_begin < g_end) prefetch(g_begin, pre0);
+    if (g_begin + 1 < g_end) prefetch(g_begin + 1, pre1);
+    auto trip = [&](int it, Pre &pre) {
+        const int g = g_begin + it;
+        const int stage = it & 1;
+        const bool live = g < g_end;
+        if (live) stage_to_lds(g, stage, pre);
         __syncthreads();
-        if (g + 1 < G) prefetch(g + 1);
+        if (!live) return;
+        if (g + 2 < g_end) prefetch(g + 2, pre);
 
         const unsigned char *sA = smem + stage * STAGE;
         const unsigned char *sB = sA + BM * 128;
@@ -179,6 +212,34 @@ void w4a4_gemm_kernel(const GemmParams p)
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) c[i][j][r] = 0;
+        if (g < G4) {
+            // A lane reads packed piece 2*kp + (lane >> 5) of its rows once and feeds two MFMAs
+            // from it: the low nibbles of its 32 channels, then the high ones (as 16 * code; both
+            // operands deal the group's channels to the four MFMAs the same way, and an exact
+            // integer sum does not depend on the order).
+#pragma unroll
+            for (int kp = 0; kp < 2; ++kp) {
+                const int piece = 2 * kp + (lane >> 5);
+                v4i alo[TM], ahi[TM], blo[TN], bhi[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const v4u r = *reinterpret_cast<const v4u *>(sA + lds_off(wm * WM + 32 * i + (lane & 31), piece));
+                    alo[i] = nibbles_lo(r); ahi[i] = nibbles_hi(r);
+                }
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const v4u r = *reinterpret_cast<const v4u *>(sB + lds_off(wn * WN + 32 * j + (lane & 31), piece));
+                    blo[j] = nibbles_lo(r); bhi[j] = nibbles_hi(r);
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i], blo[j], c[i][j], 0, 0, 0);
+                        c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi[i], bhi[j], c[i][j], 0, 0, 0);
+                    }
+            }
+        } else {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             v4i a[TM], b[TN];
@@ -194,6 +255,7 @@ void w4a4_gemm_kernel(const GemmParams p)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], c[i][j], 0, 0, 0);
+        }
         }
 
         // steps 2 and 3: dequantise the group's tile and add it in fp32
@@ -217,6 +279,35 @@ void w4a4_gemm_kernel(const GemmParams p)
                 }
             }
         }
+    };
+    for (int it = 0; it < trips; it += 2) {
+        trip(it, pre0);
+        if (it + 1 < trips) trip(it + 1, pre1);
+    }
+
+    if constexpr (KS > 1) {
+        // sets 1 .. KS-1 hand their tiles over (value v of thread t at [v][t]: conflict-free)
+        float *red = reinterpret_cast<float *>(smem_all);
+        __syncthreads();                                  // every set is done with its stages
+        if (set > 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        red[(((set - 1) * TM * TN + i * TN + j) * 16 + r) * NT + tid] = acc[i][j][r];
+        }
+        __syncthreads();
+        if (set > 0) return;
+        for (int s2 = 0; s2 < KS - 1; ++s2)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[i][j][r] += red[((s2 * TM * TN + i * TN + j) * 16 + r) * NT + tid];
     }
 
 #pragma unroll
@@ -232,13 +323,15 @@ void w4a4_gemm_kernel(const GemmParams p)
             }
 }
 
-template <int BM, int BN, int WM, int WN, bool DBG>
+template <int BM, int BN, int WM, int WN, bool DBG, int KS = 1>
 hipError_t launch_tile(const GemmParams &p, hipStream_t stream)
 {
-    constexpr int NT = (BM / WM) * (BN / WN) * 64;
-    constexpr int LDS = 2 * ((BM + BN) * 128 + (BM + BN) * 4);
+    constexpr int NT = (BM / WM) * (BN / WN) * 64 * KS;
+    constexpr int LDS = KS * 2 * ((BM + BN) * 128 + (BM + BN) * 4);
+    static_assert(NT <= 1024 && LDS <= 160 * 1024, "workgroup limits");
+    static_assert((KS - 1) * (NT / KS) * (WM / 32) * (WN / 32) * 16 * 4 <= LDS, "the sets' tiles fit the stages");
     const int64_t MB = (p.M + BM - 1) / BM, NB = (p.N + BN - 1) / BN;
-    auto kern = &w4a4_gemm_kernel<BM, BN, WM, WN, DBG>;
+    auto kern = &w4a4_gemm_kernel<BM, BN, WM, WN, DBG, KS>;
     static bool configured = false;   // one attribute call per kernel variant and process
     if (!configured) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -253,12 +346,19 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t stream)
 template <bool DBG>
 hipError_t dispatch(const GemmParams &p, hipStream_t stream)
 {
-    // M <= 64 streams the weights; but from 33 rows on, with many output channels, the big-tile
-    // kernel is the faster one (measured at K = 4096: M = 64, N = 11008 42.8 us against 27.1 us,
-    // N = 22016 82.6 against 32.5; at N = 4096 the streaming kernel wins, 15.6 against 26.4)
+    // M <= 64 streams the weights; but from 33 rows on, with many output channels, a tiled
+    // kernel is the faster one (measured at K = 4096: M = 64, N = 11008 42.8 us against 27.1 us
+    // on the big-tile kernel; at N = 4096 the streaming kernel wins, 10.3 against 26.4).
     if (!DBG && p.M <= 64 && !(p.M > 32 && p.N >= 8192)) return launch_decode(p, stream);
+    // Launches of few tiles are bound by the latency of one tile's chain of K-steps: 64 x 64
+    // tiles put every compute unit to work and four (or two) wavefront sets per workgroup split
+    // that chain (M = 256, N = K = 4096: 25.7 us on 128 x 128 tiles with two sets).
+    if constexpr (!DBG) {
+        const int64_t t64 = ((p.M + 63) / 64) * ((p.N + 63) / 64);
+        if (t64 <= 256) return launch_tile<64, 64, 32, 32, false, 4>(p, stream);
+        if (t64 <= 512) return launch_tile<64, 64, 32, 32, false, 2>(p, stream);
+    }
     if (!DBG && p.M <= 64) return launch_big(p, stream);
-    if (p.M <= 32) return launch_tile<32, 64, 32, 32, DBG>(p, stream);
     if (p.M <= 64) return launch_tile<64, 64, 32, 32, DBG>(p, stream);
     return launch_big(p, stream);
 }

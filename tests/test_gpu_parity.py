@@ -73,6 +73,9 @@ def test_config1_tiny():
     (16, 5120, 48, 128, True),     # 40 groups (Llama-13B): five blocks over eight wavefronts, three of them idle
     (40, 2560, 32, 128, True),     # four row blocks, 20 groups
     (24, 768, 20, 256, True),      # two INT8 groups: the general slots with the blocked runs (6 groups, 2 blocks)
+    (100, 256, 200, 128, True),    # 64 x 64 tiles, four wavefront sets and two groups: two sets stay empty
+    (130, 640, 136, 256, False),   # four sets on five groups (1, 1, 1, 2), two of them INT8, ragged tile edges
+    (320, 1024, 3500, 128, True),  # 275 tiles of 64 x 64: two wavefront sets per workgroup
     (48, 384, 8200, 128, False),   # 33..64 rows and many output channels: the big-tile kernel on one partial row tile
     (200, 4096, 300, 128, True),   # six tiles of the big-tile kernel at the Llama-7B K (33 K-steps, two wavefront sets)
     (300, 2048, 1000, 256, False), # 24 tiles, 18 K-steps, two INT8 groups, ragged edges
