@@ -280,6 +280,17 @@ def test_decode_gemm_scale_alignment(K, shift):
     assert y_rel_err(npy(y1), ref["y"]) <= Y_TOL
 
 
+@pytest.mark.parametrize("M,N,norm", [(3, 40, True), (70, 24, False)])
+def test_maximum_k(M, N, norm):
+    """K = 32768, the largest the library takes (256 groups): front end with the whole fp32
+    row staged, decode kernel (M = 3) and few-tile kernel (M = 70) on the longest chains."""
+    _check_linear(_rand_linear(M, 32768, N, 128, seed=91 + M, norm=norm), f"K=32768 M={M}")
+    lin = _rand_linear(2, 32768 + 128, 8, 128, seed=5, norm=False)
+    with pytest.raises(atom.AtomError) as e:
+        atom.atom_quantize_act(dev(lin.x), None, 0.0, dev(lin.idx))
+    assert e.value.status == 3          # K above the limit: unsupported, nothing launched
+
+
 @pytest.mark.parametrize("which", [0, 1])
 def test_config2_llama7b_attention(which):
     _check_linear(synth.make(2, which), f"config2[{which}]", full_partials=(which == 0))
