@@ -144,7 +144,13 @@ atom_status atom_quantize_weight(const void *w_f16, int64_t N, int64_t ldw,
  * Mixed-precision group GEMM (Section 4.2, fused GEMM operator, steps 1-3):
  *   P[m, n, g] = sum over the 128 channels of group g of aq * wq   (int32)
  *   Y[m, n]    = fp16( sum_g float(P[m, n, g]) * a_scale[m, g] * w_scale[n, g] )
- * accumulated in fp32 over ascending g.
+ * accumulated in fp32: one fused multiply-add per group, over ascending g
+ * within a contiguous run of groups.  Large launches take all of K as one run;
+ * launches of few rows or few tiles split K into 2, 4 or 8 contiguous runs
+ * that are added in run order.  The order depends on the shape only, so
+ * results are deterministic; they differ from a single ascending chain by
+ * fp32 rounding (inside 1e-3 of the result's range).  The integer sums P are
+ * exact in every case.
  *
  *   a_q4 / a_q8 / a_scale   activation codes and scales for M rows
  *   w_q4 / w_q8 / w_scale   weight codes and scales for N rows
