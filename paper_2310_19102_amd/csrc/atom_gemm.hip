@@ -346,15 +346,18 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t stream)
 template <bool DBG>
 hipError_t dispatch(const GemmParams &p, hipStream_t stream)
 {
-    // M <= 64 streams the weights; but from 33 rows on, with many output channels, a tiled
-    // kernel is the faster one (measured at K = 4096: M = 64, N = 11008 42.8 us against 27.1 us
-    // on the big-tile kernel; at N = 4096 the streaming kernel wins, 10.3 against 26.4).
-    if (!DBG && p.M <= 64 && !(p.M > 32 && p.N >= 8192)) return launch_decode(p, stream);
+    // M <= 64 streams the weights; but from 33 rows on (four row blocks, one workgroup per CU)
+    // and more than 4096 output channels (more than one round of workgroups) a tiled kernel is
+    // the faster one.  Measured with the weights coming from HBM, K = 4096: M = 64, N = 5120
+    // 18.3 us streaming against 15.1 us tiled, N = 8192 19.1 against 15.5, N = 11008 27.5 against
+    // 19.7; at N = 4096 the streaming kernel wins, 10.2 against 14.4.
+    if (!DBG && p.M <= 64 && !(p.M > 32 && p.N > 4096)) return launch_decode(p, stream);
     // Launches of few tiles are bound by the latency of one tile's chain of K-steps: 64 x 64
     // tiles put every compute unit to work and four (or two) wavefront sets per workgroup split
     // that chain (M = 256, N = K = 4096: 25.7 us on 128 x 128 tiles with two sets).
     if constexpr (!DBG) {
         const int64_t t64 = ((p.M + 63) / 64) * ((p.N + 63) / 64);
+        if (t64 <= 128) return launch_tile<64, 32, 32, 32, false, 4>(p, stream);    // twice the tiles
         if (t64 <= 256) return launch_tile<64, 64, 32, 32, false, 4>(p, stream);
         if (t64 <= 512) return launch_tile<64, 64, 32, 32, false, 2>(p, stream);
     }
