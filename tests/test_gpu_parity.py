@@ -77,6 +77,7 @@ def test_config1_tiny():
     (130, 640, 136, 256, False),   # four sets on five groups (1, 1, 1, 2), two of them INT8, ragged tile edges
     (320, 1024, 3500, 128, True),  # 275 tiles of 64 x 64: two wavefront sets per workgroup
     (260, 512, 4200, 256, False),  # two sets, four groups: set 0 the INT4 pair, set 1 the INT8 pair
+    (5000, 256, 24, 128, True),    # tall and narrow: 79 row tiles of one partial 64 x 32 column tile
     (48, 384, 4200, 128, False),   # 33..64 rows, just over 4096 output channels: 64 x 32 tiles, ragged in M and N
     (48, 384, 8200, 128, False),   # 33..64 rows and many output channels: the big-tile kernel on one partial row tile
     (200, 4096, 300, 128, True),   # six tiles of the big-tile kernel at the Llama-7B K (33 K-steps, two wavefront sets)
