@@ -325,8 +325,7 @@ def decode_layer_measurements():
             _, *qa = atom.atom_add_quantize_act(x_in, res_in, gamma, 1e-5, idx_h, sum_out=bufs["h"])
             for name in ("q", "k", "v"):
                 atom.atom_w4a4_gemm(*qa, *lw[name], out=bufs[name])
-            atom.atom_kv_quantize(bufs["k"].view(B, H, D), cache=lw["kc"], pos=pos)
-            atom.atom_kv_quantize(bufs["v"].view(B, H, D), cache=lw["vc"], pos=pos)
+            atom.atom_kv_quantize_pair(bufs["k"].view(B, H, D), bufs["v"].view(B, H, D), lw["kc"], lw["vc"], pos)
             atom.atom_decode_attention_kv4(bufs["q"].view(B, H, D), lw["kc"], lw["vc"], seq_len, D ** -0.5,
                                            out=bufs["att"], workspace=ws)
             qo = atom.atom_quantize_act(bufs["att"].view(B, Hd), None, 0.0, idx_h)
@@ -345,7 +344,7 @@ def decode_layer_measurements():
         wbytes = sum(sum(t_.numel() * t_.element_size() for t_ in lw[name])
                      for lw in layers[:1] for name in ("q", "k", "v", "o", "gu", "down"))
         cbytes = 2 * B * H * T * (D // 2 + 4)
-        out.append({"workload": f"Llama-7B decoder layer at decode time, B={B}, {T} cached tokens, 13 launches per "
+        out.append({"workload": f"Llama-7B decoder layer at decode time, B={B}, {T} cached tokens, 12 launches per "
                                 f"layer, HIP graph over {n_layers} layers with their own weights and caches",
                     "us_per_layer": t * 1e6, "weight_bytes_per_layer": wbytes, "cache_bytes_per_layer": cbytes,
                     "GBs": (wbytes + cbytes) / t / 1e9, "hbm_frac": (wbytes + cbytes) / t / 1e9 / PEAK_HBM_GBS,

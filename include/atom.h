@@ -207,6 +207,21 @@ atom_status atom_kv_quantize(const void *x_f16, int64_t R, int64_t ldx,
                              void *scale_f16, void *zero_i16, void *stream);
 
 /*
+ * The K rows and the V rows of one step in one launch (Section 4.5: the
+ * quantisation of K and V sits behind the one operator that produces both):
+ * exactly atom_kv_quantize(k_f16, ..., k_q, k_scale, k_zero) followed by
+ * atom_kv_quantize(v_f16, ..., v_q, v_scale, v_zero), with R, ldx, D, clip,
+ * pos, rows_per_seq and Tmax shared.  Arguments, layouts, results and errors
+ * as there, for either tensor; the six outputs must not overlap.
+ */
+atom_status atom_kv_quantize_pair(const void *k_f16, const void *v_f16, int64_t R,
+                                  int64_t ldx, int32_t D, float clip,
+                                  const int32_t *pos, int32_t rows_per_seq,
+                                  int64_t Tmax, void *k_q, void *k_scale_f16,
+                                  void *k_zero_i16, void *v_q, void *v_scale_f16,
+                                  void *v_zero_i16, void *stream);
+
+/*
  * Decode-stage self-attention of one new token per sequence over the INT4 KV
  * cache (Section 4.4: the cache is loaded in 4 bits and dequantised inside the
  * attention operator, whose arithmetic stays in floating point; Section 4.5):

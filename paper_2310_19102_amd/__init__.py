@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     atom_mx_gemm,
     atom_calibrate_reorder,
     atom_kv_quantize,
+    atom_kv_quantize_pair,
     atom_decode_attention_kv4,
     atom_decode_attention_kv4_workspace_bytes,
     atom_status_string,

@@ -28,6 +28,7 @@ EXPORTS = (
     "atom_calibrate_reorder",
     "atom_calibrate_reorder_workspace_bytes",
     "atom_kv_quantize",
+    "atom_kv_quantize_pair",
     "atom_decode_attention_kv4",
     "atom_decode_attention_kv4_workspace_bytes",
     "atom_check_reorder_idx",
@@ -88,6 +89,8 @@ def load_library():
     L.atom_calibrate_reorder_workspace_bytes.argtypes = [i64, i32]
     L.atom_kv_quantize.restype = ctypes.c_int
     L.atom_kv_quantize.argtypes = [vp, i64, i64, i32, f32, vp, i32, i64, vp, vp, vp, vp]
+    L.atom_kv_quantize_pair.restype = ctypes.c_int
+    L.atom_kv_quantize_pair.argtypes = [vp, vp, i64, i64, i32, f32, vp, i32, i64, vp, vp, vp, vp, vp, vp, vp]
     L.atom_decode_attention_kv4.restype = ctypes.c_int
     L.atom_decode_attention_kv4.argtypes = [vp, i32, i32, i32, i32, i64, vp, vp, vp, vp, vp, vp, vp,
                                             f32, vp, vp, sz, vp]
@@ -335,6 +338,38 @@ def atom_kv_quantize(x: torch.Tensor, clip: float = 1.0,
     if st != 0:
         raise AtomError(st, "atom_kv_quantize")
     return codes, scale, zero
+
+
+def atom_kv_quantize_pair(k: torch.Tensor, v: torch.Tensor, k_cache: Tuple[torch.Tensor, ...],
+                          v_cache: Tuple[torch.Tensor, ...], pos: torch.Tensor, clip: float = 1.0):
+    """The new K and V rows of every sequence ([B, Hkv, D] fp16 each) appended in place to
+    their caches at position ``pos[b]`` in one launch; the same results as two
+    ``atom_kv_quantize`` calls.  Returns ``(k_cache, v_cache)``."""
+    L = load_library()
+    _dev(pos, torch.int32, "pos")
+    for x, cache, nm in ((k, k_cache, "k"), (v, v_cache, "v")):
+        _dev(x, torch.float16, nm)
+        codes, scale, zero = cache
+        _dev(codes, torch.uint8, nm + " cache codes")
+        _dev(scale, torch.float16, nm + " cache scale")
+        _dev(zero, torch.int16, nm + " cache zero")
+        if x.dim() != 3 or codes.dim() != 4 or not (x.is_contiguous() and codes.is_contiguous()
+                                                    and scale.is_contiguous() and zero.is_contiguous()):
+            raise ValueError(nm + " must be contiguous [B, Hkv, D] and its cache contiguous [B, Hkv, Tmax, ...]")
+    B, Hkv, Tmax = k_cache[0].shape[:3]
+    D = k.shape[-1]
+    for x, (codes, scale, zero) in ((k, k_cache), (v, v_cache)):
+        if (tuple(x.shape) != (B, Hkv, D) or tuple(codes.shape) != (B, Hkv, Tmax, D // 2)
+                or tuple(scale.shape) != (B, Hkv, Tmax) or tuple(zero.shape) != (B, Hkv, Tmax)):
+            raise ValueError("cache and row shapes disagree")
+    if tuple(pos.shape) != (B,) or not pos.is_contiguous():
+        raise ValueError("pos must be contiguous int32 [B]")
+    st = L.atom_kv_quantize_pair(_ptr(k), _ptr(v), B * Hkv, D, D, clip, _ptr(pos), Hkv, Tmax,
+                                 _ptr(k_cache[0]), _ptr(k_cache[1]), _ptr(k_cache[2]),
+                                 _ptr(v_cache[0]), _ptr(v_cache[1]), _ptr(v_cache[2]), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_kv_quantize_pair")
+    return k_cache, v_cache
 
 
 def atom_decode_attention_kv4(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...],

@@ -160,6 +160,29 @@ atom_status atom_kv_quantize(const void *x_f16, int64_t R, int64_t ldx, int32_t 
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
+atom_status atom_kv_quantize_pair(const void *k_f16, const void *v_f16, int64_t R, int64_t ldx,
+                                  int32_t D, float clip, const int32_t *pos, int32_t rows_per_seq,
+                                  int64_t Tmax, void *k_q, void *k_scale_f16, void *k_zero_i16,
+                                  void *v_q, void *v_scale_f16, void *v_zero_i16, void *stream)
+{
+    if (D != 64 && D != 128) return D > 0 && D % 2 == 0 ? ATOM_ERR_UNSUPPORTED : ATOM_ERR_SHAPE;
+    if (R < 0 || ldx < D) return ATOM_ERR_SHAPE;
+    if (pos && (rows_per_seq <= 0 || R % rows_per_seq || Tmax <= 0)) return ATOM_ERR_SHAPE;
+    if (R == 0) return ATOM_OK;
+    if (!k_f16 || !k_q || !k_scale_f16 || !k_zero_i16 || !v_f16 || !v_q || !v_scale_f16 || !v_zero_i16)
+        return ATOM_ERR_NULL;
+    if (!aligned(k_f16, 16) || !aligned(v_f16, 16) || (ldx % 8) || !aligned(k_q, 4) || !aligned(v_q, 4) ||
+        !aligned(k_scale_f16, 2) || !aligned(v_scale_f16, 2) || !aligned(k_zero_i16, 2) ||
+        !aligned(v_zero_i16, 2) || (pos && !aligned(pos, 4)))
+        return ATOM_ERR_ALIGN;
+    if (R * (D / 8) / 256 + 1 > 0x7fffffffLL) return ATOM_ERR_UNSUPPORTED;
+    hipError_t err = atom_internal::launch_kv_quantize(k_f16, R, ldx, D, clip, pos, rows_per_seq, Tmax,
+                                                       k_q, k_scale_f16, k_zero_i16,
+                                                       static_cast<hipStream_t>(stream), v_f16, v_q,
+                                                       v_scale_f16, v_zero_i16);
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
 atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H, int32_t Hkv,
                                       int32_t D, int64_t Tmax, const int32_t *seq_len,
                                       const void *k_codes, const void *k_scale, const void *k_zero,

@@ -51,7 +51,10 @@ hipError_t launch_calibrate_reorder(const void *x, int64_t T, int64_t ldx, int K
 // KV cache: asymmetric INT4 rows of D = 64 or 128 values; decode attention over the cache.
 hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, float clip,
                               const int32_t *pos, int32_t rows_per_seq, int64_t Tmax, void *q,
-                              void *scale, void *zero, hipStream_t stream);
+                              void *scale, void *zero, hipStream_t stream,
+                              // optional second tensor and cache, same rows and positions
+                              const void *x2 = nullptr, void *q2 = nullptr, void *scale2 = nullptr,
+                              void *zero2 = nullptr);
 hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int64_t Tmax,
                                        const int32_t *seq_len, const void *kq, const void *ks,
                                        const void *kz, const void *vq, const void *vs,

@@ -57,12 +57,20 @@ __device__ __forceinline__ void row_minmax(float &mx, float &mn)
 // append of a few hundred rows (there four rows per lane group only quarter the grid)
 template <int LPR, int kRows>
 __global__ __launch_bounds__(256)
-void kv_quantize_kernel(const __half *__restrict__ x, int64_t R, int64_t ldx, float clip,
+void kv_quantize_kernel(const __half *__restrict__ x0, int64_t R, int64_t ldx, float clip,
                         const int32_t *__restrict__ pos, int32_t rows_per_seq, int64_t Tmax,
-                        uint8_t *__restrict__ q, __half *__restrict__ scale,
-                        int16_t *__restrict__ zero)
+                        uint8_t *__restrict__ q0, __half *__restrict__ scale0,
+                        int16_t *__restrict__ zero0, const __half *__restrict__ x1,
+                        uint8_t *__restrict__ q1, __half *__restrict__ scale1,
+                        int16_t *__restrict__ zero1)
 {
     constexpr int D = 8 * LPR;
+    // grid.y = 2: the same rows of a second tensor into a second cache (K and V of one append)
+    const bool second = blockIdx.y != 0;
+    const __half *__restrict__ x     = second ? x1 : x0;
+    uint8_t      *__restrict__ q     = second ? q1 : q0;
+    __half       *__restrict__ scale = second ? scale1 : scale0;
+    int16_t      *__restrict__ zero  = second ? zero1 : zero0;
     const int64_t r0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
     const int64_t stride = (int64_t)gridDim.x * (256 / LPR);
     const int     j = threadIdx.x % LPR;
@@ -869,16 +877,18 @@ namespace atom_internal {
 
 hipError_t launch_kv_quantize(const void *x, int64_t R, int64_t ldx, int D, float clip,
                               const int32_t *pos, int32_t rows_per_seq, int64_t Tmax, void *q,
-                              void *scale, void *zero, hipStream_t stream)
+                              void *scale, void *zero, hipStream_t stream, const void *x2, void *q2,
+                              void *scale2, void *zero2)
 {
     const int     lpr  = D / 8;
     const bool    bulk = R >= 65536;                    // four rows per lane group
     const int64_t per  = (bulk ? 4 : 1) * (256 / lpr);  // rows per workgroup
     const int64_t grid = (R + per - 1) / per;
 #define ATOM_KVQ_LAUNCH(LPR, ROWS)                                                                    \
-    hipLaunchKernelGGL((kv_quantize_kernel<LPR, ROWS>), dim3((unsigned)grid), dim3(256), 0, stream,   \
-                       (const __half *)x, R, ldx, clip, pos, rows_per_seq, Tmax, (uint8_t *)q,        \
-                       (__half *)scale, (int16_t *)zero)
+    hipLaunchKernelGGL((kv_quantize_kernel<LPR, ROWS>), dim3((unsigned)grid, x2 ? 2 : 1), dim3(256),  \
+                       0, stream, (const __half *)x, R, ldx, clip, pos, rows_per_seq, Tmax,           \
+                       (uint8_t *)q, (__half *)scale, (int16_t *)zero, (const __half *)x2,            \
+                       (uint8_t *)q2, (__half *)scale2, (int16_t *)zero2)
     if (D == 128) { if (bulk) ATOM_KVQ_LAUNCH(16, 4); else ATOM_KVQ_LAUNCH(16, 1); }
     else          { if (bulk) ATOM_KVQ_LAUNCH(8, 4);  else ATOM_KVQ_LAUNCH(8, 1); }
 #undef ATOM_KVQ_LAUNCH

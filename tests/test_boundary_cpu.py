@@ -100,6 +100,13 @@ def test_host_side_validation_of_the_kv_cache_and_mx_entry_points():
     assert kvq(p, 4, 128, 128, 1.0, p, 4, 0, p, p, p, None) == 2                # Tmax
     assert kvq(p, 0, 128, 128, 1.0, None, 0, 0, p, p, p, None) == 0
     assert kvq(ctypes.c_void_p(0x1002), 4, 128, 128, 1.0, None, 0, 0, p, p, p, None) == 4
+    kvp = lib.atom_kv_quantize_pair
+    assert kvp(p, None, 4, 128, 128, 1.0, p, 4, 16, p, p, p, p, p, p, None) == 1   # no V rows
+    assert kvp(p, p, 4, 128, 128, 1.0, p, 4, 16, p, p, p, p, p, None, None) == 1   # no V zero points
+    assert kvp(p, p, 4, 128, 96, 1.0, p, 4, 16, p, p, p, p, p, p, None) == 3
+    assert kvp(p, p, 5, 128, 128, 1.0, p, 4, 16, p, p, p, p, p, p, None) == 2
+    assert kvp(p, ctypes.c_void_p(0x1002), 4, 128, 128, 1.0, p, 4, 16, p, p, p, p, p, p, None) == 4
+    assert kvp(p, p, 0, 128, 128, 1.0, p, 4, 16, p, p, p, p, p, p, None) == 0
     att = lib.atom_decode_attention_kv4
     base = [p, 2, 8, 4, 128, 64, p, p, p, p, p, p, p, 1.0, p]
     assert att(*base[:2], 6, *base[3:], None, 0, None) == 2                     # H % Hkv

@@ -111,6 +111,36 @@ def test_kv_append_in_place():
     _quant_equal(cache, want, "append")
 
 
+@pytest.mark.parametrize("D", [128, 64])
+def test_kv_append_pair(D):
+    """K and V rows appended by one launch: both caches equal what the oracle gives for the new
+    rows at pos[b] (bit-exact), the rest of either cache is untouched, an out-of-range position
+    writes nothing."""
+    B, Hkv, Tmax = 5, 3, 37
+    g = torch.Generator().manual_seed(23 + D)
+    old_k = torch.randn((B, Hkv, Tmax, D), generator=g).to(torch.float16)
+    old_v = (0.5 * torch.randn((B, Hkv, Tmax, D), generator=g) + 0.25).to(torch.float16)
+    kc = tuple(t.clone() for t in atom.atom_kv_quantize(old_k.cuda(), 1.0))
+    vc = tuple(t.clone() for t in atom.atom_kv_quantize(old_v.cuda(), 1.0))
+    want_k = tuple(_npy(t).copy() for t in kc)
+    want_v = tuple(_npy(t).copy() for t in vc)
+    new_k = torch.randn((B, Hkv, D), generator=g).to(torch.float16)
+    new_v = (3.0 * torch.randn((B, Hkv, D), generator=g) - 1.0).to(torch.float16)
+    pos = torch.tensor([0, 36, 17, 37, -1], dtype=torch.int32)    # the last two are out of range
+    atom.atom_kv_quantize_pair(new_k.cuda(), new_v.cuda(), kc, vc, pos.cuda(), 0.95)
+    torch.cuda.synchronize()
+    ref_k = oracle.kv_quantize(new_k.numpy(), 0.95)
+    ref_v = oracle.kv_quantize(new_v.numpy(), 0.95)
+    for b in range(3):
+        for i in range(3):
+            want_k[i][b, :, int(pos[b])] = ref_k[i][b]
+            want_v[i][b, :, int(pos[b])] = ref_v[i][b]
+    _quant_equal(kc, want_k, "pair append K")
+    _quant_equal(vc, want_v, "pair append V")
+    with pytest.raises(ValueError):
+        atom.atom_kv_quantize_pair(new_k.cuda(), new_v[:, :2].contiguous().cuda(), kc, vc, pos.cuda())
+
+
 def test_kv_quantize_errors():
     x = torch.zeros((4, 128), dtype=torch.float16, device="cuda")
     with pytest.raises(atom.AtomError) as e:
