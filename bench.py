@@ -400,6 +400,7 @@ def kv_cache_measurements():
             atom.atom_kv_quantize(new, cache=kc, pos=pos)
             atom.atom_kv_quantize(new, cache=vc, pos=pos)
         entry["append_k_and_v_us"] = graph_time(append, 20, 5) * 1e6
+        entry["append_pair_us"] = graph_time(lambda: atom.atom_kv_quantize_pair(new, new, kc, vc, pos), 20, 5) * 1e6
         out.append(entry)
         del kc, vc, ws
         torch.cuda.empty_cache()
