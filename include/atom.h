@@ -174,6 +174,44 @@ size_t atom_w4a4_gemm_workspace_bytes(int64_t M, int64_t N,
                                       const atom_desc *d);
 
 /*
+ * The same GEMM on weights in an opaque tiled layout (Section 4.1: the weights
+ * are prepared once, offline; Section 4.2 for the arithmetic, which is that of
+ * atom_w4a4_gemm).  atom_pack_weight turns canonical (w_q4, w_q8, w_scale) into
+ * the layout the compute-bound kernel streams without any address arithmetic:
+ * tiles of 64 rows, group by group, every INT4 code re-encoded as the FP6
+ * (E3M2) number of the same integer value -- every integer in [-8, 8] is one,
+ * so nothing is re-quantised -- which lets the group sums run on the FP6
+ * matrix instruction at twice the INT8 rate; its fp32 accumulation of these
+ * integers is exact, so P[m, n, g] is the same integer as above.  INT8 groups
+ * and scales are carried as they are.  The packed bytes are a bijection of the
+ * canonical arrays (plus zero rows up to a multiple of 64); the canonical
+ * layouts stay what parity is judged on.
+ *
+ *   atom_pack_weight_bytes(N, d)   size of the packed buffer (0 on bad d or N)
+ *   w_packed      device, 256-byte aligned, packed_bytes >= that size
+ * atom_w4a4_gemm_packed: activations canonical as atom_quantize_act writes
+ * them; they are re-tiled into `workspace` first (one extra launch), which must
+ * hold atom_w4a4_gemm_packed_workspace_bytes(M, N, d) bytes, 256-byte aligned.
+ * Y is accumulated over ascending g in one chain of fused multiply-adds, the
+ * INT8 groups last: the definition's order.  partials_dbg as in atom_w4a4_gemm.
+ * Any M is accepted; the kernel is meant for M > 64.
+ * Errors: as atom_w4a4_gemm, and ATOM_ERR_UNSUPPORTED beyond 65535 * 64 rows
+ * of either operand; ATOM_ERR_WORKSPACE when w_packed or workspace is too small.
+ */
+size_t atom_pack_weight_bytes(int64_t N, const atom_desc *d);
+atom_status atom_pack_weight(const void *w_q4, const void *w_q8,
+                             const void *w_scale, int64_t N, const atom_desc *d,
+                             void *w_packed, size_t packed_bytes, void *stream);
+size_t atom_w4a4_gemm_packed_workspace_bytes(int64_t M, int64_t N,
+                                             const atom_desc *d);
+atom_status atom_w4a4_gemm_packed(const void *a_q4, const void *a_q8,
+                                  const void *a_scale, int64_t M,
+                                  const void *w_packed, int64_t N,
+                                  const atom_desc *d, void *y_f16, int64_t ldy,
+                                  int32_t *partials_dbg, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
+/*
  * KV-cache quantisation (Section 2, asymmetric uniform quantisation; Section
  * 4.4: one scale and zero point per attention head, 4 bits; Section 4.5: fused
  * into the operator that produces K and V, here a kernel of its own that the

@@ -24,6 +24,9 @@ from .binding import (  # noqa: F401
     atom_status_string,
     atom_w4a4_gemm,
     atom_w4a4_gemm_workspace_bytes,
+    atom_pack_weight,
+    atom_w4a4_gemm_packed,
+    atom_w4a4_gemm_packed_workspace_bytes,
     library_path,
     load_library,
 )

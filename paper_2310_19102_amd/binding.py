@@ -22,6 +22,10 @@ EXPORTS = (
     "atom_quantize_weight",
     "atom_w4a4_gemm",
     "atom_w4a4_gemm_workspace_bytes",
+    "atom_pack_weight_bytes",
+    "atom_pack_weight",
+    "atom_w4a4_gemm_packed_workspace_bytes",
+    "atom_w4a4_gemm_packed",
     "atom_mx_quantize_act",
     "atom_mx_quantize_weight",
     "atom_mx_gemm",
@@ -76,6 +80,14 @@ def load_library():
     L.atom_w4a4_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, dp, vp, i64, vp, vp, sz, vp]
     L.atom_w4a4_gemm_workspace_bytes.restype = sz
     L.atom_w4a4_gemm_workspace_bytes.argtypes = [i64, i64, dp]
+    L.atom_pack_weight_bytes.restype = sz
+    L.atom_pack_weight_bytes.argtypes = [i64, dp]
+    L.atom_pack_weight.restype = ctypes.c_int
+    L.atom_pack_weight.argtypes = [vp, vp, vp, i64, dp, vp, sz, vp]
+    L.atom_w4a4_gemm_packed_workspace_bytes.restype = sz
+    L.atom_w4a4_gemm_packed_workspace_bytes.argtypes = [i64, i64, dp]
+    L.atom_w4a4_gemm_packed.restype = ctypes.c_int
+    L.atom_w4a4_gemm_packed.argtypes = [vp, vp, vp, i64, vp, i64, dp, vp, i64, vp, vp, sz, vp]
     i32 = ctypes.c_int32
     L.atom_mx_quantize_act.restype = ctypes.c_int
     L.atom_mx_quantize_act.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, vp, vp, vp]
@@ -288,6 +300,68 @@ def atom_w4a4_gemm(a_q4, a_q8, a_scale, w_q4, w_q8, w_scale, group_size: int = 1
     return out
 
 
+def atom_pack_weight(w_q4, w_q8, w_scale, group_size: int = 128, out: Optional[torch.Tensor] = None):
+    """Canonical weight codes and scales -> the opaque tiled layout of ``atom_w4a4_gemm_packed``
+    (a uint8 device tensor)."""
+    L = load_library()
+    for t, dt, nm in ((w_q4, torch.uint8, "w_q4"), (w_q8, torch.int8, "w_q8"), (w_scale, torch.float16, "w_scale")):
+        _dev(t, dt, nm)
+        if not t.is_contiguous():
+            raise ValueError(f"{nm} must be contiguous")
+    N, O = w_q8.shape
+    K = w_q4.shape[1] * 2 + O
+    d = _desc(K, group_size, n_outlier=O)
+    need = int(L.atom_pack_weight_bytes(N, ctypes.byref(d)))
+    if out is None:
+        out = torch.empty(max(need, 1), dtype=torch.uint8, device=w_q4.device)
+    _dev(out, torch.uint8, "out")
+    st = L.atom_pack_weight(_ptr(w_q4), _ptr(w_q8), _ptr(w_scale), N, ctypes.byref(d), _ptr(out),
+                            out.numel(), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_pack_weight")
+    return out
+
+
+def atom_w4a4_gemm_packed_workspace_bytes(M: int, N: int, K: int, group_size: int = 128,
+                                          n_outlier: int = 128) -> int:
+    d = _desc(K, group_size, n_outlier)
+    return int(load_library().atom_w4a4_gemm_packed_workspace_bytes(M, N, ctypes.byref(d)))
+
+
+def atom_w4a4_gemm_packed(a_q4, a_q8, a_scale, w_packed, N: int, group_size: int = 128,
+                          out: Optional[torch.Tensor] = None, partials: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None):
+    """``atom_w4a4_gemm`` against weights packed by ``atom_pack_weight``."""
+    L = load_library()
+    for t, dt, nm in ((a_q4, torch.uint8, "a_q4"), (a_q8, torch.int8, "a_q8"),
+                      (a_scale, torch.float16, "a_scale"), (w_packed, torch.uint8, "w_packed")):
+        _dev(t, dt, nm)
+        if not t.is_contiguous():
+            raise ValueError(f"{nm} must be contiguous")
+    M, O = a_q8.shape
+    K = a_q4.shape[1] * 2 + O
+    d = _desc(K, group_size, n_outlier=O)
+    if w_packed.numel() < int(L.atom_pack_weight_bytes(N, ctypes.byref(d))):
+        raise ValueError("w_packed is smaller than atom_pack_weight_bytes(N)")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=a_q4.device)
+    _dev(out, torch.float16, "out")
+    if partials is not None:
+        _dev(partials, torch.int32, "partials")
+        if tuple(partials.shape) != (M, N, K // group_size) or not partials.is_contiguous():
+            raise ValueError("partials must be contiguous int32 [M, N, G]")
+    need = int(L.atom_w4a4_gemm_packed_workspace_bytes(M, N, ctypes.byref(d)))
+    if workspace is None or workspace.numel() * workspace.element_size() < need:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=a_q4.device)
+    st = L.atom_w4a4_gemm_packed(_ptr(a_q4), _ptr(a_q8), _ptr(a_scale), M, _ptr(w_packed), N,
+                                 ctypes.byref(d), _ptr(out), out.stride(0) if M > 1 else max(N, out.stride(0)),
+                                 _ptr(partials), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _stream())
+    if st != 0:
+        raise AtomError(st, "atom_w4a4_gemm_packed")
+    return out
+
+
 def atom_decode_attention_kv4_workspace_bytes(B: int, H: int, Hkv: int, D: int, Tmax: int) -> int:
     return int(load_library().atom_decode_attention_kv4_workspace_bytes(B, H, Hkv, D, Tmax))
 
@@ -372,14 +446,7 @@ def atom_kv_quantize_pair(k: torch.Tensor, v: torch.Tensor, k_cache: Tuple[torch
     return k_cache, v_cache
 
 
-def atom_decode_attention_kv4(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...],
-                              v_cache: Tuple[torch.Tensor, ...], seq_len: torch.Tensor,
-                              sm_scale: float, out: Optional[torch.Tensor] = None,
-                              workspace: Optional[torch.Tensor] = None):
-    """Attention of one query token per sequence over the INT4 cache.  ``q`` [B, H, D] fp16;
-    each cache is ``(codes [B, Hkv, Tmax, D/2] uint8, scale [B, Hkv, Tmax] fp16,
-    zero [B, Hkv, Tmax] int16)``; ``seq_len`` device int32 [B].  Returns [B, H, D] fp16."""
-    L = load_library()
+def _attention_args(q, k_cache, v_cache, seq_len, out):
     _dev(q, torch.float16, "q")
     _dev(seq_len, torch.int32, "seq_len")
     if q.dim() != 3 or not q.is_contiguous():
@@ -405,6 +472,20 @@ def atom_decode_attention_kv4(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...]
     _dev(out, torch.float16, "out")
     if tuple(out.shape) != (B, H, D) or not out.is_contiguous():
         raise ValueError("out must be contiguous [B, H, D]")
+    return B, H, Hkv, D, Tmax, out
+
+
+def atom_decode_attention_kv4(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...],
+                              v_cache: Tuple[torch.Tensor, ...], seq_len: torch.Tensor,
+                              sm_scale: float, out: Optional[torch.Tensor] = None,
+                              workspace: Optional[torch.Tensor] = None):
+    """Attention of one query token per sequence over the INT4 cache.  ``q`` [B, H, D] fp16;
+    each cache is ``(codes [B, Hkv, Tmax, D/2] uint8, scale [B, Hkv, Tmax] fp16,
+    zero [B, Hkv, Tmax] int16)``; ``seq_len`` device int32 [B].  Returns [B, H, D] fp16."""
+    L = load_library()
+    B, H, Hkv, D, Tmax, out = _attention_args(q, k_cache, v_cache, seq_len, out)
+    kq, ks, kz = k_cache
+    vq, vs, vz = v_cache
     need = int(L.atom_decode_attention_kv4_workspace_bytes(B, H, Hkv, D, Tmax))
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)

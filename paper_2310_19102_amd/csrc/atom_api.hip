@@ -141,6 +141,62 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8, const void *a_sca
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
+size_t atom_pack_weight_bytes(int64_t N, const atom_desc *d)
+{
+    if (check_desc(d) != ATOM_OK || N <= 0) return 0;
+    return atom_internal::f6_packed_bytes(N, d->K, d->n_outlier);
+}
+
+atom_status atom_pack_weight(const void *w_q4, const void *w_q8, const void *w_scale, int64_t N,
+                             const atom_desc *d, void *w_packed, size_t packed_bytes, void *stream)
+{
+    atom_status st = check_desc(d);
+    if (st != ATOM_OK) return st;
+    if (N < 0) return ATOM_ERR_SHAPE;
+    if (N == 0) return ATOM_OK;
+    if (!w_q4 || !w_q8 || !w_scale || !w_packed) return ATOM_ERR_NULL;
+    if (!aligned(w_q4, 16) || !aligned(w_q8, 16) || !aligned(w_scale, 2) || !aligned(w_packed, 256))
+        return ATOM_ERR_ALIGN;
+    if ((N + 63) / 64 > 65535) return ATOM_ERR_UNSUPPORTED;          // one grid row per 64 rows
+    if (packed_bytes < atom_internal::f6_packed_bytes(N, d->K, d->n_outlier)) return ATOM_ERR_WORKSPACE;
+    hipError_t err = atom_internal::launch_f6_pack(w_q4, w_q8, w_scale, N, d->K, d->n_outlier, w_packed,
+                                                   static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
+size_t atom_w4a4_gemm_packed_workspace_bytes(int64_t M, int64_t N, const atom_desc *d)
+{
+    (void)N;
+    if (check_desc(d) != ATOM_OK || M <= 0) return 0;
+    return atom_internal::f6_packed_bytes(M, d->K, d->n_outlier);
+}
+
+atom_status atom_w4a4_gemm_packed(const void *a_q4, const void *a_q8, const void *a_scale, int64_t M,
+                                  const void *w_packed, int64_t N, const atom_desc *d, void *y_f16,
+                                  int64_t ldy, int32_t *partials_dbg, void *workspace,
+                                  size_t workspace_bytes, void *stream)
+{
+    atom_status st = check_desc(d);
+    if (st != ATOM_OK) return st;
+    if (M < 0 || N < 0 || ldy < N) return ATOM_ERR_SHAPE;
+    if (M == 0 || N == 0) return ATOM_OK;
+    if (!a_q4 || !a_q8 || !a_scale || !w_packed || !y_f16) return ATOM_ERR_NULL;
+    if (!aligned(a_q4, 16) || !aligned(a_q8, 16) || !aligned(a_scale, 2) || !aligned(w_packed, 256) ||
+        !aligned(y_f16, 2) || (partials_dbg && !aligned(partials_dbg, 4)))
+        return ATOM_ERR_ALIGN;
+    const int64_t mu = (M + 63) / 64, nu = (N + 63) / 64;
+    if (mu > 65535 || mu * ((nu + 1) / 2) > 0x7fffffffLL) return ATOM_ERR_UNSUPPORTED;
+    const size_t need = atom_internal::f6_packed_bytes(M, d->K, d->n_outlier);
+    if (!workspace || workspace_bytes < need) return ATOM_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return ATOM_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t err = atom_internal::launch_f6_pack(a_q4, a_q8, a_scale, M, d->K, d->n_outlier, workspace, s);
+    if (err != hipSuccess) return ATOM_ERR_HIP;
+    err = atom_internal::launch_f6_gemm(workspace, M, w_packed, N, d->K, d->n_outlier, y_f16, ldy,
+                                        partials_dbg, s);
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
 atom_status atom_kv_quantize(const void *x_f16, int64_t R, int64_t ldx, int32_t D, float clip,
                              const int32_t *pos, int32_t rows_per_seq, int64_t Tmax, void *q,
                              void *scale_f16, void *zero_i16, void *stream)

@@ -1,0 +1,581 @@
+// Group GEMM on pre-tiled operands with the INT4 groups carried in FP6 (Section 4.2 of the
+// paper, steps 1-3; the arithmetic is that of atom_gemm.hip).
+//
+// gfx950 has no INT4 matrix instruction, and on the INT8 one a 4-bit code costs as much as an
+// 8-bit code.  It does have v_mfma_f32_32x32x64_f8f6f4, which runs FP6 operands at twice the INT8
+// rate, and the E3M2 variant of FP6 represents every integer in [-8, 8] exactly.  An INT4 code is
+// therefore re-encoded (not re-quantised) as the E3M2 number of the same value; the products of a
+// group are integers of at most 7 bits, their sum over the 128 channels of a group is below 2^14,
+// and the instruction's fp32 accumulation of such values is exact (checked on the hardware against
+// integer sums, with accumulator inputs up to 2^23).  So the fp32 result tile IS the group's
+// integer partial sum P[m, n, g], and step 2 needs no integer-to-float conversion: one fused
+// multiply-add per element and group against the tile of scale products.  The 128 outlier channels
+// stay INT8 on the INT8 MFMA.
+//
+// Operands come in an opaque tiled layout (pack_rows_kernel below writes it, from the canonical
+// q4 / q8 / scale arrays; weights once, offline; activations per call into the workspace).  A
+// "unit" is 64 rows; for every unit the images of its groups follow each other, each image being
+// byte for byte what one LDS stage holds for that unit and group, so the K loop's loader is a
+// linear copy global -> LDS by global_load_lds_dwordx4 (no registers, no address arithmetic, whole
+// cache lines).
+//   INT4 group image, 6400 bytes: a lane of the MFMA holds 32 consecutive channels of a row = 24
+//     bytes of FP6 ("piece" p = 0..3 of the row's group).  Bytes 0-15 of piece p of row r sit at
+//     64 r + 16 ((p + r/4) % 4), bytes 16-23 at 4096 + 32 r + 8 ((p + r/8) % 4) (rotations: the
+//     128-bit and 64-bit fragment reads of 32 consecutive rows are bank-conflict free), the fp16
+//     scale of row r, zero-extended to 32 bits, at 6144 + 4 r.
+//   INT8 group image, 8448 bytes: 16-byte chunk c of row r at 128 r + 16 ((c ^ r ^ (r/8 % 2)) % 8),
+//     scale at 8192 + 4 r.
+// Rows past the end of the matrix hold zero codes and zero scales.
+//
+// Kernel: 256 x 128 (or 128 x 128, 64 x 128) tile, wavefront tile 64 x 64 = four 32 x 32 sub-tiles,
+// NST LDS stages.  Per INT4 group and sub-tile: two FP6 MFMAs (64 channels each) and one fp16 MFMA
+// that forms the 32 x 32 tile of scale products a_scale[m] * w_scale[n] (rank 1, exact in fp32),
+// then 16 fused multiply-adds per lane.  Groups are added in ascending order, the INT8 group(s)
+// last, each by one fmaf: the accumulation chain of the definition.
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "atom_gemm_common.h"
+#include "atom_internal.h"
+
+namespace {
+
+using namespace atom_gemm;
+
+typedef int      v8i  __attribute__((ext_vector_type(8)));
+typedef int      v6i  __attribute__((ext_vector_type(6)));
+typedef unsigned v6u  __attribute__((ext_vector_type(6)));
+typedef unsigned v2u  __attribute__((ext_vector_type(2)));
+typedef unsigned v4u  __attribute__((ext_vector_type(4)));
+typedef float    v16f __attribute__((ext_vector_type(16)));
+typedef _Float16 v32h __attribute__((ext_vector_type(32)));
+typedef _Float16 v4h  __attribute__((ext_vector_type(4)));
+
+constexpr int IMG4 = 6400;                // bytes of an INT4 group image of one unit
+constexpr int IMG8 = 8448;                // bytes of an INT8 group image of one unit
+constexpr int SC4  = 6144;                // offset of the scales inside an INT4 image
+constexpr int SC8  = 8192;
+
+__host__ __device__ constexpr int round_kb(int x) { return (x + 1023) / 1024 * 1024; }
+
+// ------------------------------------------------------------------------------------------
+// Packing: canonical rows -> unit images.  One thread per 16-byte destination chunk.
+// ------------------------------------------------------------------------------------------
+struct PackParams {
+    const uint8_t *q4; const int8_t *q8; const uint16_t *scale;
+    uint8_t *out;
+    int64_t rows;                         // valid rows
+    int     units, G4, G8, O;
+    int64_t ustride;                      // bytes per unit = G4 * IMG4 + G8 * IMG8
+};
+
+__global__ __launch_bounds__(256)
+void pack_rows_kernel(const PackParams p)
+{
+    const int     G    = p.G4 + p.G8;
+    const int64_t K4h  = (int64_t)p.G4 * 64;          // bytes of a canonical q4 row
+    const int     unit = blockIdx.y;
+    const int     g    = blockIdx.x;                   // group; INT4 groups first
+    uint8_t *img = p.out + (int64_t)unit * p.ustride + (g < p.G4 ? (int64_t)g * IMG4 : (int64_t)p.G4 * IMG4 + (int64_t)(g - p.G4) * IMG8);
+    const int t = threadIdx.x;
+    if (g < p.G4) {
+        // chunk t of the 16-byte region: row t / 4, slot t % 4 holds piece (slot - row / 4) % 4
+        const int row = t >> 2, slot = t & 3, piece = (slot - (row >> 2)) & 3;
+        const int64_t m = (int64_t)unit * 64 + row;
+        v6u packed = {0u, 0u, 0u, 0u, 0u, 0u};
+        uint32_t sbits = 0;
+        if (m < p.rows) {
+            const v4u w = *reinterpret_cast<const v4u *>(p.q4 + m * K4h + (int64_t)g * 64 + piece * 16);
+            v32h h;
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    h[8 * d + k] = (_Float16)(((int)(w[d] << (28 - 4 * k))) >> 28);   // sign-extended nibble k
+            // the E3M2 number of each code (scale 1: a plain conversion; every code is representable)
+            packed = __builtin_amdgcn_cvt_scalef32_pk32_bf6_f16(h, 1.0f);
+            sbits = p.scale[m * G + g];
+        }
+        *reinterpret_cast<v4u *>(img + 16 * t) = v4u{packed[0], packed[1], packed[2], packed[3]};
+        *reinterpret_cast<v2u *>(img + 4096 + 32 * row + 8 * ((piece + (row >> 3)) & 3)) = v2u{packed[4], packed[5]};
+        if (slot == 0) *reinterpret_cast<uint32_t *>(img + SC4 + 4 * row) = sbits;
+    } else {
+        // two chunks per thread: chunk ids t and t + 256 of the 512; row id / 8, slot id % 8
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int id = t + 256 * half, row = id >> 3, slot = id & 7;
+            const int chunk = (slot ^ row ^ ((row >> 3) & 1)) & 7;
+            const int64_t m = (int64_t)unit * 64 + row;
+            v4u w = {0u, 0u, 0u, 0u};
+            uint32_t sbits = 0;
+            if (m < p.rows) {
+                w = *reinterpret_cast<const v4u *>(p.q8 + m * p.O + (int64_t)(g - p.G4) * 128 + chunk * 16);
+                sbits = p.scale[m * G + g];
+            }
+            *reinterpret_cast<v4u *>(img + 16 * id) = w;
+            if (slot == 0) *reinterpret_cast<uint32_t *>(img + SC8 + 4 * row) = sbits;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// The GEMM
+// ------------------------------------------------------------------------------------------
+struct F6Params {
+    const uint8_t *a_pk, *w_pk;           // unit images of the activations / weights
+    uint16_t *y; int32_t *partials;
+    int64_t M, N, ldy;
+    int     a_units, w_units, G4, G8;
+    int64_t ustride;
+};
+
+__device__ __forceinline__ void dma16(uint32_t lds, uint32_t voff, const uint8_t *sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+
+// s_waitcnt immediate: vmcnt(n), lgkmcnt(0), expcnt untouched
+__host__ __device__ constexpr int wait_imm(int n) { return (n & 15) | (7 << 4) | (0 << 8) | ((n >> 4) << 14); }
+
+__device__ __forceinline__ v16f mfma_f6(v6i a, v6i b, v16f c)
+{
+    // cbsz = blgp = 3: both operands E3M2 (six registers each); scale bytes 127 = 2^0
+    const v8i a8 = __builtin_shufflevector(a, a, 0, 1, 2, 3, 4, 5, -1, -1);
+    const v8i b8 = __builtin_shufflevector(b, b, 0, 1, 2, 3, 4, 5, -1, -1);
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 3, 3, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+}
+
+// Order control.  MFMAs and fused multiply-adds have no side effects, so instruction selection
+// is free to let them drift towards their consumers, which bunches each MFMA with the
+// multiply-adds that wait for it.  An empty volatile asm that takes a value as an in/out operand
+// is ordered with the other volatile statements and with the scheduling fences: whatever produces
+// the value stays above it, whatever consumes it stays below.
+#define ATOM_F6_PIN(x) asm volatile("" : "+v"(x))
+#define ATOM_F6_SLOT_END()                         \
+    do {                                           \
+        asm volatile("" ::: "memory");             \
+        __builtin_amdgcn_sched_barrier(0);         \
+    } while (0)
+
+template <int WM>
+struct F6Geom {
+    static constexpr int NWAVE = WM * 2;
+    static constexpr int NT    = NWAVE * 64;
+    static constexpr int NST   = WM == 4 ? 4 : 3;                 // LDS stages
+    static constexpr int APART = round_kb(WM * IMG4);              // activation units of a stage (padded to whole DMA instructions)
+    static constexpr int STAGE = APART + round_kb(2 * IMG4);
+    static constexpr int NA    = APART / 1024, NI = STAGE / 1024; // DMA instructions per stage: NA for activations
+    static constexpr int LPW   = (NI + NWAVE - 1) / NWAVE;        // at most, per wavefront
+    static constexpr int APART8 = round_kb(WM * IMG8);
+    static constexpr int STAGE8 = APART8 + round_kb(2 * IMG8);
+    static constexpr int NA8   = APART8 / 1024, NI8 = STAGE8 / 1024;
+    static constexpr int LPW8  = (NI8 + NWAVE - 1) / NWAVE;
+    static constexpr int OSTRIDE = 144;                            // output staging: bytes per row of a wavefront's 64 x 64 fp16 tile
+    static constexpr int OUT   = NWAVE * 64 * OSTRIDE;
+    static constexpr int SPARE = NST * STAGE;                      // a kilobyte that is written and never read
+    static constexpr int LDS0  = NST * STAGE + 1024 > STAGE8 ? NST * STAGE + 1024 : STAGE8;
+    static constexpr int LDS   = LDS0 > OUT ? LDS0 : OUT;
+};
+
+template <int WM, bool DBG>
+__global__ __launch_bounds__(WM * 128, 2)
+void w4a4_gemm_f6_kernel(const F6Params p)
+{
+    using Gm = F6Geom<WM>;
+    constexpr int NWAVE = Gm::NWAVE, NST = Gm::NST, STAGE = Gm::STAGE, APART = Gm::APART;
+    constexpr int NA = Gm::NA, NI = Gm::NI, LPW = Gm::LPW;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int tid  = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;
+    const int r = lane & 31, g = lane >> 5;
+
+    // tile of this workgroup: M-tiles fastest, in bands of up to eight M-tiles so that the tiles an
+    // XCD works on at one time share both activation and weight units in its L2
+    const int TM = (p.a_units + WM - 1) / WM, TN = (p.w_units + 1) / 2;
+    int tm, tn;
+    {
+        const int logical = xcd_contiguous_block_id();
+        const int band = 8 * TN, b = logical / band, rem = logical - b * band;
+        const int hgt = TM - 8 * b < 8 ? TM - 8 * b : 8;          // M-tiles in this band
+        tm = 8 * b + rem % hgt;
+        tn = rem / hgt;
+    }
+    const int au0 = tm * WM, wu0 = tn * 2;
+    const int a_valid = p.a_units - au0 < WM ? p.a_units - au0 : WM;
+    const int w_valid = p.w_units - wu0 < 2 ? p.w_units - wu0 : 2;
+    const uint8_t *a_tile = p.a_pk + (int64_t)au0 * p.ustride;
+    const uint8_t *w_tile = p.w_pk + (int64_t)wu0 * p.ustride;
+
+    // ---- loader: DMA instruction j of a stage fills LDS bytes [1024 j, 1024 j + 1024) of the
+    // stage; j < NA: activation units, else weight units.  Wavefront w issues j = w, w + NWAVE, ...
+    // Lanes past the end of a part repeat its last chunk (they land in the padding).
+    // Every wavefront issues LPW instructions per stage, so that the waits below are the same
+    // immediate in every wavefront and no branch sits inside a K-step: a wavefront without an
+    // LPW-th block repeats its first block into a spare kilobyte that nobody reads.
+    uint32_t voff[LPW];
+#pragma unroll
+    for (int k = 0; k < LPW; ++k) {
+        const int j0 = wave + NWAVE * k, j = j0 < NI ? j0 : wave;
+        const bool isa = j < NA;
+        int q = 64 * (isa ? j : j - NA) + lane;                   // 16-byte chunk within the part
+        const int nq = (isa ? WM : 2) * (IMG4 / 16);
+        q = q < nq ? q : nq - 1;
+        int unit = q / (IMG4 / 16);
+        const int off = q - unit * (IMG4 / 16);
+        const int valid = isa ? a_valid : w_valid;
+        unit = unit < valid ? unit : valid - 1;                   // ragged tiles repeat their last unit
+        voff[k] = (uint32_t)unit * (uint32_t)p.ustride + 16u * off;
+    }
+    const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem);
+    // Group v into stage `stage`.  Past the last INT4 group (`real` false) the same number of
+    // instructions is issued, so that the count a wait refers to never changes: every lane then
+    // reads the first 16 bytes of the tile (one cache line per instruction) into the spare kilobyte.
+    auto request = [&](int v, int stage, bool real) __attribute__((always_inline)) {
+        // (selected with masks, not with ?: -- the compiler turned those into branches)
+        const uint32_t m = 0u - (uint32_t)real;                    // all ones, or zero
+        const uint32_t st = lds0 + stage * STAGE, spare = lds0 + Gm::SPARE;
+        const uint64_t goff = (uint64_t)((uint32_t)v * (uint32_t)IMG4 & m);
+        const uint8_t *ab = a_tile + goff, *wb = w_tile + goff;
+#pragma unroll
+        for (int k = 0; k < LPW; ++k) {
+            const int j0 = wave + NWAVE * k, j = j0 < NI ? j0 : wave;
+            const uint32_t mk = NWAVE * (k + 1) <= NI ? m : m & (0u - (uint32_t)(j0 < NI));
+            const uint32_t dst = spare + ((st + 1024 * j - spare) & mk);
+            dma16(dst, voff[k] & m, j < NA ? ab : wb);
+        }
+    };
+
+    // ---- fragment addresses inside a stage (without the stage's base)
+    const int a_unit = wm * IMG4, b_unit = APART + wn * IMG4;
+    const int o16 = 64 * r + 16 * ((g + (r >> 2)) & 3);           // K-half 0; K-half 1 is ^ 32; rows + 32: + 2048
+    const int o8  = 4096 + 32 * r + 8 * ((g + (r >> 3)) & 3);     // K-half 1 is ^ 16; rows + 32: + 1024
+    const int sa_off = a_unit + SC4 + 4 * r, sb_off = b_unit + SC4 + 4 * r;
+
+    auto read_frag = [&](const unsigned char *unit_base, int i, int s) __attribute__((always_inline)) {
+        const v4u lo = *reinterpret_cast<const v4u *>(unit_base + ((o16 ^ (32 * s)) + 2048 * i));
+        const v2u hi = *reinterpret_cast<const v2u *>(unit_base + ((o8 ^ (16 * s)) + 1024 * i));
+        v6i f = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1]};
+        return f;
+    };
+
+    v16f acc[4];
+    const v16f zf = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = zf;
+
+    auto scale_tile = [&](uint32_t abits, uint32_t bbits) __attribute__((always_inline)) {
+        const v2u ta = {abits, 0u}, tb = {bbits, 0u};
+        return __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_bit_cast(v4h, ta), __builtin_bit_cast(v4h, tb), zf, 0, 0, 0);
+    };
+    const int64_t m_w = (int64_t)au0 * 64 + wm * 64, n_w = (int64_t)wu0 * 64 + wn * 64;
+    // steps 2 and 3 for elements e0 .. e1-1 of sub-tile (i, j) of group grp
+    auto dequant = [&](int grp, int i, int j, const v16f &c, const v16f &s, int e0, int e1) __attribute__((always_inline)) {
+#pragma unroll
+        for (int e = e0; e < e1; ++e) acc[2 * i + j][e] = fmaf(c[e], s[e], acc[2 * i + j][e]);
+        if (DBG && grp >= 0) {
+#pragma unroll
+            for (int e = e0; e < e1; ++e) {
+                const int64_t m = m_w + 32 * i + 8 * (e >> 2) + 4 * g + (e & 3), n = n_w + 32 * j + r;
+                if (m < p.M && n < p.N) p.partials[(m * p.N + n) * (p.G4 + p.G8) + grp] = (int32_t)c[e];
+            }
+        }
+    };
+
+    const int G4 = p.G4;
+    // ---- prologue: the first NST groups are requested, the first one has landed
+#pragma unroll
+    for (int v = 0; v < NST; ++v) request(v, v, v < G4);
+    __builtin_amdgcn_s_waitcnt(wait_imm((NST - 1) * LPW));
+    __syncthreads();
+    // carried from step to step: the fragments of sub-tile row 0 / column 0 and the scale bits of the
+    // coming step, and the integer and scale tiles of the last sub-tile of the step before
+    v6i af0[2], bf0[2];
+    uint32_t sa[2], sb[2];
+    {
+        const unsigned char *st = smem;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) { af0[s] = read_frag(st + a_unit, 0, s); bf0[s] = read_frag(st + b_unit, 0, s); }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            sa[i] = *reinterpret_cast<const uint32_t *>(st + sa_off + 128 * i);
+            const uint32_t wb = *reinterpret_cast<const uint32_t *>(st + sb_off + 128 * i);
+            sb[i] = g == 0 ? wb : 0u;          // zero on one side keeps k-slots 4..7 of the fp16 MFMA empty
+        }
+    }
+    v16f c_pend = zf, s_pend = zf;
+    int  u_pend = -1;
+
+    // One K-step = one INT4 group.  Twelve slots of one MFMA each, fenced so that the compiler keeps
+    // their order.  Sub-tiles in the order (0,0) (1,0) (0,1) (1,1): column fragments 0 are free after
+    // the second sub-tile and row fragments 0 after the third, and are refilled from the next stage
+    // behind the barrier in the middle of the step.  The dequantisation of a sub-tile sits two slots
+    // behind its last MFMA.
+    // A step has no branch (one inside it lets the compiler sink MFMAs past the barrier): group
+    // u + NST is requested whether it exists or not (see `request`), so at the barrier the
+    // requests of NST - 2 groups may always remain in flight.
+    int cur = 0;                                // stage of group u
+    auto step = [&](int u) __attribute__((always_inline)) {
+        const int nxt = cur + 1 == NST ? 0 : cur + 1;
+        const unsigned char *st  = smem + cur * STAGE;
+        const unsigned char *nst = smem + nxt * STAGE;
+        v6i af1[2], bf1[2];
+        v16f c0, c1, c2, c3, s0, s1, s2, s3;
+        uint32_t nsa[2], nsb[2];
+        // slot 0
+        ATOM_F6_PIN(af0[0]);
+        c0 = mfma_f6(af0[0], bf0[0], zf);
+        ATOM_F6_PIN(c0);
+        af1[0] = read_frag(st + a_unit, 1, 0);
+        af1[1] = read_frag(st + a_unit, 1, 1);
+        ATOM_F6_SLOT_END();
+        // slot 1
+        ATOM_F6_PIN(sa[0]);
+        s0 = scale_tile(sa[0], sb[0]);
+        ATOM_F6_PIN(s0);
+        dequant(u_pend, 1, 1, c_pend, s_pend, 0, 8);
+        bf1[0] = read_frag(st + b_unit, 1, 0);
+        bf1[1] = read_frag(st + b_unit, 1, 1);
+        ATOM_F6_PIN(acc[3]);
+        ATOM_F6_SLOT_END();
+        // slot 2
+        c0 = mfma_f6(af0[1], bf0[1], c0);
+        ATOM_F6_PIN(c0);
+        dequant(u_pend, 1, 1, c_pend, s_pend, 8, 16);
+        ATOM_F6_PIN(acc[3]);
+        ATOM_F6_SLOT_END();
+        // slot 3
+        ATOM_F6_PIN(af1[0]);
+        c1 = mfma_f6(af1[0], bf0[0], zf);
+        ATOM_F6_PIN(c1);
+        ATOM_F6_SLOT_END();
+        // slot 4
+        ATOM_F6_PIN(sa[1]);
+        s1 = scale_tile(sa[1], sb[0]);
+        ATOM_F6_PIN(s1);
+        dequant(u, 0, 0, c0, s0, 0, 8);
+        ATOM_F6_PIN(acc[0]);
+        ATOM_F6_SLOT_END();
+        // slot 5
+        c1 = mfma_f6(af1[1], bf0[1], c1);
+        ATOM_F6_PIN(c1);
+        dequant(u, 0, 0, c0, s0, 8, 16);
+        ATOM_F6_PIN(acc[0]);
+        ATOM_F6_SLOT_END();
+        // group u+1 has landed (this wavefront's share; the barrier makes it everybody's), and this
+        // wavefront's reads of stage u are complete: after the barrier the stage may be refilled
+        __builtin_amdgcn_s_waitcnt(wait_imm((NST - 2) * LPW));
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        request(u + NST, cur, u + NST < G4);
+        // slot 6
+        ATOM_F6_PIN(bf1[0]);
+        c2 = mfma_f6(af0[0], bf1[0], zf);
+        ATOM_F6_PIN(c2);
+        bf0[0] = read_frag(nst + b_unit, 0, 0);
+        bf0[1] = read_frag(nst + b_unit, 0, 1);
+        ATOM_F6_SLOT_END();
+        // slot 7
+        ATOM_F6_PIN(sb[1]);
+        s2 = scale_tile(sa[0], sb[1]);
+        ATOM_F6_PIN(s2);
+        dequant(u, 1, 0, c1, s1, 0, 8);
+        ATOM_F6_PIN(acc[2]);
+        ATOM_F6_SLOT_END();
+        // slot 8
+        c2 = mfma_f6(af0[1], bf1[1], c2);
+        ATOM_F6_PIN(c2);
+        dequant(u, 1, 0, c1, s1, 8, 16);
+        ATOM_F6_PIN(acc[2]);
+        ATOM_F6_SLOT_END();
+        // slot 9
+        ATOM_F6_PIN(af1[0]);
+        c3 = mfma_f6(af1[0], bf1[0], zf);
+        ATOM_F6_PIN(c3);
+        af0[0] = read_frag(nst + a_unit, 0, 0);
+        af0[1] = read_frag(nst + a_unit, 0, 1);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            nsa[i] = *reinterpret_cast<const uint32_t *>(nst + sa_off + 128 * i);
+            nsb[i] = *reinterpret_cast<const uint32_t *>(nst + sb_off + 128 * i);
+        }
+        ATOM_F6_SLOT_END();
+        // slot 10
+        ATOM_F6_PIN(sa[1]);
+        s3 = scale_tile(sa[1], sb[1]);
+        ATOM_F6_PIN(s3);
+        dequant(u, 0, 1, c2, s2, 0, 8);
+        ATOM_F6_PIN(acc[1]);
+        ATOM_F6_SLOT_END();
+        // slot 11
+        c3 = mfma_f6(af1[1], bf1[1], c3);
+        ATOM_F6_PIN(c3);
+        dequant(u, 0, 1, c2, s2, 8, 16);
+        ATOM_F6_PIN(acc[1]);
+        sa[0] = nsa[0]; sa[1] = nsa[1];
+        sb[0] = g == 0 ? nsb[0] : 0u; sb[1] = g == 0 ? nsb[1] : 0u;
+        ATOM_F6_SLOT_END();
+        c_pend = c3; s_pend = s3; u_pend = u;
+        cur = nxt;
+    };
+    for (int u = 0; u < G4; ++u) step(u);
+    dequant(u_pend, 1, 1, c_pend, s_pend, 0, 16);
+
+    // ---- the INT8 groups: INT8 MFMA, int32 tile converted to fp32, the same dequantisation
+    {
+        constexpr int NA8 = Gm::NA8, NI8 = Gm::NI8, LPW8 = Gm::LPW8, APART8 = Gm::APART8;
+        uint32_t voff8[LPW8];
+#pragma unroll
+        for (int k = 0; k < LPW8; ++k) {
+            const int j = wave + NWAVE * k;
+            const bool isa = j < NA8;
+            int q = 64 * (isa ? j : j - NA8) + lane;
+            const int nq = (isa ? WM : 2) * (IMG8 / 16);
+            q = q < nq ? q : nq - 1;
+            int unit = q / (IMG8 / 16);
+            const int off = q - unit * (IMG8 / 16);
+            const int valid = isa ? a_valid : w_valid;
+            unit = unit < valid ? unit : valid - 1;
+            voff8[k] = (uint32_t)unit * (uint32_t)p.ustride + 16u * off;
+        }
+        const int a_unit8 = wm * IMG8, b_unit8 = APART8 + wn * IMG8;
+        int ck[4];                                                 // byte offset of chunk 2 kk + g of row r
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) ck[kk] = 128 * r + 16 * (((2 * kk + g) ^ r ^ ((r >> 3) & 1)) & 7);
+        __builtin_amdgcn_s_waitcnt(wait_imm(0));                   // the last (dummy) requests of the K loop
+        for (int g8 = 0; g8 < p.G8; ++g8) {
+            __syncthreads();                                       // every read of the LDS contents so far is done
+            const uint8_t *ab = a_tile + (int64_t)G4 * IMG4 + (int64_t)g8 * IMG8;
+            const uint8_t *wb = w_tile + (int64_t)G4 * IMG4 + (int64_t)g8 * IMG8;
+#pragma unroll
+            for (int k = 0; k < LPW8; ++k) {
+                const int j = wave + NWAVE * k;
+                if (j < NI8) dma16(lds0 + 1024 * j, voff8[k], j < NA8 ? ab : wb);
+            }
+            __builtin_amdgcn_s_waitcnt(wait_imm(0));
+            __syncthreads();
+            uint32_t qa[2], qb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                qa[i] = *reinterpret_cast<const uint32_t *>(smem + a_unit8 + SC8 + 4 * r + 128 * i);
+                const uint32_t t = *reinterpret_cast<const uint32_t *>(smem + b_unit8 + SC8 + 4 * r + 128 * i);
+                qb[i] = g == 0 ? t : 0u;
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    v16i ci = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) {
+                        const v4i a = *reinterpret_cast<const v4i *>(smem + a_unit8 + ck[kk] + 4096 * i);
+                        const v4i b = *reinterpret_cast<const v4i *>(smem + b_unit8 + ck[kk] + 4096 * j);
+                        ci = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, ci, 0, 0, 0);
+                    }
+                    const v16f s = scale_tile(qa[i], qb[j]);
+                    v16f cf;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) cf[e] = (float)ci[e];
+                    dequant(G4 + g8, i, j, cf, s, 0, 16);
+                }
+        }
+    }
+    __syncthreads();                                               // LDS is free
+
+    // ---- store: the 64 x 64 fp16 tile of a wavefront goes through LDS so that global memory sees
+    // whole 128-byte rows (a lane holds one column of the MFMA layout)
+    constexpr int OSTRIDE = Gm::OSTRIDE;
+    unsigned char *ot = smem + wave * (64 * OSTRIDE);
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int row = 32 * (t >> 1) + 8 * (e >> 2) + 4 * g + (e & 3);
+            const int col = 32 * (t & 1) + r;
+            *reinterpret_cast<uint16_t *>(ot + row * OSTRIDE + col * 2) = __half_as_ushort(__float2half_rn(acc[t][e]));
+        }
+    __builtin_amdgcn_s_waitcnt(wait_imm(0));                       // the wavefront reads only what it wrote itself
+    const bool vec_ok = ((reinterpret_cast<uintptr_t>(p.y) | (uintptr_t)(p.ldy * 2)) & 15) == 0;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int row = it * 8 + (lane >> 3), ch = lane & 7;
+        const int64_t m = m_w + row, n = n_w + ch * 8;
+        if (m >= p.M || n >= p.N) continue;
+        const uint4 v = *reinterpret_cast<const uint4 *>(ot + row * OSTRIDE + ch * 16);
+        uint16_t *dst = p.y + m * p.ldy + n;
+        if (vec_ok && n + 8 <= p.N) {
+            *reinterpret_cast<uint4 *>(dst) = v;
+        } else {
+            const uint16_t *hv = reinterpret_cast<const uint16_t *>(&v);
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (n + k < p.N) dst[k] = hv[k];
+        }
+    }
+}
+
+template <int WM, bool DBG>
+hipError_t launch_f6_cfg(const F6Params &p, hipStream_t stream)
+{
+    using Gm = F6Geom<WM>;
+    static_assert(Gm::LDS <= 160 * 1024, "LDS of a compute unit");
+    static_assert(Gm::LPW * (Gm::NST - 1) <= 63, "vmcnt is a 6-bit counter");
+    const int64_t TM = (p.a_units + WM - 1) / WM, TN = (p.w_units + 1) / 2;
+    auto kern = &w4a4_gemm_f6_kernel<WM, DBG>;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Gm::LDS);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(TM * TN)), dim3(Gm::NT), Gm::LDS, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+namespace atom_internal {
+
+size_t f6_packed_bytes(int64_t rows, int K, int O)
+{
+    const int64_t units = (rows + 63) / 64;
+    const int G4 = (K - O) >> 7, G8 = O >> 7;
+    return (size_t)(units * ((int64_t)G4 * IMG4 + (int64_t)G8 * IMG8));
+}
+
+hipError_t launch_f6_pack(const void *q4, const void *q8, const void *scale, int64_t rows, int K, int O,
+                          void *out, hipStream_t stream)
+{
+    PackParams p;
+    p.q4 = static_cast<const uint8_t *>(q4); p.q8 = static_cast<const int8_t *>(q8);
+    p.scale = static_cast<const uint16_t *>(scale);
+    p.out = static_cast<uint8_t *>(out);
+    p.rows = rows;
+    p.units = (int)((rows + 63) / 64);
+    p.G4 = (K - O) >> 7; p.G8 = O >> 7; p.O = O;
+    p.ustride = (int64_t)p.G4 * IMG4 + (int64_t)p.G8 * IMG8;
+    hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)(p.G4 + p.G8), (unsigned)p.units), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_f6_gemm(const void *a_pk, int64_t M, const void *w_pk, int64_t N, int K, int O, void *y,
+                          int64_t ldy, int32_t *partials, hipStream_t stream)
+{
+    F6Params p;
+    p.a_pk = static_cast<const uint8_t *>(a_pk); p.w_pk = static_cast<const uint8_t *>(w_pk);
+    p.y = static_cast<uint16_t *>(y); p.partials = partials;
+    p.M = M; p.N = N; p.ldy = ldy;
+    p.a_units = (int)((M + 63) / 64); p.w_units = (int)((N + 63) / 64);
+    p.G4 = (K - O) >> 7; p.G8 = O >> 7;
+    p.ustride = (int64_t)p.G4 * IMG4 + (int64_t)p.G8 * IMG8;
+    if (partials) return launch_f6_cfg<4, true>(p, stream);
+    // 256-row tiles when they fill the compute units at least once; smaller tiles for fewer rows
+    if (M > 128) return launch_f6_cfg<4, false>(p, stream);
+    if (M > 64)  return launch_f6_cfg<2, false>(p, stream);
+    return launch_f6_cfg<1, false>(p, stream);
+}
+
+}  // namespace atom_internal

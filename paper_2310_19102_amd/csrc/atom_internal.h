@@ -34,6 +34,14 @@ struct GemmArgs {
 size_t     gemm_workspace_bytes(int64_t M, int64_t N, int K, int O);
 hipError_t launch_w4a4_gemm(const GemmArgs &a, hipStream_t stream);
 
+// Group GEMM on pre-tiled operands, INT4 groups carried in FP6 (atom_gemm_f6.hip): bytes of the
+// tiled image of `rows` rows, the packing kernel (canonical q4 / q8 / scale -> image), the GEMM.
+size_t     f6_packed_bytes(int64_t rows, int K, int O);
+hipError_t launch_f6_pack(const void *q4, const void *q8, const void *scale, int64_t rows, int K, int O,
+                          void *out, hipStream_t stream);
+hipError_t launch_f6_gemm(const void *a_pk, int64_t M, const void *w_pk, int64_t N, int K, int O, void *y,
+                          int64_t ldy, int32_t *partials, hipStream_t stream);
+
 // MX variant: front end (FP4 / FP8 codes, E8M0 scale byte per 32 channels) and GEMM on the
 // scaled FP8/FP6/FP4 MFMA.
 hipError_t launch_quantize_rows_mx(const void *x, int64_t rows, int64_t ld, const void *gamma,
@@ -61,6 +69,5 @@ hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int
                                        const void *vz, float sm_scale, void *out, void *workspace,
                                        hipStream_t stream);
 size_t     decode_attention_workspace_bytes(int B, int H, int Hkv, int64_t Tmax);
-
 }  // namespace atom_internal
 #endif
