@@ -298,6 +298,32 @@ atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H,
                                       void *workspace, size_t workspace_bytes,
                                       void *stream);
 
+/*
+ * atom_decode_attention_kv4 for callers that cannot allocate device memory and
+ * have no workspace to hand over (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same kernels, with the partials
+ * of a split launch in a scratch array of atom_static_scratch_bytes() = 4 MiB
+ * that is part of the library's device image (each GPU the library runs on
+ * holds its own copy until the process ends).  The call allocates nothing; the
+ * array's address is looked up on the first call on a device.  Arguments,
+ * results and errors as atom_decode_attention_kv4 without the workspace; sizes
+ * whose partials exceed the array return ATOM_ERR_WORKSPACE
+ * (atom_decode_attention_kv4_workspace_bytes tells).  The scratch needs no
+ * initialisation and is dead after the call, but every call on a GPU uses the
+ * same array: calls that may overlap on one GPU (different streams) race.
+ */
+atom_status atom_decode_attention_kv4_static(const void *q_f16, int32_t B,
+                                             int32_t H, int32_t Hkv, int32_t D,
+                                             int64_t Tmax, const int32_t *seq_len,
+                                             const void *k_codes,
+                                             const void *k_scale,
+                                             const void *k_zero,
+                                             const void *v_codes,
+                                             const void *v_scale,
+                                             const void *v_zero, float sm_scale,
+                                             void *out_f16, void *stream);
+size_t atom_static_scratch_bytes(void);
+
 /* Scratch atom_decode_attention_kv4 needs for these sizes (0 when none). */
 size_t atom_decode_attention_kv4_workspace_bytes(int32_t B, int32_t H,
                                                  int32_t Hkv, int32_t D,

@@ -21,6 +21,8 @@ from .binding import (  # noqa: F401
     atom_kv_quantize_pair,
     atom_decode_attention_kv4,
     atom_decode_attention_kv4_workspace_bytes,
+    atom_decode_attention_kv4_static,
+    atom_static_scratch_bytes,
     atom_status_string,
     atom_w4a4_gemm,
     atom_w4a4_gemm_workspace_bytes,

@@ -35,6 +35,8 @@ EXPORTS = (
     "atom_kv_quantize_pair",
     "atom_decode_attention_kv4",
     "atom_decode_attention_kv4_workspace_bytes",
+    "atom_decode_attention_kv4_static",
+    "atom_static_scratch_bytes",
     "atom_check_reorder_idx",
     "atom_status_string",
 )
@@ -108,6 +110,11 @@ def load_library():
                                             f32, vp, vp, sz, vp]
     L.atom_decode_attention_kv4_workspace_bytes.restype = sz
     L.atom_decode_attention_kv4_workspace_bytes.argtypes = [i32, i32, i32, i32, i64]
+    L.atom_decode_attention_kv4_static.restype = ctypes.c_int
+    L.atom_decode_attention_kv4_static.argtypes = [vp, i32, i32, i32, i32, i64, vp, vp, vp, vp, vp, vp, vp,
+                                                   f32, vp, vp]
+    L.atom_static_scratch_bytes.restype = sz
+    L.atom_static_scratch_bytes.argtypes = []
     L.atom_check_reorder_idx.restype = ctypes.c_int
     L.atom_check_reorder_idx.argtypes = [vp, ctypes.c_int32]
     L.atom_status_string.restype = ctypes.c_char_p
@@ -495,6 +502,29 @@ def atom_decode_attention_kv4(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...]
                                      _ptr(workspace), ws_bytes, _stream())
     if st != 0:
         raise AtomError(st, "atom_decode_attention_kv4")
+    return out
+
+
+def atom_static_scratch_bytes() -> int:
+    return int(load_library().atom_static_scratch_bytes())
+
+
+def atom_decode_attention_kv4_static(q: torch.Tensor, k_cache: Tuple[torch.Tensor, ...],
+                                     v_cache: Tuple[torch.Tensor, ...], seq_len: torch.Tensor,
+                                     sm_scale: float, out: torch.Tensor):
+    """``atom_decode_attention_kv4`` through the entry point that allocates nothing: ``out`` is the
+    caller's, the partials of a split launch live in the library's own per-GPU scratch array."""
+    L = load_library()
+    if out is None:
+        raise ValueError("out must be given: this call allocates nothing")
+    B, H, Hkv, D, Tmax, out = _attention_args(q, k_cache, v_cache, seq_len, out)
+    kq, ks, kz = k_cache
+    vq, vs, vz = v_cache
+    st = L.atom_decode_attention_kv4_static(_ptr(q), B, H, Hkv, D, Tmax, _ptr(seq_len), _ptr(kq), _ptr(ks),
+                                            _ptr(kz), _ptr(vq), _ptr(vs), _ptr(vz), sm_scale, _ptr(out),
+                                            _stream())
+    if st != 0:
+        raise AtomError(st, "atom_decode_attention_kv4_static")
     return out
 
 

@@ -270,6 +270,30 @@ atom_status atom_decode_attention_kv4(const void *q_f16, int32_t B, int32_t H, i
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
+size_t atom_static_scratch_bytes(void) { return atom_internal::static_scratch_bytes(); }
+
+atom_status atom_decode_attention_kv4_static(const void *q_f16, int32_t B, int32_t H, int32_t Hkv,
+                                             int32_t D, int64_t Tmax, const int32_t *seq_len,
+                                             const void *k_codes, const void *k_scale,
+                                             const void *k_zero, const void *v_codes,
+                                             const void *v_scale, const void *v_zero, float sm_scale,
+                                             void *out_f16, void *stream)
+{
+    if (B < 0 || H <= 0 || Hkv <= 0 || H % Hkv || D <= 0 || Tmax < 0 || Tmax > 0x7fffffffLL)
+        return ATOM_ERR_SHAPE;
+    if (D != 128) return ATOM_ERR_UNSUPPORTED;
+    if ((int64_t)B * H > 0x7fffffffLL || Tmax > (1LL << 25)) return ATOM_ERR_UNSUPPORTED;
+    if (B == 0) return ATOM_OK;
+    // the partials of a split launch must fit the library's own scratch array
+    const size_t need = atom_internal::decode_attention_workspace_bytes(B, H, Hkv, Tmax);
+    if (need > atom_internal::static_scratch_bytes()) return ATOM_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (atom_internal::static_scratch(&ws) != hipSuccess) return ATOM_ERR_HIP;
+    return atom_decode_attention_kv4(q_f16, B, H, Hkv, D, Tmax, seq_len, k_codes, k_scale, k_zero, v_codes,
+                                     v_scale, v_zero, sm_scale, out_f16, ws,
+                                     atom_internal::static_scratch_bytes(), stream);
+}
+
 size_t atom_decode_attention_kv4_workspace_bytes(int32_t B, int32_t H, int32_t Hkv, int32_t D,
                                                  int64_t Tmax)
 {

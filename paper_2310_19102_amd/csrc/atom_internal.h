@@ -69,5 +69,10 @@ hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int
                                        const void *vz, float sm_scale, void *out, void *workspace,
                                        hipStream_t stream);
 size_t     decode_attention_workspace_bytes(int B, int H, int Hkv, int64_t Tmax);
+// The library's own per-GPU scratch array (for the entry point that allocates nothing): its size,
+// and its device address on the current device (looked up on the first call per device).
+size_t     static_scratch_bytes();
+hipError_t static_scratch(void **ptr);
+
 }  // namespace atom_internal
 #endif

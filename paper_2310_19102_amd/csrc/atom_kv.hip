@@ -13,6 +13,8 @@
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "atom_internal.h"
 
 namespace {
@@ -974,6 +976,36 @@ hipError_t launch_decode_attention_kv4(const void *q, int B, int H, int Hkv, int
     hipLaunchKernelGGL(decode_attention_merge_kernel, dim3((unsigned)(B * H)), dim3(128), 0, stream,
                        (const float *)part, S, (__half *)out);
     return hipGetLastError();
+}
+
+// Scratch for callers that cannot allocate: one array per GPU, in the library's own device
+// image, held until the process ends.  Host code never passes the array's name to a kernel (there
+// it is only a handle for the symbol): the device address is looked up once per device with that
+// device current, and only that pointer is used afterwards.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void *> scratch_ptr[kMaxDevices];
+}  // namespace
+
+size_t static_scratch_bytes() { return kStaticScratchBytes; }
+
+hipError_t static_scratch(void **ptr)
+{
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (!p) return hipErrorInvalidSymbol;
+        scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return hipSuccess;
 }
 
 }  // namespace atom_internal
