@@ -6,7 +6,10 @@
  * Conventions common to every entry point
  *   - Every data pointer is a DEVICE pointer unless it says "host".
  *   - The caller owns every buffer.  Except where stated the library
- *     allocates nothing and keeps no state between calls.
+ *     allocates nothing; the only state it keeps between calls is the
+ *     one-time, per-process and per-device kernel attribute set-up (the opt-in
+ *     for more than 64 KB of LDS), held in atomics: calls may come from
+ *     several host threads.
  *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*;
  *     NULL = the default stream).  Outputs are valid once the stream has
  *     reached the end of the call.
@@ -161,6 +164,9 @@ atom_status atom_quantize_weight(const void *w_f16, int64_t N, int64_t ldw,
  *                 atom_w4a4_gemm_workspace_bytes(M, N, d) bytes, 256-byte
  *                 aligned; may be NULL when that size is 0
  * Code pointers must be 16-byte aligned, scale pointers 2-byte aligned.
+ * ATOM_ERR_UNSUPPORTED when a code or scale array of either operand reaches
+ * 4 GiB (rows * K4 / 2, rows * O or rows * G >= 2^32: the kernels use 32-bit
+ * offsets) or the launch would have more than 2^31 - 1 tiles.
  */
 atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8,
                            const void *a_scale, int64_t M, const void *w_q4,
@@ -204,6 +210,23 @@ atom_status atom_pack_weight(const void *w_q4, const void *w_q8,
                              void *w_packed, size_t packed_bytes, void *stream);
 size_t atom_w4a4_gemm_packed_workspace_bytes(int64_t M, int64_t N,
                                              const atom_desc *d);
+/*
+ * The two halves of atom_w4a4_gemm_packed as calls of their own, for a caller
+ * that keeps the tiled activations (several GEMMs on one input: Q, K and V),
+ * or wants to time the stages apart: atom_pack_act re-tiles the canonical
+ * activation arrays of M rows into a_packed (atom_pack_weight_bytes(M, d)
+ * bytes, 256-byte aligned; the same layout as the weights'), and
+ * atom_w4a4_gemm_prepacked is the GEMM on two tiled operands.  Errors as
+ * atom_pack_weight / atom_w4a4_gemm_packed.
+ */
+atom_status atom_pack_act(const void *a_q4, const void *a_q8,
+                          const void *a_scale, int64_t M, const atom_desc *d,
+                          void *a_packed, size_t packed_bytes, void *stream);
+atom_status atom_w4a4_gemm_prepacked(const void *a_packed, int64_t M,
+                                     const void *w_packed, int64_t N,
+                                     const atom_desc *d, void *y_f16,
+                                     int64_t ldy, int32_t *partials_dbg,
+                                     void *stream);
 atom_status atom_w4a4_gemm_packed(const void *a_q4, const void *a_q8,
                                   const void *a_scale, int64_t M,
                                   const void *w_packed, int64_t N,

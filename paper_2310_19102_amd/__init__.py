@@ -27,6 +27,8 @@ from .binding import (  # noqa: F401
     atom_w4a4_gemm,
     atom_w4a4_gemm_workspace_bytes,
     atom_pack_weight,
+    atom_pack_act,
+    atom_w4a4_gemm_prepacked,
     atom_w4a4_gemm_packed,
     atom_w4a4_gemm_packed_workspace_bytes,
     library_path,

@@ -26,6 +26,8 @@ EXPORTS = (
     "atom_pack_weight",
     "atom_w4a4_gemm_packed_workspace_bytes",
     "atom_w4a4_gemm_packed",
+    "atom_pack_act",
+    "atom_w4a4_gemm_prepacked",
     "atom_mx_quantize_act",
     "atom_mx_quantize_weight",
     "atom_mx_gemm",
@@ -90,6 +92,10 @@ def load_library():
     L.atom_w4a4_gemm_packed_workspace_bytes.argtypes = [i64, i64, dp]
     L.atom_w4a4_gemm_packed.restype = ctypes.c_int
     L.atom_w4a4_gemm_packed.argtypes = [vp, vp, vp, i64, vp, i64, dp, vp, i64, vp, vp, sz, vp]
+    L.atom_pack_act.restype = ctypes.c_int
+    L.atom_pack_act.argtypes = [vp, vp, vp, i64, dp, vp, sz, vp]
+    L.atom_w4a4_gemm_prepacked.restype = ctypes.c_int
+    L.atom_w4a4_gemm_prepacked.argtypes = [vp, i64, vp, i64, dp, vp, i64, vp, vp]
     i32 = ctypes.c_int32
     L.atom_mx_quantize_act.restype = ctypes.c_int
     L.atom_mx_quantize_act.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, vp, vp, vp]
@@ -326,6 +332,51 @@ def atom_pack_weight(w_q4, w_q8, w_scale, group_size: int = 128, out: Optional[t
                             out.numel(), _stream())
     if st != 0:
         raise AtomError(st, "atom_pack_weight")
+    return out
+
+
+def atom_pack_act(a_q4, a_q8, a_scale, group_size: int = 128, out: Optional[torch.Tensor] = None):
+    """Canonical activation codes and scales -> the tiled layout (``atom_w4a4_gemm_prepacked``)."""
+    L = load_library()
+    for t, dt, nm in ((a_q4, torch.uint8, "a_q4"), (a_q8, torch.int8, "a_q8"), (a_scale, torch.float16, "a_scale")):
+        _dev(t, dt, nm)
+        if not t.is_contiguous():
+            raise ValueError(f"{nm} must be contiguous")
+    M, O = a_q8.shape
+    K = a_q4.shape[1] * 2 + O
+    d = _desc(K, group_size, n_outlier=O)
+    need = int(L.atom_pack_weight_bytes(M, ctypes.byref(d)))
+    if out is None:
+        out = torch.empty(max(need, 1), dtype=torch.uint8, device=a_q4.device)
+    _dev(out, torch.uint8, "out")
+    st = L.atom_pack_act(_ptr(a_q4), _ptr(a_q8), _ptr(a_scale), M, ctypes.byref(d), _ptr(out), out.numel(), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_pack_act")
+    return out
+
+
+def atom_w4a4_gemm_prepacked(a_packed, M: int, w_packed, N: int, K: int, group_size: int = 128,
+                             n_outlier: int = 128, out: Optional[torch.Tensor] = None,
+                             partials: Optional[torch.Tensor] = None):
+    """The GEMM on two tiled operands (``atom_pack_act`` / ``atom_pack_weight``)."""
+    L = load_library()
+    _dev(a_packed, torch.uint8, "a_packed")
+    _dev(w_packed, torch.uint8, "w_packed")
+    d = _desc(K, group_size, n_outlier)
+    if (a_packed.numel() < int(L.atom_pack_weight_bytes(M, ctypes.byref(d))) or
+            w_packed.numel() < int(L.atom_pack_weight_bytes(N, ctypes.byref(d)))):
+        raise ValueError("a packed operand is smaller than atom_pack_weight_bytes of its rows")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=a_packed.device)
+    _dev(out, torch.float16, "out")
+    if partials is not None:
+        _dev(partials, torch.int32, "partials")
+        if tuple(partials.shape) != (M, N, K // group_size) or not partials.is_contiguous():
+            raise ValueError("partials must be contiguous int32 [M, N, G]")
+    st = L.atom_w4a4_gemm_prepacked(_ptr(a_packed), M, _ptr(w_packed), N, ctypes.byref(d), _ptr(out),
+                                    out.stride(0) if M > 1 else max(N, out.stride(0)), _ptr(partials), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_w4a4_gemm_prepacked")
     return out
 
 

@@ -116,6 +116,15 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8, const void *a_sca
         !aligned(w_q8, 16) || !aligned(w_scale, 2) || !aligned(y_f16, 2) ||
         (partials_dbg && !aligned(partials_dbg, 4)))
         return ATOM_ERR_ALIGN;
+    // the tiled kernels address the code and scale arrays with 32-bit offsets and number their
+    // tiles in 32 bits
+    {
+        const uint64_t lim = 1ull << 32, K4h = (uint64_t)(d->K - d->n_outlier) / 2, O = (uint64_t)d->n_outlier,
+                       G = (uint64_t)(d->K / d->group_size);
+        const uint64_t rows = (uint64_t)(M > N ? M : N);
+        if (rows * K4h >= lim || rows * O >= lim || rows * G >= lim) return ATOM_ERR_UNSUPPORTED;
+        if (((uint64_t)M + 63) / 64 * (((uint64_t)N + 31) / 32) > 0x7fffffffull) return ATOM_ERR_UNSUPPORTED;
+    }
     const size_t need = atom_internal::gemm_workspace_bytes(M, N, d->K, d->n_outlier);
     if (need) {
         if (!workspace || workspace_bytes < need) return ATOM_ERR_WORKSPACE;
@@ -164,6 +173,31 @@ atom_status atom_pack_weight(const void *w_q4, const void *w_q8, const void *w_s
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
+atom_status atom_pack_act(const void *a_q4, const void *a_q8, const void *a_scale, int64_t M,
+                          const atom_desc *d, void *a_packed, size_t packed_bytes, void *stream)
+{
+    return atom_pack_weight(a_q4, a_q8, a_scale, M, d, a_packed, packed_bytes, stream);
+}
+
+atom_status atom_w4a4_gemm_prepacked(const void *a_packed, int64_t M, const void *w_packed, int64_t N,
+                                     const atom_desc *d, void *y_f16, int64_t ldy, int32_t *partials_dbg,
+                                     void *stream)
+{
+    atom_status st = check_desc(d);
+    if (st != ATOM_OK) return st;
+    if (M < 0 || N < 0 || ldy < N) return ATOM_ERR_SHAPE;
+    if (M == 0 || N == 0) return ATOM_OK;
+    if (!a_packed || !w_packed || !y_f16) return ATOM_ERR_NULL;
+    if (!aligned(a_packed, 256) || !aligned(w_packed, 256) || !aligned(y_f16, 2) ||
+        (partials_dbg && !aligned(partials_dbg, 4)))
+        return ATOM_ERR_ALIGN;
+    const int64_t mu = (M + 63) / 64, nu = (N + 63) / 64;
+    if (mu > 65535 || mu * ((nu + 1) / 2) > 0x7fffffffLL) return ATOM_ERR_UNSUPPORTED;
+    hipError_t err = atom_internal::launch_f6_gemm(a_packed, M, w_packed, N, d->K, d->n_outlier, y_f16, ldy,
+                                                   partials_dbg, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
 size_t atom_w4a4_gemm_packed_workspace_bytes(int64_t M, int64_t N, const atom_desc *d)
 {
     (void)N;
@@ -189,12 +223,9 @@ atom_status atom_w4a4_gemm_packed(const void *a_q4, const void *a_q8, const void
     const size_t need = atom_internal::f6_packed_bytes(M, d->K, d->n_outlier);
     if (!workspace || workspace_bytes < need) return ATOM_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return ATOM_ERR_ALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t err = atom_internal::launch_f6_pack(a_q4, a_q8, a_scale, M, d->K, d->n_outlier, workspace, s);
-    if (err != hipSuccess) return ATOM_ERR_HIP;
-    err = atom_internal::launch_f6_gemm(workspace, M, w_packed, N, d->K, d->n_outlier, y_f16, ldy,
-                                        partials_dbg, s);
-    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+    st = atom_pack_act(a_q4, a_q8, a_scale, M, d, workspace, workspace_bytes, stream);
+    if (st != ATOM_OK) return st;
+    return atom_w4a4_gemm_prepacked(workspace, M, w_packed, N, d, y_f16, ldy, partials_dbg, stream);
 }
 
 atom_status atom_kv_quantize(const void *x_f16, int64_t R, int64_t ldx, int32_t D, float clip,

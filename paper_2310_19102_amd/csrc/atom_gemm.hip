@@ -27,6 +27,7 @@
 #include "atom_internal.h"
 
 #include "atom_gemm_common.h"
+#include "atom_launch.h"
 
 namespace {
 
@@ -332,13 +333,9 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t stream)
     static_assert((KS - 1) * (NT / KS) * (WM / 32) * (WN / 32) * 16 * 4 <= LDS, "the sets' tiles fit the stages");
     const int64_t MB = (p.M + BM - 1) / BM, NB = (p.N + BN - 1) / BN;
     auto kern = &w4a4_gemm_kernel<BM, BN, WM, WN, DBG, KS>;
-    static bool configured = false;   // one attribute call per kernel variant and process
-    if (!configured) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (err != hipSuccess) return err;
-        configured = true;
-    }
+    static atom_launch::LdsOptIn opt_in;   // one attribute call per kernel variant and device
+    hipError_t err = atom_launch::ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), LDS);
+    if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kern, dim3((unsigned)(MB * NB)), dim3(NT), LDS, stream, p);
     return hipGetLastError();
 }

@@ -34,6 +34,7 @@
 #include <type_traits>
 
 #include "atom_gemm_common.h"
+#include "atom_launch.h"
 
 namespace {
 
@@ -421,13 +422,9 @@ hipError_t launch_cfg(const GemmParams &p, hipStream_t stream)
     constexpr int LDS = KS * 2 * ((BM + BN) * 128 + NT * 4);
     const int64_t MB = (p.M + BM - 1) / BM, NB = (p.N + BN - 1) / BN;
     auto kern = &w4a4_gemm_big_kernel<BM, BN, KS, DBG>;
-    static bool configured = false;   // one attribute call per kernel variant and process
-    if (!configured) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (err != hipSuccess) return err;
-        configured = true;
-    }
+    static atom_launch::LdsOptIn opt_in;   // one attribute call per kernel variant and device
+    hipError_t err = atom_launch::ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), LDS);
+    if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kern, dim3((unsigned)(MB * NB)), dim3(NT * KS), LDS, stream, p);
     return hipGetLastError();
 }

@@ -18,13 +18,15 @@
 // byte for byte what one LDS stage holds for that unit and group, so the K loop's loader is a
 // linear copy global -> LDS by global_load_lds_dwordx4 (no registers, no address arithmetic, whole
 // cache lines).
-//   INT4 group image, 6400 bytes: a lane of the MFMA holds 32 consecutive channels of a row = 24
-//     bytes of FP6 ("piece" p = 0..3 of the row's group).  Bytes 0-15 of piece p of row r sit at
-//     64 r + 16 ((p + r/4) % 4), bytes 16-23 at 4096 + 32 r + 8 ((p + r/8) % 4) (rotations: the
-//     128-bit and 64-bit fragment reads of 32 consecutive rows are bank-conflict free), the fp16
-//     scale of row r, zero-extended to 32 bits, at 6144 + 4 r.
-//   INT8 group image, 8448 bytes: 16-byte chunk c of row r at 128 r + 16 ((c ^ r ^ (r/8 % 2)) % 8),
-//     scale at 8192 + 4 r.
+//   INT4 group image, 6656 bytes: lane (row r, half g) of the two FP6 MFMAs of a group holds the
+//     channels 32 g .. 32 g + 31 (first MFMA) and 64 + 32 g .. 64 + 32 g + 31 (second) of its row:
+//     2 x 24 = 48 bytes of FP6, stored as three 16-byte chunks c = 0, 1, 2 at
+//     2048 c + 1024 g + 16 r, so that one 128-bit fragment read of a wavefront is one contiguous
+//     kilobyte (bank-conflict free) and every address of a step is the lane's base plus an
+//     immediate; the fp16 scale of row r, zero-extended to 64 bits (the operand of the fp16 MFMA
+//     that forms the scale products: the scale in its first element, zeros behind), at 6144 + 8 r.
+//   INT8 group image, 8704 bytes: 16-byte chunk c of row r at 128 r + 16 ((c ^ r ^ (r/8 % 2)) % 8),
+//     scale at 8192 + 8 r.
 // Rows past the end of the matrix hold zero codes and zero scales.
 //
 // Kernel: 256 x 128 (or 128 x 128, 64 x 128) tile, wavefront tile 64 x 64 = four 32 x 32 sub-tiles,
@@ -41,13 +43,14 @@
 
 #include "atom_gemm_common.h"
 #include "atom_internal.h"
+#include "atom_launch.h"
 
 namespace {
 
 using namespace atom_gemm;
 
 typedef int      v8i  __attribute__((ext_vector_type(8)));
-typedef int      v6i  __attribute__((ext_vector_type(6)));
+typedef int      v12i __attribute__((ext_vector_type(12)));
 typedef unsigned v6u  __attribute__((ext_vector_type(6)));
 typedef unsigned v2u  __attribute__((ext_vector_type(2)));
 typedef unsigned v4u  __attribute__((ext_vector_type(4)));
@@ -55,8 +58,8 @@ typedef float    v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v32h __attribute__((ext_vector_type(32)));
 typedef _Float16 v4h  __attribute__((ext_vector_type(4)));
 
-constexpr int IMG4 = 6400;                // bytes of an INT4 group image of one unit
-constexpr int IMG8 = 8448;                // bytes of an INT8 group image of one unit
+constexpr int IMG4 = 6656;                // bytes of an INT4 group image of one unit
+constexpr int IMG8 = 8704;                // bytes of an INT8 group image of one unit
 constexpr int SC4  = 6144;                // offset of the scales inside an INT4 image
 constexpr int SC8  = 8192;
 
@@ -83,26 +86,34 @@ void pack_rows_kernel(const PackParams p)
     uint8_t *img = p.out + (int64_t)unit * p.ustride + (g < p.G4 ? (int64_t)g * IMG4 : (int64_t)p.G4 * IMG4 + (int64_t)(g - p.G4) * IMG8);
     const int t = threadIdx.x;
     if (g < p.G4) {
-        // chunk t of the 16-byte region: row t / 4, slot t % 4 holds piece (slot - row / 4) % 4
-        const int row = t >> 2, slot = t & 3, piece = (slot - (row >> 2)) & 3;
+        // thread t < 128: row t % 64, half t / 64; its 48 bytes are pieces `half` and `half + 2` of
+        // the group (a piece = 32 consecutive channels = 16 canonical bytes = 24 bytes of FP6)
+        if (t >= 128) return;
+        const int row = t & 63, half = t >> 6;
         const int64_t m = (int64_t)unit * 64 + row;
-        v6u packed = {0u, 0u, 0u, 0u, 0u, 0u};
+        uint32_t out[12] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
         uint32_t sbits = 0;
         if (m < p.rows) {
-            const v4u w = *reinterpret_cast<const v4u *>(p.q4 + m * K4h + (int64_t)g * 64 + piece * 16);
-            v32h h;
 #pragma unroll
-            for (int d = 0; d < 4; ++d)
+            for (int s = 0; s < 2; ++s) {
+                const v4u w = *reinterpret_cast<const v4u *>(p.q4 + m * K4h + (int64_t)g * 64 + (half + 2 * s) * 16);
+                v32h h;
 #pragma unroll
-                for (int k = 0; k < 8; ++k)
-                    h[8 * d + k] = (_Float16)(((int)(w[d] << (28 - 4 * k))) >> 28);   // sign-extended nibble k
-            // the E3M2 number of each code (scale 1: a plain conversion; every code is representable)
-            packed = __builtin_amdgcn_cvt_scalef32_pk32_bf6_f16(h, 1.0f);
+                for (int d = 0; d < 4; ++d)
+#pragma unroll
+                    for (int k = 0; k < 8; ++k)
+                        h[8 * d + k] = (_Float16)(((int)(w[d] << (28 - 4 * k))) >> 28);   // sign-extended nibble k
+                // the E3M2 number of each code (scale 1: a plain conversion; every code is representable)
+                const v6u packed = __builtin_amdgcn_cvt_scalef32_pk32_bf6_f16(h, 1.0f);
+#pragma unroll
+                for (int d = 0; d < 6; ++d) out[6 * s + d] = packed[d];
+            }
             sbits = p.scale[m * G + g];
         }
-        *reinterpret_cast<v4u *>(img + 16 * t) = v4u{packed[0], packed[1], packed[2], packed[3]};
-        *reinterpret_cast<v2u *>(img + 4096 + 32 * row + 8 * ((piece + (row >> 3)) & 3)) = v2u{packed[4], packed[5]};
-        if (slot == 0) *reinterpret_cast<uint32_t *>(img + SC4 + 4 * row) = sbits;
+#pragma unroll
+        for (int c = 0; c < 3; ++c)
+            *reinterpret_cast<v4u *>(img + 2048 * c + 1024 * half + 16 * row) = v4u{out[4 * c], out[4 * c + 1], out[4 * c + 2], out[4 * c + 3]};
+        if (half == 0) *reinterpret_cast<v2u *>(img + SC4 + 8 * row) = v2u{sbits, 0u};
     } else {
         // two chunks per thread: chunk ids t and t + 256 of the 512; row id / 8, slot id % 8
 #pragma unroll
@@ -117,7 +128,7 @@ void pack_rows_kernel(const PackParams p)
                 sbits = p.scale[m * G + g];
             }
             *reinterpret_cast<v4u *>(img + 16 * id) = w;
-            if (slot == 0) *reinterpret_cast<uint32_t *>(img + SC8 + 4 * row) = sbits;
+            if (slot == 0) *reinterpret_cast<v2u *>(img + SC8 + 8 * row) = v2u{sbits, 0u};
         }
     }
 }
@@ -142,11 +153,14 @@ __device__ __forceinline__ void dma16(uint32_t lds, uint32_t voff, const uint8_t
 // s_waitcnt immediate: vmcnt(n), lgkmcnt(0), expcnt untouched
 __host__ __device__ constexpr int wait_imm(int n) { return (n & 15) | (7 << 4) | (0 << 8) | ((n >> 4) << 14); }
 
-__device__ __forceinline__ v16f mfma_f6(v6i a, v6i b, v16f c)
+// A lane's operands of the two MFMAs of a group, as the three 128-bit fragment reads deliver them:
+// registers 0-5 feed the first MFMA (channels 0-63 of the group), registers 6-11 the second.
+template <int S>
+__device__ __forceinline__ v16f mfma_f6(const v12i &a, const v12i &b, v16f c)
 {
     // cbsz = blgp = 3: both operands E3M2 (six registers each); scale bytes 127 = 2^0
-    const v8i a8 = __builtin_shufflevector(a, a, 0, 1, 2, 3, 4, 5, -1, -1);
-    const v8i b8 = __builtin_shufflevector(b, b, 0, 1, 2, 3, 4, 5, -1, -1);
+    const v8i a8 = __builtin_shufflevector(a, a, 6 * S, 6 * S + 1, 6 * S + 2, 6 * S + 3, 6 * S + 4, 6 * S + 5, -1, -1);
+    const v8i b8 = __builtin_shufflevector(b, b, 6 * S, 6 * S + 1, 6 * S + 2, 6 * S + 3, 6 * S + 4, 6 * S + 5, -1, -1);
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 3, 3, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
 }
 
@@ -197,6 +211,7 @@ void w4a4_gemm_f6_kernel(const F6Params p)
     const int wm = wave % WM, wn = wave / WM;
     const int r = lane & 31, g = lane >> 5;
 
+    const int G4 = p.G4;
     // tile of this workgroup: M-tiles fastest, in bands of up to eight M-tiles so that the tiles an
     // XCD works on at one time share both activation and weight units in its L2
     const int TM = (p.a_units + WM - 1) / WM, TN = (p.w_units + 1) / 2;
@@ -234,36 +249,43 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         unit = unit < valid ? unit : valid - 1;                   // ragged tiles repeat their last unit
         voff[k] = (uint32_t)unit * (uint32_t)p.ustride + 16u * off;
     }
-    const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem);
-    // Group v into stage `stage`.  Past the last INT4 group (`real` false) the same number of
-    // instructions is issued, so that the count a wait refers to never changes: every lane then
-    // reads the first 16 bytes of the tile (one cache line per instruction) into the spare kilobyte.
-    auto request = [&](int v, int stage, bool real) __attribute__((always_inline)) {
-        // (selected with masks, not with ?: -- the compiler turned those into branches)
-        const uint32_t m = 0u - (uint32_t)real;                    // all ones, or zero
-        const uint32_t st = lds0 + stage * STAGE, spare = lds0 + Gm::SPARE;
-        const uint64_t goff = (uint64_t)((uint32_t)v * (uint32_t)IMG4 & m);
-        const uint8_t *ab = a_tile + goff, *wb = w_tile + goff;
-#pragma unroll
-        for (int k = 0; k < LPW; ++k) {
-            const int j0 = wave + NWAVE * k, j = j0 < NI ? j0 : wave;
-            const uint32_t mk = NWAVE * (k + 1) <= NI ? m : m & (0u - (uint32_t)(j0 < NI));
-            const uint32_t dst = spare + ((st + 1024 * j - spare) & mk);
-            dma16(dst, voff[k] & m, j < NA ? ab : wb);
-        }
+    const uint32_t vzero = 0;
+    const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem), spare = lds0 + Gm::SPARE;
+    // instruction k of the request of group v into stage `stage`
+    auto request_one = [&](int k, int v, int stage) __attribute__((always_inline)) {
+        const int j0 = wave + NWAVE * k, j = j0 < NI ? j0 : wave;
+        // (selected with a mask, not with ?: -- the compiler turns that into a branch)
+        const uint32_t mk = NWAVE * (k + 1) <= NI ? ~0u : 0u - (uint32_t)(j0 < NI);
+        const uint32_t dst = spare + ((lds0 + stage * STAGE + 1024 * j - spare) & mk);
+        dma16(dst, voff[k], (j < NA ? a_tile : w_tile) + (int64_t)v * IMG4);
     };
+    // Past the last INT4 group the same number of instructions is issued, so that the count a wait
+    // refers to never changes: every lane reads the tile's first 16 bytes (one cache line per
+    // instruction) into the spare kilobyte.
+    auto request_dummy = [&]() __attribute__((always_inline)) { dma16(spare, vzero, a_tile); };
 
-    // ---- fragment addresses inside a stage (without the stage's base)
-    const int a_unit = wm * IMG4, b_unit = APART + wn * IMG4;
-    const int o16 = 64 * r + 16 * ((g + (r >> 2)) & 3);           // K-half 0; K-half 1 is ^ 32; rows + 32: + 2048
-    const int o8  = 4096 + 32 * r + 8 * ((g + (r >> 3)) & 3);     // K-half 1 is ^ 16; rows + 32: + 1024
-    const int sa_off = a_unit + SC4 + 4 * r, sb_off = b_unit + SC4 + 4 * r;
+    // ---- fragment addresses: one register per operand (and one per operand for the scales) holds
+    // the lane's address inside the stage of the coming group; everything a step reads is that
+    // plus an immediate.  The registers move on by one stage per step.
+    const uint32_t lane_off = lds0 + 1024 * g + 16 * r;
+    const uint32_t a_off = wm * IMG4 + lane_off, b_off = APART + wn * IMG4 + lane_off;
+    const uint32_t sa_off = lds0 + wm * IMG4 + SC4 + 8 * r, sb_off = lds0 + APART + wn * IMG4 + SC4 + 8 * r;
 
-    auto read_frag = [&](const unsigned char *unit_base, int i, int s) __attribute__((always_inline)) {
-        const v4u lo = *reinterpret_cast<const v4u *>(unit_base + ((o16 ^ (32 * s)) + 2048 * i));
-        const v2u hi = *reinterpret_cast<const v2u *>(unit_base + ((o8 ^ (16 * s)) + 1024 * i));
-        v6i f = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1]};
-        return f;
+    // the 48 bytes of sub-tile row (column) block i of a unit: the operands of its two MFMAs
+    // (addresses are 32-bit LDS addresses, the workgroup's base included)
+    typedef __attribute__((address_space(3))) const v4i *lds_v4i;
+    typedef __attribute__((address_space(3))) const v2u *lds_v2u;
+    auto read_pair = [&](uint32_t addr, int i) __attribute__((always_inline)) -> v12i {
+        const v4i c0 = *(lds_v4i)(uintptr_t)(addr + 512 * i);
+        const v4i c1 = *(lds_v4i)(uintptr_t)(addr + 512 * i + 2048);
+        const v4i c2 = *(lds_v4i)(uintptr_t)(addr + 512 * i + 4096);
+        const v8i lo = __builtin_shufflevector(c0, c1, 0, 1, 2, 3, 4, 5, 6, 7);
+        const v8i hi = __builtin_shufflevector(c2, c2, 0, 1, 2, 3, -1, -1, -1, -1);
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11);
+    };
+    // scale operand of rows 32 i + r: {fp16 bits, 0, 0, 0}
+    auto read_scale = [&](uint32_t addr, int i) __attribute__((always_inline)) -> v2u {
+        return *(lds_v2u)(uintptr_t)(addr + 256 * i);
     };
 
     v16f acc[4];
@@ -271,8 +293,7 @@ void w4a4_gemm_f6_kernel(const F6Params p)
 #pragma unroll
     for (int t = 0; t < 4; ++t) acc[t] = zf;
 
-    auto scale_tile = [&](uint32_t abits, uint32_t bbits) __attribute__((always_inline)) {
-        const v2u ta = {abits, 0u}, tb = {bbits, 0u};
+    auto scale_tile = [&](v2u ta, v2u tb) __attribute__((always_inline)) -> v16f {
         return __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_bit_cast(v4h, ta), __builtin_bit_cast(v4h, tb), zf, 0, 0, 0);
     };
     const int64_t m_w = (int64_t)au0 * 64 + wm * 64, n_w = (int64_t)wu0 * 64 + wn * 64;
@@ -289,72 +310,96 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         }
     };
 
-    const int G4 = p.G4;
     // ---- prologue: the first NST groups are requested, the first one has landed
 #pragma unroll
-    for (int v = 0; v < NST; ++v) request(v, v, v < G4);
+    for (int v = 0; v < NST; ++v) {
+        if (v < G4) {
+#pragma unroll
+            for (int k = 0; k < LPW; ++k) request_one(k, v, v);
+        } else {
+#pragma unroll
+            for (int k = 0; k < LPW; ++k) request_dummy();
+        }
+    }
     __builtin_amdgcn_s_waitcnt(wait_imm((NST - 1) * LPW));
     __syncthreads();
-    // carried from step to step: the fragments of sub-tile row 0 / column 0 and the scale bits of the
-    // coming step, and the integer and scale tiles of the last sub-tile of the step before
-    v6i af0[2], bf0[2];
-    uint32_t sa[2], sb[2];
-    {
-        const unsigned char *st = smem;
+    // carried from step to step: the fragments of sub-tile row 0 / column 0 and the scale operands of
+    // the coming step, and the integer and scale tiles of the last sub-tile of the step before
+    v12i af0 = read_pair(a_off, 0), bf0 = read_pair(b_off, 0);
+    v2u sa[2], sb[2];
 #pragma unroll
-        for (int s = 0; s < 2; ++s) { af0[s] = read_frag(st + a_unit, 0, s); bf0[s] = read_frag(st + b_unit, 0, s); }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            sa[i] = *reinterpret_cast<const uint32_t *>(st + sa_off + 128 * i);
-            const uint32_t wb = *reinterpret_cast<const uint32_t *>(st + sb_off + 128 * i);
-            sb[i] = g == 0 ? wb : 0u;          // zero on one side keeps k-slots 4..7 of the fp16 MFMA empty
-        }
+    for (int i = 0; i < 2; ++i) {
+        sa[i] = read_scale(sa_off, i);
+        sb[i] = read_scale(sb_off, i);
+        sb[i][0] = g == 0 ? sb[i][0] : 0u;     // zero on one side keeps k-slots 4..7 of the fp16 MFMA empty
     }
     v16f c_pend = zf, s_pend = zf;
     int  u_pend = -1;
 
     // One K-step = one INT4 group.  Twelve slots of one MFMA each, fenced so that the compiler keeps
     // their order.  Sub-tiles in the order (0,0) (1,0) (0,1) (1,1): column fragments 0 are free after
-    // the second sub-tile and row fragments 0 after the third, and are refilled from the next stage
-    // behind the barrier in the middle of the step.  The dequantisation of a sub-tile sits two slots
-    // behind its last MFMA.
-    // A step has no branch (one inside it lets the compiler sink MFMAs past the barrier): group
-    // u + NST is requested whether it exists or not (see `request`), so at the barrier the
-    // requests of NST - 2 groups may always remain in flight.
+    // the second sub-tile and row fragments 0 after the third, and are refilled from the next stage.
+    // Of the three slots of a sub-tile the first carries the step's memory instructions and address
+    // updates, the other two eight fused multiply-adds each of the sub-tile before (its last MFMA
+    // is two slots back by then): the vector ALU has about as much to do as the matrix pipe, and an
+    // in-order wavefront that meets more than 32 cycles of vector work between two MFMAs holds
+    // the matrix pipe up.  The barrier comes after the third slot: group u+1 has landed (each
+    // wavefront waited for its own share before it) and every read of stage u is complete (issued
+    // in the first slot), so from there on stage u is refilled with group u + NST, spread over
+    // three slots: issued in one burst the requests fill the address queue and hold up MFMAs.
+    // A step has no branch (one inside it lets the compiler sink MFMAs past the barrier): REAL says
+    // at compile time whether group u + NST exists.
     int cur = 0;                                // stage of group u
-    auto step = [&](int u) __attribute__((always_inline)) {
+    uint32_t a_cur = a_off, b_cur = b_off;      // lane addresses in stage `cur`
+    auto step = [&](int u, auto real_c) __attribute__((always_inline)) {
+        constexpr bool REAL = decltype(real_c)::value;
         const int nxt = cur + 1 == NST ? 0 : cur + 1;
-        const unsigned char *st  = smem + cur * STAGE;
-        const unsigned char *nst = smem + nxt * STAGE;
-        v6i af1[2], bf1[2];
+        // lane addresses in the next stage (they become the current ones of the next step)
+        const uint32_t a_nxt = a_off + nxt * STAGE, b_nxt = b_off + nxt * STAGE;
+        const uint32_t sa_nxt = sa_off + nxt * STAGE, sb_nxt = sb_off + nxt * STAGE;
+        v12i af1, bf1;
         v16f c0, c1, c2, c3, s0, s1, s2, s3;
-        uint32_t nsa[2], nsb[2];
+        v2u nsa[2], nsb[2];
+        int kreq = 0;                           // DMA instructions of this step issued so far
+        auto dma_slot = [&](int n) __attribute__((always_inline)) {
+#pragma unroll
+            for (int q = 0; q < n; ++q, ++kreq) {
+                if (kreq < LPW) {
+                    if (REAL) request_one(kreq, u + NST, cur);
+                    else      request_dummy();
+                }
+            }
+        };
+        constexpr int PER = (LPW + 2) / 3;      // per slot, over the three memory slots behind the barrier
         // slot 0
-        ATOM_F6_PIN(af0[0]);
-        c0 = mfma_f6(af0[0], bf0[0], zf);
+        ATOM_F6_PIN(af0);
+        c0 = mfma_f6<0>(af0, bf0, zf);
         ATOM_F6_PIN(c0);
-        af1[0] = read_frag(st + a_unit, 1, 0);
-        af1[1] = read_frag(st + a_unit, 1, 1);
+        af1 = read_pair(a_cur, 1);
+        bf1 = read_pair(b_cur, 1);
         ATOM_F6_SLOT_END();
         // slot 1
         ATOM_F6_PIN(sa[0]);
         s0 = scale_tile(sa[0], sb[0]);
         ATOM_F6_PIN(s0);
         dequant(u_pend, 1, 1, c_pend, s_pend, 0, 8);
-        bf1[0] = read_frag(st + b_unit, 1, 0);
-        bf1[1] = read_frag(st + b_unit, 1, 1);
         ATOM_F6_PIN(acc[3]);
         ATOM_F6_SLOT_END();
         // slot 2
-        c0 = mfma_f6(af0[1], bf0[1], c0);
+        c0 = mfma_f6<1>(af0, bf0, c0);
         ATOM_F6_PIN(c0);
         dequant(u_pend, 1, 1, c_pend, s_pend, 8, 16);
         ATOM_F6_PIN(acc[3]);
         ATOM_F6_SLOT_END();
+        __builtin_amdgcn_s_waitcnt(wait_imm((NST - 2) * LPW));
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
         // slot 3
-        ATOM_F6_PIN(af1[0]);
-        c1 = mfma_f6(af1[0], bf0[0], zf);
+        ATOM_F6_PIN(af1);
+        ATOM_F6_PIN(bf0);
+        c1 = mfma_f6<0>(af1, bf0, zf);
         ATOM_F6_PIN(c1);
+        dma_slot(PER);
         ATOM_F6_SLOT_END();
         // slot 4
         ATOM_F6_PIN(sa[1]);
@@ -364,23 +409,17 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         ATOM_F6_PIN(acc[0]);
         ATOM_F6_SLOT_END();
         // slot 5
-        c1 = mfma_f6(af1[1], bf0[1], c1);
+        c1 = mfma_f6<1>(af1, bf0, c1);
         ATOM_F6_PIN(c1);
         dequant(u, 0, 0, c0, s0, 8, 16);
         ATOM_F6_PIN(acc[0]);
         ATOM_F6_SLOT_END();
-        // group u+1 has landed (this wavefront's share; the barrier makes it everybody's), and this
-        // wavefront's reads of stage u are complete: after the barrier the stage may be refilled
-        __builtin_amdgcn_s_waitcnt(wait_imm((NST - 2) * LPW));
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        request(u + NST, cur, u + NST < G4);
         // slot 6
-        ATOM_F6_PIN(bf1[0]);
-        c2 = mfma_f6(af0[0], bf1[0], zf);
+        ATOM_F6_PIN(bf1);
+        c2 = mfma_f6<0>(af0, bf1, zf);
         ATOM_F6_PIN(c2);
-        bf0[0] = read_frag(nst + b_unit, 0, 0);
-        bf0[1] = read_frag(nst + b_unit, 0, 1);
+        bf0 = read_pair(b_nxt, 0);
+        dma_slot(PER);
         ATOM_F6_SLOT_END();
         // slot 7
         ATOM_F6_PIN(sb[1]);
@@ -390,22 +429,22 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         ATOM_F6_PIN(acc[2]);
         ATOM_F6_SLOT_END();
         // slot 8
-        c2 = mfma_f6(af0[1], bf1[1], c2);
+        c2 = mfma_f6<1>(af0, bf1, c2);
         ATOM_F6_PIN(c2);
         dequant(u, 1, 0, c1, s1, 8, 16);
         ATOM_F6_PIN(acc[2]);
         ATOM_F6_SLOT_END();
         // slot 9
-        ATOM_F6_PIN(af1[0]);
-        c3 = mfma_f6(af1[0], bf1[0], zf);
+        ATOM_F6_PIN(af1);
+        c3 = mfma_f6<0>(af1, bf1, zf);
         ATOM_F6_PIN(c3);
-        af0[0] = read_frag(nst + a_unit, 0, 0);
-        af0[1] = read_frag(nst + a_unit, 0, 1);
+        af0 = read_pair(a_nxt, 0);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            nsa[i] = *reinterpret_cast<const uint32_t *>(nst + sa_off + 128 * i);
-            nsb[i] = *reinterpret_cast<const uint32_t *>(nst + sb_off + 128 * i);
+            nsa[i] = read_scale(sa_nxt, i);
+            nsb[i] = read_scale(sb_nxt, i);
         }
+        dma_slot(LPW);                          // whatever is left
         ATOM_F6_SLOT_END();
         // slot 10
         ATOM_F6_PIN(sa[1]);
@@ -415,17 +454,23 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         ATOM_F6_PIN(acc[1]);
         ATOM_F6_SLOT_END();
         // slot 11
-        c3 = mfma_f6(af1[1], bf1[1], c3);
+        c3 = mfma_f6<1>(af1, bf1, c3);
         ATOM_F6_PIN(c3);
         dequant(u, 0, 1, c2, s2, 8, 16);
         ATOM_F6_PIN(acc[1]);
+        ATOM_F6_PIN(nsa[0]); ATOM_F6_PIN(nsa[1]); ATOM_F6_PIN(nsb[0]); ATOM_F6_PIN(nsb[1]);   // (keeps the wait for these reads down here)
         sa[0] = nsa[0]; sa[1] = nsa[1];
-        sb[0] = g == 0 ? nsb[0] : 0u; sb[1] = g == 0 ? nsb[1] : 0u;
+        sb[0] = nsb[0]; sb[1] = nsb[1];
+        sb[0][0] = g == 0 ? sb[0][0] : 0u; sb[1][0] = g == 0 ? sb[1][0] : 0u;
         ATOM_F6_SLOT_END();
         c_pend = c3; s_pend = s3; u_pend = u;
-        cur = nxt;
+        cur = nxt; a_cur = a_nxt; b_cur = b_nxt;
     };
-    for (int u = 0; u < G4; ++u) step(u);
+    {
+        int u = 0;
+        for (; u + NST < G4; ++u) step(u, std::true_type{});
+        for (; u < G4; ++u) step(u, std::false_type{});
+    }
     dequant(u_pend, 1, 1, c_pend, s_pend, 0, 16);
 
     // ---- the INT8 groups: INT8 MFMA, int32 tile converted to fp32, the same dequantisation
@@ -461,12 +506,12 @@ void w4a4_gemm_f6_kernel(const F6Params p)
             }
             __builtin_amdgcn_s_waitcnt(wait_imm(0));
             __syncthreads();
-            uint32_t qa[2], qb[2];
+            v2u qa[2], qb[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                qa[i] = *reinterpret_cast<const uint32_t *>(smem + a_unit8 + SC8 + 4 * r + 128 * i);
-                const uint32_t t = *reinterpret_cast<const uint32_t *>(smem + b_unit8 + SC8 + 4 * r + 128 * i);
-                qb[i] = g == 0 ? t : 0u;
+                qa[i] = *reinterpret_cast<const v2u *>(smem + a_unit8 + SC8 + 8 * r + 256 * i);
+                qb[i] = *reinterpret_cast<const v2u *>(smem + b_unit8 + SC8 + 8 * r + 256 * i);
+                qb[i][0] = g == 0 ? qb[i][0] : 0u;
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -529,7 +574,8 @@ hipError_t launch_f6_cfg(const F6Params &p, hipStream_t stream)
     static_assert(Gm::LPW * (Gm::NST - 1) <= 63, "vmcnt is a 6-bit counter");
     const int64_t TM = (p.a_units + WM - 1) / WM, TN = (p.w_units + 1) / 2;
     auto kern = &w4a4_gemm_f6_kernel<WM, DBG>;
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, Gm::LDS);
+    static atom_launch::LdsOptIn opt_in;   // one attribute call per kernel variant and device
+    hipError_t err = atom_launch::ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), Gm::LDS);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kern, dim3((unsigned)(TM * TN)), dim3(Gm::NT), Gm::LDS, stream, p);
     return hipGetLastError();
@@ -571,11 +617,15 @@ hipError_t launch_f6_gemm(const void *a_pk, int64_t M, const void *w_pk, int64_t
     p.a_units = (int)((M + 63) / 64); p.w_units = (int)((N + 63) / 64);
     p.G4 = (K - O) >> 7; p.G8 = O >> 7;
     p.ustride = (int64_t)p.G4 * IMG4 + (int64_t)p.G8 * IMG8;
-    if (partials) return launch_f6_cfg<4, true>(p, stream);
-    // 256-row tiles when they fill the compute units at least once; smaller tiles for fewer rows
-    if (M > 128) return launch_f6_cfg<4, false>(p, stream);
-    if (M > 64)  return launch_f6_cfg<2, false>(p, stream);
-    return launch_f6_cfg<1, false>(p, stream);
+    // 256-row tiles halve the weight traffic per row but want at least four rounds of tiles over the
+    // 256 compute units (measured: M = 4096 shapes of 1024 tiles and more are 5-7 % faster with
+    // them, M = 1024 shapes 4-15 % slower); 128-row tiles run two workgroups per compute unit,
+    // which hides one's prologue, barriers and store behind the other's K loop
+    const int64_t tiles256 = ((M + 255) / 256) * ((N + 127) / 128);
+    // (the dump of the integer sums runs the same tile shape as the plain call)
+    if (M > 128 && tiles256 >= 1024) return partials ? launch_f6_cfg<4, true>(p, stream) : launch_f6_cfg<4, false>(p, stream);
+    if (M > 64) return partials ? launch_f6_cfg<2, true>(p, stream) : launch_f6_cfg<2, false>(p, stream);
+    return partials ? launch_f6_cfg<1, true>(p, stream) : launch_f6_cfg<1, false>(p, stream);
 }
 
 }  // namespace atom_internal

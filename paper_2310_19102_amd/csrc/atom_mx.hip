@@ -18,12 +18,12 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include <type_traits>
 
 #include "atom_gemm_common.h"
 #include "atom_internal.h"
+#include "atom_launch.h"
 
 namespace {
 
@@ -73,267 +73,10 @@ __device__ __forceinline__ v8i join(v4i lo, v4i hi)
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
-// One K step per iteration: 64 bytes of every tile row, i.e. 64 FP8 channels (one MFMA per
-// tile pair; these outlier steps come first) or 128 FP4 channels (two MFMA sub-steps).  One wavefront per SIMD: the 16 accumulator tiles of a
-// wavefront (256 registers) live in the accumulation registers, everything else in the
-// architectural ones.  Global -> registers -> LDS with two LDS stages: while step u is
-// multiplied, step u+1 sits in the other stage and step u+2 is on its way into registers;
-// one barrier per step.
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void mx_gemm_kernel(MxParams p)
-{
-    extern __shared__ __align__(16) uint8_t smem[];
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
-    const int lr = lane & 31, g = lane >> 5;
-
-    const int tiles_m = (int)((p.M + BM - 1) / BM);
-    const int bid = atom_gemm::xcd_contiguous_block_id();
-    const int64_t m0 = (int64_t)(bid % tiles_m) * BM, n0 = (int64_t)(bid / tiles_m) * BN;
-
-    const int K4 = p.K - p.O;
-    const int S4 = K4 >> 7, S8 = p.O >> 6, S = S4 + S8;
-
-    // ---- loader: chunk id = tid + NT * i, row = id / 4 (A rows first), chunk = tid % 4.  The
-    // operands are stored step-major ([step][row][64 bytes]), so a step's 64 bytes of 16
-    // consecutive rows are one contiguous kilobyte and every cache line that is fetched is used.
-    // The scale dwords of the step's 512 rows ([K / 128][rows][4 bytes]) travel the same way,
-    // two per thread, into the 2 KB behind the codes of a stage.
-    const int ch = tid & 3;
-    uint32_t off[NLD];                                             // byte offset inside a step's slab
-    int dst[NLD];
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-        const int row = (tid + NT * i) >> 2;                       // i < NLD / 2: A rows, else B rows
-        int64_t r = i < NLD / 2 ? m0 + row : n0 + (row - BM);
-        const int64_t last = (i < NLD / 2 ? p.M : p.N) - 1;
-        r = r < last ? r : last;                                   // ragged tiles repeat the last row
-        off[i] = (uint32_t)r * ROWB + 16u * ch;
-        dst[i] = mx_lds_off(row, ch);
-    }
-    const uint32_t sca = (uint32_t)(m0 + tid < p.M ? m0 + tid : p.M - 1) * 4u;
-    const uint32_t scb = (uint32_t)(n0 + tid < p.N ? n0 + tid : p.N - 1) * 4u;
-    struct Regs { v4i v[NLD]; uint32_t sa, sb; };
-    // steps 0 .. S8-1 are the FP8 (outlier) steps, the FP4 steps follow: S8 is even, so the
-    // parity of a step is known at compile time wherever the two-step unrolling needs it
-    auto fetch = [&](int u, Regs &r) __attribute__((always_inline)) {
-        const bool    f8 = u < S8;
-        const int64_t sl = f8 ? u : u - S8;                        // slab index inside q8 or q4
-        const int64_t d  = f8 ? S4 + (u >> 1) : u - S8;            // slab index inside e8
-        const uint8_t *pa = (f8 ? p.a_q8 : p.a_q4) + sl * p.M * ROWB;
-        const uint8_t *pw = (f8 ? p.w_q8 : p.w_q4) + sl * p.N * ROWB;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i)
-            r.v[i] = *reinterpret_cast<const v4i *>((i < NLD / 2 ? pa : pw) + off[i]);
-        r.sa = *reinterpret_cast<const uint32_t *>(p.a_e8 + d * p.M * 4 + sca);
-        r.sb = *reinterpret_cast<const uint32_t *>(p.w_e8 + d * p.N * 4 + scb);
-    };
-    auto stage = [&](int buf, const Regs &r) __attribute__((always_inline)) {
-        uint8_t *st = smem + buf * STAGE;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) *reinterpret_cast<v4i *>(st + dst[i]) = r.v[i];
-        *reinterpret_cast<uint32_t *>(st + CODES + 4 * tid)          = r.sa;
-        *reinterpret_cast<uint32_t *>(st + CODES + 4 * (BM + tid))   = r.sb;
-    };
-
-    v16f acc[4][4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[s][t][v] = 0.0f;
-
-    // fragment addresses: A rows 128 wm + 32 s + lr, B rows BM + 128 wn + 32 t + lr.  Rows 32
-    // apart rotate alike, so sub-tiles are a constant 2048 bytes apart; chunk c + 2 is the
-    // xor of chunk c's offset with 32.
-    const int a_base = mx_lds_off(128 * wm + lr, g);
-    const int b_base = mx_lds_off(BM + 128 * wn + lr, g);
-    const int sa_off = CODES + 4 * (128 * wm + lr), sb_off = CODES + 4 * (BM + 128 * wn + lr);
-    // the four blocks of a row's 128 channels are the bytes of its scale dword; shifted by
-    // 8 g, the lane's own block of a sub-step sits in byte 0 or 2, which op_sel picks
-    int sa[4], sb[4];
-    auto read_scales = [&](const uint8_t *buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            sa[s] = (int)(*reinterpret_cast<const uint32_t *>(buf + sa_off + 128 * s) >> (8 * g));
-            sb[s] = (int)(*reinterpret_cast<const uint32_t *>(buf + sb_off + 128 * s) >> (8 * g));
-        }
-    };
-
-    // two register sets in flight: tile t travels in set t & 1, requested two steps before it is
-    // staged (one step of MFMAs is shorter than a trip to memory under load)
-    Regs regs[2];
-    fetch(0, regs[0]);
-    stage(0, regs[0]);
-    fetch(min(1, S - 1), regs[1]);
-    fetch(min(2, S - 1), regs[0]);
-    __syncthreads();
-
-    // 16 MFMAs on one set of fragments; format and scale byte are compile-time
-    auto mma16 = [&](auto fmt, auto opsel, const v8i (&af)[4], const v8i (&bf)[4], const int (&sa_)[4],
-                     const int (&sb_)[4]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-                acc[s][t] = mfma_mx<decltype(fmt)::value, decltype(opsel)::value>(af[s], bf[t], acc[s][t],
-                                                                                  sa_[s], sb_[t]);
-    };
-    // top of step u: tile u+1 goes from its register set into the other stage (last read in
-    // step u-1, before that step's barrier), tile u+3 leaves global memory into the same set.
-    // Nothing here is conditional (the last steps stage and fetch data nobody reads): with one
-    // path through the loop the compiler's wait counts let the loads of two steps stay in
-    // flight.  (Macros rather than lambdas that capture the lambdas above: closures nested
-    // that way keep the register arrays in scratch memory.)
-#define ATOM_MX_STAGE(u, SET) stage(((u) + 1) & 1, regs[SET])
-#define ATOM_MX_FETCH(u, SET) fetch(min((u) + 3, S - 1), regs[SET])
-#define ATOM_MX_ADVANCE(u, SET)                                                                  \
-    do {                                                                                         \
-        ATOM_MX_STAGE(u, SET);                                                                   \
-        ATOM_MX_FETCH(u, SET);                                                                   \
-    } while (0)
-    using fp4 = std::integral_constant<int, 4>;
-    using fp8 = std::integral_constant<int, 0>;
-    using b0  = std::integral_constant<int, 0>;
-    using b2  = std::integral_constant<int, 2>;
-
-    // ---- FP8 steps first, in pairs (64 channels each): the lane's low 16 bytes are chunk g
-    // (block 0 of the step), its high 16 bytes chunk 2 + g (block 1); it carries the scale of
-    // block g, byte 2 (step & 1) + g of the pair's dword
-    auto load8 = [&](const uint8_t *buf, v8i (&af8)[4], v8i (&bf8)[4]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            af8[s] = join(*reinterpret_cast<const v4i *>(buf + (a_base + 2048 * s)),
-                          *reinterpret_cast<const v4i *>(buf + ((a_base ^ 32) + 2048 * s)));
-            bf8[s] = join(*reinterpret_cast<const v4i *>(buf + (b_base + 2048 * s)),
-                          *reinterpret_cast<const v4i *>(buf + ((b_base ^ 32) + 2048 * s)));
-        }
-    };
-#define ATOM_MX_FP8_STEP(u, SET, OPSEL)                                                          \
-    do {                                                                                         \
-        ATOM_MX_ADVANCE(u, SET);                                                                 \
-        v8i af8[4], bf8[4];                                                                      \
-        load8(smem + ((u) & 1) * STAGE, af8, bf8);                                               \
-        read_scales(smem + ((u) & 1) * STAGE);                                                   \
-        mma16(fp8{}, OPSEL{}, af8, bf8, sa, sb);                                                 \
-        __syncthreads();                                                                         \
-    } while (0)
-    int u = 0;
-    for (; u < S8; u += 2) {              // tile u+1 is odd: set 1; tile u+2 even: set 0
-        ATOM_MX_FP8_STEP(u, 1, b0);
-        ATOM_MX_FP8_STEP(u + 1, 0, b2);
-    }
-#undef ATOM_MX_FP8_STEP
-
-    // ---- FP4 steps: two sub-steps of 64 channels, bytes [0,32) and [32,64) of the row; the
-    // lane takes chunk 2 k + g.  Software pipeline: the second sub-step's fragments are read
-    // under the first sub-step's MFMAs, the next step's first fragments and scales under the
-    // second's (the barrier that publishes the next stage sits between the two).
-    v8i af[4], bf[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {         // u is even here: stage 0
-        af[s] = widen(*reinterpret_cast<const v4i *>(smem + (a_base + 2048 * s)));
-        bf[s] = widen(*reinterpret_cast<const v4i *>(smem + (b_base + 2048 * s)));
-    }
-    read_scales(smem);
-#define ATOM_MX_RD(old, ptr) widen(*reinterpret_cast<const v4i *>(ptr))
-#define ATOM_MX_SYNC() __syncthreads()
-#define ATOM_MX_FP4_STEP(u, SET)                                                                 \
-    do {                                                                                         \
-        const uint8_t *buf = smem + ((u) & 1) * STAGE, *nbuf = smem + (((u) + 1) & 1) * STAGE;   \
-        ATOM_MX_ADVANCE(u, SET);                                                                 \
-        v8i ag[4], bg[4];                                                                        \
-        _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                          \
-            ag[s] = ATOM_MX_RD(af[s], buf + ((a_base ^ 32) + 2048 * s));                         \
-            bg[s] = ATOM_MX_RD(bf[s], buf + ((b_base ^ 32) + 2048 * s));                         \
-        }                                                                                        \
-        mma16(fp4{}, b0{}, af, bf, sa, sb);                                                      \
-        /* the eight reads go out under the first eight MFMAs, the other eight cover them */    \
-        _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                          \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); /* one MFMA */                    \
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); /* one LDS read */                \
-        }                                                                                        \
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                       \
-        ATOM_MX_SYNC(); /* stage u+1 is complete, stage u has been read */                       \
-        __builtin_amdgcn_sched_barrier(0);                                                       \
-        /* (after the last step these reads fetch bytes that are not used) */                    \
-        int sc[4], sd[4];                                                                        \
-        _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                          \
-            sc[s] = sa[s];                                                                       \
-            sd[s] = sb[s];                                                                       \
-            af[s] = ATOM_MX_RD(af[s], nbuf + (a_base + 2048 * s));                               \
-            bf[s] = ATOM_MX_RD(bf[s], nbuf + (b_base + 2048 * s));                               \
-        }                                                                                        \
-        read_scales(nbuf);                                                                       \
-        mma16(fp4{}, b2{}, ag, bg, sc, sd);                                                      \
-        _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                          \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);                                   \
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);                                   \
-        }                                                                                        \
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 1);                                       \
-        __builtin_amdgcn_sched_barrier(0);                                                       \
-    } while (0)
-    for (; u + 1 < S; u += 2) {
-        ATOM_MX_FP4_STEP(u, 1);
-        ATOM_MX_FP4_STEP(u + 1, 0);
-    }
-    if (u < S) ATOM_MX_FP4_STEP(u, 1);
-#undef ATOM_MX_FP4_STEP
-#undef ATOM_MX_ADVANCE
-
-    // ---- store: lane holds column lr of sub-tile t, rows 8 (v / 4) + 4 g + v % 4 of sub-tile s.
-    const int64_t wrow = m0 + 128 * wm, wcol = n0 + 128 * wn;      // this wavefront's 128 x 128 block
-    const bool whole = wrow + 128 <= p.M && wcol + 128 <= p.N && (p.ldy & 7) == 0 &&
-                       (reinterpret_cast<uintptr_t>(p.y) & 15) == 0;
-    __syncthreads();                                               // the stages are dead from here on
-    if (whole) {
-        // Through LDS, so that global memory sees whole 16-byte pieces of rows (2-byte stores
-        // straight from the accumulator layout cost several times the K loop of a tile): two
-        // passes of 64 rows; a wavefront's region is 64 rows x 128 columns of fp16, rows 272
-        // bytes apart (the pad keeps the two row groups of a write on different banks).
-        uint8_t *reg = smem + wave * EPI_WAVE;
-#pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
-#pragma unroll
-            for (int sh = 0; sh < 2; ++sh)
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int r = 32 * sh + 8 * (v >> 2) + 4 * g + (v & 3);
-                        *reinterpret_cast<uint16_t *>(reg + r * EPI_PITCH + 2 * (32 * t + lr)) =
-                            __half_as_ushort(__float2half_rn(acc[2 * pass + sh][t][v]));
-                    }
-            // 16 lanes per row: lane l takes columns 8 (l % 16) .. +7 of rows l / 16 + 4 i
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int r = 4 * i + (lane >> 4);
-                const v4i d = *reinterpret_cast<const v4i *>(reg + r * EPI_PITCH + 16 * (lane & 15));
-                *reinterpret_cast<v4i *>(p.y + (wrow + 64 * pass + r) * p.ldy + wcol + 8 * (lane & 15)) = d;
-            }
-        }
-    } else {
-        // ragged edge tiles: element by element
-        const int64_t row0 = wrow + 4 * g, col0 = wcol + lr;
-        uint16_t *yp = p.y + row0 * p.ldy + col0;
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int dr = 32 * s + 8 * (v >> 2) + (v & 3);
-                if (row0 + dr < p.M) {
-                    uint16_t *yr = yp + (int64_t)dr * p.ldy;
-#pragma unroll
-                    for (int t = 0; t < 4; ++t)
-                        if (col0 + 32 * t < p.N) yr[32 * t] = __half_as_ushort(__float2half_rn(acc[s][t][v]));
-                }
-            }
-    }
-}
-
-// The same GEMM with the operands going from global memory straight into LDS
+// One K step per iteration: 64 bytes of every tile row, i.e. 64 FP8 channels (one MFMA per tile
+// pair; these outlier steps come first) or 128 FP4 channels (two MFMA sub-steps).  The accumulator
+// tiles of a wavefront live in the accumulation registers, everything else in the architectural
+// ones.  The operands go from global memory straight into LDS
 // (global_load_lds_dwordx4: lane i's 16 bytes land at the LDS address in M0 plus 16 i), so no
 // wavefront spends issue slots on staging registers and ds_write.  Four stages: while step u
 // is multiplied, tile u+1 has landed or is landing, tile u+2 is on its way and tile u+3 is
@@ -501,7 +244,8 @@ void mx_gemm_dma_kernel(MxParams p)
     }
 #undef ATOM_MX_FP8_STEP
 
-    // ---- FP4 steps, software-pipelined as in mx_gemm_kernel
+    // ---- FP4 steps, software-pipelined: the second sub-step's fragments are read under the first
+    // sub-step's MFMAs, the next step's first fragments and scales under the second's
     v8i af[WT], bf[WT];
 #pragma unroll
     for (int s = 0; s < WT; ++s) {
@@ -551,8 +295,8 @@ void mx_gemm_dma_kernel(MxParams p)
 #undef ATOM_MX_ROTATE
 #undef ATOM_MX_LANDED
 
-    // ---- store, as in mx_gemm_kernel; the last (repeated) requests must have landed before the
-    // stages are reused
+    // ---- store: through LDS, so that global memory sees 16-byte row pieces; the last (repeated)
+    // requests must have landed before the stages are reused
     __builtin_amdgcn_s_waitcnt(0x0F70);                            // vmcnt(0)
     const int64_t wrow = m0 + 32 * WT * wm, wcol = n0 + 32 * WT * wn;
     const bool whole = wrow + 32 * WT <= p.M && wcol + 32 * WT <= p.N && (p.ldy & 7) == 0 &&
@@ -612,36 +356,18 @@ hipError_t launch_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8, 
     p.w_q4 = (const uint8_t *)w_q4; p.w_q8 = (const uint8_t *)w_q8; p.w_e8 = (const uint8_t *)w_e8;
     p.y = (uint16_t *)y; p.M = M; p.N = N; p.ldy = ldy; p.K = K; p.O = O;
     const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-    static const bool use_regs = getenv("ATOM_MX_NO_DMA") != nullptr;   // the register-staged kernel, for comparison
-    if (use_regs) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-            if (err != hipSuccess) return err;
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(mx_gemm_kernel, dim3((unsigned)tiles), dim3(NT), LDS_BYTES, stream, p);
-    } else if (tiles >= 192) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_dma_kernel<4>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, DmaGeom<4>::LDS);
-            if (err != hipSuccess) return err;
-            attr_set = true;
-        }
+    if (tiles >= 192) {
+        static atom_launch::LdsOptIn opt_in;
+        hipError_t err = atom_launch::ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(&mx_gemm_dma_kernel<4>), DmaGeom<4>::LDS);
+        if (err != hipSuccess) return err;
         hipLaunchKernelGGL(mx_gemm_dma_kernel<4>, dim3((unsigned)tiles), dim3(NT), DmaGeom<4>::LDS, stream, p);
     } else {
         // fewer 256 x 256 tiles than would occupy three quarters of the CUs: 128 x 128 tiles, two
         // workgroups per CU (measured on M = 1024, K = 11008, N = 4096: 82 -> 40 us)
         const int64_t small = ((M + 127) / 128) * ((N + 127) / 128);
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(&mx_gemm_dma_kernel<2>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, DmaGeom<2>::LDS);
-            if (err != hipSuccess) return err;
-            attr_set = true;
-        }
+        static atom_launch::LdsOptIn opt_in;
+        hipError_t err = atom_launch::ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(&mx_gemm_dma_kernel<2>), DmaGeom<2>::LDS);
+        if (err != hipSuccess) return err;
         hipLaunchKernelGGL(mx_gemm_dma_kernel<2>, dim3((unsigned)small), dim3(NT), DmaGeom<2>::LDS, stream, p);
     }
     return hipGetLastError();

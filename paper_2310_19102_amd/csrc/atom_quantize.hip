@@ -24,6 +24,7 @@
 #include <stdint.h>
 
 #include "atom_internal.h"
+#include "atom_launch.h"
 
 namespace {
 
@@ -515,23 +516,12 @@ template <bool NORM, int NS, int NT, int PRE>
 hipError_t launch_fast(const QuantArgs &a, size_t lds, hipStream_t stream)
 {
     auto kern = &quantize_rows_fast_kernel<NORM, NS, NT, PRE>;
-    static size_t allowed = 0;        // the opt-in for more than 64 KB of dynamic LDS
-    if (lds > allowed) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (err != hipSuccess) return err;
-        allowed = lds;
-    }
+    static atom_launch::LdsOptIn opt_in;   // the opt-in for more than 64 KB of dynamic LDS
+    hipError_t err = atom_launch::ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), lds);
+    if (err != hipSuccess) return err;
     // workgroups resident per CU (LDS- and wave-limited), then rows dealt evenly over one
     // wave of them
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            n = 256;
-        cus = n;
-    }
+    const int cus = atom_launch::compute_units();
     int64_t per_cu = (int64_t)(160 * 1024) / (int64_t)(lds > 0 ? lds : 1);
     const int64_t by_waves = 2048 / NT;                 // 32 wavefronts per CU
     per_cu = per_cu < 1 ? 1 : (per_cu > by_waves ? by_waves : per_cu);
@@ -551,13 +541,9 @@ hipError_t launch_plain(const QuantArgs &a, size_t lds, hipStream_t stream)
     auto kern = &quantize_rows_kernel<NORM, PRE>;
     const int grid = (int)(a.rows < (int64_t)1 << 20 ? a.rows : (int64_t)1 << 20);
     // the opt-in for more than 64 KB of dynamic LDS is raised only when a call needs more
-    static size_t allowed = 0;
-    if (lds > allowed) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (err != hipSuccess) return err;
-        allowed = lds;
-    }
+    static atom_launch::LdsOptIn opt_in;
+    hipError_t err = atom_launch::ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), lds);
+    if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, (const __half *)a.x, a.rows,
                        a.ld, (const __half *)a.res, a.ldr, (__half *)a.sum_out, a.ldo,
                        (const __half *)a.gamma, a.eps, a.idx, a.K, a.O, a.nbits, a.clip, (uint8_t *)a.q4,
@@ -590,13 +576,9 @@ hipError_t launch_quantize_rows_mx(const void *x, int64_t rows, int64_t ld, cons
     const bool   norm = gamma != nullptr;
     const size_t lds  = quantize_lds_bytes(K, norm);
     auto kern = norm ? &quantize_rows_kernel<true, kPlain, true> : &quantize_rows_kernel<false, kPlain, true>;
-    static size_t allowed[2] = {0, 0};
-    if (lds > allowed[norm]) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (err != hipSuccess) return err;
-        allowed[norm] = lds;
-    }
+    static atom_launch::LdsOptIn opt_in[2];
+    hipError_t err = atom_launch::ensure_dynamic_lds(opt_in[norm], reinterpret_cast<const void *>(kern), lds);
+    if (err != hipSuccess) return err;
     const int grid = (int)(rows < (int64_t)1 << 20 ? rows : (int64_t)1 << 20);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, (const __half *)x, rows, ld,
                        (const __half *)nullptr, (int64_t)0, (__half *)nullptr, (int64_t)0,

@@ -150,3 +150,59 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
+
+
+def test_gemm_refuses_shapes_beyond_its_32_bit_offsets():
+    """The tiled kernels index the code and scale arrays with 32-bit offsets: shapes whose arrays
+    reach 4 GiB are refused on the host, before any launch (fake pointers, never dereferenced)."""
+    lib = atom.load_library()
+    D = binding._Desc
+    p = ctypes.c_void_p(0x1000)
+    g = lib.atom_w4a4_gemm
+    d = D(32768, 128, 128, 4, 8)
+    rows = (1 << 32) // ((32768 - 128) // 2) + 1                     # rows * K4 / 2 >= 2^32
+    assert g(p, p, p, rows, p, p, p, 128, ctypes.byref(d), p, 128, None, None, 0, None) == 3
+    assert g(p, p, p, 128, p, p, p, rows, ctypes.byref(d), p, rows, None, None, 0, None) == 3
+    d = D(256, 128, 128, 4, 8)                                        # tiny K: the tile count overflows first
+    big = 1 << 24
+    assert g(p, p, p, big, p, p, p, big, ctypes.byref(d), p, big, None, None, 0, None) == 3
+
+
+def test_packed_gemm_argument_validation():
+    lib = atom.load_library()
+    D = binding._Desc
+    p = ctypes.c_void_p(0x1000)
+    ok = D(4096, 128, 128, 4, 8)
+    nbytes = lib.atom_pack_weight_bytes(4096, ctypes.byref(ok))
+    assert nbytes == 64 * (31 * 6656 + 8704)                         # 64 units of 64 rows, 31 INT4 images and one INT8 image each
+    assert lib.atom_pack_weight_bytes(4097, ctypes.byref(ok)) == 65 * (31 * 6656 + 8704)
+    assert lib.atom_pack_weight_bytes(0, ctypes.byref(ok)) == 0
+    assert lib.atom_pack_weight_bytes(4096, ctypes.byref(D(4096, 64, 128, 4, 8))) == 0
+    pk = lib.atom_pack_weight
+    assert pk(None, p, p, 4096, ctypes.byref(ok), p, nbytes, None) == 1
+    assert pk(p, p, p, 4096, ctypes.byref(ok), p, nbytes - 1, None) == 5
+    assert pk(p, p, p, 4096, ctypes.byref(ok), ctypes.c_void_p(0x1010), nbytes, None) == 4
+    assert pk(p, p, p, -1, ctypes.byref(ok), p, nbytes, None) == 2
+    assert pk(p, p, p, 0, ctypes.byref(ok), p, 0, None) == 0
+    assert pk(p, p, p, 65536 * 64, ctypes.byref(ok), p, 1 << 62, None) == 3
+    g = lib.atom_w4a4_gemm_packed
+    need = lib.atom_w4a4_gemm_packed_workspace_bytes(256, 4096, ctypes.byref(ok))
+    assert need == 4 * (31 * 6656 + 8704)
+    assert g(p, p, p, 256, p, 4096, ctypes.byref(ok), p, 4096, None, None, 0, None) == 5
+    assert g(p, p, p, 256, p, 4096, ctypes.byref(ok), p, 4096, None, p, need - 1, None) == 5
+    assert g(p, p, p, 256, p, 4096, ctypes.byref(ok), p, 4000, None, p, need, None) == 2
+    assert g(p, p, p, 256, None, 4096, ctypes.byref(ok), p, 4096, None, p, need, None) == 1
+    assert g(p, p, p, 0, p, 4096, ctypes.byref(ok), p, 4096, None, p, need, None) == 0
+    assert g(p, p, p, 256, p, 4096, ctypes.byref(ok), p, 4096, None, ctypes.c_void_p(0x1010), need, None) == 4
+
+
+def test_static_scratch_entry_point_validation():
+    lib = atom.load_library()
+    p = ctypes.c_void_p(0x1000)
+    st = lib.atom_decode_attention_kv4_static
+    f = ctypes.c_float(1.0)
+    assert lib.atom_static_scratch_bytes() == 4 << 20
+    assert st(p, 0, 32, 32, 128, 64, p, p, p, p, p, p, p, f, p, None) == 0           # B == 0
+    assert st(p, 1, 32, 5, 128, 64, p, p, p, p, p, p, p, f, p, None) == 2            # H % Hkv
+    assert st(p, 1, 32, 32, 64, 64, p, p, p, p, p, p, p, f, p, None) == 3            # D
+    assert st(p, 1, 1024, 64, 128, 1 << 20, p, p, p, p, p, p, p, f, p, None) == 5    # partials beyond the array
