@@ -434,6 +434,21 @@ atom_status atom_calibrate_reorder(const void *x_f16, int64_t T, int64_t ldx,
                                    void *stream);
 size_t atom_calibrate_reorder_workspace_bytes(int64_t T, int32_t K);
 
+/*
+ * Measurement helper, not a step of the method (the roofline of Section 3 is
+ * priced against the matrix units' peak; this quotes what the device sustains):
+ * launches a kernel that issues nothing but independent matrix instructions,
+ * 4 * iters per wavefront on 4096 wavefronts -- kind 0: INT8 32x32x32 (the
+ * canonical GEMM kernels and the outlier group), kind 1: FP6 32x32x64 (the
+ * INT4 groups of the packed GEMM) -- and returns the number of integer /
+ * floating-point operations of the launch (2 per multiply-add); time the
+ * launch on `stream` and divide.  scratch4: 4 writable device bytes.  *status
+ * (may be NULL) receives ATOM_ERR_SHAPE (kind, iters <= 0), ATOM_ERR_NULL,
+ * ATOM_ERR_ALIGN or ATOM_ERR_HIP, and the return value is then 0.
+ */
+double atom_mfma_rate_probe(int32_t kind, int32_t iters, void *scratch4,
+                            void *stream, atom_status *status);
+
 /* Host helper: ATOM_OK iff idx_host[0..K) is a permutation of 0..K-1. */
 atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K);
 

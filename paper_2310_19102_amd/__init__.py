@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     atom_decode_attention_kv4_static,
     atom_static_scratch_bytes,
     atom_status_string,
+    atom_mfma_rate_probe,
     atom_w4a4_gemm,
     atom_w4a4_gemm_workspace_bytes,
     atom_pack_weight,

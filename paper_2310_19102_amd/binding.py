@@ -39,6 +39,7 @@ EXPORTS = (
     "atom_decode_attention_kv4_workspace_bytes",
     "atom_decode_attention_kv4_static",
     "atom_static_scratch_bytes",
+    "atom_mfma_rate_probe",
     "atom_check_reorder_idx",
     "atom_status_string",
 )
@@ -121,6 +122,8 @@ def load_library():
                                                    f32, vp, vp]
     L.atom_static_scratch_bytes.restype = sz
     L.atom_static_scratch_bytes.argtypes = []
+    L.atom_mfma_rate_probe.restype = ctypes.c_double
+    L.atom_mfma_rate_probe.argtypes = [i32, i32, vp, vp, ctypes.POINTER(ctypes.c_int)]
     L.atom_check_reorder_idx.restype = ctypes.c_int
     L.atom_check_reorder_idx.argtypes = [vp, ctypes.c_int32]
     L.atom_status_string.restype = ctypes.c_char_p
@@ -147,6 +150,16 @@ def _dev(t: torch.Tensor, dtype, name: str):
     if t.dtype != dtype:
         raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
     return t
+
+
+def atom_mfma_rate_probe(kind: int, iters: int, scratch: torch.Tensor) -> float:
+    """Launch the MFMA-only loop (0: INT8 32x32x32, 1: FP6 32x32x64) on the current stream; returns
+    the operations of the launch."""
+    st = ctypes.c_int(0)
+    ops = load_library().atom_mfma_rate_probe(kind, iters, _ptr(scratch), _stream(), ctypes.byref(st))
+    if st.value != 0:
+        raise AtomError(st.value, "atom_mfma_rate_probe")
+    return float(ops)
 
 
 def atom_status_string(status: int) -> str:

@@ -432,6 +432,22 @@ atom_status atom_calibrate_reorder(const void *x_f16, int64_t T, int64_t ldx, in
 
 extern "C" {
 
+double atom_mfma_rate_probe(int32_t kind, int32_t iters, void *scratch4, void *stream, atom_status *status)
+{
+    atom_status st = ATOM_OK;
+    double ops = 0.0;
+    if ((kind != 0 && kind != 1) || iters <= 0) st = ATOM_ERR_SHAPE;
+    else if (!scratch4) st = ATOM_ERR_NULL;
+    else if (!aligned(scratch4, 4)) st = ATOM_ERR_ALIGN;
+    else {
+        st = atom_internal::launch_mfma_rate_probe(kind, iters, scratch4, static_cast<hipStream_t>(stream)) == hipSuccess
+                 ? ATOM_OK : ATOM_ERR_HIP;
+        if (st == ATOM_OK) ops = atom_internal::mfma_rate_probe_ops(kind, iters);
+    }
+    if (status) *status = st;
+    return ops;
+}
+
 atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K)
 {
     if (!idx_host) return ATOM_ERR_NULL;

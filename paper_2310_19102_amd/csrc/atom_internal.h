@@ -42,6 +42,10 @@ hipError_t launch_f6_pack(const void *q4, const void *q8, const void *scale, int
 hipError_t launch_f6_gemm(const void *a_pk, int64_t M, const void *w_pk, int64_t N, int K, int O, void *y,
                           int64_t ldy, int32_t *partials, hipStream_t stream);
 
+// Measurement helper (atom_probe.hip): a loop of MFMAs only; kind 0 = INT8 32x32x32, 1 = FP6 32x32x64.
+double     mfma_rate_probe_ops(int kind, int iters);
+hipError_t launch_mfma_rate_probe(int kind, int iters, void *out, hipStream_t stream);
+
 // MX variant: front end (FP4 / FP8 codes, E8M0 scale byte per 32 channels) and GEMM on the
 // scaled FP8/FP6/FP4 MFMA.
 hipError_t launch_quantize_rows_mx(const void *x, int64_t rows, int64_t ld, const void *gamma,
