@@ -334,7 +334,9 @@ void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
     const int G4   = K4 >> 7;
 
     // gather offsets (bytes into ybuf) of this lane's 8 channels in each of its groups
-    uint32_t off[NS][8];
+    // (with 1024 threads two 16-bit channel numbers share a register)
+    constexpr bool OPACK = NT >= 1024;
+    uint32_t off[NS][OPACK ? 4 : 8];
 #pragma unroll
     for (int j = 0; j < NS; ++j) {
         const int g  = 4 * wave + (lane >> 4) + (NT / 16) * j;
@@ -344,10 +346,18 @@ void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
         const int4 i1 = *reinterpret_cast<const int4 *>(idx + j0 + 4);
         const int id[8] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) off[j][e] = 4u * min((unsigned)id[e], (unsigned)(K - 1));
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t c = min((unsigned)id[e], (unsigned)(K - 1));
+            if (!OPACK)          off[j][e] = 4u * c;
+            else if (e % 2 == 0) off[j][e / 2] = c;
+            else                 off[j][e / 2] |= c << 16;
+        }
     }
-    uint4 graw[NORM ? NS : 1];
-    if (NORM) {
+    // gamma stays in registers too, except with 1024 threads (128 registers per lane):
+    // there each row re-reads it through the cache
+    constexpr bool GREG = NT < 1024;
+    uint4 graw[NORM && GREG ? NS : 1];
+    if (NORM && GREG) {
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
             const int v = tid + NT * i;
@@ -419,7 +429,7 @@ void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
                 }
                 if (NORM) {
                     float g[8];
-                    halves_to_floats(graw[i], g);
+                    halves_to_floats(GREG ? graw[i] : *reinterpret_cast<const uint4 *>(gamma + 8 * v), g);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) f[e] = (f[e] * r) * g[e];
                 }
@@ -442,7 +452,14 @@ void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
             float amax = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                y[e] = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(ybuf) + off[j][e]);
+                uint32_t o = off[j][OPACK ? e / 2 : e];
+                if (OPACK) {
+                    // unpacked here, per row: hoisted out of the row loop the unpacked
+                    // offsets would take the registers the packing saves
+                    asm volatile("" : "+v"(o));
+                    o = e % 2 ? (o >> 16) << 2 : (o & 0xffffu) << 2;
+                }
+                y[e] = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(ybuf) + o);
                 amax = fmaxf(amax, fabsf(y[e]));
             }
             amax = row16_max_dpp(amax);
@@ -556,14 +573,18 @@ hipError_t dispatch_quantize(const QuantArgs &a, hipStream_t stream)
 {
     const size_t lds = quantize_lds_bytes(a.K, NORM);
     // The fast kernel keeps ceil(K / (8 * threads)) gather-offset sets in registers and
-    // relies on a sane clip; rows of 8192 channels and more are spread over 512 threads.
-    if (a.K <= 16384 && a.clip >= 9.5367431640625e-07f && a.clip <= 1.0f) {
+    // relies on a sane clip; rows of 8192 channels and more are spread over 512 threads,
+    // rows beyond 16384 channels over 1024 (one workgroup per CU: the staged row fills
+    // most of the LDS).
+    if (a.K <= 32768 && a.clip >= 9.5367431640625e-07f && a.clip <= 1.0f) {
         if (a.K <= 2048)  return launch_fast<NORM, 1, 256, PRE>(a, lds, stream);
         if (a.K <= 4096)  return launch_fast<NORM, 2, 256, PRE>(a, lds, stream);
         if (a.K < 8192)   return launch_fast<NORM, 4, 256, PRE>(a, lds, stream);
         if (a.K <= 8192)  return launch_fast<NORM, 2, 512, PRE>(a, lds, stream);
         if (a.K <= 12288) return launch_fast<NORM, 3, 512, PRE>(a, lds, stream);
-        return launch_fast<NORM, 4, 512, PRE>(a, lds, stream);
+        if (a.K <= 16384) return launch_fast<NORM, 4, 512, PRE>(a, lds, stream);
+        if (a.K <= 24576) return launch_fast<NORM, 3, 1024, PRE>(a, lds, stream);
+        return launch_fast<NORM, 4, 1024, PRE>(a, lds, stream);
     }
     return launch_plain<NORM, PRE>(a, lds, stream);
 }

@@ -69,6 +69,7 @@ def test_config1_tiny():
     (200, 1152, 300, 256, True),   # two wavefront sets, two INT8 groups, odd/even split of the steps
     (1200, 256, 3000, 128, False), # 128x128 tiles, one set, minimal K (one INT4 + one INT8 group)
     (5, 12416, 24, 128, True),     # front end with eight register sets of gather offsets (K > 12288)
+    (520, 28672, 24, 128, True),   # front end on 1024 threads per row (K > 16384), several rows per workgroup
     (8, 11008, 40, 128, False),    # decode kernel at the Llama-7B down projection: 86 groups = 21.5 blocks of four
     (16, 5120, 48, 128, True),     # 40 groups (Llama-13B): five blocks over eight wavefronts, three of them idle
     (40, 2560, 32, 128, True),     # four row blocks, 20 groups
@@ -104,8 +105,7 @@ def test_degenerate_values():
 
 def test_front_end_plain_and_fast_kernels_agree():
     """The front end has a fast kernel (shared reciprocal refinement for the division) and a
-    plain one (compiler-generated IEEE division) that takes over for clip < 2^-20 and for
-    K > 16384; both must give the oracle's codes and scales, whose division is the C
+    plain one (compiler-generated IEEE division) that takes over for clip < 2^-20; both must give the oracle's codes and scales, whose division is the C
     compiler's.  Values chosen so that quotients land on and next to rounding ties."""
     lin = _rand_linear(6, 1024, 32, 128, seed=11, norm=False)
     # rows of exact multiples of half a quantisation step: every quotient is a tie or an integer
@@ -123,7 +123,8 @@ def test_front_end_plain_and_fast_kernels_agree():
     (33, 4096, 128, True, 0.9),      # the Llama-7B hidden size
     (9, 11008, 128, False, 0.9),     # 512 threads per row
     (3000, 512, 256, True, 1.0),     # several rows per workgroup: the next row is prefetched
-    (4, 20480, 128, True, 0.9),      # K > 16384: the plain kernel
+    (4, 20480, 128, True, 0.9),      # K > 16384: 1024 threads per row, three register sets
+    (530, 28672, 128, True, 0.9),    # the Llama-70B intermediate size, four sets, rows prefetched
     (5, 1024, 128, False, 1e-8),     # clip below 2^-20: the plain kernel
 ])
 def test_add_quantize_act(M, K, O, norm, clip):
@@ -187,7 +188,8 @@ def test_add_quantize_act_strided_and_errors():
     (7, 512, 128, 0.9),
     (33, 11008, 128, 0.9),           # the Llama-7B intermediate size, 512 threads per row
     (3000, 256, 128, 1.0),           # several rows per workgroup
-    (4, 20480, 256, 0.9),            # K > 16384: the plain kernel
+    (4, 20480, 256, 0.9),            # K > 16384: 1024 threads per row, three register sets
+    (530, 28672, 128, 0.9),          # the Llama-70B intermediate size, four sets, rows prefetched
     (5, 1024, 128, 1e-8),            # clip below 2^-20: the plain kernel
 ])
 def test_swiglu_quantize_act(M, K, O, clip):

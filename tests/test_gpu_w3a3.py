@@ -26,7 +26,7 @@ def _inputs(M, K, N, seed, norm):
     (1, 512, 64, 128, True),         # single token, decode GEMM
     (33, 1024, 200, 256, True),      # ragged M and N, two INT8 groups
     (70, 1408, 130, 128, False),     # 11 groups, big-tile GEMM
-    (9, 20480, 24, 128, True),       # K > 16384: the plain front-end kernel
+    (9, 20480, 24, 128, True),       # K > 16384: 1024 threads per row in the front end
 ])
 def test_w3a3_linear(M, K, N, O, norm):
     x, w, gamma, idx = _inputs(M, K, N, 31 * M + K, norm)
