@@ -233,6 +233,29 @@ def step_summary(config, steps=100, warmup=10):
     return out
 
 
+def decode_sweep():
+    """Decode-sized GEMMs against the HBM roofline: config 3's eight shapes and the fused gate/up
+    projection at M = 8, weights walked through a ring of copies > 1 GB."""
+    out = []
+    sweep = [synth.make(3, w) for w in range(len(synth.CONFIG_SHAPES[3]))]
+    sweep.append(synth.llama_linear("decode_m8_n22016", 8, 4096, 22016, 3, tensor_base=90))
+    for lin in sweep:
+        row = (lin.K - lin.n_outlier) // 2 + lin.n_outlier + 2 * (lin.K // lin.group_size)
+        copies = max(2, int(1.2e9 // (lin.N * row)) + 1)
+        L = DeviceLinear(lin, n_weight_copies=copies)
+        per = decode_gemm_in_graph(L, copies)
+        t, ge, fe, pk, _ = run_steps([L], 100, 10, 0.02)
+        out.append({"workload": f"config3 decode M={lin.M} K=4096 N={lin.N}, weight ring of {copies}",
+                    "gemm_us_in_graph": per * 1e6, "gemm_bytes": L.gemm_bytes,
+                    "gemm_GBs": L.gemm_bytes / per / 1e9,
+                    "gemm_hbm_frac": L.gemm_bytes / per / 1e9 / PEAK_HBM_GBS,
+                    "step_us_front_end_plus_gemm": t * 1e6,
+                    "effective_tops": L.ops / t / 1e12})
+        del L
+        torch.cuda.empty_cache()
+    return out
+
+
 def extra_measurements(headline_config):
     """Context lines beside the headline: the other large configuration, the M=256 attention
     projection, and the decode-sized GEMM sweep against the HBM roofline (weights walked through a
@@ -257,23 +280,7 @@ def extra_measurements(headline_config):
                 "gemm_frac_of_int8_mfma_peak": L.ops / ge / 1e12 / PEAK_INT8_TOPS})
     del L
     torch.cuda.empty_cache()
-    # decode sweep: config 3's eight shapes and the fused gate/up projection at M = 8
-    sweep = [synth.make(3, w) for w in range(len(synth.CONFIG_SHAPES[3]))]
-    sweep.append(synth.llama_linear("decode_m8_n22016", 8, 4096, 22016, 3, tensor_base=90))
-    for lin in sweep:
-        row = (lin.K - lin.n_outlier) // 2 + lin.n_outlier + 2 * (lin.K // lin.group_size)
-        copies = max(2, int(1.2e9 // (lin.N * row)) + 1)
-        L = DeviceLinear(lin, n_weight_copies=copies)
-        per = decode_gemm_in_graph(L, copies)
-        t, ge, fe, pk, _ = run_steps([L], 100, 10, 0.02)
-        out.append({"workload": f"config3 decode M={lin.M} K=4096 N={lin.N}, weight ring of {copies}",
-                    "gemm_us_in_graph": per * 1e6, "gemm_bytes": L.gemm_bytes,
-                    "gemm_GBs": L.gemm_bytes / per / 1e9,
-                    "gemm_hbm_frac": L.gemm_bytes / per / 1e9 / PEAK_HBM_GBS,
-                    "step_us_front_end_plus_gemm": t * 1e6,
-                    "effective_tops": L.ops / t / 1e12})
-        del L
-        torch.cuda.empty_cache()
+    out.extend(decode_sweep())
     # the front end alone, plain and behind the fused residual add, against the HBM roofline
     for (cfg, which) in ((4, 0), (5, 0)):
         lin = synth.make(cfg, which)
@@ -600,6 +607,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--cpu-rows", type=int, default=256,
                     help="rows of each linear the CPU oracle is timed on (256 rows of config 5 take about 20 s)")
+    ap.add_argument("--decode-only", action="store_true",
+                    help="only the decode-sized GEMM sweep (for profiler runs)")
     ap.add_argument("--kv-only", action="store_true",
                     help="print only the INT4 KV-cache measurements (a short run to put under rocprofv3)")
     ap.add_argument("--layer-only", action="store_true",
@@ -624,6 +633,9 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
+    if args.decode_only:
+        print(json.dumps({"decode_sweep": decode_sweep()}))
+        return
     if args.kv_only:
         print(json.dumps({"kv_cache": kv_cache_measurements()}))
         return
