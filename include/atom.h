@@ -175,6 +175,39 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8,
                            int32_t *partials_dbg, void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/*
+ * One launch for a whole linear layer at decode-sized batches (Section 3:
+ * small-batch dense layers are bound by reading the weights; Sections 4.1 and
+ * 4.2): the front end of atom_quantize_act (RMSNorm when gamma is given,
+ * reorder, dynamic group quantisation) runs in the prologue of the
+ * weight-streaming group GEMM, so the codes never travel through HBM.
+ * Codes and scales are those of atom_quantize_act bit for bit; Y is that of
+ * atom_w4a4_gemm on them up to the order of the fp32 sum over groups (eight
+ * contiguous runs of groups, added in run order; the same tree atom_w4a4_gemm
+ * uses at these sizes when its scale arrays are 8-byte aligned).
+ *
+ *   x_f16 [M, ldx], gamma_f16, eps, reorder_idx, clip   as atom_quantize_act
+ *   w_q4 / w_q8 / w_scale   canonical weight codes and scales for N rows
+ *   y_f16 [M, ldy] fp16 out, ldy >= N
+ *   dbg_q4 / dbg_q8 / dbg_scale   all NULL, or device arrays as the outputs of
+ *                 atom_quantize_act for M rows: the codes and scales the
+ *                 kernel computed are also written (verification)
+ * ATOM_ERR_UNSUPPORTED unless 1 <= M <= 16 (M = 0 is a no-op), K <= 12288,
+ * 2^-20 <= clip <= 1 and atom_decode_linear_lds_bytes(M, d, norm) <= 163840
+ * (the staged row and the codes of all M rows live in one workgroup's LDS).
+ * Alignment as atom_quantize_act and atom_w4a4_gemm; debug arrays 4-byte.
+ */
+atom_status atom_decode_linear(const void *x_f16, int64_t M, int64_t ldx,
+                               const void *gamma_f16, float eps,
+                               const int32_t *reorder_idx, const atom_desc *d,
+                               float clip, const void *w_q4, const void *w_q8,
+                               const void *w_scale, int64_t N, void *y_f16,
+                               int64_t ldy, void *dbg_q4, void *dbg_q8,
+                               void *dbg_scale, void *stream);
+
+/* LDS bytes per workgroup atom_decode_linear needs (0 for a bad descriptor). */
+size_t atom_decode_linear_lds_bytes(int64_t M, const atom_desc *d, int with_norm);
+
 /* Scratch the GEMM needs for these sizes (0 when it needs none). */
 size_t atom_w4a4_gemm_workspace_bytes(int64_t M, int64_t N,
                                       const atom_desc *d);

@@ -27,6 +27,8 @@ from .binding import (  # noqa: F401
     atom_mfma_rate_probe,
     atom_w4a4_gemm,
     atom_w4a4_gemm_workspace_bytes,
+    atom_decode_linear,
+    atom_decode_linear_lds_bytes,
     atom_pack_weight,
     atom_pack_act,
     atom_w4a4_gemm_prepacked,

@@ -22,6 +22,8 @@ EXPORTS = (
     "atom_quantize_weight",
     "atom_w4a4_gemm",
     "atom_w4a4_gemm_workspace_bytes",
+    "atom_decode_linear",
+    "atom_decode_linear_lds_bytes",
     "atom_pack_weight_bytes",
     "atom_pack_weight",
     "atom_w4a4_gemm_packed_workspace_bytes",
@@ -72,6 +74,7 @@ def load_library():
             "(hipcc, gfx950).  This package has no CPU or PyTorch fallback.")
     L = ctypes.CDLL(_LIB_PATH)
     vp, i64, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    i32 = ctypes.c_int32
     dp = ctypes.POINTER(_Desc)
     L.atom_quantize_act.restype = ctypes.c_int
     L.atom_quantize_act.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, vp, vp, vp]
@@ -85,6 +88,10 @@ def load_library():
     L.atom_w4a4_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, dp, vp, i64, vp, vp, sz, vp]
     L.atom_w4a4_gemm_workspace_bytes.restype = sz
     L.atom_w4a4_gemm_workspace_bytes.argtypes = [i64, i64, dp]
+    L.atom_decode_linear.restype = ctypes.c_int
+    L.atom_decode_linear.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp]
+    L.atom_decode_linear_lds_bytes.restype = sz
+    L.atom_decode_linear_lds_bytes.argtypes = [i64, dp, i32]
     L.atom_pack_weight_bytes.restype = sz
     L.atom_pack_weight_bytes.argtypes = [i64, dp]
     L.atom_pack_weight.restype = ctypes.c_int
@@ -203,6 +210,42 @@ def atom_quantize_act(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float
     if st != 0:
         raise AtomError(st, "atom_quantize_act")
     return q4, q8, sc
+
+
+def atom_decode_linear(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float,
+                       reorder_idx: torch.Tensor, w_q4: torch.Tensor, w_q8: torch.Tensor,
+                       w_scale: torch.Tensor, group_size: int = 128, clip: float = 0.9,
+                       out: Optional[torch.Tensor] = None, debug: bool = False, bits: int = 4):
+    """One launch for ``Y = linear(x)`` at M <= 16 rows: front end (RMSNorm when ``gamma`` is given,
+    reorder, group quantisation) and weight-streaming group GEMM.  Returns ``Y`` [M, N] fp16, or
+    ``(Y, (q4, q8, scale))`` with ``debug`` (the activation codes the kernel computed)."""
+    L = load_library()
+    _dev(x, torch.float16, "x")
+    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if gamma is not None:
+        _dev(gamma, torch.float16, "gamma")
+    _dev(w_q4, torch.uint8, "w_q4")
+    _dev(w_q8, torch.int8, "w_q8")
+    _dev(w_scale, torch.float16, "w_scale")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [M, K] with a contiguous last dimension")
+    M, K = x.shape
+    N, O = w_q8.shape
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=x.device)
+    dbg = _quant_outputs(M, K, group_size, O, x.device) if debug else (None, None, None)
+    d = _desc(K, group_size, O, bits)
+    st = L.atom_decode_linear(_ptr(x), M, x.stride(0) if M > 1 else max(K, x.stride(0)), _ptr(gamma), eps,
+                              _ptr(reorder_idx), ctypes.byref(d), clip, _ptr(w_q4), _ptr(w_q8), _ptr(w_scale), N,
+                              _ptr(y), y.stride(0) if M > 1 else max(N, y.stride(0)), _ptr(dbg[0]), _ptr(dbg[1]),
+                              _ptr(dbg[2]), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_decode_linear")
+    return (y, dbg) if debug else y
+
+
+def atom_decode_linear_lds_bytes(M: int, K: int, n_outlier: int = 128, norm: bool = True, group_size: int = 128) -> int:
+    d = _desc(K, group_size, n_outlier, 4)
+    return int(load_library().atom_decode_linear_lds_bytes(M, ctypes.byref(d), 1 if norm else 0))
 
 
 def atom_add_quantize_act(x: torch.Tensor, residual: torch.Tensor, gamma: Optional[torch.Tensor],

@@ -150,6 +150,39 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8, const void *a_sca
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
+size_t atom_decode_linear_lds_bytes(int64_t M, const atom_desc *d, int with_norm)
+{
+    if (check_desc(d) != ATOM_OK || M <= 0 || M > 16) return 0;
+    return atom_internal::decode_linear_lds_bytes((int)M, d->K, d->n_outlier, with_norm != 0);
+}
+
+atom_status atom_decode_linear(const void *x_f16, int64_t M, int64_t ldx, const void *gamma_f16,
+                               float eps, const int32_t *reorder_idx, const atom_desc *d, float clip,
+                               const void *w_q4, const void *w_q8, const void *w_scale, int64_t N,
+                               void *y_f16, int64_t ldy, void *dbg_q4, void *dbg_q8, void *dbg_scale,
+                               void *stream)
+{
+    atom_status st = check_desc(d);
+    if (st != ATOM_OK) return st;
+    if (M < 0 || N < 0 || ldx < d->K || ldy < N) return ATOM_ERR_SHAPE;
+    if (M == 0 || N == 0) return ATOM_OK;
+    if (M > 16 || d->K > 12288 || !(clip >= 9.5367431640625e-07f && clip <= 1.0f)) return ATOM_ERR_UNSUPPORTED;
+    if (atom_internal::decode_linear_lds_bytes((int)M, d->K, d->n_outlier, gamma_f16 != nullptr) > 160 * 1024)
+        return ATOM_ERR_UNSUPPORTED;
+    if (!x_f16 || !reorder_idx || !w_q4 || !w_q8 || !w_scale || !y_f16) return ATOM_ERR_NULL;
+    const int ndbg = (dbg_q4 != nullptr) + (dbg_q8 != nullptr) + (dbg_scale != nullptr);
+    if (ndbg != 0 && ndbg != 3) return ATOM_ERR_NULL;
+    if (!aligned(x_f16, 16) || (ldx % 8) || !aligned(reorder_idx, 16) || (gamma_f16 && !aligned(gamma_f16, 16)) ||
+        !aligned(w_q4, 16) || !aligned(w_q8, 16) || !aligned(w_scale, 2) || !aligned(y_f16, 2) ||
+        (ndbg && (!aligned(dbg_q4, 4) || !aligned(dbg_q8, 4) || !aligned(dbg_scale, 2))))
+        return ATOM_ERR_ALIGN;
+    hipError_t err = atom_internal::launch_decode_linear(x_f16, (int)M, ldx, gamma_f16, eps, reorder_idx, d->K,
+                                                         d->n_outlier, d->bits_normal, clip, w_q4, w_q8, w_scale,
+                                                         N, y_f16, ldy, dbg_q4, dbg_q8, dbg_scale,
+                                                         static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
 size_t atom_pack_weight_bytes(int64_t N, const atom_desc *d)
 {
     if (check_desc(d) != ATOM_OK || N <= 0) return 0;

@@ -48,6 +48,15 @@ hipError_t launch_mfma_rate_probe(int kind, int iters, void *out, hipStream_t st
 
 // MX variant: front end (FP4 / FP8 codes, E8M0 scale byte per 32 channels) and GEMM on the
 // scaled FP8/FP6/FP4 MFMA.
+// One-launch decode linear (atom_decode_fused.hip): front end in the prologue of the
+// weight-streaming GEMM, M <= 16.
+size_t decode_linear_lds_bytes(int M, int K, int O, bool norm);
+hipError_t launch_decode_linear(const void *x, int M, int64_t ldx, const void *gamma, float eps,
+                                const int32_t *idx, int K, int O, int nbits, float clip,
+                                const void *w_q4, const void *w_q8, const void *w_scale, int64_t N,
+                                void *y, int64_t ldy, void *dbg_q4, void *dbg_q8, void *dbg_scale,
+                                hipStream_t stream);
+
 hipError_t launch_quantize_rows_mx(const void *x, int64_t rows, int64_t ld, const void *gamma,
                                    float eps, const int32_t *idx, int K, int O, float clip, void *q4,
                                    void *q8, void *e8, hipStream_t stream);

@@ -1,0 +1,319 @@
+// Row routine of the activation front end, shared by the stand-alone front-end kernels and
+// by the decode kernel that runs the front end in its prologue: RMSNorm, reorder (Section 4.1
+// of the paper), dynamic group quantisation (Section 4.2, Section 2 symmetric equations).
+//
+// Compile WITHOUT fast-math: the fp32 division, sqrt and the absence of fused multiply-adds
+// are part of the bit-exact contract with the CPU oracle.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+namespace atom_quantize_rows {
+
+__device__ __forceinline__ void halves_to_floats(const uint4 &raw, float *f)
+{
+    const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float2 t = __half22float2(h[i]);
+        f[2 * i]     = t.x;
+        f[2 * i + 1] = t.y;
+    }
+}
+
+// h = fp16(a + b) per element: the sum of two fp16 values formed in fp32 and rounded once
+// (where the fp32 sum is inexact the addends are more than 2^13 apart, nowhere near an
+// fp16 rounding tie, so this is the correctly rounded fp16 sum)
+__device__ __forceinline__ uint4 add_halves(const uint4 &a, const uint4 &b)
+{
+    float fa[8], fb[8];
+    halves_to_floats(a, fa);
+    halves_to_floats(b, fb);
+    uint4 out;
+    uint32_t *o = reinterpret_cast<uint32_t *>(&out);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t lo = __half_as_ushort(__float2half_rn(fa[2 * i] + fb[2 * i]));
+        const uint32_t hi = __half_as_ushort(__float2half_rn(fa[2 * i + 1] + fb[2 * i + 1]));
+        o[i] = lo | (hi << 16);
+    }
+    return out;
+}
+
+// exp(x) on [-87, 87] from IEEE operations only (one value on every machine, the CPU
+// oracle's included): n = round(x*log2(e)); r = x - n*ln2 with ln2 split in two, the first
+// part short enough for n*ln2_hi to be exact; e^r by its Taylor polynomial of degree 7 in
+// Horner form; 2^n through the exponent field.
+__device__ __forceinline__ float exp_ieee(float x)
+{
+    x = x < -87.0f ? -87.0f : x;
+    x = x > 87.0f ? 87.0f : x;
+    const float n = rintf(x * 1.44269502162933349609375f);
+    float r = fmaf(n, -0.693145751953125f, x);
+    r = fmaf(n, -1.428606765330187045037746429443359375e-06f, r);
+    float p = 1.0f / 5040.0f;
+    p = fmaf(p, r, 1.0f / 720.0f);
+    p = fmaf(p, r, 1.0f / 120.0f);
+    p = fmaf(p, r, 1.0f / 24.0f);
+    p = fmaf(p, r, 1.0f / 6.0f);
+    p = fmaf(p, r, 0.5f);
+    p = fmaf(p, r, 1.0f);
+    p = fmaf(p, r, 1.0f);
+    return p * __int_as_float(((int)n + 127) << 23);
+}
+
+// silu(g) * u in fp32: sigma = 1/(1 + exp(-g)) with an IEEE division, then (g*sigma)*u
+__device__ __forceinline__ float silu_mul(float g, float u)
+{
+    const float sigma = 1.0f / (1.0f + exp_ieee(-g));
+    return (g * sigma) * u;
+}
+
+// what happens to a row before it is normalised and quantised
+constexpr int kPlain = 0;    // nothing
+constexpr int kAdd = 1;      // x + res, rounded to fp16 and written to sum_out
+constexpr int kSwiglu = 2;   // silu(x) * res in fp32 (x = gate row, res = up row), not stored
+
+// max over the 16 lanes of a DPP row (xor butterfly; max is exact in any order)
+__device__ __forceinline__ float row16_max(float v)
+{
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
+    return v;
+}
+
+// max over the 16 lanes of a DPP row by rotations (max is exact in any order); one
+// v_max_f32 with a DPP operand per step, no LDS crossbar traffic
+__device__ __forceinline__ float row16_max_dpp(float v)
+{
+#define ATOM_ROW_ROR(n)                                                                          \
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(                          \
+                     0, __builtin_bit_cast(int, v), 0x120 | (n), 0xF, 0xF, false)))
+    ATOM_ROW_ROR(8);
+    ATOM_ROW_ROR(4);
+    ATOM_ROW_ROR(2);
+    ATOM_ROW_ROR(1);
+#undef ATOM_ROW_ROR
+    return v;
+}
+
+// Same result as the plain front-end kernel (compiler-generated IEEE division), bit for bit, for
+// K <= 8 * NT * NS and clip >= 2^-20
+// (NT threads per row),
+// with the per-element work cut down:
+//   * a workgroup walks several rows; the gather offsets of the reorder (they are the same
+//     for every row) and gamma stay in registers, and the next row's global loads are in
+//     flight while this row is quantised;
+//   * the IEEE division by the group's scale shares the reciprocal refinement across the
+//     group: r = rcp(s), r += r*(1 - s*r), then per element q = y*r and two residual
+//     corrections q += r*(y - s*q).  This is instruction for instruction what the
+//     compiler emits for y / s when v_div_scale does not rescale, which it does not for
+//     the quotients that matter here: s comes from the group's own maximum, so
+//     |y| / s <= (2^n - 1)/(2 clip) * (1 + 2^-11) and s >= 2^-24; quotients below 2^-100
+//     round to code 0 either way.  A zero scale (all-zero group) yields zero codes;
+//   * the group maximum is a DPP rotation reduction.
+// The rows row_first, row_first + row_step, ... < rows are handled by the calling workgroup
+// (NT threads, all of them call); lds holds K + (NORM ? K / 8 : 0) floats.  q4, q8 and scale
+// are the canonical arrays (row strides (K - O) / 2, O and K / 128) and may live in LDS.
+template <bool NORM, int NS, int NT, int PRE>
+__device__ __forceinline__
+void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
+                             const __half *x, int64_t rows, int64_t ld,
+                             const __half *res, int64_t ldr, __half *sum_out, int64_t ldo,
+                             const __half *__restrict__ gamma, float eps,
+                             const int32_t *__restrict__ idx, int K, int O, int nbits, float clip,
+                             uint8_t *q4, int8_t *q8, __half *scale)
+{
+    float *ybuf = lds;            // [K]   staged row, original channel order
+    float *qbuf = lds + K;        // [K/8] per-vector sums of squares (NORM only)
+
+    const int tid  = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: group decisions become scalar
+    const int V    = K >> 3;
+    const int K4   = K - O;
+    const int G    = K >> 7;
+    const int G4   = K4 >> 7;
+
+    // gather offsets (bytes into ybuf) of this lane's 8 channels in each of its groups
+    // (with 1024 threads two 16-bit channel numbers share a register)
+    constexpr bool OPACK = NT >= 1024;
+    uint32_t off[NS][OPACK ? 4 : 8];
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+        const int g  = 4 * wave + (lane >> 4) + (NT / 16) * j;
+        const int gg = g < G ? g : G - 1;
+        const int j0 = gg * 128 + (lane & 15) * 8;
+        const int4 i0 = *reinterpret_cast<const int4 *>(idx + j0);
+        const int4 i1 = *reinterpret_cast<const int4 *>(idx + j0 + 4);
+        const int id[8] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t c = min((unsigned)id[e], (unsigned)(K - 1));
+            if (!OPACK)          off[j][e] = 4u * c;
+            else if (e % 2 == 0) off[j][e / 2] = c;
+            else                 off[j][e / 2] |= c << 16;
+        }
+    }
+    // gamma stays in registers too, except with 1024 threads (128 registers per lane):
+    // there each row re-reads it through the cache
+    constexpr bool GREG = NT < 1024;
+    uint4 graw[NORM && GREG ? NS : 1];
+    if (NORM && GREG) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const int v = tid + NT * i;
+            graw[i] = v < V ? *reinterpret_cast<const uint4 *>(gamma + 8 * v) : make_uint4(0, 0, 0, 0);
+        }
+    }
+
+    uint4 raw[NS];
+    uint4 rres[PRE != kPlain ? NS : 1];
+    auto fetch_row = [&](int64_t row) {
+        const __half *xr = x + row * ld;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const int v = tid + NT * i;
+            raw[i] = v < V ? *reinterpret_cast<const uint4 *>(xr + 8 * v) : make_uint4(0, 0, 0, 0);
+            if (PRE != kPlain)
+                rres[i] = v < V ? *reinterpret_cast<const uint4 *>(res + row * ldr + 8 * v)
+                                : make_uint4(0, 0, 0, 0);
+        }
+    };
+    int64_t row = row_first;
+    if (row < rows) fetch_row(row);
+
+    for (; row < rows; row += row_step) {
+        // ---- 0. residual add; the sum is the new residual stream and the row quantised below
+        if (PRE == kAdd) {
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                const int v = tid + NT * i;
+                if (v < V) {
+                    raw[i] = add_halves(raw[i], rres[i]);
+                    *reinterpret_cast<uint4 *>(sum_out + row * ldo + 8 * v) = raw[i];
+                }
+            }
+        }
+        // ---- 1./2. stage the row (after RMSNorm, if any) in LDS, original channel order
+        float r = 1.0f;
+        if (NORM) {
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                const int v = tid + NT * i;
+                if (v < V) {
+                    float f[8];
+                    halves_to_floats(raw[i], f);
+                    float s0 = f[0] * f[0], s1 = f[1] * f[1], s2 = f[2] * f[2], s3 = f[3] * f[3];
+                    float s4 = f[4] * f[4], s5 = f[5] * f[5], s6 = f[6] * f[6], s7 = f[7] * f[7];
+                    qbuf[v] = ((s0 + s1) + (s2 + s3)) + ((s4 + s5) + (s6 + s7));
+                }
+            }
+            __syncthreads();
+            float L = 0.0f;
+            for (int v = lane; v < V; v += 64) L = L + qbuf[v];
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) L = L + __shfl_xor(L, d, 64);
+            const float mean = L / (float)K;
+            r = 1.0f / sqrtf(mean + eps);
+        }
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            const int v = tid + NT * i;
+            if (v < V) {
+                float f[8];
+                halves_to_floats(raw[i], f);
+                if (PRE == kSwiglu) {
+                    float u[8];
+                    halves_to_floats(rres[i], u);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) f[e] = silu_mul(f[e], u[e]);
+                }
+                if (NORM) {
+                    float g[8];
+                    halves_to_floats(GREG ? graw[i] : *reinterpret_cast<const uint4 *>(gamma + 8 * v), g);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) f[e] = (f[e] * r) * g[e];
+                }
+                *reinterpret_cast<float4 *>(ybuf + 8 * v)     = make_float4(f[0], f[1], f[2], f[3]);
+                *reinterpret_cast<float4 *>(ybuf + 8 * v + 4) = make_float4(f[4], f[5], f[6], f[7]);
+            }
+        }
+        // the next row's loads fly while this one is quantised
+        if (row + row_step < rows) fetch_row(row + row_step);
+        __syncthreads();
+
+        // ---- 3./4. reorder, group amax, scale, quantise, pack ----------------
+#pragma unroll
+        for (int j = 0; j < NS; ++j) {
+            const int  g    = 4 * wave + (lane >> 4) + (NT / 16) * j;
+            const bool live = g < G;          // ragged last sweep: whole 16-lane rows idle
+            const int  gg   = live ? g : G - 1;
+            const int  j0   = gg * 128 + (lane & 15) * 8;
+            float y[8];
+            float amax = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                uint32_t o = off[j][OPACK ? e / 2 : e];
+                if (OPACK) {
+                    // unpacked here, per row: hoisted out of the row loop the unpacked
+                    // offsets would take the registers the packing saves
+                    asm volatile("" : "+v"(o));
+                    o = e % 2 ? (o >> 16) << 2 : (o & 0xffffu) << 2;
+                }
+                y[e] = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(ybuf) + o);
+                amax = fmaxf(amax, fabsf(y[e]));
+            }
+            amax = row16_max_dpp(amax);
+
+            const bool  is4   = gg < G4;
+            // normal channels: n = nbits (4, or 3 with the codes still in nibbles), outliers n = 8
+            const float denom = is4 ? (nbits == 3 ? 7.0f : 15.0f) : 255.0f;
+            const float qmin  = is4 ? (nbits == 3 ? -4.0f : -8.0f) : -128.0f;
+            const float qmax  = is4 ? (nbits == 3 ? 3.0f : 7.0f) : 127.0f;
+            const float s32   = ((2.0f * amax) * clip) / denom;
+            const __half sh   = (s32 > 65504.0f) ? __ushort_as_half((unsigned short)0x7bffu)
+                                                 : __float2half_rn(s32);
+            const float s     = __half2float(sh);
+            const float r0    = __builtin_amdgcn_rcpf(s);
+            const float e0    = fmaf(-s, r0, 1.0f);
+            const float r1    = fmaf(e0, r0, r0);
+            int q[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float qf = y[e] * r1;
+                float t  = fmaf(-s, qf, y[e]);
+                qf = fmaf(t, r1, qf);
+                t  = fmaf(-s, qf, y[e]);
+                qf = fmaf(t, r1, qf);
+                qf = rintf(qf);
+                qf = fminf(fmaxf(qf, qmin), qmax);
+                q[e] = (int)qf;
+            }
+            const bool nz = s != 0.0f;
+            if (live) {
+                if (is4) {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) w |= (uint32_t)(q[e] & 0xF) << (4 * e);
+                    *reinterpret_cast<uint32_t *>(q4 + row * (int64_t)(K4 >> 1) + (j0 >> 1)) = nz ? w : 0u;
+                } else {
+                    uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        w0 |= (uint32_t)(q[e] & 0xFF) << (8 * e);
+                        w1 |= (uint32_t)(q[e + 4] & 0xFF) << (8 * e);
+                    }
+                    *reinterpret_cast<uint2 *>(q8 + row * (int64_t)O + (j0 - K4)) =
+                        make_uint2(nz ? w0 : 0u, nz ? w1 : 0u);
+                }
+                if ((lane & 15) == 0) scale[row * (int64_t)G + gg] = sh;
+            }
+        }
+        __syncthreads();   // ybuf is rewritten by the next row
+    }
+}
+
+}  // namespace atom_quantize_rows

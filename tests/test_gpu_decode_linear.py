@@ -1,0 +1,99 @@
+"""The one-launch decode linear (front end in the prologue of the weight-streaming GEMM) against
+the CPU oracle: activation codes and scales bit-identical (Sections 4.1 and 4.2 of the paper), Y
+within 1e-3 of the oracle's group GEMM on those codes, and bit-identical to the two-launch path
+(atom_quantize_act, atom_w4a4_gemm), whose sum over groups is the same tree at these shapes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2310_19102_amd as atom
+from paper_2310_19102_amd import synth
+from _gpu_util import (Y_TOL, assert_quant_equal, dev, gpu_quantize_weight, npy, ref_quantize_act,
+                       ref_quantize_weight, y_rel_err)
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand_linear(M, K, N, O, seed, norm=True):
+    g = torch.Generator().manual_seed(seed)
+    sigma = torch.exp(1.5 * torch.randn(K, generator=g))
+    x = (torch.randn((M, K), generator=g) * sigma).to(torch.float16)
+    w = (0.02 * torch.randn((N, K), generator=g)).to(torch.float16)
+    gamma = (1 + 0.1 * torch.randn(K, generator=g)).to(torch.float16) if norm else None
+    idx = torch.argsort(sigma, stable=True).to(torch.int32)
+    return synth.Linear("rand", x, w, gamma, idx, n_outlier=O)
+
+
+@pytest.mark.parametrize("M,K,N,O,norm,same_tree", [
+    (1, 4096, 4096, 128, True, True),      # Llama-7B attention projection, one token
+    (8, 4096, 11008, 128, True, True),     # Llama-7B gate or up projection
+    (16, 4096, 200, 128, False, True),     # the largest M, ragged N, no norm
+    (8, 11008, 4096, 128, False, True),    # Llama-7B down projection: 86 groups, runs of 8 and 12 groups
+    (5, 8192, 130, 128, True, True),       # two register sets in the front end, one batch of eight groups
+    (3, 1408, 40, 128, True, False),       # 11 groups (odd): runs of single groups
+    (7, 768, 24, 256, True, True),         # two INT8 groups
+    (2, 256, 16, 128, False, False),       # one INT4 + one INT8 group: most wavefronts have no group
+    (16, 12288, 32, 128, True, True),      # the largest K
+])
+def test_decode_linear_matches_oracle_and_two_launch_path(M, K, N, O, norm, same_tree):
+    print(f"[case] decode linear M={M} K={K} N={N} O={O} norm={norm}", flush=True)
+    lin = _rand_linear(M, K, N, O, seed=M * 31 + K + N, norm=norm)
+    gw = gpu_quantize_weight(lin)
+    rw = ref_quantize_weight(lin)
+    assert_quant_equal(gw, rw, "weight")
+    y, codes = atom.atom_decode_linear(dev(lin.x), dev(lin.gamma), lin.eps, dev(lin.idx), *gw,
+                                       lin.group_size, lin.clip_act, debug=True)
+    torch.cuda.synchronize()
+    ra = ref_quantize_act(lin)
+    assert_quant_equal(codes, ra, "activation codes computed in the prologue")
+    ref = oracle.w4a4_gemm(*ra, *rw, lin.group_size)
+    err = y_rel_err(npy(y), ref["y"])
+    assert err <= Y_TOL, f"Y rel err {err}"
+    # without the debug outputs: the same Y
+    y1 = atom.atom_decode_linear(dev(lin.x), dev(lin.gamma), lin.eps, dev(lin.idx), *gw, lin.group_size, lin.clip_act)
+    assert torch.equal(y, y1)
+    # the two-launch path
+    qa = atom.atom_quantize_act(dev(lin.x), dev(lin.gamma), lin.eps, dev(lin.idx), lin.group_size, O, lin.clip_act)
+    y2 = atom.atom_w4a4_gemm(*qa, *gw, lin.group_size)
+    torch.cuda.synchronize()
+    if same_tree:
+        assert torch.equal(y, y2), "one launch and two launches differ"
+    else:
+        assert y_rel_err(npy(y), npy(y2)) <= Y_TOL
+
+
+def test_decode_linear_strided_and_w3a3():
+    """Row strides on x and Y; 3-bit normal codes (Section 5.4.1's W3A3 variant)."""
+    lin = _rand_linear(6, 2048, 72, 128, seed=77)
+    xs = torch.zeros((6, 2048 + 64), dtype=torch.float16, device="cuda")
+    xs[:, :2048] = dev(lin.x)
+    ys = torch.full((6, 100), 7.0, dtype=torch.float16, device="cuda")
+    for bits in (4, 3):
+        gw = atom.atom_quantize_weight(dev(lin.w), dev(lin.idx), 128, 128, lin.clip_weight, bits=bits)
+        y, codes = atom.atom_decode_linear(xs[:, :2048], dev(lin.gamma), lin.eps, dev(lin.idx), *gw, 128,
+                                           lin.clip_act, out=ys[:, :72], debug=True, bits=bits)
+        torch.cuda.synchronize()
+        ra = oracle.quantize_act(lin.x.numpy(), lin.gamma.numpy(), lin.eps, lin.idx.numpy(), 128, 128,
+                                 lin.clip_act, bits)
+        assert_quant_equal(codes, ra, f"codes, {bits} bits")
+        rw = oracle.quantize_weight(lin.w.numpy(), lin.idx.numpy(), 128, 128, lin.clip_weight, bits)
+        ref = oracle.w4a4_gemm(*ra, *rw, 128)
+        assert y_rel_err(npy(ys[:, :72]), ref["y"]) <= Y_TOL
+        assert (ys[:, 72:] == 7.0).all(), "columns beyond N were written"
+
+
+def test_decode_linear_limits():
+    lin = _rand_linear(2, 512, 16, 128, seed=3)
+    gw = gpu_quantize_weight(lin)
+    x17 = torch.zeros((17, 512), dtype=torch.float16, device="cuda")
+    with pytest.raises(atom.AtomError) as e:
+        atom.atom_decode_linear(x17, None, 0.0, dev(lin.idx), *gw)
+    assert e.value.status == 3                       # M > 16: unsupported
+    with pytest.raises(atom.AtomError) as e:
+        atom.atom_decode_linear(dev(lin.x), None, 0.0, dev(lin.idx), *gw, clip=1e-9)
+    assert e.value.status == 3                       # clip below 2^-20
+    assert atom.atom_decode_linear_lds_bytes(16, 12288, 128, True) <= 160 * 1024
+    y = atom.atom_decode_linear(torch.zeros((0, 512), dtype=torch.float16, device="cuda"), None, 0.0,
+                                dev(lin.idx), *gw)
+    assert y.shape == (0, 16)
