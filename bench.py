@@ -97,6 +97,17 @@ class DeviceLinear:
         self.turn += 1
         atom.atom_w4a4_gemm(*self.qa, *qw, self.lin.group_size, out=self.y)
 
+    def two_launches(self):
+        self.front_end()
+        self.gemm()
+
+    def one_launch(self):
+        """Front end and GEMM of a decode-sized linear in one kernel (M <= 16)."""
+        l = self.lin
+        qw = self.qw_ring[self.turn % len(self.qw_ring)]
+        self.turn += 1
+        atom.atom_decode_linear(self.x, self.gamma, l.eps, self.idx, *qw, l.group_size, l.clip_act, out=self.y)
+
 
 def run_steps(layers, steps, warmup, clock_warmup_s=0.0):
     """Time `steps` passes; HIP events (on the stream the kernels run on)
@@ -196,17 +207,18 @@ def mfma_rates():
     return out
 
 
-def decode_gemm_in_graph(L, copies):
-    """Seconds per decode-sized GEMM launch inside one HIP graph that walks the weight ring (the
-    host's per-call cost is then outside the measurement)."""
+def decode_gemm_in_graph(L, copies, fn=None):
+    """Seconds per decode-sized GEMM launch (or per call of fn) inside one HIP graph that walks the
+    weight ring (the host's per-call cost is then outside the measurement)."""
+    fn = fn or L.gemm
     for _ in range(20):
-        L.gemm()
+        fn()
     torch.cuda.synchronize()
     reps = 4 * copies
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         for _ in range(reps):
-            L.gemm()
+            fn()
     warm_replays(graph)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
@@ -245,12 +257,21 @@ def decode_sweep():
         L = DeviceLinear(lin, n_weight_copies=copies)
         per = decode_gemm_in_graph(L, copies)
         t, ge, fe, pk, _ = run_steps([L], 100, 10, 0.02)
-        out.append({"workload": f"config3 decode M={lin.M} K=4096 N={lin.N}, weight ring of {copies}",
-                    "gemm_us_in_graph": per * 1e6, "gemm_bytes": L.gemm_bytes,
-                    "gemm_GBs": L.gemm_bytes / per / 1e9,
-                    "gemm_hbm_frac": L.gemm_bytes / per / 1e9 / PEAK_HBM_GBS,
-                    "step_us_front_end_plus_gemm": t * 1e6,
-                    "effective_tops": L.ops / t / 1e12})
+        entry = {"workload": f"config3 decode M={lin.M} K=4096 N={lin.N}, weight ring of {copies}",
+                 "gemm_us_in_graph": per * 1e6, "gemm_bytes": L.gemm_bytes,
+                 "gemm_GBs": L.gemm_bytes / per / 1e9,
+                 "gemm_hbm_frac": L.gemm_bytes / per / 1e9 / PEAK_HBM_GBS,
+                 "step_us_front_end_plus_gemm": t * 1e6,
+                 "effective_tops": L.ops / t / 1e12}
+        # the whole linear (front end + GEMM) inside a graph: two launches, and the one-launch kernel
+        two = decode_gemm_in_graph(L, copies, L.two_launches)
+        entry["step_us_in_graph_two_launches"] = two * 1e6
+        if lin.M <= 16:
+            one = decode_gemm_in_graph(L, copies, L.one_launch)
+            step_bytes = L.gemm_bytes - lin.M * ((lin.K - lin.n_outlier) // 2 + lin.n_outlier + 2 * L.G) + 2 * lin.M * lin.K
+            entry["step_us_in_graph_one_launch"] = one * 1e6
+            entry["one_launch_hbm_frac"] = step_bytes / one / 1e9 / PEAK_HBM_GBS
+        out.append(entry)
         del L
         torch.cuda.empty_cache()
     return out

@@ -78,7 +78,13 @@ typedef struct {
  *   x_f16        [M, ldx] fp16, ldx >= K, 16-byte aligned rows (ldx % 8 == 0)
  *   gamma_f16    [K] fp16 in ORIGINAL channel order, or NULL for no norm
  *   eps          RMSNorm epsilon
- *   reorder_idx  [K] int32: output column j reads input column idx[j]
+ *   reorder_idx  [K] int32: output column j reads input column idx[j]; or
+ *                NULL when x already is in reordered channel order (Section
+ *                4.1: the reorder fused into the operator that produced x,
+ *                see atom_permute_rows): same result as the identity index,
+ *                without the gather.  Every front-end entry point (this one,
+ *                atom_add_quantize_act, atom_swiglu_quantize_act,
+ *                atom_quantize_weight, atom_decode_linear) takes NULL so.
  *   clip         clip factor c (0.9 for activations in Section 5.1)
  *   q4, q8, scale_f16   outputs in the layouts above; q4 and q8 16-byte
  *                       aligned, scale_f16 2-byte aligned
@@ -176,6 +182,27 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8,
                            size_t workspace_bytes, void *stream);
 
 /*
+ * Offline helper of the fused reorder (Section 4.1: the reorder index is known
+ * after calibration, so the operator that PRODUCES an activation can emit it
+ * in reordered order at no run-time cost):  out[r, :] = in[row_idx[r], :] over
+ * fp16 matrices.  Applied once to the rows of the producing weight (e.g. the
+ * gate and up projections, with the down projection's index: their output
+ * columns, and so silu(gate) * up, then arrive reordered) or to gamma as a
+ * [K, 1] matrix; the consuming front end is then called with a NULL index.
+ * A GEMM with permuted weight rows computes the same values in permuted
+ * columns, so the codes are those of the gathering front end bit for bit
+ * (without RMSNorm; with it, the sum of squares runs over the permuted order).
+ *
+ *   in_f16  [rows_in, ld_in] fp16;  out_f16 [rows_out, ld_out] fp16, not in place
+ *   row_idx [rows_out] int32 on the device, values in [0, rows_in) (others are
+ *           clamped into the array)
+ */
+atom_status atom_permute_rows(const void *in_f16, int64_t rows_in, int64_t cols,
+                              int64_t ld_in, const int32_t *row_idx,
+                              int64_t rows_out, void *out_f16, int64_t ld_out,
+                              void *stream);
+
+/*
  * One launch for a whole linear layer at decode-sized batches (Section 3:
  * small-batch dense layers are bound by reading the weights; Sections 4.1 and
  * 4.2): the front end of atom_quantize_act (RMSNorm when gamma is given,
@@ -193,8 +220,10 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8,
  *                 atom_quantize_act for M rows: the codes and scales the
  *                 kernel computed are also written (verification)
  * ATOM_ERR_UNSUPPORTED unless 1 <= M <= 16 (M = 0 is a no-op), K <= 12288,
- * 2^-20 <= clip <= 1 and atom_decode_linear_lds_bytes(M, d, norm) <= 163840
- * (the staged row and the codes of all M rows live in one workgroup's LDS).
+ * 2^-20 <= clip <= 1 and atom_decode_linear_lds_bytes(M, d, norm, index) <=
+ * 163840 (the codes of all M rows and, with an index, the staged row live in
+ * one workgroup's LDS).  With an index the rows are quantised one after the
+ * other by the whole workgroup; without one, one wavefront per row.
  * Alignment as atom_quantize_act and atom_w4a4_gemm; debug arrays 4-byte.
  */
 atom_status atom_decode_linear(const void *x_f16, int64_t M, int64_t ldx,
@@ -206,7 +235,8 @@ atom_status atom_decode_linear(const void *x_f16, int64_t M, int64_t ldx,
                                void *dbg_scale, void *stream);
 
 /* LDS bytes per workgroup atom_decode_linear needs (0 for a bad descriptor). */
-size_t atom_decode_linear_lds_bytes(int64_t M, const atom_desc *d, int with_norm);
+size_t atom_decode_linear_lds_bytes(int64_t M, const atom_desc *d, int with_norm,
+                                    int with_index);
 
 /* Scratch the GEMM needs for these sizes (0 when it needs none). */
 size_t atom_w4a4_gemm_workspace_bytes(int64_t M, int64_t N,

@@ -28,6 +28,7 @@ from .binding import (  # noqa: F401
     atom_w4a4_gemm,
     atom_w4a4_gemm_workspace_bytes,
     atom_decode_linear,
+    atom_permute_rows,
     atom_decode_linear_lds_bytes,
     atom_pack_weight,
     atom_pack_act,

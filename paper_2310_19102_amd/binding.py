@@ -22,6 +22,7 @@ EXPORTS = (
     "atom_quantize_weight",
     "atom_w4a4_gemm",
     "atom_w4a4_gemm_workspace_bytes",
+    "atom_permute_rows",
     "atom_decode_linear",
     "atom_decode_linear_lds_bytes",
     "atom_pack_weight_bytes",
@@ -88,10 +89,12 @@ def load_library():
     L.atom_w4a4_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, dp, vp, i64, vp, vp, sz, vp]
     L.atom_w4a4_gemm_workspace_bytes.restype = sz
     L.atom_w4a4_gemm_workspace_bytes.argtypes = [i64, i64, dp]
+    L.atom_permute_rows.restype = ctypes.c_int
+    L.atom_permute_rows.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp]
     L.atom_decode_linear.restype = ctypes.c_int
     L.atom_decode_linear.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp]
     L.atom_decode_linear_lds_bytes.restype = sz
-    L.atom_decode_linear_lds_bytes.argtypes = [i64, dp, i32]
+    L.atom_decode_linear_lds_bytes.argtypes = [i64, dp, i32, i32]
     L.atom_pack_weight_bytes.restype = sz
     L.atom_pack_weight_bytes.argtypes = [i64, dp]
     L.atom_pack_weight.restype = ctypes.c_int
@@ -189,14 +192,15 @@ def _quant_outputs(rows: int, K: int, group_size: int, n_outlier: int, device):
 
 
 def atom_quantize_act(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float,
-                      reorder_idx: torch.Tensor, group_size: int = 128, n_outlier: int = 128,
+                      reorder_idx: Optional[torch.Tensor], group_size: int = 128, n_outlier: int = 128,
                       clip: float = 0.9, out: Optional[Tuple[torch.Tensor, ...]] = None, bits: int = 4):
     """Fused RMSNorm -> reorder -> dynamic group quantisation of ``x`` [M, K]
     (fp16, last dim contiguous).  Returns ``(q4, q8, scale)`` device tensors.  ``bits``: width
     of the normal channels, 4 or 3 (same layouts: one code per nibble)."""
     L = load_library()
     _dev(x, torch.float16, "x")
-    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if reorder_idx is not None:        # None: x already is in reordered order
+        _dev(reorder_idx, torch.int32, "reorder_idx")
     if gamma is not None:
         _dev(gamma, torch.float16, "gamma")
     if x.dim() != 2 or x.stride(1) != 1:
@@ -212,8 +216,27 @@ def atom_quantize_act(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float
     return q4, q8, sc
 
 
+def atom_permute_rows(mat: torch.Tensor, row_idx: torch.Tensor, out: Optional[torch.Tensor] = None):
+    """``out[r, :] = mat[row_idx[r], :]`` for an fp16 matrix (or a vector, taken as one column): the
+    offline step that lets the operator producing an activation emit it in reordered order."""
+    L = load_library()
+    _dev(mat, torch.float16, "mat")
+    _dev(row_idx, torch.int32, "row_idx")
+    m2 = mat if mat.dim() == 2 else mat.reshape(-1, 1)
+    if m2.stride(1) != 1 and m2.shape[1] != 1:
+        raise ValueError("mat must have a contiguous last dimension")
+    R, C = row_idx.numel(), m2.shape[1]
+    o = out if out is not None else torch.empty((R, C), dtype=torch.float16, device=mat.device)
+    o2 = o if o.dim() == 2 else o.reshape(-1, 1)
+    st = L.atom_permute_rows(_ptr(m2), m2.shape[0], C, max(C, m2.stride(0)), _ptr(row_idx), R, _ptr(o2),
+                             max(C, o2.stride(0)), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_permute_rows")
+    return o if mat.dim() == 2 else o.reshape(-1)
+
+
 def atom_decode_linear(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float,
-                       reorder_idx: torch.Tensor, w_q4: torch.Tensor, w_q8: torch.Tensor,
+                       reorder_idx: Optional[torch.Tensor], w_q4: torch.Tensor, w_q8: torch.Tensor,
                        w_scale: torch.Tensor, group_size: int = 128, clip: float = 0.9,
                        out: Optional[torch.Tensor] = None, debug: bool = False, bits: int = 4):
     """One launch for ``Y = linear(x)`` at M <= 16 rows: front end (RMSNorm when ``gamma`` is given,
@@ -221,7 +244,8 @@ def atom_decode_linear(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: floa
     ``(Y, (q4, q8, scale))`` with ``debug`` (the activation codes the kernel computed)."""
     L = load_library()
     _dev(x, torch.float16, "x")
-    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if reorder_idx is not None:        # None: x already is in reordered order
+        _dev(reorder_idx, torch.int32, "reorder_idx")
     if gamma is not None:
         _dev(gamma, torch.float16, "gamma")
     _dev(w_q4, torch.uint8, "w_q4")
@@ -243,13 +267,14 @@ def atom_decode_linear(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: floa
     return (y, dbg) if debug else y
 
 
-def atom_decode_linear_lds_bytes(M: int, K: int, n_outlier: int = 128, norm: bool = True, group_size: int = 128) -> int:
+def atom_decode_linear_lds_bytes(M: int, K: int, n_outlier: int = 128, norm: bool = True, group_size: int = 128,
+                                 index: bool = True) -> int:
     d = _desc(K, group_size, n_outlier, 4)
-    return int(load_library().atom_decode_linear_lds_bytes(M, ctypes.byref(d), 1 if norm else 0))
+    return int(load_library().atom_decode_linear_lds_bytes(M, ctypes.byref(d), 1 if norm else 0, 1 if index else 0))
 
 
 def atom_add_quantize_act(x: torch.Tensor, residual: torch.Tensor, gamma: Optional[torch.Tensor],
-                          eps: float, reorder_idx: torch.Tensor, group_size: int = 128,
+                          eps: float, reorder_idx: Optional[torch.Tensor], group_size: int = 128,
                           n_outlier: int = 128, clip: float = 0.9,
                           sum_out: Optional[torch.Tensor] = None,
                           out: Optional[Tuple[torch.Tensor, ...]] = None, bits: int = 4):
@@ -259,7 +284,8 @@ def atom_add_quantize_act(x: torch.Tensor, residual: torch.Tensor, gamma: Option
     L = load_library()
     _dev(x, torch.float16, "x")
     _dev(residual, torch.float16, "residual")
-    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if reorder_idx is not None:        # None: x already is in reordered order
+        _dev(reorder_idx, torch.int32, "reorder_idx")
     if gamma is not None:
         _dev(gamma, torch.float16, "gamma")
     if x.dim() != 2 or x.stride(1) != 1 or residual.shape != x.shape or residual.stride(1) != 1:
@@ -281,7 +307,7 @@ def atom_add_quantize_act(x: torch.Tensor, residual: torch.Tensor, gamma: Option
     return sum_out, q4, q8, sc
 
 
-def atom_swiglu_quantize_act(gate: torch.Tensor, up: torch.Tensor, reorder_idx: torch.Tensor,
+def atom_swiglu_quantize_act(gate: torch.Tensor, up: torch.Tensor, reorder_idx: Optional[torch.Tensor],
                              group_size: int = 128, n_outlier: int = 128, clip: float = 0.9,
                              out: Optional[Tuple[torch.Tensor, ...]] = None, bits: int = 4):
     """``silu(gate) * up`` (fp32, never stored) followed by reorder and group quantisation.
@@ -290,7 +316,8 @@ def atom_swiglu_quantize_act(gate: torch.Tensor, up: torch.Tensor, reorder_idx: 
     L = load_library()
     _dev(gate, torch.float16, "gate")
     _dev(up, torch.float16, "up")
-    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if reorder_idx is not None:        # None: x already is in reordered order
+        _dev(reorder_idx, torch.int32, "reorder_idx")
     if gate.dim() != 2 or gate.stride(1) != 1 or up.shape != gate.shape or up.stride(1) != 1:
         raise ValueError("gate and up must be [M, K] with a contiguous last dimension")
     M, K = gate.shape
@@ -304,13 +331,14 @@ def atom_swiglu_quantize_act(gate: torch.Tensor, up: torch.Tensor, reorder_idx: 
     return q4, q8, sc
 
 
-def atom_quantize_weight(w: torch.Tensor, reorder_idx: torch.Tensor, group_size: int = 128,
+def atom_quantize_weight(w: torch.Tensor, reorder_idx: Optional[torch.Tensor], group_size: int = 128,
                          n_outlier: int = 128, clip: float = 0.85,
                          out: Optional[Tuple[torch.Tensor, ...]] = None, bits: int = 4):
     """One-time reorder + group quantisation of ``w`` [N, K] fp16."""
     L = load_library()
     _dev(w, torch.float16, "w")
-    _dev(reorder_idx, torch.int32, "reorder_idx")
+    if reorder_idx is not None:        # None: x already is in reordered order
+        _dev(reorder_idx, torch.int32, "reorder_idx")
     if w.dim() != 2 or w.stride(1) != 1:
         raise ValueError("w must be [N, K] with a contiguous last dimension")
     N, K = w.shape

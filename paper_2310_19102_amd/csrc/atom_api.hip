@@ -41,7 +41,7 @@ atom_status quantize_common(const void *x, int64_t rows, int64_t ld, int pre, co
     if (pre != 0 && ldr < d->K) return ATOM_ERR_SHAPE;
     if (pre == 1 && ldo < d->K) return ATOM_ERR_SHAPE;
     if (rows == 0) return ATOM_OK;
-    if (!x || !idx || !q4 || !q8 || !scale) return ATOM_ERR_NULL;
+    if (!x || !q4 || !q8 || !scale) return ATOM_ERR_NULL;     // idx may be null: identity order
     if (pre != 0 && !res) return ATOM_ERR_NULL;
     if (pre == 1 && !sum_out) return ATOM_ERR_NULL;
     if (!aligned(x, 16) || (ld % 8) || !aligned(idx, 16) || !aligned(q4, 16) || !aligned(q8, 16) ||
@@ -150,10 +150,25 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8, const void *a_sca
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
-size_t atom_decode_linear_lds_bytes(int64_t M, const atom_desc *d, int with_norm)
+atom_status atom_permute_rows(const void *in_f16, int64_t rows_in, int64_t cols, int64_t ld_in,
+                              const int32_t *row_idx, int64_t rows_out, void *out_f16, int64_t ld_out,
+                              void *stream)
+{
+    if (rows_in <= 0 || rows_out < 0 || cols < 0 || ld_in < cols || ld_out < cols) return ATOM_ERR_SHAPE;
+    if (rows_out == 0 || cols == 0) return ATOM_OK;
+    if (!in_f16 || !row_idx || !out_f16) return ATOM_ERR_NULL;
+    if (!aligned(in_f16, 2) || !aligned(out_f16, 2) || !aligned(row_idx, 4)) return ATOM_ERR_ALIGN;
+    if (in_f16 == out_f16) return ATOM_ERR_UNSUPPORTED;           // not in place
+    if (rows_out > 0x7fffffff) return ATOM_ERR_UNSUPPORTED;
+    hipError_t err = atom_internal::launch_permute_rows(in_f16, rows_in, rows_out, cols, ld_in, row_idx, out_f16,
+                                                        ld_out, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
+size_t atom_decode_linear_lds_bytes(int64_t M, const atom_desc *d, int with_norm, int with_index)
 {
     if (check_desc(d) != ATOM_OK || M <= 0 || M > 16) return 0;
-    return atom_internal::decode_linear_lds_bytes((int)M, d->K, d->n_outlier, with_norm != 0);
+    return atom_internal::decode_linear_lds_bytes((int)M, d->K, d->n_outlier, with_norm != 0, with_index == 0);
 }
 
 atom_status atom_decode_linear(const void *x_f16, int64_t M, int64_t ldx, const void *gamma_f16,
@@ -167,9 +182,9 @@ atom_status atom_decode_linear(const void *x_f16, int64_t M, int64_t ldx, const 
     if (M < 0 || N < 0 || ldx < d->K || ldy < N) return ATOM_ERR_SHAPE;
     if (M == 0 || N == 0) return ATOM_OK;
     if (M > 16 || d->K > 12288 || !(clip >= 9.5367431640625e-07f && clip <= 1.0f)) return ATOM_ERR_UNSUPPORTED;
-    if (atom_internal::decode_linear_lds_bytes((int)M, d->K, d->n_outlier, gamma_f16 != nullptr) > 160 * 1024)
+    if (atom_internal::decode_linear_lds_bytes((int)M, d->K, d->n_outlier, gamma_f16 != nullptr, reorder_idx == nullptr) > 160 * 1024)
         return ATOM_ERR_UNSUPPORTED;
-    if (!x_f16 || !reorder_idx || !w_q4 || !w_q8 || !w_scale || !y_f16) return ATOM_ERR_NULL;
+    if (!x_f16 || !w_q4 || !w_q8 || !w_scale || !y_f16) return ATOM_ERR_NULL;       // reorder_idx may be null
     const int ndbg = (dbg_q4 != nullptr) + (dbg_q8 != nullptr) + (dbg_scale != nullptr);
     if (ndbg != 0 && ndbg != 3) return ATOM_ERR_NULL;
     if (!aligned(x_f16, 16) || (ldx % 8) || !aligned(reorder_idx, 16) || (gamma_f16 && !aligned(gamma_f16, 16)) ||

@@ -48,9 +48,13 @@ hipError_t launch_mfma_rate_probe(int kind, int iters, void *out, hipStream_t st
 
 // MX variant: front end (FP4 / FP8 codes, E8M0 scale byte per 32 channels) and GEMM on the
 // scaled FP8/FP6/FP4 MFMA.
+// out[r, :] = in[row_idx[r], :] over fp16 matrices (offline helper of the fused reorder).
+hipError_t launch_permute_rows(const void *in, int64_t rows_in, int64_t rows_out, int64_t cols, int64_t ld_in,
+                               const int32_t *row_idx, void *out, int64_t ld_out, hipStream_t stream);
+
 // One-launch decode linear (atom_decode_fused.hip): front end in the prologue of the
 // weight-streaming GEMM, M <= 16.
-size_t decode_linear_lds_bytes(int M, int K, int O, bool norm);
+size_t decode_linear_lds_bytes(int M, int K, int O, bool norm, bool ident);
 hipError_t launch_decode_linear(const void *x, int M, int64_t ldx, const void *gamma, float eps,
                                 const int32_t *idx, int K, int O, int nbits, float clip,
                                 const void *w_q4, const void *w_q8, const void *w_scale, int64_t N,

@@ -116,9 +116,16 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
             const bool live = g < G;          // ragged last sweep: whole 16-lane rows idle
             const int  gg   = live ? g : G - 1;
             const int  j0   = gg * 128 + (lane & 15) * 8;
-            const int4 i0 = *reinterpret_cast<const int4 *>(idx + j0);
-            const int4 i1 = *reinterpret_cast<const int4 *>(idx + j0 + 4);
-            const int  id[8] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
+            int id[8];
+            if (idx) {
+                const int4 i0 = *reinterpret_cast<const int4 *>(idx + j0);
+                const int4 i1 = *reinterpret_cast<const int4 *>(idx + j0 + 4);
+                id[0] = i0.x; id[1] = i0.y; id[2] = i0.z; id[3] = i0.w;
+                id[4] = i1.x; id[5] = i1.y; id[6] = i1.z; id[7] = i1.w;
+            } else {           // no index: the row already is in reordered order
+#pragma unroll
+                for (int e = 0; e < 8; ++e) id[e] = j0 + e;
+            }
             float y[8];
             float amax = 0.0f;
 #pragma unroll
@@ -214,7 +221,7 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
 }
 
 
-template <bool NORM, int NS, int NT, int PRE>
+template <bool NORM, int NS, int NT, int PRE, bool IDENT>
 __global__ __launch_bounds__(NT)
 void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
                                const __half *res, int64_t ldr, __half *sum_out, int64_t ldo,
@@ -224,8 +231,20 @@ void quantize_rows_fast_kernel(const __half *x, int64_t rows, int64_t ld,
                                __half *__restrict__ scale)
 {
     extern __shared__ __align__(16) float lds[];
-    quantize_rows_fast_body<NORM, NS, NT, PRE>(lds, blockIdx.x, gridDim.x, x, rows, ld, res, ldr, sum_out, ldo,
+    quantize_rows_fast_body<NORM, NS, NT, PRE, IDENT>(lds, blockIdx.x, gridDim.x, x, rows, ld, res, ldr, sum_out, ldo,
                                                gamma, eps, idx, K, O, nbits, clip, q4, q8, scale);
+}
+
+// out[r, :] = in[row_idx[r], :]: the offline helper that fuses a reorder into the operator
+// producing the activations (its weight rows are permuted once); one workgroup per row
+__global__ __launch_bounds__(256)
+void permute_rows_kernel(const uint16_t *in, int64_t rows_in, int64_t cols, int64_t ld_in,
+                         const int32_t *__restrict__ row_idx, uint16_t *__restrict__ out, int64_t ld_out)
+{
+    const int64_t r = blockIdx.x;
+    int64_t src = row_idx[r];
+    src = src < 0 ? 0 : (src >= rows_in ? rows_in - 1 : src);    // a bad index cannot leave the array
+    for (int64_t c = threadIdx.x; c < cols; c += 256) out[r * ld_out + c] = in[src * ld_in + c];
 }
 
 }  // namespace
@@ -245,10 +264,10 @@ struct QuantArgs {
     void *q4, *q8, *scale;
 };
 
-template <bool NORM, int NS, int NT, int PRE>
+template <bool NORM, int NS, int NT, int PRE, bool IDENT = false>
 hipError_t launch_fast(const QuantArgs &a, size_t lds, hipStream_t stream)
 {
-    auto kern = &quantize_rows_fast_kernel<NORM, NS, NT, PRE>;
+    auto kern = &quantize_rows_fast_kernel<NORM, NS, NT, PRE, IDENT>;
     static atom_launch::LdsOptIn opt_in;   // the opt-in for more than 64 KB of dynamic LDS
     hipError_t err = atom_launch::ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), lds);
     if (err != hipSuccess) return err;
@@ -287,12 +306,25 @@ hipError_t launch_plain(const QuantArgs &a, size_t lds, hipStream_t stream)
 template <bool NORM, int PRE>
 hipError_t dispatch_quantize(const QuantArgs &a, hipStream_t stream)
 {
+    const bool sane_clip = a.clip >= 9.5367431640625e-07f && a.clip <= 1.0f;
+    if (!a.idx && a.K <= 32768 && sane_clip) {
+        // no index: the row already is in reordered order; nothing is staged in LDS but the
+        // sums of squares, so the register sets alone bound the threads per row
+        const size_t lq = NORM ? sizeof(float) * (size_t)(a.K / 8) : 0;
+        if (a.K <= 2048)  return launch_fast<NORM, 1, 256, PRE, true>(a, lq, stream);
+        if (a.K <= 4096)  return launch_fast<NORM, 2, 256, PRE, true>(a, lq, stream);
+        if (a.K <= 8192)  return launch_fast<NORM, 2, 512, PRE, true>(a, lq, stream);
+        if (a.K <= 12288) return launch_fast<NORM, 3, 512, PRE, true>(a, lq, stream);
+        if (a.K <= 16384) return launch_fast<NORM, 4, 512, PRE, true>(a, lq, stream);
+        if (a.K <= 24576) return launch_fast<NORM, 3, 1024, PRE, true>(a, lq, stream);
+        return launch_fast<NORM, 4, 1024, PRE, true>(a, lq, stream);
+    }
     const size_t lds = quantize_lds_bytes(a.K, NORM);
     // The fast kernel keeps ceil(K / (8 * threads)) gather-offset sets in registers and
     // relies on a sane clip; rows of 8192 channels and more are spread over 512 threads,
     // rows beyond 16384 channels over 1024 (one workgroup per CU: the staged row fills
     // most of the LDS).
-    if (a.K <= 32768 && a.clip >= 9.5367431640625e-07f && a.clip <= 1.0f) {
+    if (a.K <= 32768 && sane_clip) {
         if (a.K <= 2048)  return launch_fast<NORM, 1, 256, PRE>(a, lds, stream);
         if (a.K <= 4096)  return launch_fast<NORM, 2, 256, PRE>(a, lds, stream);
         if (a.K < 8192)   return launch_fast<NORM, 4, 256, PRE>(a, lds, stream);
@@ -335,6 +367,14 @@ hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, int pre
     if (pre == kAdd)
         return norm ? dispatch_quantize<true, kAdd>(a, stream) : dispatch_quantize<false, kAdd>(a, stream);
     return norm ? dispatch_quantize<true, kPlain>(a, stream) : dispatch_quantize<false, kPlain>(a, stream);
+}
+
+hipError_t launch_permute_rows(const void *in, int64_t rows_in, int64_t rows_out, int64_t cols, int64_t ld_in,
+                               const int32_t *row_idx, void *out, int64_t ld_out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(permute_rows_kernel, dim3((unsigned)rows_out), dim3(256), 0, stream,
+                       (const uint16_t *)in, rows_in, cols, ld_in, row_idx, (uint16_t *)out, ld_out);
+    return hipGetLastError();
 }
 
 }  // namespace atom_internal

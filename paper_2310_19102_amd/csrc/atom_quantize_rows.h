@@ -99,6 +99,38 @@ __device__ __forceinline__ float row16_max_dpp(float v)
     return v;
 }
 
+// Scale of a group from its maximum (Section 2 symmetric equations, fp32, stored as fp16) and the
+// codes of this lane's eight values: IEEE division by the stored scale through the shared
+// reciprocal refinement described below, round-half-to-even, clamp.  Returns the stored scale,
+// s = its fp32 value.
+__device__ __forceinline__ __half quantise_lane8(const float (&y)[8], float amax, bool is4, int nbits, float clip,
+                                                 int (&q)[8], float &s)
+{
+    // normal channels: n = nbits (4, or 3 with the codes still in nibbles), outliers n = 8
+    const float denom = is4 ? (nbits == 3 ? 7.0f : 15.0f) : 255.0f;
+    const float qmin  = is4 ? (nbits == 3 ? -4.0f : -8.0f) : -128.0f;
+    const float qmax  = is4 ? (nbits == 3 ? 3.0f : 7.0f) : 127.0f;
+    const float s32   = ((2.0f * amax) * clip) / denom;
+    const __half sh   = (s32 > 65504.0f) ? __ushort_as_half((unsigned short)0x7bffu)
+                                         : __float2half_rn(s32);
+    s = __half2float(sh);
+    const float r0    = __builtin_amdgcn_rcpf(s);
+    const float e0    = fmaf(-s, r0, 1.0f);
+    const float r1    = fmaf(e0, r0, r0);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float qf = y[e] * r1;
+        float t  = fmaf(-s, qf, y[e]);
+        qf = fmaf(t, r1, qf);
+        t  = fmaf(-s, qf, y[e]);
+        qf = fmaf(t, r1, qf);
+        qf = rintf(qf);
+        qf = fminf(fmaxf(qf, qmin), qmax);
+        q[e] = (int)qf;
+    }
+    return sh;
+}
+
 // Same result as the plain front-end kernel (compiler-generated IEEE division), bit for bit, for
 // K <= 8 * NT * NS and clip >= 2^-20
 // (NT threads per row),
@@ -117,7 +149,11 @@ __device__ __forceinline__ float row16_max_dpp(float v)
 // The rows row_first, row_first + row_step, ... < rows are handled by the calling workgroup
 // (NT threads, all of them call); lds holds K + (NORM ? K / 8 : 0) floats.  q4, q8 and scale
 // are the canonical arrays (row strides (K - O) / 2, O and K / 128) and may live in LDS.
-template <bool NORM, int NS, int NT, int PRE>
+// IDENT: the row already is in reordered channel order (the producer emitted it so, Section 4.1
+// of the paper: the reorder fused into the prior operator): thread t's vector t + NT*i is its own
+// share of group (t + NT*i) / 16, nothing is staged or gathered, idx is not read and lds holds
+// the K / 8 sums of squares only (NORM) or nothing.
+template <bool NORM, int NS, int NT, int PRE, bool IDENT = false>
 __device__ __forceinline__
 void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
                              const __half *x, int64_t rows, int64_t ld,
@@ -126,8 +162,8 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
                              const int32_t *__restrict__ idx, int K, int O, int nbits, float clip,
                              uint8_t *q4, int8_t *q8, __half *scale)
 {
-    float *ybuf = lds;            // [K]   staged row, original channel order
-    float *qbuf = lds + K;        // [K/8] per-vector sums of squares (NORM only)
+    float *ybuf = lds;                        // [K]   staged row, original channel order (not IDENT)
+    float *qbuf = lds + (IDENT ? 0 : K);      // [K/8] per-vector sums of squares (NORM only)
 
     const int tid  = threadIdx.x;
     const int lane = tid & 63;
@@ -140,9 +176,9 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
     // gather offsets (bytes into ybuf) of this lane's 8 channels in each of its groups
     // (with 1024 threads two 16-bit channel numbers share a register)
     constexpr bool OPACK = NT >= 1024;
-    uint32_t off[NS][OPACK ? 4 : 8];
+    uint32_t off[IDENT ? 1 : NS][OPACK ? 4 : 8];
 #pragma unroll
-    for (int j = 0; j < NS; ++j) {
+    for (int j = 0; j < (IDENT ? 0 : NS); ++j) {
         const int g  = 4 * wave + (lane >> 4) + (NT / 16) * j;
         const int gg = g < G ? g : G - 1;
         const int j0 = gg * 128 + (lane & 15) * 8;
@@ -186,6 +222,7 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
     if (row < rows) fetch_row(row);
 
     for (; row < rows; row += row_step) {
+        float yv[IDENT ? NS : 1][8];          // IDENT: the row, normalised, stays in registers
         // ---- 0. residual add; the sum is the new residual stream and the row quantised below
         if (PRE == kAdd) {
 #pragma unroll
@@ -237,13 +274,21 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
 #pragma unroll
                     for (int e = 0; e < 8; ++e) f[e] = (f[e] * r) * g[e];
                 }
-                *reinterpret_cast<float4 *>(ybuf + 8 * v)     = make_float4(f[0], f[1], f[2], f[3]);
-                *reinterpret_cast<float4 *>(ybuf + 8 * v + 4) = make_float4(f[4], f[5], f[6], f[7]);
+                if constexpr (IDENT) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) yv[i][e] = f[e];
+                } else {
+                    *reinterpret_cast<float4 *>(ybuf + 8 * v)     = make_float4(f[0], f[1], f[2], f[3]);
+                    *reinterpret_cast<float4 *>(ybuf + 8 * v + 4) = make_float4(f[4], f[5], f[6], f[7]);
+                }
+            } else if constexpr (IDENT) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) yv[i][e] = 0.0f;
             }
         }
         // the next row's loads fly while this one is quantised
         if (row + row_step < rows) fetch_row(row + row_step);
-        __syncthreads();
+        if (!IDENT) __syncthreads();
 
         // ---- 3./4. reorder, group amax, scale, quantise, pack ----------------
 #pragma unroll
@@ -256,42 +301,26 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
             float amax = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                uint32_t o = off[j][OPACK ? e / 2 : e];
-                if (OPACK) {
-                    // unpacked here, per row: hoisted out of the row loop the unpacked
-                    // offsets would take the registers the packing saves
-                    asm volatile("" : "+v"(o));
-                    o = e % 2 ? (o >> 16) << 2 : (o & 0xffffu) << 2;
+                if constexpr (IDENT) {
+                    y[e] = yv[j][e];
+                } else {
+                    uint32_t o = off[j][OPACK ? e / 2 : e];
+                    if (OPACK) {
+                        // unpacked here, per row: hoisted out of the row loop the unpacked
+                        // offsets would take the registers the packing saves
+                        asm volatile("" : "+v"(o));
+                        o = e % 2 ? (o >> 16) << 2 : (o & 0xffffu) << 2;
+                    }
+                    y[e] = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(ybuf) + o);
                 }
-                y[e] = *reinterpret_cast<const float *>(reinterpret_cast<const unsigned char *>(ybuf) + o);
                 amax = fmaxf(amax, fabsf(y[e]));
             }
             amax = row16_max_dpp(amax);
 
             const bool  is4   = gg < G4;
-            // normal channels: n = nbits (4, or 3 with the codes still in nibbles), outliers n = 8
-            const float denom = is4 ? (nbits == 3 ? 7.0f : 15.0f) : 255.0f;
-            const float qmin  = is4 ? (nbits == 3 ? -4.0f : -8.0f) : -128.0f;
-            const float qmax  = is4 ? (nbits == 3 ? 3.0f : 7.0f) : 127.0f;
-            const float s32   = ((2.0f * amax) * clip) / denom;
-            const __half sh   = (s32 > 65504.0f) ? __ushort_as_half((unsigned short)0x7bffu)
-                                                 : __float2half_rn(s32);
-            const float s     = __half2float(sh);
-            const float r0    = __builtin_amdgcn_rcpf(s);
-            const float e0    = fmaf(-s, r0, 1.0f);
-            const float r1    = fmaf(e0, r0, r0);
             int q[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float qf = y[e] * r1;
-                float t  = fmaf(-s, qf, y[e]);
-                qf = fmaf(t, r1, qf);
-                t  = fmaf(-s, qf, y[e]);
-                qf = fmaf(t, r1, qf);
-                qf = rintf(qf);
-                qf = fminf(fmaxf(qf, qmin), qmax);
-                q[e] = (int)qf;
-            }
+            float s;
+            const __half sh = quantise_lane8(y, amax, is4, nbits, clip, q, s);
             const bool nz = s != 0.0f;
             if (live) {
                 if (is4) {
@@ -312,7 +341,7 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
                 if ((lane & 15) == 0) scale[row * (int64_t)G + gg] = sh;
             }
         }
-        __syncthreads();   // ybuf is rewritten by the next row
+        if (!IDENT || NORM) __syncthreads();   // ybuf and qbuf are rewritten by the next row
     }
 }
 

@@ -97,3 +97,35 @@ def test_decode_linear_limits():
     y = atom.atom_decode_linear(torch.zeros((0, 512), dtype=torch.float16, device="cuda"), None, 0.0,
                                 dev(lin.idx), *gw)
     assert y.shape == (0, 16)
+
+
+@pytest.mark.parametrize("M,K,N,O,norm", [
+    (1, 4096, 4096, 128, False),     # one wavefront per row
+    (8, 4096, 256, 128, True),       # the same with RMSNorm: the wavefront's own sum of squares
+    (16, 4096, 48, 128, True),       # two rows per wavefront
+    (8, 11008, 4096, 128, False),    # Llama-7B down projection behind a permuted gate/up: 22 vectors per lane, ragged
+    (5, 8192, 130, 128, True),       # RMSNorm over a long row: the workgroup-wide routine without its gather
+    (16, 12288, 32, 128, True),
+    (3, 1408, 40, 128, False),
+    (7, 768, 24, 256, True),         # two INT8 groups
+])
+def test_decode_linear_without_index(M, K, N, O, norm):
+    """No reorder index: x already is in reordered order.  Codes as the oracle's with the identity index."""
+    print(f"[case] decode linear, no index, M={M} K={K} N={N} O={O} norm={norm}", flush=True)
+    lin = _rand_linear(M, K, N, O, seed=M * 17 + K + N, norm=norm)
+    ident = np.arange(K, dtype=np.int32)
+    gw = atom.atom_quantize_weight(dev(lin.w), None, lin.group_size, O, lin.clip_weight)
+    rw = oracle.quantize_weight(lin.w.numpy(), ident, lin.group_size, O, lin.clip_weight)
+    assert_quant_equal(gw, rw, "weight")
+    y, codes = atom.atom_decode_linear(dev(lin.x), dev(lin.gamma), lin.eps, None, *gw, lin.group_size, lin.clip_act,
+                                       debug=True)
+    torch.cuda.synchronize()
+    ra = oracle.quantize_act(lin.x.numpy(), None if lin.gamma is None else lin.gamma.numpy(), lin.eps, ident,
+                             lin.group_size, O, lin.clip_act)
+    assert_quant_equal(codes, ra, "activation codes computed in the prologue")
+    ref = oracle.w4a4_gemm(*ra, *rw, lin.group_size)
+    assert y_rel_err(npy(y), ref["y"]) <= Y_TOL
+    qa = atom.atom_quantize_act(dev(lin.x), dev(lin.gamma), lin.eps, None, lin.group_size, O, lin.clip_act)
+    y2 = atom.atom_w4a4_gemm(*qa, *gw, lin.group_size)
+    torch.cuda.synchronize()
+    assert y_rel_err(npy(y), npy(y2)) <= Y_TOL
