@@ -108,6 +108,14 @@ class DeviceLinear:
         self.turn += 1
         atom.atom_decode_linear(self.x, self.gamma, l.eps, self.idx, *qw, l.group_size, l.clip_act, out=self.y)
 
+    def one_launch_no_index(self):
+        """The same for an input that already is in reordered order (the producer's weight rows were
+        permuted offline): no gather, one wavefront per row."""
+        l = self.lin
+        qw = self.qw_ring[self.turn % len(self.qw_ring)]
+        self.turn += 1
+        atom.atom_decode_linear(self.x, self.gamma, l.eps, None, *qw, l.group_size, l.clip_act, out=self.y)
+
 
 def run_steps(layers, steps, warmup, clock_warmup_s=0.0):
     """Time `steps` passes; HIP events (on the stream the kernels run on)
@@ -271,6 +279,18 @@ def decode_sweep():
             step_bytes = L.gemm_bytes - lin.M * ((lin.K - lin.n_outlier) // 2 + lin.n_outlier + 2 * L.G) + 2 * lin.M * lin.K
             entry["step_us_in_graph_one_launch"] = one * 1e6
             entry["one_launch_hbm_frac"] = step_bytes / one / 1e9 / PEAK_HBM_GBS
+            # outside a graph the host's launch cost dominates these sizes: one launch instead of two
+            for _ in range(20):
+                L.one_launch()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(200):
+                L.one_launch()
+            torch.cuda.synchronize()
+            entry["step_us_eager_one_launch"] = (time.perf_counter() - t0) / 200 * 1e6
+            one_n = decode_gemm_in_graph(L, copies, L.one_launch_no_index)
+            entry["step_us_in_graph_one_launch_no_index"] = one_n * 1e6
+            entry["one_launch_no_index_hbm_frac"] = step_bytes / one_n / 1e9 / PEAK_HBM_GBS
         out.append(entry)
         del L
         torch.cuda.empty_cache()
@@ -586,17 +606,37 @@ def mlp_block_chain():
         atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], idx2, out=qa2)
         atom.atom_w4a4_gemm_packed(*qa2, w2p, K, out=y2, workspace=a2p)
 
+    # the same chain with the down projection's reorder fused into the producer: the rows of the
+    # gate and up weights are permuted once, offline, and silu(gate)*up is quantised without an index
+    rows = torch.cat([idx2, idx2 + I]).to(torch.int32)
+    w1_perm = atom.atom_quantize_weight(atom.atom_permute_rows(up_lin.w.cuda(), rows), idx1, up_lin.group_size,
+                                        up_lin.n_outlier, up_lin.clip_weight)
+    w1pp = atom.atom_pack_weight(*w1_perm)
+    del w1_perm
+
+    def chain_packed_fused_reorder():
+        atom.atom_add_quantize_act(x, res, gamma, up_lin.eps, idx1, sum_out=hsum, out=qa1)
+        atom.atom_w4a4_gemm_packed(*qa1, w1pp, 2 * I, out=y1, workspace=a1p)
+        atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], None, out=qa2)
+        atom.atom_w4a4_gemm_packed(*qa2, w2p, K, out=y2, workspace=a2p)
+
     t = graph_time(chain)
     tp = graph_time(chain_packed)
+    tpf = graph_time(chain_packed_fused_reorder)
     t_swiglu = graph_time(lambda: atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], idx2, out=qa2), 50, 4)
+    t_swiglu_in_order = graph_time(lambda: atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], None, out=qa2), 50, 4)
     ops = 2 * M * (2 * I) * K + 2 * M * K * I
     codes = (I - down_lin.n_outlier) // 2 + down_lin.n_outlier + 2 * (I // down_lin.group_size)
     sw_bytes = M * (2 * 2 * I + codes)
     return {"workload": "Llama-7B MLP block chain M=1024 (add+RMSNorm+quant -> gate/up -> swiglu+quant -> down), HIP graph",
             "us_per_block_packed_weights": tp * 1e6, "effective_tops_packed_weights": ops / tp / 1e12,
+            "us_per_block_packed_weights_reorder_fused_into_gate_up": tpf * 1e6,
+            "effective_tops_packed_weights_reorder_fused_into_gate_up": ops / tpf / 1e12,
             "us_per_block_canonical_weights": t * 1e6, "effective_tops_canonical_weights": ops / t / 1e12,
             "swiglu_front_end_us": t_swiglu * 1e6, "swiglu_front_end_bytes": sw_bytes,
-            "swiglu_front_end_hbm_frac": sw_bytes / t_swiglu / 1e9 / PEAK_HBM_GBS}
+            "swiglu_front_end_hbm_frac": sw_bytes / t_swiglu / 1e9 / PEAK_HBM_GBS,
+            "swiglu_front_end_no_index_us": t_swiglu_in_order * 1e6,
+            "swiglu_front_end_no_index_hbm_frac": sw_bytes / t_swiglu_in_order / 1e9 / PEAK_HBM_GBS}
 
 
 def measured_traffic(config):
@@ -630,6 +670,8 @@ def main():
                     help="rows of each linear the CPU oracle is timed on (256 rows of config 5 take about 20 s)")
     ap.add_argument("--decode-only", action="store_true",
                     help="only the decode-sized GEMM sweep (for profiler runs)")
+    ap.add_argument("--mlp-only", action="store_true",
+                    help="only the Llama-7B MLP block chain (for profiler runs)")
     ap.add_argument("--kv-only", action="store_true",
                     help="print only the INT4 KV-cache measurements (a short run to put under rocprofv3)")
     ap.add_argument("--layer-only", action="store_true",
@@ -656,6 +698,9 @@ def main():
 
     if args.decode_only:
         print(json.dumps({"decode_sweep": decode_sweep()}))
+        return
+    if args.mlp_only:
+        print(json.dumps({"mlp_block_chain": mlp_block_chain()}))
         return
     if args.kv_only:
         print(json.dumps({"kv_cache": kv_cache_measurements()}))

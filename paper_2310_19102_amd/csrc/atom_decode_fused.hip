@@ -6,10 +6,15 @@
 // Every workgroup owns 16 output channels and all of K, as in the stand-alone decode GEMM,
 // and needs the quantised codes of all M rows.  M is tiny, so each workgroup quantises the
 // rows itself, into LDS, with the row routine of the stand-alone front end (bit-identical
-// codes and scales), while the first batch of its weight loads is already in flight:
-//   1. every wavefront issues the loads of the first groups of its K-slice;
-//   2. the workgroup walks the M rows through the front-end routine; codes and scales land
-//      in LDS in the canonical layout ([M][K4/2] nibbles, [M][O] bytes, [M][G] fp16);
+// codes and scales), while the first batch of its weight loads is in flight.  Every CU repeats
+// that work (M K elements at some 20 vector operations each, one to two microseconds per row of
+// 4096 channels), which is why the kernel pays only for the smallest batches:
+//   1. the workgroup walks the M rows through the front-end routine (with the reorder index, or
+//      without its gather when x already is in reordered order); codes and scales land in LDS in
+//      the canonical layout ([M][K4/2] nibbles, [M][O] bytes, [M][G] fp16);
+//   2. right after the loads of the first row of x, every wavefront issues the loads of the first
+//      groups of its K-slice (loads return in order: issued earlier, they would hold the front
+//      end back until the weights have arrived from HBM);
 //   3. each wavefront multiplies its K-slice (INT8 MFMA 16x16x64 on nibbles widened to the
 //      high half of a byte, the 2^-8 folded into the weight scale), dequantises per group
 //      with fused multiply-adds in fp32, ascending groups;
@@ -63,90 +68,10 @@ __device__ __forceinline__ v4i widen_hi(const uint4 &w)
     return __builtin_bit_cast(v4i, t);
 }
 
-// The front end for a row that already is in reordered channel order (no index): one wavefront
-// per row, nothing staged, no barrier.  Lane l holds the vectors l + 64 i of the row, so its share
-// of the sum of squares is the one the workgroup-wide routine folds (vector v -> lane v mod 64 in
-// increasing v, then the xor butterfly), and a 16-lane row of the wavefront holds one group.
-template <bool NORM, int NV>
-__device__ __forceinline__
-void quantise_row_in_order(const __half *xr, const __half *gamma, float eps, int K, int O, int nbits, float clip,
-                           uint8_t *a4r, int8_t *a8r, uint16_t *asr, int lane)
-{
-    const int V = K >> 3, K4 = K - O, G4 = K4 >> 7;
-    uint4 raw[NV];
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int v = lane + 64 * i;
-        raw[i] = v < V ? *reinterpret_cast<const uint4 *>(xr + 8 * v) : make_uint4(0, 0, 0, 0);
-    }
-    float r = 1.0f;
-    if (NORM) {
-        float L = 0.0f;
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            float f[8];
-            halves_to_floats(raw[i], f);
-            float s0 = f[0] * f[0], s1 = f[1] * f[1], s2 = f[2] * f[2], s3 = f[3] * f[3];
-            float s4 = f[4] * f[4], s5 = f[5] * f[5], s6 = f[6] * f[6], s7 = f[7] * f[7];
-            const float qv = ((s0 + s1) + (s2 + s3)) + ((s4 + s5) + (s6 + s7));
-            if (lane + 64 * i < V) L = L + qv;
-        }
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) L = L + __shfl_xor(L, d, 64);
-        const float mean = L / (float)K;
-        r = 1.0f / sqrtf(mean + eps);
-    }
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int  v    = lane + 64 * i;
-        const bool live = v < V;
-        const int  g    = v >> 4;                       // group of this 16-lane row
-        float y[8];
-        halves_to_floats(raw[i], y);
-        if (NORM) {
-            float gm[8];
-            halves_to_floats(live ? *reinterpret_cast<const uint4 *>(gamma + 8 * v) : make_uint4(0, 0, 0, 0), gm);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) y[e] = (y[e] * r) * gm[e];
-        }
-        float amax = 0.0f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(y[e]));
-        amax = row16_max_dpp(amax);
-        const bool is4 = g < G4;
-        int   q[8];
-        float s;
-        const __half sh = quantise_lane8(y, amax, is4, nbits, clip, q, s);
-        const bool nz = s != 0.0f;
-        if (live) {
-            if (is4) {
-                uint32_t w = 0;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) w |= (uint32_t)(q[e] & 0xF) << (4 * e);
-                *reinterpret_cast<uint32_t *>(a4r + 4 * v) = nz ? w : 0u;
-            } else {
-                uint32_t w0 = 0, w1 = 0;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    w0 |= (uint32_t)(q[e] & 0xFF) << (8 * e);
-                    w1 |= (uint32_t)(q[e + 4] & 0xFF) << (8 * e);
-                }
-                *reinterpret_cast<uint2 *>(a8r + (8 * v - K4)) = make_uint2(nz ? w0 : 0u, nz ? w1 : 0u);
-            }
-            if ((lane & 15) == 0) asr[g] = __half_as_ushort(sh);
-        }
-        // one vector after the other: interleaved, the temporaries of all NV of them are live at once
-        __builtin_amdgcn_sched_barrier(0);
-    }
-}
-
 // NORM: RMSNorm in the front end.  NS: register sets of the front end (K <= 4096 * NS).
 // DEPTH: groups whose weight loads are in flight together per wavefront.
-// MODE: kGather = with a reorder index, the workgroup-wide row routine; kWavePerRow, kInOrder =
-// no index (x already is in reordered order): one wavefront per row, or (RMSNorm over long rows,
-// where a wavefront cannot hold a row in registers) the workgroup-wide routine without its gather.
-constexpr int kGather = 0, kWavePerRow = 1, kInOrder = 2;
-template <bool NORM, int NS, int DEPTH, int MODE>
+// IDENT: no reorder index (x already is in reordered order): the row routine without its gather.
+template <bool NORM, int NS, int DEPTH, bool IDENT>
 __global__ __launch_bounds__(NT)
 void decode_linear_kernel(const FusedParams p)
 {
@@ -194,23 +119,16 @@ void decode_linear_kernel(const FusedParams p)
             wsc[d] = ws[gc];
         }
     };
-    load_weights(g_begin);
 
     // ---- the front end, all rows, into LDS ---------------------------------------------------
-    if constexpr (MODE == kWavePerRow) {
-        for (int m = wave; m < M; m += NW)
-            quantise_row_in_order<NORM, 8 * NS>(p.x + (int64_t)m * p.ldx, p.gamma, p.eps, K, O, p.nbits, p.clip,
-                                                a4 + (size_t)m * (K4 >> 1), a8 + (size_t)m * O, as + (size_t)m * G,
-                                                lane);
-        __syncthreads();
-    } else {
-        quantize_rows_fast_body<NORM, NS, NT, kPlain, MODE == kInOrder>(front, 0, 1, p.x, M, p.ldx, nullptr, 0,
-                                                                        nullptr, 0, p.gamma, p.eps, p.idx, K, O,
-                                                                        p.nbits, p.clip, a4, a8,
-                                                                        reinterpret_cast<__half *>(as));
-        if (MODE == kInOrder && !NORM) __syncthreads();       // (that variant of the routine has no barrier)
-        // (the routine ends on a barrier: every code and scale is in LDS)
-    }
+    // The first weight loads are issued from inside the routine, right after the loads of its
+    // first row: loads return in order, and the routine must not wait for the weights.
+    quantize_rows_fast_body<NORM, NS, NT, kPlain, IDENT>(front, 0, 1, p.x, M, p.ldx, nullptr, 0, nullptr, 0,
+                                                         p.gamma, p.eps, p.idx, K, O, p.nbits, p.clip, a4, a8,
+                                                         reinterpret_cast<__half *>(as),
+                                                         [&]() { load_weights(g_begin); });
+    if (IDENT && !NORM) __syncthreads();       // (that variant of the routine has no barrier of its own)
+    // every code and scale is in LDS
     if (p.dbg_q4 && blockIdx.x == 0) {
         for (int i = tid; i < M * (K4 >> 1) / 4; i += NT)
             reinterpret_cast<uint32_t *>(p.dbg_q4)[i] = reinterpret_cast<const uint32_t *>(a4)[i];
@@ -275,23 +193,17 @@ void decode_linear_kernel(const FusedParams p)
     }
 }
 
-int mode_of(int K, bool norm, bool ident)
-{
-    return !ident ? kGather : (norm && K > 4096 ? kInOrder : kWavePerRow);
-}
-
 unsigned front_bytes(int K, bool norm, bool ident)
 {
-    const int mode = mode_of(K, norm, ident);
-    const unsigned need = mode == kWavePerRow ? 0u : 4u * (unsigned)((mode == kGather ? K : 0) + (norm ? K / 8 : 0));
+    const unsigned need = 4u * (unsigned)((ident ? 0 : K) + (norm ? K / 8 : 0));
     const unsigned red  = NW * 4 * 64 * 4;
     return ((need > red ? need : red) + 15u) & ~15u;
 }
 
-template <bool NORM, int NS, int DEPTH, int MODE>
+template <bool NORM, int NS, int DEPTH, bool IDENT>
 hipError_t launch_cfg(const FusedParams &p, size_t lds, hipStream_t stream)
 {
-    auto kern = &decode_linear_kernel<NORM, NS, DEPTH, MODE>;
+    auto kern = &decode_linear_kernel<NORM, NS, DEPTH, IDENT>;
     static atom_launch::LdsOptIn opt_in;
     hipError_t err = atom_launch::ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), lds);
     if (err != hipSuccess) return err;
@@ -307,13 +219,8 @@ hipError_t launch_depth(const FusedParams &p, size_t lds, hipStream_t stream)
     const bool blocks4 = G % 2 == 0 && G >= 4;
     const int nblk = blocks4 ? (G + 3) >> 2 : G;
     const int run = (blocks4 ? 4 : 1) * ((nblk + NW - 1) / NW);
-    if (p.idx) return run <= 4 ? launch_cfg<NORM, NS, 4, kGather>(p, lds, stream) : launch_cfg<NORM, NS, 8, kGather>(p, lds, stream);
-    if constexpr (NORM && NS > 1)
-        return run <= 4 ? launch_cfg<NORM, NS, 4, kInOrder>(p, lds, stream) : launch_cfg<NORM, NS, 8, kInOrder>(p, lds, stream);
-    else if constexpr (NS > 2)       // a wavefront holds 96 registers of the row: the short batch of weight loads
-        return launch_cfg<NORM, NS, 4, kWavePerRow>(p, lds, stream);
-    else
-        return run <= 4 ? launch_cfg<NORM, NS, 4, kWavePerRow>(p, lds, stream) : launch_cfg<NORM, NS, 8, kWavePerRow>(p, lds, stream);
+    if (p.idx) return run <= 4 ? launch_cfg<NORM, NS, 4, false>(p, lds, stream) : launch_cfg<NORM, NS, 8, false>(p, lds, stream);
+    return run <= 4 ? launch_cfg<NORM, NS, 4, true>(p, lds, stream) : launch_cfg<NORM, NS, 8, true>(p, lds, stream);
 }
 
 }  // namespace

@@ -153,14 +153,18 @@ __device__ __forceinline__ __half quantise_lane8(const float (&y)[8], float amax
 // of the paper: the reorder fused into the prior operator): thread t's vector t + NT*i is its own
 // share of group (t + NT*i) / 16, nothing is staged or gathered, idx is not read and lds holds
 // the K / 8 sums of squares only (NORM) or nothing.
-template <bool NORM, int NS, int NT, int PRE, bool IDENT = false>
+struct NoHook { __device__ __forceinline__ void operator()() const {} };
+
+// after_first_fetch is called once, right after the global loads of the first row are issued (a
+// caller with loads of its own that may take longer to return issues them there).
+template <bool NORM, int NS, int NT, int PRE, bool IDENT = false, class Hook = NoHook>
 __device__ __forceinline__
 void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
                              const __half *x, int64_t rows, int64_t ld,
                              const __half *res, int64_t ldr, __half *sum_out, int64_t ldo,
                              const __half *__restrict__ gamma, float eps,
                              const int32_t *__restrict__ idx, int K, int O, int nbits, float clip,
-                             uint8_t *q4, int8_t *q8, __half *scale)
+                             uint8_t *q4, int8_t *q8, __half *scale, Hook after_first_fetch = Hook())
 {
     float *ybuf = lds;                        // [K]   staged row, original channel order (not IDENT)
     float *qbuf = lds + (IDENT ? 0 : K);      // [K/8] per-vector sums of squares (NORM only)
@@ -220,6 +224,7 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
     };
     int64_t row = row_first;
     if (row < rows) fetch_row(row);
+    after_first_fetch();
 
     for (; row < rows; row += row_step) {
         float yv[IDENT ? NS : 1][8];          // IDENT: the row, normalised, stays in registers
