@@ -97,6 +97,12 @@ class DeviceLinear:
         self.turn += 1
         atom.atom_w4a4_gemm(*self.qa, *qw, self.lin.group_size, out=self.y)
 
+    def gemm_tiled(self):
+        """Decode-sized GEMM on weight codes re-tiled into whole lines per load (M <= 64)."""
+        t4, t8, ws = self.tiled_ring[self.turn % len(self.tiled_ring)]
+        self.turn += 1
+        atom.atom_w4a4_gemm_decode_tiled(*self.qa, t4, t8, ws, self.lin.group_size, out=self.y)
+
     def two_launches(self):
         self.front_end()
         self.gemm()
@@ -264,11 +270,21 @@ def decode_sweep():
         copies = max(2, int(1.2e9 // (lin.N * row)) + 1)
         L = DeviceLinear(lin, n_weight_copies=copies)
         per = decode_gemm_in_graph(L, copies)
+        # the same GEMM on re-tiled weight codes (the canonical copies are replaced, one at a time)
+        L.tiled_ring = []
+        for i in range(len(L.qw_ring)):
+            q4, q8, ws = L.qw_ring[i]
+            L.tiled_ring.append((*atom.atom_tile_weight_decode(q4, q8, lin.group_size), ws))
+        per_tiled = decode_gemm_in_graph(L, copies, L.gemm_tiled)
+        del L.tiled_ring
+        torch.cuda.empty_cache()
         t, ge, fe, pk, _ = run_steps([L], 100, 10, 0.02)
         entry = {"workload": f"config3 decode M={lin.M} K=4096 N={lin.N}, weight ring of {copies}",
                  "gemm_us_in_graph": per * 1e6, "gemm_bytes": L.gemm_bytes,
                  "gemm_GBs": L.gemm_bytes / per / 1e9,
                  "gemm_hbm_frac": L.gemm_bytes / per / 1e9 / PEAK_HBM_GBS,
+                 "gemm_us_in_graph_tiled_weights": per_tiled * 1e6,
+                 "gemm_hbm_frac_tiled_weights": L.gemm_bytes / per_tiled / 1e9 / PEAK_HBM_GBS,
                  "step_us_front_end_plus_gemm": t * 1e6,
                  "effective_tops": L.ops / t / 1e12}
         # the whole linear (front end + GEMM) inside a graph: two launches, and the one-launch kernel

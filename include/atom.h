@@ -182,6 +182,36 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8,
                            size_t workspace_bytes, void *stream);
 
 /*
+ * Decode-sized group GEMM (M <= 64) on weight codes re-tiled for it (Section 3:
+ * at these sizes a dense layer is bound by reading its weights; Section 4.2
+ * for the arithmetic).  atom_tile_weight_decode rewrites the canonical code
+ * arrays once, offline, into blocks of 16 rows x one group x 64 lanes x 16
+ * bytes, so that every load instruction of the kernel reads whole 128-byte
+ * lines (the canonical rows, (K - O)/2 bytes long, start in the middle of
+ * lines); rows past N are zeros.  Scales stay canonical.  Same arithmetic and
+ * the same sum over groups as atom_w4a4_gemm at these sizes: bit-identical Y.
+ *
+ *   atom_tile_weight_decode_bytes(N, d, which)   size of the tiled INT4
+ *                 (which = 0) or INT8 (which = 1) array: ceil(N/16)*16 rows
+ *   w_q4_tiled / w_q8_tiled   16-byte aligned device arrays of those sizes
+ * atom_w4a4_gemm_decode_tiled: ATOM_ERR_UNSUPPORTED unless M <= 64,
+ * n_outlier = 128, K/128 a multiple of 4 and at least 8, and the arrays stay
+ * below 4 GiB; both scale arrays 8-byte aligned (ATOM_ERR_ALIGN).
+ */
+size_t atom_tile_weight_decode_bytes(int64_t N, const atom_desc *d, int which);
+atom_status atom_tile_weight_decode(const void *w_q4, const void *w_q8, int64_t N,
+                                    const atom_desc *d, void *w_q4_tiled,
+                                    size_t q4_bytes, void *w_q8_tiled,
+                                    size_t q8_bytes, void *stream);
+atom_status atom_w4a4_gemm_decode_tiled(const void *a_q4, const void *a_q8,
+                                        const void *a_scale, int64_t M,
+                                        const void *w_q4_tiled,
+                                        const void *w_q8_tiled,
+                                        const void *w_scale, int64_t N,
+                                        const atom_desc *d, void *y_f16,
+                                        int64_t ldy, void *stream);
+
+/*
  * Offline helper of the fused reorder (Section 4.1: the reorder index is known
  * after calibration, so the operator that PRODUCES an activation can emit it
  * in reordered order at no run-time cost):  out[r, :] = in[row_idx[r], :] over

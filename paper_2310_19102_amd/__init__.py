@@ -29,6 +29,8 @@ from .binding import (  # noqa: F401
     atom_w4a4_gemm_workspace_bytes,
     atom_decode_linear,
     atom_permute_rows,
+    atom_tile_weight_decode,
+    atom_w4a4_gemm_decode_tiled,
     atom_decode_linear_lds_bytes,
     atom_pack_weight,
     atom_pack_act,

@@ -22,6 +22,9 @@ EXPORTS = (
     "atom_quantize_weight",
     "atom_w4a4_gemm",
     "atom_w4a4_gemm_workspace_bytes",
+    "atom_tile_weight_decode_bytes",
+    "atom_tile_weight_decode",
+    "atom_w4a4_gemm_decode_tiled",
     "atom_permute_rows",
     "atom_decode_linear",
     "atom_decode_linear_lds_bytes",
@@ -89,6 +92,12 @@ def load_library():
     L.atom_w4a4_gemm.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, dp, vp, i64, vp, vp, sz, vp]
     L.atom_w4a4_gemm_workspace_bytes.restype = sz
     L.atom_w4a4_gemm_workspace_bytes.argtypes = [i64, i64, dp]
+    L.atom_tile_weight_decode_bytes.restype = sz
+    L.atom_tile_weight_decode_bytes.argtypes = [i64, dp, i32]
+    L.atom_tile_weight_decode.restype = ctypes.c_int
+    L.atom_tile_weight_decode.argtypes = [vp, vp, i64, dp, vp, sz, vp, sz, vp]
+    L.atom_w4a4_gemm_decode_tiled.restype = ctypes.c_int
+    L.atom_w4a4_gemm_decode_tiled.argtypes = [vp, vp, vp, i64, vp, vp, vp, i64, dp, vp, i64, vp]
     L.atom_permute_rows.restype = ctypes.c_int
     L.atom_permute_rows.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp]
     L.atom_decode_linear.restype = ctypes.c_int
@@ -214,6 +223,42 @@ def atom_quantize_act(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float
     if st != 0:
         raise AtomError(st, "atom_quantize_act")
     return q4, q8, sc
+
+
+def atom_tile_weight_decode(w_q4: torch.Tensor, w_q8: torch.Tensor, group_size: int = 128):
+    """Re-tile canonical weight codes for ``atom_w4a4_gemm_decode_tiled`` (once, offline).  Returns
+    ``(w_q4_tiled, w_q8_tiled)`` as flat uint8 / int8 device tensors."""
+    L = load_library()
+    _dev(w_q4, torch.uint8, "w_q4")
+    _dev(w_q8, torch.int8, "w_q8")
+    N, O = w_q8.shape
+    K = 2 * w_q4.shape[1] + O
+    d = _desc(K, group_size, O, 4)
+    b4 = int(L.atom_tile_weight_decode_bytes(N, ctypes.byref(d), 0))
+    b8 = int(L.atom_tile_weight_decode_bytes(N, ctypes.byref(d), 1))
+    t4 = torch.empty(b4, dtype=torch.uint8, device=w_q4.device)
+    t8 = torch.empty(b8, dtype=torch.int8, device=w_q4.device)
+    st = L.atom_tile_weight_decode(_ptr(w_q4), _ptr(w_q8), N, ctypes.byref(d), _ptr(t4), b4, _ptr(t8), b8, _stream())
+    if st != 0:
+        raise AtomError(st, "atom_tile_weight_decode")
+    return t4, t8
+
+
+def atom_w4a4_gemm_decode_tiled(a_q4, a_q8, a_scale, w_q4_tiled, w_q8_tiled, w_scale, group_size: int = 128,
+                                out: Optional[torch.Tensor] = None):
+    """Decode-sized group GEMM (M <= 64) on re-tiled weight codes; ``w_scale`` [N, G] canonical."""
+    L = load_library()
+    M, O = a_q8.shape
+    N, G = w_scale.shape
+    K = G * group_size
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=a_q4.device)
+    d = _desc(K, group_size, O, 4)
+    st = L.atom_w4a4_gemm_decode_tiled(_ptr(a_q4), _ptr(a_q8), _ptr(a_scale), M, _ptr(w_q4_tiled), _ptr(w_q8_tiled),
+                                       _ptr(w_scale), N, ctypes.byref(d), _ptr(y),
+                                       y.stride(0) if M > 1 else max(N, y.stride(0)), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_w4a4_gemm_decode_tiled")
+    return y
 
 
 def atom_permute_rows(mat: torch.Tensor, row_idx: torch.Tensor, out: Optional[torch.Tensor] = None):

@@ -198,6 +198,65 @@ atom_status atom_decode_linear(const void *x_f16, int64_t M, int64_t ldx, const 
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
+size_t atom_tile_weight_decode_bytes(int64_t N, const atom_desc *d, int which)
+{
+    if (check_desc(d) != ATOM_OK || N <= 0 || (which != 0 && which != 1)) return 0;
+    const size_t rows = (size_t)((N + 15) / 16) * 16;
+    return rows * (which == 0 ? (size_t)(d->K - d->n_outlier) / 2 : (size_t)d->n_outlier);
+}
+
+atom_status atom_tile_weight_decode(const void *w_q4, const void *w_q8, int64_t N, const atom_desc *d,
+                                    void *w_q4_tiled, size_t q4_bytes, void *w_q8_tiled, size_t q8_bytes,
+                                    void *stream)
+{
+    atom_status st = check_desc(d);
+    if (st != ATOM_OK) return st;
+    if (N < 0) return ATOM_ERR_SHAPE;
+    if (N == 0) return ATOM_OK;
+    if (!w_q4 || !w_q8 || !w_q4_tiled || !w_q8_tiled) return ATOM_ERR_NULL;
+    if (!aligned(w_q4, 16) || !aligned(w_q8, 16) || !aligned(w_q4_tiled, 16) || !aligned(w_q8_tiled, 16))
+        return ATOM_ERR_ALIGN;
+    if (q4_bytes < atom_tile_weight_decode_bytes(N, d, 0) || q8_bytes < atom_tile_weight_decode_bytes(N, d, 1))
+        return ATOM_ERR_WORKSPACE;
+    if ((N + 15) / 16 > 0x7fffffff) return ATOM_ERR_UNSUPPORTED;
+    hipError_t err = atom_internal::launch_tile_weight_decode(w_q4, w_q8, N, d->K, d->n_outlier, w_q4_tiled,
+                                                              w_q8_tiled, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
+atom_status atom_w4a4_gemm_decode_tiled(const void *a_q4, const void *a_q8, const void *a_scale, int64_t M,
+                                        const void *w_q4_tiled, const void *w_q8_tiled, const void *w_scale,
+                                        int64_t N, const atom_desc *d, void *y_f16, int64_t ldy, void *stream)
+{
+    atom_status st = check_desc(d);
+    if (st != ATOM_OK) return st;
+    if (M < 0 || N < 0 || ldy < N) return ATOM_ERR_SHAPE;
+    if (M == 0 || N == 0) return ATOM_OK;
+    if (!a_q4 || !a_q8 || !a_scale || !w_q4_tiled || !w_q8_tiled || !w_scale || !y_f16) return ATOM_ERR_NULL;
+    if (!aligned(a_q4, 16) || !aligned(a_q8, 16) || !aligned(a_scale, 8) || !aligned(w_q4_tiled, 16) ||
+        !aligned(w_q8_tiled, 16) || !aligned(w_scale, 8) || !aligned(y_f16, 2))
+        return ATOM_ERR_ALIGN;
+    atom_internal::GemmArgs g;
+    g.a_q4 = static_cast<const uint8_t *>(a_q4);
+    g.a_q8 = static_cast<const int8_t *>(a_q8);
+    g.a_scale = static_cast<const uint16_t *>(a_scale);
+    g.M = M;
+    g.w_q4 = static_cast<const uint8_t *>(w_q4_tiled);
+    g.w_q8 = static_cast<const int8_t *>(w_q8_tiled);
+    g.w_scale = static_cast<const uint16_t *>(w_scale);
+    g.N = N;
+    g.K = d->K;
+    g.O = d->n_outlier;
+    g.y = static_cast<uint16_t *>(y_f16);
+    g.ldy = ldy;
+    g.partials = nullptr;
+    g.workspace = nullptr;
+    g.workspace_bytes = 0;
+    if (!atom_internal::decode_tiled_supported(g)) return ATOM_ERR_UNSUPPORTED;
+    hipError_t err = atom_internal::launch_w4a4_gemm_decode_tiled(g, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
 size_t atom_pack_weight_bytes(int64_t N, const atom_desc *d)
 {
     if (check_desc(d) != ATOM_OK || N <= 0) return 0;

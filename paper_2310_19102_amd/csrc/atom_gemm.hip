@@ -379,4 +379,27 @@ hipError_t launch_w4a4_gemm(const GemmArgs &a, hipStream_t stream)
     return a.partials ? dispatch<true>(p, stream) : dispatch<false>(p, stream);
 }
 
+static GemmParams params_of(const GemmArgs &a)
+{
+    GemmParams p;
+    p.a_q4 = a.a_q4; p.a_q8 = a.a_q8; p.a_scale = a.a_scale;
+    p.w_q4 = a.w_q4; p.w_q8 = a.w_q8; p.w_scale = a.w_scale;
+    p.y = a.y; p.partials = nullptr;
+    p.M = a.M; p.N = a.N; p.ldy = a.ldy; p.K = a.K; p.O = a.O;
+    return p;
+}
+
+bool decode_tiled_supported(const GemmArgs &a) { return atom_gemm::decode_tiled_supported(params_of(a)); }
+
+hipError_t launch_w4a4_gemm_decode_tiled(const GemmArgs &a, hipStream_t stream)
+{
+    return atom_gemm::launch_decode_tiled(params_of(a), stream);
+}
+
+hipError_t launch_tile_weight_decode(const void *q4, const void *q8, int64_t N, int K, int O, void *t4, void *t8,
+                                     hipStream_t stream)
+{
+    return atom_gemm::launch_tile_weight(q4, q8, N, K, O, t4, t8, stream);
+}
+
 }  // namespace atom_internal

@@ -53,6 +53,11 @@ hipError_t launch_big(const GemmParams &p, hipStream_t stream);
 
 // Weight-streaming kernel for decode-sized M <= 64 (atom_gemm_decode.hip).
 hipError_t launch_decode(const GemmParams &p, hipStream_t stream);
+// The same on weight codes re-tiled by launch_tile_weight (w_q4, w_q8 of p are the tiled arrays).
+hipError_t launch_tile_weight(const void *q4, const void *q8, int64_t N, int K, int O, void *t4, void *t8,
+                              hipStream_t stream);
+bool decode_tiled_supported(const GemmParams &p);
+hipError_t launch_decode_tiled(const GemmParams &p, hipStream_t stream);
 
 }  // namespace atom_gemm
 #endif

@@ -63,7 +63,10 @@ __device__ __forceinline__ v4i widen_hi(const uint4 &w)
 //     last wavefront's run.  The second 64 bytes of its rows then have registers of their own, and
 //     the slots hold one 16-byte piece each: 24 registers less per row block, which is what lets two
 //     workgroups share a CU once every load of a batch is in flight at the same time.
-template <int RB, bool VS, bool ONE8 = false, bool Q4 = false>
+// TILED (with ONE8): the weight codes were re-tiled for this kernel (tile_weight_kernel below):
+//     block of 16 rows, group, lane -> 16 bytes, so one load instruction of a wavefront reads 1 KB
+//     of consecutive bytes (eight whole 128-byte lines) instead of sixteen 64-byte pieces.
+template <int RB, bool VS, bool ONE8 = false, bool Q4 = false, bool TILED = false>
 __global__ __launch_bounds__(NT, (ONE8 && RB == 1 && Q4) ? 6 : 1)    // six wavefronts per SIMD = three workgroups per CU: 80 registers
 void w4a4_gemm_decode_kernel(const GemmParams p)
 {
@@ -110,7 +113,10 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
     }
     // ONE8 addresses every load as scalar base + 32-bit byte offset (arrays below 4 GiB: host),
     // one register per stream instead of a 64-bit pointer per load
-    const uint32_t w4o = (uint32_t)(wr * (K4 >> 1)) + kc * 16, w8o = (uint32_t)(wr * p.O) + kc * 16;
+    static_assert(!TILED || ONE8, "the tiled layout is read by the one-INT8-group variants");
+    constexpr uint32_t GSTEP = TILED ? 1024u : 64u;      // from one group's piece to the next, and to the second half of the INT8 group
+    const uint32_t w4o = TILED ? (uint32_t)blockIdx.x * (uint32_t)(G4 * 1024) + lane * 16 : (uint32_t)(wr * (K4 >> 1)) + kc * 16;
+    const uint32_t w8o = TILED ? (uint32_t)blockIdx.x * 2048u + lane * 16 : (uint32_t)(wr * p.O) + kc * 16;
     uint32_t a4o[RB], a8o[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -149,7 +155,7 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
             // (an INT4 slot leaves its second half alone: writing zeros there made the compiler wait
             // for every load in flight, since one of an earlier batch might still target the register)
             if constexpr (ONE8) {         // one load per slot: array and offset are scalar selects
-                wq[d][0] = *reinterpret_cast<const uint4 *>((is4 ? p.w_q4 : w8b) + (is4 ? w4o + (uint32_t)gc * 64u : w8o));
+                wq[d][0] = *reinterpret_cast<const uint4 *>((is4 ? p.w_q4 : w8b) + (is4 ? w4o + (uint32_t)gc * GSTEP : w8o));
             } else if (is4) {
                 wq[d][0] = *reinterpret_cast<const uint4 *>(w4 + (size_t)gc * 64);
             } else {
@@ -182,7 +188,7 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
             // a batch without the INT8 group reads the first piece of its first group once more.
             const bool has8 = g_end > G4 && gb + DEPTH >= g_end;
             const int  g0   = gb < G4 ? gb : G4 - 1;
-            wx = *reinterpret_cast<const uint4 *>((has8 ? w8b : p.w_q4) + (has8 ? w8o + 64u : w4o + (uint32_t)g0 * 64u));
+            wx = *reinterpret_cast<const uint4 *>((has8 ? w8b : p.w_q4) + (has8 ? w8o + GSTEP : w4o + (uint32_t)g0 * GSTEP));
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
                 ax[rb] = *reinterpret_cast<const uint4 *>((has8 ? a8b : p.a_q4) + (has8 ? a8o[rb] + 64u : a4o[rb] + (uint32_t)g0 * 64u));
@@ -259,9 +265,62 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
     }
 }
 
+// Re-tiling of the canonical weight codes for the TILED variants: one workgroup per block of 16
+// rows; rows past N are zeros.
+__global__ __launch_bounds__(256)
+void tile_weight_kernel(const uint8_t *__restrict__ q4, const int8_t *__restrict__ q8, int64_t N, int K4h, int O,
+                        uint8_t *__restrict__ t4, uint8_t *__restrict__ t8)
+{
+    const int64_t blk = blockIdx.x;
+    const int G4 = K4h >> 6, G8 = O >> 7;
+    // INT4: piece p = (group, lane) -> row blk*16 + (lane & 15), bytes [64 g + 16 (lane >> 4), +16)
+    for (int p = threadIdx.x; p < G4 * 64; p += 256) {
+        const int g = p >> 6, l = p & 63;
+        const int64_t row = blk * 16 + (l & 15);
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (row < N) v = *reinterpret_cast<const uint4 *>(q4 + row * K4h + g * 64 + (l >> 4) * 16);
+        *reinterpret_cast<uint4 *>(t4 + (blk * G4 + g) * 1024 + l * 16) = v;
+    }
+    // INT8: piece (group, half, lane) -> row, bytes [128 g + 64 half + 16 (lane >> 4), +16)
+    for (int p = threadIdx.x; p < G8 * 128; p += 256) {
+        const int g = p >> 7, h = (p >> 6) & 1, l = p & 63;
+        const int64_t row = blk * 16 + (l & 15);
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (row < N) v = *reinterpret_cast<const uint4 *>(q8 + row * O + g * 128 + h * 64 + (l >> 4) * 16);
+        *reinterpret_cast<uint4 *>(t8 + ((blk * G8 + g) * 2 + h) * 1024 + l * 16) = v;
+    }
+}
+
 }  // namespace
 
 namespace atom_gemm {
+
+hipError_t launch_tile_weight(const void *q4, const void *q8, int64_t N, int K, int O, void *t4, void *t8,
+                              hipStream_t stream)
+{
+    hipLaunchKernelGGL(tile_weight_kernel, dim3((unsigned)((N + TN - 1) / TN)), dim3(256), 0, stream,
+                       (const uint8_t *)q4, (const int8_t *)q8, N, (K - O) >> 1, O, (uint8_t *)t4, (uint8_t *)t8);
+    return hipGetLastError();
+}
+
+// What the tiled variants need: one INT8 group that is the last group of the last wavefront's run,
+// whole blocks of four groups with 8-byte aligned scale rows, M <= 64.
+bool decode_tiled_supported(const GemmParams &p)
+{
+    const int G = p.K >> 7;
+    return p.M <= 64 && p.O == 128 && G >= NW && G % 4 == 0 &&
+           ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 7) == 0 &&
+           (uint64_t)(p.N + TN) * (uint64_t)(p.K >> 1) < (1ull << 32) && (uint64_t)p.N * (uint64_t)G < (1ull << 31);
+}
+
+hipError_t launch_decode_tiled(const GemmParams &p, hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)((p.N + TN - 1) / TN);
+    if (p.M <= 16)      hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+    else if (p.M <= 32) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+    else                hipLaunchKernelGGL((w4a4_gemm_decode_kernel<4, true, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+    return hipGetLastError();
+}
 
 hipError_t launch_decode(const GemmParams &p, hipStream_t stream)
 {

@@ -34,6 +34,13 @@ struct GemmArgs {
 size_t     gemm_workspace_bytes(int64_t M, int64_t N, int K, int O);
 hipError_t launch_w4a4_gemm(const GemmArgs &a, hipStream_t stream);
 
+// Decode-sized GEMM (M <= 64) on weight codes re-tiled into whole 128-byte lines per load
+// (atom_gemm_decode.hip); w_q4 / w_q8 of the arguments are the tiled arrays, scales canonical.
+bool       decode_tiled_supported(const GemmArgs &a);
+hipError_t launch_w4a4_gemm_decode_tiled(const GemmArgs &a, hipStream_t stream);
+hipError_t launch_tile_weight_decode(const void *q4, const void *q8, int64_t N, int K, int O, void *t4, void *t8,
+                                     hipStream_t stream);
+
 // Group GEMM on pre-tiled operands, INT4 groups carried in FP6 (atom_gemm_f6.hip): bytes of the
 // tiled image of `rows` rows, the packing kernel (canonical q4 / q8 / scale -> image), the GEMM.
 size_t     f6_packed_bytes(int64_t rows, int K, int O);

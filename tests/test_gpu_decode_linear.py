@@ -129,3 +129,33 @@ def test_decode_linear_without_index(M, K, N, O, norm):
     y2 = atom.atom_w4a4_gemm(*qa, *gw, lin.group_size)
     torch.cuda.synchronize()
     assert y_rel_err(npy(y), npy(y2)) <= Y_TOL
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 4096, 4096), (8, 4096, 11008), (16, 4096, 200), (32, 4096, 4096),
+                                   (64, 4096, 1030), (8, 11264, 4090), (3, 1024, 16)])
+def test_decode_gemm_on_tiled_weights_is_bit_identical(M, K, N):
+    """Weight codes re-tiled into whole 128-byte lines per load: same arithmetic, same tree, same Y
+    as the canonical decode-sized GEMM, which the other tests hold against the oracle; ragged N
+    (rows past N are zeros in the tiled arrays)."""
+    print(f"[case] tiled decode weights M={M} K={K} N={N}", flush=True)
+    lin = _rand_linear(M, K, N, 128, seed=M + K + N, norm=False)
+    gw = gpu_quantize_weight(lin)
+    qa = atom.atom_quantize_act(dev(lin.x), None, 0.0, dev(lin.idx), 128, 128, lin.clip_act)
+    t4, t8 = atom.atom_tile_weight_decode(gw[0], gw[1])
+    y = atom.atom_w4a4_gemm(*qa, *gw)
+    yt = atom.atom_w4a4_gemm_decode_tiled(*qa, t4, t8, gw[2])
+    torch.cuda.synchronize()
+    assert torch.equal(y, yt)
+    ra = ref_quantize_act(lin)
+    ref = oracle.w4a4_gemm(*ra, *ref_quantize_weight(lin), 128)
+    assert y_rel_err(npy(yt), ref["y"]) <= Y_TOL
+
+
+def test_decode_tiled_limits():
+    lin = _rand_linear(4, 768, 32, 256, seed=8)          # two INT8 groups: not taken
+    gw = gpu_quantize_weight(lin)
+    qa = atom.atom_quantize_act(dev(lin.x), dev(lin.gamma), lin.eps, dev(lin.idx), 128, 256, lin.clip_act)
+    t4, t8 = atom.atom_tile_weight_decode(gw[0], gw[1])
+    with pytest.raises(atom.AtomError) as e:
+        atom.atom_w4a4_gemm_decode_tiled(*qa, t4, t8, gw[2])
+    assert e.value.status == 3
