@@ -507,16 +507,18 @@ atom_status atom_mx_gemm(const void *a_q4, const void *a_q8, const void *a_e8,
  * are reordered by their indices).  From calibration activations X [T, ldx]
  * fp16 (device; T rows of K channels, e.g. the inputs a layer saw on the
  * calibration sentences):
- *   stat[k] = sum_t X[t, k]^2 in double, the rows of a chunk of 256 added in
- *             ascending order, then the chunk sums in ascending order
- *   idx     = the channels in ascending order of (stat, channel number): a
+ *   stat[k] = sum_t X[t, k]^2, exact: every square is a multiple of 2^-48
+ *             below 2^32, so the sum is an integer of at most 112 bits in any
+ *             order of the additions; reported as the nearest double (ties to
+ *             even); Inf and NaN count as magnitude 2^16
+ *   idx     = the channels in ascending order of (exact stat, channel number): a
  *             permutation whose last O entries are the O channels with the
  *             highest square sums, for every O; equal channels keep their order
  * idx is what atom_quantize_act / atom_quantize_weight (and the MX variants)
  * take as reorder_idx.  Results are bit-exact.  T == 0 gives the identity.
  *
  *   workspace  device scratch of atom_calibrate_reorder_workspace_bytes(T, K)
- *              bytes, 8-byte aligned; its last K doubles hold stat afterwards
+ *              bytes, 16-byte aligned; its last K doubles hold stat afterwards
  *   idx_out    device int32 [K]
  * Errors: ATOM_ERR_NULL, ATOM_ERR_SHAPE (T < 0, K <= 0, ldx < K),
  * ATOM_ERR_UNSUPPORTED (K > 32768), ATOM_ERR_ALIGN, ATOM_ERR_WORKSPACE.

@@ -631,33 +631,42 @@ int atom_ref_mx_gemm(const uint8_t *a_q4, const uint8_t *a_q8, const uint8_t *a_
 /* ------------------------------------------------ offline calibration -- */
 /* Section 5.1: the outlier channels are the ones with the highest square sum
  * over the calibration activations; activations and weights are reordered by
- * their indices.  Statistic of channel k: sum_t x[t,k]^2 in double, the rows
- * of a chunk of 256 added in ascending order and the chunk sums added in
- * ascending order (one fixed tree, so the value is unique).  Index: channels in
- * ascending order of (statistic, channel number): the O largest come last for
- * every O, and equal channels keep their order. */
+ * their indices.  Statistic of channel k: sum_t x[t,k]^2, EXACTLY: the square
+ * of an fp16 value is an integer multiple of 2^-48 below 2^32, so the sum is
+ * an integer of at most 112 bits whatever the order of the additions.  It is
+ * reported as the nearest double (one rounding, ties to even); channels are
+ * ranked by the exact integers.  Inf and NaN count as magnitude 2^16.
+ * Index: channels in ascending order of (statistic, channel number): the O
+ * largest come last for every O, and equal channels keep their order. */
+static unsigned __int128 square_units(uint16_t h)     /* x^2 in units of 2^-48 */
+{
+    unsigned e = (h >> 10) & 31u, f = h & 1023u;
+    uint64_t m;
+    int      E;                                         /* |x| = m * 2^E */
+    if (e == 0) { m = f; E = -24; }
+    else if (e == 31) { m = 1024; E = 6; }
+    else { m = 1024 + f; E = (int)e - 25; }
+    return (unsigned __int128)(m * m) << (2 * E + 48);
+}
+
 int atom_ref_calibrate_reorder(const uint16_t *x, int64_t T, int64_t ldx, int32_t K,
                                double *stat, int32_t *idx)
 {
     if (T < 0 || K <= 0 || ldx < K) return -1;
+    unsigned __int128 *exact = (unsigned __int128 *)malloc((size_t)K * sizeof(unsigned __int128));
+    if (!exact) return -1;
     for (int32_t k = 0; k < K; ++k) {
-        double s = 0.0;
-        for (int64_t c = 0; c < T; c += 256) {
-            double part = 0.0;
-            int64_t end = c + 256 < T ? c + 256 : T;
-            for (int64_t t = c; t < end; ++t) {
-                double v = (double)atom_ref_f16_to_f32(x[t * ldx + k]);
-                part += v * v;
-            }
-            s += part;
-        }
-        stat[k] = s;
+        unsigned __int128 s = 0;
+        for (int64_t t = 0; t < T; ++t) s += square_units(x[t * ldx + k]);
+        exact[k] = s;
+        stat[k] = ldexp((double)s, -48);                /* integer -> double rounds to nearest even */
     }
     for (int32_t i = 0; i < K; ++i) {
         int32_t rank = 0;
         for (int32_t j = 0; j < K; ++j)
-            if (stat[j] < stat[i] || (stat[j] == stat[i] && j < i)) ++rank;
+            if (exact[j] < exact[i] || (exact[j] == exact[i] && j < i)) ++rank;
         idx[rank] = i;
     }
+    free(exact);
     return 0;
 }

@@ -201,10 +201,11 @@ int atom_ref_mx_gemm(const uint8_t *a_q4, const uint8_t *a_q8, const uint8_t *a_
                      uint16_t *y_f16, int64_t ldy);
 
 /* ---- Offline calibration (Section 5.1): per-channel square sum of the
- * calibration activations x [T, ldx] fp16 in double (rows of a 256-row chunk in
- * ascending order, then the chunks in ascending order), and the reorder index:
- * channels in ascending order of (square sum, channel number), so that the O
- * channels with the highest square sums come last. */
+ * calibration activations x [T, ldx] fp16, exact (an integer count of 2^-48,
+ * independent of the order of the additions; reported as the nearest double),
+ * and the reorder index: channels in ascending order of (exact square sum,
+ * channel number), so that the O channels with the highest square sums come
+ * last. */
 int atom_ref_calibrate_reorder(const uint16_t *x_f16, int64_t T, int64_t ldx, int32_t K,
                                double *stat /* [K] */, int32_t *idx /* [K] */);
 

@@ -528,7 +528,7 @@ atom_status atom_calibrate_reorder(const void *x_f16, int64_t T, int64_t ldx, in
     if (T < 0 || K <= 0 || ldx < K) return ATOM_ERR_SHAPE;
     if (K > atom_internal::kMaxK || (T + 255) / 256 > 65535) return ATOM_ERR_UNSUPPORTED;
     if (!idx_out || !workspace || (T > 0 && !x_f16)) return ATOM_ERR_NULL;
-    if (!aligned(x_f16, 2) || !aligned(workspace, 8) || !aligned(idx_out, 4)) return ATOM_ERR_ALIGN;
+    if (!aligned(x_f16, 2) || !aligned(workspace, 16) || !aligned(idx_out, 4)) return ATOM_ERR_ALIGN;
     if (workspace_bytes < atom_internal::calibrate_workspace_bytes(T, K)) return ATOM_ERR_WORKSPACE;
     hipError_t err = atom_internal::launch_calibrate_reorder(x_f16, T, ldx, K, workspace, idx_out,
                                                              static_cast<hipStream_t>(stream));

@@ -26,9 +26,18 @@ def test_statistic_against_exact_rationals_and_numpy():
     sigma = np.exp(1.5 * rng.standard_normal(64))
     x = (rng.standard_normal((1000, 64)) * sigma).astype(np.float16)
     stat, idx = oracle.calibrate_reorder(x)
-    for k in (0, 13, 63):
+    # the statistic is the exact rational sum rounded once (Fraction -> float rounds to nearest even)
+    for k in range(64):
         exact = sum(Fraction(float(v)) ** 2 for v in x[:, k])
-        assert abs(Fraction(float(stat[k])) - exact) <= exact * Fraction(1, 2 ** 45)
+        assert float(stat[k]) == float(exact)
+    # ... which no fixed order of double additions reproduces on every channel of this input: a
+    # chunked or a sequential double sum in place of the exact one fails this pin
+    x64 = x.astype(np.float64) ** 2
+    seq = np.zeros(64)
+    for t in range(1000):
+        seq += x64[t]
+    chunk = sum(x64[c:c + 256].sum(axis=0) for c in range(0, 1000, 256))
+    assert (seq != stat).any() and (chunk != stat).any()
     ref = np.square(x.astype(np.float64)).sum(axis=0)
     assert np.allclose(stat, ref, rtol=1e-12, atol=0)
     # heavy-tailed channels are far apart: the index is the plain stable argsort
@@ -36,6 +45,25 @@ def test_statistic_against_exact_rationals_and_numpy():
     # a permutation whose last 8 entries are the 8 largest channels
     assert sorted(idx.tolist()) == list(range(64))
     assert set(idx[-8:].tolist()) == set(np.argsort(ref)[-8:].tolist())
+
+
+def test_order_of_rows_does_not_matter_and_special_values():
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((900, 32)) * np.exp(2.0 * rng.standard_normal(32))).astype(np.float16)
+    x[::2, 0] = 65504.0
+    x[1::2, 0] = 6e-8                                     # the smallest subnormal beside the largest value
+    x[:, 1] = 6e-8
+    stat, idx = oracle.calibrate_reorder(x)
+    s2, i2 = oracle.calibrate_reorder(x[rng.permutation(900)])
+    assert np.array_equal(stat.view(np.uint64), s2.view(np.uint64)) and np.array_equal(idx, i2)
+    tiny = float(np.float16(6e-8)) ** 2
+    assert stat[1] == 900 * tiny                          # 900 * 2^-48: exact
+    assert stat[0] == float(450 * Fraction(65504) ** 2 + 450 * Fraction(tiny))
+    y = np.ones((4, 3), np.float16)
+    y[0, 1] = np.inf
+    y[1, 2] = np.nan
+    stat, idx = oracle.calibrate_reorder(y)               # Inf and NaN count as magnitude 2^16
+    assert stat.tolist() == [4.0, 3.0 + 2.0 ** 32, 3.0 + 2.0 ** 32] and idx.tolist() == [0, 1, 2]
 
 
 def test_chunking_and_edge_shapes():
