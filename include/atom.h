@@ -548,7 +548,7 @@ double atom_mfma_rate_probe(int32_t kind, int32_t iters, void *scratch4,
 atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K);
 
 /* Static, NUL-terminated description of a status code. */
-const char *atom_status_string(atom_status s);
+const char *atom_status_string(int status);   /* any int: values that are no atom_status give "unknown status" */
 
 #ifdef __cplusplus
 }

@@ -571,9 +571,9 @@ atom_status atom_check_reorder_idx(const int32_t *idx_host, int32_t K)
     return st;
 }
 
-const char *atom_status_string(atom_status s)
+const char *atom_status_string(int status)
 {
-    switch (s) {
+    switch (status) {
     case ATOM_OK:              return "ok";
     case ATOM_ERR_NULL:        return "a required pointer is NULL";
     case ATOM_ERR_SHAPE:       return "invalid shape, leading dimension or reorder index";
