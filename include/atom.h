@@ -52,7 +52,7 @@ typedef enum {
     ATOM_OK              = 0,
     ATOM_ERR_NULL        = 1,  /* a required pointer is NULL                   */
     ATOM_ERR_SHAPE       = 2,  /* negative size, ld too small, K % Gs != 0 ... */
-    ATOM_ERR_UNSUPPORTED = 3,  /* Gs != 128, bits not (4, 8) or (3, 8), K too large */
+    ATOM_ERR_UNSUPPORTED = 3,  /* a group size, bit width, K or shape the entry point does not take */
     ATOM_ERR_ALIGN       = 4,  /* a pointer or leading dimension is misaligned */
     ATOM_ERR_WORKSPACE   = 5,  /* workspace missing or too small               */
     ATOM_ERR_HIP         = 6   /* the HIP runtime refused the launch           */
@@ -61,7 +61,10 @@ typedef enum {
 /* The quantisation set-up of Section 5.1: { K, 128, 128, 4, 8 }. */
 typedef struct {
     int32_t K;             /* input channels of the linear layer            */
-    int32_t group_size;    /* Gs, Section 4.2                               */
+    int32_t group_size;    /* Gs, Section 4.2: 128; 64 and 256 (the variation
+                              of Section 5.4.1) on the front-end entry points
+                              and atom_w4a4_gemm, on plain kernels; all other
+                              entry points: ATOM_ERR_UNSUPPORTED            */
     int32_t n_outlier;     /* O, Section 4.1                                */
     int32_t bits_normal;   /* 4, or 3 (W3A3, Section 5.2)                   */
     int32_t bits_outlier;  /* 8                                             */

@@ -16,12 +16,15 @@ inline bool aligned(const void *p, uintptr_t a)
     return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;
 }
 
-atom_status check_desc(const atom_desc *d)
+// other_groups: the entry point also takes the group sizes 64 and 256 (the front ends and
+// atom_w4a4_gemm); everything else is built around the group of 128
+atom_status check_desc(const atom_desc *d, bool other_groups = false)
 {
     if (!d) return ATOM_ERR_NULL;
     if (d->K <= 0 || d->group_size <= 0 || d->n_outlier < 0) return ATOM_ERR_SHAPE;
-    if (d->group_size != atom_internal::kGroup || (d->bits_normal != 4 && d->bits_normal != 3) ||
-        d->bits_outlier != 8)
+    const bool gs_ok = d->group_size == atom_internal::kGroup ||
+                       (other_groups && (d->group_size == 64 || d->group_size == 256));
+    if (!gs_ok || (d->bits_normal != 4 && d->bits_normal != 3) || d->bits_outlier != 8)
         return ATOM_ERR_UNSUPPORTED;
     if (d->K % d->group_size || d->n_outlier % d->group_size) return ATOM_ERR_SHAPE;
     if (d->n_outlier >= d->K) return ATOM_ERR_SHAPE;
@@ -35,7 +38,7 @@ atom_status quantize_common(const void *x, int64_t rows, int64_t ld, int pre, co
                             const int32_t *idx, const atom_desc *d, float clip, void *q4,
                             void *q8, void *scale, void *stream)
 {
-    atom_status st = check_desc(d);
+    atom_status st = check_desc(d, true);
     if (st != ATOM_OK) return st;
     if (rows < 0 || ld < d->K) return ATOM_ERR_SHAPE;
     if (pre != 0 && ldr < d->K) return ATOM_ERR_SHAPE;
@@ -53,7 +56,7 @@ atom_status quantize_common(const void *x, int64_t rows, int64_t ld, int pre, co
                                                          gamma, eps, idx, d->K, d->n_outlier,
                                                          d->bits_normal, clip,
                                                          q4, q8, scale,
-                                                         static_cast<hipStream_t>(stream));
+                                                         static_cast<hipStream_t>(stream), d->group_size);
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
@@ -98,7 +101,7 @@ atom_status atom_quantize_weight(const void *w_f16, int64_t N, int64_t ldw,
 
 size_t atom_w4a4_gemm_workspace_bytes(int64_t M, int64_t N, const atom_desc *d)
 {
-    if (check_desc(d) != ATOM_OK || M <= 0 || N <= 0) return 0;
+    if (check_desc(d, true) != ATOM_OK || M <= 0 || N <= 0) return 0;
     return atom_internal::gemm_workspace_bytes(M, N, d->K, d->n_outlier);
 }
 
@@ -107,7 +110,7 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8, const void *a_sca
                            const atom_desc *d, void *y_f16, int64_t ldy, int32_t *partials_dbg,
                            void *workspace, size_t workspace_bytes, void *stream)
 {
-    atom_status st = check_desc(d);
+    atom_status st = check_desc(d, true);
     if (st != ATOM_OK) return st;
     if (M < 0 || N < 0 || ldy < N) return ATOM_ERR_SHAPE;
     if (M == 0 || N == 0) return ATOM_OK;
@@ -146,6 +149,11 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8, const void *a_sca
     g.partials = partials_dbg;
     g.workspace = workspace;
     g.workspace_bytes = workspace_bytes;
+    if (d->group_size != atom_internal::kGroup) {
+        if ((M + 63) / 64 > 65535) return ATOM_ERR_UNSUPPORTED;         // grid rows of the plain kernel
+        hipError_t e2 = atom_internal::launch_w4a4_gemm_gs(g, d->group_size, static_cast<hipStream_t>(stream));
+        return e2 == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+    }
     hipError_t err = atom_internal::launch_w4a4_gemm(g, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }

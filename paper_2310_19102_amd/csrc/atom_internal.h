@@ -20,7 +20,7 @@ size_t quantize_lds_bytes(int K, bool norm);
 hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, int pre, const void *res,
                                 int64_t ldr, void *sum_out, int64_t ldo, const void *gamma,
                                 float eps, const int32_t *idx, int K, int O, int nbits, float clip,
-                                void *q4, void *q8, void *scale, hipStream_t stream);
+                                void *q4, void *q8, void *scale, hipStream_t stream, int group_size = 128);
 
 struct GemmArgs {
     const uint8_t *a_q4; const int8_t *a_q8; const uint16_t *a_scale; int64_t M;
@@ -33,6 +33,8 @@ struct GemmArgs {
 
 size_t     gemm_workspace_bytes(int64_t M, int64_t N, int K, int O);
 hipError_t launch_w4a4_gemm(const GemmArgs &a, hipStream_t stream);
+// Group sizes 64 and 256 (atom_gemm_gs.hip): one plain kernel, a single ascending chain of groups.
+hipError_t launch_w4a4_gemm_gs(const GemmArgs &a, int group_size, hipStream_t stream);
 
 // Decode-sized GEMM (M <= 64) on weight codes re-tiled into whole 128-byte lines per load
 // (atom_gemm_decode.hip); w_q4 / w_q8 of the arguments are the tiled arrays, scales canonical.

@@ -43,8 +43,10 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
                           const __half *__restrict__ gamma, float eps,
                           const int32_t *__restrict__ idx, int K, int O, int nbits, float clip,
                           uint8_t *__restrict__ q4, int8_t *__restrict__ q8,
-                          __half *__restrict__ scale)
+                          __half *__restrict__ scale, int gl)
 {
+    // gl: lanes per group = group size / 8 (8, 16 or 32; Section 5.4.1 of the paper varies the
+    // group size); the MX variant passes 16 (its sweep of 128 channels holds four MX blocks)
     extern __shared__ __align__(16) float lds[];
     float *ybuf = lds;            // [K]   staged row, original channel order
     float *qbuf = lds + K;        // [K/8] per-vector sums of squares (NORM only)
@@ -54,8 +56,11 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: group decisions become scalar
     const int V    = K >> 3;      // 8-channel vectors per row
     const int K4   = K - O;
-    const int G    = K >> 7;
-    const int G4   = K4 >> 7;
+    const int gs   = 8 * gl;      // group size
+    const int glsh = 31 - __builtin_clz((unsigned)gl);
+    const int G    = K / gs;
+    const int G4   = K4 / gs;
+    const int gpw  = 64 / gl;     // groups per wavefront sweep
 
     for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
         const __half *xr = x + row * ld;
@@ -111,11 +116,11 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
         }
 
         // ---- 3./4. reorder, group amax, scale, quantise, pack ----------------
-        // A wavefront sweep covers 4 groups: DPP row (lane/16) <-> group.
-        for (int g = 4 * wave + (lane >> 4); g < ((G + 3) & ~3); g += 4 * (kThreads / 64)) {
-            const bool live = g < G;          // ragged last sweep: whole 16-lane rows idle
+        // A wavefront sweep covers 64 / gl groups: gl consecutive lanes <-> group.
+        for (int g = gpw * wave + (lane >> glsh); g < ((G + gpw - 1) & ~(gpw - 1)); g += gpw * (kThreads / 64)) {
+            const bool live = g < G;          // ragged last sweep: whole groups of lanes idle
             const int  gg   = live ? g : G - 1;
-            const int  j0   = gg * 128 + (lane & 15) * 8;
+            const int  j0   = gg * gs + (lane & (gl - 1)) * 8;
             int id[8];
             if (idx) {
                 const int4 i0 = *reinterpret_cast<const int4 *>(idx + j0);
@@ -181,7 +186,7 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
                 }
                 continue;
             }
-            amax = row16_max(amax);
+            for (int d = 1; d < gl; d <<= 1) amax = fmaxf(amax, __shfl_xor(amax, d, 64));   // max is exact in any order
 
             // normal channels: n = nbits (4, or 3 with the codes still in nibbles), outliers n = 8
             const float denom = is4 ? (nbits == 3 ? 7.0f : 15.0f) : 255.0f;
@@ -213,7 +218,7 @@ void quantize_rows_kernel(const __half *x, int64_t rows, int64_t ld,
                     }
                     *reinterpret_cast<uint2 *>(q8 + row * (int64_t)O + (j0 - K4)) = make_uint2(w0, w1);
                 }
-                if ((lane & 15) == 0) scale[row * (int64_t)G + gg] = sh;
+                if ((lane & (gl - 1)) == 0) scale[row * (int64_t)G + gg] = sh;
             }
         }
         __syncthreads();   // ybuf is rewritten by the next row
@@ -262,6 +267,7 @@ struct QuantArgs {
     const void *res; int64_t ldr; void *sum_out; int64_t ldo;     // second input row / fp16 sum out
     const void *gamma; float eps; const int32_t *idx; int K, O, nbits; float clip;
     void *q4, *q8, *scale;
+    int gs;                                                        // group size: 128, or 64 / 256 (plain kernel)
 };
 
 template <bool NORM, int NS, int NT, int PRE, bool IDENT = false>
@@ -299,14 +305,14 @@ hipError_t launch_plain(const QuantArgs &a, size_t lds, hipStream_t stream)
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, (const __half *)a.x, a.rows,
                        a.ld, (const __half *)a.res, a.ldr, (__half *)a.sum_out, a.ldo,
                        (const __half *)a.gamma, a.eps, a.idx, a.K, a.O, a.nbits, a.clip, (uint8_t *)a.q4,
-                       (int8_t *)a.q8, (__half *)a.scale);
+                       (int8_t *)a.q8, (__half *)a.scale, a.gs / 8);
     return hipGetLastError();
 }
 
 template <bool NORM, int PRE>
 hipError_t dispatch_quantize(const QuantArgs &a, hipStream_t stream)
 {
-    const bool sane_clip = a.clip >= 9.5367431640625e-07f && a.clip <= 1.0f;
+    const bool sane_clip = a.clip >= 9.5367431640625e-07f && a.clip <= 1.0f && a.gs == 128;   // what the fast kernels take
     if (!a.idx && a.K <= 32768 && sane_clip) {
         // no index: the row already is in reordered order; nothing is staged in LDS but the
         // sums of squares, so the register sets alone bound the threads per row
@@ -352,16 +358,17 @@ hipError_t launch_quantize_rows_mx(const void *x, int64_t rows, int64_t ld, cons
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, (const __half *)x, rows, ld,
                        (const __half *)nullptr, (int64_t)0, (__half *)nullptr, (int64_t)0,
                        (const __half *)gamma, eps, idx, K, O, 4, clip, (uint8_t *)q4, (int8_t *)q8,
-                       (__half *)e8);
+                       (__half *)e8, 16);
     return hipGetLastError();
 }
 
 hipError_t launch_quantize_rows(const void *x, int64_t rows, int64_t ld, int pre, const void *res,
                                 int64_t ldr, void *sum_out, int64_t ldo, const void *gamma,
                                 float eps, const int32_t *idx, int K, int O, int nbits, float clip,
-                                void *q4, void *q8, void *scale, hipStream_t stream)
+                                void *q4, void *q8, void *scale, hipStream_t stream, int group_size)
 {
-    const QuantArgs a = {x, rows, ld, pre, res, ldr, sum_out, ldo, gamma, eps, idx, K, O, nbits, clip, q4, q8, scale};
+    const QuantArgs a = {x, rows, ld, pre, res, ldr, sum_out, ldo, gamma, eps, idx, K, O, nbits, clip, q4, q8, scale,
+                         group_size};
     const bool norm = gamma != nullptr;
     if (pre == kSwiglu) return dispatch_quantize<false, kSwiglu>(a, stream);   // no norm behind an activation
     if (pre == kAdd)

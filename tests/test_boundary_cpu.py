@@ -59,7 +59,7 @@ def test_host_side_argument_validation_needs_no_gpu():
     assert q(p, 0, 4096, None, 0.0, p, ctypes.byref(ok), 0.9, p, p, p, None) == 0
     assert q(ctypes.c_void_p(0x1002), 4, 4096, None, 0.0, p, ctypes.byref(ok), 0.9, p, p, p, None) == 4
     assert q(p, 4, 4100, None, 0.0, p, ctypes.byref(ok), 0.9, p, p, p, None) == 4
-    for desc, want in ((D(4096, 64, 128, 4, 8), 3), (D(4096, 128, 128, 5, 8), 3), (D(4096, 128, 128, 2, 8), 3), (D(4096, 128, 128, 3, 4), 3),
+    for desc, want in ((D(4096, 32, 128, 4, 8), 3), (D(4096, 512, 512, 4, 8), 3), (D(4096, 128, 128, 5, 8), 3), (D(4096, 128, 128, 2, 8), 3), (D(4096, 128, 128, 3, 4), 3),
                        (D(4100, 128, 128, 4, 8), 2), (D(4096, 128, 100, 4, 8), 2),
                        (D(128, 128, 128, 4, 8), 2), (D(65536, 128, 128, 4, 8), 3),
                        (D(4096, 128, 0, 4, 8), 3)):

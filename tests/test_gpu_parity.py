@@ -246,7 +246,7 @@ def test_empty_and_error_paths():
         atom.atom_quantize_act(dev(lin.x[:, :500].contiguous()), None, 0.0, dev(lin.idx[:500]))
     assert e.value.status == 2          # K % 128 != 0
     with pytest.raises(atom.AtomError) as e:
-        atom.atom_quantize_act(dev(lin.x), None, 0.0, dev(lin.idx), group_size=64)
+        atom.atom_quantize_act(dev(lin.x), None, 0.0, dev(lin.idx), group_size=32)
     assert e.value.status == 3
 
 
