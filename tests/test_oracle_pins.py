@@ -392,7 +392,7 @@ def test_weight_path_equals_front_end_without_norm():
 # -------------------------------------------------------- GEMM brute force --
 
 @pytest.mark.parametrize("M,N,K,Gs,O", [(3, 5, 16, 2, 4), (4, 3, 32, 4, 8), (5, 7, 512, 128, 128),
-                                        (2, 4, 768, 128, 256)])
+                                        (2, 4, 768, 128, 256), (5, 7, 512, 64, 128), (3, 4, 1024, 256, 256)])
 def test_gemm_against_fp64_dequant_matmul(M, N, K, Gs, O):
     rng = np.random.default_rng(M * 100 + N)
     x, idx = _heavy(rng, M, K)
