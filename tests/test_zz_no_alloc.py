@@ -28,10 +28,12 @@ def _both(kv):
     want = atom.atom_decode_attention_kv4(q, k, v, sl, kv.sm_scale)
     got = torch.full_like(want, float("nan"))
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
+    # the number of device allocations made so far (a count of events: tensors of earlier tests
+    # that the garbage collector frees in the meantime do not change it)
+    before = torch.cuda.memory_stats().get("allocation.all.allocated", 0)
     atom.atom_decode_attention_kv4_static(q, k, v, sl, kv.sm_scale, out=got)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_stats().get("allocation.all.allocated", 0) == before, "the call allocated device memory"
     return got.cpu().numpy(), want.cpu().numpy()
 
 
