@@ -49,11 +49,18 @@ WORKLOAD_NAMES = {
 class DeviceLinear:
     """Device-resident operands of one quantised linear layer."""
 
-    def __init__(self, lin, n_weight_copies=1, packed=None):
+    def __init__(self, lin, n_weight_copies=1, packed=None, fused_retile=None):
         self.name, self.M, self.K, self.N = lin.name, lin.M, lin.K, lin.N
         self.G = lin.K // lin.group_size
         self.lin = lin
         self.packed = lin.M > 64 if packed is None else packed
+        # packed path: the front end can write the tiled activations itself (one launch less, no
+        # canonical arrays).  As kernel time it is 5-10 % behind front end + re-tiling pass (its 16-byte
+        # stores are scattered over the unit images), so it pays where the launches, not the kernels,
+        # set the pace: activations of up to 16 M elements
+        if fused_retile is None:
+            fused_retile = lin.M * lin.K <= (1 << 24)
+        self.fused_retile = fused_retile and self.packed
         self.x = lin.x.cuda()
         self.gamma = None if lin.gamma is None else lin.gamma.cuda()
         self.idx = lin.idx.cuda()
@@ -80,12 +87,17 @@ class DeviceLinear:
 
     def front_end(self):
         l = self.lin
+        if self.fused_retile:
+            atom.atom_quantize_act_packed(self.x, self.gamma, l.eps, self.idx, l.group_size, l.n_outlier,
+                                          l.clip_act, out=self.a_pk)
+            return
         atom.atom_quantize_act(self.x, self.gamma, l.eps, self.idx, l.group_size, l.n_outlier,
                                l.clip_act, out=self.qa)
 
     def pack(self):
-        """Re-tiling of the activation codes for the packed GEMM (nothing on the canonical path)."""
-        if self.packed:
+        """Re-tiling of the activation codes for the packed GEMM as a pass of its own (nothing on the
+        canonical path, and nothing when the front end writes the tiled layout itself)."""
+        if self.packed and not self.fused_retile:
             atom.atom_pack_act(*self.qa, self.lin.group_size, out=self.a_pk)
 
     def gemm(self):
@@ -148,26 +160,34 @@ def run_steps(layers, steps, warmup, clock_warmup_s=0.0):
     torch.cuda.synchronize()
     # one event between any two launches: events 3i .. 3i+3 around front end, re-tiling, GEMM of
     # launch group i
+    # (a layer without a re-tiling pass of its own gets no event for it: an empty bracket still
+    # costs a few microseconds of the step)
     n = steps * len(layers)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * n + 1)]
+    has_pass = [L.packed and not L.fused_retile for L in layers]
     t0 = time.perf_counter()
     i = 0
     ev[0].record()
     for _ in range(steps):
-        for L in layers:
+        for L, hp in zip(layers, has_pass):
             L.front_end()
             ev[3 * i + 1].record()
-            L.pack()
-            ev[3 * i + 2].record()
+            if hp:
+                L.pack()
+                ev[3 * i + 2].record()
             L.gemm()
             ev[3 * i + 3].record()
             i += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    fe = sum(ev[3 * j].elapsed_time(ev[3 * j + 1]) for j in range(n)) * 1e-3 / steps
-    pk = sum(ev[3 * j + 1].elapsed_time(ev[3 * j + 2]) for j in range(n)) * 1e-3 / steps
-    ge = sum(ev[3 * j + 2].elapsed_time(ev[3 * j + 3]) for j in range(n)) * 1e-3 / steps
-    return dt / steps, ge, fe, pk, len(layers)
+    fe = pk = ge = 0.0
+    for j in range(n):
+        hp = has_pass[j % len(layers)]
+        fe += ev[3 * j].elapsed_time(ev[3 * j + 1])
+        if hp:
+            pk += ev[3 * j + 1].elapsed_time(ev[3 * j + 2])
+        ge += ev[3 * j + 2 if hp else 3 * j + 1].elapsed_time(ev[3 * j + 3])
+    return dt / steps, ge * 1e-3 / steps, fe * 1e-3 / steps, pk * 1e-3 / steps, len(layers)
 
 
 def cpu_baseline(config, sample_rows):
@@ -245,12 +265,15 @@ def decode_gemm_in_graph(L, copies, fn=None):
     return per
 
 
-def step_summary(config, steps=100, warmup=10):
-    """Front end + re-tiling + GEMM of every linear of a configuration on the packed path."""
-    layers = [DeviceLinear(synth.make(config, w)) for w in range(len(synth.CONFIG_SHAPES[config]))]
+def step_summary(config, steps=100, warmup=10, fused_retile=None):
+    """Front end (+ re-tiling pass, when it is not fused into the front end) + GEMM of every linear of
+    a configuration on the packed path."""
+    layers = [DeviceLinear(synth.make(config, w), fused_retile=fused_retile)
+              for w in range(len(synth.CONFIG_SHAPES[config]))]
     t, ge, fe, pk, _ = run_steps(layers, steps, warmup, 0.1)
     ops = sum(L.ops for L in layers)
-    out = {"workload": WORKLOAD_NAMES[config] + " (packed weights)", "ms_per_step": t * 1e3,
+    how = ("re-tiling " + " / ".join("in the front end" if L.fused_retile else "as a pass" for L in layers))
+    out = {"workload": WORKLOAD_NAMES[config] + f" (packed weights; {how})", "ms_per_step": t * 1e3,
            "effective_tops": ops / t / 1e12, "gemm_us": ge * 1e6, "front_end_us": fe * 1e6, "retile_us": pk * 1e6,
            "gemm_tops": ops / ge / 1e12, "gemm_frac_of_int8_mfma_peak": ops / ge / 1e12 / PEAK_INT8_TOPS,
            "gemm_frac_of_fp6_mfma_peak": ops / ge / 1e12 / PEAK_FP6_TFLOPS}
@@ -320,6 +343,10 @@ def extra_measurements(headline_config):
     out = []
     other = 4 if headline_config != 4 else 5
     out.append(step_summary(other))
+    # both steps with the other choice for the activation re-tiling (fused into the front end:
+    # atom_quantize_act_packed; a pass of its own: atom_quantize_act, atom_pack_act)
+    out.append(step_summary(5, steps=30, fused_retile=True))
+    out.append(step_summary(4, steps=100, fused_retile=False))
     for packed in (True, False):
         L = DeviceLinear(synth.make(2, 0), packed=packed)
         t, ge, fe, pk, _ = run_steps([L], 200, 20, 0.05)
@@ -616,11 +643,17 @@ def mlp_block_chain():
         atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], idx2, out=qa2)
         atom.atom_w4a4_gemm(*qa2, *w2, out=y2)
 
-    def chain_packed():
+    def chain_packed_retile_pass():
         atom.atom_add_quantize_act(x, res, gamma, up_lin.eps, idx1, sum_out=hsum, out=qa1)
         atom.atom_w4a4_gemm_packed(*qa1, w1p, 2 * I, out=y1, workspace=a1p)
         atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], idx2, out=qa2)
         atom.atom_w4a4_gemm_packed(*qa2, w2p, K, out=y2, workspace=a2p)
+
+    def chain_packed():
+        atom.atom_add_quantize_act_packed(x, res, gamma, up_lin.eps, idx1, sum_out=hsum, out=a1p)
+        atom.atom_w4a4_gemm_prepacked(a1p, M, w1p, 2 * I, K, out=y1)
+        atom.atom_swiglu_quantize_act_packed(y1[:, :I], y1[:, I:], idx2, out=a2p)
+        atom.atom_w4a4_gemm_prepacked(a2p, M, w2p, K, I, out=y2)
 
     # the same chain with the down projection's reorder fused into the producer: the rows of the
     # gate and up weights are permuted once, offline, and silu(gate)*up is quantised without an index
@@ -631,13 +664,14 @@ def mlp_block_chain():
     del w1_perm
 
     def chain_packed_fused_reorder():
-        atom.atom_add_quantize_act(x, res, gamma, up_lin.eps, idx1, sum_out=hsum, out=qa1)
-        atom.atom_w4a4_gemm_packed(*qa1, w1pp, 2 * I, out=y1, workspace=a1p)
-        atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], None, out=qa2)
-        atom.atom_w4a4_gemm_packed(*qa2, w2p, K, out=y2, workspace=a2p)
+        atom.atom_add_quantize_act_packed(x, res, gamma, up_lin.eps, idx1, sum_out=hsum, out=a1p)
+        atom.atom_w4a4_gemm_prepacked(a1p, M, w1pp, 2 * I, K, out=y1)
+        atom.atom_swiglu_quantize_act_packed(y1[:, :I], y1[:, I:], None, out=a2p)
+        atom.atom_w4a4_gemm_prepacked(a2p, M, w2p, K, I, out=y2)
 
     t = graph_time(chain)
     tp = graph_time(chain_packed)
+    tpr = graph_time(chain_packed_retile_pass)
     tpf = graph_time(chain_packed_fused_reorder)
     t_swiglu = graph_time(lambda: atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], idx2, out=qa2), 50, 4)
     t_swiglu_in_order = graph_time(lambda: atom.atom_swiglu_quantize_act(y1[:, :I], y1[:, I:], None, out=qa2), 50, 4)
@@ -646,6 +680,7 @@ def mlp_block_chain():
     sw_bytes = M * (2 * 2 * I + codes)
     return {"workload": "Llama-7B MLP block chain M=1024 (add+RMSNorm+quant -> gate/up -> swiglu+quant -> down), HIP graph",
             "us_per_block_packed_weights": tp * 1e6, "effective_tops_packed_weights": ops / tp / 1e12,
+            "us_per_block_packed_weights_retile_as_a_pass": tpr * 1e6,
             "us_per_block_packed_weights_reorder_fused_into_gate_up": tpf * 1e6,
             "effective_tops_packed_weights_reorder_fused_into_gate_up": ops / tpf / 1e12,
             "us_per_block_canonical_weights": t * 1e6, "effective_tops_canonical_weights": ops / t / 1e12,
@@ -771,7 +806,10 @@ def main():
                    "linears": [{"name": L.name, "M": L.M, "K": L.K, "N": L.N} for L in layers],
                    "group_size": 128, "n_outlier": 128, "clip_act": synth.CLIP_ACT,
                    "clip_weight": synth.CLIP_WEIGHT,
-                   "weights": "packed once by atom_pack_weight" if packed else "canonical"},
+                   "weights": "packed once by atom_pack_weight" if packed else "canonical",
+                   "path": [("atom_quantize_act_packed -> atom_w4a4_gemm_prepacked" if L.fused_retile else
+                             "atom_quantize_act -> atom_pack_act -> atom_w4a4_gemm_prepacked") if L.packed else
+                            "atom_quantize_act -> atom_w4a4_gemm" for L in layers]},
         "effective_frac_of_int8_mfma_peak": ops / sec / 1e12 / PEAK_INT8_TOPS,
         "roofline": roof,
     }

@@ -331,6 +331,41 @@ atom_status atom_w4a4_gemm_packed(const void *a_q4, const void *a_q8,
                                   size_t workspace_bytes, void *stream);
 
 /*
+ * The front ends writing the tiled activations directly (Sections 4.1 - 4.3:
+ * everything between the producing operator and the GEMM in one kernel): the
+ * result in a_packed is byte for byte what atom_quantize_act (or
+ * atom_add_quantize_act, atom_swiglu_quantize_act) followed by atom_pack_act
+ * leaves there, without the canonical arrays and without the re-tiling pass;
+ * atom_w4a4_gemm_prepacked takes it.  Arguments as the canonical entry points
+ * (reorder_idx may be NULL likewise); a_packed: atom_pack_weight_bytes(M, d)
+ * bytes, 256-byte aligned.
+ * ATOM_ERR_UNSUPPORTED unless group_size = 128, 2^-20 <= clip <= 1 and the
+ * row's staging fits the LDS (4 K bytes with an index, K / 2 with RMSNorm,
+ * 3 (K - O) / 4 + O for the packed row: K <= 28672 with an index and RMSNorm,
+ * every K without an index); ATOM_ERR_WORKSPACE when packed_bytes is too small.
+ */
+atom_status atom_quantize_act_packed(const void *x_f16, int64_t M, int64_t ldx,
+                                     const void *gamma_f16, float eps,
+                                     const int32_t *reorder_idx,
+                                     const atom_desc *d, float clip,
+                                     void *a_packed, size_t packed_bytes,
+                                     void *stream);
+atom_status atom_add_quantize_act_packed(const void *x_f16, const void *residual_f16,
+                                         int64_t M, int64_t ldx, int64_t ldr,
+                                         void *sum_out_f16, int64_t ldo,
+                                         const void *gamma_f16, float eps,
+                                         const int32_t *reorder_idx,
+                                         const atom_desc *d, float clip,
+                                         void *a_packed, size_t packed_bytes,
+                                         void *stream);
+atom_status atom_swiglu_quantize_act_packed(const void *gate_f16, const void *up_f16,
+                                            int64_t M, int64_t ldg, int64_t ldu,
+                                            const int32_t *reorder_idx,
+                                            const atom_desc *d, float clip,
+                                            void *a_packed, size_t packed_bytes,
+                                            void *stream);
+
+/*
  * KV-cache quantisation (Section 2, asymmetric uniform quantisation; Section
  * 4.4: one scale and zero point per attention head, 4 bits; Section 4.5: fused
  * into the operator that produces K and V, here a kernel of its own that the

@@ -34,6 +34,9 @@ from .binding import (  # noqa: F401
     atom_decode_linear_lds_bytes,
     atom_pack_weight,
     atom_pack_act,
+    atom_quantize_act_packed,
+    atom_add_quantize_act_packed,
+    atom_swiglu_quantize_act_packed,
     atom_w4a4_gemm_prepacked,
     atom_w4a4_gemm_packed,
     atom_w4a4_gemm_packed_workspace_bytes,

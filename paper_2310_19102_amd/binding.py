@@ -33,6 +33,9 @@ EXPORTS = (
     "atom_w4a4_gemm_packed_workspace_bytes",
     "atom_w4a4_gemm_packed",
     "atom_pack_act",
+    "atom_quantize_act_packed",
+    "atom_add_quantize_act_packed",
+    "atom_swiglu_quantize_act_packed",
     "atom_w4a4_gemm_prepacked",
     "atom_mx_quantize_act",
     "atom_mx_quantize_weight",
@@ -114,6 +117,12 @@ def load_library():
     L.atom_w4a4_gemm_packed.argtypes = [vp, vp, vp, i64, vp, i64, dp, vp, i64, vp, vp, sz, vp]
     L.atom_pack_act.restype = ctypes.c_int
     L.atom_pack_act.argtypes = [vp, vp, vp, i64, dp, vp, sz, vp]
+    L.atom_quantize_act_packed.restype = ctypes.c_int
+    L.atom_quantize_act_packed.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, sz, vp]
+    L.atom_add_quantize_act_packed.restype = ctypes.c_int
+    L.atom_add_quantize_act_packed.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, f32, vp, dp, f32, vp, sz, vp]
+    L.atom_swiglu_quantize_act_packed.restype = ctypes.c_int
+    L.atom_swiglu_quantize_act_packed.argtypes = [vp, vp, i64, i64, i64, vp, dp, f32, vp, sz, vp]
     L.atom_w4a4_gemm_prepacked.restype = ctypes.c_int
     L.atom_w4a4_gemm_prepacked.argtypes = [vp, i64, vp, i64, dp, vp, i64, vp, vp]
     i32 = ctypes.c_int32
@@ -481,6 +490,71 @@ def atom_pack_act(a_q4, a_q8, a_scale, group_size: int = 128, out: Optional[torc
     st = L.atom_pack_act(_ptr(a_q4), _ptr(a_q8), _ptr(a_scale), M, ctypes.byref(d), _ptr(out), out.numel(), _stream())
     if st != 0:
         raise AtomError(st, "atom_pack_act")
+    return out
+
+
+def _packed_out(L, M, d, out, device):
+    need = int(L.atom_pack_weight_bytes(M, ctypes.byref(d)))
+    if out is None:
+        out = torch.empty(max(need, 1), dtype=torch.uint8, device=device)
+    _dev(out, torch.uint8, "out")
+    return out
+
+
+def atom_quantize_act_packed(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float,
+                             reorder_idx: Optional[torch.Tensor], group_size: int = 128, n_outlier: int = 128,
+                             clip: float = 0.9, out: Optional[torch.Tensor] = None, bits: int = 4):
+    """``atom_quantize_act`` writing the tiled activations of ``atom_w4a4_gemm_prepacked`` directly
+    (the bytes ``atom_pack_act`` would make of its result)."""
+    L = load_library()
+    _dev(x, torch.float16, "x")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [M, K] with a contiguous last dimension")
+    M, K = x.shape
+    d = _desc(K, group_size, n_outlier, bits)
+    out = _packed_out(L, M, d, out, x.device)
+    st = L.atom_quantize_act_packed(_ptr(x), M, x.stride(0) if M > 1 else max(K, x.stride(0)), _ptr(gamma), eps,
+                                    _ptr(reorder_idx), ctypes.byref(d), clip, _ptr(out), out.numel(), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_quantize_act_packed")
+    return out
+
+
+def atom_add_quantize_act_packed(x: torch.Tensor, residual: torch.Tensor, gamma: Optional[torch.Tensor], eps: float,
+                                 reorder_idx: Optional[torch.Tensor], group_size: int = 128, n_outlier: int = 128,
+                                 clip: float = 0.9, sum_out: Optional[torch.Tensor] = None,
+                                 out: Optional[torch.Tensor] = None, bits: int = 4):
+    """``atom_add_quantize_act`` writing the tiled activations directly.  Returns ``(h, a_packed)``."""
+    L = load_library()
+    _dev(x, torch.float16, "x")
+    _dev(residual, torch.float16, "residual")
+    M, K = x.shape
+    h = sum_out if sum_out is not None else torch.empty((M, K), dtype=torch.float16, device=x.device)
+    d = _desc(K, group_size, n_outlier, bits)
+    out = _packed_out(L, M, d, out, x.device)
+    ld = lambda t: t.stride(0) if M > 1 else max(K, t.stride(0))
+    st = L.atom_add_quantize_act_packed(_ptr(x), _ptr(residual), M, ld(x), ld(residual), _ptr(h), ld(h), _ptr(gamma),
+                                        eps, _ptr(reorder_idx), ctypes.byref(d), clip, _ptr(out), out.numel(), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_add_quantize_act_packed")
+    return h, out
+
+
+def atom_swiglu_quantize_act_packed(gate: torch.Tensor, up: torch.Tensor, reorder_idx: Optional[torch.Tensor],
+                                    group_size: int = 128, n_outlier: int = 128, clip: float = 0.9,
+                                    out: Optional[torch.Tensor] = None, bits: int = 4):
+    """``atom_swiglu_quantize_act`` writing the tiled activations directly."""
+    L = load_library()
+    _dev(gate, torch.float16, "gate")
+    _dev(up, torch.float16, "up")
+    M, K = gate.shape
+    d = _desc(K, group_size, n_outlier, bits)
+    out = _packed_out(L, M, d, out, gate.device)
+    ld = lambda t: t.stride(0) if M > 1 else max(K, t.stride(0))
+    st = L.atom_swiglu_quantize_act_packed(_ptr(gate), _ptr(up), M, ld(gate), ld(up), _ptr(reorder_idx),
+                                           ctypes.byref(d), clip, _ptr(out), out.numel(), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_swiglu_quantize_act_packed")
     return out
 
 

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libatom.so")
-SOURCES = ["atom_api.hip", "atom_quantize.hip", "atom_gemm.hip", "atom_gemm_big.hip", "atom_gemm_decode.hip", "atom_gemm_gs.hip", "atom_decode_fused.hip", "atom_gemm_f6.hip", "atom_kv.hip", "atom_mx.hip", "atom_calib.hip", "atom_probe.hip"]
+SOURCES = ["atom_api.hip", "atom_quantize.hip", "atom_quantize_packed.hip", "atom_gemm.hip", "atom_gemm_big.hip", "atom_gemm_decode.hip", "atom_gemm_gs.hip", "atom_decode_fused.hip", "atom_gemm_f6.hip", "atom_kv.hip", "atom_mx.hip", "atom_calib.hip", "atom_probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

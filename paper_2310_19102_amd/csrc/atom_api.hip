@@ -60,9 +60,62 @@ atom_status quantize_common(const void *x, int64_t rows, int64_t ld, int pre, co
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
+atom_status quantize_packed_common(const void *x, int64_t rows, int64_t ld, int pre, const void *res, int64_t ldr,
+                                   void *sum_out, int64_t ldo, const void *gamma, float eps, const int32_t *idx,
+                                   const atom_desc *d, float clip, void *out, size_t out_bytes, void *stream)
+{
+    atom_status st = check_desc(d);
+    if (st != ATOM_OK) return st;
+    if (rows < 0 || ld < d->K) return ATOM_ERR_SHAPE;
+    if (pre != 0 && ldr < d->K) return ATOM_ERR_SHAPE;
+    if (pre == 1 && ldo < d->K) return ATOM_ERR_SHAPE;
+    if (rows == 0) return ATOM_OK;
+    if (!x || !out) return ATOM_ERR_NULL;
+    if (pre != 0 && !res) return ATOM_ERR_NULL;
+    if (pre == 1 && !sum_out) return ATOM_ERR_NULL;
+    if (!aligned(x, 16) || (ld % 8) || !aligned(idx, 16) || !aligned(out, 256) || (gamma && !aligned(gamma, 16)))
+        return ATOM_ERR_ALIGN;
+    if (pre != 0 && (!aligned(res, 16) || (ldr % 8))) return ATOM_ERR_ALIGN;
+    if (pre == 1 && (!aligned(sum_out, 16) || (ldo % 8))) return ATOM_ERR_ALIGN;
+    if (!(clip >= 9.5367431640625e-07f && clip <= 1.0f)) return ATOM_ERR_UNSUPPORTED;
+    if (atom_internal::quantize_packed_lds_bytes(d->K, d->n_outlier, gamma != nullptr, idx == nullptr) > 160 * 1024)
+        return ATOM_ERR_UNSUPPORTED;
+    if ((rows + 63) / 64 > 65535) return ATOM_ERR_UNSUPPORTED;       // what the packed GEMM takes
+    if (out_bytes < atom_internal::f6_packed_bytes(rows, d->K, d->n_outlier)) return ATOM_ERR_WORKSPACE;
+    hipError_t err = atom_internal::launch_quantize_rows_packed(x, rows, ld, pre, res, ldr, sum_out, ldo, gamma, eps, idx,
+                                                                d->K, d->n_outlier, d->bits_normal, clip, out,
+                                                                static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
+atom_status atom_quantize_act_packed(const void *x_f16, int64_t M, int64_t ldx, const void *gamma_f16, float eps,
+                                     const int32_t *reorder_idx, const atom_desc *d, float clip, void *a_packed,
+                                     size_t packed_bytes, void *stream)
+{
+    return quantize_packed_common(x_f16, M, ldx, 0, nullptr, 0, nullptr, 0, gamma_f16, eps, reorder_idx, d, clip,
+                                  a_packed, packed_bytes, stream);
+}
+
+atom_status atom_add_quantize_act_packed(const void *x_f16, const void *residual_f16, int64_t M, int64_t ldx,
+                                         int64_t ldr, void *sum_out_f16, int64_t ldo, const void *gamma_f16, float eps,
+                                         const int32_t *reorder_idx, const atom_desc *d, float clip, void *a_packed,
+                                         size_t packed_bytes, void *stream)
+{
+    return quantize_packed_common(x_f16, M, ldx, 1, residual_f16, ldr, sum_out_f16, ldo, gamma_f16, eps, reorder_idx, d,
+                                  clip, a_packed, packed_bytes, stream);
+}
+
+atom_status atom_swiglu_quantize_act_packed(const void *gate_f16, const void *up_f16, int64_t M, int64_t ldg,
+                                            int64_t ldu, const int32_t *reorder_idx, const atom_desc *d, float clip,
+                                            void *a_packed, size_t packed_bytes, void *stream)
+{
+    return quantize_packed_common(gate_f16, M, ldg, 2, up_f16, ldu, nullptr, 0, nullptr, 0.0f, reorder_idx, d, clip,
+                                  a_packed, packed_bytes, stream);
+}
+
 
 atom_status atom_quantize_act(const void *x_f16, int64_t M, int64_t ldx, const void *gamma_f16,
                               float eps, const int32_t *reorder_idx, const atom_desc *d,

@@ -57,6 +57,13 @@ hipError_t launch_mfma_rate_probe(int kind, int iters, void *out, hipStream_t st
 
 // MX variant: front end (FP4 / FP8 codes, E8M0 scale byte per 32 channels) and GEMM on the
 // scaled FP8/FP6/FP4 MFMA.
+// The front end writing the packed GEMM's unit images directly (atom_quantize_packed.hip); pre as
+// launch_quantize_rows.
+size_t quantize_packed_lds_bytes(int K, int O, bool norm, bool ident);
+hipError_t launch_quantize_rows_packed(const void *x, int64_t rows, int64_t ld, int pre, const void *res, int64_t ldr,
+                                       void *sum_out, int64_t ldo, const void *gamma, float eps, const int32_t *idx,
+                                       int K, int O, int nbits, float clip, void *out, hipStream_t stream);
+
 // out[r, :] = in[row_idx[r], :] over fp16 matrices (offline helper of the fused reorder).
 hipError_t launch_permute_rows(const void *in, int64_t rows_in, int64_t rows_out, int64_t cols, int64_t ld_in,
                                const int32_t *row_idx, void *out, int64_t ld_out, hipStream_t stream);

@@ -157,14 +157,25 @@ struct NoHook { __device__ __forceinline__ void operator()() const {} };
 
 // after_first_fetch is called once, right after the global loads of the first row are issued (a
 // caller with loads of its own that may take longer to return issues them there).
-template <bool NORM, int NS, int NT, int PRE, bool IDENT = false, class Hook = NoHook>
+// PACKED: the codes and scales do not go to the canonical arrays but straight into the unit images
+// the packed GEMM reads (units of 64 rows; per unit one image per group: INT4 codes as FP6 E3M2 in
+// three 16-byte chunks per row and half at 2048 c + 1024 h + 16 r, scales as 8-byte entries at
+// 6144 + 8 r; INT8: chunk c of row r at 128 r + 16 ((c ^ r ^ (r/8 % 2)) % 8), scales at 8192 + 8 r).
+// A row's packed bytes are first collected in LDS (pk_lds: 3 K4 / 4 + O bytes, in the order group,
+// half, chunk), then copied out as whole 16-byte chunks.
+typedef _Float16 pk_v32h __attribute__((ext_vector_type(32)));
+typedef unsigned pk_v6u  __attribute__((ext_vector_type(6)));
+constexpr int kImg4 = 6656, kImg8 = 8704, kSc4 = 6144, kSc8 = 8192;
+
+template <bool NORM, int NS, int NT, int PRE, bool IDENT = false, bool PACKED = false, class Hook = NoHook>
 __device__ __forceinline__
 void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
                              const __half *x, int64_t rows, int64_t ld,
                              const __half *res, int64_t ldr, __half *sum_out, int64_t ldo,
                              const __half *__restrict__ gamma, float eps,
                              const int32_t *__restrict__ idx, int K, int O, int nbits, float clip,
-                             uint8_t *q4, int8_t *q8, __half *scale, Hook after_first_fetch = Hook())
+                             uint8_t *q4, int8_t *q8, __half *scale, Hook after_first_fetch = Hook(),
+                             uint8_t *pk_out = nullptr, uint8_t *pk_lds = nullptr)
 {
     float *ybuf = lds;                        // [K]   staged row, original channel order (not IDENT)
     float *qbuf = lds + (IDENT ? 0 : K);      // [K/8] per-vector sums of squares (NORM only)
@@ -327,7 +338,40 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
             float s;
             const __half sh = quantise_lane8(y, amax, is4, nbits, clip, q, s);
             const bool nz = s != 0.0f;
-            if (live) {
+            if constexpr (PACKED) {
+                if (live) {
+                    const int pos = lane & 15;                      // 8 channels at 8 * pos of the group
+                    const int64_t unit = row >> 6;
+                    const int     r    = (int)(row & 63);
+                    uint8_t *ubase = pk_out + unit * ((int64_t)G4 * kImg4 + (int64_t)(G - G4) * kImg8);
+                    if (is4) {
+                        // the E3M2 number of each code (a plain conversion: every code is representable);
+                        // eight codes = 48 bits, at byte 6 (pos % 4) of the 24 bytes of their 32-channel block
+                        pk_v32h h;
+#pragma unroll
+                        for (int e = 0; e < 32; ++e) h[e] = e < 8 ? (_Float16)(float)(nz ? q[e & 7] : 0) : (_Float16)0.0f;
+                        const pk_v6u f6 = __builtin_amdgcn_cvt_scalef32_pk32_bf6_f16(h, 1.0f);
+                        const int blk = pos >> 2;                   // block b: half b % 2, first or second MFMA b / 2
+                        uint16_t *dst = reinterpret_cast<uint16_t *>(pk_lds + 96 * gg + 48 * (blk & 1) + 24 * (blk >> 1) + 6 * (pos & 3));
+                        dst[0] = (uint16_t)f6[0];
+                        dst[1] = (uint16_t)(f6[0] >> 16);
+                        dst[2] = (uint16_t)f6[1];
+                        if (pos == 0)
+                            *reinterpret_cast<uint2 *>(ubase + (int64_t)gg * kImg4 + kSc4 + 8 * r) = make_uint2(__half_as_ushort(sh), 0u);
+                    } else {
+                        uint32_t w0 = 0, w1 = 0;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            w0 |= (uint32_t)(q[e] & 0xFF) << (8 * e);
+                            w1 |= (uint32_t)(q[e + 4] & 0xFF) << (8 * e);
+                        }
+                        *reinterpret_cast<uint2 *>(pk_lds + 3 * (K4 >> 2) + (j0 - K4)) = make_uint2(nz ? w0 : 0u, nz ? w1 : 0u);
+                        if (pos == 0)
+                            *reinterpret_cast<uint2 *>(ubase + (int64_t)G4 * kImg4 + (int64_t)(gg - G4) * kImg8 + kSc8 + 8 * r) =
+                                make_uint2(__half_as_ushort(sh), 0u);
+                    }
+                }
+            } else if (live) {
                 if (is4) {
                     uint32_t w = 0;
 #pragma unroll
@@ -346,7 +390,28 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
                 if ((lane & 15) == 0) scale[row * (int64_t)G + gg] = sh;
             }
         }
-        if (!IDENT || NORM) __syncthreads();   // ybuf and qbuf are rewritten by the next row
+        if (!IDENT || NORM || PACKED) __syncthreads();   // ybuf and qbuf are rewritten by the next row
+        if constexpr (PACKED) {
+            // the row's packed bytes, 16 at a time: chunk j of the INT4 part is (group j / 6, half
+            // (j % 6) / 3, chunk j % 3); chunk j of the INT8 part is (group j / 8, source chunk j % 8)
+            const int64_t unit = row >> 6;
+            const int     r    = (int)(row & 63);
+            uint8_t *ubase = pk_out + unit * ((int64_t)G4 * kImg4 + (int64_t)(G - G4) * kImg8);
+            const int n4 = 6 * G4, n8 = O >> 4;
+            for (int j = tid; j < n4 + n8; j += NT) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(pk_lds + 16 * j);
+                uint8_t *dst;
+                if (j < n4) {
+                    const int gq = j / 6, hc = j - 6 * gq, hh = hc >= 3 ? 1 : 0, c = hc - 3 * hh;
+                    dst = ubase + (int64_t)gq * kImg4 + 2048 * c + 1024 * hh + 16 * r;
+                } else {
+                    const int j8 = j - n4, g8 = j8 >> 3, c = j8 & 7;
+                    dst = ubase + (int64_t)G4 * kImg4 + (int64_t)g8 * kImg8 + 128 * r + 16 * ((c ^ r ^ ((r >> 3) & 1)) & 7);
+                }
+                *reinterpret_cast<uint4 *>(dst) = v;
+            }
+            if (IDENT && !NORM) __syncthreads();     // (no other barrier stands before the next row's writes to pk_lds)
+        }
     }
 }
 
