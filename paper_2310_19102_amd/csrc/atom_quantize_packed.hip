@@ -27,7 +27,15 @@ void quantize_rows_packed_kernel(const __half *x, int64_t rows, int64_t ld, cons
 {
     extern __shared__ __align__(16) float lds[];
     uint8_t *pk_lds = reinterpret_cast<uint8_t *>(lds) + pk_lds_off;
-    quantize_rows_fast_body<NORM, NS, NT, PRE, IDENT, true>(lds, blockIdx.x, gridDim.x, x, rows, ld, res, ldr, sum_out,
+    // A workgroup takes a run of consecutive rows, and consecutive runs go to workgroups of the same
+    // XCD (the hardware deals workgroup ids round-robin to the 8 XCDs): the 16-byte pieces that the
+    // rows r .. r+7 of a unit put into one 128-byte line then meet in one L2 instead of eight.
+    const int64_t nb = gridDim.x, b = blockIdx.x;
+    const int64_t per = nb >> 3, rem = nb & 7, xcd = b & 7;
+    const int64_t logical = xcd * per + (xcd < rem ? xcd : rem) + (b >> 3);
+    const int64_t rpw = (rows + nb - 1) / nb;
+    const int64_t first = logical * rpw, last = first + rpw < rows ? first + rpw : rows;
+    quantize_rows_fast_body<NORM, NS, NT, PRE, IDENT, true>(lds, first, 1, x, last, ld, res, ldr, sum_out,
                                                             ldo, gamma, eps, idx, K, O, nbits, clip, nullptr, nullptr,
                                                             nullptr, NoHook(), pk_out, pk_lds);
     // rows past the end of the matrix, up to the end of the last unit: zero codes, zero scales
