@@ -14,7 +14,8 @@
 //     group (16 rows x 64 bytes per instruction, four groups in flight) and never
 //     shares them, so no LDS staging and no barrier sits on the streaming path;
 //   * the activation codes (M x K/2 bytes, L2-resident) are fetched per wavefront
-//     in the same MFMA register layout; rows >= M are zeros;
+//     in the same MFMA register layout (at M <= 16 in the common case: the real rows
+//     only, through a copy in LDS); rows >= M are zeros or never stored;
 //   * the contraction is the INT8 MFMA 16x16x64: one 128-channel INT4 group is two
 //     MFMAs (even-position and odd-position codes after the nibble widening), an
 //     INT8 group is two MFMAs of 64 channels;
@@ -28,6 +29,8 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "atom_gemm_common.h"
 
@@ -53,21 +56,18 @@ __device__ __forceinline__ v4i widen_hi(const uint4 &w)
     return __builtin_bit_cast(v4i, t);
 }
 
+// The general kernel.
 // RB: 16-row blocks of activations (M <= 16 * RB)
 // VS: the wavefronts' runs are whole blocks of four groups (G even), so the four scales of a
 //     batch are one 8-byte load per row (instead of four 2-byte loads that several wavefronts
 //     request from the same lines); needs 4-byte aligned scale arrays
-// Q4: with VS, G is a multiple of four and the scale arrays are 8-byte aligned: every block is a
-//     whole one, its scales an aligned piece, and scale number d of the piece belongs to slot d
 // ONE8: there is exactly one INT8 group (O = 128, the set-up of the paper), the last group of the
 //     last wavefront's run.  The second 64 bytes of its rows then have registers of their own, and
-//     the slots hold one 16-byte piece each: 24 registers less per row block, which is what lets two
-//     workgroups share a CU once every load of a batch is in flight at the same time.
-// TILED (with ONE8): the weight codes were re-tiled for this kernel (tile_weight_kernel below):
-//     block of 16 rows, group, lane -> 16 bytes, so one load instruction of a wavefront reads 1 KB
-//     of consecutive bytes (eight whole 128-byte lines) instead of sixteen 64-byte pieces.
-template <int RB, bool VS, bool ONE8 = false, bool Q4 = false, bool TILED = false>
-__global__ __launch_bounds__(NT, (ONE8 && RB == 1 && Q4) ? 6 : 1)    // six wavefronts per SIMD = three workgroups per CU: 80 registers
+//     the slots hold one 16-byte piece each.
+// The common decoding case (ONE8, G a multiple of four, 8-byte aligned scale rows) has kernels of
+// its own below; this one takes everything else.
+template <int RB, bool VS, bool ONE8 = false>
+__global__ __launch_bounds__(NT, 1)
 void w4a4_gemm_decode_kernel(const GemmParams p)
 {
     __shared__ float red[NW][RB][4][64];   // [slice][row block][register][lane]
@@ -113,10 +113,9 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
     }
     // ONE8 addresses every load as scalar base + 32-bit byte offset (arrays below 4 GiB: host),
     // one register per stream instead of a 64-bit pointer per load
-    static_assert(!TILED || ONE8, "the tiled layout is read by the one-INT8-group variants");
-    constexpr uint32_t GSTEP = TILED ? 1024u : 64u;      // from one group's piece to the next, and to the second half of the INT8 group
-    const uint32_t w4o = TILED ? (uint32_t)blockIdx.x * (uint32_t)(G4 * 1024) + lane * 16 : (uint32_t)(wr * (K4 >> 1)) + kc * 16;
-    const uint32_t w8o = TILED ? (uint32_t)blockIdx.x * 2048u + lane * 16 : (uint32_t)(wr * p.O) + kc * 16;
+    constexpr uint32_t GSTEP = 64u;                      // from one group's piece to the next, and to the second half of the INT8 group
+    const uint32_t w4o = (uint32_t)(wr * (K4 >> 1)) + kc * 16;
+    const uint32_t w8o = (uint32_t)(wr * p.O) + kc * 16;
     uint32_t a4o[RB], a8o[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -196,17 +195,16 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
         if constexpr (VS) {
             static_assert(!VS || DEPTH == 4, "a batch is four groups");
             // (32-bit element offsets on the scalar bases: M * G and N * G are far below 2^31)
-            // Q4: one aligned 8-byte piece.  Otherwise a row of scales starts on an even element
-            // (G even) and its four-blocks on 4-byte boundaries: two 4-byte loads, the second one
-            // held inside the row where the last block of K has two groups only (its slots are dead).
+            // A row of scales starts on an even element (G even) and its four-blocks on 4-byte
+            // boundaries: two 4-byte loads, the second one held inside the row where the last block
+            // of K has two groups only (its slots are dead).
             const int g2 = gb + 2 <= G - 2 ? gb + 2 : G - 2;
             // (scalar base + 32-bit byte offset per lane, like the codes)
             auto load4 = [&](const uint16_t *base, uint32_t row) {
                 const uint8_t *sb  = reinterpret_cast<const uint8_t *>(base);
                 const uint32_t off = row * (uint32_t)(2 * G);
-                if constexpr (Q4) return *reinterpret_cast<const uint2 *>(base + (row * (uint32_t)G + (uint32_t)gb));
-                else return make_uint2(*reinterpret_cast<const uint32_t *>(sb + 2 * gb + off),
-                                       *reinterpret_cast<const uint32_t *>(sb + 2 * g2 + off));
+                return make_uint2(*reinterpret_cast<const uint32_t *>(sb + 2 * gb + off),
+                                  *reinterpret_cast<const uint32_t *>(sb + 2 * g2 + off));
             };
             wvs = load4(p.w_scale, (uint32_t)wr);
 #pragma unroll
@@ -265,6 +263,302 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
     }
 }
 
+// The cases decoding runs in, written out on their own: RB blocks of 16 activation rows
+// (M <= 16 RB), O = 128 (one INT8 group, the last group of K), G a multiple of four, 8-byte aligned
+// scale rows, 32-bit offsets.  Same sums in the same order as w4a4_gemm_decode_kernel<RB, true,
+// true> (eight K-slices of whole four-group blocks, ascending inside a slice, slices added
+// 0..7), so the two agree bit for bit.  What differs is the vector work per weight byte and the
+// bytes the vector memory path returns to registers (64 per clock and CU), which set the pace here:
+//   * a batch is four INT4 groups; the batch that holds the INT8 group (the last one of the last
+//     wavefront) is code of its own: no per-slot case analysis, no second half of an INT8 group
+//     loaded where there is none;
+//   * rows >= M are not zeroed in the operand: an MFMA row depends on its own operand row only, and
+//     those rows are never stored;
+//   * the accumulator holds 256 x the sum (the nibble widening's factor stays in; the INT8 group's
+//     scale products are multiplied by 256 instead, an exact scaling): one multiplication per
+//     wavefront at the end instead of one per group;
+//   * the scale products of a group and row block are one fp16 MFMA (activation scales of the
+//     operand rows against the weight scales of the columns, both in k-slot 0: the result has the
+//     layout of the integer tile; a product of two fp16 numbers is exact in fp32), so a lane loads
+//     one 8-byte piece of activation scales per batch and row block, not four.
+typedef _Float16 v4h16 __attribute__((ext_vector_type(4)));
+typedef float    v4f32 __attribute__((ext_vector_type(4)));
+
+// Scale operand of group D of a batch: the fp16 number in k-slot 0 (lanes 0-15 hold k-slots 0-3;
+// the pieces of the other lanes were zeroed), zeros in slots 1-3.
+template <int D>
+__device__ __forceinline__ v4h16 scale_operand(const uint2 &piece)
+{
+    const uint32_t r = D < 2 ? piece.x : piece.y;
+    return __builtin_bit_cast(v4h16, make_uint2((D & 1) ? r >> 16 : r & 0xffffu, 0u));
+}
+
+template <int RB, bool TILED>
+__global__ __launch_bounds__(NT, RB == 4 ? 2 : 4)     // RB = 2: two workgroups per CU; RB = 4 spills below 146 registers
+void w4a4_gemm_decode16_kernel(const GemmParams p)
+{
+    __shared__ float red[NW][RB][4][64];      // [slice][row block][register][lane]
+
+    const int tid  = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 15, kc = lane >> 4;
+
+    const int K4 = p.K - 128, G = p.K >> 7;
+    const int M = (int)p.M;
+    const int64_t n0 = (int64_t)blockIdx.x * TN;
+    const int nblk    = G >> 2;
+    const int g_begin = 4 * (int)((int64_t)wave * nblk / NW);
+    const int g_end   = 4 * (int)((int64_t)(wave + 1) * nblk / NW);
+
+    int64_t wr = n0 + col;                                // clamped: columns >= N are computed and never stored
+    wr = wr < p.N ? wr : p.N - 1;
+    constexpr uint32_t GSTEP = TILED ? 1024u : 64u;
+    const uint32_t w4o = TILED ? (uint32_t)blockIdx.x * (uint32_t)((G - 1) * 1024) + lane * 16 : (uint32_t)(wr * (K4 >> 1)) + kc * 16;
+    const uint32_t w8o = TILED ? (uint32_t)blockIdx.x * 2048u + lane * 16 : (uint32_t)(wr * 128) + kc * 16;
+    const uint8_t *w8b = reinterpret_cast<const uint8_t *>(p.w_q8), *a8b = reinterpret_cast<const uint8_t *>(p.a_q8);
+    // operand row 16 rb + col of this lane (rows >= M read row 0): codes and scales
+    uint32_t a4o[RB], a8o[RB], aso[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const uint32_t ar = 16 * rb + col < M ? 16 * rb + col : 0;
+        a4o[rb] = ar * (uint32_t)(K4 >> 1) + kc * 16;
+        a8o[rb] = ar * 128u + kc * 16;
+        aso[rb] = ar * (uint32_t)G;
+    }
+    const uint32_t wso = (uint32_t)wr * (uint32_t)G;
+
+    float acc[RB][4];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[rb][e] = 0.0f;
+    const v4i   zi = {0, 0, 0, 0};
+    const v4f32 zf = {0.0f, 0.0f, 0.0f, 0.0f};
+
+    auto batch = [&](int gb, auto has8_c) __attribute__((always_inline)) {
+        constexpr bool HAS8 = decltype(has8_c)::value;
+        // every load of the batch is issued before the first is used; the scales first, they are
+        // needed with the first group
+        uint2 wvs = *reinterpret_cast<const uint2 *>(p.w_scale + (wso + (uint32_t)gb));
+        uint2 avs[RB];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) avs[rb] = *reinterpret_cast<const uint2 *>(p.a_scale + (aso[rb] + (uint32_t)gb));
+        uint4 wq[4], aq[4][RB], wx, ax[RB];
+#pragma unroll
+        for (int d = 0; d < (HAS8 ? 3 : 4); ++d) {
+            wq[d] = *reinterpret_cast<const uint4 *>(p.w_q4 + (w4o + (uint32_t)(gb + d) * GSTEP));
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                aq[d][rb] = *reinterpret_cast<const uint4 *>(p.a_q4 + (a4o[rb] + (uint32_t)(gb + d) * 64u));
+        }
+        if constexpr (HAS8) {
+            wq[3] = *reinterpret_cast<const uint4 *>(w8b + w8o);
+            wx    = *reinterpret_cast<const uint4 *>(w8b + (w8o + GSTEP));
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                aq[3][rb] = *reinterpret_cast<const uint4 *>(a8b + a8o[rb]);
+                ax[rb]    = *reinterpret_cast<const uint4 *>(a8b + (a8o[rb] + 64u));
+            }
+        }
+        // (the fence keeps the loads here: left alone the compiler spreads them between the MFMAs
+        // to save registers, which turns one memory round trip per batch into several)
+        __builtin_amdgcn_sched_barrier(0);
+        if (kc != 0) {                                    // k-slots 4 .. 15 of the scale MFMA stay empty
+            wvs = make_uint2(0, 0);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) avs[rb] = make_uint2(0, 0);
+        }
+
+        auto int4_group = [&](const uint4 &w, const uint4 (&a)[RB], auto dc) __attribute__((always_inline)) {
+            constexpr int D = decltype(dc)::value;
+            const v4i b0 = widen_lo(w), b1 = widen_hi(w);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(widen_lo(a[rb]), b0, zi, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_i32_16x16x64_i8(widen_hi(a[rb]), b1, c, 0, 0, 0);
+                const v4f32 sc = __builtin_amdgcn_mfma_f32_16x16x16f16(scale_operand<D>(avs[rb]), scale_operand<D>(wvs), zf, 0, 0, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[rb][e] = fmaf((float)c[e], sc[e], acc[rb][e]);
+            }
+        };
+        int4_group(wq[0], aq[0], std::integral_constant<int, 0>());
+        int4_group(wq[1], aq[1], std::integral_constant<int, 1>());
+        int4_group(wq[2], aq[2], std::integral_constant<int, 2>());
+        if constexpr (!HAS8) {
+            int4_group(wq[3], aq[3], std::integral_constant<int, 3>());
+        } else {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, aq[3][rb]), __builtin_bit_cast(v4i, wq[3]), zi, 0, 0, 0);
+                c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, ax[rb]), __builtin_bit_cast(v4i, wx), c, 0, 0, 0);
+                const v4f32 sc = __builtin_amdgcn_mfma_f32_16x16x16f16(scale_operand<3>(avs[rb]), scale_operand<3>(wvs), zf, 0, 0, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[rb][e] = fmaf((float)c[e], 256.0f * sc[e], acc[rb][e]);
+            }
+        }
+    };
+
+    const int g_plain = wave == NW - 1 ? g_end - 4 : g_end;
+    for (int gb = g_begin; gb < g_plain; gb += 4) batch(gb, std::false_type());
+    if (wave == NW - 1) batch(G - 4, std::true_type());
+
+    // the eight K-slices meet in LDS and are added in slice order
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) red[wave][rb][e][lane] = acc[rb][e] * (1.0f / 256.0f);
+    __syncthreads();
+    for (int idx = tid; idx < RB * 4 * 64; idx += NT) {
+        const int l = idx & 63, e = (idx >> 6) & 3, rb = idx >> 8;
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s += red[w][rb][e][l];
+        const int64_t m = 16 * rb + 4 * (l >> 4) + e;
+        const int64_t n = n0 + (l & 15);
+        if (m < p.M && n < p.N) p.y[m * p.ldy + n] = __half_as_ushort(__float2half_rn(s));
+    }
+}
+
+// One block of activation rows (M <= 16), otherwise the cases and the arithmetic of
+// w4a4_gemm_decode16_kernel.  What it adds: the activation operand is 16 rows whatever M is, as
+// many bytes returned to registers as the weights.  Here a wavefront copies the M real rows of its
+// batch's activation codes (256 bytes per row: four groups) into a region of LDS of its own, four
+// rows per load instruction (SI instructions), and reads its MFMA operand from there; rows >= M of
+// the operand repeat row 0.  No barrier: LDS instructions of one wavefront execute in order.
+template <int SI, bool TILED>
+__global__ __launch_bounds__(NT, 6)
+void w4a4_gemm_decode_staged_kernel(const GemmParams p)
+{
+    constexpr int ROWB = 272;                 // a staged row: 256 bytes and 16 that spread the rows over the banks
+    constexpr int WREG = 16 * ROWB;           // per wavefront
+    __shared__ __align__(16) unsigned char stage[NW * WREG];
+
+    const int tid  = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 15, kc = lane >> 4;
+
+    const int K4 = p.K - 128, G = p.K >> 7;
+    const int M = (int)p.M;
+    const int64_t n0 = (int64_t)blockIdx.x * TN;
+    const int nblk    = G >> 2;
+    const int g_begin = 4 * (int)((int64_t)wave * nblk / NW);
+    const int g_end   = 4 * (int)((int64_t)(wave + 1) * nblk / NW);
+
+    int64_t wr = n0 + col;                                // clamped: columns >= N are computed and never stored
+    wr = wr < p.N ? wr : p.N - 1;
+    constexpr uint32_t GSTEP = TILED ? 1024u : 64u;
+    const uint32_t w4o = TILED ? (uint32_t)blockIdx.x * (uint32_t)((G - 1) * 1024) + lane * 16 : (uint32_t)(wr * (K4 >> 1)) + kc * 16;
+    const uint32_t w8o = TILED ? (uint32_t)blockIdx.x * 2048u + lane * 16 : (uint32_t)(wr * 128) + kc * 16;
+    const uint8_t *w8b = reinterpret_cast<const uint8_t *>(p.w_q8), *a8b = reinterpret_cast<const uint8_t *>(p.a_q8);
+    // staging: instruction i moves rows 4 i .. 4 i + 3, lane -> row 4 i + kc, 16-byte chunk `col` of
+    // the row's 256 bytes; rows >= M repeat row M - 1
+    uint32_t srow[SI];
+#pragma unroll
+    for (int i = 0; i < SI; ++i) srow[i] = (uint32_t)(4 * i + kc < M ? 4 * i + kc : M - 1) * (uint32_t)(K4 >> 1);
+    unsigned char *mine = stage + wave * WREG;
+    unsigned char *st_w = mine + kc * ROWB + col * 16;                        // + 4 i ROWB
+    const uint32_t ar = col < M ? col : 0;                                    // operand row of this lane
+    const unsigned char *st_r = mine + ar * ROWB + kc * 16;                   // + 64 d
+    const uint32_t a8o = ar * 128u + kc * 16;
+    const uint32_t wso = (uint32_t)wr * (uint32_t)G, aso = ar * (uint32_t)G;
+
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const v4i   zi = {0, 0, 0, 0};
+    const v4f32 zf = {0.0f, 0.0f, 0.0f, 0.0f};
+
+    auto batch = [&](int gb, auto has8_c) __attribute__((always_inline)) {
+        constexpr bool HAS8 = decltype(has8_c)::value;
+        // every load of the batch is issued before the first is used; the activation rows first
+        // (they go through LDS), then the scales
+        // (named registers, not an array: the array stayed in scratch memory)
+        uint4 st0, st1, st2, st3;
+        const uint32_t ch = HAS8 ? (col < 12 ? col : 11) : col;              // three INT4 groups only: 12 chunks
+        auto stage_load = [&](int i) __attribute__((always_inline)) {
+            return *reinterpret_cast<const uint4 *>(p.a_q4 + (srow[i] + (uint32_t)gb * 64u + ch * 16u));
+        };
+        st0 = stage_load(0);
+        if constexpr (SI > 1) st1 = stage_load(1);
+        if constexpr (SI > 2) { st2 = stage_load(2); st3 = stage_load(3); }
+        uint2 avs = *reinterpret_cast<const uint2 *>(p.a_scale + (aso + (uint32_t)gb));
+        uint2 wvs = *reinterpret_cast<const uint2 *>(p.w_scale + (wso + (uint32_t)gb));
+        uint4 wq[4], wx, a8[2];
+#pragma unroll
+        for (int d = 0; d < 3; ++d) wq[d] = *reinterpret_cast<const uint4 *>(p.w_q4 + (w4o + (uint32_t)(gb + d) * GSTEP));
+        if constexpr (HAS8) {
+            wq[3] = *reinterpret_cast<const uint4 *>(w8b + w8o);
+            wx    = *reinterpret_cast<const uint4 *>(w8b + (w8o + GSTEP));
+            a8[0] = *reinterpret_cast<const uint4 *>(a8b + a8o);
+            a8[1] = *reinterpret_cast<const uint4 *>(a8b + (a8o + 64u));
+        } else {
+            wq[3] = *reinterpret_cast<const uint4 *>(p.w_q4 + (w4o + (uint32_t)(gb + 3) * GSTEP));
+        }
+        // (the fence keeps the loads here: left alone the compiler spreads them between the MFMAs
+        // to save registers, which turns one memory round trip per batch into several)
+        __builtin_amdgcn_sched_barrier(0);
+        *reinterpret_cast<uint4 *>(st_w) = st0;
+        if constexpr (SI > 1) *reinterpret_cast<uint4 *>(st_w + 4 * ROWB) = st1;
+        if constexpr (SI > 2) { *reinterpret_cast<uint4 *>(st_w + 8 * ROWB) = st2; *reinterpret_cast<uint4 *>(st_w + 12 * ROWB) = st3; }
+        uint4 aq[4];
+#pragma unroll
+        for (int d = 0; d < (HAS8 ? 3 : 4); ++d) aq[d] = *reinterpret_cast<const uint4 *>(st_r + 64 * d);
+        if (kc != 0) { avs = make_uint2(0, 0); wvs = make_uint2(0, 0); }     // k-slots 4 .. 15 of the scale MFMA stay empty
+
+        auto scales = [&](auto dc) __attribute__((always_inline)) -> v4f32 {
+            constexpr int D = decltype(dc)::value;
+            return __builtin_amdgcn_mfma_f32_16x16x16f16(scale_operand<D>(avs), scale_operand<D>(wvs), zf, 0, 0, 0);
+        };
+        auto int4_group = [&](const uint4 &w, const uint4 &a, auto dc) __attribute__((always_inline)) {
+            v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(widen_lo(a), widen_lo(w), zi, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_i32_16x16x64_i8(widen_hi(a), widen_hi(w), c, 0, 0, 0);
+            const v4f32 sc = scales(dc);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = fmaf((float)c[e], sc[e], acc[e]);
+        };
+        int4_group(wq[0], aq[0], std::integral_constant<int, 0>());
+        int4_group(wq[1], aq[1], std::integral_constant<int, 1>());
+        int4_group(wq[2], aq[2], std::integral_constant<int, 2>());
+        if constexpr (!HAS8) {
+            int4_group(wq[3], aq[3], std::integral_constant<int, 3>());
+        } else {
+            v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, a8[0]), __builtin_bit_cast(v4i, wq[3]), zi, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, a8[1]), __builtin_bit_cast(v4i, wx), c, 0, 0, 0);
+            const v4f32 sc = scales(std::integral_constant<int, 3>());
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = fmaf((float)c[e], 256.0f * sc[e], acc[e]);   // the accumulator holds 256 x the sum
+        }
+    };
+
+    const int g_plain = wave == NW - 1 ? g_end - 4 : g_end;
+    for (int gb = g_begin; gb < g_plain; gb += 4) batch(gb, std::false_type());
+    if (wave == NW - 1) batch(G - 4, std::true_type());
+
+    // the eight K-slices meet in LDS (each wavefront's region, its operand reads are complete) and
+    // are added in slice order
+    float *red = reinterpret_cast<float *>(mine);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[e * 64 + lane] = acc[e] * (1.0f / 256.0f);
+    __syncthreads();
+    if (tid < 256) {
+        const int l = tid & 63, e = tid >> 6;
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s += reinterpret_cast<const float *>(stage + w * WREG)[e * 64 + l];
+        const int64_t m = 4 * (l >> 4) + e;
+        const int64_t n = n0 + (l & 15);
+        if (m < p.M && n < p.N) p.y[m * p.ldy + n] = __half_as_ushort(__float2half_rn(s));
+    }
+}
+
+template <bool TILED>
+void launch_staged(const GemmParams &p, unsigned blocks, hipStream_t stream)
+{
+    if (p.M <= 4)      hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<1, TILED>), dim3(blocks), dim3(NT), 0, stream, p);
+    else if (p.M <= 8) hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<2, TILED>), dim3(blocks), dim3(NT), 0, stream, p);
+    else               hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<4, TILED>), dim3(blocks), dim3(NT), 0, stream, p);
+}
+
 // Re-tiling of the canonical weight codes for the TILED variants: one workgroup per block of 16
 // rows; rows past N are zeros.
 __global__ __launch_bounds__(256)
@@ -316,9 +610,9 @@ bool decode_tiled_supported(const GemmParams &p)
 hipError_t launch_decode_tiled(const GemmParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)((p.N + TN - 1) / TN);
-    if (p.M <= 16)      hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
-    else if (p.M <= 32) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
-    else                hipLaunchKernelGGL((w4a4_gemm_decode_kernel<4, true, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+    if (p.M <= 16)      launch_staged<true>(p, blocks, stream);
+    else if (p.M <= 32) hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<2, true>), dim3(blocks), dim3(NT), 0, stream, p);
+    else                hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, true>), dim3(blocks), dim3(NT), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -334,13 +628,13 @@ hipError_t launch_decode(const GemmParams &p, hipStream_t stream)
     const bool one8 = p.O == 128 && G >= NW && (uint64_t)p.N * (uint64_t)(p.K >> 1) < (1ull << 32);   // 32-bit byte offsets
     const bool q4 = G % 4 == 0 && ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 7) == 0;
     if (p.M <= 16 && vs && one8) {
-        if (q4) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        if (q4) launch_staged<false>(p, blocks, stream);
         else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (p.M <= 32 && vs && one8) {
-        if (q4) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        if (q4) hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<2, false>), dim3(blocks), dim3(NT), 0, stream, p);
         else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (vs && one8) {
-        if (q4) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<4, true, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        if (q4) hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, false>), dim3(blocks), dim3(NT), 0, stream, p);
         else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<4, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (p.M <= 16) {
         if (vs) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true>), dim3(blocks), dim3(NT), 0, stream, p);

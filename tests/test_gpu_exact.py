@@ -193,3 +193,28 @@ def test_one_group_check_sees_a_single_wrong_code():
             bad.append(g)
             assert (got != want).any(axis=1).nonzero()[0].tolist() == [3], "only the changed row differs"
     assert bad == [5]
+
+
+@pytest.mark.parametrize("M,K,N,packed", [(8, 4096, 4096, False), (8, 1024, 64, False), (40, 1024, 64, False),
+                                          (200, 1024, 256, False), (2048, 1024, 2048, False),
+                                          (200, 1024, 256, True), (1024, 4096, 4096, True)])
+def test_subnormal_scales_are_not_flushed(M, K, N, packed):
+    """Activation scales that are fp16 subnormals (2^-16, 2^-17: tiny activations) against weight
+    scales of 2^6, 2^7: every term is a multiple of 2^-11 below 2^11, every sum exact in fp32 in any
+    order, so Y equals the oracle's bit for bit, unless a kernel reads a subnormal scale as zero."""
+    print(f"[case] subnormal activation scales M={M} K={K} N={N} packed={packed}", flush=True)
+    pr = _Problem(M, K, N, 128, seed=M + K + N + 5, small8=True)
+    asc = (2.0 ** pr.rng.integers(-17, -15, (pr.M, pr.G))).astype(np.float16)
+    wsc = (2.0 ** pr.rng.integers(6, 8, (pr.N, pr.G))).astype(np.float16)
+    assert (asc > 0).all() and (asc < 2.0 ** -14).all()
+    want = pr.oracle(asc, wsc)["y"]
+    assert (want != 0).mean() > 0.9
+    ad, wd = torch.from_numpy(asc).cuda(), torch.from_numpy(wsc).cuda()
+    pk = None
+    if packed:
+        ws = torch.empty(atom.atom_w4a4_gemm_packed_workspace_bytes(pr.M, pr.N, pr.K), dtype=torch.uint8, device="cuda")
+        pk = (atom.atom_pack_weight(pr.dev[2], pr.dev[3], wd), ws)
+    y = _run(pr, ad, wd, pk)
+    torch.cuda.synchronize()
+    got = npy(y[torch.from_numpy(pr.rows).cuda()][:, torch.from_numpy(pr.cols).cuda()])
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16)), "Y differs from the oracle's"
