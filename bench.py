@@ -283,11 +283,12 @@ def step_summary(config, steps=100, warmup=10, fused_retile=None):
 
 
 def decode_sweep():
-    """Decode-sized GEMMs against the HBM roofline: config 3's eight shapes and the fused gate/up
-    projection at M = 8, weights walked through a ring of copies > 1 GB."""
+    """Decode-sized GEMMs against the HBM roofline: config 3's eight shapes, the fused gate/up
+    projection and the down projection at M = 8, weights walked through a ring of copies > 1 GB."""
     out = []
     sweep = [synth.make(3, w) for w in range(len(synth.CONFIG_SHAPES[3]))]
     sweep.append(synth.llama_linear("decode_m8_n22016", 8, 4096, 22016, 3, tensor_base=90))
+    sweep.append(synth.llama_linear("decode_m8_down", 8, 11008, 4096, 3, tensor_base=92, norm=False))   # the down projection: 86 groups
     for lin in sweep:
         row = (lin.K - lin.n_outlier) // 2 + lin.n_outlier + 2 * (lin.K // lin.group_size)
         copies = max(2, int(1.2e9 // (lin.N * row)) + 1)
@@ -302,7 +303,7 @@ def decode_sweep():
         del L.tiled_ring
         torch.cuda.empty_cache()
         t, ge, fe, pk, _ = run_steps([L], 100, 10, 0.02)
-        entry = {"workload": f"config3 decode M={lin.M} K=4096 N={lin.N}, weight ring of {copies}",
+        entry = {"workload": f"config3 decode M={lin.M} K={lin.K} N={lin.N}, weight ring of {copies}",
                  "gemm_us_in_graph": per * 1e6, "gemm_bytes": L.gemm_bytes,
                  "gemm_GBs": L.gemm_bytes / per / 1e9,
                  "gemm_hbm_frac": L.gemm_bytes / per / 1e9 / PEAK_HBM_GBS,

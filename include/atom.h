@@ -198,7 +198,7 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8,
  *                 (which = 0) or INT8 (which = 1) array: ceil(N/16)*16 rows
  *   w_q4_tiled / w_q8_tiled   16-byte aligned device arrays of those sizes
  * atom_w4a4_gemm_decode_tiled: ATOM_ERR_UNSUPPORTED unless M <= 64,
- * n_outlier = 128, K/128 a multiple of 4 and at least 8, and the arrays stay
+ * n_outlier = 128, K/128 even and at least 8, and the arrays stay
  * below 4 GiB; both scale arrays 8-byte aligned (ATOM_ERR_ALIGN).
  */
 size_t atom_tile_weight_decode_bytes(int64_t N, const atom_desc *d, int which);

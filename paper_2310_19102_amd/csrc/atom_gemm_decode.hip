@@ -264,13 +264,16 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
 }
 
 // The cases decoding runs in, written out on their own: RB blocks of 16 activation rows
-// (M <= 16 RB), O = 128 (one INT8 group, the last group of K), G a multiple of four, 8-byte aligned
-// scale rows, 32-bit offsets.  Same sums in the same order as w4a4_gemm_decode_kernel<RB, true,
+// (M <= 16 RB), O = 128 (one INT8 group, the last group of K), 32-bit offsets, and either G a
+// multiple of four with 8-byte aligned scale rows (TAIL = 3: the last block of four is three INT4
+// groups and the INT8 group; the four scales of a batch are one 8-byte load) or G = 4 j + 2 with
+// 4-byte aligned scale rows (TAIL = 1: the last block is one INT4 group and the INT8 group; two
+// 4-byte loads).  Same sums in the same order as w4a4_gemm_decode_kernel<RB, true,
 // true> (eight K-slices of whole four-group blocks, ascending inside a slice, slices added
 // 0..7), so the two agree bit for bit.  What differs is the vector work per weight byte and the
 // bytes the vector memory path returns to registers (64 per clock and CU), which set the pace here:
-//   * a batch is four INT4 groups; the batch that holds the INT8 group (the last one of the last
-//     wavefront) is code of its own: no per-slot case analysis, no second half of an INT8 group
+//   * a batch is four INT4 groups; the batch that holds the INT8 group (the last block of K, in
+//     the last wavefront) is code of its own: no per-slot case analysis, no second half of an INT8 group
 //     loaded where there is none;
 //   * rows >= M are not zeroed in the operand: an MFMA row depends on its own operand row only, and
 //     those rows are never stored;
@@ -293,7 +296,20 @@ __device__ __forceinline__ v4h16 scale_operand(const uint2 &piece)
     return __builtin_bit_cast(v4h16, make_uint2((D & 1) ? r >> 16 : r & 0xffffu, 0u));
 }
 
-template <int RB, bool TILED>
+// The (up to) four scales of the batch that starts at group gb of scale row `row_off` (in elements).
+// A8: one aligned 8-byte piece.  Otherwise the row starts on an even element and the batch on a
+// multiple of four: two 4-byte loads, the second held inside the row where the batch is the last
+// block of two groups.
+template <bool A8>
+__device__ __forceinline__ uint2 load_scales(const uint16_t *base, uint32_t row_off, int gb, int G)
+{
+    if constexpr (A8) return *reinterpret_cast<const uint2 *>(base + (row_off + (uint32_t)gb));
+    const int g2 = gb + 2 <= G - 2 ? gb + 2 : G - 2;
+    return make_uint2(*reinterpret_cast<const uint32_t *>(base + (row_off + (uint32_t)gb)),
+                      *reinterpret_cast<const uint32_t *>(base + (row_off + (uint32_t)g2)));
+}
+
+template <int RB, bool TILED, int TAIL>
 __global__ __launch_bounds__(NT, RB == 4 ? 2 : 4)     // RB = 2: two workgroups per CU; RB = 4 spills below 146 registers
 void w4a4_gemm_decode16_kernel(const GemmParams p)
 {
@@ -307,9 +323,10 @@ void w4a4_gemm_decode16_kernel(const GemmParams p)
     const int K4 = p.K - 128, G = p.K >> 7;
     const int M = (int)p.M;
     const int64_t n0 = (int64_t)blockIdx.x * TN;
-    const int nblk    = G >> 2;
+    constexpr bool A8 = TAIL == 3;
+    const int nblk    = (G + 3) >> 2;
     const int g_begin = 4 * (int)((int64_t)wave * nblk / NW);
-    const int g_end   = 4 * (int)((int64_t)(wave + 1) * nblk / NW);
+    const int g_end   = min(G, 4 * (int)((int64_t)(wave + 1) * nblk / NW));
 
     int64_t wr = n0 + col;                                // clamped: columns >= N are computed and never stored
     wr = wr < p.N ? wr : p.N - 1;
@@ -340,25 +357,26 @@ void w4a4_gemm_decode16_kernel(const GemmParams p)
         constexpr bool HAS8 = decltype(has8_c)::value;
         // every load of the batch is issued before the first is used; the scales first, they are
         // needed with the first group
-        uint2 wvs = *reinterpret_cast<const uint2 *>(p.w_scale + (wso + (uint32_t)gb));
+        constexpr int NG4 = HAS8 ? TAIL : 4;               // INT4 groups of the batch
+        uint2 wvs = load_scales<A8>(p.w_scale, wso, gb, G);
         uint2 avs[RB];
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) avs[rb] = *reinterpret_cast<const uint2 *>(p.a_scale + (aso[rb] + (uint32_t)gb));
+        for (int rb = 0; rb < RB; ++rb) avs[rb] = load_scales<A8>(p.a_scale, aso[rb], gb, G);
         uint4 wq[4], aq[4][RB], wx, ax[RB];
 #pragma unroll
-        for (int d = 0; d < (HAS8 ? 3 : 4); ++d) {
+        for (int d = 0; d < NG4; ++d) {
             wq[d] = *reinterpret_cast<const uint4 *>(p.w_q4 + (w4o + (uint32_t)(gb + d) * GSTEP));
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
                 aq[d][rb] = *reinterpret_cast<const uint4 *>(p.a_q4 + (a4o[rb] + (uint32_t)(gb + d) * 64u));
         }
         if constexpr (HAS8) {
-            wq[3] = *reinterpret_cast<const uint4 *>(w8b + w8o);
-            wx    = *reinterpret_cast<const uint4 *>(w8b + (w8o + GSTEP));
+            wq[TAIL] = *reinterpret_cast<const uint4 *>(w8b + w8o);
+            wx       = *reinterpret_cast<const uint4 *>(w8b + (w8o + GSTEP));
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                aq[3][rb] = *reinterpret_cast<const uint4 *>(a8b + a8o[rb]);
-                ax[rb]    = *reinterpret_cast<const uint4 *>(a8b + (a8o[rb] + 64u));
+                aq[TAIL][rb] = *reinterpret_cast<const uint4 *>(a8b + a8o[rb]);
+                ax[rb]       = *reinterpret_cast<const uint4 *>(a8b + (a8o[rb] + 64u));
             }
         }
         // (the fence keeps the loads here: left alone the compiler spreads them between the MFMAs
@@ -383,25 +401,24 @@ void w4a4_gemm_decode16_kernel(const GemmParams p)
             }
         };
         int4_group(wq[0], aq[0], std::integral_constant<int, 0>());
-        int4_group(wq[1], aq[1], std::integral_constant<int, 1>());
-        int4_group(wq[2], aq[2], std::integral_constant<int, 2>());
-        if constexpr (!HAS8) {
-            int4_group(wq[3], aq[3], std::integral_constant<int, 3>());
-        } else {
+        if constexpr (NG4 > 1) int4_group(wq[1], aq[1], std::integral_constant<int, 1>());
+        if constexpr (NG4 > 2) int4_group(wq[2], aq[2], std::integral_constant<int, 2>());
+        if constexpr (NG4 > 3) int4_group(wq[3], aq[3], std::integral_constant<int, 3>());
+        if constexpr (HAS8) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, aq[3][rb]), __builtin_bit_cast(v4i, wq[3]), zi, 0, 0, 0);
+                v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, aq[TAIL][rb]), __builtin_bit_cast(v4i, wq[TAIL]), zi, 0, 0, 0);
                 c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, ax[rb]), __builtin_bit_cast(v4i, wx), c, 0, 0, 0);
-                const v4f32 sc = __builtin_amdgcn_mfma_f32_16x16x16f16(scale_operand<3>(avs[rb]), scale_operand<3>(wvs), zf, 0, 0, 0);
+                const v4f32 sc = __builtin_amdgcn_mfma_f32_16x16x16f16(scale_operand<TAIL>(avs[rb]), scale_operand<TAIL>(wvs), zf, 0, 0, 0);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[rb][e] = fmaf((float)c[e], 256.0f * sc[e], acc[rb][e]);
             }
         }
     };
 
-    const int g_plain = wave == NW - 1 ? g_end - 4 : g_end;
+    const int g_plain = wave == NW - 1 ? g_end - (TAIL + 1) : g_end;
     for (int gb = g_begin; gb < g_plain; gb += 4) batch(gb, std::false_type());
-    if (wave == NW - 1) batch(G - 4, std::true_type());
+    if (wave == NW - 1) batch(G - (TAIL + 1), std::true_type());
 
     // the eight K-slices meet in LDS and are added in slice order
 #pragma unroll
@@ -426,7 +443,7 @@ void w4a4_gemm_decode16_kernel(const GemmParams p)
 // batch's activation codes (256 bytes per row: four groups) into a region of LDS of its own, four
 // rows per load instruction (SI instructions), and reads its MFMA operand from there; rows >= M of
 // the operand repeat row 0.  No barrier: LDS instructions of one wavefront execute in order.
-template <int SI, bool TILED>
+template <int SI, bool TILED, int TAIL>
 __global__ __launch_bounds__(NT, 6)
 void w4a4_gemm_decode_staged_kernel(const GemmParams p)
 {
@@ -442,9 +459,10 @@ void w4a4_gemm_decode_staged_kernel(const GemmParams p)
     const int K4 = p.K - 128, G = p.K >> 7;
     const int M = (int)p.M;
     const int64_t n0 = (int64_t)blockIdx.x * TN;
-    const int nblk    = G >> 2;
+    constexpr bool A8 = TAIL == 3;
+    const int nblk    = (G + 3) >> 2;
     const int g_begin = 4 * (int)((int64_t)wave * nblk / NW);
-    const int g_end   = 4 * (int)((int64_t)(wave + 1) * nblk / NW);
+    const int g_end   = min(G, 4 * (int)((int64_t)(wave + 1) * nblk / NW));
 
     int64_t wr = n0 + col;                                // clamped: columns >= N are computed and never stored
     wr = wr < p.N ? wr : p.N - 1;
@@ -474,25 +492,24 @@ void w4a4_gemm_decode_staged_kernel(const GemmParams p)
         // (they go through LDS), then the scales
         // (named registers, not an array: the array stayed in scratch memory)
         uint4 st0, st1, st2, st3;
-        const uint32_t ch = HAS8 ? (col < 12 ? col : 11) : col;              // three INT4 groups only: 12 chunks
+        constexpr int NG4 = HAS8 ? TAIL : 4;                                  // INT4 groups of the batch
+        const uint32_t ch = col < 4 * NG4 ? col : 4 * NG4 - 1;               // their 64-byte pieces: 4 NG4 chunks of a row
         auto stage_load = [&](int i) __attribute__((always_inline)) {
             return *reinterpret_cast<const uint4 *>(p.a_q4 + (srow[i] + (uint32_t)gb * 64u + ch * 16u));
         };
         st0 = stage_load(0);
         if constexpr (SI > 1) st1 = stage_load(1);
         if constexpr (SI > 2) { st2 = stage_load(2); st3 = stage_load(3); }
-        uint2 avs = *reinterpret_cast<const uint2 *>(p.a_scale + (aso + (uint32_t)gb));
-        uint2 wvs = *reinterpret_cast<const uint2 *>(p.w_scale + (wso + (uint32_t)gb));
+        uint2 avs = load_scales<A8>(p.a_scale, aso, gb, G);
+        uint2 wvs = load_scales<A8>(p.w_scale, wso, gb, G);
         uint4 wq[4], wx, a8[2];
 #pragma unroll
-        for (int d = 0; d < 3; ++d) wq[d] = *reinterpret_cast<const uint4 *>(p.w_q4 + (w4o + (uint32_t)(gb + d) * GSTEP));
+        for (int d = 0; d < NG4; ++d) wq[d] = *reinterpret_cast<const uint4 *>(p.w_q4 + (w4o + (uint32_t)(gb + d) * GSTEP));
         if constexpr (HAS8) {
-            wq[3] = *reinterpret_cast<const uint4 *>(w8b + w8o);
-            wx    = *reinterpret_cast<const uint4 *>(w8b + (w8o + GSTEP));
-            a8[0] = *reinterpret_cast<const uint4 *>(a8b + a8o);
-            a8[1] = *reinterpret_cast<const uint4 *>(a8b + (a8o + 64u));
-        } else {
-            wq[3] = *reinterpret_cast<const uint4 *>(p.w_q4 + (w4o + (uint32_t)(gb + 3) * GSTEP));
+            wq[TAIL] = *reinterpret_cast<const uint4 *>(w8b + w8o);
+            wx       = *reinterpret_cast<const uint4 *>(w8b + (w8o + GSTEP));
+            a8[0]    = *reinterpret_cast<const uint4 *>(a8b + a8o);
+            a8[1]    = *reinterpret_cast<const uint4 *>(a8b + (a8o + 64u));
         }
         // (the fence keeps the loads here: left alone the compiler spreads them between the MFMAs
         // to save registers, which turns one memory round trip per batch into several)
@@ -502,7 +519,7 @@ void w4a4_gemm_decode_staged_kernel(const GemmParams p)
         if constexpr (SI > 2) { *reinterpret_cast<uint4 *>(st_w + 8 * ROWB) = st2; *reinterpret_cast<uint4 *>(st_w + 12 * ROWB) = st3; }
         uint4 aq[4];
 #pragma unroll
-        for (int d = 0; d < (HAS8 ? 3 : 4); ++d) aq[d] = *reinterpret_cast<const uint4 *>(st_r + 64 * d);
+        for (int d = 0; d < NG4; ++d) aq[d] = *reinterpret_cast<const uint4 *>(st_r + 64 * d);
         if (kc != 0) { avs = make_uint2(0, 0); wvs = make_uint2(0, 0); }     // k-slots 4 .. 15 of the scale MFMA stay empty
 
         auto scales = [&](auto dc) __attribute__((always_inline)) -> v4f32 {
@@ -517,22 +534,21 @@ void w4a4_gemm_decode_staged_kernel(const GemmParams p)
             for (int e = 0; e < 4; ++e) acc[e] = fmaf((float)c[e], sc[e], acc[e]);
         };
         int4_group(wq[0], aq[0], std::integral_constant<int, 0>());
-        int4_group(wq[1], aq[1], std::integral_constant<int, 1>());
-        int4_group(wq[2], aq[2], std::integral_constant<int, 2>());
-        if constexpr (!HAS8) {
-            int4_group(wq[3], aq[3], std::integral_constant<int, 3>());
-        } else {
-            v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, a8[0]), __builtin_bit_cast(v4i, wq[3]), zi, 0, 0, 0);
+        if constexpr (NG4 > 1) int4_group(wq[1], aq[1], std::integral_constant<int, 1>());
+        if constexpr (NG4 > 2) int4_group(wq[2], aq[2], std::integral_constant<int, 2>());
+        if constexpr (NG4 > 3) int4_group(wq[3], aq[3], std::integral_constant<int, 3>());
+        if constexpr (HAS8) {
+            v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, a8[0]), __builtin_bit_cast(v4i, wq[TAIL]), zi, 0, 0, 0);
             c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, a8[1]), __builtin_bit_cast(v4i, wx), c, 0, 0, 0);
-            const v4f32 sc = scales(std::integral_constant<int, 3>());
+            const v4f32 sc = scales(std::integral_constant<int, TAIL>());
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[e] = fmaf((float)c[e], 256.0f * sc[e], acc[e]);   // the accumulator holds 256 x the sum
         }
     };
 
-    const int g_plain = wave == NW - 1 ? g_end - 4 : g_end;
+    const int g_plain = wave == NW - 1 ? g_end - (TAIL + 1) : g_end;
     for (int gb = g_begin; gb < g_plain; gb += 4) batch(gb, std::false_type());
-    if (wave == NW - 1) batch(G - 4, std::true_type());
+    if (wave == NW - 1) batch(G - (TAIL + 1), std::true_type());
 
     // the eight K-slices meet in LDS (each wavefront's region, its operand reads are complete) and
     // are added in slice order
@@ -551,12 +567,30 @@ void w4a4_gemm_decode_staged_kernel(const GemmParams p)
     }
 }
 
-template <bool TILED>
-void launch_staged(const GemmParams &p, unsigned blocks, hipStream_t stream)
+// The kernels of the common case: M <= 16 staged, else blocks of 16 rows.
+template <bool TILED, int TAIL>
+void launch_common(const GemmParams &p, unsigned blocks, hipStream_t stream)
 {
-    if (p.M <= 4)      hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<1, TILED>), dim3(blocks), dim3(NT), 0, stream, p);
-    else if (p.M <= 8) hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<2, TILED>), dim3(blocks), dim3(NT), 0, stream, p);
-    else               hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<4, TILED>), dim3(blocks), dim3(NT), 0, stream, p);
+    if (p.M <= 4)       hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<1, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
+    else if (p.M <= 8)  hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<2, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
+    else if (p.M <= 16) hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<4, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
+    else if (p.M <= 32) hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<2, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
+    else                hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
+}
+
+// 3: G a multiple of four, scale rows 8-byte aligned; 1: G = 4 j + 2, scale rows 4-byte aligned; 0: neither.
+// In both cases: exactly one INT8 group that is the last group of the last wavefront's run (G >= 8),
+// M <= 64, 32-bit offsets.
+int common_tail(const GemmParams &p)
+{
+    const int G = p.K >> 7;
+    const uintptr_t al = reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale);
+    if (!(p.M <= 64 && p.O == 128 && G >= NW && (uint64_t)(p.N + TN) * (uint64_t)(p.K >> 1) < (1ull << 32) &&
+          (uint64_t)p.N * (uint64_t)G < (1ull << 31)))
+        return 0;
+    if (G % 4 == 0 && (al & 7) == 0) return 3;
+    if (G % 4 == 2 && (al & 3) == 0) return 1;
+    return 0;
 }
 
 // Re-tiling of the canonical weight codes for the TILED variants: one workgroup per block of 16
@@ -597,45 +631,36 @@ hipError_t launch_tile_weight(const void *q4, const void *q8, int64_t N, int K, 
     return hipGetLastError();
 }
 
-// What the tiled variants need: one INT8 group that is the last group of the last wavefront's run,
-// whole blocks of four groups with 8-byte aligned scale rows, M <= 64.
-bool decode_tiled_supported(const GemmParams &p)
-{
-    const int G = p.K >> 7;
-    return p.M <= 64 && p.O == 128 && G >= NW && G % 4 == 0 &&
-           ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 7) == 0 &&
-           (uint64_t)(p.N + TN) * (uint64_t)(p.K >> 1) < (1ull << 32) && (uint64_t)p.N * (uint64_t)G < (1ull << 31);
-}
+// What the kernels that read tiled weights need: the common case (see common_tail).
+bool decode_tiled_supported(const GemmParams &p) { return common_tail(p) != 0; }
 
 hipError_t launch_decode_tiled(const GemmParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)((p.N + TN - 1) / TN);
-    if (p.M <= 16)      launch_staged<true>(p, blocks, stream);
-    else if (p.M <= 32) hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<2, true>), dim3(blocks), dim3(NT), 0, stream, p);
-    else                hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, true>), dim3(blocks), dim3(NT), 0, stream, p);
+    if (common_tail(p) == 3) launch_common<true, 3>(p, blocks, stream);
+    else                     launch_common<true, 1>(p, blocks, stream);
     return hipGetLastError();
 }
 
 hipError_t launch_decode(const GemmParams &p, hipStream_t stream)
 {
     const unsigned blocks = (unsigned)((p.N + TN - 1) / TN);
-    // vector scale loads: G even (a scale row then starts on a 4-byte boundary), both scale arrays
-    // 4-byte aligned
+    const int tail = common_tail(p);
+    if (tail == 3) { launch_common<false, 3>(p, blocks, stream); return hipGetLastError(); }
+    if (tail == 1) { launch_common<false, 1>(p, blocks, stream); return hipGetLastError(); }
+    // The general kernel.  Vector scale loads: G even (a scale row then starts on a 4-byte boundary),
+    // both scale arrays 4-byte aligned
     const int  G  = p.K >> 7;
     const bool vs = G % 2 == 0 && G >= 4 && ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 3) == 0 &&
                     (uint64_t)p.N * (uint64_t)G < (1ull << 31);          // 32-bit scale offsets
     // exactly one INT8 group, and it is the last group of the last wavefront's run (G >= 8)
     const bool one8 = p.O == 128 && G >= NW && (uint64_t)p.N * (uint64_t)(p.K >> 1) < (1ull << 32);   // 32-bit byte offsets
-    const bool q4 = G % 4 == 0 && ((reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale)) & 7) == 0;
     if (p.M <= 16 && vs && one8) {
-        if (q4) launch_staged<false>(p, blocks, stream);
-        else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (p.M <= 32 && vs && one8) {
-        if (q4) hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<2, false>), dim3(blocks), dim3(NT), 0, stream, p);
-        else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        hipLaunchKernelGGL((w4a4_gemm_decode_kernel<2, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (vs && one8) {
-        if (q4) hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, false>), dim3(blocks), dim3(NT), 0, stream, p);
-        else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<4, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
+        hipLaunchKernelGGL((w4a4_gemm_decode_kernel<4, true, true>), dim3(blocks), dim3(NT), 0, stream, p);
     } else if (p.M <= 16) {
         if (vs) hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, true>), dim3(blocks), dim3(NT), 0, stream, p);
         else    hipLaunchKernelGGL((w4a4_gemm_decode_kernel<1, false>), dim3(blocks), dim3(NT), 0, stream, p);
