@@ -126,6 +126,17 @@ class DeviceLinear:
         self.turn += 1
         atom.atom_decode_linear(self.x, self.gamma, l.eps, self.idx, *qw, l.group_size, l.clip_act, out=self.y)
 
+    def one_launch_coop(self):
+        """One kernel whose first M workgroups run the front end once while the others already
+        stream their weights (M <= 16)."""
+        l = self.lin
+        qw = self.qw_ring[self.turn % len(self.qw_ring)]
+        self.turn += 1
+        if not hasattr(self, "sync"):
+            self.sync = atom.atom_decode_linear_coop_sync(self.x.device)
+        atom.atom_decode_linear_coop(self.x, self.gamma, l.eps, self.idx, *qw, self.sync, l.group_size, l.clip_act,
+                                     out=self.y, codes=self.qa)
+
     def one_launch_no_index(self):
         """The same for an input that already is in reordered order (the producer's weight rows were
         permuted offline): no gather, one wavefront per row."""
@@ -319,6 +330,20 @@ def decode_sweep():
             step_bytes = L.gemm_bytes - lin.M * ((lin.K - lin.n_outlier) // 2 + lin.n_outlier + 2 * L.G) + 2 * lin.M * lin.K
             entry["step_us_in_graph_one_launch"] = one * 1e6
             entry["one_launch_hbm_frac"] = step_bytes / one / 1e9 / PEAK_HBM_GBS
+            L.one_launch_coop()          # (allocates the counters outside the capture)
+            torch.cuda.synchronize()
+            coop = decode_gemm_in_graph(L, copies, L.one_launch_coop)
+            entry["step_us_in_graph_one_launch_coop"] = coop * 1e6
+            entry["one_launch_coop_hbm_frac"] = step_bytes / coop / 1e9 / PEAK_HBM_GBS
+            assert int(L.sync.abs().sum().item()) == 0, "a workgroup's wait for the rows ran out"
+            for _ in range(20):
+                L.one_launch_coop()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(200):
+                L.one_launch_coop()
+            torch.cuda.synchronize()
+            entry["step_us_eager_one_launch_coop"] = (time.perf_counter() - t0) / 200 * 1e6
             # outside a graph the host's launch cost dominates these sizes: one launch instead of two
             for _ in range(20):
                 L.one_launch()

@@ -255,8 +255,8 @@ atom_status atom_permute_rows(const void *in_f16, int64_t rows_in, int64_t cols,
  * ATOM_ERR_UNSUPPORTED unless 1 <= M <= 16 (M = 0 is a no-op), K <= 12288,
  * 2^-20 <= clip <= 1 and atom_decode_linear_lds_bytes(M, d, norm, index) <=
  * 163840 (the codes of all M rows and, with an index, the staged row live in
- * one workgroup's LDS).  With an index the rows are quantised one after the
- * other by the whole workgroup; without one, one wavefront per row.
+ * one workgroup's LDS).  Every workgroup quantises the M rows itself, one after
+ * the other (atom_decode_linear_coop does it once per launch instead).
  * Alignment as atom_quantize_act and atom_w4a4_gemm; debug arrays 4-byte.
  */
 atom_status atom_decode_linear(const void *x_f16, int64_t M, int64_t ldx,
@@ -266,6 +266,48 @@ atom_status atom_decode_linear(const void *x_f16, int64_t M, int64_t ldx,
                                const void *w_scale, int64_t N, void *y_f16,
                                int64_t ldy, void *dbg_q4, void *dbg_q8,
                                void *dbg_scale, void *stream);
+
+/*
+ * The same linear layer in one launch with the front end done once (Sections
+ * 3, 4.1, 4.2, 4.5): the first M workgroups of the launch quantise one row of
+ * x each into a_q4 / a_q8 / a_scale (the outputs of atom_quantize_act, bit
+ * for bit) and count themselves in; all other workgroups are those of
+ * atom_w4a4_gemm at this size: they request their weights, wait until M rows
+ * are counted, and fetch the codes, so the front end runs while the weights
+ * travel from HBM.  Y is bit-identical to atom_quantize_act followed by
+ * atom_w4a4_gemm (the same kernel routine, the same sum over groups).
+ *
+ *   a_q4 [M, (K-O)/2], a_q8 [M, O], a_scale [M, K/Gs]   outputs (device), also
+ *                 the kernel's own channel between its workgroups: each
+ *                 128-byte aligned, and nothing else that the call reads may
+ *                 lie in the same 128-byte lines (the consumers rely on
+ *                 finding none of these lines in a cache before the rows are
+ *                 counted)
+ *   sync_words    atom_decode_linear_coop_sync_bytes() bytes of device memory,
+ *                 128-byte aligned, that hold zeros before the first call
+ *                 (hipMemset once) and are used by no other call at the same
+ *                 time; a call leaves them zero again, so calls in stream
+ *                 order, and replays of a captured graph, need no clearing in
+ *                 between.  The second 32-bit word stays zero unless a workgroup
+ *                 waited for the rows longer than 2^18 polls (it then goes on
+ *                 with whatever the arrays hold; the kernel always ends):
+ *                 nonzero means Y of some call was wrong, e.g. because the
+ *                 words were not zero at its start.
+ * ATOM_ERR_UNSUPPORTED unless 1 <= M <= 16 (M = 0 is a no-op), K <= 12288,
+ * n_outlier = 128, K/128 even and at least 8, 2^-20 <= clip <= 1 and the arrays
+ * below 4 GiB.  Alignment otherwise as atom_quantize_act and atom_w4a4_gemm,
+ * w_scale 8-byte aligned.
+ */
+size_t atom_decode_linear_coop_sync_bytes(void);
+atom_status atom_decode_linear_coop(const void *x_f16, int64_t M, int64_t ldx,
+                                    const void *gamma_f16, float eps,
+                                    const int32_t *reorder_idx,
+                                    const atom_desc *d, float clip,
+                                    const void *w_q4, const void *w_q8,
+                                    const void *w_scale, int64_t N, void *y_f16,
+                                    int64_t ldy, void *a_q4, void *a_q8,
+                                    void *a_scale, void *sync_words,
+                                    void *stream);
 
 /* LDS bytes per workgroup atom_decode_linear needs (0 for a bad descriptor). */
 size_t atom_decode_linear_lds_bytes(int64_t M, const atom_desc *d, int with_norm,

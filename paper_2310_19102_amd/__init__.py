@@ -28,6 +28,8 @@ from .binding import (  # noqa: F401
     atom_w4a4_gemm,
     atom_w4a4_gemm_workspace_bytes,
     atom_decode_linear,
+    atom_decode_linear_coop,
+    atom_decode_linear_coop_sync,
     atom_permute_rows,
     atom_tile_weight_decode,
     atom_w4a4_gemm_decode_tiled,

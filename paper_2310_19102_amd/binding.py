@@ -27,6 +27,8 @@ EXPORTS = (
     "atom_w4a4_gemm_decode_tiled",
     "atom_permute_rows",
     "atom_decode_linear",
+    "atom_decode_linear_coop",
+    "atom_decode_linear_coop_sync_bytes",
     "atom_decode_linear_lds_bytes",
     "atom_pack_weight_bytes",
     "atom_pack_weight",
@@ -105,6 +107,10 @@ def load_library():
     L.atom_permute_rows.argtypes = [vp, i64, i64, i64, vp, i64, vp, i64, vp]
     L.atom_decode_linear.restype = ctypes.c_int
     L.atom_decode_linear.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp]
+    L.atom_decode_linear_coop_sync_bytes.restype = sz
+    L.atom_decode_linear_coop_sync_bytes.argtypes = []
+    L.atom_decode_linear_coop.restype = ctypes.c_int
+    L.atom_decode_linear_coop.argtypes = [vp, i64, i64, vp, f32, vp, dp, f32, vp, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp]
     L.atom_decode_linear_lds_bytes.restype = sz
     L.atom_decode_linear_lds_bytes.argtypes = [i64, dp, i32, i32]
     L.atom_pack_weight_bytes.restype = sz
@@ -319,6 +325,49 @@ def atom_decode_linear(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: floa
     if st != 0:
         raise AtomError(st, "atom_decode_linear")
     return (y, dbg) if debug else y
+
+
+def atom_decode_linear_coop_sync(device="cuda") -> torch.Tensor:
+    """The zeroed counters atom_decode_linear_coop works with (one per stream of calls)."""
+    n = int(load_library().atom_decode_linear_coop_sync_bytes())
+    return torch.zeros(n // 4, dtype=torch.int32, device=device)
+
+
+def atom_decode_linear_coop(x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float,
+                            reorder_idx: Optional[torch.Tensor], w_q4: torch.Tensor, w_q8: torch.Tensor,
+                            w_scale: torch.Tensor, sync_words: torch.Tensor, group_size: int = 128,
+                            clip: float = 0.9, out: Optional[torch.Tensor] = None,
+                            codes: Optional[Tuple[torch.Tensor, ...]] = None, bits: int = 4):
+    """One launch for ``Y = linear(x)`` at M <= 16 rows with the front end done once: the first M
+    workgroups quantise the rows, the others stream the weights meanwhile.  ``sync_words``:
+    ``atom_decode_linear_coop_sync()`` (int32 zeros on the device), zero before the first call, left
+    zero by every call (word 1 set = a wait ran out).  Returns ``(Y, (q4, q8, scale))``: the codes are outputs as in atom_quantize_act."""
+    L = load_library()
+    _dev(x, torch.float16, "x")
+    if reorder_idx is not None:        # None: x already is in reordered order
+        _dev(reorder_idx, torch.int32, "reorder_idx")
+    if gamma is not None:
+        _dev(gamma, torch.float16, "gamma")
+    _dev(w_q4, torch.uint8, "w_q4")
+    _dev(w_q8, torch.int8, "w_q8")
+    _dev(w_scale, torch.float16, "w_scale")
+    _dev(sync_words, torch.int32, "sync_words")
+    if 4 * sync_words.numel() < int(L.atom_decode_linear_coop_sync_bytes()) or not sync_words.is_contiguous():
+        raise ValueError("sync_words is too small: take atom_decode_linear_coop_sync()")
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [M, K] with a contiguous last dimension")
+    M, K = x.shape
+    N, O = w_q8.shape
+    y = out if out is not None else torch.empty((M, N), dtype=torch.float16, device=x.device)
+    q = codes if codes is not None else _quant_outputs(M, K, group_size, O, x.device)
+    d = _desc(K, group_size, O, bits)
+    st = L.atom_decode_linear_coop(_ptr(x), M, x.stride(0) if M > 1 else max(K, x.stride(0)), _ptr(gamma), eps,
+                                   _ptr(reorder_idx), ctypes.byref(d), clip, _ptr(w_q4), _ptr(w_q8), _ptr(w_scale),
+                                   N, _ptr(y), y.stride(0) if M > 1 else max(N, y.stride(0)), _ptr(q[0]), _ptr(q[1]),
+                                   _ptr(q[2]), _ptr(sync_words), _stream())
+    if st != 0:
+        raise AtomError(st, "atom_decode_linear_coop")
+    return y, q
 
 
 def atom_decode_linear_lds_bytes(M: int, K: int, n_outlier: int = 128, norm: bool = True, group_size: int = 128,

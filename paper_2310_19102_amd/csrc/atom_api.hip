@@ -259,6 +259,34 @@ atom_status atom_decode_linear(const void *x_f16, int64_t M, int64_t ldx, const 
     return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
 }
 
+size_t atom_decode_linear_coop_sync_bytes(void) { return atom_internal::decode_linear_coop_sync_bytes(); }
+
+atom_status atom_decode_linear_coop(const void *x_f16, int64_t M, int64_t ldx, const void *gamma_f16,
+                                    float eps, const int32_t *reorder_idx, const atom_desc *d, float clip,
+                                    const void *w_q4, const void *w_q8, const void *w_scale, int64_t N,
+                                    void *y_f16, int64_t ldy, void *a_q4, void *a_q8, void *a_scale,
+                                    void *sync_words, void *stream)
+{
+    atom_status st = check_desc(d);
+    if (st != ATOM_OK) return st;
+    if (M < 0 || N < 0 || ldx < d->K || ldy < N) return ATOM_ERR_SHAPE;
+    if (M == 0 || N == 0) return ATOM_OK;
+    if (!x_f16 || !w_q4 || !w_q8 || !w_scale || !y_f16 || !a_q4 || !a_q8 || !a_scale || !sync_words)
+        return ATOM_ERR_NULL;                                                        // reorder_idx may be null
+    if (!aligned(x_f16, 16) || (ldx % 8) || !aligned(reorder_idx, 16) || (gamma_f16 && !aligned(gamma_f16, 16)) ||
+        !aligned(w_q4, 16) || !aligned(w_q8, 16) || !aligned(w_scale, 8) || !aligned(y_f16, 2) ||
+        !aligned(a_q4, 128) || !aligned(a_q8, 128) || !aligned(a_scale, 128) || !aligned(sync_words, 128))
+        return ATOM_ERR_ALIGN;
+    if (M > 16 || !(clip >= 9.5367431640625e-07f && clip <= 1.0f) ||
+        !atom_internal::decode_linear_coop_supported((int)M, d->K, d->n_outlier, a_scale, w_scale, N))
+        return ATOM_ERR_UNSUPPORTED;
+    hipError_t err = atom_internal::launch_decode_linear_coop(x_f16, (int)M, ldx, gamma_f16, eps, reorder_idx, d->K,
+                                                              d->n_outlier, d->bits_normal, clip, w_q4, w_q8,
+                                                              w_scale, N, y_f16, ldy, a_q4, a_q8, a_scale,
+                                                              sync_words, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? ATOM_OK : ATOM_ERR_HIP;
+}
+
 size_t atom_tile_weight_decode_bytes(int64_t N, const atom_desc *d, int which)
 {
     if (check_desc(d) != ATOM_OK || N <= 0 || (which != 0 && which != 1)) return 0;

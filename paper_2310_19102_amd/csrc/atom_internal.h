@@ -77,6 +77,17 @@ hipError_t launch_decode_linear(const void *x, int M, int64_t ldx, const void *g
                                 void *y, int64_t ldy, void *dbg_q4, void *dbg_q8, void *dbg_scale,
                                 hipStream_t stream);
 
+// The one-launch decode linear with the front end done once by the first M workgroups (see
+// atom_decode_fused.hip); a_q4 / a_q8 / a_scale are outputs, sync decode_linear_coop_sync_bytes()
+// zeroed bytes.
+size_t     decode_linear_coop_sync_bytes();
+bool       decode_linear_coop_supported(int M, int K, int O, const void *a_scale, const void *w_scale, int64_t N);
+hipError_t launch_decode_linear_coop(const void *x, int M, int64_t ldx, const void *gamma, float eps,
+                                     const int32_t *idx, int K, int O, int nbits, float clip,
+                                     const void *w_q4, const void *w_q8, const void *w_scale, int64_t N,
+                                     void *y, int64_t ldy, void *a_q4, void *a_q8, void *a_scale, void *sync,
+                                     hipStream_t stream);
+
 hipError_t launch_quantize_rows_mx(const void *x, int64_t rows, int64_t ld, const void *gamma,
                                    float eps, const int32_t *idx, int K, int O, float clip, void *q4,
                                    void *q8, void *e8, hipStream_t stream);
