@@ -263,6 +263,25 @@ void w4a4_gemm_f6_kernel(const F6Params p)
     // refers to never changes: every lane reads the tile's first 16 bytes (one cache line per
     // instruction) into the spare kilobyte.
     auto request_dummy = [&]() __attribute__((always_inline)) { dma16(spare, vzero, a_tile); };
+    // Instruction k of the request of the first INT8 group, activation part (NA8 instructions) or
+    // weight part, into stage `stage`: issued in place of the dummies of two of the last steps,
+    // whose stages are free by then, so that the group has landed when the K loop ends.
+    auto request_int8 = [&](int k, int stage, bool act) __attribute__((always_inline)) {
+        constexpr int NA8 = Gm::NA8, NW8 = Gm::NI8 - Gm::NA8;
+        const int j = wave + NWAVE * k;
+        const bool real = j < (act ? NA8 : NW8);
+        int q = 64 * j + lane;                                    // 16-byte chunk within the part
+        const int nq = (act ? WM : 2) * (IMG8 / 16);
+        q = q < nq ? q : nq - 1;
+        int unit = q / (IMG8 / 16);
+        const int off = q - unit * (IMG8 / 16);
+        const int valid = act ? a_valid : w_valid;
+        unit = unit < valid ? unit : valid - 1;
+        const uint32_t vo = (uint32_t)unit * (uint32_t)p.ustride + 16u * off;
+        const uint32_t mk = 0u - (uint32_t)real;
+        const uint32_t dst = spare + ((lds0 + stage * STAGE + 1024 * j - spare) & mk);
+        dma16(dst, vo, (act ? a_tile : w_tile) + (int64_t)G4 * IMG4);
+    };
 
     // ---- fragment addresses: one register per operand (and one per operand for the scales) holds
     // the lane's address inside the stage of the coming group; everything a step reads is that
@@ -347,12 +366,13 @@ void w4a4_gemm_f6_kernel(const F6Params p)
     // wavefront waited for its own share before it) and every read of stage u is complete (issued
     // in the first slot), so from there on stage u is refilled with group u + NST, spread over
     // three slots: issued in one burst the requests fill the address queue and hold up MFMAs.
-    // A step has no branch (one inside it lets the compiler sink MFMAs past the barrier): REAL says
-    // at compile time whether group u + NST exists.
+    // A step has no branch (one inside it lets the compiler sink MFMAs past the barrier): MODE says
+    // at compile time what the step requests: 0 group u + NST, 1 nothing (dummies), 2 / 3 the
+    // activation / weight part of the first INT8 group.
     int cur = 0;                                // stage of group u
     uint32_t a_cur = a_off, b_cur = b_off;      // lane addresses in stage `cur`
-    auto step = [&](int u, auto real_c) __attribute__((always_inline)) {
-        constexpr bool REAL = decltype(real_c)::value;
+    auto step = [&](int u, auto mode_c) __attribute__((always_inline)) {
+        constexpr int MODE = decltype(mode_c)::value;
         const int nxt = cur + 1 == NST ? 0 : cur + 1;
         // lane addresses in the next stage (they become the current ones of the next step)
         const uint32_t a_nxt = a_off + nxt * STAGE, b_nxt = b_off + nxt * STAGE;
@@ -365,8 +385,10 @@ void w4a4_gemm_f6_kernel(const F6Params p)
 #pragma unroll
             for (int q = 0; q < n; ++q, ++kreq) {
                 if (kreq < LPW) {
-                    if (REAL) request_one(kreq, u + NST, cur);
-                    else      request_dummy();
+                    if constexpr (MODE == 0)      request_one(kreq, u + NST, cur);
+                    else if constexpr (MODE == 2) request_int8(kreq, cur, true);
+                    else if constexpr (MODE == 3) request_int8(kreq, cur, false);
+                    else                          request_dummy();
                 }
             }
         };
@@ -466,10 +488,19 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         c_pend = c3; s_pend = s3; u_pend = u;
         cur = nxt; a_cur = a_nxt; b_cur = b_nxt;
     };
+    // The last NST steps have nothing of the K loop left to request.  Two of them fetch the first
+    // INT8 group instead (its two parts fit a stage each), which then costs no round trip of its own.
+    static_assert(Gm::NA8 <= LPW * NWAVE && Gm::NI8 - Gm::NA8 <= LPW * NWAVE && Gm::NA8 * 1024 <= STAGE, "a part per step and stage");
+    const bool pre8 = p.G8 >= 1 && G4 >= NST;
+    int stage8a = 0, stage8w = 0;
     {
         int u = 0;
-        for (; u + NST < G4; ++u) step(u, std::true_type{});
-        for (; u < G4; ++u) step(u, std::false_type{});
+        for (; u + NST < G4; ++u) step(u, std::integral_constant<int, 0>{});
+        if (pre8) {
+            stage8a = cur; step(u++, std::integral_constant<int, 2>{});
+            stage8w = cur; step(u++, std::integral_constant<int, 3>{});
+        }
+        for (; u < G4; ++u) step(u, std::integral_constant<int, 1>{});
     }
     dequant(u_pend, 1, 1, c_pend, s_pend, 0, 16);
 
@@ -490,22 +521,26 @@ void w4a4_gemm_f6_kernel(const F6Params p)
             unit = unit < valid ? unit : valid - 1;
             voff8[k] = (uint32_t)unit * (uint32_t)p.ustride + 16u * off;
         }
-        const int a_unit8 = wm * IMG8, b_unit8 = APART8 + wn * IMG8;
         int ck[4];                                                 // byte offset of chunk 2 kk + g of row r
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) ck[kk] = 128 * r + 16 * (((2 * kk + g) ^ r ^ ((r >> 3) & 1)) & 7);
         __builtin_amdgcn_s_waitcnt(wait_imm(0));                   // the last (dummy) requests of the K loop
         for (int g8 = 0; g8 < p.G8; ++g8) {
+            const bool here = pre8 && g8 == 0;                     // requested during the K loop, in two stages
+            const int a_unit8 = (here ? stage8a * STAGE : 0) + wm * IMG8;
+            const int b_unit8 = (here ? stage8w * STAGE : APART8) + wn * IMG8;
             __syncthreads();                                       // every read of the LDS contents so far is done
-            const uint8_t *ab = a_tile + (int64_t)G4 * IMG4 + (int64_t)g8 * IMG8;
-            const uint8_t *wb = w_tile + (int64_t)G4 * IMG4 + (int64_t)g8 * IMG8;
+            if (!here) {
+                const uint8_t *ab = a_tile + (int64_t)G4 * IMG4 + (int64_t)g8 * IMG8;
+                const uint8_t *wb = w_tile + (int64_t)G4 * IMG4 + (int64_t)g8 * IMG8;
 #pragma unroll
-            for (int k = 0; k < LPW8; ++k) {
-                const int j = wave + NWAVE * k;
-                if (j < NI8) dma16(lds0 + 1024 * j, voff8[k], j < NA8 ? ab : wb);
+                for (int k = 0; k < LPW8; ++k) {
+                    const int j = wave + NWAVE * k;
+                    if (j < NI8) dma16(lds0 + 1024 * j, voff8[k], j < NA8 ? ab : wb);
+                }
+                __builtin_amdgcn_s_waitcnt(wait_imm(0));
+                __syncthreads();
             }
-            __builtin_amdgcn_s_waitcnt(wait_imm(0));
-            __syncthreads();
             v2u qa[2], qb[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {

@@ -111,3 +111,25 @@ def test_coop_decode_linear_limits():
     assert y.shape == (0, 32)
     torch.cuda.synchronize()
     assert not npy(sync).any()
+
+
+def test_coop_decode_linear_strided_and_w3a3():
+    """Row strides on x and Y; 3-bit normal codes (Section 5.4.1's W3A3 variant)."""
+    lin = _rand_linear(6, 2048, 72, seed=77)
+    xs = torch.zeros((6, 2048 + 64), dtype=torch.float16, device="cuda")
+    xs[:, :2048] = dev(lin.x)
+    ys = torch.full((6, 100), 7.0, dtype=torch.float16, device="cuda")
+    sync = atom.atom_decode_linear_coop_sync()
+    for bits in (4, 3):
+        gw = atom.atom_quantize_weight(dev(lin.w), dev(lin.idx), 128, 128, lin.clip_weight, bits=bits)
+        y, codes = atom.atom_decode_linear_coop(xs[:, :2048], dev(lin.gamma), lin.eps, dev(lin.idx), *gw, sync, 128,
+                                                lin.clip_act, out=ys[:, :72], bits=bits)
+        torch.cuda.synchronize()
+        ra = oracle.quantize_act(lin.x.numpy(), lin.gamma.numpy(), lin.eps, lin.idx.numpy(), 128, 128,
+                                 lin.clip_act, bits)
+        assert_quant_equal(codes, ra, f"codes, {bits} bits")
+        rw = oracle.quantize_weight(lin.w.numpy(), lin.idx.numpy(), 128, 128, lin.clip_weight, bits)
+        ref = oracle.w4a4_gemm(*ra, *rw, 128)
+        assert y_rel_err(npy(ys[:, :72]), ref["y"]) <= Y_TOL
+        assert (ys[:, 72:] == 7.0).all(), "columns beyond N were written"
+        assert not npy(sync).any()
