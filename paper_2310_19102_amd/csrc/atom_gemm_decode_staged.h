@@ -84,12 +84,18 @@ struct NoWait {
     __device__ __forceinline__ void passed() const {}
 };
 
-// One block of activation rows (M <= 16), otherwise the cases and the arithmetic of
-// w4a4_gemm_decode16_kernel (atom_gemm_decode.hip; its header lists them).  What it adds: the activation operand is 16 rows whatever M is, as
-// many bytes returned to registers as the weights.  Here a wavefront copies the M real rows of its
-// batch's activation codes (256 bytes per row: four groups) into a region of LDS of its own, four
-// rows per load instruction (SI instructions), and reads its MFMA operand from there; rows >= M of
-// the operand repeat row 0.  No barrier: LDS instructions of one wavefront execute in order.
+// The routine.  Cases: M <= 16, O = 128 (one INT8 group, the last group of K), 32-bit offsets, and
+// either G a multiple of four with 8-byte aligned scale rows (TAIL = 3) or G = 4 j + 2 with 4-byte
+// aligned ones (TAIL = 1); weight codes canonical or re-tiled (TILED).  Arithmetic and order of the
+// sums are those of w4a4_gemm_decode16_kernel (atom_gemm_decode.hip, whose header explains them:
+// eight K-slices of four-group blocks, scale products on an fp16 MFMA, an accumulator that holds
+// 256 x the sum, the batch with the INT8 group as code of its own).
+// What it adds: an MFMA operand is 16 rows whatever M is, as many bytes returned to registers as
+// the weights.  Here a wavefront copies the M real rows of its batch's activation codes (256
+// bytes per row: four groups) into a region of LDS of its own, four rows per load instruction (SI
+// instructions), and reads its operand from there; rows >= M of the operand repeat row 0.  No
+// barrier: LDS instructions of one wavefront execute in order.
+//
 // `block`: which 16 output channels; `stage`: kStageBytes of LDS, 16-byte aligned.
 // LATE: the activation codes and scales are not ready when the workgroup starts (another workgroup
 // of the same launch writes them): sync.early() runs (a first look whose answer returns before
