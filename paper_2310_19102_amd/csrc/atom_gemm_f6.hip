@@ -60,6 +60,7 @@ typedef _Float16 v4h  __attribute__((ext_vector_type(4)));
 
 constexpr int IMG4 = 6656;                // bytes of an INT4 group image of one unit
 constexpr int IMG8 = 8704;                // bytes of an INT8 group image of one unit
+constexpr int kU8  = 9216;                // pitch of the INT8 images in LDS where they are fetched during the K loop
 constexpr int SC4  = 6144;                // offset of the scales inside an INT4 image
 constexpr int SC8  = 8192;
 
@@ -266,20 +267,18 @@ void w4a4_gemm_f6_kernel(const F6Params p)
     // Instruction k of the request of the first INT8 group, activation part (NA8 instructions) or
     // weight part, into stage `stage`: issued in place of the dummies of two of the last steps,
     // whose stages are free by then, so that the group has landed when the K loop ends.
+    // (Here an image starts on a multiple of kU8 = 9 KB of the stage and is moved by nine
+    // instructions of its own, so that everything but the lane's chunk is the same in all lanes.)
     auto request_int8 = [&](int k, int stage, bool act) __attribute__((always_inline)) {
-        constexpr int NA8 = Gm::NA8, NW8 = Gm::NI8 - Gm::NA8;
         const int j = wave + NWAVE * k;
-        const bool real = j < (act ? NA8 : NW8);
-        int q = 64 * j + lane;                                    // 16-byte chunk within the part
-        const int nq = (act ? WM : 2) * (IMG8 / 16);
-        q = q < nq ? q : nq - 1;
-        int unit = q / (IMG8 / 16);
-        const int off = q - unit * (IMG8 / 16);
+        const bool real = j < 9 * (act ? WM : 2);
+        const int unit = j / 9, jin = j - 9 * unit;               // (uniform)
         const int valid = act ? a_valid : w_valid;
-        unit = unit < valid ? unit : valid - 1;
-        const uint32_t vo = (uint32_t)unit * (uint32_t)p.ustride + 16u * off;
-        const uint32_t mk = 0u - (uint32_t)real;
-        const uint32_t dst = spare + ((lds0 + stage * STAGE + 1024 * j - spare) & mk);
+        const int src_unit = unit < valid ? unit : valid - 1;     // ragged tiles repeat their last unit
+        int chunk = 64 * jin + lane;                              // 16-byte chunk of the image; its last instruction is half empty
+        chunk = chunk < IMG8 / 16 ? chunk : IMG8 / 16 - 1;
+        const uint32_t vo = (uint32_t)src_unit * (uint32_t)p.ustride + 16u * chunk;
+        const uint32_t dst = real ? lds0 + stage * STAGE + unit * kU8 + 1024 * jin : spare;
         dma16(dst, vo, (act ? a_tile : w_tile) + (int64_t)G4 * IMG4);
     };
 
@@ -490,7 +489,7 @@ void w4a4_gemm_f6_kernel(const F6Params p)
     };
     // The last NST steps have nothing of the K loop left to request.  Two of them fetch the first
     // INT8 group instead (its two parts fit a stage each), which then costs no round trip of its own.
-    static_assert(Gm::NA8 <= LPW * NWAVE && Gm::NI8 - Gm::NA8 <= LPW * NWAVE && Gm::NA8 * 1024 <= STAGE, "a part per step and stage");
+    static_assert(9 * WM <= LPW * NWAVE && 9 * 2 <= LPW * NWAVE && WM * kU8 <= STAGE && 2 * kU8 <= STAGE, "a part per step and stage");
     const bool pre8 = p.G8 >= 1 && G4 >= NST;
     int stage8a = 0, stage8w = 0;
     {
@@ -527,8 +526,8 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         __builtin_amdgcn_s_waitcnt(wait_imm(0));                   // the last (dummy) requests of the K loop
         for (int g8 = 0; g8 < p.G8; ++g8) {
             const bool here = pre8 && g8 == 0;                     // requested during the K loop, in two stages
-            const int a_unit8 = (here ? stage8a * STAGE : 0) + wm * IMG8;
-            const int b_unit8 = (here ? stage8w * STAGE : APART8) + wn * IMG8;
+            const int a_unit8 = here ? stage8a * STAGE + wm * kU8 : wm * IMG8;
+            const int b_unit8 = here ? stage8w * STAGE + wn * kU8 : APART8 + wn * IMG8;
             __syncthreads();                                       // every read of the LDS contents so far is done
             if (!here) {
                 const uint8_t *ab = a_tile + (int64_t)G4 * IMG4 + (int64_t)g8 * IMG8;
