@@ -134,7 +134,9 @@ def test_decode_linear_without_index(M, K, N, O, norm):
 @pytest.mark.parametrize("M,K,N", [(1, 4096, 4096), (8, 4096, 11008), (16, 4096, 200), (32, 4096, 4096),
                                    (64, 4096, 1030), (8, 11264, 4090), (3, 1024, 16),
                                    # K/128 = 4 j + 2: the last block is one INT4 group and the INT8 group
-                                   (8, 11008, 4096), (1, 11008, 100), (13, 1280, 48), (32, 11008, 520), (50, 1792, 64)])
+                                   (8, 11008, 4096), (1, 11008, 100), (13, 1280, 48), (32, 11008, 520), (50, 1792, 64),
+                                   # the fused gate/up projection of the benchmark's decode sweep: two rounds of workgroups
+                                   (8, 4096, 22016)])
 def test_decode_gemm_on_tiled_weights_is_bit_identical(M, K, N):
     """Weight codes re-tiled into whole 128-byte lines per load: same arithmetic, same tree, same Y
     as the canonical decode-sized GEMM, which the other tests hold against the oracle; ragged N
