@@ -206,3 +206,32 @@ def test_static_scratch_entry_point_validation():
     assert st(p, 1, 32, 5, 128, 64, p, p, p, p, p, p, p, f, p, None) == 2            # H % Hkv
     assert st(p, 1, 32, 32, 64, 64, p, p, p, p, p, p, p, f, p, None) == 3            # D
     assert st(p, 1, 1024, 64, 128, 1 << 20, p, p, p, p, p, p, p, f, p, None) == 5    # partials beyond the array
+
+
+def test_cooperative_decode_linear_argument_validation():
+    """atom_decode_linear_coop decides every refusal on the host (fake pointers, never dereferenced)."""
+    lib = atom.load_library()
+    D = binding._Desc
+    p = ctypes.c_void_p(0x1000)
+    ok = D(4096, 128, 128, 4, 8)
+    assert lib.atom_decode_linear_coop_sync_bytes() == 4 * (64 + 32 * 32)
+    f = lib.atom_decode_linear_coop
+
+    def call(x=p, M=8, ldx=4096, d=ok, clip=0.9, N=4096, ldy=4096, codes=p, scales=p, sync=p, w_scale=p):
+        return f(x, M, ldx, p, ctypes.c_float(1e-5), p, ctypes.byref(d), ctypes.c_float(clip), p, p, w_scale, N, p, ldy,
+                 codes, codes, scales, sync, None)
+
+    assert call(M=0) == 0                                        # nothing to do
+    assert call(N=0) == 0
+    assert call(M=-1) == 2 and call(ldx=4095) == 2 and call(ldy=4095) == 2
+    assert call(x=None) == 1 and call(sync=None) == 1 and call(codes=None) == 1
+    assert call(codes=ctypes.c_void_p(0x1040)) == 4              # the code arrays own whole 128-byte lines
+    assert call(sync=ctypes.c_void_p(0x1040)) == 4
+    assert call(w_scale=ctypes.c_void_p(0x1004)) == 4
+    assert call(M=17) == 3                                       # more rows than producers
+    assert call(clip=1e-8) == 3
+    assert call(d=D(1408, 128, 128, 4, 8), ldx=1408) == 3        # 11 groups: odd
+    assert call(d=D(768, 128, 128, 4, 8), ldx=768) == 3          # six groups: fewer than wavefronts
+    assert call(d=D(4096, 128, 256, 4, 8)) == 3                  # two INT8 groups
+    assert call(d=D(16384, 128, 128, 4, 8), ldx=16384) == 3      # K beyond the front end of one workgroup
+    assert call(d=D(4096, 64, 128, 4, 8)) == 3                   # group size
