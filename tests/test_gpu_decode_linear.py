@@ -163,3 +163,26 @@ def test_decode_tiled_limits():
     with pytest.raises(atom.AtomError) as e:
         atom.atom_w4a4_gemm_decode_tiled(*qa, t4, t8, gw[2])
     assert e.value.status == 3
+
+
+def test_decode_gemm_random_shapes():
+    """Seeded random decode-sized problems (M 1..64, even group counts 8..30, ragged N): canonical and
+    tiled weights give the same bits wherever both run the decode kernels, and Y is the oracle's within
+    the bar."""
+    rng = np.random.default_rng(2024)
+    for case in range(24):
+        M = int(rng.integers(1, 65))
+        G = int(rng.choice([8, 10, 12, 14, 16, 18, 22, 26, 30]))
+        K = 128 * G
+        N = int(rng.integers(1, 700))
+        print(f"[case] random decode GEMM {case}: M={M} K={K} N={N}", flush=True)
+        lin = _rand_linear(M, K, N, 128, seed=1000 + case, norm=False)
+        gw = gpu_quantize_weight(lin)
+        qa = atom.atom_quantize_act(dev(lin.x), None, 0.0, dev(lin.idx), 128, 128, lin.clip_act)
+        t4, t8 = atom.atom_tile_weight_decode(gw[0], gw[1])
+        y = atom.atom_w4a4_gemm(*qa, *gw)
+        yt = atom.atom_w4a4_gemm_decode_tiled(*qa, t4, t8, gw[2])
+        torch.cuda.synchronize()
+        assert torch.equal(y, yt), f"case {case}: tiled and canonical weights differ"
+        ref = oracle.w4a4_gemm(*ref_quantize_act(lin), *ref_quantize_weight(lin), 128)
+        assert y_rel_err(npy(yt), ref["y"]) <= Y_TOL, f"case {case}"

@@ -133,3 +133,29 @@ def test_coop_decode_linear_strided_and_w3a3():
         assert y_rel_err(npy(ys[:, :72]), ref["y"]) <= Y_TOL
         assert (ys[:, 72:] == 7.0).all(), "columns beyond N were written"
         assert not npy(sync).any()
+
+
+def test_coop_decode_linear_random_shapes():
+    """Seeded random problems (M 1..16, even group counts 8..30, ragged N, with and without norm and
+    index) on one set of counters: Y of the one launch equals Y of the two launches bit for bit."""
+    rng = np.random.default_rng(77)
+    sync = atom.atom_decode_linear_coop_sync()
+    for case in range(24):
+        M = int(rng.integers(1, 17))
+        G = int(rng.choice([8, 10, 12, 14, 16, 18, 22, 26, 30]))
+        K = 128 * G
+        N = int(rng.integers(1, 3000))
+        norm, index = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        print(f"[case] random cooperative decode linear {case}: M={M} K={K} N={N} norm={norm} index={index}", flush=True)
+        lin = _rand_linear(M, K, N, seed=3000 + case, norm=norm)
+        gw = gpu_quantize_weight(lin)
+        idx = dev(lin.idx) if index else None
+        y, codes = atom.atom_decode_linear_coop(dev(lin.x), dev(lin.gamma), lin.eps, idx, *gw, sync, lin.group_size,
+                                                lin.clip_act)
+        qa = atom.atom_quantize_act(dev(lin.x), dev(lin.gamma), lin.eps, idx, lin.group_size, 128, lin.clip_act)
+        y2 = atom.atom_w4a4_gemm(*qa, *gw, lin.group_size)
+        torch.cuda.synchronize()
+        for got, want in zip(codes, qa):
+            assert torch.equal(got, want), f"case {case}: codes"
+        assert torch.equal(y, y2), f"case {case}: Y"
+        assert not npy(sync).any(), f"case {case}: counters"
