@@ -343,12 +343,14 @@ hipError_t launch_tile(const GemmParams &p, hipStream_t stream)
 template <bool DBG>
 hipError_t dispatch(const GemmParams &p, hipStream_t stream)
 {
-    // M <= 64 streams the weights; but from 33 rows on (four row blocks, one workgroup per CU)
-    // and more than 4096 output channels (more than one round of workgroups) a tiled kernel is
-    // the faster one.  Measured with the weights coming from HBM, K = 4096: M = 64, N = 5120
-    // 18.3 us streaming against 15.1 us tiled, N = 8192 19.1 against 15.5, N = 11008 27.5 against
-    // 19.7; at N = 4096 the streaming kernel wins, 10.2 against 14.4.
-    if (!DBG && p.M <= 64 && !(p.M > 32 && p.N > 4096)) return launch_decode(p, stream);
+    // M <= 64 streams the weights.  Outside the common decoding case (one INT8 group, whole blocks
+    // of four groups or two left over, aligned scales: decode_tiled_supported), where the general
+    // streaming kernel runs, a tiled kernel is the faster one from 33 rows on (four row blocks,
+    // one workgroup per CU) and more than 4096 output channels (more than one round of
+    // workgroups).  Measured with the weights coming from HBM, K = 4096, M = 64: N = 5120 18.3 us
+    // general streaming kernel against 15.1 us tiled, N = 8192 19.1 against 15.5, N = 11008 27.5
+    // against 19.7 (the kernels of the common case: 8.3, 9.1 and 15.3 us).
+    if (!DBG && p.M <= 64 && (decode_tiled_supported(p) || !(p.M > 32 && p.N > 4096))) return launch_decode(p, stream);
     // Launches of few tiles are bound by the latency of one tile's chain of K-steps: 64 x 64
     // tiles put every compute unit to work and four (or two) wavefront sets per workgroup split
     // that chain (M = 256, N = K = 4096: 25.7 us on 128 x 128 tiles with two sets).

@@ -34,6 +34,7 @@
 
 #include "atom_gemm_common.h"
 #include "atom_gemm_decode_staged.h"
+#include "atom_launch.h"
 
 namespace {
 
@@ -269,11 +270,20 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
 //     operand rows against the weight scales of the columns, both in k-slot 0: the result has the
 //     layout of the integer tile; a product of two fp16 numbers is exact in fp32), so a lane loads
 //     one 8-byte piece of activation scales per batch and row block, not four.
-template <int RB, bool TILED, int TAIL>
-__global__ __launch_bounds__(NT, RB == 4 ? 2 : 4)     // RB = 2: two workgroups per CU; RB = 4 spills below 146 registers
+//   * CB blocks of 16 output channels per workgroup share the activation operand: what a
+//     workgroup reads of the activations does not depend on how many channels it covers, and with
+//     32 rows and more these reads, all of them hits in the L2, are most of what the L2 delivers
+//     (about 8 TB/s to all CUs together in these kernels, whatever the shape).  The rows come as
+//     whole rows (a load instruction brings four rows of 256 contiguous bytes) and reach the
+//     operand layout through a region of LDS of the wavefront's own, like the rows of the staged
+//     kernel, one row block at a time.
+template <int RB, int CB, bool TILED, int TAIL>
+__global__ __launch_bounds__(NT, RB * CB <= 2 ? 4 : 2)     // 128 registers do for two row blocks of one channel block
 void w4a4_gemm_decode16_kernel(const GemmParams p)
 {
-    __shared__ float red[NW][RB][4][64];      // [slice][row block][register][lane]
+    // per wavefront: 16 staged rows of activation codes (one row block at a time), later its partial sums
+    constexpr int WREG = CB * RB * 1024 > kStageWave ? CB * RB * 1024 : kStageWave;
+    __shared__ __align__(16) unsigned char stage[NW * WREG];
 
     const int tid  = threadIdx.x;
     const int lane = tid & 63;
@@ -282,97 +292,166 @@ void w4a4_gemm_decode16_kernel(const GemmParams p)
 
     const int K4 = p.K - 128, G = p.K >> 7;
     const int M = (int)p.M;
-    const int64_t n0 = (int64_t)blockIdx.x * TN;
+    const int64_t n0 = (int64_t)blockIdx.x * (TN * CB);
     constexpr bool A8 = TAIL == 3;
     const int nblk    = (G + 3) >> 2;
     const int g_begin = 4 * (int)((int64_t)wave * nblk / NW);
     const int g_end   = min(G, 4 * (int)((int64_t)(wave + 1) * nblk / NW));
 
-    int64_t wr = n0 + col;                                // clamped: columns >= N are computed and never stored
-    wr = wr < p.N ? wr : p.N - 1;
     constexpr uint32_t GSTEP = TILED ? 1024u : 64u;
-    const uint32_t w4o = TILED ? (uint32_t)blockIdx.x * (uint32_t)((G - 1) * 1024) + lane * 16 : (uint32_t)(wr * (K4 >> 1)) + kc * 16;
-    const uint32_t w8o = TILED ? (uint32_t)blockIdx.x * 2048u + lane * 16 : (uint32_t)(wr * 128) + kc * 16;
+    const uint32_t nb16 = (uint32_t)((p.N + TN - 1) / TN);
+    uint32_t w4o[CB], w8o[CB], wso[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        int64_t wr = n0 + TN * cb + col;                  // clamped: columns >= N are computed and never stored
+        wr = wr < p.N ? wr : p.N - 1;
+        uint32_t b16 = (uint32_t)blockIdx.x * CB + cb;    // block of 16 channels in the tiled arrays, clamped likewise
+        b16 = b16 < nb16 ? b16 : nb16 - 1;
+        w4o[cb] = TILED ? b16 * (uint32_t)((G - 1) * 1024) + lane * 16 : (uint32_t)(wr * (K4 >> 1)) + kc * 16;
+        w8o[cb] = TILED ? b16 * 2048u + lane * 16 : (uint32_t)(wr * 128) + kc * 16;
+        wso[cb] = (uint32_t)wr * (uint32_t)G;
+    }
     const uint8_t *w8b = reinterpret_cast<const uint8_t *>(p.w_q8), *a8b = reinterpret_cast<const uint8_t *>(p.a_q8);
-    // operand row 16 rb + col of this lane (rows >= M read row 0): codes and scales
-    uint32_t a4o[RB], a8o[RB], aso[RB];
+    // operand row 16 rb + col of this lane (rows >= M read row 0): INT8 codes and scales
+    uint32_t a8o[RB], aso[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const uint32_t ar = 16 * rb + col < M ? 16 * rb + col : 0;
-        a4o[rb] = ar * (uint32_t)(K4 >> 1) + kc * 16;
         a8o[rb] = ar * 128u + kc * 16;
         aso[rb] = ar * (uint32_t)G;
     }
-    const uint32_t wso = (uint32_t)wr * (uint32_t)G;
-
-    float acc[RB][4];
+    // staging of the INT4 activation codes: instruction (rb, i) moves rows 16 rb + 4 i .. + 3, lane -> row
+    // 16 rb + 4 i + kc, 16-byte chunk `col` of the row's 256 bytes (four groups); rows >= M repeat row M - 1
+    uint32_t srow[RB][4];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[rb][e] = 0.0f;
+        for (int i = 0; i < 4; ++i) {
+            const int r = 16 * rb + 4 * i + kc;
+            srow[rb][i] = (uint32_t)(r < M ? r : M - 1) * (uint32_t)(K4 >> 1) + col * 16;
+        }
+    unsigned char *mine = stage + wave * WREG;
+    unsigned char *st_w = mine + kc * kStageRow + col * 16;                    // + 4 i kStageRow
+    const unsigned char *st_r = mine + col * kStageRow + kc * 16;              // + 64 d
+
+    float acc[CB][RB][4];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[cb][rb][e] = 0.0f;
     const v4i   zi = {0, 0, 0, 0};
     const v4f32 zf = {0.0f, 0.0f, 0.0f, 0.0f};
 
     auto batch = [&](int gb, auto has8_c) __attribute__((always_inline)) {
         constexpr bool HAS8 = decltype(has8_c)::value;
-        // every load of the batch is issued before the first is used; the scales first, they are
-        // needed with the first group
+        // Every load of the batch is issued before the first is used, the activation rows first: they
+        // come from the L2, the weights from HBM, and loads return in order.  In the batch with the
+        // INT8 group the chunks of a row past the INT4 groups repeat the last one.
         constexpr int NG4 = HAS8 ? TAIL : 4;               // INT4 groups of the batch
-        uint2 wvs = load_scales<A8>(p.w_scale, wso, gb, G);
+        // (named registers, not an array: the array stayed in scratch memory)
+        uint4 s00, s01, s02, s03, s10, s11, s12, s13, s20, s21, s22, s23, s30, s31, s32, s33;
+        const uint32_t back = HAS8 && col >= 4 * NG4 ? (uint32_t)(col - (4 * NG4 - 1)) * 16u : 0u;
+        auto stage_load = [&](int rb, int i) __attribute__((always_inline)) {
+            return *reinterpret_cast<const uint4 *>(p.a_q4 + (srow[rb][i] + (uint32_t)gb * 64u - back));
+        };
+        s00 = stage_load(0, 0); s01 = stage_load(0, 1); s02 = stage_load(0, 2); s03 = stage_load(0, 3);
+        s10 = stage_load(1, 0); s11 = stage_load(1, 1); s12 = stage_load(1, 2); s13 = stage_load(1, 3);
+        if constexpr (RB > 2) {
+            s20 = stage_load(2, 0); s21 = stage_load(2, 1); s22 = stage_load(2, 2); s23 = stage_load(2, 3);
+            s30 = stage_load(3, 0); s31 = stage_load(3, 1); s32 = stage_load(3, 2); s33 = stage_load(3, 3);
+        }
         uint2 avs[RB];
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) avs[rb] = load_scales<A8>(p.a_scale, aso[rb], gb, G);
-        uint4 wq[4], aq[4][RB], wx, ax[RB];
-#pragma unroll
-        for (int d = 0; d < NG4; ++d) {
-            wq[d] = *reinterpret_cast<const uint4 *>(p.w_q4 + (w4o + (uint32_t)(gb + d) * GSTEP));
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-                aq[d][rb] = *reinterpret_cast<const uint4 *>(p.a_q4 + (a4o[rb] + (uint32_t)(gb + d) * 64u));
-        }
+        uint4 a8lo[RB], a8hi[RB];
         if constexpr (HAS8) {
-            wq[TAIL] = *reinterpret_cast<const uint4 *>(w8b + w8o);
-            wx       = *reinterpret_cast<const uint4 *>(w8b + (w8o + GSTEP));
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                aq[TAIL][rb] = *reinterpret_cast<const uint4 *>(a8b + a8o[rb]);
-                ax[rb]       = *reinterpret_cast<const uint4 *>(a8b + (a8o[rb] + 64u));
+                a8lo[rb] = *reinterpret_cast<const uint4 *>(a8b + a8o[rb]);
+                a8hi[rb] = *reinterpret_cast<const uint4 *>(a8b + (a8o[rb] + 64u));
+            }
+        }
+        // (keeps the activation rows ahead of the weights in the order of the requests)
+        __builtin_amdgcn_sched_barrier(0);
+        uint2 wvs[CB];
+        uint4 wq[CB][4], wx[CB];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            wvs[cb] = load_scales<A8>(p.w_scale, wso[cb], gb, G);
+#pragma unroll
+            for (int d = 0; d < NG4; ++d) wq[cb][d] = *reinterpret_cast<const uint4 *>(p.w_q4 + (w4o[cb] + (uint32_t)(gb + d) * GSTEP));
+            if constexpr (HAS8) {
+                wq[cb][TAIL] = *reinterpret_cast<const uint4 *>(w8b + w8o[cb]);
+                wx[cb]       = *reinterpret_cast<const uint4 *>(w8b + (w8o[cb] + GSTEP));
             }
         }
         // (the fence keeps the loads here: left alone the compiler spreads them between the MFMAs
         // to save registers, which turns one memory round trip per batch into several)
         __builtin_amdgcn_sched_barrier(0);
+        // one row block at a time through the wavefront's region (LDS instructions of a wavefront
+        // execute in order: the next block's writes come after this block's reads)
+        uint4 aq[RB][4];
+        auto through_lds = [&](auto rbc, const uint4 &r0, const uint4 &r1, const uint4 &r2, const uint4 &r3) __attribute__((always_inline)) {
+            constexpr int rb = decltype(rbc)::value;
+            *reinterpret_cast<uint4 *>(st_w)                  = r0;
+            *reinterpret_cast<uint4 *>(st_w + 4 * kStageRow)  = r1;
+            *reinterpret_cast<uint4 *>(st_w + 8 * kStageRow)  = r2;
+            *reinterpret_cast<uint4 *>(st_w + 12 * kStageRow) = r3;
+#pragma unroll
+            for (int d = 0; d < NG4; ++d) aq[rb][d] = *reinterpret_cast<const uint4 *>(st_r + 64 * d);
+        };
+        through_lds(std::integral_constant<int, 0>(), s00, s01, s02, s03);
+        through_lds(std::integral_constant<int, 1>(), s10, s11, s12, s13);
+        if constexpr (RB > 2) {
+            through_lds(std::integral_constant<int, 2>(), s20, s21, s22, s23);
+            through_lds(std::integral_constant<int, 3>(), s30, s31, s32, s33);
+        }
         if (kc != 0) {                                    // k-slots 4 .. 15 of the scale MFMA stay empty
-            wvs = make_uint2(0, 0);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) avs[rb] = make_uint2(0, 0);
         }
+        // (what needs the weights stays behind what does not)
+        __builtin_amdgcn_sched_barrier(0);
+        if (kc != 0) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) wvs[cb] = make_uint2(0, 0);
+        }
 
-        auto int4_group = [&](const uint4 &w, const uint4 (&a)[RB], auto dc) __attribute__((always_inline)) {
+        auto int4_group = [&](auto dc) __attribute__((always_inline)) {
             constexpr int D = decltype(dc)::value;
-            const v4i b0 = widen_lo(w), b1 = widen_hi(w);
+            v4i b0[CB], b1[CB];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) { b0[cb] = widen_lo(wq[cb][D]); b1[cb] = widen_hi(wq[cb][D]); }
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(widen_lo(a[rb]), b0, zi, 0, 0, 0);
-                c = __builtin_amdgcn_mfma_i32_16x16x64_i8(widen_hi(a[rb]), b1, c, 0, 0, 0);
-                const v4f32 sc = __builtin_amdgcn_mfma_f32_16x16x16f16(scale_operand<D>(avs[rb]), scale_operand<D>(wvs), zf, 0, 0, 0);
+                const v4i x0 = widen_lo(aq[rb][D]), x1 = widen_hi(aq[rb][D]);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[rb][e] = fmaf((float)c[e], sc[e], acc[rb][e]);
+                for (int cb = 0; cb < CB; ++cb) {
+                    v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(x0, b0[cb], zi, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_i32_16x16x64_i8(x1, b1[cb], c, 0, 0, 0);
+                    const v4f32 sc = __builtin_amdgcn_mfma_f32_16x16x16f16(scale_operand<D>(avs[rb]), scale_operand<D>(wvs[cb]), zf, 0, 0, 0);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[cb][rb][e] = fmaf((float)c[e], sc[e], acc[cb][rb][e]);
+                }
             }
         };
-        int4_group(wq[0], aq[0], std::integral_constant<int, 0>());
-        if constexpr (NG4 > 1) int4_group(wq[1], aq[1], std::integral_constant<int, 1>());
-        if constexpr (NG4 > 2) int4_group(wq[2], aq[2], std::integral_constant<int, 2>());
-        if constexpr (NG4 > 3) int4_group(wq[3], aq[3], std::integral_constant<int, 3>());
+        int4_group(std::integral_constant<int, 0>());
+        if constexpr (NG4 > 1) int4_group(std::integral_constant<int, 1>());
+        if constexpr (NG4 > 2) int4_group(std::integral_constant<int, 2>());
+        if constexpr (NG4 > 3) int4_group(std::integral_constant<int, 3>());
         if constexpr (HAS8) {
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, aq[TAIL][rb]), __builtin_bit_cast(v4i, wq[TAIL]), zi, 0, 0, 0);
-                c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, ax[rb]), __builtin_bit_cast(v4i, wx), c, 0, 0, 0);
-                const v4f32 sc = __builtin_amdgcn_mfma_f32_16x16x16f16(scale_operand<TAIL>(avs[rb]), scale_operand<TAIL>(wvs), zf, 0, 0, 0);
+            for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[rb][e] = fmaf((float)c[e], 256.0f * sc[e], acc[rb][e]);
-            }
+                for (int cb = 0; cb < CB; ++cb) {
+                    v4i c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, a8lo[rb]), __builtin_bit_cast(v4i, wq[cb][TAIL]), zi, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(v4i, a8hi[rb]), __builtin_bit_cast(v4i, wx[cb]), c, 0, 0, 0);
+                    const v4f32 sc = __builtin_amdgcn_mfma_f32_16x16x16f16(scale_operand<TAIL>(avs[rb]), scale_operand<TAIL>(wvs[cb]), zf, 0, 0, 0);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[cb][rb][e] = fmaf((float)c[e], 256.0f * sc[e], acc[cb][rb][e]);
+                }
         }
     };
 
@@ -380,19 +459,23 @@ void w4a4_gemm_decode16_kernel(const GemmParams p)
     for (int gb = g_begin; gb < g_plain; gb += 4) batch(gb, std::false_type());
     if (wave == NW - 1) batch(G - (TAIL + 1), std::true_type());
 
-    // the eight K-slices meet in LDS and are added in slice order
+    // the eight K-slices meet in LDS (each wavefront's region, its operand reads are complete) and
+    // are added in slice order
+    float *red = reinterpret_cast<float *>(mine);        // [channel block][row block][register][lane]
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+    for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) red[wave][rb][e][lane] = acc[rb][e] * (1.0f / 256.0f);
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) red[((cb * RB + rb) * 4 + e) * 64 + lane] = acc[cb][rb][e] * (1.0f / 256.0f);
     __syncthreads();
-    for (int idx = tid; idx < RB * 4 * 64; idx += NT) {
-        const int l = idx & 63, e = (idx >> 6) & 3, rb = idx >> 8;
+    for (int idx = tid; idx < CB * RB * 4 * 64; idx += NT) {
+        const int l = idx & 63, e = (idx >> 6) & 3, rb = (idx >> 8) % RB, cb = (idx >> 8) / RB;
         float s = 0.0f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) s += red[w][rb][e][l];
+        for (int w = 0; w < NW; ++w) s += reinterpret_cast<const float *>(stage + w * WREG)[idx];
         const int64_t m = 16 * rb + 4 * (l >> 4) + e;
-        const int64_t n = n0 + (l & 15);
+        const int64_t n = n0 + TN * cb + (l & 15);
         if (m < p.M && n < p.N) p.y[m * p.ldy + n] = __half_as_ushort(__float2half_rn(s));
     }
 }
@@ -413,8 +496,14 @@ void launch_common(const GemmParams &p, unsigned blocks, hipStream_t stream)
     if (p.M <= 4)       hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<1, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
     else if (p.M <= 8)  hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<2, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
     else if (p.M <= 16) hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<4, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
-    else if (p.M <= 32) hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<2, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
-    else                hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
+    else if (p.M <= 32) hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<2, 1, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
+    // Four row blocks: two channel blocks per workgroup once there is more than one block of 16
+    // channels per CU.  M = 64, K = 4096, weights from HBM: N = 4096 6.6 us with one, 8.2 us with two;
+    // N = 5120 10.9 / 8.3; N = 8192 11.5 / 9.1; N = 11008 16.2 / 15.3; N = 22016 30.8 / 23.7.
+    else if ((int)blocks <= atom_launch::compute_units())
+        hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, 1, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
+    else
+        hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, 2, TILED, TAIL>), dim3((blocks + 1) / 2), dim3(NT), 0, stream, p);
 }
 
 // Re-tiling of the canonical weight codes for the TILED variants: one workgroup per block of 16

@@ -136,7 +136,10 @@ def test_decode_linear_without_index(M, K, N, O, norm):
                                    # K/128 = 4 j + 2: the last block is one INT4 group and the INT8 group
                                    (8, 11008, 4096), (1, 11008, 100), (13, 1280, 48), (32, 11008, 520), (50, 1792, 64),
                                    # the fused gate/up projection of the benchmark's decode sweep: two rounds of workgroups
-                                   (8, 4096, 22016)])
+                                   (8, 4096, 22016),
+                                   # more than 32 rows and more blocks of 16 channels than CUs: two channel blocks per
+                                   # workgroup; an odd number of blocks, a ragged last block, both kinds of last batch
+                                   (64, 1024, 4112), (40, 1280, 4200), (33, 4096, 11008)])
 def test_decode_gemm_on_tiled_weights_is_bit_identical(M, K, N):
     """Weight codes re-tiled into whole 128-byte lines per load: same arithmetic, same tree, same Y
     as the canonical decode-sized GEMM, which the other tests hold against the oracle; ragged N

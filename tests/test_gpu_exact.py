@@ -68,12 +68,14 @@ def _run(pr, asc, wsc, packed=None, out=None):
 
 # M, K, N, O, what the dispatcher picks
 SHAPES = [
-    (8, 4096, 4096, 128, "decode <1, vector scales, one INT8 group, aligned blocks of four>"),
-    (8, 11008, 4096, 128, "decode <1, vector scales, one INT8 group>: 86 groups"),
-    (32, 4096, 4096, 128, "decode <2, ..., aligned>"),
-    (32, 11008, 4096, 128, "decode <2, ...>: 86 groups"),
-    (64, 4096, 4096, 128, "decode <4, ..., aligned>"),
-    (64, 11008, 4096, 128, "decode <4, ...>: 86 groups"),
+    (8, 4096, 4096, 128, "decode, staged rows <2 staging instructions>, whole blocks of four groups"),
+    (8, 11008, 4096, 128, "decode, staged rows: 86 groups (two left over)"),
+    (32, 4096, 4096, 128, "decode <2 row blocks, 1 channel block>"),
+    (32, 11008, 4096, 128, "decode <2 row blocks, 1 channel block>: 86 groups"),
+    (64, 4096, 4096, 128, "decode <4 row blocks, 1 channel block>"),
+    (64, 11008, 4096, 128, "decode <4 row blocks, 1 channel block>: 86 groups"),
+    (64, 4096, 11008, 128, "decode <4 row blocks, 2 channel blocks>"),
+    (48, 1792, 4112, 128, "decode <4 row blocks, 2 channel blocks>: 14 groups, an odd number of channel blocks"),
     (8, 768, 64, 256, "decode <1, vector scales> with two INT8 groups"),
     (8, 1408, 64, 128, "decode <1, 2-byte scale loads>: 11 groups"),
     (24, 1408, 64, 128, "decode <2, 2-byte scale loads>"),
