@@ -34,6 +34,19 @@
 // that forms the 32 x 32 tile of scale products a_scale[m] * w_scale[n] (rank 1, exact in fp32),
 // then 16 fused multiply-adds per lane.  Groups are added in ascending order, the INT8 group(s)
 // last, each by one fmaf: the accumulation chain of the definition.
+//
+// PERSIST (256-row tiles, one INT8 group, at least as many tiles as CUs): one workgroup per CU walks
+// its share of the tiles, and the stream of requests never stops at a tile's end.  The K loop's last
+// two steps, which have nothing of their own tile left to ask for, request groups 0 and 1 of the
+// next tile into the stages they have just freed; the INT8 group sits in the other two stages,
+// which afterwards hold the output staging areas and then, behind one barrier, the next tile's
+// groups 2 and 3.  The next tile starts with its first group long in LDS: no burst of four groups'
+// requests, no round trip to memory, no wait for another workgroup to be launched.  Same sums in
+// the same order as the one-tile kernel.  The waits count instructions (vmcnt returns in order),
+// so what lies between the requests of a tile's groups 3 and 4 is kept at exactly eight
+// vector-memory instructions: the eight 16-byte stores of the tile before, or eight dummy
+// requests (first tile; a wavefront whose part of the tile is cut by M or N stores first,
+// conditionally, and waits for all of it).
 
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
@@ -197,7 +210,7 @@ struct F6Geom {
     static constexpr int LDS   = LDS0 > OUT ? LDS0 : OUT;
 };
 
-template <int WM, bool DBG>
+template <int WM, bool DBG, bool PERSIST = false>
 __global__ __launch_bounds__(WM * 128, 2)
 void w4a4_gemm_f6_kernel(const F6Params p)
 {
@@ -216,19 +229,58 @@ void w4a4_gemm_f6_kernel(const F6Params p)
     // tile of this workgroup: M-tiles fastest, in bands of up to eight M-tiles so that the tiles an
     // XCD works on at one time share both activation and weight units in its L2
     const int TM = (p.a_units + WM - 1) / WM, TN = (p.w_units + 1) / 2;
-    int tm, tn;
-    {
-        const int logical = xcd_contiguous_block_id();
-        const int band = 8 * TN, b = logical / band, rem = logical - b * band;
-        const int hgt = TM - 8 * b < 8 ? TM - 8 * b : 8;          // M-tiles in this band
-        tm = 8 * b + rem % hgt;
-        tn = rem / hgt;
+    // PERSIST: a workgroup walks tiles logical, logical + lstep, ... < lend of its XCD's contiguous share
+    int logical, lstep = 1, lend;
+    if constexpr (PERSIST) {
+        const int ntiles = TM * TN, nb = gridDim.x, xcd = blockIdx.x & 7;
+        const int per = ntiles >> 3, rem = ntiles & 7;
+        const int start = xcd * per + (xcd < rem ? xcd : rem);
+        logical = start + (int)(blockIdx.x >> 3);
+        lstep   = (nb - xcd + 7) >> 3;
+        lend    = start + per + (xcd < rem ? 1 : 0);
+    } else {
+        logical = xcd_contiguous_block_id();
+        lend    = logical + 1;
     }
-    const int au0 = tm * WM, wu0 = tn * 2;
-    const int a_valid = p.a_units - au0 < WM ? p.a_units - au0 : WM;
-    const int w_valid = p.w_units - wu0 < 2 ? p.w_units - wu0 : 2;
-    const uint8_t *a_tile = p.a_pk + (int64_t)au0 * p.ustride;
-    const uint8_t *w_tile = p.w_pk + (int64_t)wu0 * p.ustride;
+    constexpr int LPWc = Gm::LPW;
+    struct Tile {
+        int a_valid, w_valid;
+        const uint8_t *a_tile, *w_tile;
+        int64_t m_w, n_w;
+        uint32_t voff[LPWc];
+    };
+    // (the lane number as the per-tile code sees it: made opaque once per tile, so that what is
+    // derived from it is recomputed there and does not hold registers through the K loop)
+    int lane_t = lane;
+    auto tile_of = [&](int lt) __attribute__((always_inline)) -> Tile {
+        Tile t;
+        const int band = 8 * TN, b = lt / band, rem = lt - b * band;
+        const int hgt = TM - 8 * b < 8 ? TM - 8 * b : 8;          // M-tiles in this band
+        const int tm = 8 * b + rem % hgt, tn = rem / hgt;
+        const int au0 = tm * WM, wu0 = tn * 2;
+        t.a_valid = p.a_units - au0 < WM ? p.a_units - au0 : WM;
+        t.w_valid = p.w_units - wu0 < 2 ? p.w_units - wu0 : 2;
+        t.a_tile = p.a_pk + (int64_t)au0 * p.ustride;
+        t.w_tile = p.w_pk + (int64_t)wu0 * p.ustride;
+        t.m_w = (int64_t)au0 * 64 + wm * 64;
+        t.n_w = (int64_t)wu0 * 64 + wn * 64;
+#pragma unroll
+        for (int k = 0; k < LPW; ++k) {
+            const int j0 = wave + NWAVE * k, j = j0 < NI ? j0 : wave;
+            const bool isa = j < NA;
+            int q = 64 * (isa ? j : j - NA) + lane_t;             // 16-byte chunk within the part
+            const int nq = (isa ? WM : 2) * (IMG4 / 16);
+            q = q < nq ? q : nq - 1;
+            int unit = q / (IMG4 / 16);
+            const int off = q - unit * (IMG4 / 16);
+            const int valid = isa ? t.a_valid : t.w_valid;
+            unit = unit < valid ? unit : valid - 1;               // ragged tiles repeat their last unit
+            t.voff[k] = (uint32_t)unit * (uint32_t)p.ustride + 16u * off;
+        }
+        return t;
+    };
+    Tile T = tile_of(logical), Tn = T;
+    uint32_t more_mask = 0;
 
     // ---- loader: DMA instruction j of a stage fills LDS bytes [1024 j, 1024 j + 1024) of the
     // stage; j < NA: activation units, else weight units.  Wavefront w issues j = w, w + NWAVE, ...
@@ -236,20 +288,6 @@ void w4a4_gemm_f6_kernel(const F6Params p)
     // Every wavefront issues LPW instructions per stage, so that the waits below are the same
     // immediate in every wavefront and no branch sits inside a K-step: a wavefront without an
     // LPW-th block repeats its first block into a spare kilobyte that nobody reads.
-    uint32_t voff[LPW];
-#pragma unroll
-    for (int k = 0; k < LPW; ++k) {
-        const int j0 = wave + NWAVE * k, j = j0 < NI ? j0 : wave;
-        const bool isa = j < NA;
-        int q = 64 * (isa ? j : j - NA) + lane;                   // 16-byte chunk within the part
-        const int nq = (isa ? WM : 2) * (IMG4 / 16);
-        q = q < nq ? q : nq - 1;
-        int unit = q / (IMG4 / 16);
-        const int off = q - unit * (IMG4 / 16);
-        const int valid = isa ? a_valid : w_valid;
-        unit = unit < valid ? unit : valid - 1;                   // ragged tiles repeat their last unit
-        voff[k] = (uint32_t)unit * (uint32_t)p.ustride + 16u * off;
-    }
     const uint32_t vzero = 0;
     const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem), spare = lds0 + Gm::SPARE;
     // instruction k of the request of group v into stage `stage`
@@ -258,12 +296,20 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         // (selected with a mask, not with ?: -- the compiler turns that into a branch)
         const uint32_t mk = NWAVE * (k + 1) <= NI ? ~0u : 0u - (uint32_t)(j0 < NI);
         const uint32_t dst = spare + ((lds0 + stage * STAGE + 1024 * j - spare) & mk);
-        dma16(dst, voff[k], (j < NA ? a_tile : w_tile) + (int64_t)v * IMG4);
+        dma16(dst, T.voff[k], (j < NA ? T.a_tile : T.w_tile) + (int64_t)v * IMG4);
+    };
+    // the same for group v of the workgroup's next tile (nothing real when there is none: the
+    // current tile's bytes go to the spare kilobyte)
+    auto request_next = [&](int k, int v, int stage) __attribute__((always_inline)) {
+        const int j0 = wave + NWAVE * k, j = j0 < NI ? j0 : wave;
+        const uint32_t mk = (NWAVE * (k + 1) <= NI ? ~0u : 0u - (uint32_t)(j0 < NI)) & more_mask;
+        const uint32_t dst = spare + ((lds0 + stage * STAGE + 1024 * j - spare) & mk);
+        dma16(dst, Tn.voff[k], (j < NA ? Tn.a_tile : Tn.w_tile) + (int64_t)v * IMG4);
     };
     // Past the last INT4 group the same number of instructions is issued, so that the count a wait
     // refers to never changes: every lane reads the tile's first 16 bytes (one cache line per
     // instruction) into the spare kilobyte.
-    auto request_dummy = [&]() __attribute__((always_inline)) { dma16(spare, vzero, a_tile); };
+    auto request_dummy = [&]() __attribute__((always_inline)) { dma16(spare, vzero, T.a_tile); };
     // Instruction k of the request of the first INT8 group, activation part (NA8 instructions) or
     // weight part, into stage `stage`: issued in place of the dummies of two of the last steps,
     // whose stages are free by then, so that the group has landed when the K loop ends.
@@ -273,13 +319,13 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         const int j = wave + NWAVE * k;
         const bool real = j < 9 * (act ? WM : 2);
         const int unit = j / 9, jin = j - 9 * unit;               // (uniform)
-        const int valid = act ? a_valid : w_valid;
+        const int valid = act ? T.a_valid : T.w_valid;
         const int src_unit = unit < valid ? unit : valid - 1;     // ragged tiles repeat their last unit
-        int chunk = 64 * jin + lane;                              // 16-byte chunk of the image; its last instruction is half empty
+        int chunk = 64 * jin + lane_t;                            // 16-byte chunk of the image; its last instruction is half empty
         chunk = chunk < IMG8 / 16 ? chunk : IMG8 / 16 - 1;
         const uint32_t vo = (uint32_t)src_unit * (uint32_t)p.ustride + 16u * chunk;
         const uint32_t dst = real ? lds0 + stage * STAGE + unit * kU8 + 1024 * jin : spare;
-        dma16(dst, vo, (act ? a_tile : w_tile) + (int64_t)G4 * IMG4);
+        dma16(dst, vo, (act ? T.a_tile : T.w_tile) + (int64_t)G4 * IMG4);
     };
 
     // ---- fragment addresses: one register per operand (and one per operand for the scales) holds
@@ -308,13 +354,10 @@ void w4a4_gemm_f6_kernel(const F6Params p)
 
     v16f acc[4];
     const v16f zf = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-    for (int t = 0; t < 4; ++t) acc[t] = zf;
 
     auto scale_tile = [&](v2u ta, v2u tb) __attribute__((always_inline)) -> v16f {
         return __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_bit_cast(v4h, ta), __builtin_bit_cast(v4h, tb), zf, 0, 0, 0);
     };
-    const int64_t m_w = (int64_t)au0 * 64 + wm * 64, n_w = (int64_t)wu0 * 64 + wn * 64;
     // steps 2 and 3 for elements e0 .. e1-1 of sub-tile (i, j) of group grp
     auto dequant = [&](int grp, int i, int j, const v16f &c, const v16f &s, int e0, int e1) __attribute__((always_inline)) {
 #pragma unroll
@@ -322,37 +365,66 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         if (DBG && grp >= 0) {
 #pragma unroll
             for (int e = e0; e < e1; ++e) {
-                const int64_t m = m_w + 32 * i + 8 * (e >> 2) + 4 * g + (e & 3), n = n_w + 32 * j + r;
+                const int64_t m = T.m_w + 32 * i + 8 * (e >> 2) + 4 * g + (e & 3), n = T.n_w + 32 * j + r;
                 if (m < p.M && n < p.N) p.partials[(m * p.N + n) * (p.G4 + p.G8) + grp] = (int32_t)c[e];
             }
         }
     };
 
-    // ---- prologue: the first NST groups are requested, the first one has landed
-#pragma unroll
-    for (int v = 0; v < NST; ++v) {
-        if (v < G4) {
-#pragma unroll
-            for (int k = 0; k < LPW; ++k) request_one(k, v, v);
-        } else {
-#pragma unroll
-            for (int k = 0; k < LPW; ++k) request_dummy();
-        }
+    // PERSIST: extra vector-memory instructions that stand between the requests of groups 3 and 4
+    // of a tile: the eight stores of the tile before (the first tile: eight dummy requests)
+    constexpr int XTRA = PERSIST ? 8 : 0;
+    int base = 0;                               // stage of the current tile's group 0
+    bool first = true;
+    v12i af0, bf0;
+    v2u sa[2], sb[2];
+    v16f c_pend, s_pend;
+    int  u_pend;
+    int cur;
+    uint32_t a_cur, b_cur;
+    for (;;) {
+    if constexpr (PERSIST) {
+        int tz = 0;
+        asm volatile("" : "+s"(tz));
+        lane_t = lane + tz;
+        const int nlogical = logical + lstep;
+        const bool more = nlogical < lend;
+        more_mask = more ? ~0u : 0u;
+        Tn = tile_of(more ? nlogical : logical);
     }
-    __builtin_amdgcn_s_waitcnt(wait_imm((NST - 1) * LPW));
+    // ---- prologue: the first NST groups are requested (a later tile of a persistent workgroup: they
+    // were, by the tile before), the first one has landed
+    if (first) {
+#pragma unroll
+        for (int v = 0; v < NST; ++v) {
+            if (v < G4) {
+#pragma unroll
+                for (int k = 0; k < LPW; ++k) request_one(k, v, v);
+            } else {
+#pragma unroll
+                for (int k = 0; k < LPW; ++k) request_dummy();
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < XTRA; ++k) request_dummy();
+        first = false;
+    }
+    __builtin_amdgcn_s_waitcnt(wait_imm((NST - 1) * LPW + XTRA));
     __syncthreads();
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = zf;
+    cur = base; a_cur = a_off + base * STAGE; b_cur = b_off + base * STAGE;
     // carried from step to step: the fragments of sub-tile row 0 / column 0 and the scale operands of
     // the coming step, and the integer and scale tiles of the last sub-tile of the step before
-    v12i af0 = read_pair(a_off, 0), bf0 = read_pair(b_off, 0);
-    v2u sa[2], sb[2];
+    af0 = read_pair(a_cur, 0); bf0 = read_pair(b_cur, 0);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        sa[i] = read_scale(sa_off, i);
-        sb[i] = read_scale(sb_off, i);
+        sa[i] = read_scale(sa_off + base * STAGE, i);
+        sb[i] = read_scale(sb_off + base * STAGE, i);
         sb[i][0] = g == 0 ? sb[i][0] : 0u;     // zero on one side keeps k-slots 4..7 of the fp16 MFMA empty
     }
-    v16f c_pend = zf, s_pend = zf;
-    int  u_pend = -1;
+    c_pend = zf; s_pend = zf;
+    u_pend = -1;
 
     // One K-step = one INT4 group.  Twelve slots of one MFMA each, fenced so that the compiler keeps
     // their order.  Sub-tiles in the order (0,0) (1,0) (0,1) (1,1): column fragments 0 are free after
@@ -367,11 +439,13 @@ void w4a4_gemm_f6_kernel(const F6Params p)
     // three slots: issued in one burst the requests fill the address queue and hold up MFMAs.
     // A step has no branch (one inside it lets the compiler sink MFMAs past the barrier): MODE says
     // at compile time what the step requests: 0 group u + NST, 1 nothing (dummies), 2 / 3 the
-    // activation / weight part of the first INT8 group.
-    int cur = 0;                                // stage of group u
-    uint32_t a_cur = a_off, b_cur = b_off;      // lane addresses in stage `cur`
-    auto step = [&](int u, auto mode_c) __attribute__((always_inline)) {
+    // activation / weight part of the first INT8 group, 4 / 5 group 0 / 1 of the next tile; LOOSE
+    // how many vector-memory instructions beside the requests of two groups may be outstanding at
+    // the step's wait (the first three steps of a tile of a persistent workgroup: the eight that
+    // stand between groups 3 and 4).
+    auto step = [&](int u, auto mode_c, auto loose_c) __attribute__((always_inline)) {
         constexpr int MODE = decltype(mode_c)::value;
+        constexpr int LOOSE = decltype(loose_c)::value;
         const int nxt = cur + 1 == NST ? 0 : cur + 1;
         // lane addresses in the next stage (they become the current ones of the next step)
         const uint32_t a_nxt = a_off + nxt * STAGE, b_nxt = b_off + nxt * STAGE;
@@ -387,6 +461,8 @@ void w4a4_gemm_f6_kernel(const F6Params p)
                     if constexpr (MODE == 0)      request_one(kreq, u + NST, cur);
                     else if constexpr (MODE == 2) request_int8(kreq, cur, true);
                     else if constexpr (MODE == 3) request_int8(kreq, cur, false);
+                    else if constexpr (MODE == 4) request_next(kreq, 0, cur);
+                    else if constexpr (MODE == 5) request_next(kreq, 1, cur);
                     else                          request_dummy();
                 }
             }
@@ -412,7 +488,7 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         dequant(u_pend, 1, 1, c_pend, s_pend, 8, 16);
         ATOM_F6_PIN(acc[3]);
         ATOM_F6_SLOT_END();
-        __builtin_amdgcn_s_waitcnt(wait_imm((NST - 2) * LPW));
+        __builtin_amdgcn_s_waitcnt(wait_imm((NST - 2) * LPW + LOOSE));
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
         // slot 3
@@ -493,13 +569,22 @@ void w4a4_gemm_f6_kernel(const F6Params p)
     const bool pre8 = p.G8 >= 1 && G4 >= NST;
     int stage8a = 0, stage8w = 0;
     {
+        using std::integral_constant;
         int u = 0;
-        for (; u + NST < G4; ++u) step(u, std::integral_constant<int, 0>{});
-        if (pre8) {
-            stage8a = cur; step(u++, std::integral_constant<int, 2>{});
-            stage8w = cur; step(u++, std::integral_constant<int, 3>{});
+        if constexpr (PERSIST) {                // (G4 >= NST + 3: the launcher sees to it)
+            for (; u < 3; ++u) step(u, integral_constant<int, 0>{}, integral_constant<int, XTRA>{});
         }
-        for (; u < G4; ++u) step(u, std::integral_constant<int, 1>{});
+        for (; u + NST < G4; ++u) step(u, integral_constant<int, 0>{}, integral_constant<int, 0>{});
+        if (pre8) {
+            stage8a = cur; step(u++, integral_constant<int, 2>{}, integral_constant<int, 0>{});
+            stage8w = cur; step(u++, integral_constant<int, 3>{}, integral_constant<int, 0>{});
+        }
+        if constexpr (PERSIST) {
+            step(u++, integral_constant<int, 4>{}, integral_constant<int, 0>{});
+            step(u++, integral_constant<int, 5>{}, integral_constant<int, 0>{});
+        } else {
+            for (; u < G4; ++u) step(u, integral_constant<int, 1>{}, integral_constant<int, 0>{});
+        }
     }
     dequant(u_pend, 1, 1, c_pend, s_pend, 0, 16);
 
@@ -511,27 +596,28 @@ void w4a4_gemm_f6_kernel(const F6Params p)
         for (int k = 0; k < LPW8; ++k) {
             const int j = wave + NWAVE * k;
             const bool isa = j < NA8;
-            int q = 64 * (isa ? j : j - NA8) + lane;
+            int q = 64 * (isa ? j : j - NA8) + lane_t;
             const int nq = (isa ? WM : 2) * (IMG8 / 16);
             q = q < nq ? q : nq - 1;
             int unit = q / (IMG8 / 16);
             const int off = q - unit * (IMG8 / 16);
-            const int valid = isa ? a_valid : w_valid;
+            const int valid = isa ? T.a_valid : T.w_valid;
             unit = unit < valid ? unit : valid - 1;
             voff8[k] = (uint32_t)unit * (uint32_t)p.ustride + 16u * off;
         }
         int ck[4];                                                 // byte offset of chunk 2 kk + g of row r
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) ck[kk] = 128 * r + 16 * (((2 * kk + g) ^ r ^ ((r >> 3) & 1)) & 7);
-        __builtin_amdgcn_s_waitcnt(wait_imm(0));                   // the last (dummy) requests of the K loop
+        for (int kk = 0; kk < 4; ++kk) ck[kk] = 128 * (lane_t & 31) + 16 * (((2 * kk + (lane_t >> 5)) ^ (lane_t & 31) ^ (((lane_t & 31) >> 3) & 1)) & 7);
+        // the requests of the K loop's last steps (PERSIST: all but the next tile's two groups)
+        __builtin_amdgcn_s_waitcnt(wait_imm(PERSIST ? 2 * LPW : 0));
         for (int g8 = 0; g8 < p.G8; ++g8) {
             const bool here = pre8 && g8 == 0;                     // requested during the K loop, in two stages
             const int a_unit8 = here ? stage8a * STAGE + wm * kU8 : wm * IMG8;
             const int b_unit8 = here ? stage8w * STAGE + wn * kU8 : APART8 + wn * IMG8;
             __syncthreads();                                       // every read of the LDS contents so far is done
             if (!here) {
-                const uint8_t *ab = a_tile + (int64_t)G4 * IMG4 + (int64_t)g8 * IMG8;
-                const uint8_t *wb = w_tile + (int64_t)G4 * IMG4 + (int64_t)g8 * IMG8;
+                const uint8_t *ab = T.a_tile + (int64_t)G4 * IMG4 + (int64_t)g8 * IMG8;
+                const uint8_t *wb = T.w_tile + (int64_t)G4 * IMG4 + (int64_t)g8 * IMG8;
 #pragma unroll
                 for (int k = 0; k < LPW8; ++k) {
                     const int j = wave + NWAVE * k;
@@ -566,12 +652,15 @@ void w4a4_gemm_f6_kernel(const F6Params p)
                 }
         }
     }
-    __syncthreads();                                               // LDS is free
+    __syncthreads();                                               // LDS is free (PERSIST: but for the two stages of the next tile)
 
     // ---- store: the 64 x 64 fp16 tile of a wavefront goes through LDS so that global memory sees
-    // whole 128-byte rows (a lane holds one column of the MFMA layout)
+    // whole 128-byte rows (a lane holds one column of the MFMA layout).  PERSIST: the staging areas lie
+    // in the two stages the INT8 group was in.
     constexpr int OSTRIDE = Gm::OSTRIDE;
-    unsigned char *ot = smem + wave * (64 * OSTRIDE);
+    static_assert(!PERSIST || (NWAVE / 2) * 64 * OSTRIDE <= STAGE, "four staging areas per stage");
+    unsigned char *ot = PERSIST ? smem + (wave < NWAVE / 2 ? stage8a : stage8w) * STAGE + (wave % (NWAVE / 2)) * (64 * OSTRIDE)
+                                : smem + wave * (64 * OSTRIDE);
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -580,38 +669,92 @@ void w4a4_gemm_f6_kernel(const F6Params p)
             const int col = 32 * (t & 1) + r;
             *reinterpret_cast<uint16_t *>(ot + row * OSTRIDE + col * 2) = __half_as_ushort(__float2half_rn(acc[t][e]));
         }
-    __builtin_amdgcn_s_waitcnt(wait_imm(0));                       // the wavefront reads only what it wrote itself
     const bool vec_ok = ((reinterpret_cast<uintptr_t>(p.y) | (uintptr_t)(p.ldy * 2)) & 15) == 0;
+    if constexpr (!PERSIST) {
+        __builtin_amdgcn_s_waitcnt(wait_imm(0));                   // the wavefront reads only what it wrote itself
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-        const int row = it * 8 + (lane >> 3), ch = lane & 7;
-        const int64_t m = m_w + row, n = n_w + ch * 8;
-        if (m >= p.M || n >= p.N) continue;
-        const uint4 v = *reinterpret_cast<const uint4 *>(ot + row * OSTRIDE + ch * 16);
-        uint16_t *dst = p.y + m * p.ldy + n;
-        if (vec_ok && n + 8 <= p.N) {
-            *reinterpret_cast<uint4 *>(dst) = v;
-        } else {
-            const uint16_t *hv = reinterpret_cast<const uint16_t *>(&v);
+        for (int it = 0; it < 8; ++it) {
+            const int row = it * 8 + (lane >> 3), ch = lane & 7;
+            const int64_t m = T.m_w + row, n = T.n_w + ch * 8;
+            if (m >= p.M || n >= p.N) continue;
+            const uint4 v = *reinterpret_cast<const uint4 *>(ot + row * OSTRIDE + ch * 16);
+            uint16_t *dst = p.y + m * p.ldy + n;
+            if (vec_ok && n + 8 <= p.N) {
+                *reinterpret_cast<uint4 *>(dst) = v;
+            } else {
+                const uint16_t *hv = reinterpret_cast<const uint16_t *>(&v);
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if (n + k < p.N) dst[k] = hv[k];
+                for (int k = 0; k < 8; ++k)
+                    if (n + k < p.N) dst[k] = hv[k];
+            }
         }
+        break;
+    } else {
+        __builtin_amdgcn_s_waitcnt(wait_imm(63));                  // (LDS only: the wavefront reads what it wrote itself)
+        uint4 ov[8];
+#pragma unroll
+        for (int it = 0; it < 8; ++it) ov[it] = *reinterpret_cast<const uint4 *>(ot + (it * 8 + (lane >> 3)) * OSTRIDE + (lane & 7) * 16);
+        __builtin_amdgcn_s_waitcnt(wait_imm(63));
+        __syncthreads();                                           // every staging area is read: the two stages are free
+        const bool full = vec_ok && T.m_w + 64 <= p.M && T.n_w + 64 <= p.N;    // (the same in all lanes of a wavefront)
+        auto store_rows = [&](auto full_c) __attribute__((always_inline)) {
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int row = it * 8 + (lane >> 3), ch = lane & 7;
+                const int64_t m = T.m_w + row, n = T.n_w + ch * 8;
+                uint16_t *dst = p.y + m * p.ldy + n;
+                if constexpr (decltype(full_c)::value) {
+                    *reinterpret_cast<uint4 *>(dst) = ov[it];
+                } else if (m < p.M && n < p.N) {
+                    if (vec_ok && n + 8 <= p.N) {
+                        *reinterpret_cast<uint4 *>(dst) = ov[it];
+                    } else {
+                        const uint16_t *hv = reinterpret_cast<const uint16_t *>(&ov[it]);
+#pragma unroll
+                        for (int k = 0; k < 8; ++k)
+                            if (n + k < p.N) dst[k] = hv[k];
+                    }
+                }
+            }
+        };
+        // The next tile's groups 2 and 3, then exactly eight more vector-memory instructions: the K
+        // loop's first waits count on them.  A wavefront whose part of the tile is cut by M or N
+        // stores first, waits for everything, and issues eight dummy requests in their place.
+        if (!full) {
+            store_rows(std::false_type());
+            __builtin_amdgcn_s_waitcnt(wait_imm(0));
+        }
+#pragma unroll
+        for (int k = 0; k < LPW; ++k) request_next(k, 2, stage8a);
+#pragma unroll
+        for (int k = 0; k < LPW; ++k) request_next(k, 3, stage8w);
+        if (full) {
+            store_rows(std::true_type());
+        } else {
+#pragma unroll
+            for (int k = 0; k < XTRA; ++k) request_dummy();
+        }
+        if (more_mask == 0) break;
+        logical += lstep;
+        T = Tn;
+        base = (base + G4 - 2) % NST;
+    }
     }
 }
 
-template <int WM, bool DBG>
+template <int WM, bool DBG, bool PERSIST = false>
 hipError_t launch_f6_cfg(const F6Params &p, hipStream_t stream)
 {
     using Gm = F6Geom<WM>;
     static_assert(Gm::LDS <= 160 * 1024, "LDS of a compute unit");
     static_assert(Gm::LPW * (Gm::NST - 1) <= 63, "vmcnt is a 6-bit counter");
     const int64_t TM = (p.a_units + WM - 1) / WM, TN = (p.w_units + 1) / 2;
-    auto kern = &w4a4_gemm_f6_kernel<WM, DBG>;
+    auto kern = &w4a4_gemm_f6_kernel<WM, DBG, PERSIST>;
     static atom_launch::LdsOptIn opt_in;   // one attribute call per kernel variant and device
     hipError_t err = atom_launch::ensure_dynamic_lds(opt_in, reinterpret_cast<const void *>(kern), Gm::LDS);
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(TM * TN)), dim3(Gm::NT), Gm::LDS, stream, p);
+    const int64_t grid = PERSIST ? (int64_t)atom_launch::compute_units() : TM * TN;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(Gm::NT), Gm::LDS, stream, p);
     return hipGetLastError();
 }
 
@@ -657,7 +800,14 @@ hipError_t launch_f6_gemm(const void *a_pk, int64_t M, const void *w_pk, int64_t
     // which hides one's prologue, barriers and store behind the other's K loop
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 127) / 128);
     // (the dump of the integer sums runs the same tile shape as the plain call)
-    if (M > 128 && tiles256 >= 1024) return partials ? launch_f6_cfg<4, true>(p, stream) : launch_f6_cfg<4, false>(p, stream);
+    if (M > 128 && tiles256 >= 1024) {
+        if (partials) return launch_f6_cfg<4, true>(p, stream);
+        // one workgroup per CU that walks the tiles (see PERSIST in the file header): M = 4096, K = 8192:
+        // N = 57344 1649 -> 1587 us, N = 10240 322 -> 314 us; K = 28672, N = 8192 787 us either way
+        if (p.G8 == 1 && p.G4 >= F6Geom<4>::NST + 3 && tiles256 >= atom_launch::compute_units())
+            return launch_f6_cfg<4, false, true>(p, stream);
+        return launch_f6_cfg<4, false>(p, stream);
+    }
     if (M > 64) return partials ? launch_f6_cfg<2, true>(p, stream) : launch_f6_cfg<2, false>(p, stream);
     return partials ? launch_f6_cfg<1, true>(p, stream) : launch_f6_cfg<1, false>(p, stream);
 }
