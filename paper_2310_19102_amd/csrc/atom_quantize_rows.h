@@ -102,9 +102,10 @@ __device__ __forceinline__ float row16_max_dpp(float v)
 // Scale of a group from its maximum (Section 2 symmetric equations, fp32, stored as fp16) and the
 // codes of this lane's eight values: IEEE division by the stored scale through the shared
 // reciprocal refinement described below, round-half-to-even, clamp.  Returns the stored scale,
-// s = its fp32 value.
+// s = its fp32 value.  The codes stay floats (whole numbers): what packs them needs no integers
+// (pack_nibbles8 below, the conversion to FP6).
 __device__ __forceinline__ __half quantise_lane8(const float (&y)[8], float amax, bool is4, int nbits, float clip,
-                                                 int (&q)[8], float &s)
+                                                 float (&q)[8], float &s)
 {
     // normal channels: n = nbits (4, or 3 with the codes still in nibbles), outliers n = 8
     const float denom = is4 ? (nbits == 3 ? 7.0f : 15.0f) : 255.0f;
@@ -125,10 +126,23 @@ __device__ __forceinline__ __half quantise_lane8(const float (&y)[8], float amax
         t  = fmaf(-s, qf, y[e]);
         qf = fmaf(t, r1, qf);
         qf = rintf(qf);
-        qf = fminf(fmaxf(qf, qmin), qmax);
-        q[e] = (int)qf;
+        q[e] = __builtin_amdgcn_fmed3f(qf, qmin, qmax);      // (finite: the same as min(max(qf, qmin), qmax))
     }
     return sh;
+}
+
+// Eight codes in [-8, 7], given as floats, to eight two's-complement nibbles, code 0 lowest.
+// c0 + 16 c1 + 256 c2 + 4096 c3 is a whole number below 2^16 in magnitude, exact in fp32; with 8
+// added to every code (0x8888 to the sum) the digits are the offset-binary nibbles and no digit
+// borrows from the next; flipping the top bit of each nibble turns offset binary into two's
+// complement.  Eleven instructions instead of a conversion, a mask, a shift and an or per code.
+__device__ __forceinline__ uint32_t pack_nibbles8(const float (&c)[8])
+{
+    const float lo = fmaf(c[3], 4096.0f, fmaf(c[2], 256.0f, fmaf(c[1], 16.0f, c[0])));
+    const float hi = fmaf(c[7], 4096.0f, fmaf(c[6], 256.0f, fmaf(c[5], 16.0f, c[4])));
+    const uint32_t a = (uint32_t)((int)lo + 0x8888);                       // in [0, 0xffff]
+    const uint32_t b = ((uint32_t)(int)hi << 16) + 0x88880000u;
+    return (a | b) ^ 0x88888888u;
 }
 
 // Same result as the plain front-end kernel (compiler-generated IEEE division), bit for bit, for
@@ -334,7 +348,7 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
             amax = row16_max_dpp(amax);
 
             const bool  is4   = gg < G4;
-            int q[8];
+            float q[8];
             float s;
             const __half sh = quantise_lane8(y, amax, is4, nbits, clip, q, s);
             const bool nz = s != 0.0f;
@@ -349,7 +363,8 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
                         // eight codes = 48 bits, at byte 6 (pos % 4) of the 24 bytes of their 32-channel block
                         pk_v32h h;
 #pragma unroll
-                        for (int e = 0; e < 32; ++e) h[e] = e < 8 ? (_Float16)(float)(nz ? q[e & 7] : 0) : (_Float16)0.0f;
+                        // (+ 0.0f: a code that was rounded up to zero is -0.0f, and FP6 has a sign bit)
+                        for (int e = 0; e < 32; ++e) h[e] = e < 8 ? (_Float16)((nz ? q[e & 7] : 0.0f) + 0.0f) : (_Float16)0.0f;
                         const pk_v6u f6 = __builtin_amdgcn_cvt_scalef32_pk32_bf6_f16(h, 1.0f);
                         const int blk = pos >> 2;                   // block b: half b % 2, first or second MFMA b / 2
                         uint16_t *dst = reinterpret_cast<uint16_t *>(pk_lds + 96 * gg + 48 * (blk & 1) + 24 * (blk >> 1) + 6 * (pos & 3));
@@ -362,8 +377,8 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
                         uint32_t w0 = 0, w1 = 0;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            w0 |= (uint32_t)(q[e] & 0xFF) << (8 * e);
-                            w1 |= (uint32_t)(q[e + 4] & 0xFF) << (8 * e);
+                            w0 |= (uint32_t)((int)q[e] & 0xFF) << (8 * e);
+                            w1 |= (uint32_t)((int)q[e + 4] & 0xFF) << (8 * e);
                         }
                         *reinterpret_cast<uint2 *>(pk_lds + 3 * (K4 >> 2) + (j0 - K4)) = make_uint2(nz ? w0 : 0u, nz ? w1 : 0u);
                         if (pos == 0)
@@ -373,16 +388,14 @@ void quantize_rows_fast_body(float *lds, int64_t row_first, int64_t row_step,
                 }
             } else if (live) {
                 if (is4) {
-                    uint32_t w = 0;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) w |= (uint32_t)(q[e] & 0xF) << (4 * e);
+                    const uint32_t w = pack_nibbles8(q);
                     *reinterpret_cast<uint32_t *>(q4 + row * (int64_t)(K4 >> 1) + (j0 >> 1)) = nz ? w : 0u;
                 } else {
                     uint32_t w0 = 0, w1 = 0;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        w0 |= (uint32_t)(q[e] & 0xFF) << (8 * e);
-                        w1 |= (uint32_t)(q[e + 4] & 0xFF) << (8 * e);
+                        w0 |= (uint32_t)((int)q[e] & 0xFF) << (8 * e);
+                        w1 |= (uint32_t)((int)q[e + 4] & 0xFF) << (8 * e);
                     }
                     *reinterpret_cast<uint2 *>(q8 + row * (int64_t)O + (j0 - K4)) =
                         make_uint2(nz ? w0 : 0u, nz ? w1 : 0u);
