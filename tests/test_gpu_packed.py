@@ -110,6 +110,25 @@ def test_packed_gemm_strided_output_and_errors():
     assert e.value.status == 5
 
 
+def test_packed_gemm_many_tiles_strided_and_unaligned_output():
+    """1032 tiles of 256 rows (workgroups that walk several tiles) with an output whose rows are
+    not 16-byte aligned: every wavefront takes the conditional store path, tile after tile.  Same bits
+    as the contiguous output, nothing written outside."""
+    lin = _rand_linear(2048, 1024, 16500, 128, seed=11, norm=False)
+    print(f"[case] packed, many tiles, strided output: M={lin.M} K={lin.K} N={lin.N}", flush=True)
+    ga, gw = gpu_quantize_act(lin), gpu_quantize_weight(lin)
+    wp = atom.atom_pack_weight(*gw)
+    y = atom.atom_w4a4_gemm_packed(*ga, wp, lin.N)
+    big = torch.full((lin.M, lin.N + 13), 7.0, dtype=torch.float16, device="cuda")
+    atom.atom_w4a4_gemm_packed(*ga, wp, lin.N, out=big[:, 5:5 + lin.N])
+    torch.cuda.synchronize()
+    assert torch.equal(big[:, 5:5 + lin.N], y)
+    assert bool((big[:, :5] == 7).all()) and bool((big[:, 5 + lin.N:] == 7).all())
+    rows = np.array([0, 255, 256, 1000, 2047])
+    ref = oracle.w4a4_gemm(*ref_quantize_act(lin, rows=torch.from_numpy(rows)), *ref_quantize_weight(lin), 128)
+    assert np.array_equal(npy(y)[rows].view(np.uint16), ref["y"].view(np.uint16))
+
+
 @pytest.mark.parametrize("which", [0, 1])
 def test_packed_config4(which):
     """Full-size Llama-7B MLP launches; sampled rows against the oracle, bit for bit."""
