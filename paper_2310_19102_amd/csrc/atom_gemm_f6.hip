@@ -734,7 +734,11 @@ void w4a4_gemm_f6_kernel(const F6Params p)
 #pragma unroll
             for (int k = 0; k < XTRA; ++k) request_dummy();
         }
-        if (more_mask == 0) break;
+        if (more_mask == 0) {
+            // (the last requests went to the spare kilobyte: they have landed before the workgroup's LDS is given up)
+            __builtin_amdgcn_s_waitcnt(wait_imm(0));
+            break;
+        }
         logical += lstep;
         T = Tn;
         base = (base + G4 - 2) % NST;
