@@ -295,15 +295,19 @@ def step_summary(config, steps=100, warmup=10, fused_retile=None):
 
 def decode_sweep():
     """Decode-sized GEMMs against the HBM roofline: config 3's eight shapes, the fused gate/up
-    projection and the down projection at M = 8, weights walked through a ring of copies > 1 GB."""
+    projection and the down projection at M = 8, two shapes at M = 128, weights walked through a ring
+    of copies > 1 GB."""
     out = []
     sweep = [synth.make(3, w) for w in range(len(synth.CONFIG_SHAPES[3]))]
     sweep.append(synth.llama_linear("decode_m8_n22016", 8, 4096, 22016, 3, tensor_base=90))
     sweep.append(synth.llama_linear("decode_m8_down", 8, 11008, 4096, 3, tensor_base=92, norm=False))   # the down projection: 86 groups
+    # beyond config 3's batch sizes: 128 rows still stream the weights (two blocks of 64 rows)
+    sweep.append(synth.llama_linear("decode_m128_n4096", 128, 4096, 4096, 3, tensor_base=94))
+    sweep.append(synth.llama_linear("decode_m128_n11008", 128, 4096, 11008, 3, tensor_base=96))
     for lin in sweep:
         row = (lin.K - lin.n_outlier) // 2 + lin.n_outlier + 2 * (lin.K // lin.group_size)
         copies = max(2, int(1.2e9 // (lin.N * row)) + 1)
-        L = DeviceLinear(lin, n_weight_copies=copies)
+        L = DeviceLinear(lin, n_weight_copies=copies, packed=False)
         per = decode_gemm_in_graph(L, copies)
         # the same GEMM on re-tiled weight codes (the canonical copies are replaced, one at a time)
         L.tiled_ring = []

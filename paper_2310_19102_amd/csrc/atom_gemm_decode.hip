@@ -291,7 +291,9 @@ void w4a4_gemm_decode16_kernel(const GemmParams p)
     const int col = lane & 15, kc = lane >> 4;
 
     const int K4 = p.K - 128, G = p.K >> 7;
-    const int M = (int)p.M;
+    // blockIdx.y: which 16 RB rows of the activations (one block for M <= 64, two for up to 128 rows)
+    const int row0 = (int)blockIdx.y * (16 * RB);
+    const int M = min((int)p.M - row0, 16 * RB);          // rows of this workgroup
     const int64_t n0 = (int64_t)blockIdx.x * (TN * CB);
     constexpr bool A8 = TAIL == 3;
     const int nblk    = (G + 3) >> 2;
@@ -316,7 +318,7 @@ void w4a4_gemm_decode16_kernel(const GemmParams p)
     uint32_t a8o[RB], aso[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        const uint32_t ar = 16 * rb + col < M ? 16 * rb + col : 0;
+        const uint32_t ar = row0 + (16 * rb + col < M ? 16 * rb + col : 0);
         a8o[rb] = ar * 128u + kc * 16;
         aso[rb] = ar * (uint32_t)G;
     }
@@ -328,7 +330,7 @@ void w4a4_gemm_decode16_kernel(const GemmParams p)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int r = 16 * rb + 4 * i + kc;
-            srow[rb][i] = (uint32_t)(r < M ? r : M - 1) * (uint32_t)(K4 >> 1) + col * 16;
+            srow[rb][i] = (uint32_t)(row0 + (r < M ? r : M - 1)) * (uint32_t)(K4 >> 1) + col * 16;
         }
     unsigned char *mine = stage + wave * WREG;
     unsigned char *st_w = mine + kc * kStageRow + col * 16;                    // + 4 i kStageRow
@@ -474,9 +476,9 @@ void w4a4_gemm_decode16_kernel(const GemmParams p)
         float s = 0.0f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) s += reinterpret_cast<const float *>(stage + w * WREG)[idx];
-        const int64_t m = 16 * rb + 4 * (l >> 4) + e;
+        const int m = 16 * rb + 4 * (l >> 4) + e;
         const int64_t n = n0 + TN * cb + (l & 15);
-        if (m < p.M && n < p.N) p.y[m * p.ldy + n] = __half_as_ushort(__float2half_rn(s));
+        if (m < M && n < p.N) p.y[(int64_t)(row0 + m) * p.ldy + n] = __half_as_ushort(__float2half_rn(s));
     }
 }
 
@@ -497,13 +499,18 @@ void launch_common(const GemmParams &p, unsigned blocks, hipStream_t stream)
     else if (p.M <= 8)  hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<2, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
     else if (p.M <= 16) hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<4, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
     else if (p.M <= 32) hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<2, 1, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
-    // Four row blocks: two channel blocks per workgroup once there is more than one block of 16
-    // channels per CU.  M = 64, K = 4096, weights from HBM: N = 4096 6.6 us with one, 8.2 us with two;
-    // N = 5120 10.9 / 8.3; N = 8192 11.5 / 9.1; N = 11008 16.2 / 15.3; N = 22016 30.8 / 23.7.
-    else if ((int)blocks <= atom_launch::compute_units())
-        hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, 1, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
-    else
-        hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, 2, TILED, TAIL>), dim3((blocks + 1) / 2), dim3(NT), 0, stream, p);
+    // Four row blocks (and with more than 64 rows a second set of workgroups for rows 64 and up: the
+    // weights of a channel block are then read twice, the second time from the caches): two channel
+    // blocks per workgroup once there is more than one workgroup per CU otherwise.  M = 64, K = 4096,
+    // weights from HBM: N = 4096 6.6 us with one, 8.2 us with two; N = 5120 10.9 / 8.3; N = 8192 11.5 /
+    // 9.1; N = 11008 16.2 / 15.3; N = 22016 30.8 / 23.7.
+    else {
+        const unsigned yb = (unsigned)((p.M + 63) / 64);
+        if ((int64_t)blocks * yb <= atom_launch::compute_units())
+            hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, 1, TILED, TAIL>), dim3(blocks, yb), dim3(NT), 0, stream, p);
+        else
+            hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<4, 2, TILED, TAIL>), dim3((blocks + 1) / 2, yb), dim3(NT), 0, stream, p);
+    }
 }
 
 // Re-tiling of the canonical weight codes for the TILED variants: one workgroup per block of 16

@@ -65,12 +65,14 @@ __device__ __forceinline__ uint2 load_scales(const uint16_t *base, uint32_t row_
 // Which variant of the common decoding case a problem is (host side).
 // 3: G a multiple of four, scale rows 8-byte aligned; 1: G = 4 j + 2, scale rows 4-byte aligned; 0: neither.
 // In both cases: exactly one INT8 group that is the last group of the last wavefront's run (G >= 8),
-// M <= 64, 32-bit offsets.
-inline int common_tail(const GemmParams &p)
+// M <= max_rows (the kernels take blocks of 64 rows; more than 128 rows are the tiled kernels' business),
+// 32-bit offsets.
+constexpr int kDecodeMaxRows = 128;       // two blocks of 64 rows
+inline int common_tail(const GemmParams &p, int max_rows = kDecodeMaxRows)
 {
     const int G = p.K >> 7;
     const uintptr_t al = reinterpret_cast<uintptr_t>(p.a_scale) | reinterpret_cast<uintptr_t>(p.w_scale);
-    if (!(p.M <= 64 && p.O == 128 && G >= NW && (uint64_t)(p.N + TN) * (uint64_t)(p.K >> 1) < (1ull << 32) &&
+    if (!(p.M <= max_rows && p.O == 128 && G >= NW && (uint64_t)(p.N + TN) * (uint64_t)(p.K >> 1) < (1ull << 32) &&
           (uint64_t)p.N * (uint64_t)G < (1ull << 31)))
         return 0;
     if (G % 4 == 0 && (al & 7) == 0) return 3;

@@ -81,7 +81,9 @@ SHAPES = [
     (24, 1408, 64, 128, "decode <2, 2-byte scale loads>"),
     (24, 768, 64, 256, "decode <2, vector scales>, two INT8 groups"),
     (48, 768, 64, 256, "decode <4>, two INT8 groups"),
-    (128, 4096, 4096, 128, "few tiles <64, 32, four wavefront sets>"),
+    (128, 4096, 4096, 128, "decode <4 row blocks, 2 channel blocks>, two blocks of 64 rows"),
+    (96, 11008, 4096, 128, "decode, two blocks of 64 rows, the second of 32; 86 groups"),
+    (192, 4096, 2048, 128, "few tiles <64, 32, four wavefront sets>"),
     (256, 4096, 4096, 128, "few tiles <64, 64, four sets>"),
     (256, 11008, 4096, 128, "few tiles <64, 64, four sets>, 86 groups"),
     (256, 4096, 8192, 128, "few tiles <64, 64, two sets>"),
