@@ -46,6 +46,20 @@ WORKLOAD_NAMES = {
 }
 
 
+def streams_weights(lin, compute_units=256):
+    """Whether atom_w4a4_gemm takes its weight-streaming kernels for this linear layer (the library's
+    rule: up to 64 rows always, up to 256 rows when the workgroups of the blocks of 64 rows pass in
+    at most three rounds); such a layer keeps the canonical weights, larger ones the packed ones."""
+    G = lin.K // lin.group_size
+    if lin.M <= 64:
+        return True
+    if lin.M > 256 or lin.n_outlier != 128 or G % 2 or G < 8 or lin.group_size != 128:
+        return False
+    blocks, yb = (lin.N + 15) // 16, (lin.M + 63) // 64
+    wgs = blocks * yb if blocks * yb <= compute_units else (blocks + 1) // 2 * yb
+    return (wgs + compute_units - 1) // compute_units <= 3
+
+
 class DeviceLinear:
     """Device-resident operands of one quantised linear layer."""
 
@@ -53,7 +67,7 @@ class DeviceLinear:
         self.name, self.M, self.K, self.N = lin.name, lin.M, lin.K, lin.N
         self.G = lin.K // lin.group_size
         self.lin = lin
-        self.packed = lin.M > 64 if packed is None else packed
+        self.packed = (lin.M > 64 and not streams_weights(lin)) if packed is None else packed
         # packed path: the front end can write the tiled activations itself (one launch less, no
         # canonical arrays).  As kernel time it is 5-10 % behind front end + re-tiling pass (its 16-byte
         # stores are scattered over the unit images), so it pays where the launches, not the kernels,
@@ -380,10 +394,21 @@ def extra_measurements(headline_config):
     for packed in (True, False):
         L = DeviceLinear(synth.make(2, 0), packed=packed)
         t, ge, fe, pk, _ = run_steps([L], 200, 20, 0.05)
+
+        def one_step(L=L):
+            L.front_end()
+            L.pack()
+            L.gemm()
+        # (a step of 20 to 30 us is shorter than what the host needs to issue it: the eager figures
+        # above hold the host's time, the graph's do not)
+        tg = graph_time(one_step, launches=20, replays=10)
+        tgemm = graph_time(L.gemm, launches=20, replays=10)
         out.append({"workload": "config2 attn_proj M=256 K=4096 N=4096, " + ("packed weights" if packed else "canonical weights"),
                     "ms_per_step": t * 1e3, "effective_tops": L.ops / t / 1e12, "gemm_us": ge * 1e6,
                     "front_end_us": fe * 1e6, "retile_us": pk * 1e6,
-                    "gemm_frac_of_int8_mfma_peak": L.ops / ge / 1e12 / PEAK_INT8_TOPS})
+                    "gemm_frac_of_int8_mfma_peak": L.ops / ge / 1e12 / PEAK_INT8_TOPS,
+                    "step_us_in_graph": tg * 1e6, "effective_tops_in_graph": L.ops / tg / 1e12,
+                    "gemm_us_in_graph_warm_weights": tgemm * 1e6})
         del L
         torch.cuda.empty_cache()
     # the canonical INT8-MFMA kernel on the Llama-7B gate/up shape, for comparison with the packed one

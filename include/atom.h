@@ -185,7 +185,7 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8,
                            size_t workspace_bytes, void *stream);
 
 /*
- * Decode-sized group GEMM (M <= 128) on weight codes re-tiled for it (Section 3:
+ * Decode-sized group GEMM (M <= 256) on weight codes re-tiled for it (Section 3:
  * at these sizes a dense layer is bound by reading its weights; Section 4.2
  * for the arithmetic).  atom_tile_weight_decode rewrites the canonical code
  * arrays once, offline, into blocks of 16 rows x one group x 64 lanes x 16
@@ -197,7 +197,7 @@ atom_status atom_w4a4_gemm(const void *a_q4, const void *a_q8,
  *   atom_tile_weight_decode_bytes(N, d, which)   size of the tiled INT4
  *                 (which = 0) or INT8 (which = 1) array: ceil(N/16)*16 rows
  *   w_q4_tiled / w_q8_tiled   16-byte aligned device arrays of those sizes
- * atom_w4a4_gemm_decode_tiled: ATOM_ERR_UNSUPPORTED unless M <= 128,
+ * atom_w4a4_gemm_decode_tiled: ATOM_ERR_UNSUPPORTED unless M <= 256,
  * n_outlier = 128, K/128 even and at least 8, and the arrays stay
  * below 4 GiB; both scale arrays 8-byte aligned (ATOM_ERR_ALIGN).
  */

@@ -261,7 +261,7 @@ def atom_tile_weight_decode(w_q4: torch.Tensor, w_q8: torch.Tensor, group_size: 
 
 def atom_w4a4_gemm_decode_tiled(a_q4, a_q8, a_scale, w_q4_tiled, w_q8_tiled, w_scale, group_size: int = 128,
                                 out: Optional[torch.Tensor] = None):
-    """Decode-sized group GEMM (M <= 128) on re-tiled weight codes; ``w_scale`` [N, G] canonical."""
+    """Decode-sized group GEMM (M <= 256) on re-tiled weight codes; ``w_scale`` [N, G] canonical."""
     L = load_library()
     M, O = a_q8.shape
     N, G = w_scale.shape

@@ -351,11 +351,12 @@ hipError_t dispatch(const GemmParams &p, hipStream_t stream)
     // general streaming kernel against 15.1 us tiled, N = 8192 19.1 against 15.5, N = 11008 27.5
     // against 19.7 (the kernels of the common case: 8.3, 9.1 and 15.3 us).
     if (!DBG && p.M <= 64 && (decode_tiled_supported(p) || !(p.M > 32 && p.N > 4096))) return launch_decode(p, stream);
-    // 65 to 128 rows of the common case: the same streaming kernels on two blocks of 64 rows, up to
-    // three rounds of workgroups (weights from HBM, K = 4096, M = 128: N = 4096 8.1 us against 14.2 us on
-    // the tiled kernels below, N = 8192 15.1 / 18.3, N = 12288 21.6 / 26.3, N = 16384 29.0 / 27.6,
-    // N = 22016 41.2 / 31.7; K = 11008, N = 4096: 19.8 / 34.3)
-    if (!DBG && p.M <= 128 && p.N <= 12288 && decode_tiled_supported(p)) return launch_decode(p, stream);
+    // 65 to 256 rows of the common case: the same streaming kernels on blocks of 64 rows, as long as
+    // their workgroups pass in at most three rounds (weights from HBM, K = 4096, against the tiled
+    // kernels below: M = 128: N = 4096 8.1 / 14.2 us, N = 8192 15.1 / 18.3, N = 12288 21.6 / 26.3, but
+    // N = 16384 29.0 / 27.6; M = 192: N = 8192 21.0 / 24.2; M = 256: N = 4096 14.0 / 17.2, but N = 8192
+    // 27.3 / 25.3; K = 11008, N = 4096: M = 128 19.8 / 34.3, M = 256 35.6 / 46.7)
+    if (!DBG && p.M <= 256 && decode_tiled_supported(p) && decode_rounds(p) <= 3) return launch_decode(p, stream);
     // Launches of few tiles are bound by the latency of one tile's chain of K-steps: 64 x 64
     // tiles put every compute unit to work and four (or two) wavefront sets per workgroup split
     // that chain (M = 256, N = K = 4096: 25.7 us on 128 x 128 tiles with two sets).

@@ -57,6 +57,8 @@ hipError_t launch_decode(const GemmParams &p, hipStream_t stream);
 hipError_t launch_tile_weight(const void *q4, const void *q8, int64_t N, int K, int O, void *t4, void *t8,
                               hipStream_t stream);
 bool decode_tiled_supported(const GemmParams &p);
+// rounds of workgroups (one per CU) the streaming kernels take for more than 64 rows
+int decode_rounds(const GemmParams &p);
 hipError_t launch_decode_tiled(const GemmParams &p, hipStream_t stream);
 
 }  // namespace atom_gemm

@@ -291,7 +291,7 @@ void w4a4_gemm_decode16_kernel(const GemmParams p)
     const int col = lane & 15, kc = lane >> 4;
 
     const int K4 = p.K - 128, G = p.K >> 7;
-    // blockIdx.y: which 16 RB rows of the activations (one block for M <= 64, two for up to 128 rows)
+    // blockIdx.y: which 16 RB rows of the activations (one block for M <= 64, up to four for 256 rows)
     const int row0 = (int)blockIdx.y * (16 * RB);
     const int M = min((int)p.M - row0, 16 * RB);          // rows of this workgroup
     const int64_t n0 = (int64_t)blockIdx.x * (TN * CB);
@@ -499,8 +499,8 @@ void launch_common(const GemmParams &p, unsigned blocks, hipStream_t stream)
     else if (p.M <= 8)  hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<2, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
     else if (p.M <= 16) hipLaunchKernelGGL((w4a4_gemm_decode_staged_kernel<4, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
     else if (p.M <= 32) hipLaunchKernelGGL((w4a4_gemm_decode16_kernel<2, 1, TILED, TAIL>), dim3(blocks), dim3(NT), 0, stream, p);
-    // Four row blocks (and with more than 64 rows a second set of workgroups for rows 64 and up: the
-    // weights of a channel block are then read twice, the second time from the caches): two channel
+    // Four row blocks (and with more than 64 rows further sets of workgroups for rows 64 and up: the
+    // weights of a channel block are then read again, out of the caches): two channel
     // blocks per workgroup once there is more than one workgroup per CU otherwise.  M = 64, K = 4096,
     // weights from HBM: N = 4096 6.6 us with one, 8.2 us with two; N = 5120 10.9 / 8.3; N = 8192 11.5 /
     // 9.1; N = 11008 16.2 / 15.3; N = 22016 30.8 / 23.7.
@@ -553,6 +553,14 @@ hipError_t launch_tile_weight(const void *q4, const void *q8, int64_t N, int K, 
 
 // What the kernels that read tiled weights need: the common case (see common_tail).
 bool decode_tiled_supported(const GemmParams &p) { return common_tail(p) != 0; }
+
+int decode_rounds(const GemmParams &p)
+{
+    const int64_t cus = atom_launch::compute_units();
+    const int64_t blocks = (p.N + TN - 1) / TN, yb = (p.M + 63) / 64;
+    const int64_t wgs = blocks * yb <= cus ? blocks * yb : (blocks + 1) / 2 * yb;     // as launch_common picks them
+    return (int)((wgs + cus - 1) / cus);
+}
 
 hipError_t launch_decode_tiled(const GemmParams &p, hipStream_t stream)
 {

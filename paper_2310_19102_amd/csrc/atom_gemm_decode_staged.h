@@ -65,9 +65,9 @@ __device__ __forceinline__ uint2 load_scales(const uint16_t *base, uint32_t row_
 // Which variant of the common decoding case a problem is (host side).
 // 3: G a multiple of four, scale rows 8-byte aligned; 1: G = 4 j + 2, scale rows 4-byte aligned; 0: neither.
 // In both cases: exactly one INT8 group that is the last group of the last wavefront's run (G >= 8),
-// M <= max_rows (the kernels take blocks of 64 rows; more than 128 rows are the tiled kernels' business),
+// M <= max_rows (the kernels take blocks of 64 rows; more than 256 rows are the tiled kernels' business),
 // 32-bit offsets.
-constexpr int kDecodeMaxRows = 128;       // two blocks of 64 rows
+constexpr int kDecodeMaxRows = 256;       // four blocks of 64 rows
 inline int common_tail(const GemmParams &p, int max_rows = kDecodeMaxRows)
 {
     const int G = p.K >> 7;

@@ -140,8 +140,9 @@ def test_decode_linear_without_index(M, K, N, O, norm):
                                    # more than 32 rows and more blocks of 16 channels than CUs: two channel blocks per
                                    # workgroup; an odd number of blocks, a ragged last block, both kinds of last batch
                                    (64, 1024, 4112), (40, 1280, 4200), (33, 4096, 11008),
-                                   # 65 to 128 rows: two blocks of 64 rows, the second one ragged or not
-                                   (65, 1024, 520), (100, 4096, 4096), (128, 1280, 4200), (128, 1792, 48)])
+                                   # 65 to 256 rows: blocks of 64 rows, the last one ragged or not
+                                   (65, 1024, 520), (100, 4096, 4096), (128, 1280, 4200), (128, 1792, 48),
+                                   (200, 1024, 520), (256, 4096, 4096)])
 def test_decode_gemm_on_tiled_weights_is_bit_identical(M, K, N):
     """Weight codes re-tiled into whole 128-byte lines per load: same arithmetic, same tree, same Y
     as the canonical decode-sized GEMM, which the other tests hold against the oracle; ragged N

@@ -84,8 +84,10 @@ SHAPES = [
     (128, 4096, 4096, 128, "decode <4 row blocks, 2 channel blocks>, two blocks of 64 rows"),
     (96, 11008, 4096, 128, "decode, two blocks of 64 rows, the second of 32; 86 groups"),
     (192, 4096, 2048, 128, "few tiles <64, 32, four wavefront sets>"),
-    (256, 4096, 4096, 128, "few tiles <64, 64, four sets>"),
-    (256, 11008, 4096, 128, "few tiles <64, 64, four sets>, 86 groups"),
+    (256, 4096, 4096, 128, "decode <4 row blocks, 2 channel blocks>, four blocks of 64 rows"),
+    (256, 11008, 4096, 128, "decode, four blocks of 64 rows, 86 groups"),
+    (320, 4096, 3072, 128, "few tiles <64, 64, four sets>"),
+    (320, 11008, 3072, 128, "few tiles <64, 64, four sets>, 86 groups"),
     (256, 4096, 8192, 128, "few tiles <64, 64, two sets>"),
     (1024, 4096, 22016, 128, "big <256, 128, one set>: Llama-7B gate/up"),
     (1024, 11008, 4096, 128, "big <128, 128, two sets>: Llama-7B down"),
