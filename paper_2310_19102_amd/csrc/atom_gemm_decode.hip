@@ -249,8 +249,8 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
     }
 }
 
-// The cases decoding runs in, written out on their own: RB blocks of 16 activation rows
-// (M <= 16 RB), O = 128 (one INT8 group, the last group of K), 32-bit offsets, and either G a
+// The cases decoding runs in, written out on their own: RB blocks of 16 activation rows per
+// workgroup (blockIdx.y says which 16 RB rows: up to four sets of workgroups, 256 rows), O = 128 (one INT8 group, the last group of K), 32-bit offsets, and either G a
 // multiple of four with 8-byte aligned scale rows (TAIL = 3: the last block of four is three INT4
 // groups and the INT8 group; the four scales of a batch are one 8-byte load) or G = 4 j + 2 with
 // 4-byte aligned scale rows (TAIL = 1: the last block is one INT4 group and the INT8 group; two
@@ -269,7 +269,7 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
 //   * the scale products of a group and row block are one fp16 MFMA (activation scales of the
 //     operand rows against the weight scales of the columns, both in k-slot 0: the result has the
 //     layout of the integer tile; a product of two fp16 numbers is exact in fp32), so a lane loads
-//     one 8-byte piece of activation scales per batch and row block, not four.
+//     one 8-byte piece of activation scales per batch and row block, not four;
 //   * CB blocks of 16 output channels per workgroup share the activation operand: what a
 //     workgroup reads of the activations does not depend on how many channels it covers, and with
 //     32 rows and more these reads, all of them hits in the L2, are most of what the L2 delivers
