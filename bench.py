@@ -528,7 +528,7 @@ def decode_layer_measurements():
     idx_h = torch.randperm(Hd, generator=gen, device="cuda").to(torch.int32)
     idx_f = torch.randperm(F, generator=gen, device="cuda").to(torch.int32)
     gamma = (1.0 + 0.1 * torch.randn(Hd, generator=gen, device="cuda")).to(torch.float16)
-    for (B, T) in ((8, 1024), (64, 1024)):
+    for (B, T) in ((8, 1024), (64, 1024), (128, 1024)):
         n_layers = 12                       # 12 x (107 MB weights + caches): well beyond 256 MB
         layers = []
         for _ in range(n_layers):
