@@ -192,3 +192,26 @@ def test_decode_gemm_random_shapes():
         assert torch.equal(y, yt), f"case {case}: tiled and canonical weights differ"
         ref = oracle.w4a4_gemm(*ref_quantize_act(lin), *ref_quantize_weight(lin), 128)
         assert y_rel_err(npy(yt), ref["y"]) <= Y_TOL, f"case {case}"
+
+
+def test_decode_gemm_random_shapes_up_to_256_rows():
+    """The same for 65 to 256 rows (blocks of 64 rows along the grid's second dimension) and up to
+    4200 output channels (one or two channel blocks per workgroup)."""
+    rng = np.random.default_rng(2025)
+    for case in range(8):
+        M = int(rng.integers(65, 257))
+        G = int(rng.choice([8, 10, 14, 16, 22]))
+        K = 128 * G
+        N = int(rng.integers(1, 4200))
+        print(f"[case] random decode GEMM, many rows {case}: M={M} K={K} N={N}", flush=True)
+        lin = _rand_linear(M, K, N, 128, seed=3000 + case, norm=False)
+        gw = gpu_quantize_weight(lin)
+        qa = atom.atom_quantize_act(dev(lin.x), None, 0.0, dev(lin.idx), 128, 128, lin.clip_act)
+        t4, t8 = atom.atom_tile_weight_decode(gw[0], gw[1])
+        y = atom.atom_w4a4_gemm(*qa, *gw)
+        yt = atom.atom_w4a4_gemm_decode_tiled(*qa, t4, t8, gw[2])
+        torch.cuda.synchronize()
+        ref = oracle.w4a4_gemm(*ref_quantize_act(lin), *ref_quantize_weight(lin), 128)
+        assert y_rel_err(npy(yt), ref["y"]) <= Y_TOL, f"case {case}"
+        assert y_rel_err(npy(y), ref["y"]) <= Y_TOL, f"case {case} (canonical weights)"
+

@@ -129,6 +129,37 @@ def test_packed_gemm_many_tiles_strided_and_unaligned_output():
     assert np.array_equal(npy(y)[rows].view(np.uint16), ref["y"].view(np.uint16))
 
 
+def test_packed_gemm_many_tiles_random_shapes():
+    """Seeded random problems of 1024 and more tiles of 256 rows (one workgroup per CU walks them): Y
+    must be the bits of the instantiation that also dumps the integer sums, which runs one
+    workgroup per tile and is held against the oracle by the tests above.  Random codes and
+    scales; ragged M and N, odd unit counts, seven to eleven INT4 groups."""
+    rng = np.random.default_rng(77)
+    g = torch.Generator(device="cuda").manual_seed(77)
+    for case in range(6):
+        G = int(rng.integers(8, 13))
+        K, O = 128 * G, 128
+        mt = int(rng.integers(5, 12))                                   # row tiles of 256
+        M = 256 * mt - int(rng.integers(0, 256))
+        nt = -(-1024 // mt) + int(rng.integers(0, 40))                  # column tiles of 128
+        N = 128 * nt - int(rng.integers(0, 128))
+        print(f"[case] packed, many tiles, random {case}: M={M} K={K} N={N}", flush=True)
+        a = (torch.randint(0, 256, (M, (K - O) // 2), dtype=torch.uint8, device="cuda", generator=g),
+             torch.randint(-128, 128, (M, O), dtype=torch.int8, device="cuda", generator=g),
+             (torch.rand((M, G), device="cuda", generator=g) * 0.01 + 0.001).half())
+        w = (torch.randint(0, 256, (N, (K - O) // 2), dtype=torch.uint8, device="cuda", generator=g),
+             torch.randint(-128, 128, (N, O), dtype=torch.int8, device="cuda", generator=g),
+             (torch.rand((N, G), device="cuda", generator=g) * 0.01 + 0.001).half())
+        wp = atom.atom_pack_weight(*w)
+        y = atom.atom_w4a4_gemm_packed(*a, wp, N)
+        part = torch.empty((M, N, G), dtype=torch.int32, device="cuda")
+        y2 = atom.atom_w4a4_gemm_packed(*a, wp, N, partials=part)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y2), f"case {case}"
+        del part, y, y2, wp, a, w
+        torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("which", [0, 1])
 def test_packed_config4(which):
     """Full-size Llama-7B MLP launches; sampled rows against the oracle, bit for bit."""
