@@ -118,7 +118,6 @@ void w4a4_gemm_decode_kernel(const GemmParams p)
         for (int e = 0; e < 4; ++e) acc[rb][e] = 0.0f;
 
     const v4i zi = {0, 0, 0, 0};
-    const uint4 z4 = make_uint4(0, 0, 0, 0);
 
     // Groups are processed in batches of DEPTH.  Every load of a batch (weight codes,
     // weight scales, activation codes, activation scales) is issued before the first is
